@@ -1,0 +1,314 @@
+"""Pins for the float64 oracle against things that are not the oracle: definitions written out as loops,
+numpy's least-squares routine, brute force over all supports, closed forms and special cases.
+Citations are to the paper's sections / equations."""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+import osscar_inputs as inp
+from oracle import osscar_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def make_problem(p, q, m, n, seed, corr=0.6, lam=1e-3):
+    rng = np.random.default_rng(seed)
+    d1 = p * q
+    Z = rng.standard_normal((n, d1))
+    # correlated columns so that swaps are non-trivial
+    A = np.eye(d1) + corr * rng.standard_normal((d1, d1)) / math.sqrt(d1)
+    X = Z @ A
+    W = rng.standard_normal((d1, m)) / math.sqrt(d1)
+    H, G, c0, lam_used = orc.gram(X, W, lam_abs=lam)
+    return X, W, H, G, c0, lam_used
+
+
+# ---------------------------------------------------------------- Gram / objective (Section 3)
+def test_gram_is_sum_of_outer_products():
+    X, W, H, G, c0, lam = make_problem(6, 1, 3, 20, 0, lam=0.25)
+    H_loop = np.zeros((6, 6))
+    for i in range(X.shape[0]):
+        for a in range(6):
+            for b in range(6):
+                H_loop[a, b] += X[i, a] * X[i, b]
+    for a in range(6):
+        H_loop[a, a] += 0.25
+    assert np.allclose(H, H_loop, rtol=1e-13, atol=1e-13)
+    assert np.allclose(H, H.T)
+    assert np.min(np.linalg.eigvalsh(H)) > 0
+    assert np.allclose(G, H_loop @ W)
+    assert np.isclose(c0, np.trace(W.T @ H_loop @ W))
+
+
+def test_lambda_rel_uses_diag_before_ridge():
+    rng = np.random.default_rng(1)
+    X = rng.standard_normal((50, 5))
+    W = rng.standard_normal((5, 2))
+    H, G, c0, lam = orc.gram(X, W, lam_abs=0.5, lam_rel=0.1)
+    want = 0.5 + 0.1 * np.mean(np.sum(X * X, axis=0))
+    assert np.isclose(lam, want, rtol=1e-14)
+    assert np.allclose(H - X.T @ X, lam * np.eye(5), atol=1e-12)
+
+
+def test_quadratic_objective_equals_reconstruction_loss():
+    # pins the minus sign of the linear term (eq. (MIQP)) and c0
+    X, W, H, G, c0, lam = make_problem(8, 1, 4, 40, 2)
+    rng = np.random.default_rng(3)
+    What = rng.standard_normal(W.shape)
+    assert np.isclose(orc.objective_direct(X, W, What, lam), orc.objective_quadratic(H, G, c0, What), rtol=1e-11)
+    assert abs(orc.objective_quadratic(H, G, c0, W)) < 1e-9 * c0
+
+
+# ---------------------------------------------------------------- optimum for a fixed support (eq. (optf))
+@pytest.mark.parametrize("q", [1, 3])
+def test_solve_support_matches_ridge_least_squares(q):
+    p, m, n = 6, 4, 60
+    X, W, H, G, c0, lam = make_problem(p, q, m, n, 4, lam=0.3)
+    groups = [0, 2, 5]
+    What, obj = orc.solve_support(H, G, c0, groups, q)
+    rows = orc.rows_of(groups, q)
+    # textbook ridge LS on the stacked system [X_K; sqrt(lam) I_K; 0] What_K ~ [X W; sqrt(lam) W]
+    d1 = p * q
+    A = np.vstack([X[:, rows], math.sqrt(lam) * np.eye(d1)[:, rows]])
+    Y = np.vstack([X @ W, math.sqrt(lam) * W])
+    sol, *_ = np.linalg.lstsq(A, Y, rcond=None)
+    assert np.allclose(What[rows], sol, rtol=1e-8, atol=1e-10)
+    other = np.setdiff1d(np.arange(d1), rows)
+    assert np.all(What[other] == 0)
+    assert np.isclose(obj, orc.objective_direct(X, W, What, lam), rtol=1e-10)
+    # normal equations on the kept rows; eq. (optf): f = -1/2 Tr(G_K^T H_KK^-1 G_K)
+    assert np.allclose(H[np.ix_(rows, rows)] @ What[rows], G[rows], rtol=1e-9, atol=1e-9)
+    f = -0.5 * np.trace(G[rows].T @ np.linalg.inv(H[np.ix_(rows, rows)]) @ G[rows])
+    assert np.isclose(obj, c0 + 2 * f, rtol=1e-10)
+
+
+def test_keep_everything_recovers_dense_weights():
+    X, W, H, G, c0, lam = make_problem(5, 2, 3, 30, 5)
+    What, obj = orc.solve_support(H, G, c0, range(5), 2)
+    assert np.allclose(What, W, atol=1e-10)
+    assert abs(obj) < 1e-9 * c0
+
+
+def test_residual_identity_on_pruned_rows():
+    # obj(K) = <W_Kc, R>, R = G_Kc - H_{Kc,K} What_K  (follows from G = H W and the normal equations)
+    X, W, H, G, c0, lam = make_problem(7, 2, 3, 50, 6)
+    groups = [1, 3, 4]
+    What, obj = orc.solve_support(H, G, c0, groups, 2)
+    rows = orc.rows_of(groups, 2)
+    crow = np.setdiff1d(np.arange(14), rows)
+    R = G[crow] - H[np.ix_(crow, rows)] @ What[rows]
+    assert np.isclose(obj, np.sum(W[crow] * R), rtol=1e-10)
+
+
+# ---------------------------------------------------------------- enumeration (Section 4.1)
+def test_combination_counter_matches_paper_count():
+    with open(os.path.join(GOLDEN, "paper_counts.txt")) as fh:
+        rows = [ln.split() for ln in fh if ln.strip() and not ln.startswith("#")]
+    for name, n, k, lower, exact in rows:
+        c = orc.n_choose_k(int(n), int(k))
+        assert c > int(lower)
+        assert c == int(exact) == math.comb(int(n), int(k))
+    assert orc.n_choose_k(16, 8) == 12870
+
+
+def test_brute_force_enumerates_everything_and_search_is_bounded_by_it():
+    cfg = inp.CONFIGS["cfg1x"]
+    X = inp.gen_X(cfg).double().numpy()
+    W = inp.gen_W(cfg).double().numpy()
+    H, G, c0, lam = orc.gram(X, W, cfg.lam_abs, cfg.lam_rel)
+    best, best_obj, objs = orc.brute_force(H, G, c0, cfg.p, cfg.q, cfg.k)
+    assert len(objs) == 12870
+    assert best_obj == objs.min()
+    # spot-check three enumerated objectives against the reconstruction loss itself
+    combos = list(itertools.combinations(range(cfg.p), cfg.k))
+    for idx in (0, 6000, 12869):
+        What, o = orc.solve_support(H, G, c0, combos[idx], cfg.q)
+        assert np.isclose(objs[idx], orc.objective_direct(X, W, What, lam), rtol=1e-9)
+    # search from the magnitude support cannot beat the global optimum, and never gets worse than its start
+    K0 = orc.magnitude_support(W, cfg.p, cfg.q, cfg.k)
+    res = orc.local_search(H, G, c0, K0, cfg.p, cfg.q, cfg.swaps)
+    assert res.obj_final >= best_obj * (1 - 1e-12)
+    assert res.obj_final <= res.obj_initial
+    # the global optimum is a fixed point: no 1-out/1-in swap improves it, so nothing is accepted
+    res2 = orc.local_search(H, G, c0, best, cfg.p, cfg.q, 10)
+    assert res2.accepted == 0 and res2.support == sorted(best)
+    # and whatever the search returns is 1-swap-stable only w.r.t. its selected pair; check its objective
+    _, o = orc.solve_support(H, G, c0, res.support, cfg.q)
+    assert np.isclose(o, res.obj_final, rtol=1e-9)
+
+
+# ---------------------------------------------------------------- impact scores (eq. (impact), Prop. 4.1)
+@pytest.mark.parametrize("q", [1, 2, 4])
+def test_scores_equal_differences_of_full_resolves(q):
+    p, m, n, k = 9, 5, 80, 5
+    X, W, H, G, c0, lam = make_problem(p, q, m, n, 7 + q)
+    K = [0, 2, 3, 6, 8]
+    st = orc.init_state(H, G, K, q)
+    _, objK = orc.solve_support(H, G, c0, K, q)
+    assert np.isclose(c0 + 2 * st.f, objK, rtol=1e-10)
+    rem = orc.removal_scores(st, p, q)
+    add = orc.addition_scores(st, H, G, p, q)
+    for g in range(p):
+        if g in K:
+            _, o = orc.solve_support(H, G, c0, [x for x in K if x != g], q)
+            assert np.isclose(rem[g], o - objK, rtol=1e-8), ("rem", g)
+            assert rem[g] >= 0 and add[g] == -np.inf
+        else:
+            _, o = orc.solve_support(H, G, c0, K + [g], q)
+            assert np.isclose(add[g], objK - o, rtol=1e-8), ("add", g)
+            assert add[g] >= 0 and rem[g] == np.inf
+            # the one-candidate Case-2 formula agrees with the batched evaluation
+            assert np.isclose(orc.addition_score(st, H, G, g, q), add[g], rtol=1e-9)
+
+
+@pytest.mark.parametrize("q", [1, 3])
+def test_updates_match_fresh_state_and_are_involutive(q):
+    p, m, n = 8, 4, 70
+    X, W, H, G, c0, lam = make_problem(p, q, m, n, 20 + q)
+    K = [1, 2, 4, 7]
+    st = orc.init_state(H, G, K, q)
+    rows = orc.rows_of(K, q)
+    assert np.allclose(st.P @ H[np.ix_(rows, rows)], np.eye(len(rows)), atol=1e-9)
+    # Case 1: remove group 4 (slot 2)
+    mid = orc.remove_group(st, 2, q)
+    fresh = orc.init_state(H, G, [1, 2, 7], q)
+    assert mid.groups == [1, 2, 7]
+    assert np.allclose(mid.P, fresh.P, rtol=1e-8, atol=1e-11)
+    assert np.allclose(mid.What_K, fresh.What_K, rtol=1e-8, atol=1e-11)
+    assert np.isclose(mid.f, fresh.f, rtol=1e-10)
+    assert mid.f > st.f                      # removing rows raises f (sign reading of the f update)
+    # Case 2: add group 5
+    new = orc.add_group(mid, H, G, 5, q)
+    fresh2 = orc.init_state(H, G, [1, 2, 7, 5], q)
+    assert new.groups == [1, 2, 7, 5]
+    assert np.allclose(new.P, fresh2.P, rtol=1e-8, atol=1e-11)
+    assert np.allclose(new.What_K, fresh2.What_K, rtol=1e-8, atol=1e-11)
+    assert np.isclose(new.f, fresh2.f, rtol=1e-10)
+    assert new.f < mid.f                     # adding rows lowers f
+    # involution: remove 4 then add 4 gives back the state (up to the slot permutation)
+    back = orc.add_group(mid, H, G, 4, q)
+    ref = orc.init_state(H, G, [1, 2, 7, 4], q)
+    assert np.allclose(back.P, ref.P, rtol=1e-8, atol=1e-11)
+    assert np.isclose(back.f, st.f, rtol=1e-10)
+    # the optimal weights are the solution of the normal equations on the kept rows
+    r2 = orc.rows_of(new.groups, q)
+    assert np.allclose(H[np.ix_(r2, r2)] @ new.What_K, G[r2], rtol=1e-8, atol=1e-9)
+
+
+@pytest.mark.parametrize("q", [1, 3])
+def test_swap_delta_equals_resolve_difference(q):
+    p, m, n = 8, 4, 70
+    X, W, H, G, c0, lam = make_problem(p, q, m, n, 30 + q)
+    K = [0, 3, 5, 6]
+    st = orc.init_state(H, G, K, q)
+    _, objK = orc.solve_support(H, G, c0, K, q)
+    for g in K:
+        for j in (1, 2, 4, 7):
+            delta, _ = orc.swap_delta(st, H, G, g, j, q)
+            _, o = orc.solve_support(H, G, c0, [x for x in K if x != g] + [j], q)
+            assert np.isclose(delta, o - objK, rtol=1e-7, atol=1e-9 * objK)
+
+
+# ---------------------------------------------------------------- search invariants
+@pytest.mark.parametrize("q,seed", [(1, 40), (2, 41), (1, 42)])
+def test_search_objective_is_monotone_and_tracked_exactly(q, seed):
+    p, m, n, k = 24, 6, 200, 10
+    X, W, H, G, c0, lam = make_problem(p, q, m, n, seed, corr=1.5)
+    K0 = orc.magnitude_support(W, p, q, k)
+    res = orc.local_search(H, G, c0, K0, p, q, 40)
+    objs = [res.obj_initial] + [r.obj_after for r in res.trace if r.accepted]
+    assert all(b < a for a, b in zip(objs, objs[1:]))
+    assert res.accepted >= 1                                  # the planted correlation makes swaps pay
+    for r in res.trace:
+        if r.accepted:
+            assert r.delta < 0
+    _, o = orc.solve_support(H, G, c0, res.support, q)
+    assert np.isclose(o, res.obj_final, rtol=1e-9)
+    What, _ = orc.solve_support(H, G, c0, res.support, q)
+    assert np.isclose(o, orc.objective_direct(X, W, What, lam), rtol=1e-9)
+    assert len(res.support) == k and len(set(res.support)) == k
+    # the last record is the rejected one (or the budget ran out)
+    assert res.iters == res.accepted or (res.iters == res.accepted + 1 and not res.trace[-1].accepted)
+
+
+def test_follow_mode_reproduces_free_run_with_zero_deficit():
+    p, q, m, n, k = 20, 1, 5, 150, 8
+    X, W, H, G, c0, lam = make_problem(p, q, m, n, 50, corr=1.5)
+    K0 = orc.magnitude_support(W, p, q, k)
+    free = orc.local_search(H, G, c0, K0, p, q, 30)
+    pairs = [(r.g_out, r.j_in) for r in free.trace if r.accepted]
+    fol = orc.local_search(H, G, c0, K0, p, q, 30, follow=pairs)
+    assert fol.support == free.support
+    assert np.isclose(fol.obj_final, free.obj_final, rtol=1e-12)
+    assert all(r.deficit_rem == 0 and r.deficit_add == 0 for r in fol.trace)
+    # a deliberately second-best choice shows up as a positive deficit
+    st = orc.init_state(H, G, K0, q)
+    rem = orc.removal_scores(st, p, q)
+    second = int(np.argsort(rem)[1])
+    bad = orc.local_search(H, G, c0, K0, p, q, 1, follow=[(second, pairs[0][1])])
+    assert bad.trace[0].deficit_rem > 0
+
+
+def test_diagonal_H_closed_form():
+    # orthogonal columns: rem_g = add_g = H_gg ||W_g||^2, the optimum keeps the k largest, search reaches it
+    rng = np.random.default_rng(60)
+    p, m, k = 12, 4, 5
+    Qm, _ = np.linalg.qr(rng.standard_normal((40, p)))
+    X = Qm * rng.uniform(0.5, 3.0, size=p)[None, :]
+    W = rng.standard_normal((p, m))
+    H, G, c0, lam = orc.gram(X, W, lam_abs=0.1)
+    assert np.allclose(H, np.diag(np.diag(H)), atol=1e-12)
+    imp = np.diag(H) * np.sum(W * W, axis=1)
+    K0 = orc.magnitude_support(W, p, 1, k)
+    st = orc.init_state(H, G, K0, 1)
+    rem = orc.removal_scores(st, p, 1)
+    add = orc.addition_scores(st, H, G, p, 1)
+    for g in range(p):
+        assert np.isclose(rem[g] if g in K0 else add[g], imp[g], rtol=1e-9)
+    res = orc.local_search(H, G, c0, K0, p, 1, 50)
+    want = sorted(int(i) for i in np.argsort(-imp)[:k])
+    assert res.support == want
+    best, best_obj, _ = orc.brute_force(H, G, c0, p, 1, k)
+    assert sorted(best) == want and np.isclose(res.obj_final, best_obj, rtol=1e-10)
+
+
+def test_huge_ridge_makes_magnitude_support_optimal():
+    X, W, H, G, c0, lam = make_problem(10, 1, 4, 50, 70, lam=1e9)
+    K0 = orc.magnitude_support(W, 10, 1, 4)
+    res = orc.local_search(H, G, c0, K0, 10, 1, 20)
+    assert res.accepted == 0 and res.support == K0
+    best, _, _ = orc.brute_force(H, G, c0, 10, 1, 4)
+    assert sorted(best) == K0
+
+
+def test_magnitude_support_definition_and_ties():
+    W = np.array([[3.0, 4.0], [0.0, 5.0], [5.0, 0.0], [1.0, 1.0], [0.0, 0.0], [4.0, 3.0]])
+    assert np.allclose(orc.group_magnitudes(W, 6, 1), [5, 5, 5, math.sqrt(2), 0, 5])
+    assert orc.magnitude_support(W, 6, 1, 3) == [0, 1, 2]          # four-way tie: lower indices stay
+    assert np.allclose(orc.group_magnitudes(W, 3, 2), [math.sqrt(50), math.sqrt(27), 5.0])
+    assert orc.magnitude_support(W, 3, 2, 2) == [0, 1]
+
+
+def test_always_accept_runs_the_printed_algorithm():
+    p, q, m, n, k = 16, 1, 4, 100, 6
+    X, W, H, G, c0, lam = make_problem(p, q, m, n, 80, corr=1.0)
+    K0 = orc.magnitude_support(W, p, q, k)
+    res = orc.local_search(H, G, c0, K0, p, q, 12, always_accept=True)
+    assert res.iters == 12 and res.accepted == 12
+    _, o = orc.solve_support(H, G, c0, res.support, q)
+    assert np.isclose(o, res.obj_final, rtol=1e-8)
+
+
+def test_prune_layer_end_to_end_on_cfg1():
+    cfg = inp.CONFIGS["cfg1"]
+    X = inp.gen_X(cfg).double().numpy()
+    W = inp.gen_W(cfg).double().numpy()
+    out = orc.prune_layer(X, W, cfg.p, cfg.q, cfg.k, cfg.swaps, cfg.lam_abs, cfg.lam_rel)
+    assert len(out["support"]) == cfg.k
+    assert out["obj"] <= out["search"].obj_initial
+    assert np.isclose(out["obj"], orc.objective_direct(X, W, out["What"], out["lam"]), rtol=1e-9)
+    pruned = np.setdiff1d(np.arange(cfg.d1), orc.rows_of(out["support"], cfg.q))
+    assert np.all(out["What"][pruned] == 0)
