@@ -1,0 +1,156 @@
+/*
+ * osscar.h -- C interface of the MI355X (gfx950) per-layer structured-pruning solver of OSSCAR
+ * (arxiv 2403.12983).
+ *
+ * Problem (Section 3, eq. (MIQP); Section 4.1, eq. (struc)): the rows of the dense weight matrix
+ * W (d1 x m) are split into p contiguous groups of q rows (d1 = p*q: FFN neurons q = 1, conv input
+ * channels q = k_H*k_W, attention heads q = D_head).  Keep k groups K, zero the other rows and refit
+ * the kept rows so that
+ *        obj(What) = || X W - X What ||_F^2 + lambda || W - What ||_F^2
+ * is as small as the local search of Section 4.2 can make it.  With H = X^T X + lambda I, G = H W this
+ * is c0 + 2 L(What), L the quadratic of eq. (MIQP), c0 = Tr(W^T H W).
+ *
+ * Naming: this interface uses K for the KEPT groups (the paper's S is the pruned set, K its
+ * complement), W for the given dense weights (the paper's W-hat) and What for the solved weights.
+ *
+ * Conventions for every call
+ *   - "dev" pointers are device (HBM) addresses on the current HIP device, "host" pointers are host
+ *     addresses.  All matrices are row-major; leading dimensions are in elements.
+ *   - The library allocates no device memory.  The caller hands one workspace of at least
+ *     osscar_workspace_bytes() bytes (256-byte aligned) to osscar_create and owns it, X, W and What.
+ *     The context keeps pointers into the workspace only; W is read only during osscar_gram.
+ *   - All work is enqueued on the stream given to osscar_create.  Calls that return host values
+ *     synchronise that stream; osscar_gram without finalize does not.
+ *   - Every call returns an osscar_status.  No exception crosses this boundary and nothing aborts.
+ *     After a failure other than OSSCAR_EINVAL the context refuses further compute calls
+ *     (OSSCAR_ESTATE) until it is destroyed and re-created.  osscar_last_error() describes the failure.
+ *   - Groups are equal-sized and contiguous (the three cases of Section 3; Prop. 4.2 assumes equal size).
+ *   - Calls on one context must not overlap; contexts sharing a workspace must not be used concurrently.
+ */
+#ifndef OSSCAR_H
+#define OSSCAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct osscar_ctx osscar_ctx; /* opaque; host memory owned by the library */
+
+typedef enum {
+  OSSCAR_OK = 0,
+  OSSCAR_EINVAL = 1, /* bad argument (shape, k > p, NULL pointer, misaligned buffer, ...) */
+  OSSCAR_ENOMEM = 2, /* workspace too small */
+  OSSCAR_ENOTPD = 3, /* H_KK (or a q x q pivot block) is not positive definite to working precision */
+  OSSCAR_EHIP = 4,   /* a HIP runtime call failed */
+  OSSCAR_ESTATE = 5  /* call order violated, or the context is poisoned by an earlier failure */
+} osscar_status;
+
+typedef enum { OSSCAR_F32 = 0, OSSCAR_BF16 = 1 } osscar_dtype;
+
+/* Problem description (Section 3: d1 x m weights, p groups of q rows; Section 4.1: keep k = p - p'). */
+typedef struct {
+  int64_t d1;        /* rows of W = columns of X; must equal p*q */
+  int64_t m;         /* columns of W */
+  int32_t p;         /* number of groups */
+  int32_t q;         /* rows per group, 1 <= q <= 64 */
+  int32_t k;         /* groups to keep, 1 <= k <= p */
+  int32_t max_swaps; /* upper bound on the swap budget of any osscar_local_search call (sizes the trace) */
+  int32_t x_dtype;   /* osscar_dtype of X */
+  int32_t w_dtype;   /* osscar_dtype of W */
+} osscar_desc;
+
+/* Bytes of device workspace osscar_create needs for this description (0 if the description is invalid). */
+size_t osscar_workspace_bytes(const osscar_desc* desc);
+
+/* Creates a context.  workspace_dev: device, >= osscar_workspace_bytes(desc) bytes, 256-byte aligned.
+ * hip_stream: a hipStream_t (NULL = the default stream).  *out receives the context. */
+osscar_status osscar_create(osscar_ctx** out, const osscar_desc* desc, void* workspace_dev, size_t workspace_bytes,
+                            void* hip_stream);
+osscar_status osscar_destroy(osscar_ctx* ctx);
+
+/* Quadratic-form construction (Section 3, dense-layer paragraph: H = X^T X, G = X^T X W; the ridge is
+ * this build's addition).  Each call adds one chunk of calibration rows: H += Xc^T Xc with
+ * Xc dev, row-major n_c x d1 (leading dimension ldx >= d1), dtype desc.x_dtype.  Any number of chunks,
+ * any n_c >= 0; products are accumulated in float64 across chunks.
+ * finalize != 0 (after adding Xc, which may be NULL with n_c = 0): lambda = lambda_abs + lambda_rel *
+ * mean(diag(X^T X)); H += lambda I (stored float32); G = H W (float32); c0 = Tr(W^T G); the group norms
+ * ||W_{Q^j}||_F are recorded for osscar_init_support.  W_dev: dev, row-major d1 x m, leading dimension
+ * ldw, dtype desc.w_dtype (ignored unless finalize).  A new first chunk after finalize starts a new layer. */
+osscar_status osscar_gram(osscar_ctx* ctx, const void* Xc_dev, int64_t n_c, int64_t ldx, int finalize,
+                          const void* W_dev, int64_t ldw, double lambda_abs, double lambda_rel);
+
+/* Alternative to osscar_gram for callers that already hold the quadratic form: copies H (d1 x d1,
+ * symmetric positive definite, ridge included) and G (d1 x m), both dev float32 row-major and dense
+ * (ld = d1, m), and takes c0 and the p group norms (host float64) used by the magnitude mode. */
+osscar_status osscar_set_quadratic(osscar_ctx* ctx, const float* H_dev, const float* G_dev, double c0,
+                                   const double* group_norms_host);
+
+/* Support initialisation.  OSSCAR_INIT_MAGNITUDE: keep the k groups of largest Frobenius norm
+ * (Appendix B.1, "MP"; equal norms: the lower group index stays).  OSSCAR_INIT_GIVEN: keep
+ * groups_host[0..k) (distinct, any order).  Then builds the state Proposition 4.1 assumes -- the
+ * inverse P of H on the kept rows, the optimal kept weights B = P G_K (eq. (optf)) -- plus the
+ * candidate-side quantities V = P H_{K,Kc} and R = G_Kc - V^T G_K used by the impact scores
+ * (eq. (impact)), and returns obj(K) = c0 - Tr(G_K^T B) in *obj_host (may be NULL). */
+enum { OSSCAR_INIT_MAGNITUDE = 0, OSSCAR_INIT_GIVEN = 1 };
+osscar_status osscar_init_support(osscar_ctx* ctx, int mode, const int32_t* groups_host, double* obj_host);
+
+/* Local search (Section 4.2 and Algorithm 1 with t-hat = 2, p-hat = 0: one group leaves, one enters).
+ * Each iteration scores every kept group by the cost of removing it and every outside group by the
+ * gain of adding it (eq. (impact), via the closed forms of Proposition 4.1, Cases 1 and 2), picks the
+ * cheapest removal and the largest gain (ties: lowest group index), evaluates the pair's exact effect
+ * (Case 3) and applies it by low-rank up/downdates if obj drops by more than rel_tol*obj; otherwise
+ * the search stops.  At most max_swaps (<= desc.max_swaps) iterations.
+ * flags: OSSCAR_SEARCH_ALWAYS_ACCEPT applies every selected pair (Algorithm 1 as printed).
+ * refresh_every > 0 recomputes V, R and B from P, H, G by GEMM after that many accepted swaps.
+ * Optional host outputs of length max_swaps (entry i describes iteration i, including a final rejected
+ * one): trace_out / trace_in = group leaving / entering; trace_gap[2i], trace_gap[2i+1] = relative gap
+ * between best and second-best removal cost / addition gain; trace_obj[i] = obj after the iteration. */
+enum { OSSCAR_SEARCH_ALWAYS_ACCEPT = 1u };
+typedef struct {
+  int32_t iters;     /* iterations run (accepted swaps + at most one rejected) */
+  int32_t accepted;  /* swaps applied */
+  double obj_initial;
+  double obj_final;  /* tracked through the updates */
+} osscar_search_result;
+osscar_status osscar_local_search(osscar_ctx* ctx, int32_t max_swaps, double rel_tol, uint32_t flags,
+                                  int32_t refresh_every, osscar_search_result* res_host, int32_t* trace_out_host,
+                                  int32_t* trace_in_host, float* trace_gap_host, double* trace_obj_host);
+
+/* Test hook: applies the swap (group g_out leaves, g_in enters) unconditionally (Case 3). */
+osscar_status osscar_apply_swap(osscar_ctx* ctx, int32_t g_out, int32_t g_in);
+
+/* Final weights (closed-form optimum for the final kept set, Appendix A.1): What_K = (H_KK)^-1 G_K from a
+ * fresh factorisation with one step of float64-residual refinement, other rows zero.
+ * What_dev: dev, row-major d1 x m, leading dimension ldw_hat, dtype out_dtype.  support_host (may be
+ * NULL): the k kept groups, ascending.  *obj_host (may be NULL): c0 - Tr(G_K^T What_K). */
+osscar_status osscar_backsolve(osscar_ctx* ctx, void* What_dev, int64_t ldw_hat, int32_t out_dtype,
+                               int32_t* support_host, double* obj_host);
+
+/* Inspection hook: copies an internal array to dst_dev (dev, dense row-major).  float32: H d1 x d1;
+ * G d1 x m; P kr x kr; B kr x m; V kr x cr; R cr x m (kr = k*q, cr = d1 - kr; rows / columns follow the
+ * kept groups, resp. the other groups, in ascending group order).  float64: REM, ADD: length p, indexed
+ * by group id (+inf / -inf where not applicable).  int32: KEPT_SLOTS / CAND_SLOTS: the kept / other
+ * group ids, ascending. */
+enum { OSSCAR_T_H = 0, OSSCAR_T_G = 1, OSSCAR_T_P = 2, OSSCAR_T_B = 3, OSSCAR_T_V = 4, OSSCAR_T_R = 5,
+       OSSCAR_T_REM = 6, OSSCAR_T_ADD = 7, OSSCAR_T_KEPT_SLOTS = 8, OSSCAR_T_CAND_SLOTS = 9 };
+osscar_status osscar_get_tensor(osscar_ctx* ctx, int which, void* dst_dev, size_t dst_bytes);
+
+/* Scalars of the last finalize: lambda, c0 (host float64). */
+osscar_status osscar_get_scalars(osscar_ctx* ctx, double* lambda_host, double* c0_host);
+
+/* Device times of the last call of each kind, in milliseconds (HIP events on the context's stream):
+ * [0] the Gram accumulation of the chunk passed together with finalize, [1] finalize, [2] init_support,
+ * [3] local_search, [4] backsolve, [5] mean duration of one launch of the search's bulk update of N
+ * (sampled once per batch of iterations), [6] total time of the search's refreshes, [7] mean duration of one
+ * launch of the search's update of Z.  out_host: 8 doubles. */
+osscar_status osscar_get_timers(osscar_ctx* ctx, double* out_host);
+
+const char* osscar_last_error(const osscar_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OSSCAR_H */

@@ -1,0 +1,684 @@
+// C interface of libosscar: context, workspace carve-up and host-side orchestration of the kernels.
+#include "../../include/osscar.h"
+#include "internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <numeric>
+#include <string>
+#include <vector>
+
+using namespace osscar;
+
+namespace {
+
+constexpr int64_t XT_ROWS = 4096;   // calibration rows per sub-step of the generic (non-MFMA-bf16) Gram path
+constexpr int EV_SAMPLES = 64;
+
+size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+struct Carve {
+  char* base; size_t off;
+  explicit Carve(void* b) : base(reinterpret_cast<char*>(b)), off(0) {}
+  template <typename T> T* take(size_t count) {
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += align_up(count * sizeof(T));
+    return p;
+  }
+};
+
+__global__ void fill_f64_kernel(double* p, int64_t n, double v) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
+}
+__global__ void fill_f32_kernel(float* p, int64_t n, float v) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
+}
+__global__ void symmetrize_kernel(const float* __restrict__ A, float* __restrict__ out, int n) {
+  int64_t tot = (int64_t)n * n;
+  for (int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; idx < tot; idx += (int64_t)gridDim.x * blockDim.x) {
+    int i = (int)(idx / n), j = (int)(idx % n);
+    out[idx] = 0.5f * (A[idx] + A[(int64_t)j * n + i]);
+  }
+}
+__global__ void add_inplace_kernel(float* __restrict__ a, const float* __restrict__ b, int64_t n) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) a[i] += b[i];
+}
+// dst[i][j] = sign * Nsym(rows[i], cols[j])
+__global__ void gather_sym_kernel(const float* __restrict__ N, int64_t ld, const int32_t* __restrict__ rows, int nrows,
+                                  const int32_t* __restrict__ cols, int ncols, float* __restrict__ dst, float sign) {
+  int64_t tot = (int64_t)nrows * ncols;
+  for (int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; idx < tot; idx += (int64_t)gridDim.x * blockDim.x) {
+    int i = (int)(idx / ncols), j = (int)(idx % ncols);
+    int64_t r = rows[i], c = cols[j];
+    int64_t hi = r > c ? r : c, lo = r > c ? c : r;
+    dst[idx] = sign * N[hi * ld + lo];
+  }
+}
+int grid_for(int64_t n) { int64_t b = (n + 1023) / 1024; return (int)std::min<int64_t>(std::max<int64_t>(b, 1), 131072); }
+
+}  // namespace
+
+struct osscar_ctx {
+  osscar_desc desc;
+  hipStream_t stream;
+  int d1, m, p, q, k, kr, cr;
+  bool poisoned = false;
+  std::string err;
+  enum Phase { FRESH, ACCUM, FINAL, READY } phase = FRESH;
+
+  // persistent device arrays
+  float *H, *G, *N, *Z;
+  double *norms2, *score, *gram, *dblk, *small, *scal, *partial;
+  int32_t *kept, *rowsK, *rowsC, *notpd;
+  float *C1, *C2, *Cblk, *rZ1, *rZ2;
+  SearchCtrl* ctrl;
+  int32_t *trace_out, *trace_in; float* trace_gap; double* trace_obj;
+  // phase-shared scratch
+  char* scratch; size_t scratch_bytes;
+
+  double lambda = 0, c0 = 0;
+  std::vector<double> norms_host;
+  std::vector<int32_t> kept_host;
+  double timers[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  hipEvent_t ev_a = nullptr, ev_b = nullptr;
+  hipEvent_t ev_s[EV_SAMPLES][3];
+  bool ev_ok = false;
+};
+
+namespace {
+
+struct Layout {
+  size_t total = 0, scratch_bytes = 0;
+};
+
+// Carves (or just sizes, when base == nullptr) the workspace for a description.
+Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
+  const int64_t d1 = ds.d1, m = ds.m, p = ds.p, q = ds.q, kr = (int64_t)ds.k * q, cr = d1 - kr;
+  const int64_t ms = std::max<int32_t>(ds.max_swaps, 1);
+  Carve cv(base);
+  float* H = cv.take<float>(d1 * d1);
+  float* G = cv.take<float>(d1 * m);
+  float* N = cv.take<float>(d1 * d1);
+  float* Z = cv.take<float>(d1 * m);
+  double* norms2 = cv.take<double>(p);
+  double* score = cv.take<double>(p);
+  double* gram = cv.take<double>(p * q * q);
+  double* dblk = cv.take<double>(p * q * q);
+  double* small = cv.take<double>(std::max<int64_t>(16 * q * q, 64 * 64));
+  double* scal = cv.take<double>(1024);
+  double* partial = cv.take<double>(2048);
+  int32_t* kept = cv.take<int32_t>(p);
+  int32_t* rowsK = cv.take<int32_t>(d1);
+  int32_t* rowsC = cv.take<int32_t>(d1);
+  int32_t* notpd = cv.take<int32_t>(64);
+  float* C1 = cv.take<float>(d1 * q);
+  float* C2 = cv.take<float>(d1 * q);
+  float* Cblk = cv.take<float>(4 * d1 * q);
+  float* rZ1 = cv.take<float>(q * m);
+  float* rZ2 = cv.take<float>(q * m);
+  SearchCtrl* ctrl = cv.take<SearchCtrl>(4);
+  int32_t* trace_out = cv.take<int32_t>(ms);
+  int32_t* trace_in = cv.take<int32_t>(ms);
+  float* trace_gap = cv.take<float>(2 * ms);
+  double* trace_obj = cv.take<double>(ms);
+  // scratch: the larger of the Gram phase and the init / refresh / backsolve phase
+  size_t gram_phase = align_up((size_t)d1 * d1 * 8) + align_up((size_t)d1 * m * 4) + align_up((size_t)d1 * XT_ROWS * 4);
+  size_t init_phase = 4 * align_up((size_t)kr * kr * 4) + 3 * align_up((size_t)kr * cr * 4) + align_up((size_t)cr * cr * 4) +
+                      4 * align_up((size_t)kr * m * 4) + align_up((size_t)cr * m * 4) + 3 * align_up((size_t)kr * 64 * 4) + 4096;
+  size_t scratch_bytes = std::max(gram_phase, init_phase);
+  char* scratch = cv.take<char>(scratch_bytes);
+  if (c) {
+    c->H = H; c->G = G; c->N = N; c->Z = Z; c->norms2 = norms2; c->score = score; c->gram = gram; c->dblk = dblk;
+    c->small = small; c->scal = scal; c->partial = partial; c->kept = kept; c->rowsK = rowsK; c->rowsC = rowsC;
+    c->notpd = notpd; c->C1 = C1; c->C2 = C2; c->Cblk = Cblk; c->rZ1 = rZ1; c->rZ2 = rZ2; c->ctrl = ctrl;
+    c->trace_out = trace_out; c->trace_in = trace_in; c->trace_gap = trace_gap; c->trace_obj = trace_obj;
+    c->scratch = scratch; c->scratch_bytes = scratch_bytes;
+  }
+  Layout L; L.total = cv.off; L.scratch_bytes = scratch_bytes;
+  return L;
+}
+
+bool desc_ok(const osscar_desc* d) {
+  if (!d) return false;
+  if (d->d1 <= 0 || d->m <= 0 || d->p <= 0 || d->q <= 0 || d->q > 64) return false;
+  if ((int64_t)d->p * d->q != d->d1) return false;
+  if (d->k < 1 || d->k > d->p) return false;
+  if (d->d1 > 65536 || d->m > 65536 || d->max_swaps < 0) return false;
+  if (d->x_dtype != OSSCAR_F32 && d->x_dtype != OSSCAR_BF16) return false;
+  if (d->w_dtype != OSSCAR_F32 && d->w_dtype != OSSCAR_BF16) return false;
+  return true;
+}
+
+osscar_status fail(osscar_ctx* c, osscar_status st, const char* fmt, ...) {
+  char buf[512];
+  va_list ap; va_start(ap, fmt); vsnprintf(buf, sizeof buf, fmt, ap); va_end(ap);
+  if (c) { c->err = buf; if (st != OSSCAR_EINVAL && st != OSSCAR_ESTATE) c->poisoned = true; }
+  return st;
+}
+
+#define HIPCHK(c, expr)                                                                           \
+  do {                                                                                            \
+    hipError_t e__ = (expr);                                                                      \
+    if (e__ != hipSuccess) return fail((c), OSSCAR_EHIP, "%s failed: %s", #expr, hipGetErrorString(e__)); \
+  } while (0)
+
+TabDims dims(const osscar_ctx* c) { return TabDims{c->d1, c->m, c->p, c->q}; }
+TabPtrs ptrs(const osscar_ctx* c) {
+  TabPtrs t{};
+  t.N = c->N; t.Z = c->Z; t.kept = c->kept; t.score = c->score; t.gram = c->gram; t.dblk = c->dblk;
+  t.C1 = c->C1; t.C2 = c->C2; t.C1D = c->Cblk; t.C2D = c->Cblk + (int64_t)c->d1 * c->q;
+  t.rZ1 = c->rZ1; t.rZ2 = c->rZ2; t.small = c->small; t.ctrl = c->ctrl;
+  t.trace_out = c->trace_out; t.trace_in = c->trace_in; t.trace_gap = c->trace_gap; t.trace_obj = c->trace_obj;
+  return t;
+}
+
+hipError_t gemm(hipStream_t s, int M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb, const float* Cin,
+                int64_t ldcin, float* C, int64_t ldc, double alpha, double beta, double diag_add = 0.0, int lower_only = 0,
+                int trans_b = 0) {
+  GemmArgs g{};
+  g.M = M; g.N = N; g.K = K; g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.Cin = Cin; g.ldcin = ldcin; g.C = C; g.ldc = ldc;
+  g.alpha = alpha; g.beta = beta; g.diag_add = diag_add; g.c_is_f64 = 0; g.lower_only = lower_only; g.trans_b = trans_b;
+  return launch_gemm_f64acc(g, s);
+}
+
+// Host copy of the membership flags -> sorted row lists on the device.
+osscar_status upload_rows(osscar_ctx* c) {
+  std::vector<int32_t> rk, rc;
+  rk.reserve(c->kr); rc.reserve(c->cr);
+  for (int g = 0; g < c->p; g++)
+    for (int r = 0; r < c->q; r++) (c->kept_host[g] ? rk : rc).push_back(g * c->q + r);
+  if ((int)rk.size() != c->kr) return fail(c, OSSCAR_ESTATE, "internal: kept set has %zu rows, expected %d", rk.size(), c->kr);
+  HIPCHK(c, hipMemcpyAsync(c->rowsK, rk.data(), rk.size() * 4, hipMemcpyHostToDevice, c->stream));
+  if (!rc.empty()) HIPCHK(c, hipMemcpyAsync(c->rowsC, rc.data(), rc.size() * 4, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));   // the vectors die at return
+  return OSSCAR_OK;
+}
+
+// P = (H_KK)^-1 (full, symmetric) and B = P G_K with one float64-residual refinement step, for the rows in
+// c->rowsK.  Buffers come from the scratch region: HKK (kept), P, T1, T2 (kr x kr each), GK, B (kr x m), T3, T4.
+struct InvBufs { float *HKK, *P, *T1, *T2, *GK, *B, *T3, *T4, *panels; };
+
+osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b) {
+  hipStream_t s = c->stream;
+  const int kr = c->kr, m = c->m;
+  HIPCHK(c, launch_gather(c->H, c->d1, c->rowsK, kr, c->rowsK, kr, b.HKK, kr, s));
+  HIPCHK(c, launch_gather(c->H, c->d1, c->rowsK, kr, c->rowsK, kr, b.P, kr, s));
+  HIPCHK(c, hipMemsetAsync(c->notpd, 0, 64 * 4, s));
+  HIPCHK(c, spd_inverse_inplace(b.P, kr, b.panels, b.panels + (int64_t)kr * 64, c->small, c->notpd, s));
+  // Newton-Schulz: P <- P + P (I - H_KK P), residual accumulated in float64
+  for (int step = 0; step < 3; step++) {
+    HIPCHK(c, gemm(s, kr, kr, kr, b.HKK, kr, b.P, kr, nullptr, 0, b.T1, kr, -1.0, 0.0, 1.0));
+    HIPCHK(c, launch_absmax(b.T1, (int64_t)kr * kr, c->partial, s));
+    HIPCHK(c, gemm(s, kr, kr, kr, b.P, kr, b.T1, kr, b.P, kr, b.T2, kr, 1.0, 1.0));
+    hipLaunchKernelGGL(symmetrize_kernel, dim3(grid_for((int64_t)kr * kr)), dim3(256), 0, s, b.T2, b.P, kr);
+    double part[256]; int32_t bad = 0;
+    HIPCHK(c, hipMemcpyAsync(part, c->partial, sizeof part, hipMemcpyDeviceToHost, s));
+    HIPCHK(c, hipMemcpyAsync(&bad, c->notpd, 4, hipMemcpyDeviceToHost, s));
+    HIPCHK(c, hipStreamSynchronize(s));
+    double resid = 0; for (double v : part) resid = std::max(resid, v);
+    if (bad || !(resid < 0.9))
+      return fail(c, OSSCAR_ENOTPD, "H restricted to the kept rows is not positive definite to working precision "
+                                     "(pivot flag %d, |I - H P|_max = %.3g)", bad, resid);
+    if (resid < 1e-3) break;     // one more step squares it below float32 resolution
+  }
+  // B = P G_K, then B += P (G_K - H_KK B)
+  HIPCHK(c, launch_gather(c->G, m, c->rowsK, kr, nullptr, m, b.GK, m, s));
+  HIPCHK(c, gemm(s, kr, m, kr, b.P, kr, b.GK, m, nullptr, 0, b.T3, m, 1.0, 0.0));
+  HIPCHK(c, gemm(s, kr, m, kr, b.HKK, kr, b.T3, m, b.GK, m, b.T4, m, -1.0, 1.0));
+  HIPCHK(c, gemm(s, kr, m, kr, b.P, kr, b.T4, m, b.T3, m, b.B, m, 1.0, 1.0));
+  return OSSCAR_OK;
+}
+
+InvBufs carve_inv(osscar_ctx* c, Carve& cv) {
+  const int64_t kr = c->kr, m = c->m;
+  InvBufs b;
+  b.HKK = cv.take<float>(kr * kr); b.P = cv.take<float>(kr * kr); b.T1 = cv.take<float>(kr * kr); b.T2 = cv.take<float>(kr * kr);
+  b.GK = cv.take<float>(kr * m); b.B = cv.take<float>(kr * m); b.T3 = cv.take<float>(kr * m); b.T4 = cv.take<float>(kr * m);
+  b.panels = cv.take<float>(3 * kr * 64);
+  return b;
+}
+
+// obj = c0 - <G_K, B>
+osscar_status objective_from(osscar_ctx* c, const float* GK, const float* B, double* obj) {
+  HIPCHK(c, launch_dot64(GK, B, (int64_t)c->kr * c->m, c->scal + 8, c->partial, c->stream));
+  double dot = 0;
+  HIPCHK(c, hipMemcpyAsync(&dot, c->scal + 8, 8, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  *obj = c->c0 - dot;
+  return OSSCAR_OK;
+}
+
+// Builds N, Z, the scores and the tracked objective for the kept set in c->kept_host.
+osscar_status build_state(osscar_ctx* c, double* obj_out) {
+  hipStream_t s = c->stream;
+  const int d1 = c->d1, m = c->m, kr = c->kr, cr = c->cr;
+  osscar_status st = upload_rows(c);
+  if (st != OSSCAR_OK) return st;
+  HIPCHK(c, hipMemcpyAsync(c->kept, c->kept_host.data(), c->p * 4, hipMemcpyHostToDevice, s));
+  Carve cv(c->scratch);
+  InvBufs b = carve_inv(c, cv);
+  float* HKC = cv.take<float>((int64_t)kr * cr);
+  float* V = cv.take<float>((int64_t)kr * cr);
+  float* HCK = cv.take<float>((int64_t)cr * kr);
+  float* S = cv.take<float>((int64_t)cr * cr);
+  float* R = cv.take<float>((int64_t)cr * m);
+  if (cv.off > c->scratch_bytes) return fail(c, OSSCAR_ENOMEM, "internal: scratch carve-up exceeds the workspace");
+  st = inverse_and_weights(c, b);
+  if (st != OSSCAR_OK) return st;
+  if (cr > 0) {
+    HIPCHK(c, launch_gather(c->H, d1, c->rowsK, kr, c->rowsC, cr, HKC, cr, s));
+    HIPCHK(c, launch_gather(c->H, d1, c->rowsC, cr, c->rowsK, kr, HCK, kr, s));
+    HIPCHK(c, launch_gather(c->H, d1, c->rowsC, cr, c->rowsC, cr, S, cr, s));
+    HIPCHK(c, launch_gather(c->G, m, c->rowsC, cr, nullptr, m, R, m, s));
+    HIPCHK(c, gemm(s, kr, cr, kr, b.P, kr, HKC, cr, nullptr, 0, V, cr, 1.0, 0.0));             // V = P H_{K,Kc}
+    HIPCHK(c, gemm(s, cr, cr, kr, HCK, kr, V, cr, S, cr, S, cr, -1.0, 1.0, 0.0, 1));            // S = H_cc - H_cK V (lower)
+    HIPCHK(c, gemm(s, cr, m, kr, HCK, kr, b.B, m, R, m, R, m, -1.0, 1.0));                      // R = G_c - H_cK B
+    HIPCHK(c, launch_scatter(V, cr, c->rowsK, kr, c->rowsC, cr, c->N, d1, 1.f, 0, s));
+    HIPCHK(c, launch_scatter(S, cr, c->rowsC, cr, c->rowsC, cr, c->N, d1, 1.f, 1, s));
+    HIPCHK(c, launch_scatter_rows(R, m, c->rowsC, cr, m, c->Z, m, 0, s));
+  }
+  HIPCHK(c, launch_scatter(b.P, kr, c->rowsK, kr, c->rowsK, kr, c->N, d1, -1.f, 1, s));
+  HIPCHK(c, launch_scatter_rows(b.B, m, c->rowsK, kr, m, c->Z, m, 0, s));
+  HIPCHK(c, launch_refresh_scores(dims(c), ptrs(c), s));
+  double obj = 0;
+  st = objective_from(c, b.GK, b.B, &obj);
+  if (st != OSSCAR_OK) return st;
+  if (obj_out) *obj_out = obj;
+  return OSSCAR_OK;
+}
+
+osscar_status read_kept(osscar_ctx* c) {
+  c->kept_host.resize(c->p);
+  HIPCHK(c, hipMemcpyAsync(c->kept_host.data(), c->kept, c->p * 4, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return OSSCAR_OK;
+}
+
+osscar_status check_ctx(osscar_ctx* c) {
+  if (!c) return OSSCAR_EINVAL;
+  if (c->poisoned) return OSSCAR_ESTATE;
+  return OSSCAR_OK;
+}
+
+double elapsed(osscar_ctx* c) {
+  float ms = 0;
+  if (c->ev_ok && hipEventSynchronize(c->ev_b) == hipSuccess) hipEventElapsedTime(&ms, c->ev_a, c->ev_b);
+  return ms;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t osscar_workspace_bytes(const osscar_desc* desc) {
+  if (!desc_ok(desc)) return 0;
+  return carve_all(*desc, nullptr, nullptr).total + 256;
+}
+
+osscar_status osscar_create(osscar_ctx** out, const osscar_desc* desc, void* workspace_dev, size_t workspace_bytes,
+                            void* hip_stream) {
+  if (!out) return OSSCAR_EINVAL;
+  *out = nullptr;
+  if (!desc_ok(desc) || !workspace_dev) return OSSCAR_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(workspace_dev) & 255) != 0) return OSSCAR_EINVAL;
+  size_t need = carve_all(*desc, nullptr, nullptr).total + 256;
+  if (workspace_bytes < need) return OSSCAR_ENOMEM;
+  osscar_ctx* c = new (std::nothrow) osscar_ctx();
+  if (!c) return OSSCAR_ENOMEM;
+  c->desc = *desc;
+  c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  c->d1 = (int)desc->d1; c->m = (int)desc->m; c->p = desc->p; c->q = desc->q; c->k = desc->k;
+  c->kr = desc->k * desc->q; c->cr = c->d1 - c->kr;
+  carve_all(*desc, workspace_dev, c);
+  c->ev_ok = (hipEventCreate(&c->ev_a) == hipSuccess) && (hipEventCreate(&c->ev_b) == hipSuccess);
+  for (int i = 0; i < EV_SAMPLES && c->ev_ok; i++)
+    for (int j = 0; j < 3; j++) c->ev_ok = c->ev_ok && (hipEventCreate(&c->ev_s[i][j]) == hipSuccess);
+  if (!c->ev_ok) { delete c; return OSSCAR_EHIP; }
+  *out = c;
+  return OSSCAR_OK;
+}
+
+osscar_status osscar_destroy(osscar_ctx* c) {
+  if (!c) return OSSCAR_EINVAL;
+  hipStreamSynchronize(c->stream);
+  if (c->ev_a) hipEventDestroy(c->ev_a);
+  if (c->ev_b) hipEventDestroy(c->ev_b);
+  for (int i = 0; i < EV_SAMPLES; i++)
+    for (int j = 0; j < 3; j++) hipEventDestroy(c->ev_s[i][j]);
+  delete c;
+  return OSSCAR_OK;
+}
+
+const char* osscar_last_error(const osscar_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+osscar_status osscar_gram(osscar_ctx* c, const void* Xc, int64_t n_c, int64_t ldx, int finalize, const void* W, int64_t ldw,
+                          double lambda_abs, double lambda_rel) {
+  osscar_status st = check_ctx(c);
+  if (st != OSSCAR_OK) return st;
+  if (n_c < 0 || (n_c > 0 && (!Xc || ldx < c->d1))) return fail(c, OSSCAR_EINVAL, "osscar_gram: bad chunk (n_c=%lld, ldx=%lld)", (long long)n_c, (long long)ldx);
+  if (finalize && (!W || ldw < c->m)) return fail(c, OSSCAR_EINVAL, "osscar_gram: finalize needs W with ldw >= m");
+  hipStream_t s = c->stream;
+  const int d1 = c->d1, m = c->m;
+  Carve cv(c->scratch);
+  double* H64 = cv.take<double>((int64_t)d1 * d1);
+  float* Wf = cv.take<float>((int64_t)d1 * m);
+  float* Xt = cv.take<float>((int64_t)d1 * XT_ROWS);
+  if (c->phase != osscar_ctx::ACCUM) {   // first chunk of a layer
+    hipLaunchKernelGGL(fill_f64_kernel, dim3(grid_for((int64_t)d1 * d1)), dim3(256), 0, s, H64, (int64_t)d1 * d1, 0.0);
+    c->phase = osscar_ctx::ACCUM;
+    c->timers[0] = 0;
+  }
+  if (n_c > 0) {
+    HIPCHK(c, hipEventRecord(c->ev_a, s));
+    const bool bf16 = c->desc.x_dtype == OSSCAR_BF16;
+    const bool fast = bf16 && (d1 % 8 == 0) && (ldx % 8 == 0) && ((reinterpret_cast<uintptr_t>(Xc) & 15) == 0);
+    if (fast) {
+      HIPCHK(c, launch_gram_bf16(Xc, n_c, ldx, d1, H64, s));
+    } else {
+      const size_t esz = bf16 ? 2 : 4;
+      for (int64_t r0 = 0; r0 < n_c; r0 += XT_ROWS) {
+        int64_t nr = std::min<int64_t>(XT_ROWS, n_c - r0);
+        const char* src = reinterpret_cast<const char*>(Xc) + (size_t)r0 * ldx * esz;
+        HIPCHK(c, launch_transpose_to_f32(src, bf16, nr, d1, ldx, Xt, XT_ROWS, s));
+        GemmArgs g{};
+        g.M = d1; g.N = d1; g.K = (int)nr; g.A = Xt; g.lda = XT_ROWS; g.B = Xt; g.ldb = XT_ROWS; g.trans_b = 1;
+        g.Cin = reinterpret_cast<const float*>(H64); g.ldcin = d1; g.C = H64; g.ldc = d1; g.alpha = 1.0; g.beta = 1.0;
+        g.c_is_f64 = 1; g.lower_only = 1;
+        HIPCHK(c, launch_gemm_f64acc(g, s));
+      }
+    }
+    HIPCHK(c, hipEventRecord(c->ev_b, s));
+    if (finalize) c->timers[0] += elapsed(c);
+  }
+  if (!finalize) return OSSCAR_OK;
+
+  HIPCHK(c, hipEventRecord(c->ev_a, s));
+  HIPCHK(c, launch_trace64(H64, d1, c->scal, s));
+  double tr = 0;
+  HIPCHK(c, hipMemcpyAsync(&tr, c->scal, 8, hipMemcpyDeviceToHost, s));
+  HIPCHK(c, hipStreamSynchronize(s));
+  c->lambda = lambda_abs + lambda_rel * tr / d1;
+  HIPCHK(c, hipMemcpyAsync(c->scal + 1, &c->lambda, 8, hipMemcpyHostToDevice, s));
+  HIPCHK(c, launch_finalize_H(H64, c->H, d1, c->scal + 1, s));
+  HIPCHK(c, launch_convert_to_f32(W, c->desc.w_dtype == OSSCAR_BF16, d1, m, ldw, Wf, s));
+  HIPCHK(c, gemm(s, d1, m, d1, c->H, d1, Wf, m, nullptr, 0, c->G, m, 1.0, 0.0));
+  HIPCHK(c, launch_dot64(Wf, c->G, (int64_t)d1 * m, c->scal + 2, c->partial, s));
+  HIPCHK(c, launch_group_norms(Wf, c->p, c->q, m, c->norms2, s));
+  c->norms_host.resize(c->p);
+  HIPCHK(c, hipMemcpyAsync(&c->c0, c->scal + 2, 8, hipMemcpyDeviceToHost, s));
+  HIPCHK(c, hipMemcpyAsync(c->norms_host.data(), c->norms2, c->p * 8, hipMemcpyDeviceToHost, s));
+  HIPCHK(c, hipEventRecord(c->ev_b, s));
+  HIPCHK(c, hipStreamSynchronize(s));
+  c->timers[1] = elapsed(c);
+  for (auto& v : c->norms_host) v = std::sqrt(v);
+  c->phase = osscar_ctx::FINAL;
+  return OSSCAR_OK;
+}
+
+osscar_status osscar_set_quadratic(osscar_ctx* c, const float* H_dev, const float* G_dev, double c0, const double* norms) {
+  osscar_status st = check_ctx(c);
+  if (st != OSSCAR_OK) return st;
+  if (!H_dev || !G_dev || !norms) return fail(c, OSSCAR_EINVAL, "osscar_set_quadratic: NULL argument");
+  hipStream_t s = c->stream;
+  HIPCHK(c, hipMemcpyAsync(c->H, H_dev, (size_t)c->d1 * c->d1 * 4, hipMemcpyDeviceToDevice, s));
+  HIPCHK(c, hipMemcpyAsync(c->G, G_dev, (size_t)c->d1 * c->m * 4, hipMemcpyDeviceToDevice, s));
+  HIPCHK(c, hipStreamSynchronize(s));
+  c->c0 = c0; c->lambda = 0;
+  c->norms_host.assign(norms, norms + c->p);
+  c->phase = osscar_ctx::FINAL;
+  return OSSCAR_OK;
+}
+
+osscar_status osscar_init_support(osscar_ctx* c, int mode, const int32_t* groups, double* obj_host) {
+  osscar_status st = check_ctx(c);
+  if (st != OSSCAR_OK) return st;
+  if (c->phase != osscar_ctx::FINAL && c->phase != osscar_ctx::READY)
+    return fail(c, OSSCAR_ESTATE, "osscar_init_support: no quadratic form yet (call osscar_gram with finalize first)");
+  c->kept_host.assign(c->p, 0);
+  if (mode == OSSCAR_INIT_MAGNITUDE) {
+    std::vector<int32_t> order(c->p);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return c->norms_host[a] > c->norms_host[b]; });
+    for (int i = 0; i < c->k; i++) c->kept_host[order[i]] = 1;
+  } else if (mode == OSSCAR_INIT_GIVEN) {
+    if (!groups) return fail(c, OSSCAR_EINVAL, "osscar_init_support: groups_host is NULL");
+    for (int i = 0; i < c->k; i++) {
+      int g = groups[i];
+      if (g < 0 || g >= c->p || c->kept_host[g]) return fail(c, OSSCAR_EINVAL, "osscar_init_support: group %d out of range or repeated", g);
+      c->kept_host[g] = 1;
+    }
+  } else {
+    return fail(c, OSSCAR_EINVAL, "osscar_init_support: unknown mode %d", mode);
+  }
+  HIPCHK(c, hipEventRecord(c->ev_a, c->stream));
+  double obj = 0;
+  st = build_state(c, &obj);
+  if (st != OSSCAR_OK) return st;
+  SearchCtrl h{};
+  h.obj = obj; h.g_out = -1; h.g_in = -1;
+  HIPCHK(c, hipMemcpyAsync(c->ctrl, &h, sizeof h, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(c, hipEventRecord(c->ev_b, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  c->timers[2] = elapsed(c);
+  if (obj_host) *obj_host = obj;
+  c->phase = osscar_ctx::READY;
+  return OSSCAR_OK;
+}
+
+static osscar_status read_ctrl(osscar_ctx* c, SearchCtrl* h) {
+  HIPCHK(c, hipMemcpyAsync(h, c->ctrl, sizeof *h, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return OSSCAR_OK;
+}
+
+osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_tol, uint32_t flags, int32_t refresh_every,
+                                  osscar_search_result* res, int32_t* t_out, int32_t* t_in, float* t_gap, double* t_obj) {
+  osscar_status st = check_ctx(c);
+  if (st != OSSCAR_OK) return st;
+  if (c->phase != osscar_ctx::READY) return fail(c, OSSCAR_ESTATE, "osscar_local_search: call osscar_init_support first");
+  if (max_swaps < 0 || max_swaps > c->desc.max_swaps || rel_tol < 0)
+    return fail(c, OSSCAR_EINVAL, "osscar_local_search: max_swaps %d outside [0, desc.max_swaps = %d] or rel_tol < 0", max_swaps, c->desc.max_swaps);
+  hipStream_t s = c->stream;
+  SearchCtrl h{};
+  st = read_ctrl(c, &h);
+  if (st != OSSCAR_OK) return st;
+  const double obj0 = h.obj;
+  h.done = (c->cr == 0) ? 1 : 0; h.iters = 0; h.accepted = 0; h.notpd = 0; h.rel_tol = rel_tol; h.g_out = h.g_in = -1;
+  HIPCHK(c, hipMemcpyAsync(c->ctrl, &h, sizeof h, hipMemcpyHostToDevice, s));
+  HIPCHK(c, hipStreamSynchronize(s));
+  const int always = (flags & OSSCAR_SEARCH_ALWAYS_ACCEPT) ? 1 : 0;
+  TabDims d = dims(c);
+  TabPtrs t = ptrs(c);
+  HIPCHK(c, hipEventRecord(c->ev_a, s));
+  int launched = 0, since_refresh_base = 0, samples = 0;
+  double refresh_ms = 0, upd_n_ms = 0, upd_z_ms = 0;
+  const int BATCH = 32;
+  while (launched < max_swaps && !h.done) {
+    int nb = std::min(BATCH, max_swaps - launched);
+    if (refresh_every > 0) nb = std::min(nb, std::max(1, refresh_every - (h.accepted - since_refresh_base)));
+    const bool sample = samples + 1 < EV_SAMPLES;
+    for (int i = 0; i < nb; i++) {
+      HIPCHK(c, launch_search_iteration(d, t, -1, -1, always, s, (i == 0 && sample) ? c->ev_s[samples + 1] : nullptr));
+    }
+    launched += nb;
+    st = read_ctrl(c, &h);
+    if (st != OSSCAR_OK) return st;
+    if (sample) {   // the sampled iteration ran its updates unless the search had already stopped before it
+      float a = 0, b = 0;
+      hipEventElapsedTime(&a, c->ev_s[samples + 1][0], c->ev_s[samples + 1][1]);
+      hipEventElapsedTime(&b, c->ev_s[samples + 1][1], c->ev_s[samples + 1][2]);
+      upd_n_ms += a; upd_z_ms += b; samples++;
+    }
+    if (h.notpd) return fail(c, OSSCAR_ENOTPD, "osscar_local_search: a pivot block lost definiteness at iteration %d", h.iters);
+    if (!h.done && refresh_every > 0 && h.accepted - since_refresh_base >= refresh_every && launched < max_swaps) {
+      hipEvent_t r0 = c->ev_s[0][0], r1 = c->ev_s[0][1];
+      HIPCHK(c, hipEventRecord(r0, s));
+      st = read_kept(c);
+      if (st != OSSCAR_OK) return st;
+      double obj = 0;
+      st = build_state(c, &obj);
+      if (st != OSSCAR_OK) return st;
+      HIPCHK(c, hipMemcpyAsync(reinterpret_cast<char*>(c->ctrl) + offsetof(SearchCtrl, obj), &obj, 8, hipMemcpyHostToDevice, s));
+      HIPCHK(c, hipEventRecord(r1, s));
+      HIPCHK(c, hipStreamSynchronize(s));
+      float ms = 0; hipEventElapsedTime(&ms, r0, r1); refresh_ms += ms;
+      since_refresh_base = h.accepted;
+      h.obj = obj;
+    }
+  }
+  HIPCHK(c, hipEventRecord(c->ev_b, s));
+  st = read_ctrl(c, &h);
+  if (st != OSSCAR_OK) return st;
+  c->timers[3] = elapsed(c);
+  c->timers[6] = refresh_ms;
+  c->timers[5] = samples ? upd_n_ms / samples : 0;
+  c->timers[7] = samples ? upd_z_ms / samples : 0;
+  if (res) { res->iters = h.iters; res->accepted = h.accepted; res->obj_initial = obj0; res->obj_final = h.obj; }
+  const int n = h.iters;
+  if (n > 0) {
+    if (t_out) HIPCHK(c, hipMemcpyAsync(t_out, c->trace_out, n * 4, hipMemcpyDeviceToHost, s));
+    if (t_in) HIPCHK(c, hipMemcpyAsync(t_in, c->trace_in, n * 4, hipMemcpyDeviceToHost, s));
+    if (t_gap) HIPCHK(c, hipMemcpyAsync(t_gap, c->trace_gap, n * 8, hipMemcpyDeviceToHost, s));
+    if (t_obj) HIPCHK(c, hipMemcpyAsync(t_obj, c->trace_obj, n * 8, hipMemcpyDeviceToHost, s));
+    HIPCHK(c, hipStreamSynchronize(s));
+  }
+  return OSSCAR_OK;
+}
+
+osscar_status osscar_apply_swap(osscar_ctx* c, int32_t g_out, int32_t g_in) {
+  osscar_status st = check_ctx(c);
+  if (st != OSSCAR_OK) return st;
+  if (c->phase != osscar_ctx::READY) return fail(c, OSSCAR_ESTATE, "osscar_apply_swap: call osscar_init_support first");
+  if (g_out < 0 || g_out >= c->p || g_in < 0 || g_in >= c->p) return fail(c, OSSCAR_EINVAL, "osscar_apply_swap: group out of range");
+  st = read_kept(c);
+  if (st != OSSCAR_OK) return st;
+  if (!c->kept_host[g_out] || c->kept_host[g_in]) return fail(c, OSSCAR_EINVAL, "osscar_apply_swap: %d must be kept and %d must not", g_out, g_in);
+  SearchCtrl h{};
+  st = read_ctrl(c, &h);
+  if (st != OSSCAR_OK) return st;
+  h.done = 0; h.iters = 0; h.notpd = 0;
+  HIPCHK(c, hipMemcpyAsync(c->ctrl, &h, sizeof h, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  TabPtrs t = ptrs(c);
+  t.trace_out = nullptr;
+  HIPCHK(c, launch_search_iteration(dims(c), t, g_out, g_in, 1, c->stream));
+  st = read_ctrl(c, &h);
+  if (st != OSSCAR_OK) return st;
+  if (h.notpd) return fail(c, OSSCAR_ENOTPD, "osscar_apply_swap: pivot block not definite");
+  return OSSCAR_OK;
+}
+
+osscar_status osscar_backsolve(osscar_ctx* c, void* What, int64_t ldw_hat, int32_t out_dtype, int32_t* support, double* obj_host) {
+  osscar_status st = check_ctx(c);
+  if (st != OSSCAR_OK) return st;
+  if (c->phase != osscar_ctx::READY) return fail(c, OSSCAR_ESTATE, "osscar_backsolve: call osscar_init_support first");
+  if (!What || ldw_hat < c->m || (out_dtype != OSSCAR_F32 && out_dtype != OSSCAR_BF16))
+    return fail(c, OSSCAR_EINVAL, "osscar_backsolve: bad output buffer");
+  hipStream_t s = c->stream;
+  HIPCHK(c, hipEventRecord(c->ev_a, s));
+  st = read_kept(c);
+  if (st != OSSCAR_OK) return st;
+  st = upload_rows(c);
+  if (st != OSSCAR_OK) return st;
+  Carve cv(c->scratch);
+  InvBufs b = carve_inv(c, cv);
+  st = inverse_and_weights(c, b);
+  if (st != OSSCAR_OK) return st;
+  HIPCHK(c, launch_fill_rows_zero(What, ldw_hat, c->d1, c->m, out_dtype == OSSCAR_BF16, s));
+  HIPCHK(c, launch_scatter_rows(b.B, c->m, c->rowsK, c->kr, c->m, What, ldw_hat, out_dtype == OSSCAR_BF16, s));
+  double obj = 0;
+  st = objective_from(c, b.GK, b.B, &obj);
+  if (st != OSSCAR_OK) return st;
+  HIPCHK(c, hipEventRecord(c->ev_b, s));
+  HIPCHK(c, hipStreamSynchronize(s));
+  c->timers[4] = elapsed(c);
+  if (obj_host) *obj_host = obj;
+  if (support) {
+    int n = 0;
+    for (int g = 0; g < c->p; g++) if (c->kept_host[g]) support[n++] = g;
+  }
+  return OSSCAR_OK;
+}
+
+osscar_status osscar_get_tensor(osscar_ctx* c, int which, void* dst, size_t dst_bytes) {
+  osscar_status st = check_ctx(c);
+  if (st != OSSCAR_OK) return st;
+  if (!dst) return fail(c, OSSCAR_EINVAL, "osscar_get_tensor: NULL destination");
+  hipStream_t s = c->stream;
+  const int64_t d1 = c->d1, m = c->m, kr = c->kr, cr = c->cr;
+  auto need = [&](size_t b) { return dst_bytes >= b; };
+  if (which == OSSCAR_T_H || which == OSSCAR_T_G) {
+    if (c->phase != osscar_ctx::FINAL && c->phase != osscar_ctx::READY) return fail(c, OSSCAR_ESTATE, "no quadratic form yet");
+    size_t b = (which == OSSCAR_T_H ? d1 * d1 : d1 * m) * 4;
+    if (!need(b)) return fail(c, OSSCAR_EINVAL, "osscar_get_tensor: destination too small");
+    HIPCHK(c, hipMemcpyAsync(dst, which == OSSCAR_T_H ? c->H : c->G, b, hipMemcpyDeviceToDevice, s));
+    HIPCHK(c, hipStreamSynchronize(s));
+    return OSSCAR_OK;
+  }
+  if (c->phase != osscar_ctx::READY) return fail(c, OSSCAR_ESTATE, "osscar_get_tensor: no search state yet");
+  st = read_kept(c);
+  if (st != OSSCAR_OK) return st;
+  if (which == OSSCAR_T_REM || which == OSSCAR_T_ADD) {
+    if (!need((size_t)c->p * 8)) return fail(c, OSSCAR_EINVAL, "osscar_get_tensor: destination too small");
+    std::vector<double> sc(c->p);
+    HIPCHK(c, hipMemcpyAsync(sc.data(), c->score, c->p * 8, hipMemcpyDeviceToHost, s));
+    HIPCHK(c, hipStreamSynchronize(s));
+    for (int g = 0; g < c->p; g++) {
+      if (which == OSSCAR_T_REM && !c->kept_host[g]) sc[g] = INFINITY;
+      if (which == OSSCAR_T_ADD && c->kept_host[g]) sc[g] = -INFINITY;
+    }
+    HIPCHK(c, hipMemcpy(dst, sc.data(), c->p * 8, hipMemcpyHostToDevice));
+    return OSSCAR_OK;
+  }
+  if (which == OSSCAR_T_KEPT_SLOTS || which == OSSCAR_T_CAND_SLOTS) {
+    std::vector<int32_t> ids;
+    for (int g = 0; g < c->p; g++) if ((c->kept_host[g] != 0) == (which == OSSCAR_T_KEPT_SLOTS)) ids.push_back(g);
+    if (!need(ids.size() * 4)) return fail(c, OSSCAR_EINVAL, "osscar_get_tensor: destination too small");
+    if (!ids.empty()) HIPCHK(c, hipMemcpy(dst, ids.data(), ids.size() * 4, hipMemcpyHostToDevice));
+    return OSSCAR_OK;
+  }
+  st = upload_rows(c);
+  if (st != OSSCAR_OK) return st;
+  float* out = reinterpret_cast<float*>(dst);
+  switch (which) {
+    case OSSCAR_T_P:
+      if (!need(kr * kr * 4)) return fail(c, OSSCAR_EINVAL, "osscar_get_tensor: destination too small");
+      hipLaunchKernelGGL(gather_sym_kernel, dim3(grid_for(kr * kr)), dim3(256), 0, s, c->N, d1, c->rowsK, (int)kr, c->rowsK, (int)kr, out, -1.f);
+      break;
+    case OSSCAR_T_V:
+      if (!need(kr * cr * 4)) return fail(c, OSSCAR_EINVAL, "osscar_get_tensor: destination too small");
+      if (cr > 0) hipLaunchKernelGGL(gather_sym_kernel, dim3(grid_for(kr * cr)), dim3(256), 0, s, c->N, d1, c->rowsK, (int)kr, c->rowsC, (int)cr, out, 1.f);
+      break;
+    case OSSCAR_T_B:
+      if (!need(kr * m * 4)) return fail(c, OSSCAR_EINVAL, "osscar_get_tensor: destination too small");
+      HIPCHK(c, launch_gather(c->Z, m, c->rowsK, (int)kr, nullptr, (int)m, out, m, s));
+      break;
+    case OSSCAR_T_R:
+      if (!need(cr * m * 4)) return fail(c, OSSCAR_EINVAL, "osscar_get_tensor: destination too small");
+      if (cr > 0) HIPCHK(c, launch_gather(c->Z, m, c->rowsC, (int)cr, nullptr, (int)m, out, m, s));
+      break;
+    default:
+      return fail(c, OSSCAR_EINVAL, "osscar_get_tensor: unknown tensor id %d", which);
+  }
+  HIPCHK(c, hipGetLastError());
+  HIPCHK(c, hipStreamSynchronize(s));
+  return OSSCAR_OK;
+}
+
+osscar_status osscar_get_scalars(osscar_ctx* c, double* lambda_host, double* c0_host) {
+  if (!c) return OSSCAR_EINVAL;
+  if (lambda_host) *lambda_host = c->lambda;
+  if (c0_host) *c0_host = c->c0;
+  return OSSCAR_OK;
+}
+
+osscar_status osscar_get_timers(osscar_ctx* c, double* out) {
+  if (!c || !out) return OSSCAR_EINVAL;
+  for (int i = 0; i < 8; i++) out[i] = c->timers[i];
+  return OSSCAR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,160 @@
+// General matrix product on the gfx950 matrix cores with float32 storage and float64 accumulation.
+//
+//   C = alpha * A * op(B) + beta * Cin  (+ diag_add on the main diagonal)
+//
+// Used wherever the solver needs a result that is accurate to float32 rounding of the exact value:
+// G = H W, the Newton-Schulz refinement of the inverse, B = P G_K with a float64 residual step, the
+// candidate-side products V = P H_{K,Kc}, S = H_cc - H_cK V, R = G_c - H_cK B, and the block sweeps of
+// the inverse.  Products of two float32 numbers are exact in float64, so the only rounding is the final
+// conversion of each output element.
+//
+// Tiling: one workgroup of 256 threads (4 wave64 in a 2 x 2 grid) owns a 128 x 128 tile of C; each wave
+// owns 64 x 64 as 4 x 4 v_mfma_f64_16x16x4_f64 tiles (64 float64 accumulators per lane).  A and B tiles
+// of depth 16 are staged through LDS in k-major order ([k][row]) so that the 16 lanes of an MFMA operand
+// column read consecutive LDS words.  Global loads for the next k-tile are issued before the MFMAs of
+// the current one (register double buffering).
+#include "internal.h"
+
+namespace osscar {
+
+typedef double d4 __attribute__((ext_vector_type(4)));
+
+constexpr int BM = 128, BN = 128, BK = 16, LDT = BM + 4;
+
+struct Tile8 { float v[8]; };
+
+// 8 consecutive floats of a row starting at column c0 (element stride 1), zero beyond `ncols`.
+__device__ __forceinline__ Tile8 load8(const float* __restrict__ row, int c0, int ncols, bool vec) {
+  Tile8 t;
+  if (row == nullptr) {
+#pragma unroll
+    for (int i = 0; i < 8; i++) t.v[i] = 0.f;
+    return t;
+  }
+  if (vec && c0 + 8 <= ncols) {
+    float4 a = *reinterpret_cast<const float4*>(row + c0);
+    float4 b = *reinterpret_cast<const float4*>(row + c0 + 4);
+    t.v[0] = a.x; t.v[1] = a.y; t.v[2] = a.z; t.v[3] = a.w;
+    t.v[4] = b.x; t.v[5] = b.y; t.v[6] = b.z; t.v[7] = b.w;
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; i++) t.v[i] = (c0 + i < ncols) ? row[c0 + i] : 0.f;
+  }
+  return t;
+}
+
+template <typename OutT>
+__global__ __launch_bounds__(256) void gemm_f64acc_kernel(GemmArgs g, int vecA, int vecB) {
+  __shared__ float As[2][BK][LDT];
+  __shared__ float Bs[2][BK][LDT];
+
+  int tile_m, tile_n;
+  if (g.lower_only) {
+    // linear index over the lower-triangle tiles: t = tm*(tm+1)/2 + tn, tn <= tm
+    int t = blockIdx.x;
+    int tm = (int)((sqrtf(8.f * (float)t + 1.f) - 1.f) * 0.5f);
+    while ((tm + 1) * (tm + 2) / 2 <= t) tm++;
+    while (tm * (tm + 1) / 2 > t) tm--;
+    tile_m = tm; tile_n = t - tm * (tm + 1) / 2;
+  } else {
+    int tiles_n = (g.N + BN - 1) / BN;
+    tile_m = blockIdx.x / tiles_n; tile_n = blockIdx.x % tiles_n;
+  }
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  // global -> register staging assignments
+  const int a_row = tid >> 1, a_k = (tid & 1) * 8;          // A tile: 128 rows x 16 k
+  const int bt_row = tid >> 1, bt_k = (tid & 1) * 8;        // B^T given (N x K): 128 n-rows x 16 k
+  const int b_k = tid >> 4, b_n = (tid & 15) * 8;           // B tile: 16 k x 128 n
+
+  const float* a_ptr = (m0 + a_row < g.M) ? g.A + (int64_t)(m0 + a_row) * g.lda : nullptr;
+  const float* bt_ptr = (g.trans_b && n0 + bt_row < g.N) ? g.B + (int64_t)(n0 + bt_row) * g.ldb : nullptr;
+
+  d4 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+#pragma unroll
+    for (int j = 0; j < 4; j++) acc[i][j] = d4{0, 0, 0, 0};
+
+  const int ktiles = (g.K + BK - 1) / BK;
+  Tile8 ra, rb;
+  auto gload = [&](int kt) {
+    int k0 = kt * BK;
+    ra = load8(a_ptr, k0 + a_k, g.K, vecA);
+    if (g.trans_b) {
+      rb = load8(bt_ptr, k0 + bt_k, g.K, vecB);
+    } else {
+      const float* bp = (k0 + b_k < g.K) ? g.B + (int64_t)(k0 + b_k) * g.ldb : nullptr;
+      rb = load8(bp, n0 + b_n, g.N, vecB);
+    }
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 8; i++) As[buf][a_k + i][a_row] = ra.v[i];
+    if (g.trans_b) {
+#pragma unroll
+      for (int i = 0; i < 8; i++) Bs[buf][bt_k + i][bt_row] = rb.v[i];
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; i++) Bs[buf][b_k][b_n + i] = rb.v[i];
+    }
+  };
+
+  if (ktiles > 0) { gload(0); sstore(0); }
+  __syncthreads();
+  for (int kt = 0; kt < ktiles; kt++) {
+    int buf = kt & 1;
+    if (kt + 1 < ktiles) gload(kt + 1);
+#pragma unroll
+    for (int kk = 0; kk < 4; kk++) {
+      int k = kk * 4 + (lane >> 4);
+      double a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; i++) a[i] = (double)As[buf][k][wm * 64 + i * 16 + (lane & 15)];
+#pragma unroll
+      for (int j = 0; j < 4; j++) b[j] = (double)Bs[buf][k][wn * 64 + j * 16 + (lane & 15)];
+#pragma unroll
+      for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < ktiles) sstore(buf ^ 1);
+    __syncthreads();
+  }
+
+  // epilogue: lane holds D[4*r + lane/16][lane%16] of each 16 x 16 tile
+  OutT* C = reinterpret_cast<OutT*>(g.C);
+  const OutT* Cin = reinterpret_cast<const OutT*>(g.Cin);
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        int row = m0 + wm * 64 + i * 16 + 4 * r + (lane >> 4);
+        int col = n0 + wn * 64 + j * 16 + (lane & 15);
+        if (row < g.M && col < g.N) {
+          double v = g.alpha * acc[i][j][r];
+          if (Cin != nullptr && g.beta != 0.0) v += g.beta * (double)Cin[(int64_t)row * g.ldcin + col];
+          if (row == col) v += g.diag_add;
+          C[(int64_t)row * g.ldc + col] = (OutT)v;
+        }
+      }
+}
+
+hipError_t launch_gemm_f64acc(const GemmArgs& a, hipStream_t s) {
+  if (a.M <= 0 || a.N <= 0) return hipSuccess;
+  int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
+  int blocks = a.lower_only ? tm * (tm + 1) / 2 : tm * tn;
+  int vecA = (a.lda % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.A) & 15) == 0);
+  int vecB = (a.ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.B) & 15) == 0);
+  if (a.c_is_f64)
+    hipLaunchKernelGGL(gemm_f64acc_kernel<double>, dim3(blocks), dim3(256), 0, s, a, vecA, vecB);
+  else
+    hipLaunchKernelGGL(gemm_f64acc_kernel<float>, dim3(blocks), dim3(256), 0, s, a, vecA, vecB);
+  return hipGetLastError();
+}
+
+}  // namespace osscar

@@ -1,0 +1,97 @@
+// Internal declarations shared by the translation units of libosscar (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace osscar {
+
+// ----------------------------------------------------------------------------------------------
+// gemm.hip : C = alpha * A * B + beta * Cin (+ diag_add on the diagonal), all row-major float32
+// storage, products accumulated in float64 on the matrix cores (v_mfma_f64_16x16x4_f64).
+// ----------------------------------------------------------------------------------------------
+struct GemmArgs {
+  int M, N, K;
+  const float* A; int64_t lda;   // M x K
+  const float* B; int64_t ldb;   // K x N
+  const float* Cin; int64_t ldcin;  // M x N or nullptr (treated as zero)
+  void* C; int64_t ldc;          // M x N, float or double
+  double alpha, beta, diag_add;
+  int c_is_f64;                  // output (and Cin) element type: 0 float, 1 double
+  int lower_only;                // 1: compute only tiles that touch the lower triangle (row >= col)
+  int trans_b;                   // 1: B is given as N x K row-major (C = alpha * A * B^T + ...)
+};
+hipError_t launch_gemm_f64acc(const GemmArgs& a, hipStream_t s);
+
+// ----------------------------------------------------------------------------------------------
+// gram.hip : H64 (+)= Xc^T Xc on the lower-triangle tiles
+// ----------------------------------------------------------------------------------------------
+hipError_t launch_gram_bf16(const void* Xc, int64_t n_c, int64_t ldx, int d1, double* H64, hipStream_t s);
+hipError_t launch_transpose_to_f32(const void* X, int is_bf16, int64_t rows, int64_t cols, int64_t ldx, float* Xt,
+                                   int64_t ldxt, hipStream_t s);
+// H = float(mirror(H64) + lam*I); also usable with lam = 0
+hipError_t launch_finalize_H(const double* H64, float* H, int d1, const double* lam_dev, hipStream_t s);
+// out[0] = sum_i H64[i][i]
+hipError_t launch_trace64(const double* H64, int d1, double* out, hipStream_t s);
+hipError_t launch_convert_to_f32(const void* src, int is_bf16, int64_t rows, int64_t cols, int64_t lds, float* dst,
+                                 hipStream_t s);
+// norms2[j] = sum over group j of W^2 (float64); c0 = sum W*G
+hipError_t launch_group_norms(const float* Wf, int p, int q, int m, double* norms2, hipStream_t s);
+hipError_t launch_dot64(const float* a, const float* b, int64_t n, double* out, double* partial, hipStream_t s);
+
+// ----------------------------------------------------------------------------------------------
+// tableau.hip : the swept tableau N (d1 x d1, lower triangle valid) and Z (d1 x m)
+//   N_KK = -P, N_{K,Kc} = V, N_{Kc,Kc} = S (Schur complement), Z_K = B, Z_Kc = R.
+// ----------------------------------------------------------------------------------------------
+struct SearchCtrl {          // lives in device memory
+  int32_t done;              // set when a swap is rejected (or nothing left to swap)
+  int32_t iters;             // iterations run
+  int32_t accepted;          // swaps applied
+  int32_t notpd;             // a pivot block was not definite
+  int32_t g_out, g_in;       // current selection (group ids), -1 if none
+  int32_t pad0, pad1;
+  double obj;                // tracked objective
+  double rel_tol;
+  double delta;              // exact change of the current pair
+  double gap_rem, gap_add;
+};
+
+struct TabDims { int d1, m, p, q; };
+
+hipError_t launch_gather(const float* src, int64_t lds, const int32_t* rows, int nrows, const int32_t* cols, int ncols,
+                         float* dst, int64_t ldd, hipStream_t s);
+// dst[rows[i]][cols[j]] = sign * src[i][j], only where rows[i] >= cols[j] if lower_only
+hipError_t launch_scatter(const float* src, int64_t lds, const int32_t* rows, int nrows, const int32_t* cols, int ncols,
+                          float* dst, int64_t ldd, float sign, int lower_only, hipStream_t s);
+hipError_t launch_mirror_lower(float* A, int n, int64_t lda, hipStream_t s);
+hipError_t launch_absmax(const float* A, int64_t n, double* out, hipStream_t s);
+
+// In-place inverse of the symmetric positive definite n x n matrix A (full storage on entry and exit)
+// by block sweeps of width nb; panel/work buffers are caller-provided: panel (n*nb), panelD (n*nb),
+// small (8*nb*nb doubles).  notpd_flag (device int) is set if a pivot block is not definite.
+hipError_t spd_inverse_inplace(float* A, int n, float* panel, float* panelD, double* small, int32_t* notpd_flag,
+                               hipStream_t s);
+
+struct TabPtrs {
+  float* N; float* Z;              // tableau
+  int32_t* kept;                   // p flags: 1 kept, 0 candidate
+  double* score;                   // p scores: removal cost (kept) / addition gain (candidate)
+  double* gram;                    // p * q*q : Z_g Z_g^T per group (float64)
+  double* dblk;                    // p * q*q : float64 copy of the diagonal blocks N_gg
+  float* C1; float* C2;            // d1 x q panels
+  float* C1D; float* C2D;          // d1 x q panels times D
+  float* rZ1; float* rZ2;          // q x m
+  double* small;                   // scratch for q x q algebra (>= 16*q*q doubles)
+  SearchCtrl* ctrl;
+  int32_t* trace_out; int32_t* trace_in; float* trace_gap; double* trace_obj;
+};
+
+hipError_t launch_refresh_scores(const TabDims& d, const TabPtrs& t, hipStream_t s);   // gram, dblk, score from N, Z
+// ev (optional): three events recorded before the bulk update of N, after it, and after the update of Z.
+hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int forced_out, int forced_in, int always_accept,
+                                   hipStream_t s, hipEvent_t* ev = nullptr);
+hipError_t launch_scatter_rows(const float* src, int64_t lds, const int32_t* rows, int nrows, int ncols, void* dst,
+                               int64_t ldd, int dst_is_bf16, hipStream_t s);
+hipError_t launch_fill_rows_zero(void* dst, int64_t ldd, int nrows_total, int ncols, int dst_is_bf16, hipStream_t s);
+
+}  // namespace osscar

@@ -1,0 +1,809 @@
+// The swept tableau and the kernels of the local search (Section 4.2; Proposition 4.1, Cases 1-3).
+//
+// State.  For the kept set K the library holds the symmetric d1 x d1 matrix
+//        N = [ -P   V ]      P = (H_KK)^-1,  V = P H_{K,Kc},  S = H_cc - H_cK P H_Kc
+//            [ V^T  S ]
+// in the ORIGINAL row order (row i belongs to group i / q, kept or not), lower triangle only, and
+//        Z = [ B ; R ]       B = P G_K (optimal kept weights),  R = G_Kc - H_cK B
+// as d1 x m.  N is H with the "sweep operator" applied to the pivots in K, and Z is G carried along.
+// In this form Proposition 4.1's Case 2 (a group enters) is a forward sweep on that group's q x q
+// pivot block and Case 1 (a group leaves) is the reverse sweep; both are the same rank-q update
+//        N_il -= N_it D N_tl,   Z_i -= N_it D Z_t        (D = N_tt^-1, i, l outside the pivot)
+// and differ only in the sign given to the pivot rows (+D N_tl entering, -D N_tl leaving; N_tt' = -D).
+// The change of the objective is -Tr(Z_t^T D Z_t) in both cases, and the impact score of eq. (impact)
+// of ANY group h is Tr(Z_h^T |N_hh|^-1 Z_h): removal cost if h is kept, addition gain otherwise.
+// A swap (Case 3) is the reverse sweep on g followed by the forward sweep on j; the two are fused into
+// one rank-2q pass over N and Z, with the second pivot's panel corrected for the first sweep beforehand.
+#include "internal.h"
+
+namespace osscar {
+
+// ------------------------------------------------------------------------------------------------
+// small dense helpers (float64, one workgroup, matrices in global or shared memory)
+// ------------------------------------------------------------------------------------------------
+// In-place inverse of the n x n matrix A (leading dimension n) by Gauss-Jordan without pivoting; valid for
+// definite matrices of either sign.  want_sign = +1 / -1: every pivot must have that sign, else *bad = 1.
+__device__ void small_inverse(double* A, int n, int want_sign, int32_t* bad, double* colbuf) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  for (int k = 0; k < n; k++) {
+    __syncthreads();
+    double piv = A[k * n + k];
+    if (!(piv * want_sign > 0.0)) { if (tid == 0) *bad = 1; piv = want_sign; }
+    double d = 1.0 / piv;
+    for (int i = tid; i < n; i += nt) colbuf[i] = A[i * n + k];
+    __syncthreads();
+    for (int j = tid; j < n; j += nt) if (j != k) A[k * n + j] *= d;
+    __syncthreads();
+    for (int idx = tid; idx < n * n; idx += nt) {
+      int i = idx / n, j = idx % n;
+      if (i != k && j != k) A[idx] -= colbuf[i] * A[k * n + j];
+    }
+    __syncthreads();
+    for (int i = tid; i < n; i += nt) A[i * n + k] = (i == k) ? d : -colbuf[i] * d;
+  }
+  __syncthreads();
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  return v;
+}
+
+__device__ __forceinline__ float nsym(const float* __restrict__ N, int64_t ld, int i, int t) {
+  return (i >= t) ? N[(int64_t)i * ld + t] : N[(int64_t)t * ld + i];
+}
+
+// ------------------------------------------------------------------------------------------------
+// gather / scatter / mirror / absmax
+// ------------------------------------------------------------------------------------------------
+__global__ void gather_kernel(const float* __restrict__ src, int64_t lds_, const int32_t* __restrict__ rows, int nrows,
+                              const int32_t* __restrict__ cols, int ncols, float* __restrict__ dst, int64_t ldd) {
+  int64_t n = (int64_t)nrows * ncols;
+  for (int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; idx < n; idx += (int64_t)gridDim.x * blockDim.x) {
+    int i = (int)(idx / ncols), j = (int)(idx % ncols);
+    int64_t r = rows ? rows[i] : i, c = cols ? cols[j] : j;
+    dst[(int64_t)i * ldd + j] = src[r * lds_ + c];
+  }
+}
+hipError_t launch_gather(const float* src, int64_t lds_, const int32_t* rows, int nrows, const int32_t* cols, int ncols,
+                         float* dst, int64_t ldd, hipStream_t s) {
+  int64_t n = (int64_t)nrows * ncols;
+  if (n <= 0) return hipSuccess;
+  int blocks = (int)((n + 1023) / 1024); if (blocks > 131072) blocks = 131072;
+  hipLaunchKernelGGL(gather_kernel, dim3(blocks), dim3(256), 0, s, src, lds_, rows, nrows, cols, ncols, dst, ldd);
+  return hipGetLastError();
+}
+
+// dst[max(r,c)][min(r,c)] = sign * src[i][j], r = rows[i], c = cols[j]; if tri: only i >= j
+__global__ void scatter_kernel(const float* __restrict__ src, int64_t lds_, const int32_t* __restrict__ rows, int nrows,
+                               const int32_t* __restrict__ cols, int ncols, float* __restrict__ dst, int64_t ldd,
+                               float sign, int tri) {
+  int64_t n = (int64_t)nrows * ncols;
+  for (int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; idx < n; idx += (int64_t)gridDim.x * blockDim.x) {
+    int i = (int)(idx / ncols), j = (int)(idx % ncols);
+    if (tri && i < j) continue;
+    int64_t r = rows[i], c = cols[j];
+    int64_t hi = r > c ? r : c, lo = r > c ? c : r;
+    dst[hi * ldd + lo] = sign * src[(int64_t)i * lds_ + j];
+  }
+}
+hipError_t launch_scatter(const float* src, int64_t lds_, const int32_t* rows, int nrows, const int32_t* cols, int ncols,
+                          float* dst, int64_t ldd, float sign, int tri, hipStream_t s) {
+  int64_t n = (int64_t)nrows * ncols;
+  if (n <= 0) return hipSuccess;
+  int blocks = (int)((n + 1023) / 1024); if (blocks > 131072) blocks = 131072;
+  hipLaunchKernelGGL(scatter_kernel, dim3(blocks), dim3(256), 0, s, src, lds_, rows, nrows, cols, ncols, dst, ldd, sign, tri);
+  return hipGetLastError();
+}
+
+// rows of a dense matrix into rows[] of dst (float or bf16 destination)
+__device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__global__ void scatter_rows_kernel(const float* __restrict__ src, int64_t lds_, const int32_t* __restrict__ rows,
+                                    int nrows, int ncols, void* __restrict__ dst, int64_t ldd, int dst_is_bf16) {
+  int64_t n = (int64_t)nrows * ncols;
+  for (int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; idx < n; idx += (int64_t)gridDim.x * blockDim.x) {
+    int i = (int)(idx / ncols), j = (int)(idx % ncols);
+    float v = src[(int64_t)i * lds_ + j];
+    int64_t o = (int64_t)rows[i] * ldd + j;
+    if (dst_is_bf16) reinterpret_cast<uint16_t*>(dst)[o] = float_to_bf16_rne(v);
+    else reinterpret_cast<float*>(dst)[o] = v;
+  }
+}
+hipError_t launch_scatter_rows(const float* src, int64_t lds_, const int32_t* rows, int nrows, int ncols, void* dst,
+                               int64_t ldd, int dst_is_bf16, hipStream_t s) {
+  int64_t n = (int64_t)nrows * ncols;
+  if (n <= 0) return hipSuccess;
+  int blocks = (int)((n + 1023) / 1024); if (blocks > 131072) blocks = 131072;
+  hipLaunchKernelGGL(scatter_rows_kernel, dim3(blocks), dim3(256), 0, s, src, lds_, rows, nrows, ncols, dst, ldd, dst_is_bf16);
+  return hipGetLastError();
+}
+__global__ void fill_zero_kernel(void* __restrict__ dst, int64_t ldd, int nrows, int ncols, int dst_is_bf16) {
+  int64_t n = (int64_t)nrows * ncols;
+  for (int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; idx < n; idx += (int64_t)gridDim.x * blockDim.x) {
+    int i = (int)(idx / ncols), j = (int)(idx % ncols);
+    int64_t o = (int64_t)i * ldd + j;
+    if (dst_is_bf16) reinterpret_cast<uint16_t*>(dst)[o] = 0;
+    else reinterpret_cast<float*>(dst)[o] = 0.f;
+  }
+}
+hipError_t launch_fill_rows_zero(void* dst, int64_t ldd, int nrows, int ncols, int dst_is_bf16, hipStream_t s) {
+  int64_t n = (int64_t)nrows * ncols;
+  if (n <= 0) return hipSuccess;
+  int blocks = (int)((n + 1023) / 1024); if (blocks > 131072) blocks = 131072;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, dst, ldd, nrows, ncols, dst_is_bf16);
+  return hipGetLastError();
+}
+
+// A[i][j] (j > i) = A[j][i]
+__global__ void mirror_lower_kernel(float* __restrict__ A, int n, int64_t lda) {
+  int64_t tot = (int64_t)n * n;
+  for (int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; idx < tot; idx += (int64_t)gridDim.x * blockDim.x) {
+    int i = (int)(idx / n), j = (int)(idx % n);
+    if (j > i) A[(int64_t)i * lda + j] = A[(int64_t)j * lda + i];
+  }
+}
+hipError_t launch_mirror_lower(float* A, int n, int64_t lda, hipStream_t s) {
+  int64_t tot = (int64_t)n * n;
+  if (tot <= 0) return hipSuccess;
+  int blocks = (int)((tot + 1023) / 1024); if (blocks > 131072) blocks = 131072;
+  hipLaunchKernelGGL(mirror_lower_kernel, dim3(blocks), dim3(256), 0, s, A, n, lda);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(1024) void absmax_kernel(const float* __restrict__ A, int64_t n, double* out) {
+  __shared__ double sh[16];
+  double v = 0;
+  for (int64_t i = threadIdx.x; i < n; i += 1024) { double x = fabs((double)A[i]); v = x > v ? x : v; }
+  for (int o = 32; o > 0; o >>= 1) { double w = __shfl_down(v, o, 64); v = w > v ? w : v; }
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  if (threadIdx.x == 0) { double t = 0; for (int i = 0; i < 16; i++) t = sh[i] > t ? sh[i] : t; out[0] = t; }
+}
+// out[b] for 256 blocks, then the caller reduces on the host (256 doubles)
+__global__ __launch_bounds__(256) void absmax_partial_kernel(const float* __restrict__ A, int64_t n, double* out) {
+  __shared__ double sh[4];
+  double v = 0;
+  for (int64_t i = blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    double x = fabs((double)A[i]); v = x > v ? x : v;
+  }
+  for (int o = 32; o > 0; o >>= 1) { double w = __shfl_down(v, o, 64); v = w > v ? w : v; }
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  if (threadIdx.x == 0) { double t = 0; for (int i = 0; i < 4; i++) t = sh[i] > t ? sh[i] : t; out[blockIdx.x] = t; }
+}
+hipError_t launch_absmax(const float* A, int64_t n, double* out, hipStream_t s) {  // out: 256 doubles
+  hipLaunchKernelGGL(absmax_partial_kernel, dim3(256), dim3(256), 0, s, A, n, out);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// pivot panels
+// ------------------------------------------------------------------------------------------------
+// C[i][c] = Nsym(i, t0 + c), c < w, for all rows i < n
+__global__ __launch_bounds__(256) void extract_panel_kernel(const float* __restrict__ N, int64_t ld, int n, int t0,
+                                                             int w, float* __restrict__ C) {
+  int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  for (int c = 0; c < w; c++) C[(int64_t)i * w + c] = nsym(N, ld, i, t0 + c);
+}
+
+// out[i][c] = sum_k C[i][k] * D[k][c]  (D: w x w float64), rows in [t0, t0+w) are written as zero if zero_pivot.
+// Optionally also writes Cb = C with the pivot rows zeroed.
+__global__ __launch_bounds__(256) void panel_times_small_kernel(const float* __restrict__ C, const double* __restrict__ D,
+                                                                 int n, int w, int t0, int zero_pivot,
+                                                                 float* __restrict__ out, float* __restrict__ Cb) {
+  extern __shared__ double Dsh[];
+  for (int i = threadIdx.x; i < w * w; i += 256) Dsh[i] = D[i];
+  __syncthreads();
+  int64_t tot = (int64_t)n * w;
+  for (int64_t idx = blockIdx.x * 256 + threadIdx.x; idx < tot; idx += (int64_t)gridDim.x * 256) {
+    int i = (int)(idx / w), c = (int)(idx % w);
+    bool piv = zero_pivot && i >= t0 && i < t0 + w;
+    double v = 0;
+    if (!piv)
+      for (int k = 0; k < w; k++) v += (double)C[(int64_t)i * w + k] * Dsh[k * w + c];
+    out[idx] = (float)v;
+    if (Cb) Cb[idx] = piv ? 0.f : C[idx];
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// blocked in-place inverse of an SPD matrix by sweeping nb columns at a time (lower triangle storage)
+// ------------------------------------------------------------------------------------------------
+constexpr int INV_NB = 64;
+
+__global__ __launch_bounds__(256) void inv_block_kernel(const float* __restrict__ C, int w, int t0, double* __restrict__ D,
+                                                         int32_t* notpd) {
+  __shared__ double colbuf[INV_NB];
+  for (int idx = threadIdx.x; idx < w * w; idx += 256) {
+    int r = idx / w, c = idx % w;
+    D[idx] = (double)C[(int64_t)(t0 + r) * w + c];
+  }
+  __syncthreads();
+  small_inverse(D, w, +1, notpd, colbuf);
+}
+
+// pivot rows after a forward sweep: N(t0+r, l) = CD[l][r] for l outside the pivot, N(tt) = -D
+__global__ __launch_bounds__(256) void inv_fix_kernel(float* __restrict__ N, int64_t ld, int n, int t0, int w,
+                                                       const float* __restrict__ CD, const double* __restrict__ D) {
+  int l = blockIdx.x * 256 + threadIdx.x;
+  if (l >= n) return;
+  if (l >= t0 && l < t0 + w) {
+    int r = l - t0;
+    for (int c = 0; c <= r; c++) N[(int64_t)l * ld + t0 + c] = (float)(-D[r * w + c]);
+    return;
+  }
+  for (int r = 0; r < w; r++) {
+    float v = CD[(int64_t)l * w + r];
+    if (l < t0) N[(int64_t)(t0 + r) * ld + l] = v;
+    else N[(int64_t)l * ld + t0 + r] = v;
+  }
+}
+
+// A[i][j] = -A[max][min] for all i, j (turns the swept lower triangle -A^-1 into the full inverse)
+__global__ void negate_mirror_kernel(float* __restrict__ A, int n) {
+  int64_t tot = (int64_t)n * n;
+  for (int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; idx < tot; idx += (int64_t)gridDim.x * blockDim.x) {
+    int i = (int)(idx / n), j = (int)(idx % n);
+    if (j <= i) continue;
+    float v = -A[(int64_t)j * n + i];
+    A[(int64_t)i * n + j] = v;     // upper gets the final value
+  }
+}
+__global__ void negate_lower_kernel(float* __restrict__ A, int n) {
+  int64_t tot = (int64_t)n * n;
+  for (int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; idx < tot; idx += (int64_t)gridDim.x * blockDim.x) {
+    int i = (int)(idx / n), j = (int)(idx % n);
+    if (j <= i) A[idx] = -A[idx];
+  }
+}
+
+hipError_t spd_inverse_inplace(float* A, int n, float* panel, float* panelD, double* small, int32_t* notpd_flag,
+                               hipStream_t s) {
+  float* panelB = panelD + (int64_t)n * INV_NB;   // caller provides 2*n*nb floats behind panelD
+  for (int t0 = 0; t0 < n; t0 += INV_NB) {
+    int w = (n - t0 < INV_NB) ? n - t0 : INV_NB;
+    int rb = (n + 255) / 256;
+    hipLaunchKernelGGL(extract_panel_kernel, dim3(rb), dim3(256), 0, s, A, (int64_t)n, n, t0, w, panel);
+    hipLaunchKernelGGL(inv_block_kernel, dim3(1), dim3(256), 0, s, panel, w, t0, small, notpd_flag);
+    int pb = (int)(((int64_t)n * w + 255) / 256); if (pb > 4096) pb = 4096;
+    // true C*D for the pivot-row fix, and zeroed copies for the bulk update
+    hipLaunchKernelGGL(panel_times_small_kernel, dim3(pb), dim3(256), (size_t)w * w * 8, s, panel, small, n, w, t0, 1,
+                       panelD, panelB);
+    GemmArgs g{};
+    g.M = n; g.N = n; g.K = w; g.A = panelD; g.lda = w; g.B = panelB; g.ldb = w; g.trans_b = 1;
+    g.Cin = A; g.ldcin = n; g.C = A; g.ldc = n; g.alpha = -1.0; g.beta = 1.0; g.diag_add = 0.0; g.c_is_f64 = 0;
+    g.lower_only = 1;
+    hipError_t e = launch_gemm_f64acc(g, s);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(inv_fix_kernel, dim3(rb), dim3(256), 0, s, A, (int64_t)n, n, t0, w, panelD, small);
+  }
+  int64_t tot = (int64_t)n * n;
+  int blocks = (int)((tot + 1023) / 1024); if (blocks > 131072) blocks = 131072;
+  hipLaunchKernelGGL(negate_mirror_kernel, dim3(blocks), dim3(256), 0, s, A, n);
+  hipLaunchKernelGGL(negate_lower_kernel, dim3(blocks), dim3(256), 0, s, A, n);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// scores: gram[h] = Z_h Z_h^T, dblk[h] = N_hh (float64), score[h] = Tr(gram_h |N_hh|^-1)
+// ------------------------------------------------------------------------------------------------
+// one workgroup per group; wave w takes the pairs (r, c), c <= r, in a fixed order, lanes over columns
+__device__ void group_gram(const float* __restrict__ Zg, int q, int m, double* __restrict__ gram_h) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const int npairs = q * (q + 1) / 2;
+  for (int pr = wave; pr < npairs; pr += nw) {
+    int r = (int)((sqrtf(8.f * (float)pr + 1.f) - 1.f) * 0.5f);
+    while ((r + 1) * (r + 2) / 2 <= pr) r++;
+    while (r * (r + 1) / 2 > pr) r--;
+    int c = pr - r * (r + 1) / 2;
+    const float* zr = Zg + (int64_t)r * m;
+    const float* zc = Zg + (int64_t)c * m;
+    double v = 0;
+    for (int col = lane; col < m; col += 64) v += (double)zr[col] * (double)zc[col];
+    v = wave_sum(v);
+    if (lane == 0) { gram_h[r * q + c] = v; gram_h[c * q + r] = v; }
+  }
+}
+
+__global__ __launch_bounds__(256) void gram_dblk_kernel(TabDims d, const float* __restrict__ N, const float* __restrict__ Z,
+                                                         double* __restrict__ gram, double* __restrict__ dblk) {
+  int h = blockIdx.x, q = d.q;
+  group_gram(Z + (int64_t)h * q * d.m, q, d.m, gram + (int64_t)h * q * q);
+  for (int idx = threadIdx.x; idx < q * q; idx += 256) {
+    int r = idx / q, c = idx % q;
+    dblk[(int64_t)h * q * q + idx] = (double)nsym(N, d.d1, h * q + r, h * q + c);
+  }
+}
+
+// score[h] = Tr(gram_h * (sigma * dblk_h)^-1), sigma = -1 for kept groups (N_hh = -P_hh), +1 otherwise.
+// One workgroup of 64 threads per group; Cholesky in shared memory, then one column solve per thread.
+__global__ __launch_bounds__(64) void score_kernel(TabDims d, const int32_t* __restrict__ kept,
+                                                    const double* __restrict__ gram, const double* __restrict__ dblk,
+                                                    double* __restrict__ score, SearchCtrl* ctrl) {
+  extern __shared__ double sh[];   // A: q*q, X: q*q
+  const int h = blockIdx.x, q = d.q, tid = threadIdx.x;
+  const double sigma = kept[h] ? -1.0 : 1.0;
+  if (q == 1) {
+    if (tid == 0) {
+      double a = sigma * dblk[h];
+      if (!(a > 0.0)) { ctrl->notpd = 1; a = 1.0; }
+      score[h] = gram[h] / a;
+    }
+    return;
+  }
+  double* A = sh;
+  double* X = sh + q * q;
+  for (int idx = tid; idx < q * q; idx += 64) { A[idx] = sigma * dblk[(int64_t)h * q * q + idx]; X[idx] = gram[(int64_t)h * q * q + idx]; }
+  __syncthreads();
+  // Cholesky, lower, in place (right-looking, column at a time)
+  for (int k = 0; k < q; k++) {
+    double piv = A[k * q + k];
+    if (!(piv > 0.0)) { if (tid == 0) ctrl->notpd = 1; piv = 1.0; }
+    double lkk = sqrt(piv);
+    __syncthreads();
+    for (int i = k + tid; i < q; i += 64) A[i * q + k] = (i == k) ? lkk : A[i * q + k] / lkk;
+    __syncthreads();
+    for (int idx = tid; idx < (q - k - 1) * (q - k - 1); idx += 64) {
+      int i = k + 1 + idx / (q - k - 1), j = k + 1 + idx % (q - k - 1);
+      if (j <= i) A[i * q + j] -= A[i * q + k] * A[j * q + k];
+    }
+    __syncthreads();
+  }
+  // thread c solves A x = gram[:, c]; contributes x[c]
+  double contrib = 0;
+  for (int c = tid; c < q; c += 64) {
+    for (int i = 0; i < q; i++) {              // forward: L y = b
+      double v = X[i * q + c];
+      for (int k = 0; k < i; k++) v -= A[i * q + k] * X[k * q + c];
+      X[i * q + c] = v / A[i * q + i];
+    }
+    for (int i = q - 1; i >= 0; i--) {         // backward: L^T x = y
+      double v = X[i * q + c];
+      for (int k = i + 1; k < q; k++) v -= A[k * q + i] * X[k * q + c];
+      X[i * q + c] = v / A[i * q + i];
+    }
+    contrib += X[c * q + c];
+  }
+  contrib = wave_sum(contrib);
+  if (tid == 0) score[h] = contrib;
+}
+
+hipError_t launch_refresh_scores(const TabDims& d, const TabPtrs& t, hipStream_t s) {
+  hipLaunchKernelGGL(gram_dblk_kernel, dim3(d.p), dim3(256), 0, s, d, t.N, t.Z, t.gram, t.dblk);
+  hipLaunchKernelGGL(score_kernel, dim3(d.p), dim3(64), (size_t)2 * d.q * d.q * 8, s, d, t.kept, t.gram, t.dblk, t.score,
+                     t.ctrl);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// one search iteration
+// ------------------------------------------------------------------------------------------------
+// argmin of the removal costs over kept groups, argmax of the addition gains over the others (lowest
+// index on ties), and the relative gap to the second best of each.
+__global__ __launch_bounds__(1024) void select_kernel(TabDims d, const int32_t* __restrict__ kept,
+                                                       const double* __restrict__ score, SearchCtrl* ctrl, int forced_out,
+                                                       int forced_in) {
+  __shared__ double s_min1[1024], s_min2[1024], s_max1[1024], s_max2[1024];
+  __shared__ int s_imin[1024], s_imax[1024];
+  if (ctrl->done) return;
+  const int tid = threadIdx.x;
+  double mn1 = INFINITY, mn2 = INFINITY, mx1 = -INFINITY, mx2 = -INFINITY;
+  int imn = -1, imx = -1;
+  for (int h = tid; h < d.p; h += 1024) {     // ascending h per thread: strict comparisons keep the lowest index
+    double v = score[h];
+    if (kept[h]) {
+      if (v < mn1) { mn2 = mn1; mn1 = v; imn = h; } else if (v < mn2) mn2 = v;
+    } else {
+      if (v > mx1) { mx2 = mx1; mx1 = v; imx = h; } else if (v > mx2) mx2 = v;
+    }
+  }
+  s_min1[tid] = mn1; s_min2[tid] = mn2; s_imin[tid] = imn;
+  s_max1[tid] = mx1; s_max2[tid] = mx2; s_imax[tid] = imx;
+  __syncthreads();
+  for (int o = 512; o > 0; o >>= 1) {
+    if (tid < o) {
+      {  // min side
+        double a1 = s_min1[tid], a2 = s_min2[tid], b1 = s_min1[tid + o], b2 = s_min2[tid + o];
+        int ia = s_imin[tid], ib = s_imin[tid + o];
+        bool takeb = (ib >= 0) && (ia < 0 || b1 < a1 || (b1 == a1 && ib < ia));
+        double n1 = takeb ? b1 : a1; int in_ = takeb ? ib : ia;
+        double other1 = takeb ? a1 : b1;
+        double n2 = fmin(fmin(a2, b2), other1);
+        s_min1[tid] = n1; s_min2[tid] = n2; s_imin[tid] = in_;
+      }
+      {  // max side
+        double a1 = s_max1[tid], a2 = s_max2[tid], b1 = s_max1[tid + o], b2 = s_max2[tid + o];
+        int ia = s_imax[tid], ib = s_imax[tid + o];
+        bool takeb = (ib >= 0) && (ia < 0 || b1 > a1 || (b1 == a1 && ib < ia));
+        double n1 = takeb ? b1 : a1; int in_ = takeb ? ib : ia;
+        double other1 = takeb ? a1 : b1;
+        double n2 = fmax(fmax(a2, b2), other1);
+        s_max1[tid] = n1; s_max2[tid] = n2; s_imax[tid] = in_;
+      }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    int g = s_imin[0], j = s_imax[0];
+    if (forced_out >= 0) { g = forced_out; j = forced_in; }
+    if (g < 0 || j < 0 || (forced_out >= 0 && (!kept[g] || kept[j]))) { ctrl->done = 1; ctrl->g_out = -1; ctrl->g_in = -1; return; }
+    ctrl->g_out = g; ctrl->g_in = j;
+    double m1 = s_min1[0], m2 = s_min2[0], x1 = s_max1[0], x2 = s_max2[0];
+    ctrl->gap_rem = isfinite(m2) ? fabs(m2 - m1) / fmax(fabs(m1), 1e-300) : INFINITY;
+    ctrl->gap_add = isfinite(x2) ? fabs(x1 - x2) / fmax(fabs(x1), 1e-300) : INFINITY;
+  }
+}
+
+// panels of both pivots and copies of their Z rows
+__global__ __launch_bounds__(256) void extract_pair_kernel(TabDims d, const float* __restrict__ N, const float* __restrict__ Z,
+                                                            const SearchCtrl* __restrict__ ctrl, float* __restrict__ C1,
+                                                            float* __restrict__ C2, float* __restrict__ Zg,
+                                                            float* __restrict__ Zj) {
+  if (ctrl->done) return;
+  const int q = d.q, g0 = ctrl->g_out * q, j0 = ctrl->g_in * q;
+  int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < d.d1) {
+    for (int c = 0; c < q; c++) {
+      C1[(int64_t)i * q + c] = nsym(N, d.d1, i, g0 + c);
+      C2[(int64_t)i * q + c] = nsym(N, d.d1, i, j0 + c);
+    }
+  }
+  int64_t tot = (int64_t)q * d.m;
+  for (int64_t idx = blockIdx.x * 256 + threadIdx.x; idx < tot; idx += (int64_t)gridDim.x * 256) {
+    Zg[idx] = Z[(int64_t)g0 * d.m + idx];
+    Zj[idx] = Z[(int64_t)j0 * d.m + idx];
+  }
+}
+
+// q x q algebra of the pair, the exact change of the objective, the acceptance test and the trace.
+// small layout (doubles, each q*q): [0] Dg, [1] Njg, [2] M1 = Dg Ngj, [3] Dj' , [4] W2Dj = -M1 Dj', [5] scratch
+__global__ __launch_bounds__(256) void pair_small_kernel(TabDims d, const float* __restrict__ C1, const float* __restrict__ C2,
+                                                          float* __restrict__ Zg, float* __restrict__ Zj, double* __restrict__ small,
+                                                          SearchCtrl* ctrl, int always_accept, int32_t* trace_out,
+                                                          int32_t* trace_in, float* trace_gap, double* trace_obj) {
+  __shared__ double colbuf[64];
+  __shared__ double red[4];
+  __shared__ int32_t bad;
+  if (ctrl->done) return;
+  const int q = d.q, qq = q * q, m = d.m, tid = threadIdx.x;
+  const int g0 = ctrl->g_out * q, j0 = ctrl->g_in * q;
+  double* Dg = small; double* Njg = small + qq; double* M1 = small + 2 * qq; double* Dj = small + 3 * qq;
+  double* W2Dj = small + 4 * qq;
+  if (tid == 0) bad = 0;
+  for (int idx = tid; idx < qq; idx += 256) {
+    int r = idx / q, c = idx % q;
+    Dg[idx] = (double)C1[(int64_t)(g0 + r) * q + c];       // N_gg
+    Njg[idx] = (double)C1[(int64_t)(j0 + r) * q + c];      // N(j_r, g_c)
+    Dj[idx] = (double)C2[(int64_t)(j0 + r) * q + c];       // N_jj
+  }
+  __syncthreads();
+  small_inverse(Dg, q, -1, &bad, colbuf);                  // kept pivot: N_gg = -P_gg is negative definite
+  for (int idx = tid; idx < qq; idx += 256) {              // M1 = Dg * N_gj, N_gj = Njg^T
+    int r = idx / q, c = idx % q;
+    double v = 0;
+    for (int k = 0; k < q; k++) v += Dg[r * q + k] * Njg[c * q + k];
+    M1[idx] = v;
+  }
+  __syncthreads();
+  for (int idx = tid; idx < qq; idx += 256) {              // N'_jj = N_jj - N_jg M1
+    int r = idx / q, c = idx % q;
+    double v = 0;
+    for (int k = 0; k < q; k++) v += Njg[r * q + k] * M1[k * q + c];
+    Dj[idx] -= v;
+  }
+  __syncthreads();
+  small_inverse(Dj, q, +1, &bad, colbuf);                  // entering pivot: Schur complement, positive definite
+  for (int idx = tid; idx < qq; idx += 256) {              // W2Dj = W2 * Dj', W2 = N'_gj = -M1
+    int r = idx / q, c = idx % q;
+    double v = 0;
+    for (int k = 0; k < q; k++) v -= M1[r * q + k] * Dj[k * q + c];
+    W2Dj[idx] = v;
+  }
+  __syncthreads();
+  // rZ1 = Dg Zg ; Z'j = Zj - Njg rZ1 ; rZ2 = Dj' Z'j ; delta = -<Zg, rZ1> - <Z'j, rZ2>   (column by column)
+  double part = 0;
+  for (int col = tid; col < m; col += 256) {
+    double zg[64], t1[64];
+    for (int r = 0; r < q; r++) zg[r] = (double)Zg[(int64_t)r * m + col];
+    for (int r = 0; r < q; r++) { double v = 0; for (int k = 0; k < q; k++) v += Dg[r * q + k] * zg[k]; t1[r] = v; part -= zg[r] * v; }
+    for (int r = 0; r < q; r++) {                          // zg := Z'j
+      double v = (double)Zj[(int64_t)r * m + col];
+      for (int k = 0; k < q; k++) v -= Njg[r * q + k] * t1[k];
+      zg[r] = v;
+    }
+    for (int r = 0; r < q; r++) Zg[(int64_t)r * m + col] = (float)t1[r];     // rZ1 in place
+    for (int r = 0; r < q; r++) {
+      double v = 0;
+      for (int k = 0; k < q; k++) v += Dj[r * q + k] * zg[k];
+      part -= zg[r] * v;
+      Zj[(int64_t)r * m + col] = (float)v;                                    // rZ2 in place
+    }
+  }
+  part = wave_sum(part);
+  if ((tid & 63) == 0) red[tid >> 6] = part;
+  __syncthreads();
+  if (tid == 0) {
+    double delta = red[0] + red[1] + red[2] + red[3];
+    ctrl->delta = delta;
+    if (bad) ctrl->notpd = 1;
+    int it = ctrl->iters;
+    bool ok = !bad && (always_accept || delta < -ctrl->rel_tol * ctrl->obj);
+    ctrl->iters = it + 1;
+    if (ok) { ctrl->obj += delta; ctrl->accepted += 1; } else { ctrl->done = 1; }
+    if (trace_out) {
+      trace_out[it] = ctrl->g_out; trace_in[it] = ctrl->g_in;
+      trace_gap[2 * it] = (float)ctrl->gap_rem; trace_gap[2 * it + 1] = (float)ctrl->gap_add;
+      trace_obj[it] = ctrl->obj;
+    }
+  }
+}
+
+// bulk panels: P1 = C1, P2 = C2 - C1 M1, P1D = P1 Dg, P2D = P2 Dj', with the rows of both pivots zeroed;
+// and the new pivot rows of N and Z, the diagonal blocks (float64) and the membership flags.
+// T1 (d1 x q) = true C1 Dg, T2 (d1 x q) = true (C2 - C1 M1) Dj' for rows outside the pivots.
+__global__ __launch_bounds__(256) void pair_panels_kernel(TabDims d, const float* __restrict__ C1, const float* __restrict__ C2,
+                                                           const double* __restrict__ small, const SearchCtrl* __restrict__ ctrl,
+                                                           float* __restrict__ P1, float* __restrict__ P2,
+                                                           float* __restrict__ P1D, float* __restrict__ P2D) {
+  if (ctrl->done) return;
+  extern __shared__ double sm[];   // Dg, M1, Dj : 3*q*q
+  const int q = d.q, qq = q * q;
+  const int g0 = ctrl->g_out * q, j0 = ctrl->g_in * q;
+  double* Dg = sm; double* M1 = sm + qq; double* Dj = sm + 2 * qq;
+  for (int idx = threadIdx.x; idx < qq; idx += 256) { Dg[idx] = small[idx]; M1[idx] = small[2 * qq + idx]; Dj[idx] = small[3 * qq + idx]; }
+  __syncthreads();
+  int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= d.d1) return;
+  const bool piv = (i >= g0 && i < g0 + q) || (i >= j0 && i < j0 + q);
+  if (piv) {
+    for (int c = 0; c < q; c++) { P1[(int64_t)i * q + c] = 0.f; P2[(int64_t)i * q + c] = 0.f; P1D[(int64_t)i * q + c] = 0.f; P2D[(int64_t)i * q + c] = 0.f; }
+    return;
+  }
+  double c1[64], c2[64];
+  for (int c = 0; c < q; c++) c1[c] = (double)C1[(int64_t)i * q + c];
+  for (int c = 0; c < q; c++) {
+    double v = (double)C2[(int64_t)i * q + c];
+    for (int k = 0; k < q; k++) v -= c1[k] * M1[k * q + c];
+    c2[c] = v;
+  }
+  for (int c = 0; c < q; c++) {
+    double v1 = 0, v2 = 0;
+    for (int k = 0; k < q; k++) { v1 += c1[k] * Dg[k * q + c]; v2 += c2[k] * Dj[k * q + c]; }
+    P1[(int64_t)i * q + c] = (float)c1[c];
+    P2[(int64_t)i * q + c] = (float)c2[c];
+    P1D[(int64_t)i * q + c] = (float)v1;
+    P2D[(int64_t)i * q + c] = (float)v2;
+  }
+}
+
+// New pivot rows (after both sweeps), for every l outside the pivots:
+//   N''(g_r, l) = -P1D[l][r] - sum_c W2[r][c] P2D[l][c],  W2 = -M1     (= -P1D[l][r] + sum_c M1[r][c] P2D[l][c])
+//   N''(j_r, l) =  P2D[l][r]
+// pivot-pivot blocks: N''_gg = -Dg - W2 Dj' W2^T, N''_jj = -Dj', N''(g, j) = W2 Dj'.
+// Z''_g = -rZ1 + M1 rZ2, Z''_j = rZ2.  Diagonal blocks of the other groups are updated in float64.
+__global__ __launch_bounds__(256) void pair_fix_kernel(TabDims d, float* __restrict__ N, float* __restrict__ Z,
+                                                        const float* __restrict__ P1, const float* __restrict__ P2,
+                                                        const float* __restrict__ P1D, const float* __restrict__ P2D,
+                                                        const float* __restrict__ rZ1, const float* __restrict__ rZ2,
+                                                        const double* __restrict__ small, const SearchCtrl* __restrict__ ctrl,
+                                                        double* __restrict__ dblk, int32_t* __restrict__ kept) {
+  if (ctrl->done) return;
+  const int q = d.q, qq = q * q, m = d.m;
+  const int g = ctrl->g_out, j = ctrl->g_in, g0 = g * q, j0 = j * q;
+  const double* Dg = small; const double* M1 = small + 2 * qq; const double* Dj = small + 3 * qq; const double* W2Dj = small + 4 * qq;
+  const int64_t ld = d.d1;
+  int l = blockIdx.x * 256 + threadIdx.x;
+  if (l < d.d1) {
+    const bool in_g = (l >= g0 && l < g0 + q), in_j = (l >= j0 && l < j0 + q);
+    if (!in_g && !in_j) {
+      for (int r = 0; r < q; r++) {
+        double vg = -(double)P1D[(int64_t)l * q + r];
+        for (int c = 0; c < q; c++) vg += M1[r * q + c] * (double)P2D[(int64_t)l * q + c];
+        float vj = P2D[(int64_t)l * q + r];
+        int gr = g0 + r, jr = j0 + r;
+        if (l < gr) N[(int64_t)gr * ld + l] = (float)vg; else N[(int64_t)l * ld + gr] = (float)vg;
+        if (l < jr) N[(int64_t)jr * ld + l] = vj; else N[(int64_t)l * ld + jr] = vj;
+      }
+      // float64 diagonal block of l's group (one thread per group: the one owning its first row)
+      if (l % q == 0) {
+        int h = l / q;
+        for (int r = 0; r < q; r++)
+          for (int c = 0; c < q; c++) {
+            double v = 0;
+            for (int k = 0; k < q; k++)
+              v += (double)P1D[(int64_t)(l + r) * q + k] * (double)P1[(int64_t)(l + c) * q + k] +
+                   (double)P2D[(int64_t)(l + r) * q + k] * (double)P2[(int64_t)(l + c) * q + k];
+            dblk[(int64_t)h * qq + r * q + c] -= v;
+          }
+      }
+    }
+  }
+  // pivot-pivot blocks and flags: first workgroup
+  if (blockIdx.x == 0) {
+    for (int idx = threadIdx.x; idx < qq; idx += 256) {
+      int r = idx / q, c = idx % q;
+      double ngg = -Dg[idx];
+      for (int k = 0; k < q; k++) ngg += W2Dj[r * q + k] * M1[c * q + k];     // - W2 Dj' W2^T = + (W2 Dj') M1^T
+      double njj = -Dj[idx];
+      double ngj = W2Dj[idx];                                                  // N''(g_r, j_c)
+      dblk[(int64_t)g * qq + idx] = ngg;
+      dblk[(int64_t)j * qq + idx] = njj;
+      if (c <= r) {
+        N[(int64_t)(g0 + r) * ld + g0 + c] = (float)ngg;
+        N[(int64_t)(j0 + r) * ld + j0 + c] = (float)njj;
+      }
+      if (g0 > j0) N[(int64_t)(g0 + r) * ld + j0 + c] = (float)ngj;
+      else N[(int64_t)(j0 + c) * ld + g0 + r] = (float)ngj;
+    }
+    if (threadIdx.x == 0) { kept[g] = 0; kept[j] = 1; }
+  }
+  // Z rows of the pivots
+  int64_t tot = (int64_t)q * m;
+  for (int64_t idx = blockIdx.x * 256 + threadIdx.x; idx < tot; idx += (int64_t)gridDim.x * 256) {
+    int r = (int)(idx / m), col = (int)(idx % m);
+    double vg = -(double)rZ1[idx];
+    for (int c = 0; c < q; c++) vg += M1[r * q + c] * (double)rZ2[(int64_t)c * m + col];
+    Z[(int64_t)(g0 + r) * m + col] = (float)vg;
+    Z[(int64_t)(j0 + r) * m + col] = rZ2[idx];
+  }
+}
+
+// bulk update of the lower triangle: N[i][l] -= sum_c P1D[i][c] P1[l][c] + P2D[i][c] P2[l][c]
+// generic in q; 64 x 64 tiles, 16 x 16 threads, 4 x 4 elements per thread, panels staged in LDS 16 columns at a time.
+__global__ __launch_bounds__(256) void update_N_kernel(TabDims d, float* __restrict__ N, const float* __restrict__ P1,
+                                                        const float* __restrict__ P2, const float* __restrict__ P1D,
+                                                        const float* __restrict__ P2D, const SearchCtrl* __restrict__ ctrl) {
+  if (ctrl->done) return;
+  const int tr = blockIdx.y, tc = blockIdx.x;
+  if (tc > tr) return;
+  __shared__ float sRD[2][64][17];   // P1D / P2D rows of this tile
+  __shared__ float sC[2][64][17];    // P1 / P2 rows of the column range
+  const int q = d.q, n = d.d1;
+  const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+  const int i0 = tr * 64, l0 = tc * 64;
+  float acc[4][4] = {};
+  for (int c0 = 0; c0 < q; c0 += 16) {
+    int cw = (q - c0 < 16) ? q - c0 : 16;
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < 64 * 16; idx += 256) {
+      int r = idx >> 4, c = idx & 15;
+      bool okc = c < cw;
+      int ri = i0 + r, rl = l0 + r;
+      sRD[0][r][c] = (okc && ri < n) ? P1D[(int64_t)ri * q + c0 + c] : 0.f;
+      sRD[1][r][c] = (okc && ri < n) ? P2D[(int64_t)ri * q + c0 + c] : 0.f;
+      sC[0][r][c] = (okc && rl < n) ? P1[(int64_t)rl * q + c0 + c] : 0.f;
+      sC[1][r][c] = (okc && rl < n) ? P2[(int64_t)rl * q + c0 + c] : 0.f;
+    }
+    __syncthreads();
+    for (int c = 0; c < cw; c++) {
+      float a1[4], a2[4], b1[4], b2[4];
+#pragma unroll
+      for (int u = 0; u < 4; u++) { a1[u] = sRD[0][ty * 4 + u][c]; a2[u] = sRD[1][ty * 4 + u][c]; b1[u] = sC[0][tx * 4 + u][c]; b2[u] = sC[1][tx * 4 + u][c]; }
+#pragma unroll
+      for (int u = 0; u < 4; u++)
+#pragma unroll
+        for (int v = 0; v < 4; v++) acc[u][v] += a1[u] * b1[v] + a2[u] * b2[v];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < 4; u++) {
+    int i = i0 + ty * 4 + u;
+    if (i >= n) continue;
+#pragma unroll
+    for (int v = 0; v < 4; v++) {
+      int l = l0 + tx * 4 + v;
+      if (l <= i) N[(int64_t)i * n + l] -= acc[u][v];
+    }
+  }
+}
+
+// q = 1 fast path of the bulk update: N[i][l] -= a1[i]*b1[l] + a2[i]*b2[l] on the lower triangle.
+// One workgroup streams a 32-row x 1024-column slab: each thread owns 4 consecutive columns and keeps their
+// coefficients in registers while it walks down the rows.
+__global__ __launch_bounds__(256) void update_N_q1_kernel(int n, float* __restrict__ N, const float* __restrict__ P1,
+                                                           const float* __restrict__ P2, const float* __restrict__ P1D,
+                                                           const float* __restrict__ P2D, const SearchCtrl* __restrict__ ctrl) {
+  if (ctrl->done) return;
+  const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 1024;
+  if (c0 > r0 + 31) return;
+  const int c = c0 + threadIdx.x * 4;
+  if (c >= n) return;
+  const int rend = (r0 + 32 < n) ? r0 + 32 : n;
+  if (c + 3 < n && (n & 3) == 0) {
+    const float4 b1 = *reinterpret_cast<const float4*>(P1 + c);
+    const float4 b2 = *reinterpret_cast<const float4*>(P2 + c);
+#pragma unroll 4
+    for (int i = r0; i < rend; i++) {
+      if (c > i) continue;
+      const float a1 = P1D[i], a2 = P2D[i];
+      float4* p = reinterpret_cast<float4*>(N + (int64_t)i * n + c);
+      float4 v = *p;
+      v.x -= a1 * b1.x + a2 * b2.x;
+      v.y -= a1 * b1.y + a2 * b2.y;
+      v.z -= a1 * b1.z + a2 * b2.z;
+      v.w -= a1 * b1.w + a2 * b2.w;
+      *p = v;
+    }
+  } else {
+    for (int i = r0; i < rend; i++)
+      for (int u = 0; u < 4; u++) {
+        int l = c + u;
+        if (l < n && l <= i) N[(int64_t)i * n + l] -= P1D[i] * P1[l] + P2D[i] * P2[l];
+      }
+  }
+}
+
+// Z rows of one group: Z[i][:] -= sum_c P1[i][c] rZ1[c][:] + P2[i][c] rZ2[c][:], then gram[h] = Z_h Z_h^T.
+__global__ __launch_bounds__(256) void update_Z_kernel(TabDims d, float* __restrict__ Z, const float* __restrict__ P1,
+                                                        const float* __restrict__ P2, const float* __restrict__ rZ1,
+                                                        const float* __restrict__ rZ2, double* __restrict__ gram,
+                                                        const SearchCtrl* __restrict__ ctrl) {
+  if (ctrl->done) return;
+  const int h = blockIdx.x, q = d.q, m = d.m;
+  float* Zh = Z + (int64_t)h * q * m;
+  if (q == 1) {
+    const float a1 = P1[h], a2 = P2[h];
+    double v = 0;
+    for (int col = threadIdx.x; col < m; col += 256) {
+      float z = Zh[col] - (a1 * rZ1[col] + a2 * rZ2[col]);
+      Zh[col] = z;
+      v += (double)z * (double)z;
+    }
+    __shared__ double red[4];
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) gram[h] = red[0] + red[1] + red[2] + red[3];
+    return;
+  }
+  for (int64_t idx = threadIdx.x; idx < (int64_t)q * m; idx += 256) {
+    int r = (int)(idx / m), col = (int)(idx % m);
+    const float* p1 = P1 + (int64_t)(h * q + r) * q;
+    const float* p2 = P2 + (int64_t)(h * q + r) * q;
+    float acc = 0.f;
+    for (int c = 0; c < q; c++) acc += p1[c] * rZ1[(int64_t)c * m + col] + p2[c] * rZ2[(int64_t)c * m + col];
+    Zh[idx] -= acc;
+  }
+  __syncthreads();
+  group_gram(Zh, q, m, gram + (int64_t)h * q * q);
+}
+
+hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int forced_out, int forced_in, int always_accept,
+                                   hipStream_t s, hipEvent_t* ev) {
+  const int q = d.q;
+  const int rb = (d.d1 + 255) / 256;
+  hipLaunchKernelGGL(select_kernel, dim3(1), dim3(1024), 0, s, d, t.kept, t.score, t.ctrl, forced_out, forced_in);
+  hipLaunchKernelGGL(extract_pair_kernel, dim3(rb), dim3(256), 0, s, d, t.N, t.Z, t.ctrl, t.C1, t.C2, t.rZ1, t.rZ2);
+  hipLaunchKernelGGL(pair_small_kernel, dim3(1), dim3(256), 0, s, d, t.C1, t.C2, t.rZ1, t.rZ2, t.small, t.ctrl, always_accept,
+                     t.trace_out, t.trace_in, t.trace_gap, t.trace_obj);
+  // bulk panels go to C1D/C2D (times D) and to two further panels stored behind them
+  float* P1 = t.C1D + (int64_t)2 * d.d1 * q;
+  float* P2 = P1 + (int64_t)d.d1 * q;
+  float* P1D = t.C1D;
+  float* P2D = t.C2D;
+  hipLaunchKernelGGL(pair_panels_kernel, dim3(rb), dim3(256), (size_t)3 * q * q * 8, s, d, t.C1, t.C2, t.small, t.ctrl, P1, P2,
+                     P1D, P2D);
+  hipLaunchKernelGGL(pair_fix_kernel, dim3(rb), dim3(256), 0, s, d, t.N, t.Z, P1, P2, P1D, P2D, t.rZ1, t.rZ2, t.small, t.ctrl,
+                     t.dblk, t.kept);
+  if (ev) hipEventRecord(ev[0], s);
+  if (q == 1) {
+    dim3 grid((d.d1 + 1023) / 1024, (d.d1 + 31) / 32);
+    hipLaunchKernelGGL(update_N_q1_kernel, grid, dim3(256), 0, s, d.d1, t.N, P1, P2, P1D, P2D, t.ctrl);
+  } else {
+    int tiles = (d.d1 + 63) / 64;
+    hipLaunchKernelGGL(update_N_kernel, dim3(tiles, tiles), dim3(256), 0, s, d, t.N, P1, P2, P1D, P2D, t.ctrl);
+  }
+  if (ev) hipEventRecord(ev[1], s);
+  hipLaunchKernelGGL(update_Z_kernel, dim3(d.p), dim3(256), 0, s, d, t.Z, P1, P2, t.rZ1, t.rZ2, t.gram, t.ctrl);
+  if (ev) hipEventRecord(ev[2], s);
+  hipLaunchKernelGGL(score_kernel, dim3(d.p), dim3(64), (size_t)2 * q * q * 8, s, d, t.kept, t.gram, t.dblk, t.score, t.ctrl);
+  return hipGetLastError();
+}
+
+}  // namespace osscar
