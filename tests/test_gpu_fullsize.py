@@ -1,0 +1,187 @@
+"""GPU parity at the sizes of the five benchmark layers, in the launch configuration bench.py times.
+
+cfg2 and cfg4 run whole against the oracle.  cfg3 keeps its full p, m, k and uses fewer calibration rows so
+that the oracle's Gram and its first search iterations finish in about a minute.  cfg5 (the layer bench.py
+times) is checked on sampled outputs the oracle can compute one by one -- tiles of H from the generator's
+column blocks -- and through properties that hold at any size: the normal equations of the final weights,
+the identity P H_KK = I on sampled rows, a monotone objective trace, and the tracked objective against the
+fresh solve."""
+import numpy as np
+import pytest
+import torch
+
+import osscar_inputs as inp
+from oracle import osscar_oracle as orc
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+GAP = 1e-5
+
+
+def rel(a, b):
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def gen_on_gpu(cfg, rows_per=4096):
+    X = torch.empty(cfg.n, cfg.d1, dtype=inp.torch_dtype(cfg.x_dtype), device=DEV)
+    for r0 in range(0, cfg.n, rows_per):
+        nr = min(rows_per, cfg.n - r0)
+        X[r0:r0 + nr] = inp.gen_X(cfg, r0, nr, device=DEV)
+    return X
+
+
+def make_solver(cfg, X, W):
+    import paper_2403_12983_amd as pkg
+    return pkg.Solver(cfg.d1, cfg.m, cfg.p, cfg.q, cfg.k, cfg.swaps, X.dtype, W.dtype, DEV)
+
+
+def T(s, which):
+    from paper_2403_12983_amd import binding as B
+    return s.osscar_get_tensor(getattr(B, which))
+
+
+def follow_check(cfg, H, G, c0, K0, r, max_follow):
+    pairs = list(zip(r["trace_out"].tolist(), r["trace_in"].tolist()))[: min(r["accepted"], max_follow)]
+    fol = orc.local_search(H, G, c0, K0, cfg.p, cfg.q, len(pairs), follow=pairs)
+    for i, x in enumerate(fol.trace):
+        assert x.deficit_rem <= GAP and x.deficit_add <= GAP, (i, x)
+        assert x.delta < 0, (i, x)
+        assert abs(r["trace_obj"][i] - x.obj_after) <= 1e-5 * abs(x.obj_after), (i, r["trace_obj"][i], x.obj_after)
+    return fol
+
+
+@pytest.mark.parametrize("name,max_follow", [("cfg2", 500), ("cfg4", 200)])
+def test_whole_layer_against_oracle(name, max_follow):
+    cfg = inp.CONFIGS[name]
+    X = gen_on_gpu(cfg)
+    W = inp.gen_W(cfg, DEV)
+    Xd, Wd = X.cpu().double().numpy(), W.cpu().double().numpy()
+    H, G, c0, lam = orc.gram(Xd, Wd, cfg.lam_abs, cfg.lam_rel)
+    del Xd
+    s = make_solver(cfg, X, W)
+    s.osscar_gram(X, True, W, cfg.lam_abs, cfg.lam_rel)
+    dsc = np.sqrt(np.diag(H))
+    assert np.max(np.abs(T(s, "T_H").cpu().double().numpy() - H) / np.outer(dsc, dsc)) < 1e-6
+    assert rel(T(s, "T_G").cpu().double().numpy(), G) < 1e-6
+    obj0 = s.osscar_init_support()
+    K0 = orc.magnitude_support(Wd, cfg.p, cfg.q, cfg.k)
+    assert T(s, "T_KEPT").cpu().tolist() == K0
+    r = s.osscar_local_search(cfg.swaps)
+    fol = follow_check(cfg, H, G, c0, K0, r, max_follow)
+    assert abs(obj0 - fol.obj_initial) <= 1e-5 * fol.obj_initial
+    What, support, obj = s.osscar_backsolve()
+    if r["accepted"] <= max_follow:
+        assert support.tolist() == fol.support
+    Wo, objo = orc.solve_support(H, G, c0, support.tolist(), cfg.q)
+    assert rel(What.cpu().double().numpy(), Wo) < 1e-4
+    assert abs(obj - objo) <= 1e-4 * objo
+    assert abs(r["obj_final"] - objo) <= 1e-4 * objo
+    print(f"{name}: {r['accepted']} swaps, obj {r['obj_initial']:.6g} -> {obj:.6g}, min gaps {r['trace_gap'].min(axis=0)}")
+    s.close()
+
+
+def test_cfg3_full_width_reduced_rows():
+    cfg = inp.CONFIGS["cfg3"].replace(n=16384)
+    X = gen_on_gpu(cfg)
+    W = inp.gen_W(cfg, DEV)
+    Xd, Wd = X.cpu().double().numpy(), W.cpu().double().numpy()
+    H, G, c0, lam = orc.gram(Xd, Wd, cfg.lam_abs, cfg.lam_rel)
+    del Xd
+    s = make_solver(cfg, X, W)
+    s.osscar_gram(X[:5000])
+    s.osscar_gram(X[5000:], True, W, cfg.lam_abs, cfg.lam_rel)
+    dsc = np.sqrt(np.diag(H))
+    Hg = T(s, "T_H").cpu().double().numpy()
+    assert np.max(np.abs(Hg - H) / np.outer(dsc, dsc)) < 1e-6
+    del Hg
+    s.osscar_init_support()
+    K0 = orc.magnitude_support(Wd, cfg.p, cfg.q, cfg.k)
+    assert T(s, "T_KEPT").cpu().tolist() == K0
+    st = orc.init_state(H, G, K0, cfg.q)
+    assert rel(T(s, "T_B").cpu().double().numpy(), st.What_K) < 2e-5
+    rem_o = orc.removal_scores(st, cfg.p, cfg.q)
+    rem_g = T(s, "T_REM").cpu().numpy()
+    fk = np.isfinite(rem_o)
+    assert np.max(np.abs(rem_g[fk] - rem_o[fk]) / rem_o[fk]) < 2e-5
+    r = s.osscar_local_search(300)
+    assert r["accepted"] == 300
+    follow_check(cfg, H, G, c0, K0, r, 12)
+    # final state: fresh solve against the oracle on the library's support
+    What, support, obj = s.osscar_backsolve()
+    Wo, objo = orc.solve_support(H, G, c0, support.tolist(), cfg.q)
+    assert rel(What.cpu().double().numpy(), Wo) < 1e-4
+    assert abs(obj - objo) <= 1e-4 * objo and abs(r["obj_final"] - objo) <= 1e-4 * objo
+    s.close()
+
+
+def test_cfg5_bench_configuration_sampled():
+    cfg = inp.CONFIGS["cfg5"]
+    X = gen_on_gpu(cfg)
+    W = inp.gen_W(cfg, DEV)
+    s = make_solver(cfg, X, W)
+    s.osscar_gram(X, True, W, cfg.lam_abs, cfg.lam_rel)
+    lam, c0 = s.osscar_get_scalars()
+    H = T(s, "T_H")
+    # (1) tiles of H: 6 column blocks of 32 columns from the generator on the CPU, all 36 block pairs, float64
+    rng = np.random.default_rng(5)
+    starts = sorted(int(v) for v in rng.choice(cfg.d1 // 32, size=6, replace=False) * 32)
+    cols = torch.cat([torch.arange(a, a + 32) for a in starts])
+    Xs = torch.cat([inp.gen_X(cfg, r0, 32768, cols=cols).double() for r0 in range(0, cfg.n, 32768)]).numpy()
+    Hs = Xs.T @ Xs
+    assert torch.equal(X[:, cols.to(DEV)].cpu().double(), torch.from_numpy(Xs))   # same bits on both devices
+    Hg = H[cols.to(DEV)][:, cols.to(DEV)].cpu().double().numpy()
+    ds = np.sqrt(np.diag(Hs))
+    off = Hg - Hs - lam * np.eye(len(cols))
+    assert np.max(np.abs(off) / np.outer(ds, ds)) < 1e-6
+    # lambda: mean diag of X^T X from the GPU's own diagonal, and the sampled diagonal agrees with the oracle
+    diag = torch.diagonal(H).double()
+    assert abs(lam - cfg.lam_rel * (diag.mean().item() - lam)) <= 1e-6 * lam
+    # G = H W on sampled rows (float64 on the host)
+    rows = cols[::16]
+    Gg = T(s, "T_G")[rows.to(DEV)].cpu().double().numpy()
+    Go = H[rows.to(DEV)].cpu().double().numpy() @ W.cpu().double().numpy()
+    assert rel(Gg, Go) < 1e-6
+    del H
+    # (2) support bookkeeping: magnitude top-k from the oracle's definition
+    K0 = orc.magnitude_support(W.cpu().double().numpy(), cfg.p, cfg.q, cfg.k)
+    obj0 = s.osscar_init_support()
+    assert T(s, "T_KEPT").cpu().tolist() == K0
+    # (3) search: monotone objective, all indices valid, tracked objective equals the fresh solve
+    r = s.osscar_local_search(400)
+    assert r["accepted"] == 400
+    trace = np.concatenate([[obj0], r["trace_obj"]])
+    assert np.all(np.diff(trace) < 0)
+    kept = set(K0)
+    for g, j in zip(r["trace_out"].tolist(), r["trace_in"].tolist()):
+        assert g in kept and j not in kept
+        kept.remove(g)
+        kept.add(j)
+    What, support, obj = s.osscar_backsolve()
+    assert support.tolist() == sorted(kept)
+    assert abs(obj - r["obj_final"]) <= 1e-4 * obj
+    # (4) normal equations of the final weights on sampled rows, float64 on the device: H_KK What_K = G_K
+    Kt = torch.from_numpy(support.astype(np.int64)).to(DEV)
+    Hd, Gd = T(s, "T_H"), T(s, "T_G")
+    samp = Kt[torch.arange(0, Kt.numel(), 97, device=DEV)]
+    lhs = Hd[samp][:, Kt].double() @ What[Kt].double()
+    rhs = Gd[samp].double()
+    assert (torch.linalg.norm(lhs - rhs) / torch.linalg.norm(rhs)).item() < 1e-5
+    pruned = torch.ones(cfg.d1, dtype=torch.bool, device=DEV)
+    pruned[Kt] = False
+    assert torch.count_nonzero(What[pruned]).item() == 0
+    # objective from its definition on the final weights: c0 - 2<G, What> + <What, H What> (float64, chunked)
+    quad = 0.0
+    for a in range(0, Kt.numel(), 2048):
+        idx = Kt[a:a + 2048]
+        quad += (What[idx].double() * (Hd[idx][:, Kt].double() @ What[Kt].double())).sum().item()
+    lin = (Gd[Kt].double() * What[Kt].double()).sum().item()
+    assert abs((c0 - 2 * lin + quad) - obj) <= 1e-4 * obj
+    # (5) the maintained inverse on sampled rows: P H_KK = I
+    P = T(s, "T_P")
+    rows_s = torch.arange(0, Kt.numel(), 211, device=DEV)
+    I_s = P[rows_s].double() @ Hd[Kt][:, Kt].double()
+    eye = torch.zeros_like(I_s)
+    eye[torch.arange(rows_s.numel(), device=DEV), rows_s] = 1.0
+    assert (I_s - eye).abs().max().item() < 1e-3
+    print(f"cfg5: obj {obj0:.6g} -> {obj:.6g} after 400 swaps; timers {s.osscar_get_timers()}")
+    s.close()

@@ -1,0 +1,60 @@
+"""CPU-only checks of the boundary: the shared library loads, exports every symbol the header declares,
+and its host-only entry points behave (no GPU work is issued here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    txt = open(os.path.join(ROOT, "include", "osscar.h")).read()
+    txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+    return sorted(set(re.findall(r"\b(osscar_[a-z_]+)\s*\(", txt)))
+
+
+def _lib():
+    import paper_2403_12983_amd as pkg
+    if not os.path.exists(pkg.lib_path()):
+        from paper_2403_12983_amd import build
+        build.build()
+    return pkg, pkg.load_library()
+
+
+def test_header_symbols_are_exported():
+    pkg, lib = _lib()
+    names = _declared()
+    assert {"osscar_gram", "osscar_init_support", "osscar_local_search", "osscar_backsolve"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(pkg.EXPORTED_SYMBOLS) == names
+
+
+def test_workspace_query_is_host_only_and_validates():
+    pkg, lib = _lib()
+    from paper_2403_12983_amd.binding import _Desc
+    good = _Desc(28672, 7168, 28672, 1, 14336, 5000, 1, 1)
+    nbytes = lib.osscar_workspace_bytes(C.byref(good))
+    # H, G, N, Z in float32 are a lower bound
+    assert nbytes > 4 * (2 * 28672 ** 2 + 2 * 28672 * 7168)
+    assert nbytes < 40e9
+    for bad in (_Desc(64, 32, 64, 2, 32, 10, 0, 0),      # d1 != p*q
+                _Desc(64, 32, 64, 1, 65, 10, 0, 0),      # k > p
+                _Desc(64, 32, 64, 1, 0, 10, 0, 0),       # k < 1
+                _Desc(130, 32, 2, 65, 1, 10, 0, 0),      # q > 64
+                _Desc(64, 32, 64, 1, 32, 10, 7, 0)):     # unknown dtype
+        assert lib.osscar_workspace_bytes(C.byref(bad)) == 0
+    ctx = C.c_void_p()
+    assert lib.osscar_create(C.byref(ctx), C.byref(good), None, 0, None) == 1          # EINVAL: no workspace
+    assert lib.osscar_create(C.byref(ctx), C.byref(good), C.c_void_p(256), 1024, None) == 2   # ENOMEM: too small
+    assert lib.osscar_create(C.byref(ctx), C.byref(good), C.c_void_p(257), nbytes, None) == 1  # misaligned
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    import paper_2403_12983_amd.binding as b
+    monkeypatch.setattr(b, "_LIB", None)
+    monkeypatch.setattr(b, "lib_path", lambda: str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        b.load_library()
