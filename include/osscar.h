@@ -104,11 +104,14 @@ osscar_status osscar_init_support(osscar_ctx* ctx, int mode, const int32_t* grou
  * (Case 3) and applies it by low-rank up/downdates if obj drops by more than rel_tol*obj; otherwise
  * the search stops.  At most max_swaps (<= desc.max_swaps) iterations.
  * flags: OSSCAR_SEARCH_ALWAYS_ACCEPT applies every selected pair (Algorithm 1 as printed).
+ * OSSCAR_SEARCH_EAGER applies every swap to the whole state at once (one pass over HBM per swap); by
+ * default, layers with q = 1 keep up to 64 swaps pending as a small low-rank correction and apply them
+ * together on the matrix cores -- the same swaps, with less traffic.
  * refresh_every > 0 recomputes V, R and B from P, H, G by GEMM after that many accepted swaps.
  * Optional host outputs of length max_swaps (entry i describes iteration i, including a final rejected
  * one): trace_out / trace_in = group leaving / entering; trace_gap[2i], trace_gap[2i+1] = relative gap
  * between best and second-best removal cost / addition gain; trace_obj[i] = obj after the iteration. */
-enum { OSSCAR_SEARCH_ALWAYS_ACCEPT = 1u };
+enum { OSSCAR_SEARCH_ALWAYS_ACCEPT = 1u, OSSCAR_SEARCH_EAGER = 2u };
 typedef struct {
   int32_t iters;     /* iterations run (accepted swaps + at most one rejected) */
   int32_t accepted;  /* swaps applied */
@@ -143,9 +146,10 @@ osscar_status osscar_get_scalars(osscar_ctx* ctx, double* lambda_host, double* c
 
 /* Device times of the last call of each kind, in milliseconds (HIP events on the context's stream):
  * [0] the Gram accumulation of the chunk passed together with finalize, [1] finalize, [2] init_support,
- * [3] local_search, [4] backsolve, [5] mean duration of one launch of the search's bulk update of N
- * (sampled once per batch of iterations), [6] total time of the search's refreshes, [7] mean duration of one
- * launch of the search's update of Z.  out_host: 8 doubles. */
+ * [3] local_search, [4] backsolve, [6] total time of the search's refreshes and flushes.  Sampled once
+ * per batch of iterations: eager search [5] mean duration of one bulk update of N, [7] of one update of Z;
+ * delayed-update search [5] mean duration of the per-swap pass over Z, [7] of the rest of that iteration's
+ * kernels including the pass.  out_host: 8 doubles. */
 osscar_status osscar_get_timers(osscar_ctx* ctx, double* out_host);
 
 const char* osscar_last_error(const osscar_ctx* ctx);

@@ -12,6 +12,7 @@ import torch
 OSSCAR_F32, OSSCAR_BF16 = 0, 1
 OSSCAR_INIT_MAGNITUDE, OSSCAR_INIT_GIVEN = 0, 1
 OSSCAR_SEARCH_ALWAYS_ACCEPT = 1
+OSSCAR_SEARCH_EAGER = 2
 T_H, T_G, T_P, T_B, T_V, T_R, T_REM, T_ADD, T_KEPT, T_CAND = range(10)
 _STATUS = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "ENOTPD", 4: "EHIP", 5: "ESTATE"}
 

@@ -76,6 +76,7 @@ struct osscar_ctx {
   float *C1, *C2, *Cblk, *rZ1, *rZ2;
   SearchCtrl* ctrl;
   int32_t *trace_out, *trace_in; float* trace_gap; double* trace_obj;
+  LazyPtrs lazy;
   // phase-shared scratch
   char* scratch; size_t scratch_bytes;
 
@@ -124,6 +125,17 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
   int32_t* trace_in = cv.take<int32_t>(ms);
   float* trace_gap = cv.take<float>(2 * ms);
   double* trace_obj = cv.take<double>(ms);
+  LazyPtrs L{};
+  if (q == 1) {
+    const int64_t TM = LAZY_TM;
+    L.pos = cv.take<int32_t>(d1); L.Tidx = cv.take<int32_t>(TM); L.Jsg = cv.take<float>(TM);
+    L.C0T = cv.take<float>(TM * d1); L.Minv = cv.take<double>(TM * TM); L.ZT = cv.take<double>(TM * m);
+    L.ZT32 = cv.take<float>(TM * m); L.E = cv.take<float>(d1 * TM); L.Cb = cv.take<float>(d1 * TM);
+    L.xg = cv.take<double>(TM); L.xj = cv.take<double>(TM); L.u1 = cv.take<double>(TM); L.u2 = cv.take<double>(TM);
+    L.cg = cv.take<double>(d1); L.cj = cv.take<double>(d1); L.w1 = cv.take<double>(d1); L.w2 = cv.take<double>(d1);
+    L.y1 = cv.take<double>(m); L.y2 = cv.take<double>(m); L.y1f = cv.take<float>(m); L.y2f = cv.take<float>(m);
+    L.part = cv.take<double>(((m + 255) / 256) * 5); L.ls = cv.take<double>(16);
+  }
   // scratch: the larger of the Gram phase and the init / refresh / backsolve phase
   size_t gram_phase = align_up((size_t)d1 * d1 * 8) + align_up((size_t)d1 * m * 4) + align_up((size_t)d1 * XT_ROWS * 4);
   size_t init_phase = 4 * align_up((size_t)kr * kr * 4) + 3 * align_up((size_t)kr * cr * 4) + align_up((size_t)cr * cr * 4) +
@@ -135,10 +147,10 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
     c->small = small; c->scal = scal; c->partial = partial; c->kept = kept; c->rowsK = rowsK; c->rowsC = rowsC;
     c->notpd = notpd; c->C1 = C1; c->C2 = C2; c->Cblk = Cblk; c->rZ1 = rZ1; c->rZ2 = rZ2; c->ctrl = ctrl;
     c->trace_out = trace_out; c->trace_in = trace_in; c->trace_gap = trace_gap; c->trace_obj = trace_obj;
-    c->scratch = scratch; c->scratch_bytes = scratch_bytes;
+    c->scratch = scratch; c->scratch_bytes = scratch_bytes; c->lazy = L;
   }
-  Layout L; L.total = cv.off; L.scratch_bytes = scratch_bytes;
-  return L;
+  Layout lay; lay.total = cv.off; lay.scratch_bytes = scratch_bytes;
+  return lay;
 }
 
 bool desc_ok(const osscar_desc* d) {
@@ -487,6 +499,7 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
   if (st != OSSCAR_OK) return st;
   const double obj0 = h.obj;
   h.done = (c->cr == 0) ? 1 : 0; h.iters = 0; h.accepted = 0; h.notpd = 0; h.rel_tol = rel_tol; h.g_out = h.g_in = -1;
+  h.pause = 0; h.tau = 0;
   HIPCHK(c, hipMemcpyAsync(c->ctrl, &h, sizeof h, hipMemcpyHostToDevice, s));
   HIPCHK(c, hipStreamSynchronize(s));
   const int always = (flags & OSSCAR_SEARCH_ALWAYS_ACCEPT) ? 1 : 0;
@@ -495,6 +508,66 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
   HIPCHK(c, hipEventRecord(c->ev_a, s));
   int launched = 0, since_refresh_base = 0, samples = 0;
   double refresh_ms = 0, upd_n_ms = 0, upd_z_ms = 0;
+  const bool use_lazy = (c->q == 1) && !(flags & OSSCAR_SEARCH_EAGER);
+  if (use_lazy) {
+    // delayed-update search: the tableau in HBM is only touched by a flush every FLUSH iterations
+    const LazyPtrs& L = c->lazy;
+    const int FLUSH = LAZY_TM / 2, BATCH = 32;
+    HIPCHK(c, launch_lazy_init(d, L, c->ctrl, s));
+    int since_flush = 0;
+    double flush_ms = 0; int flushes = 0;
+    auto flush = [&]() -> osscar_status {
+      hipEvent_t f0 = c->ev_s[0][0], f1 = c->ev_s[0][1];
+      HIPCHK(c, hipEventRecord(f0, s));
+      HIPCHK(c, launch_lazy_flush(d, t, L, s));
+      HIPCHK(c, hipEventRecord(f1, s));
+      HIPCHK(c, hipStreamSynchronize(s));
+      float ms = 0; hipEventElapsedTime(&ms, f0, f1); flush_ms += ms; flushes++;
+      since_flush = 0;
+      return OSSCAR_OK;
+    };
+    while (h.iters < max_swaps && !h.done) {
+      int nb = std::min(std::min(BATCH, max_swaps - h.iters), FLUSH - since_flush);
+      if (refresh_every > 0) nb = std::min(nb, std::max(1, refresh_every - (h.accepted - since_refresh_base)));
+      const bool sample = samples + 1 < EV_SAMPLES;
+      for (int i = 0; i < nb; i++)
+        HIPCHK(c, launch_lazy_iteration(d, t, L, always, s, (i == 0 && sample) ? c->ev_s[samples + 1] : nullptr));
+      const int before = h.iters;
+      st = read_ctrl(c, &h);
+      if (st != OSSCAR_OK) return st;
+      if (h.notpd) return fail(c, OSSCAR_ENOTPD, "osscar_local_search: a pivot lost definiteness at iteration %d", h.iters);
+      since_flush += h.iters - before;
+      if (sample && h.iters > before) {
+        float a = 0, b = 0;
+        hipEventElapsedTime(&a, c->ev_s[samples + 1][0], c->ev_s[samples + 1][1]);
+        hipEventElapsedTime(&b, c->ev_s[samples + 1][0], c->ev_s[samples + 1][2]);
+        upd_n_ms += a; upd_z_ms += b; samples++;
+      }
+      const bool want_refresh = !h.done && refresh_every > 0 && h.accepted - since_refresh_base >= refresh_every && h.iters < max_swaps;
+      if (h.pause || since_flush >= FLUSH || h.done || want_refresh || h.iters >= max_swaps) {
+        if (h.tau > 0 || h.pause) { st = flush(); if (st != OSSCAR_OK) return st; }
+        h.pause = 0; h.tau = 0;
+      }
+      if (want_refresh) {
+        hipEvent_t r0 = c->ev_s[0][0], r1 = c->ev_s[0][1];
+        HIPCHK(c, hipEventRecord(r0, s));
+        st = read_kept(c);
+        if (st != OSSCAR_OK) return st;
+        double obj = 0;
+        st = build_state(c, &obj);
+        if (st != OSSCAR_OK) return st;
+        HIPCHK(c, hipMemcpyAsync(reinterpret_cast<char*>(c->ctrl) + offsetof(SearchCtrl, obj), &obj, 8, hipMemcpyHostToDevice, s));
+        HIPCHK(c, hipEventRecord(r1, s));
+        HIPCHK(c, hipStreamSynchronize(s));
+        float ms = 0; hipEventElapsedTime(&ms, r0, r1); refresh_ms += ms;
+        since_refresh_base = h.accepted;
+        h.obj = obj;
+      }
+    }
+    if (h.tau > 0) { st = flush(); if (st != OSSCAR_OK) return st; }
+    c->timers[6] = refresh_ms + flush_ms;
+    (void)flushes;
+  } else {
   const int BATCH = 32;
   while (launched < max_swaps && !h.done) {
     int nb = std::min(BATCH, max_swaps - launched);
@@ -529,11 +602,12 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
       h.obj = obj;
     }
   }
+  c->timers[6] = refresh_ms;
+  }
   HIPCHK(c, hipEventRecord(c->ev_b, s));
   st = read_ctrl(c, &h);
   if (st != OSSCAR_OK) return st;
   c->timers[3] = elapsed(c);
-  c->timers[6] = refresh_ms;
   c->timers[5] = samples ? upd_n_ms / samples : 0;
   c->timers[7] = samples ? upd_z_ms / samples : 0;
   if (res) { res->iters = h.iters; res->accepted = h.accepted; res->obj_initial = obj0; res->obj_final = h.obj; }
@@ -559,7 +633,7 @@ osscar_status osscar_apply_swap(osscar_ctx* c, int32_t g_out, int32_t g_in) {
   SearchCtrl h{};
   st = read_ctrl(c, &h);
   if (st != OSSCAR_OK) return st;
-  h.done = 0; h.iters = 0; h.notpd = 0;
+  h.done = 0; h.iters = 0; h.notpd = 0; h.pause = 0; h.tau = 0;
   HIPCHK(c, hipMemcpyAsync(c->ctrl, &h, sizeof h, hipMemcpyHostToDevice, c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
   TabPtrs t = ptrs(c);

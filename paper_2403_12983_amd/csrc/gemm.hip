@@ -44,9 +44,11 @@ __device__ __forceinline__ Tile8 load8(const float* __restrict__ row, int c0, in
 }
 
 template <typename OutT>
-__global__ __launch_bounds__(256) void gemm_f64acc_kernel(GemmArgs g, int vecA, int vecB) {
-  __shared__ float As[2][BK][LDT];
-  __shared__ float Bs[2][BK][LDT];
+__global__ __launch_bounds__(256) void gemm_f64acc_kernel(GemmArgs g, int vecA, int vecB, int vecC) {
+  // A and B stages; after the main loop the same memory stages the output tile (4 waves x 16 x 66 doubles)
+  __shared__ __attribute__((aligned(16))) float smem[2 * 2 * BK * LDT];
+  float (*As)[BK][LDT] = reinterpret_cast<float (*)[BK][LDT]>(smem);
+  float (*Bs)[BK][LDT] = reinterpret_cast<float (*)[BK][LDT]>(smem + 2 * BK * LDT);
 
   int tile_m, tile_n;
   if (g.lower_only) {
@@ -127,6 +129,50 @@ __global__ __launch_bounds__(256) void gemm_f64acc_kernel(GemmArgs g, int vecA, 
   // epilogue: lane holds D[4*r + lane/16][lane%16] of each 16 x 16 tile
   OutT* C = reinterpret_cast<OutT*>(g.C);
   const OutT* Cin = reinterpret_cast<const OutT*>(g.Cin);
+  const bool use_cin = (Cin != nullptr && g.beta != 0.0);
+  if (sizeof(OutT) == 4 && vecC) {
+    // float output: each wave stages 16 x 64 of its tile in LDS and writes rows as float4 (256 contiguous bytes)
+    constexpr int SLD = 66;
+    double* st = reinterpret_cast<double*>(smem) + wave * 16 * SLD;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < 4; j++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) st[(4 * r + (lane >> 4)) * SLD + j * 16 + (lane & 15)] = g.alpha * acc[i][j][r];
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < 4; k++) {
+        const int lr = (lane >> 4) + 4 * k, lc = (lane & 15) * 4;
+        const int row = m0 + wm * 64 + i * 16 + lr;
+        const int col = n0 + wn * 64 + lc;
+        if (row < g.M && col < g.N) {
+          double v[4];
+#pragma unroll
+          for (int e = 0; e < 4; e++) v[e] = st[lr * SLD + lc + e];
+          if (col + 3 < g.N) {
+            if (use_cin) {
+              const float4 ci = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(Cin) + (int64_t)row * g.ldcin + col);
+              v[0] += g.beta * ci.x; v[1] += g.beta * ci.y; v[2] += g.beta * ci.z; v[3] += g.beta * ci.w;
+            }
+#pragma unroll
+            for (int e = 0; e < 4; e++) if (row == col + e) v[e] += g.diag_add;
+            float4 o = {(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+            *reinterpret_cast<float4*>(reinterpret_cast<float*>(C) + (int64_t)row * g.ldc + col) = o;
+          } else {
+            for (int e = 0; e < 4 && col + e < g.N; e++) {
+              double x = v[e];
+              if (use_cin) x += g.beta * (double)Cin[(int64_t)row * g.ldcin + col + e];
+              if (row == col + e) x += g.diag_add;
+              C[(int64_t)row * g.ldc + col + e] = (OutT)x;
+            }
+          }
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < 4; i++)
 #pragma unroll
@@ -137,7 +183,7 @@ __global__ __launch_bounds__(256) void gemm_f64acc_kernel(GemmArgs g, int vecA, 
         int col = n0 + wn * 64 + j * 16 + (lane & 15);
         if (row < g.M && col < g.N) {
           double v = g.alpha * acc[i][j][r];
-          if (Cin != nullptr && g.beta != 0.0) v += g.beta * (double)Cin[(int64_t)row * g.ldcin + col];
+          if (use_cin) v += g.beta * (double)Cin[(int64_t)row * g.ldcin + col];
           if (row == col) v += g.diag_add;
           C[(int64_t)row * g.ldc + col] = (OutT)v;
         }
@@ -150,10 +196,12 @@ hipError_t launch_gemm_f64acc(const GemmArgs& a, hipStream_t s) {
   int blocks = a.lower_only ? tm * (tm + 1) / 2 : tm * tn;
   int vecA = (a.lda % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.A) & 15) == 0);
   int vecB = (a.ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.B) & 15) == 0);
+  int vecC = (!a.c_is_f64) && (a.ldc % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.C) & 15) == 0) &&
+             (a.Cin == nullptr || ((a.ldcin % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.Cin) & 15) == 0)));
   if (a.c_is_f64)
-    hipLaunchKernelGGL(gemm_f64acc_kernel<double>, dim3(blocks), dim3(256), 0, s, a, vecA, vecB);
+    hipLaunchKernelGGL(gemm_f64acc_kernel<double>, dim3(blocks), dim3(256), 0, s, a, vecA, vecB, 0);
   else
-    hipLaunchKernelGGL(gemm_f64acc_kernel<float>, dim3(blocks), dim3(256), 0, s, a, vecA, vecB);
+    hipLaunchKernelGGL(gemm_f64acc_kernel<float>, dim3(blocks), dim3(256), 0, s, a, vecA, vecB, vecC);
   return hipGetLastError();
 }
 

@@ -49,7 +49,8 @@ struct SearchCtrl {          // lives in device memory
   int32_t accepted;          // swaps applied
   int32_t notpd;             // a pivot block was not definite
   int32_t g_out, g_in;       // current selection (group ids), -1 if none
-  int32_t pad0, pad1;
+  int32_t pause;             // delayed-update search: the host must flush before the search can go on
+  int32_t tau;               // delayed-update search: number of pending pivots
   double obj;                // tracked objective
   double rel_tol;
   double delta;              // exact change of the current pair
@@ -90,6 +91,33 @@ hipError_t launch_refresh_scores(const TabDims& d, const TabPtrs& t, hipStream_t
 // ev (optional): three events recorded before the bulk update of N, after it, and after the update of Z.
 hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int forced_out, int forced_in, int always_accept,
                                    hipStream_t s, hipEvent_t* ev = nullptr);
+hipError_t launch_select(const TabDims& d, const TabPtrs& t, int forced_out, int forced_in, hipStream_t s);
+
+// ----------------------------------------------------------------------------------------------
+// lazy.hip : delayed-update search for q = 1
+// ----------------------------------------------------------------------------------------------
+constexpr int LAZY_TM = 128;     // capacity of the pending pivot set (two per swap)
+struct LazyPtrs {
+  int32_t* pos;     // d1: position in the pending set or -1
+  int32_t* Tidx;    // LAZY_TM pivot indices
+  float* Jsg;       // LAZY_TM: -1 for pivots that left the kept set, +1 for pivots that entered
+  float* C0T;       // LAZY_TM x d1: base columns N0[:, T_s] as rows
+  double* Minv;     // LAZY_TM x LAZY_TM: inverse of N0[T, T]
+  double* ZT;       // LAZY_TM x m: Minv * Z0[T, :]
+  float* ZT32;      // LAZY_TM x m (flush)
+  float* E; float* Cb;  // d1 x LAZY_TM panels (flush)
+  double* xg; double* xj; double* u1; double* u2;   // LAZY_TM
+  double* cg; double* cj; double* w1; double* w2;   // d1
+  double* y1; double* y2; float* y1f; float* y2f;   // m
+  double* part;     // ceil(m/256) * 5 partial sums
+  double* ls;       // 16 scalars
+};
+hipError_t launch_lazy_init(const TabDims& d, const LazyPtrs& L, SearchCtrl* ctrl, hipStream_t s);
+// ev (optional): events recorded before and after the pass over Z0, and at the end of the iteration
+hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, int always_accept, hipStream_t s,
+                                 hipEvent_t* ev = nullptr);
+hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s);
+
 hipError_t launch_scatter_rows(const float* src, int64_t lds, const int32_t* rows, int nrows, int ncols, void* dst,
                                int64_t ldd, int dst_is_bf16, hipStream_t s);
 hipError_t launch_fill_rows_zero(void* dst, int64_t ldd, int nrows_total, int ncols, int dst_is_bf16, hipStream_t s);

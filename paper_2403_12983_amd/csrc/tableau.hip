@@ -391,7 +391,7 @@ __global__ __launch_bounds__(1024) void select_kernel(TabDims d, const int32_t* 
                                                        int forced_in) {
   __shared__ double s_min1[1024], s_min2[1024], s_max1[1024], s_max2[1024];
   __shared__ int s_imin[1024], s_imax[1024];
-  if (ctrl->done) return;
+  if (ctrl->done || ctrl->pause) return;
   const int tid = threadIdx.x;
   double mn1 = INFINITY, mn2 = INFINITY, mx1 = -INFINITY, mx2 = -INFINITY;
   int imn = -1, imx = -1;
@@ -772,6 +772,11 @@ __global__ __launch_bounds__(256) void update_Z_kernel(TabDims d, float* __restr
   }
   __syncthreads();
   group_gram(Zh, q, m, gram + (int64_t)h * q * q);
+}
+
+hipError_t launch_select(const TabDims& d, const TabPtrs& t, int forced_out, int forced_in, hipStream_t s) {
+  hipLaunchKernelGGL(select_kernel, dim3(1), dim3(1024), 0, s, d, t.kept, t.score, t.ctrl, forced_out, forced_in);
+  return hipGetLastError();
 }
 
 hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int forced_out, int forced_in, int always_accept,

@@ -272,6 +272,39 @@ def test_forced_swaps_keep_the_state_exact(name):
     s.close()
 
 
+def test_delayed_update_search_equals_eager_search():
+    # groups of one row: the delayed-update search must take exactly the swaps of the eager search and leave the
+    # same state (the flush interval of 64 swaps is crossed several times, and 'pause' flushes are exercised by the
+    # small layer, where groups re-enter within one window)
+    pkg = _pkg()
+    from paper_2403_12983_amd import binding as B
+    for cfg, swaps in ((inp.scaled(inp.CONFIGS["cfg3"], p=1024, m=260, n=6000, k=512, swaps=300), 300),
+                       (inp.scaled(inp.CONFIGS["cfg1"], p=24, m=16, n=200, k=12, swaps=80, mix=0.8), 80)):
+        X, W = inp.gen_X(cfg, device=DEV), inp.gen_W(cfg, DEV)
+        s = pkg.Solver(cfg.d1, cfg.m, cfg.p, cfg.q, cfg.k, swaps, X.dtype, W.dtype, DEV)
+        s.osscar_gram(X, True, W, cfg.lam_abs if cfg.lam_abs else 0.0, cfg.lam_rel)
+        s.osscar_init_support()
+        e = s.osscar_local_search(swaps, 0.0, B.OSSCAR_SEARCH_EAGER | B.OSSCAR_SEARCH_ALWAYS_ACCEPT)
+        Pe, Be, Ve, Re = (T(s, k) for k in ("T_P", "T_B", "T_V", "T_R"))
+        reme, adde = T(s, "T_REM"), T(s, "T_ADD")
+        s.osscar_init_support()
+        l = s.osscar_local_search(swaps, 0.0, B.OSSCAR_SEARCH_ALWAYS_ACCEPT)
+        assert e["iters"] == l["iters"] == swaps
+        # identical choices while both searches see a clear winner (the two accumulate rounding differently)
+        for i in range(swaps):
+            if (e["trace_out"][i], e["trace_in"][i]) != (l["trace_out"][i], l["trace_in"][i]):
+                assert min(e["trace_gap"][i]) < 1e-4, (i, e["trace_gap"][i])
+                break
+        else:
+            assert rel(T(s, "T_P"), Pe) < 1e-5 and rel(T(s, "T_B"), Be) < 1e-5
+            assert rel(T(s, "T_V"), Ve) < 1e-5 and rel(T(s, "T_R"), Re) < 1e-5
+            fk, fc = np.isfinite(reme), np.isfinite(adde)
+            assert np.max(np.abs(T(s, "T_REM")[fk] - reme[fk]) / reme[fk]) < 1e-4
+            assert np.max(np.abs(T(s, "T_ADD")[fc] - adde[fc]) / adde[fc]) < 1e-4
+            assert abs(e["obj_final"] - l["obj_final"]) <= 1e-5 * abs(e["obj_final"])
+        s.close()
+
+
 # ------------------------------------------------------------------------------------------ set_quadratic
 def test_set_quadratic_and_brute_force_optimum_is_a_fixed_point():
     c = case("cfg1x")
