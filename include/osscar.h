@@ -125,8 +125,10 @@ osscar_status osscar_local_search(osscar_ctx* ctx, int32_t max_swaps, double rel
 /* Test hook: applies the swap (group g_out leaves, g_in enters) unconditionally (Case 3). */
 osscar_status osscar_apply_swap(osscar_ctx* ctx, int32_t g_out, int32_t g_in);
 
-/* Final weights (closed-form optimum for the final kept set, Appendix A.1): What_K = (H_KK)^-1 G_K from a
- * fresh factorisation with one step of float64-residual refinement, other rows zero.
+/* Final weights (closed-form optimum for the final kept set, Appendix A.1): What_K = (H_KK)^-1 G_K, other
+ * rows zero.  The maintained weights are refined by float64-residual correction steps B += P (G_K - H_KK B)
+ * until the correction is below float32 resolution; if the maintained inverse P has drifted too far for
+ * that, H_KK is inverted afresh.
  * What_dev: dev, row-major d1 x m, leading dimension ldw_hat, dtype out_dtype.  support_host (may be
  * NULL): the k kept groups, ascending.  *obj_host (may be NULL): c0 - Tr(G_K^T What_K). */
 osscar_status osscar_backsolve(osscar_ctx* ctx, void* What_dev, int64_t ldw_hat, int32_t out_dtype,

@@ -19,6 +19,7 @@ constexpr int64_t XT_ROWS = 4096;   // calibration rows per sub-step of the gene
 constexpr int EV_SAMPLES = 64;
 
 size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+size_t gram_tile_entries(int64_t d1) { size_t t = (size_t)(d1 + 127) / 128; return 8 * (t * t / 2 + t + 8); }
 
 struct Carve {
   char* base; size_t off;
@@ -137,7 +138,8 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
     L.part = cv.take<double>(((m + 255) / 256) * 5); L.ls = cv.take<double>(16);
   }
   // scratch: the larger of the Gram phase and the init / refresh / backsolve phase
-  size_t gram_phase = align_up((size_t)d1 * d1 * 8) + align_up((size_t)d1 * m * 4) + align_up((size_t)d1 * XT_ROWS * 4);
+  size_t gram_phase = align_up((size_t)d1 * d1 * 8) + align_up((size_t)d1 * m * 4) + align_up((size_t)d1 * XT_ROWS * 4) +
+                      align_up(gram_tile_entries(d1) * 8);
   size_t init_phase = 4 * align_up((size_t)kr * kr * 4) + 3 * align_up((size_t)kr * cr * 4) + align_up((size_t)cr * cr * 4) +
                       4 * align_up((size_t)kr * m * 4) + align_up((size_t)cr * m * 4) + 3 * align_up((size_t)kr * 64 * 4) + 4096;
   size_t scratch_bytes = std::max(gram_phase, init_phase);
@@ -378,6 +380,8 @@ osscar_status osscar_gram(osscar_ctx* c, const void* Xc, int64_t n_c, int64_t ld
   double* H64 = cv.take<double>((int64_t)d1 * d1);
   float* Wf = cv.take<float>((int64_t)d1 * m);
   float* Xt = cv.take<float>((int64_t)d1 * XT_ROWS);
+  const size_t tile_entries = gram_tile_entries(d1);
+  int2* tile_buf = cv.take<int2>(tile_entries);
   if (c->phase != osscar_ctx::ACCUM) {   // first chunk of a layer
     hipLaunchKernelGGL(fill_f64_kernel, dim3(grid_for((int64_t)d1 * d1)), dim3(256), 0, s, H64, (int64_t)d1 * d1, 0.0);
     c->phase = osscar_ctx::ACCUM;
@@ -388,7 +392,7 @@ osscar_status osscar_gram(osscar_ctx* c, const void* Xc, int64_t n_c, int64_t ld
     const bool bf16 = c->desc.x_dtype == OSSCAR_BF16;
     const bool fast = bf16 && (d1 % 8 == 0) && (ldx % 8 == 0) && ((reinterpret_cast<uintptr_t>(Xc) & 15) == 0);
     if (fast) {
-      HIPCHK(c, launch_gram_bf16(Xc, n_c, ldx, d1, H64, s));
+      HIPCHK(c, launch_gram_bf16(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, s));
     } else {
       const size_t esz = bf16 ? 2 : 4;
       for (int64_t r0 = 0; r0 < n_c; r0 += XT_ROWS) {
@@ -659,8 +663,35 @@ osscar_status osscar_backsolve(osscar_ctx* c, void* What, int64_t ldw_hat, int32
   if (st != OSSCAR_OK) return st;
   Carve cv(c->scratch);
   InvBufs b = carve_inv(c, cv);
-  st = inverse_and_weights(c, b);
-  if (st != OSSCAR_OK) return st;
+  // Refine the maintained weights instead of refactorising: B <- B + P (G_K - H_KK B) with the maintained inverse P
+  // and a float64-accumulated residual.  One step shrinks the error by |I - P H_KK| (about 1e-3 after thousands of
+  // swaps); a second step is taken if the first correction was not tiny, and a fresh inverse if it was large.
+  {
+    const int kr = c->kr, m = c->m;
+    HIPCHK(c, launch_gather(c->H, c->d1, c->rowsK, kr, c->rowsK, kr, b.HKK, kr, s));
+    HIPCHK(c, launch_gather(c->G, m, c->rowsK, kr, nullptr, m, b.GK, m, s));
+    hipLaunchKernelGGL(gather_sym_kernel, dim3(grid_for((int64_t)kr * kr)), dim3(256), 0, s, c->N, (int64_t)c->d1, c->rowsK, kr,
+                       c->rowsK, kr, b.P, -1.f);
+    HIPCHK(c, launch_gather(c->Z, m, c->rowsK, kr, nullptr, m, b.B, m, s));
+    bool ok = false;
+    for (int step = 0; step < 3 && !ok; step++) {
+      HIPCHK(c, gemm(s, kr, m, kr, b.HKK, kr, b.B, m, b.GK, m, b.T4, m, -1.0, 1.0));      // residual
+      HIPCHK(c, gemm(s, kr, m, kr, b.P, kr, b.T4, m, nullptr, 0, b.T3, m, 1.0, 0.0));      // correction
+      HIPCHK(c, launch_dot64(b.T3, b.T3, (int64_t)kr * m, c->scal + 9, c->partial, s));
+      HIPCHK(c, launch_dot64(b.B, b.B, (int64_t)kr * m, c->scal + 10, c->partial + 1024, s));
+      hipLaunchKernelGGL(add_inplace_kernel, dim3(grid_for((int64_t)kr * m)), dim3(256), 0, s, b.B, b.T3, (int64_t)kr * m);
+      double nn[2] = {0, 0};
+      HIPCHK(c, hipMemcpyAsync(nn, c->scal + 9, 16, hipMemcpyDeviceToHost, s));
+      HIPCHK(c, hipStreamSynchronize(s));
+      const double ratio = std::sqrt(nn[0] / std::max(nn[1], 1e-300));
+      if (!(ratio < 1e-2)) break;             // the maintained inverse is not good enough: refactorise
+      if (ratio < 1e-5) ok = true;            // the next correction would be below float32 resolution
+    }
+    if (!ok) {
+      st = inverse_and_weights(c, b);
+      if (st != OSSCAR_OK) return st;
+    }
+  }
   HIPCHK(c, launch_fill_rows_zero(What, ldw_hat, c->d1, c->m, out_dtype == OSSCAR_BF16, s));
   HIPCHK(c, launch_scatter_rows(b.B, c->m, c->rowsK, c->kr, c->m, What, ldw_hat, out_dtype == OSSCAR_BF16, s));
   double obj = 0;

@@ -44,7 +44,7 @@ __device__ __forceinline__ Tile8 load8(const float* __restrict__ row, int c0, in
 }
 
 template <typename OutT>
-__global__ __launch_bounds__(256) void gemm_f64acc_kernel(GemmArgs g, int vecA, int vecB, int vecC) {
+__global__ __launch_bounds__(256, 2) void gemm_f64acc_kernel(GemmArgs g, int vecA, int vecB, int vecC) {
   // A and B stages; after the main loop the same memory stages the output tile (4 waves x 16 x 66 doubles)
   __shared__ __attribute__((aligned(16))) float smem[2 * 2 * BK * LDT];
   float (*As)[BK][LDT] = reinterpret_cast<float (*)[BK][LDT]>(smem);
