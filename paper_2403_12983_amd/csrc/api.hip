@@ -130,12 +130,13 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
   if (q == 1) {
     const int64_t TM = LAZY_TM;
     L.pos = cv.take<int32_t>(d1); L.Tidx = cv.take<int32_t>(TM); L.Jsg = cv.take<float>(TM);
-    L.C0T = cv.take<float>(TM * d1); L.Minv = cv.take<double>(TM * TM); L.ZT = cv.take<double>(TM * m);
-    L.ZT32 = cv.take<float>(TM * m); L.E = cv.take<float>(d1 * TM); L.Cb = cv.take<float>(d1 * TM);
+    L.C0R = cv.take<float>(d1 * TM); L.Minv = cv.take<double>(TM * TM); L.Minv32 = cv.take<float>(TM * TM);
+    L.ZT = cv.take<double>(TM * m); L.ZT32 = cv.take<float>(TM * m); L.E = cv.take<float>(d1 * TM);
     L.xg = cv.take<double>(TM); L.xj = cv.take<double>(TM); L.u1 = cv.take<double>(TM); L.u2 = cv.take<double>(TM);
     L.cg = cv.take<double>(d1); L.cj = cv.take<double>(d1); L.w1 = cv.take<double>(d1); L.w2 = cv.take<double>(d1);
     L.y1 = cv.take<double>(m); L.y2 = cv.take<double>(m); L.y1f = cv.take<float>(m); L.y2f = cv.take<float>(m);
-    L.part = cv.take<double>(((m + 255) / 256) * 5); L.ls = cv.take<double>(16);
+    L.part = cv.take<double>(((m + 63) / 64) * 5); L.ls = cv.take<double>(16);
+    L.sel = cv.take<SelRec>((d1 + 31) / 32); L.counter = cv.take<int32_t>(4);
   }
   // scratch: the larger of the Gram phase and the init / refresh / backsolve phase
   size_t gram_phase = align_up((size_t)d1 * d1 * 8) + align_up((size_t)d1 * m * 4) + align_up((size_t)d1 * XT_ROWS * 4) +
@@ -517,7 +518,7 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
     // delayed-update search: the tableau in HBM is only touched by a flush every FLUSH iterations
     const LazyPtrs& L = c->lazy;
     const int FLUSH = LAZY_TM / 2, BATCH = 32;
-    HIPCHK(c, launch_lazy_init(d, L, c->ctrl, s));
+    HIPCHK(c, launch_lazy_init(d, t, L, s));
     int since_flush = 0;
     double flush_ms = 0; int flushes = 0;
     auto flush = [&]() -> osscar_status {

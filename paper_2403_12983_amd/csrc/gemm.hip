@@ -190,6 +190,140 @@ __global__ __launch_bounds__(256, 2) void gemm_f64acc_kernel(GemmArgs g, int vec
       }
 }
 
+// float32-accumulating variant (v_mfma_f32_32x32x2_f32, twice the rate of the float64 matrix path) for products whose
+// result is added to float32 data anyway: the rank-64 sweeps of the inverse (refined afterwards) and the flushes of
+// the delayed-update search.  Same tiling; each wave owns 64 x 64 as 2 x 2 tiles of 32 x 32.  float output only.
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(256, 2) void gemm_f32acc_kernel(GemmArgs g, int vecA, int vecB, int vecC) {
+  __shared__ __attribute__((aligned(16))) float smem[2 * 2 * BK * LDT];
+  float (*As)[BK][LDT] = reinterpret_cast<float (*)[BK][LDT]>(smem);
+  float (*Bs)[BK][LDT] = reinterpret_cast<float (*)[BK][LDT]>(smem + 2 * BK * LDT);
+  int tile_m, tile_n;
+  if (g.lower_only) {
+    int t = blockIdx.x;
+    int tm = (int)((sqrtf(8.f * (float)t + 1.f) - 1.f) * 0.5f);
+    while ((tm + 1) * (tm + 2) / 2 <= t) tm++;
+    while (tm * (tm + 1) / 2 > t) tm--;
+    tile_m = tm; tile_n = t - tm * (tm + 1) / 2;
+  } else {
+    int tiles_n = (g.N + BN - 1) / BN;
+    tile_m = blockIdx.x / tiles_n; tile_n = blockIdx.x % tiles_n;
+  }
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int a_row = tid >> 1, a_k = (tid & 1) * 8;
+  const int bt_row = tid >> 1, bt_k = (tid & 1) * 8;
+  const int b_k = tid >> 4, b_n = (tid & 15) * 8;
+  const float* a_ptr = (m0 + a_row < g.M) ? g.A + (int64_t)(m0 + a_row) * g.lda : nullptr;
+  const float* bt_ptr = (g.trans_b && n0 + bt_row < g.N) ? g.B + (int64_t)(n0 + bt_row) * g.ldb : nullptr;
+  f16v acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int j = 0; j < 2; j++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+  const int ktiles = (g.K + BK - 1) / BK;
+  Tile8 ra, rb;
+  auto gload = [&](int kt) {
+    int k0 = kt * BK;
+    ra = load8(a_ptr, k0 + a_k, g.K, vecA);
+    if (g.trans_b) {
+      rb = load8(bt_ptr, k0 + bt_k, g.K, vecB);
+    } else {
+      const float* bp = (k0 + b_k < g.K) ? g.B + (int64_t)(k0 + b_k) * g.ldb : nullptr;
+      rb = load8(bp, n0 + b_n, g.N, vecB);
+    }
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 8; i++) As[buf][a_k + i][a_row] = ra.v[i];
+    if (g.trans_b) {
+#pragma unroll
+      for (int i = 0; i < 8; i++) Bs[buf][bt_k + i][bt_row] = rb.v[i];
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; i++) Bs[buf][b_k][b_n + i] = rb.v[i];
+    }
+  };
+  if (ktiles > 0) { gload(0); sstore(0); }
+  __syncthreads();
+  for (int kt = 0; kt < ktiles; kt++) {
+    int buf = kt & 1;
+    if (kt + 1 < ktiles) gload(kt + 1);
+#pragma unroll
+    for (int kk = 0; kk < BK / 2; kk++) {
+      const int k = kk * 2 + (lane >> 5);
+      float a[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; i++) a[i] = As[buf][k][wm * 64 + i * 32 + (lane & 31)];
+#pragma unroll
+      for (int j = 0; j < 2; j++) b[j] = Bs[buf][k][wn * 64 + j * 32 + (lane & 31)];
+#pragma unroll
+      for (int i = 0; i < 2; i++)
+#pragma unroll
+        for (int j = 0; j < 2; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < ktiles) sstore(buf ^ 1);
+    __syncthreads();
+  }
+  // epilogue: lane holds rows (r/4)*8 + (lane/32)*4 + r%4, column lane%32 of each 32 x 32 tile; staged per 32 rows
+  float* C = reinterpret_cast<float*>(g.C);
+  const float* Cin = g.Cin;
+  const bool use_cin = (Cin != nullptr && g.beta != 0.0);
+  const float alpha = (float)g.alpha, beta = (float)g.beta, dadd = (float)g.diag_add;
+  constexpr int SLD = 68;
+  float* st = smem + wave * 32 * SLD;          // 4 waves x 32 x 68 floats = 34816 bytes > smem: stage 16 rows at a time
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+#pragma unroll
+    for (int half = 0; half < 2; half++) {       // rows (r/4)*8 + ... with r/4 in {2*half, 2*half+1}
+      __syncthreads();
+      float* sth = smem + wave * 16 * SLD;
+#pragma unroll
+      for (int j = 0; j < 2; j++)
+#pragma unroll
+        for (int rq = 0; rq < 2; rq++)
+#pragma unroll
+          for (int r3 = 0; r3 < 4; r3++) {
+            const int r = (2 * half + rq) * 4 + r3;
+            sth[(rq * 8 + (lane >> 5) * 4 + r3) * SLD + j * 32 + (lane & 31)] = alpha * acc[i][j][r];
+          }
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < 4; k++) {
+        const int lr = (lane >> 4) + 4 * k, lc = (lane & 15) * 4;     // 16 staged rows x 64 columns
+        const int row = m0 + wm * 64 + i * 32 + half * 16 + lr;
+        const int col = n0 + wn * 64 + lc;
+        if (row < g.M && col < g.N) {
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; e++) v[e] = sth[lr * SLD + lc + e];
+          if (vecC && col + 3 < g.N) {
+            if (use_cin) {
+              const float4 ci = *reinterpret_cast<const float4*>(Cin + (int64_t)row * g.ldcin + col);
+              v[0] += beta * ci.x; v[1] += beta * ci.y; v[2] += beta * ci.z; v[3] += beta * ci.w;
+            }
+#pragma unroll
+            for (int e = 0; e < 4; e++) if (row == col + e) v[e] += dadd;
+            *reinterpret_cast<float4*>(C + (int64_t)row * g.ldc + col) = float4{v[0], v[1], v[2], v[3]};
+          } else {
+            for (int e = 0; e < 4 && col + e < g.N; e++) {
+              float x = v[e];
+              if (use_cin) x += beta * Cin[(int64_t)row * g.ldcin + col + e];
+              if (row == col + e) x += dadd;
+              C[(int64_t)row * g.ldc + col + e] = x;
+            }
+          }
+        }
+      }
+    }
+  }
+  (void)st;
+}
+
 hipError_t launch_gemm_f64acc(const GemmArgs& a, hipStream_t s) {
   if (a.M <= 0 || a.N <= 0) return hipSuccess;
   int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
@@ -198,7 +332,9 @@ hipError_t launch_gemm_f64acc(const GemmArgs& a, hipStream_t s) {
   int vecB = (a.ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.B) & 15) == 0);
   int vecC = (!a.c_is_f64) && (a.ldc % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.C) & 15) == 0) &&
              (a.Cin == nullptr || ((a.ldcin % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.Cin) & 15) == 0)));
-  if (a.c_is_f64)
+  if (a.acc_f32 && !a.c_is_f64)
+    hipLaunchKernelGGL(gemm_f32acc_kernel, dim3(blocks), dim3(256), 0, s, a, vecA, vecB, vecC);
+  else if (a.c_is_f64)
     hipLaunchKernelGGL(gemm_f64acc_kernel<double>, dim3(blocks), dim3(256), 0, s, a, vecA, vecB, 0);
   else
     hipLaunchKernelGGL(gemm_f64acc_kernel<float>, dim3(blocks), dim3(256), 0, s, a, vecA, vecB, vecC);

@@ -20,6 +20,7 @@ struct GemmArgs {
   int c_is_f64;                  // output (and Cin) element type: 0 float, 1 double
   int lower_only;                // 1: compute only tiles that touch the lower triangle (row >= col)
   int trans_b;                   // 1: B is given as N x K row-major (C = alpha * A * B^T + ...)
+  int acc_f32;                   // 1: accumulate in float32 (v_mfma_f32_32x32x2_f32), float output only
 };
 hipError_t launch_gemm_f64acc(const GemmArgs& a, hipStream_t s);
 
@@ -99,22 +100,26 @@ hipError_t launch_select(const TabDims& d, const TabPtrs& t, int forced_out, int
 // lazy.hip : delayed-update search for q = 1
 // ----------------------------------------------------------------------------------------------
 constexpr int LAZY_TM = 128;     // capacity of the pending pivot set (two per swap)
+struct SelRec { double mn1, mn2, mx1, mx2; int32_t imn, imx; };   // best / second-best scores of a block of rows
 struct LazyPtrs {
   int32_t* pos;     // d1: position in the pending set or -1
   int32_t* Tidx;    // LAZY_TM pivot indices
   float* Jsg;       // LAZY_TM: -1 for pivots that left the kept set, +1 for pivots that entered
-  float* C0T;       // LAZY_TM x d1: base columns N0[:, T_s] as rows
+  float* C0R;       // d1 x LAZY_TM row-major: base columns N0[:, T_s]
   double* Minv;     // LAZY_TM x LAZY_TM: inverse of N0[T, T]
+  float* Minv32;    // float copy for the flush
   double* ZT;       // LAZY_TM x m: Minv * Z0[T, :]
   float* ZT32;      // LAZY_TM x m (flush)
-  float* E; float* Cb;  // d1 x LAZY_TM panels (flush)
+  float* E;         // d1 x LAZY_TM: C0 * Minv (flush)
   double* xg; double* xj; double* u1; double* u2;   // LAZY_TM
   double* cg; double* cj; double* w1; double* w2;   // d1
   double* y1; double* y2; float* y1f; float* y2f;   // m
-  double* part;     // ceil(m/256) * 5 partial sums
+  double* part;     // ceil(m/64) * 5 partial sums
   double* ls;       // 16 scalars
+  SelRec* sel;      // ceil(d1/32) per-block score records
+  int32_t* counter; // workgroup counter of the update kernel
 };
-hipError_t launch_lazy_init(const TabDims& d, const LazyPtrs& L, SearchCtrl* ctrl, hipStream_t s);
+hipError_t launch_lazy_init(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s);
 // ev (optional): events recorded before and after the pass over Z0, and at the end of the iteration
 hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, int always_accept, hipStream_t s,
                                  hipEvent_t* ev = nullptr);

@@ -10,8 +10,14 @@
 // so one iteration needs only two columns of N_cur and two rows of Z_cur (O(tau (d1 + m))), the diagonal
 // and the squared row norms of Z_cur for the scores of eq. (impact) -- both updated incrementally, the
 // norms through one read-only pass over Z0 (w = Z0 [y1 y2]) -- and a bordering update of M^-1.  Every
-// FLUSH iterations the pending rank-tau correction is applied to N0 and Z0 as two matrix products on the
+// LAZY_TM/2 iterations the pending rank-tau correction is applied to N0 and Z0 by matrix products on the
 // matrix cores.  The sequence of swaps is exactly that of the eager search (Proposition 4.1, Cases 1-3).
+//
+// Four launches per iteration:
+//   prep    (1 workgroup)  : argmin / argmax from per-block partial records; x = M^-1 N0[T, {g, j}]; pivots
+//   vectors (rows | cols)  : current columns g, j of N; current rows g, j of Z scaled to y1, y2; partial sums
+//   gemv    (rows)         : exact change of the objective and the acceptance test; w = Z0 [y1 y2]; u = ZT [y1 y2]
+//   update  (rows|cols|M)  : norms, diagonal, scores and their partial records; C0 append; ZT and M^-1 update
 #include "internal.h"
 
 namespace osscar {
@@ -25,133 +31,227 @@ __device__ __forceinline__ double wsum(double v) {
 }
 __device__ __forceinline__ bool idle(const SearchCtrl* c) { return c->done || c->pause; }
 
-// x_g = M^-1 N0[T, g], x_j = M^-1 N0[T, j]; pauses the search if g or j is already in T.
-__global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float* __restrict__ N0, int d1, SearchCtrl* ctrl) {
-  __shared__ double bg[LAZY_TM], bj[LAZY_TM];
-  if (idle(ctrl)) return;
-  const int g = ctrl->g_out, j = ctrl->g_in, tau = ctrl->tau, tid = threadIdx.x;
-  if (L.pos[g] >= 0 || L.pos[j] >= 0 || tau + 2 > LAZY_TM) {
-    if (tid == 0) ctrl->pause = 1;
-    return;
+constexpr int ROWS_PER_BLOCK = 32;   // row kernels: 8 lanes per row, 256 threads
+constexpr int COLS_PER_BLOCK = 64;   // column kernels: 64 columns x 4 slices of the pending set
+
+// ls[] slots
+enum { LS_DG = 0, LS_NJG = 1, LS_M1 = 2, LS_DJ = 3, LS_Y11 = 4, LS_Y22 = 5, LS_Y12 = 6, LS_OBJ = 8 };
+
+// merge of two (best, second, index) records; lowest index wins ties
+__device__ __forceinline__ void merge_min(double& a1, double& a2, int& ia, double b1, double b2, int ib) {
+  const bool takeb = (ib >= 0) && (ia < 0 || b1 < a1 || (b1 == a1 && ib < ia));
+  const double n1 = takeb ? b1 : a1, other = takeb ? a1 : b1;
+  a2 = fmin(fmin(a2, b2), other); a1 = n1; ia = takeb ? ib : ia;
+}
+__device__ __forceinline__ void merge_max(double& a1, double& a2, int& ia, double b1, double b2, int ib) {
+  const bool takeb = (ib >= 0) && (ia < 0 || b1 > a1 || (b1 == a1 && ib < ia));
+  const double n1 = takeb ? b1 : a1, other = takeb ? a1 : b1;
+  a2 = fmax(fmax(a2, b2), other); a1 = n1; ia = takeb ? ib : ia;
+}
+
+// per-block record of the scores of rows [32 b, 32 b + 32): used after a flush; the update kernel writes the same records
+__global__ __launch_bounds__(64) void lazy_partials_kernel(LazyPtrs L, int p, const int32_t* __restrict__ kept,
+                                                            const double* __restrict__ score) {
+  const int h = blockIdx.x * ROWS_PER_BLOCK + threadIdx.x;
+  double mn1 = INFINITY, mn2 = INFINITY, mx1 = -INFINITY, mx2 = -INFINITY;
+  int imn = -1, imx = -1;
+  if (threadIdx.x < ROWS_PER_BLOCK && h < p) {
+    if (kept[h]) { mn1 = score[h]; imn = h; } else { mx1 = score[h]; imx = h; }
   }
-  for (int s = tid; s < tau; s += 256) {
-    int t = L.Tidx[s];
-    bg[s] = (double)nsym1(N0, d1, t, g);
-    bj[s] = (double)nsym1(N0, d1, t, j);
+  for (int o = 16; o > 0; o >>= 1) {
+    double b1 = __shfl_down(mn1, o, 64), b2 = __shfl_down(mn2, o, 64); int ib = __shfl_down(imn, o, 64);
+    merge_min(mn1, mn2, imn, b1, b2, ib);
+    b1 = __shfl_down(mx1, o, 64); b2 = __shfl_down(mx2, o, 64); ib = __shfl_down(imx, o, 64);
+    merge_max(mx1, mx2, imx, b1, b2, ib);
+  }
+  if (threadIdx.x == 0) {
+    SelRec r; r.mn1 = mn1; r.mn2 = mn2; r.mx1 = mx1; r.mx2 = mx2; r.imn = imn; r.imx = imx;
+    L.sel[blockIdx.x] = r;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------- prep
+__global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float* __restrict__ N0, int d1, int nrec,
+                                                         SearchCtrl* ctrl) {
+  __shared__ double s_mn1[256], s_mn2[256], s_mx1[256], s_mx2[256];
+  __shared__ int s_imn[256], s_imx[256];
+  __shared__ double bg[LAZY_TM], bj[LAZY_TM], red[3][4];
+  if (idle(ctrl)) return;
+  const int tid = threadIdx.x;
+  // argmin of the removal costs / argmax of the addition gains from the per-block records (fixed order)
+  double mn1 = INFINITY, mn2 = INFINITY, mx1 = -INFINITY, mx2 = -INFINITY;
+  int imn = -1, imx = -1;
+  for (int r = tid; r < nrec; r += 256) {
+    const SelRec c = L.sel[r];
+    merge_min(mn1, mn2, imn, c.mn1, c.mn2, c.imn);
+    merge_max(mx1, mx2, imx, c.mx1, c.mx2, c.imx);
+  }
+  s_mn1[tid] = mn1; s_mn2[tid] = mn2; s_imn[tid] = imn; s_mx1[tid] = mx1; s_mx2[tid] = mx2; s_imx[tid] = imx;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (tid < o) {
+      merge_min(s_mn1[tid], s_mn2[tid], s_imn[tid], s_mn1[tid + o], s_mn2[tid + o], s_imn[tid + o]);
+      merge_max(s_mx1[tid], s_mx2[tid], s_imx[tid], s_mx1[tid + o], s_mx2[tid + o], s_imx[tid + o]);
+    }
+    __syncthreads();
+  }
+  const int g = s_imn[0], j = s_imx[0], tau = ctrl->tau;
+  if (g < 0 || j < 0) { if (tid == 0) { ctrl->done = 1; ctrl->g_out = -1; ctrl->g_in = -1; } return; }
+  if (L.pos[g] >= 0 || L.pos[j] >= 0 || tau + 2 > LAZY_TM) { if (tid == 0) ctrl->pause = 1; return; }
+  // b = N0[T, {g, j}] (these are rows g, j of C0), x = M^-1 b, zero beyond tau
+  for (int s = tid; s < LAZY_TM; s += 256) {
+    bg[s] = (s < tau) ? (double)L.C0R[(int64_t)g * LAZY_TM + s] : 0.0;
+    bj[s] = (s < tau) ? (double)L.C0R[(int64_t)j * LAZY_TM + s] : 0.0;
   }
   __syncthreads();
-  for (int r = tid; r < tau; r += 256) {
+  double pgg = 0, pjg = 0, pjj = 0;
+  for (int r = tid; r < LAZY_TM; r += 256) {
     double a = 0, b = 0;
-    for (int s = 0; s < tau; s++) { double mv = L.Minv[r * LAZY_TM + s]; a += mv * bg[s]; b += mv * bj[s]; }
+    if (r < tau)
+      for (int s = 0; s < tau; s++) { const double mv = L.Minv[r * LAZY_TM + s]; a += mv * bg[s]; b += mv * bj[s]; }
     L.xg[r] = a; L.xj[r] = b;
+    pgg += bg[r] * a; pjg += bj[r] * a; pjj += bj[r] * b;
+  }
+  pgg = wsum(pgg); pjg = wsum(pjg); pjj = wsum(pjj);
+  if ((tid & 63) == 0) { red[0][tid >> 6] = pgg; red[1][tid >> 6] = pjg; red[2][tid >> 6] = pjj; }
+  __syncthreads();
+  if (tid == 0) {
+    const double ngg = (double)nsym1(N0, d1, g, g) - (red[0][0] + red[0][1] + red[0][2] + red[0][3]);
+    const double njg = (double)nsym1(N0, d1, j, g) - (red[1][0] + red[1][1] + red[1][2] + red[1][3]);
+    const double njj = (double)nsym1(N0, d1, j, j) - (red[2][0] + red[2][1] + red[2][2] + red[2][3]);
+    const bool bad1 = !(ngg < 0.0);                         // kept pivot: N_gg = -P_gg
+    const double Dg = 1.0 / (bad1 ? -1.0 : ngg);
+    const double M1 = Dg * njg;
+    const double njjp = njj - njg * M1;                     // entering pivot after the first sweep: a Schur complement
+    const bool bad2 = !(njjp > 0.0);
+    const double Dj = 1.0 / (bad2 ? 1.0 : njjp);
+    L.ls[LS_DG] = Dg; L.ls[LS_NJG] = njg; L.ls[LS_M1] = M1; L.ls[LS_DJ] = Dj; L.ls[LS_OBJ] = ctrl->obj;
+    if (bad1 || bad2) ctrl->notpd = 1;
+    ctrl->g_out = g; ctrl->g_in = j;
+    const double m1 = s_mn1[0], m2 = s_mn2[0], x1 = s_mx1[0], x2 = s_mx2[0];
+    ctrl->gap_rem = isfinite(m2) ? fabs(m2 - m1) / fmax(fabs(m1), 1e-300) : INFINITY;
+    ctrl->gap_add = isfinite(x2) ? fabs(x1 - x2) / fmax(fabs(x1), 1e-300) : INFINITY;
   }
 }
 
-// current columns g and j of N
-__global__ __launch_bounds__(256) void lazy_columns_kernel(LazyPtrs L, const float* __restrict__ N0, int d1,
-                                                            const SearchCtrl* __restrict__ ctrl) {
+// ---------------------------------------------------------------------------------------------- vectors
+// 8 lanes of a row: sum_s C0R[row][s] * (xa[s], xb[s]) over the LAZY_TM columns (x is zero beyond tau)
+__device__ __forceinline__ void row_dots(const float* __restrict__ crow, const double* __restrict__ xa,
+                                         const double* __restrict__ xb, int l8, double& a, double& b) {
+  a = 0; b = 0;
+#pragma unroll
+  for (int t = 0; t < LAZY_TM / 32; t++) {
+    const int s = (l8 + 8 * t) * 4;
+    const float4 c = *reinterpret_cast<const float4*>(crow + s);
+    a += (double)c.x * xa[s] + (double)c.y * xa[s + 1] + (double)c.z * xa[s + 2] + (double)c.w * xa[s + 3];
+    b += (double)c.x * xb[s] + (double)c.y * xb[s + 1] + (double)c.z * xb[s + 2] + (double)c.w * xb[s + 3];
+  }
+  a += __shfl_xor(a, 1, 64); b += __shfl_xor(b, 1, 64);
+  a += __shfl_xor(a, 2, 64); b += __shfl_xor(b, 2, 64);
+  a += __shfl_xor(a, 4, 64); b += __shfl_xor(b, 4, 64);
+}
+
+__global__ __launch_bounds__(256) void lazy_vectors_kernel(LazyPtrs L, const float* __restrict__ N0, const float* __restrict__ Z0,
+                                                            int d1, int m, int row_blocks, const SearchCtrl* __restrict__ ctrl) {
+  __shared__ double sa[LAZY_TM], sb[LAZY_TM];
+  __shared__ double zred[2][4][COLS_PER_BLOCK];
   if (idle(ctrl)) return;
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= d1) return;
-  const int g = ctrl->g_out, j = ctrl->g_in, tau = ctrl->tau;
-  const int ps = L.pos[i];
-  if (ps >= 0) {
-    double sg = (double)L.Jsg[ps];
-    L.cg[i] = sg * L.xg[ps];
-    L.cj[i] = sg * L.xj[ps];
+  const int tid = threadIdx.x, g = ctrl->g_out, j = ctrl->g_in, tau = ctrl->tau;
+  if ((int)blockIdx.x < row_blocks) {
+    // current columns g and j of N
+    for (int s = tid; s < LAZY_TM; s += 256) { sa[s] = L.xg[s]; sb[s] = L.xj[s]; }
+    __syncthreads();
+    const int row = blockIdx.x * ROWS_PER_BLOCK + (tid >> 3), l8 = tid & 7;
+    if (row >= d1) return;
+    const int ps = L.pos[row];
+    double a, b;
+    row_dots(L.C0R + (int64_t)row * LAZY_TM, sa, sb, l8, a, b);
+    if (l8 == 0) {
+      if (ps >= 0) {
+        const double sg = (double)L.Jsg[ps];
+        L.cg[row] = sg * sa[ps]; L.cj[row] = sg * sb[ps];
+      } else {
+        L.cg[row] = (double)nsym1(N0, d1, row, g) - a;
+        L.cj[row] = (double)nsym1(N0, d1, row, j) - b;
+      }
+    }
     return;
   }
-  double a = 0, b = 0;
-  for (int s = 0; s < tau; s++) {
-    double c = (double)L.C0T[(int64_t)s * d1 + i];
-    a += c * L.xg[s]; b += c * L.xj[s];
+  // current rows g and j of Z, scaled: y1 = Dg z_g, y2 = Dj (z_j - n_jg y1)
+  const int cb = blockIdx.x - row_blocks;
+  const int slice = tid >> 6, lc = tid & 63, col = cb * COLS_PER_BLOCK + lc;
+  for (int s = tid; s < LAZY_TM; s += 256) {
+    sa[s] = (s < tau) ? (double)L.C0R[(int64_t)g * LAZY_TM + s] : 0.0;
+    sb[s] = (s < tau) ? (double)L.C0R[(int64_t)j * LAZY_TM + s] : 0.0;
   }
-  L.cg[i] = (double)nsym1(N0, d1, i, g) - a;
-  L.cj[i] = (double)nsym1(N0, d1, i, j) - b;
-}
-
-// current rows g and j of Z, the scaled rows y1 = Dg z_g, y2 = Dj' (z_j - n_jg y1), and partial sums
-__global__ __launch_bounds__(256) void lazy_zrows_kernel(LazyPtrs L, const float* __restrict__ Z0, int d1, int m,
-                                                          SearchCtrl* ctrl) {
-  __shared__ double red[5][4];
-  if (idle(ctrl)) return;
-  const int g = ctrl->g_out, j = ctrl->g_in, tau = ctrl->tau;
-  const double ngg = L.cg[g], njg = L.cg[j];
-  const bool bad1 = !(ngg < 0.0);
-  const double Dg = 1.0 / (bad1 ? -1.0 : ngg);
-  const double M1 = Dg * njg;
-  const double njjp = L.cj[j] - njg * M1;
-  const bool bad2 = !(njjp > 0.0);
-  const double Dj = 1.0 / (bad2 ? 1.0 : njjp);
-  const int col = blockIdx.x * 256 + threadIdx.x;
+  __syncthreads();
+  double pg = 0, pj = 0;
+  if (col < m)
+    for (int s = slice; s < tau; s += 4) { const double zt = L.ZT[(int64_t)s * m + col]; pg += sa[s] * zt; pj += sb[s] * zt; }
+  zred[0][slice][lc] = pg; zred[1][slice][lc] = pj;
+  __syncthreads();
+  if (slice != 0) return;
   double v[5] = {0, 0, 0, 0, 0};
   if (col < m) {
-    double zg = (double)Z0[(int64_t)g * m + col], zj = (double)Z0[(int64_t)j * m + col];
-    for (int s = 0; s < tau; s++) {
-      double zt = L.ZT[(int64_t)s * m + col];
-      zg -= (double)L.C0T[(int64_t)s * d1 + g] * zt;
-      zj -= (double)L.C0T[(int64_t)s * d1 + j] * zt;
-    }
-    double y1 = Dg * zg, zjp = zj - njg * y1, y2 = Dj * zjp;
+    const double Dg = L.ls[LS_DG], njg = L.ls[LS_NJG], Dj = L.ls[LS_DJ];
+    const double zg = (double)Z0[(int64_t)g * m + col] - (zred[0][0][lc] + zred[0][1][lc] + zred[0][2][lc] + zred[0][3][lc]);
+    const double zj = (double)Z0[(int64_t)j * m + col] - (zred[1][0][lc] + zred[1][1][lc] + zred[1][2][lc] + zred[1][3][lc]);
+    const double y1 = Dg * zg, zjp = zj - njg * y1, y2 = Dj * zjp;
     L.y1[col] = y1; L.y2[col] = y2; L.y1f[col] = (float)y1; L.y2f[col] = (float)y2;
     v[0] = zg * y1; v[1] = zjp * y2; v[2] = y1 * y1; v[3] = y2 * y2; v[4] = y1 * y2;
   }
 #pragma unroll
-  for (int k = 0; k < 5; k++) {
-    double t = wsum(v[k]);
-    if ((threadIdx.x & 63) == 0) red[k][threadIdx.x >> 6] = t;
-  }
-  __syncthreads();
-  if (threadIdx.x < 5) L.part[blockIdx.x * 5 + threadIdx.x] = red[threadIdx.x][0] + red[threadIdx.x][1] + red[threadIdx.x][2] + red[threadIdx.x][3];
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    L.ls[0] = Dg; L.ls[1] = njg; L.ls[2] = M1; L.ls[3] = Dj;
-    if (bad1 || bad2) ctrl->notpd = 1;
-  }
+  for (int k = 0; k < 5; k++) { const double t = wsum(v[k]); if (lc == 0) L.part[cb * 5 + k] = t; }
 }
 
-// exact change of the objective for the pair (Case 3), acceptance, trace
-__global__ __launch_bounds__(64) void lazy_accept_kernel(LazyPtrs L, int nblocks, SearchCtrl* ctrl, int always_accept,
-                                                          int32_t* trace_out, int32_t* trace_in, float* trace_gap,
-                                                          double* trace_obj) {
-  if (idle(ctrl)) return;
-  if (threadIdx.x != 0) return;
-  double s[5] = {0, 0, 0, 0, 0};
-  for (int b = 0; b < nblocks; b++)
-    for (int k = 0; k < 5; k++) s[k] += L.part[b * 5 + k];
-  L.ls[4] = s[2]; L.ls[5] = s[3]; L.ls[6] = s[4];
-  const double delta = -s[0] - s[1];
-  ctrl->delta = delta;
-  const int it = ctrl->iters;
-  const bool ok = !ctrl->notpd && (always_accept || delta < -ctrl->rel_tol * ctrl->obj);
-  ctrl->iters = it + 1;
-  if (ok) { ctrl->obj += delta; ctrl->accepted += 1; } else { ctrl->done = 1; }
-  if (trace_out) {
-    trace_out[it] = ctrl->g_out; trace_in[it] = ctrl->g_in;
-    trace_gap[2 * it] = (float)ctrl->gap_rem; trace_gap[2 * it + 1] = (float)ctrl->gap_add;
-    trace_obj[it] = ctrl->obj;
-  }
-}
-
-// w1 = Z0 y1, w2 = Z0 y2 (read-only pass over Z0), and u1 = ZT y1, u2 = ZT y2 in the trailing workgroups.
-// Each wave owns 8 rows; y1, y2 are staged through LDS in chunks of LAZY_CH columns.
+// ---------------------------------------------------------------------------------------------- gemv + accept
+// Every workgroup sums the partial records to the exact change of the objective (Case 3) and takes the same
+// accept / reject decision; workgroup 0 records it.  Then w1 = Z0 y1, w2 = Z0 y2 (read-only pass over Z0) and
+// u = ZT [y1 y2] in the leading workgroups.  Each wave owns 8 rows; y1, y2 are staged through LDS.
 constexpr int LAZY_CH = 4096;
 constexpr int GEMV_ROWS = 32;
 
-__global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float* __restrict__ Z0, int d1, int m,
-                                                         const SearchCtrl* __restrict__ ctrl) {
+__global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float* __restrict__ Z0, int d1, int m, int col_blocks,
+                                                         SearchCtrl* ctrl, int always_accept, int32_t* trace_out,
+                                                         int32_t* trace_in, float* trace_gap, double* trace_obj) {
   __shared__ float sy1[LAZY_CH], sy2[LAZY_CH];
+  __shared__ int s_ok;
   if (idle(ctrl)) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) {
+    double s[5] = {0, 0, 0, 0, 0};
+    for (int b = 0; b < col_blocks; b++)
+      for (int k = 0; k < 5; k++) s[k] += L.part[b * 5 + k];
+    const double delta = -s[0] - s[1];
+    const double obj = L.ls[LS_OBJ];
+    const bool ok = !ctrl->notpd && (always_accept || delta < -ctrl->rel_tol * obj);
+    s_ok = ok ? 1 : 0;
+    if (blockIdx.x == 0) {
+      L.ls[LS_Y11] = s[2]; L.ls[LS_Y22] = s[3]; L.ls[LS_Y12] = s[4];
+      ctrl->delta = delta;
+      const int it = ctrl->iters;
+      ctrl->iters = it + 1;
+      if (ok) { ctrl->obj = obj + delta; ctrl->accepted += 1; } else { ctrl->done = 1; }
+      if (trace_out) {
+        trace_out[it] = ctrl->g_out; trace_in[it] = ctrl->g_in;
+        trace_gap[2 * it] = (float)ctrl->gap_rem; trace_gap[2 * it + 1] = (float)ctrl->gap_add;
+        trace_obj[it] = ok ? obj + delta : obj;
+      }
+    }
+  }
+  __syncthreads();
+  if (!s_ok) return;
   constexpr int ZTB = LAZY_TM / 4;                    // leading workgroups: one pending row of ZT per wave
   if ((int)blockIdx.x < ZTB) {
     const int row = blockIdx.x * 4 + wave;
-    if (row >= ctrl->tau) return;
-    const double* zt = L.ZT + (int64_t)row * m;
     double a = 0, b = 0;
+    if (row < ctrl->tau) {
+      const double* zt = L.ZT + (int64_t)row * m;
 #pragma unroll 4
-    for (int c = lane; c < m; c += 64) { const double z = zt[c]; a += z * L.y1[c]; b += z * L.y2[c]; }
-    a = wsum(a); b = wsum(b);
-    if (lane == 0) { L.u1[row] = a; L.u2[row] = b; }
+      for (int c = lane; c < m; c += 64) { const double z = zt[c]; a += z * L.y1[c]; b += z * L.y2[c]; }
+      a = wsum(a); b = wsum(b);
+    }
+    if (lane == 0) { L.u1[row] = a; L.u2[row] = b; }     // zero beyond tau
     return;
   }
   const int row0 = ((int)blockIdx.x - ZTB) * GEMV_ROWS + wave * 8;
@@ -203,121 +303,138 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
   }
 }
 
-// squared row norms, diagonal and scores after the swap; new base columns appended to C0
-__global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const float* __restrict__ N0, int d1,
-                                                           const SearchCtrl* __restrict__ ctrl, int32_t* __restrict__ kept,
+// ---------------------------------------------------------------------------------------------- update
+// rows    : squared row norms, diagonal, scores (and their per-block records), the two new columns of C0
+// columns : ZT <- M'^-1 Z0[T', :] for T' = T + {g, j}
+// M       : bordering of M^-1 by g then j
+// The last workgroup to finish advances tau.
+__global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const float* __restrict__ N0, int d1, int m, int row_blocks,
+                                                           int col_blocks, SearchCtrl* ctrl, int32_t* __restrict__ kept,
                                                            double* __restrict__ rho, double* __restrict__ diag,
                                                            double* __restrict__ score) {
+  __shared__ double sa[LAZY_TM], sb[LAZY_TM];
+  __shared__ double w_mn1[4], w_mn2[4], w_mx1[4], w_mx2[4];
+  __shared__ int w_imn[4], w_imx[4];
+  __shared__ int s_last;
   if (idle(ctrl)) return;
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= d1) return;
-  const int g = ctrl->g_out, j = ctrl->g_in, tau = ctrl->tau;
-  const double Dg = L.ls[0], M1 = L.ls[2], Dj = L.ls[3], y11 = L.ls[4], y22 = L.ls[5], y12 = L.ls[6];
-  // append the base columns of g and j (rows tau, tau + 1 of C0T)
-  L.C0T[(int64_t)tau * d1 + i] = nsym1(N0, d1, i, g);
-  L.C0T[(int64_t)(tau + 1) * d1 + i] = nsym1(N0, d1, i, j);
-  if (i == g) {
-    rho[i] = y11 - 2.0 * M1 * y12 + M1 * M1 * y22;      // || -y1 + M1 y2 ||^2
-    diag[i] = -Dg - M1 * M1 * Dj;
-    kept[i] = 0;
-    L.pos[i] = tau; L.Tidx[tau] = i; L.Jsg[tau] = -1.f;
-    score[i] = rho[i] / fabs(diag[i]);
-    return;
-  }
-  if (i == j) {
-    rho[i] = y22;
-    diag[i] = -Dj;
-    kept[i] = 1;
-    L.pos[i] = tau + 1; L.Tidx[tau + 1] = i; L.Jsg[tau + 1] = 1.f;
-    score[i] = rho[i] / fabs(diag[i]);
-    return;
-  }
-  double zy1, zy2;
-  const int ps = L.pos[i];
-  if (ps >= 0) {
-    const double sg = (double)L.Jsg[ps];
-    zy1 = sg * L.u1[ps]; zy2 = sg * L.u2[ps];
-  } else {
-    double a = 0, b = 0;
-    for (int s = 0; s < tau; s++) {
-      const double c = (double)L.C0T[(int64_t)s * d1 + i];
-      a += c * L.u1[s]; b += c * L.u2[s];
+  const int tid = threadIdx.x, g = ctrl->g_out, j = ctrl->g_in, tau = ctrl->tau;
+  const double Dg = L.ls[LS_DG], M1 = L.ls[LS_M1], Dj = L.ls[LS_DJ];
+  const int b = blockIdx.x;
+  if (b < row_blocks) {
+    for (int s = tid; s < LAZY_TM; s += 256) { sa[s] = L.u1[s]; sb[s] = L.u2[s]; }
+    __syncthreads();
+    const double y11 = L.ls[LS_Y11], y22 = L.ls[LS_Y22], y12 = L.ls[LS_Y12];
+    const int row = b * ROWS_PER_BLOCK + (tid >> 3), l8 = tid & 7;
+    double mn1 = INFINITY, mx1 = -INFINITY;
+    int imn = -1, imx = -1;
+    if (row < d1) {
+      double da, db;
+      row_dots(L.C0R + (int64_t)row * LAZY_TM, sa, sb, l8, da, db);
+      if (l8 == 0) {
+        // the base columns of g and j become columns tau, tau + 1 of C0
+        L.C0R[(int64_t)row * LAZY_TM + tau] = nsym1(N0, d1, row, g);
+        L.C0R[(int64_t)row * LAZY_TM + tau + 1] = nsym1(N0, d1, row, j);
+        double r, dn;
+        int kp;
+        if (row == g) {
+          r = y11 - 2.0 * M1 * y12 + M1 * M1 * y22;          // || -y1 + M1 y2 ||^2
+          dn = -Dg - M1 * M1 * Dj;
+          kp = 0;
+          L.pos[row] = tau; L.Tidx[tau] = row; L.Jsg[tau] = -1.f;
+        } else if (row == j) {
+          r = y22; dn = -Dj; kp = 1;
+          L.pos[row] = tau + 1; L.Tidx[tau + 1] = row; L.Jsg[tau + 1] = 1.f;
+        } else {
+          double zy1, zy2;
+          const int ps = L.pos[row];
+          if (ps >= 0) { const double sg = (double)L.Jsg[ps]; zy1 = sg * sa[ps]; zy2 = sg * sb[ps]; }
+          else { zy1 = L.w1[row] - da; zy2 = L.w2[row] - db; }
+          const double c1 = L.cg[row];
+          const double c2 = L.cj[row] - c1 * M1;
+          r = rho[row] - 2.0 * c1 * zy1 + c1 * c1 * y11;       // after the reverse sweep on g
+          const double zy2p = zy2 - c1 * y12;                  // (Z_i - c1 y1) . y2
+          r += -2.0 * c2 * zy2p + c2 * c2 * y22;               // after the forward sweep on j
+          if (r < 0.0) r = 0.0;
+          dn = diag[row] - c1 * c1 * Dg - c2 * c2 * Dj;
+          kp = kept[row];
+        }
+        rho[row] = r; diag[row] = dn; kept[row] = kp;
+        const double sc = r / fabs(dn);
+        score[row] = sc;
+        if (kp) { mn1 = sc; imn = row; } else { mx1 = sc; imx = row; }
+      }
     }
-    zy1 = L.w1[i] - a; zy2 = L.w2[i] - b;
+    // per-block record (the row leaders are lanes 0, 8, 16, ... of each wave)
+    double mn2 = INFINITY, mx2 = -INFINITY;
+    for (int o = 32; o >= 8; o >>= 1) {
+      double b1 = __shfl_down(mn1, o, 64), b2 = __shfl_down(mn2, o, 64); int ib = __shfl_down(imn, o, 64);
+      merge_min(mn1, mn2, imn, b1, b2, ib);
+      b1 = __shfl_down(mx1, o, 64); b2 = __shfl_down(mx2, o, 64); ib = __shfl_down(imx, o, 64);
+      merge_max(mx1, mx2, imx, b1, b2, ib);
+    }
+    if ((tid & 63) == 0) { const int w = tid >> 6; w_mn1[w] = mn1; w_mn2[w] = mn2; w_imn[w] = imn; w_mx1[w] = mx1; w_mx2[w] = mx2; w_imx[w] = imx; }
+    __syncthreads();
+    if (tid == 0) {
+      for (int w = 1; w < 4; w++) { merge_min(mn1, mn2, imn, w_mn1[w], w_mn2[w], w_imn[w]); merge_max(mx1, mx2, imx, w_mx1[w], w_mx2[w], w_imx[w]); }
+      SelRec rec; rec.mn1 = mn1; rec.mn2 = mn2; rec.mx1 = mx1; rec.mx2 = mx2; rec.imn = imn; rec.imx = imx;
+      L.sel[b] = rec;
+    }
+  } else if (b < row_blocks + col_blocks) {
+    const int cb = b - row_blocks, slice = tid >> 6, col = cb * COLS_PER_BLOCK + (tid & 63);
+    for (int s = tid; s < LAZY_TM; s += 256) { const double xg = L.xg[s]; sa[s] = xg; sb[s] = L.xj[s] - xg * M1; }
+    __syncthreads();
+    if (col < m) {
+      const double y1 = L.y1[col], y2 = L.y2[col];
+      for (int s = slice; s < tau; s += 4) L.ZT[(int64_t)s * m + col] -= sa[s] * y1 + sb[s] * y2;
+      if (slice == 0) { L.ZT[(int64_t)tau * m + col] = y1 - M1 * y2; L.ZT[(int64_t)(tau + 1) * m + col] = y2; }
+    }
+  } else {
+    const int mb = b - row_blocks - col_blocks, nmb = gridDim.x - row_blocks - col_blocks;
+    double* Mi = L.Minv;
+    for (int idx = mb * 256 + tid; idx < tau * tau; idx += nmb * 256) {
+      const int r = idx / tau, s = idx % tau;
+      const double xr = L.xg[r], xs = L.xg[s];
+      const double pr = L.xj[r] - xr * M1, ps = L.xj[s] - xs * M1;
+      Mi[r * LAZY_TM + s] += xr * xs * Dg + pr * ps * Dj;
+    }
+    if (mb == 0) {
+      for (int r = tid; r < tau; r += 256) {
+        const double xr = L.xg[r], pr = L.xj[r] - xr * M1;
+        const double v = -xr * Dg + pr * M1 * Dj;          // bordered by g, then corrected by the sweep on j
+        Mi[r * LAZY_TM + tau] = v; Mi[tau * LAZY_TM + r] = v;
+        const double w = -pr * Dj;
+        Mi[r * LAZY_TM + tau + 1] = w; Mi[(tau + 1) * LAZY_TM + r] = w;
+      }
+      if (tid == 0) {
+        Mi[tau * LAZY_TM + tau] = Dg + M1 * M1 * Dj;
+        Mi[tau * LAZY_TM + tau + 1] = -M1 * Dj; Mi[(tau + 1) * LAZY_TM + tau] = -M1 * Dj;
+        Mi[(tau + 1) * LAZY_TM + tau + 1] = Dj;
+      }
+    }
   }
-  const double c1 = L.cg[i];
-  const double c2 = L.cj[i] - c1 * M1;
-  double r = rho[i];
-  r += -2.0 * c1 * zy1 + c1 * c1 * y11;                   // after the reverse sweep on g
-  const double zy2p = zy2 - c1 * y12;                     // (Z_i - c1 y1) . y2
-  r += -2.0 * c2 * zy2p + c2 * c2 * y22;                  // after the forward sweep on j
-  if (r < 0.0) r = 0.0;
-  const double dnew = diag[i] - c1 * c1 * Dg - c2 * c2 * Dj;
-  rho[i] = r; diag[i] = dnew;
-  score[i] = r / fabs(dnew);
-}
-
-// ZT <- M'^-1 Z0[T', :] for T' = T + {g, j}
-__global__ __launch_bounds__(256) void lazy_zt_kernel(LazyPtrs L, int m, const SearchCtrl* __restrict__ ctrl) {
-  if (idle(ctrl)) return;
-  const int col = blockIdx.x * 256 + threadIdx.x;
-  if (col >= m) return;
-  const int tau = ctrl->tau;
-  const double M1 = L.ls[2];
-  const double y1 = L.y1[col], y2 = L.y2[col];
-  for (int s = 0; s < tau; s++) {
-    const double xg = L.xg[s], xjp = L.xj[s] - xg * M1;
-    L.ZT[(int64_t)s * m + col] -= xg * y1 + xjp * y2;
-  }
-  L.ZT[(int64_t)tau * m + col] = y1 - M1 * y2;
-  L.ZT[(int64_t)(tau + 1) * m + col] = y2;
-}
-
-// bordering of M^-1 by g then j; tau += 2
-__global__ __launch_bounds__(256) void lazy_minv_kernel(LazyPtrs L, SearchCtrl* ctrl) {
-  if (idle(ctrl)) return;
-  const int tau = ctrl->tau, tid = threadIdx.x;
-  const double Dg = L.ls[0], M1 = L.ls[2], Dj = L.ls[3];
-  double* Mi = L.Minv;
-  // x'_s = x_j[s] - x_g[s] M1 (s < tau), x'_tau = M1
-  for (int idx = tid; idx < tau * tau; idx += 256) {
-    int r = idx / tau, s = idx % tau;
-    double xr = L.xg[r], xs = L.xg[s];
-    double pr = L.xj[r] - xr * M1, ps = L.xj[s] - xs * M1;
-    Mi[r * LAZY_TM + s] += xr * xs * Dg + pr * ps * Dj;
-  }
-  for (int r = tid; r < tau; r += 256) {
-    double xr = L.xg[r], pr = L.xj[r] - xr * M1;
-    double v = -xr * Dg + pr * M1 * Dj;              // bordered by g, then corrected by the sweep on j
-    Mi[r * LAZY_TM + tau] = v; Mi[tau * LAZY_TM + r] = v;
-    double w = -pr * Dj;
-    Mi[r * LAZY_TM + tau + 1] = w; Mi[(tau + 1) * LAZY_TM + r] = w;
-  }
+  // the last workgroup to get here advances tau (all others have finished with the old value)
+  __syncthreads();
   if (tid == 0) {
-    Mi[tau * LAZY_TM + tau] = Dg + M1 * M1 * Dj;
-    Mi[tau * LAZY_TM + tau + 1] = -M1 * Dj; Mi[(tau + 1) * LAZY_TM + tau] = -M1 * Dj;
-    Mi[(tau + 1) * LAZY_TM + tau + 1] = Dj;
+    __threadfence();
+    const int done_blocks = atomicAdd(L.counter, 1);
+    s_last = (done_blocks == (int)gridDim.x - 1);
   }
   __syncthreads();
-  if (tid == 0) ctrl->tau = tau + 2;
+  if (s_last && tid == 0) { *L.counter = 0; ctrl->tau = tau + 2; }
 }
 
 hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, int always_accept, hipStream_t s,
                                  hipEvent_t* ev) {
-  const int rb = (d.d1 + 255) / 256, mb = (d.m + 255) / 256;
-  launch_select(d, t, -1, -1, s);
-  hipLaunchKernelGGL(lazy_prep_kernel, dim3(1), dim3(256), 0, s, L, t.N, d.d1, t.ctrl);
-  hipLaunchKernelGGL(lazy_columns_kernel, dim3(rb), dim3(256), 0, s, L, t.N, d.d1, t.ctrl);
-  hipLaunchKernelGGL(lazy_zrows_kernel, dim3(mb), dim3(256), 0, s, L, t.Z, d.d1, d.m, t.ctrl);
-  hipLaunchKernelGGL(lazy_accept_kernel, dim3(1), dim3(64), 0, s, L, mb, t.ctrl, always_accept, t.trace_out, t.trace_in,
-                     t.trace_gap, t.trace_obj);
+  const int rb = (d.d1 + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, cb = (d.m + COLS_PER_BLOCK - 1) / COLS_PER_BLOCK;
+  hipLaunchKernelGGL(lazy_prep_kernel, dim3(1), dim3(256), 0, s, L, t.N, d.d1, rb, t.ctrl);
+  hipLaunchKernelGGL(lazy_vectors_kernel, dim3(rb + cb), dim3(256), 0, s, L, t.N, t.Z, d.d1, d.m, rb, t.ctrl);
   const int gb = (d.d1 + GEMV_ROWS - 1) / GEMV_ROWS + LAZY_TM / 4;
   if (ev) hipEventRecord(ev[0], s);
-  hipLaunchKernelGGL(lazy_gemv_kernel, dim3(gb), dim3(256), 0, s, L, t.Z, d.d1, d.m, t.ctrl);
+  hipLaunchKernelGGL(lazy_gemv_kernel, dim3(gb), dim3(256), 0, s, L, t.Z, d.d1, d.m, cb, t.ctrl, always_accept, t.trace_out,
+                     t.trace_in, t.trace_gap, t.trace_obj);
   if (ev) hipEventRecord(ev[1], s);
-  hipLaunchKernelGGL(lazy_update_kernel, dim3(rb), dim3(256), 0, s, L, t.N, d.d1, t.ctrl, t.kept, t.gram, t.dblk, t.score);
-  hipLaunchKernelGGL(lazy_zt_kernel, dim3(mb), dim3(256), 0, s, L, d.m, t.ctrl);
-  hipLaunchKernelGGL(lazy_minv_kernel, dim3(1), dim3(256), 0, s, L, t.ctrl);
+  hipLaunchKernelGGL(lazy_update_kernel, dim3(rb + cb + 16), dim3(256), 0, s, L, t.N, d.d1, d.m, rb, cb, t.ctrl, t.kept, t.gram,
+                     t.dblk, t.score);
   if (ev) hipEventRecord(ev[2], s);
   return hipGetLastError();
 }
@@ -325,44 +442,20 @@ hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyP
 // ------------------------------------------------------------------------------------------------
 // flush: apply the pending correction to N0, Z0 and empty T
 // ------------------------------------------------------------------------------------------------
-// E = C0 M^-1 and Cb = C0 as d1 x LAZY_TM row-major panels (rows in T and columns >= tau are zero); Et keeps the
-// unzeroed E rows (they are the same rows: rows in T are never needed from E).
-__global__ __launch_bounds__(256) void lazy_panels_kernel(LazyPtrs L, int d1, const SearchCtrl* __restrict__ ctrl) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= d1) return;
+// float32 copies of M^-1 and ZT, zero beyond tau (so that stale columns of C0 drop out of the products)
+__global__ __launch_bounds__(256) void lazy_convert_kernel(LazyPtrs L, int m, const SearchCtrl* __restrict__ ctrl) {
   const int tau = ctrl->tau;
-  float* Ei = L.E + (int64_t)i * LAZY_TM;
-  float* Ci = L.Cb + (int64_t)i * LAZY_TM;
-  if (L.pos[i] >= 0) {
-    for (int s = 0; s < LAZY_TM; s++) { Ei[s] = 0.f; Ci[s] = 0.f; }
-    return;
-  }
-  for (int s0 = 0; s0 < LAZY_TM; s0 += 16) {
-    double acc[16];
-#pragma unroll
-    for (int u = 0; u < 16; u++) acc[u] = 0;
-    if (s0 < tau) {
-      for (int r = 0; r < tau; r++) {
-        const double c = (double)L.C0T[(int64_t)r * d1 + i];
-        const double* mr = L.Minv + r * LAZY_TM + s0;
-#pragma unroll
-        for (int u = 0; u < 16; u++) acc[u] += c * mr[u];
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < 16; u++) {
-      const int s = s0 + u;
-      Ei[s] = (s < tau) ? (float)acc[u] : 0.f;
-      Ci[s] = (s < tau) ? L.C0T[(int64_t)s * d1 + i] : 0.f;
+  const int64_t nz = (int64_t)LAZY_TM * m, nm = (int64_t)LAZY_TM * LAZY_TM;
+  for (int64_t idx = blockIdx.x * 256 + threadIdx.x; idx < nz + nm; idx += (int64_t)gridDim.x * 256) {
+    if (idx < nz) {
+      const int s = (int)(idx / m);
+      L.ZT32[idx] = (s < tau) ? (float)L.ZT[idx] : 0.f;
+    } else {
+      const int64_t k = idx - nz;
+      const int r = (int)(k / LAZY_TM), s = (int)(k % LAZY_TM);
+      L.Minv32[k] = (r < tau && s < tau) ? (float)L.Minv[k] : 0.f;
     }
   }
-}
-
-__global__ __launch_bounds__(256) void lazy_zt32_kernel(LazyPtrs L, int m, const SearchCtrl* __restrict__ ctrl) {
-  const int col = blockIdx.x * 256 + threadIdx.x;
-  if (col >= m) return;
-  const int tau = ctrl->tau;
-  for (int s = 0; s < LAZY_TM; s++) L.ZT32[(int64_t)s * m + col] = (s < tau) ? (float)L.ZT[(int64_t)s * m + col] : 0.f;
 }
 
 // pivot rows / columns of N0 and pivot rows of Z0
@@ -400,30 +493,48 @@ __global__ __launch_bounds__(256) void lazy_reset_kernel(LazyPtrs L, SearchCtrl*
   if (threadIdx.x == 0) { ctrl->tau = 0; ctrl->pause = 0; }
 }
 
+static hipError_t launch_partials(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s) {
+  const int rb = (d.d1 + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
+  hipLaunchKernelGGL(lazy_partials_kernel, dim3(rb), dim3(64), 0, s, L, d.p, t.kept, t.score);
+  return hipGetLastError();
+}
+
 hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s) {
   const int rb = (d.d1 + 255) / 256, mb = (d.m + 255) / 256;
-  hipLaunchKernelGGL(lazy_panels_kernel, dim3(rb), dim3(256), 0, s, L, d.d1, t.ctrl);
-  hipLaunchKernelGGL(lazy_zt32_kernel, dim3(mb), dim3(256), 0, s, L, d.m, t.ctrl);
-  GemmArgs g{};
-  g.M = d.d1; g.N = d.d1; g.K = LAZY_TM; g.A = L.E; g.lda = LAZY_TM; g.B = L.Cb; g.ldb = LAZY_TM; g.trans_b = 1;
-  g.Cin = t.N; g.ldcin = d.d1; g.C = t.N; g.ldc = d.d1; g.alpha = -1.0; g.beta = 1.0; g.lower_only = 1;
-  hipError_t e = launch_gemm_f64acc(g, s);
-  if (e != hipSuccess) return e;
-  GemmArgs z{};
-  z.M = d.d1; z.N = d.m; z.K = LAZY_TM; z.A = L.Cb; z.lda = LAZY_TM; z.B = L.ZT32; z.ldb = d.m;
-  z.Cin = t.Z; z.ldcin = d.m; z.C = t.Z; z.ldc = d.m; z.alpha = -1.0; z.beta = 1.0;
-  e = launch_gemm_f64acc(z, s);
-  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(lazy_convert_kernel, dim3(512), dim3(256), 0, s, L, d.m, t.ctrl);
+  GemmArgs e{};                         // E = C0 M^-1
+  e.M = d.d1; e.N = LAZY_TM; e.K = LAZY_TM; e.A = L.C0R; e.lda = LAZY_TM; e.B = L.Minv32; e.ldb = LAZY_TM;
+  e.C = L.E; e.ldc = LAZY_TM; e.alpha = 1.0; e.beta = 0.0;
+  hipError_t err = launch_gemm_f64acc(e, s);
+  if (err != hipSuccess) return err;
+  GemmArgs g{};                         // N0 -= E C0^T on the lower triangle (pivot rows and columns are rewritten below)
+  g.M = d.d1; g.N = d.d1; g.K = LAZY_TM; g.A = L.E; g.lda = LAZY_TM; g.B = L.C0R; g.ldb = LAZY_TM; g.trans_b = 1;
+  g.Cin = t.N; g.ldcin = d.d1; g.C = t.N; g.ldc = d.d1; g.alpha = -1.0; g.beta = 1.0; g.lower_only = 1; g.acc_f32 = 1;
+  err = launch_gemm_f64acc(g, s);
+  if (err != hipSuccess) return err;
+  GemmArgs z{};                         // Z0 -= C0 ZT
+  z.M = d.d1; z.N = d.m; z.K = LAZY_TM; z.A = L.C0R; z.lda = LAZY_TM; z.B = L.ZT32; z.ldb = d.m;
+  z.Cin = t.Z; z.ldcin = d.m; z.C = t.Z; z.ldc = d.m; z.alpha = -1.0; z.beta = 1.0; z.acc_f32 = 1;
+  err = launch_gemm_f64acc(z, s);
+  if (err != hipSuccess) return err;
   hipLaunchKernelGGL(lazy_fix_kernel, dim3(rb), dim3(256), 0, s, L, t.N, d.d1, t.ctrl);
   hipLaunchKernelGGL(lazy_fix_z_kernel, dim3(mb), dim3(256), 0, s, L, t.Z, d.m, t.ctrl);
   hipLaunchKernelGGL(lazy_reset_kernel, dim3(1), dim3(256), 0, s, L, t.ctrl);
-  return launch_refresh_scores(d, t, s);
+  err = launch_refresh_scores(d, t, s);
+  if (err != hipSuccess) return err;
+  return launch_partials(d, t, L, s);
 }
 
-hipError_t launch_lazy_init(const TabDims& d, const LazyPtrs& L, SearchCtrl* ctrl, hipStream_t s) {
+hipError_t launch_lazy_init(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s) {
   hipError_t e = hipMemsetAsync(L.pos, 0xFF, (size_t)d.d1 * 4, s);
   if (e != hipSuccess) return e;
-  return hipMemsetAsync(L.Minv, 0, (size_t)LAZY_TM * LAZY_TM * 8, s);
+  e = hipMemsetAsync(L.Minv, 0, (size_t)LAZY_TM * LAZY_TM * 8, s);
+  if (e != hipSuccess) return e;
+  e = hipMemsetAsync(L.C0R, 0, (size_t)d.d1 * LAZY_TM * 4, s);
+  if (e != hipSuccess) return e;
+  e = hipMemsetAsync(L.counter, 0, 4, s);
+  if (e != hipSuccess) return e;
+  return launch_partials(d, t, L, s);
 }
 
 }  // namespace osscar

@@ -278,7 +278,7 @@ hipError_t spd_inverse_inplace(float* A, int n, float* panel, float* panelD, dou
     GemmArgs g{};
     g.M = n; g.N = n; g.K = w; g.A = panelD; g.lda = w; g.B = panelB; g.ldb = w; g.trans_b = 1;
     g.Cin = A; g.ldcin = n; g.C = A; g.ldc = n; g.alpha = -1.0; g.beta = 1.0; g.diag_add = 0.0; g.c_is_f64 = 0;
-    g.lower_only = 1;
+    g.lower_only = 1; g.acc_f32 = 1;
     hipError_t e = launch_gemm_f64acc(g, s);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(inv_fix_kernel, dim3(rb), dim3(256), 0, s, A, (int64_t)n, n, t0, w, panelD, small);
