@@ -44,6 +44,14 @@ __global__ void symmetrize_kernel(const float* __restrict__ A, float* __restrict
     out[idx] = 0.5f * (A[idx] + A[(int64_t)j * n + i]);
   }
 }
+// out = the symmetric matrix whose lower triangle is that of A
+__global__ void mirror_from_lower_kernel(const float* __restrict__ A, float* __restrict__ out, int n) {
+  int64_t tot = (int64_t)n * n;
+  for (int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; idx < tot; idx += (int64_t)gridDim.x * blockDim.x) {
+    int i = (int)(idx / n), j = (int)(idx % n);
+    out[idx] = (j <= i) ? A[idx] : A[(int64_t)j * n + i];
+  }
+}
 __global__ void add_inplace_kernel(float* __restrict__ a, const float* __restrict__ b, int64_t n) {
   for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) a[i] += b[i];
 }
@@ -227,8 +235,9 @@ osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b) {
   for (int step = 0; step < 3; step++) {
     HIPCHK(c, gemm(s, kr, kr, kr, b.HKK, kr, b.P, kr, nullptr, 0, b.T1, kr, -1.0, 0.0, 1.0));
     HIPCHK(c, launch_absmax(b.T1, (int64_t)kr * kr, c->partial, s));
-    HIPCHK(c, gemm(s, kr, kr, kr, b.P, kr, b.T1, kr, b.P, kr, b.T2, kr, 1.0, 1.0));
-    hipLaunchKernelGGL(symmetrize_kernel, dim3(grid_for((int64_t)kr * kr)), dim3(256), 0, s, b.T2, b.P, kr);
+    // P + P (I - H P) is symmetric up to rounding: compute its lower triangle and mirror it
+    HIPCHK(c, gemm(s, kr, kr, kr, b.P, kr, b.T1, kr, b.P, kr, b.T2, kr, 1.0, 1.0, 0.0, 1));
+    hipLaunchKernelGGL(mirror_from_lower_kernel, dim3(grid_for((int64_t)kr * kr)), dim3(256), 0, s, b.T2, b.P, kr);
     double part[256]; int32_t bad = 0;
     HIPCHK(c, hipMemcpyAsync(part, c->partial, sizeof part, hipMemcpyDeviceToHost, s));
     HIPCHK(c, hipMemcpyAsync(&bad, c->notpd, 4, hipMemcpyDeviceToHost, s));

@@ -209,7 +209,9 @@ __global__ __launch_bounds__(256) void lazy_vectors_kernel(LazyPtrs L, const flo
 // accept / reject decision; workgroup 0 records it.  Then w1 = Z0 y1, w2 = Z0 y2 (read-only pass over Z0) and
 // u = ZT [y1 y2] in the leading workgroups.  Each wave owns 8 rows; y1, y2 are staged through LDS.
 constexpr int LAZY_CH = 4096;
-constexpr int GEMV_ROWS = 32;
+constexpr int GEMV_RPW = 4;        // rows per wave
+constexpr int GEMV_UNR = 4;        // float4 loads in flight per row and lane
+constexpr int GEMV_ROWS = 4 * GEMV_RPW;
 
 __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float* __restrict__ Z0, int d1, int m, int col_blocks,
                                                          SearchCtrl* ctrl, int always_accept, int32_t* trace_out,
@@ -218,24 +220,30 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
   __shared__ int s_ok;
   if (idle(ctrl)) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (tid == 0) {
-    double s[5] = {0, 0, 0, 0, 0};
-    for (int b = 0; b < col_blocks; b++)
-      for (int k = 0; k < 5; k++) s[k] += L.part[b * 5 + k];
-    const double delta = -s[0] - s[1];
-    const double obj = L.ls[LS_OBJ];
-    const bool ok = !ctrl->notpd && (always_accept || delta < -ctrl->rel_tol * obj);
-    s_ok = ok ? 1 : 0;
-    if (blockIdx.x == 0) {
-      L.ls[LS_Y11] = s[2]; L.ls[LS_Y22] = s[3]; L.ls[LS_Y12] = s[4];
-      ctrl->delta = delta;
-      const int it = ctrl->iters;
-      ctrl->iters = it + 1;
-      if (ok) { ctrl->obj = obj + delta; ctrl->accepted += 1; } else { ctrl->done = 1; }
-      if (trace_out) {
-        trace_out[it] = ctrl->g_out; trace_in[it] = ctrl->g_in;
-        trace_gap[2 * it] = (float)ctrl->gap_rem; trace_gap[2 * it + 1] = (float)ctrl->gap_add;
-        trace_obj[it] = ok ? obj + delta : obj;
+  if (wave == 0) {
+    // partial sums in a fixed order: lane l adds the records l, l + 64, ...; then a wave reduction
+    double sk[5] = {0, 0, 0, 0, 0};
+    for (int b = lane; b < col_blocks; b += 64)
+#pragma unroll
+      for (int k = 0; k < 5; k++) sk[k] += L.part[b * 5 + k];
+#pragma unroll
+    for (int k = 0; k < 5; k++) { sk[k] = wsum(sk[k]); }
+    if (lane == 0) {
+      const double delta = -sk[0] - sk[1];
+      const double obj = L.ls[LS_OBJ];
+      const bool ok = !ctrl->notpd && (always_accept || delta < -ctrl->rel_tol * obj);
+      s_ok = ok ? 1 : 0;
+      if (blockIdx.x == 0) {
+        L.ls[LS_Y11] = sk[2]; L.ls[LS_Y22] = sk[3]; L.ls[LS_Y12] = sk[4];
+        ctrl->delta = delta;
+        const int it = ctrl->iters;
+        ctrl->iters = it + 1;
+        if (ok) { ctrl->obj = obj + delta; ctrl->accepted += 1; } else { ctrl->done = 1; }
+        if (trace_out) {
+          trace_out[it] = ctrl->g_out; trace_in[it] = ctrl->g_in;
+          trace_gap[2 * it] = (float)ctrl->gap_rem; trace_gap[2 * it + 1] = (float)ctrl->gap_add;
+          trace_obj[it] = ok ? obj + delta : obj;
+        }
       }
     }
   }
@@ -254,10 +262,18 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
     if (lane == 0) { L.u1[row] = a; L.u2[row] = b; }     // zero beyond tau
     return;
   }
-  const int row0 = ((int)blockIdx.x - ZTB) * GEMV_ROWS + wave * 8;
-  double a1[8], a2[8];
+  // Each wave owns GEMV_RPW rows.  Products are summed four at a time in float32 (one float4 of Z0 against one of y)
+  // and the partial sums are accumulated in float64: the rounding this adds is below that of Z0's own float32 storage.
+  const int row0 = ((int)blockIdx.x - ZTB) * GEMV_ROWS + wave * GEMV_RPW;
+  double a1[GEMV_RPW], a2[GEMV_RPW];
+  const float* rp[GEMV_RPW];
 #pragma unroll
-  for (int r = 0; r < 8; r++) { a1[r] = 0; a2[r] = 0; }
+  for (int r = 0; r < GEMV_RPW; r++) {
+    a1[r] = 0; a2[r] = 0;
+    int row = row0 + r;
+    if (row > d1 - 1) row = d1 - 1;                 // clamped rows: their sums are discarded
+    rp[r] = Z0 + (int64_t)row * m;
+  }
   const bool vec = (m % 4 == 0);
   for (int c0 = 0; c0 < m; c0 += LAZY_CH) {
     const int cw = (m - c0 < LAZY_CH) ? m - c0 : LAZY_CH;
@@ -265,38 +281,43 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
     for (int c = tid; c < cw; c += 256) { sy1[c] = L.y1f[c0 + c]; sy2[c] = L.y2f[c0 + c]; }
     __syncthreads();
     if (vec) {
-      // rows beyond the end are clamped (their sums are discarded) so that the 8 loads of a step are issued together
-      for (int c = lane * 4; c < cw; c += 256) {
-        float4 z[8];
+      for (int c = lane * 4; c < cw; c += 256 * GEMV_UNR) {
+        float4 z[GEMV_UNR][GEMV_RPW];
 #pragma unroll
-        for (int r = 0; r < 8; r++) {
-          int row = row0 + r;
-          if (row > d1 - 1) row = d1 - 1;
-          z[r] = *reinterpret_cast<const float4*>(Z0 + (int64_t)row * m + c0 + c);
-        }
-        const float4 p1 = *reinterpret_cast<const float4*>(&sy1[c]);
-        const float4 p2 = *reinterpret_cast<const float4*>(&sy2[c]);
+        for (int u = 0; u < GEMV_UNR; u++)
 #pragma unroll
-        for (int r = 0; r < 8; r++) {
-          a1[r] += (double)z[r].x * p1.x + (double)z[r].y * p1.y + (double)z[r].z * p1.z + (double)z[r].w * p1.w;
-          a2[r] += (double)z[r].x * p2.x + (double)z[r].y * p2.y + (double)z[r].z * p2.z + (double)z[r].w * p2.w;
+          for (int r = 0; r < GEMV_RPW; r++) {
+            const int cc = c + u * 256;
+            z[u][r] = (cc < cw) ? *reinterpret_cast<const float4*>(rp[r] + c0 + cc) : float4{0.f, 0.f, 0.f, 0.f};
+          }
+#pragma unroll
+        for (int u = 0; u < GEMV_UNR; u++) {
+          int cc = c + u * 256;
+          if (cc >= cw) cc = 0;
+          const float4 p1 = *reinterpret_cast<const float4*>(&sy1[cc]);
+          const float4 p2 = *reinterpret_cast<const float4*>(&sy2[cc]);
+#pragma unroll
+          for (int r = 0; r < GEMV_RPW; r++) {
+            const float4 v = z[u][r];
+            const float s1 = v.x * p1.x + v.y * p1.y + v.z * p1.z + v.w * p1.w;
+            const float s2 = v.x * p2.x + v.y * p2.y + v.z * p2.z + v.w * p2.w;
+            a1[r] += (double)s1; a2[r] += (double)s2;
+          }
         }
       }
     } else {
       for (int c = lane; c < cw; c += 64) {
         const double p1 = sy1[c], p2 = sy2[c];
 #pragma unroll
-        for (int r = 0; r < 8; r++) {
-          int row = row0 + r;
-          if (row > d1 - 1) row = d1 - 1;
-          const double z = (double)Z0[(int64_t)row * m + c0 + c];
+        for (int r = 0; r < GEMV_RPW; r++) {
+          const double z = (double)rp[r][c0 + c];
           a1[r] += z * p1; a2[r] += z * p2;
         }
       }
     }
   }
 #pragma unroll
-  for (int r = 0; r < 8; r++) {
+  for (int r = 0; r < GEMV_RPW; r++) {
     double t1 = wsum(a1[r]), t2 = wsum(a2[r]);
     const int row = row0 + r;
     if (lane == 0 && row < d1) { L.w1[row] = t1; L.w2[row] = t2; }

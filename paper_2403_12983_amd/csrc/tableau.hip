@@ -220,12 +220,14 @@ constexpr int INV_NB = 64;
 __global__ __launch_bounds__(256) void inv_block_kernel(const float* __restrict__ C, int w, int t0, double* __restrict__ D,
                                                          int32_t* notpd) {
   __shared__ double colbuf[INV_NB];
+  __shared__ double Dsh[INV_NB * INV_NB];
   for (int idx = threadIdx.x; idx < w * w; idx += 256) {
     int r = idx / w, c = idx % w;
-    D[idx] = (double)C[(int64_t)(t0 + r) * w + c];
+    Dsh[idx] = (double)C[(int64_t)(t0 + r) * w + c];
   }
   __syncthreads();
-  small_inverse(D, w, +1, notpd, colbuf);
+  small_inverse(Dsh, w, +1, notpd, colbuf);
+  for (int idx = threadIdx.x; idx < w * w; idx += 256) D[idx] = Dsh[idx];
 }
 
 // pivot rows after a forward sweep: N(t0+r, l) = CD[l][r] for l outside the pivot, N(tt) = -D
