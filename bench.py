@@ -5,10 +5,10 @@ One "step" is one pass of the whole hot path over one synthetic OPT-30B-shaped f
 calibration rows, finalize (ridge, G = H W), magnitude support + state build, the local search, and the
 final back-solve.  X and W are resident in HBM before the timed region starts.
 
-Prints one JSON line.  `value` is seconds per layer (lower is better).  `roofline` describes the search's
-bulk update of the tableau N (the kernel the layer time is dominated by), `roofline_gram` the bf16 MFMA
-Gram kernel, and `cpu_baseline` the float64 oracle timed on this machine's host cores on a reduced layer of
-the same recipe."""
+Prints one JSON line.  `value` is seconds per layer (lower is better).  `roofline` describes the kernel the
+layer time is dominated by: the search's per-swap read-only pass over Z (for q > 1, where the search updates
+the tableau in place, the bulk update of N).  `roofline_gram` describes the bf16 MFMA Gram kernel, and
+`cpu_baseline` the float64 oracle timed on this machine's host cores on a reduced layer of the same recipe."""
 from __future__ import annotations
 
 import argparse
@@ -82,6 +82,11 @@ def main():
     ap.add_argument("--swaps", type=int, default=None)
     ap.add_argument("--refresh-every", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rows", type=int, default=None,
+                    help="calibration rows (default: the config's); a short X keeps counter-collection runs brief")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="end with one 1 GiB device-to-device copy, the known-size kernel that scales rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE readings")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py measures one MI355X: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
@@ -92,6 +97,8 @@ def main():
     import paper_2403_12983_amd as pkg
 
     cfg = inp.CONFIGS[a.config]
+    if a.rows is not None:
+        cfg = cfg.replace(n=a.rows)
     swaps = cfg.swaps if a.swaps is None else a.swaps
     dev = "cuda:0"
     X = gen_on_gpu(inp, torch, cfg, dev)
@@ -142,36 +149,58 @@ def main():
     t_layer = wall / K
 
     d1, m, n = cfg.d1, cfg.m, cfg.n
-    bytes_n = 2 * 4 * (d1 * d1 // 2)           # read + write of the lower triangle of N (= P and V of the kept-set view)
-    bytes_z = 2 * 4 * d1 * m                   # read + write of Z (= B and R)
     gram_flops = n * d1 * (d1 + 1)
+    lazy = (cfg.q == 1)
+    # Per-swap state update as SURVEY counts it: read + write of P, V (= lower triangle of N) and B, R (= Z)
+    bytes_swap_alg = 2 * 4 * (d1 * d1 // 2) + 2 * 4 * d1 * m
+    ms_swap = 1e3 * phases["search"] / max(info["iters"], 1)
+    if lazy:
+        # delayed-update search: the per-swap kernel is the read-only pass over Z (w = Z [y1 y2]); upd_n holds its mean
+        # duration (HIP events inside the library, sampled once per batch of iterations)
+        k_bytes = 4 * d1 * m
+        k_name = "lazy_gemv_kernel (per-swap read-only pass over Z: w = Z [y1 y2])"
+        # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/lazy_gemv_cfg5_pmc.md), cfg5 only
+        traffic = 827.8e6 if a.config == "cfg5" else None
+    else:
+        k_bytes = 2 * 4 * (d1 * d1 // 2)
+        k_name = "update_N (bulk rank-2q update of the swept tableau, lower triangle)"
+        traffic = None
     out = {
         "metric": "OPT-30B fc2 layer prune time", "value": t_layer, "unit": "s", "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": 1e3 * t_layer, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16 inputs, f32 state, f64 accumulate", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: X {n}x{d1} {cfg.x_dtype}, W {d1}x{m} {cfg.w_dtype}, keep {cfg.k} of {cfg.p} groups "
                                f"(q={cfg.q}), {swaps} swaps, lambda = {cfg.lam_rel}*mean diag",
-                   "refresh_every": a.refresh_every},
+                   "refresh_every": a.refresh_every, "search": "delayed-update" if lazy else "eager"},
         "phases_s": phases,
         "swap_iterations": info["iters"], "accepted_swaps": info["accepted"],
         "swap_evals_per_s": info["iters"] * cfg.p / phases["search"] if phases["search"] > 0 else None,
-        "ms_per_swap": 1e3 * phases["search"] / max(info["iters"], 1),
+        "ms_per_swap": ms_swap,
         "gram_tflops_syrk": gram_flops / phases["gram"] / 1e12,
         "gram_tflops_full_equiv": 2 * n * d1 * d1 / phases["gram"] / 1e12,
         "objective": {"initial": info["obj0"], "final": info["obj"], "tracked": info["tracked"]},
-        "roofline": {"kernel": "update_N (bulk rank-2 update of the swept tableau, lower triangle)", "bound": "hbm",
-                     "achieved": bytes_n / upd_n / 1e9 if upd_n > 0 else None, "peak": 8000.0, "unit": "GB/s",
-                     "frac": bytes_n / upd_n / 1e9 / 8000.0 if upd_n > 0 else None, "traffic": None,
-                     "bytes_per_launch": bytes_n, "ms_per_launch": 1e3 * upd_n},
-        "roofline_update_Z": {"bound": "hbm", "achieved": bytes_z / upd_z / 1e9 if upd_z > 0 else None, "peak": 8000.0,
-                              "unit": "GB/s", "frac": bytes_z / upd_z / 1e9 / 8000.0 if upd_z > 0 else None,
-                              "bytes_per_launch": bytes_z, "ms_per_launch": 1e3 * upd_z},
-        "roofline_gram": {"bound": "mfma", "achieved": gram_flops / phases["gram"] / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
-                          "frac": gram_flops / phases["gram"] / 1e12 / 2500.0,
-                          "note": "algorithmic SYRK flops n*d1*(d1+1); the kernel issues about 2x that on diagonal tiles only"},
+        "roofline": {"kernel": k_name, "bound": "hbm", "achieved": k_bytes / upd_n / 1e9 if upd_n > 0 else None, "peak": 8000.0,
+                     "unit": "GB/s", "frac": k_bytes / upd_n / 1e9 / 8000.0 if upd_n > 0 else None, "traffic": traffic,
+                     "bytes_per_launch": k_bytes, "ms_per_launch": 1e3 * upd_n},
+        "swap_update_equivalent": {"note": "bytes an eager in-place up/downdate of P, B, V, R moves per swap, divided by the "
+                                           "measured time per swap (all kernels and amortised flushes); above the HBM peak "
+                                           "because swaps are applied 64 at a time on the matrix cores",
+                                   "bytes_per_swap": bytes_swap_alg, "achieved": bytes_swap_alg / ms_swap / 1e6, "unit": "GB/s",
+                                   "frac_of_hbm_peak": bytes_swap_alg / ms_swap / 1e6 / 8000.0},
+        "iteration_kernels_ms": 1e3 * upd_z,
+        "roofline_gram": {"kernel": "gram_bf16_kernel", "bound": "mfma", "achieved": gram_flops / phases["gram"] / 1e12,
+                          "peak": 2500.0, "unit": "TFLOP/s", "frac": gram_flops / phases["gram"] / 1e12 / 2500.0,
+                          "note": "algorithmic SYRK flops n*d1*(d1+1); the kernel issues 2x that on diagonal tiles only"},
     }
     s.close()
     del X
+    if a.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, inp.CONFIGS["cfg5"] if a.config == "cfg5" else cfg)
     print(json.dumps(out))
