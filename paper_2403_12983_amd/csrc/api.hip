@@ -16,6 +16,9 @@ using namespace osscar;
 namespace {
 
 constexpr int64_t XT_ROWS = 4096;   // calibration rows per sub-step of the generic (non-MFMA-bf16) Gram path
+constexpr int64_t PACK_ROWS = 16384;   // calibration rows repacked at a time on the bf16 MFMA path
+// staging buffer of the Gram phase: float32 X^T sub-step (generic path) or repacked bf16 rows (MFMA path)
+size_t gram_stage_bytes(int64_t d1) { return (size_t)std::max<int64_t>(d1 * XT_ROWS * 4, PACK_ROWS * ((d1 + 127) / 128 * 128) * 2); }
 constexpr int EV_SAMPLES = 64;
 
 size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
@@ -147,7 +150,7 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
     L.sel = cv.take<SelRec>((d1 + 31) / 32); L.counter = cv.take<int32_t>(4);
   }
   // scratch: the larger of the Gram phase and the init / refresh / backsolve phase
-  size_t gram_phase = align_up((size_t)d1 * d1 * 8) + align_up((size_t)d1 * m * 4) + align_up((size_t)d1 * XT_ROWS * 4) +
+  size_t gram_phase = align_up((size_t)d1 * d1 * 8) + align_up((size_t)d1 * m * 4) + align_up(gram_stage_bytes(d1)) +
                       align_up(gram_tile_entries(d1) * 8);
   size_t init_phase = 4 * align_up((size_t)kr * kr * 4) + 3 * align_up((size_t)kr * cr * 4) + align_up((size_t)cr * cr * 4) +
                       4 * align_up((size_t)kr * m * 4) + align_up((size_t)cr * m * 4) + 3 * align_up((size_t)kr * 64 * 4) + 4096;
@@ -389,7 +392,7 @@ osscar_status osscar_gram(osscar_ctx* c, const void* Xc, int64_t n_c, int64_t ld
   Carve cv(c->scratch);
   double* H64 = cv.take<double>((int64_t)d1 * d1);
   float* Wf = cv.take<float>((int64_t)d1 * m);
-  float* Xt = cv.take<float>((int64_t)d1 * XT_ROWS);
+  float* Xt = reinterpret_cast<float*>(cv.take<char>(gram_stage_bytes(d1)));
   const size_t tile_entries = gram_tile_entries(d1);
   int2* tile_buf = cv.take<int2>(tile_entries);
   if (c->phase != osscar_ctx::ACCUM) {   // first chunk of a layer
@@ -402,7 +405,9 @@ osscar_status osscar_gram(osscar_ctx* c, const void* Xc, int64_t n_c, int64_t ld
     const bool bf16 = c->desc.x_dtype == OSSCAR_BF16;
     const bool fast = bf16 && (d1 % 8 == 0) && (ldx % 8 == 0) && ((reinterpret_cast<uintptr_t>(Xc) & 15) == 0);
     if (fast) {
-      HIPCHK(c, launch_gram_bf16(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, s));
+      const bool unpacked = getenv("OSSCAR_GRAM_VARIANT") != nullptr;
+      if (unpacked) HIPCHK(c, launch_gram_bf16(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, s));
+      else HIPCHK(c, launch_gram_packed(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, Xt, PACK_ROWS, s));
     } else {
       const size_t esz = bf16 ? 2 : 4;
       for (int64_t r0 = 0; r0 < n_c; r0 += XT_ROWS) {

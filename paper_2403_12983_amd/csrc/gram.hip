@@ -275,6 +275,203 @@ hipError_t launch_gram_bf16(const void* Xc, int64_t n_c, int64_t ldx, int d1, do
 }
 
 // ------------------------------------------------------------------------------------------------
+// Packed path.  gram_pack_kernel rewrites a chunk of X once into the operand format of the MFMA: for every stage
+// (64 tokens) and every panel (128 columns) one contiguous 16 KB block of 16-byte packets, packet (kg, c) = the 8
+// tokens kg*8..kg*8+7 of column c, at slot kg*128 + c.  Tokens past the chunk and columns past d1 are zero.
+// gram_packed_kernel then copies whole blocks global -> LDS (linear, no transposes or masks in the hot loop) and
+// reads MFMA operands as single ds_read_b128: 16 neighbouring lanes read 16 neighbouring packets.
+// Accuracy: the MFMA accumulators are added (v_add_f32, round to nearest) to a second float32 register set every
+// `window` stages and restarted from zero, so the accumulation inside the matrix core never spans more than
+// window*64 tokens; the second set is added to the float64 H once per launch.
+// ------------------------------------------------------------------------------------------------
+constexpr int PK_SLOTS = 8 * 128;   // packets per (stage, panel)
+
+__global__ __launch_bounds__(256) void gram_pack_kernel(const uint16_t* __restrict__ X, int64_t n_c, int64_t ldx, int d1,
+                                                         int npanels, uint4* __restrict__ Xp) {
+  const int tid = threadIdx.x;
+  const int panel = blockIdx.x * 2 + (tid >> 7);
+  if (panel >= npanels) return;
+  const int kg = (tid & 127) >> 4, cg = tid & 15;
+  const int col = panel * 128 + cg * 8;
+  const bool live = col < d1;
+  const int64_t row0 = (int64_t)blockIdx.y * GBK + kg * 8;
+  const uint16_t* src = X + (live ? col : 0);
+  uint4 st[8];
+#pragma unroll
+  for (int r = 0; r < 8; r++) {
+    const int64_t row = row0 + r;
+    const int64_t rowc = row < n_c ? row : n_c - 1;
+    st[r] = *reinterpret_cast<const uint4*>(src + rowc * ldx);
+  }
+#pragma unroll
+  for (int r = 0; r < 8; r++)
+    if (!live || row0 + r >= n_c) st[r] = uint4{0u, 0u, 0u, 0u};
+  uint4* out = Xp + ((int64_t)blockIdx.y * npanels + panel) * PK_SLOTS + kg * 128 + cg * 8;
+#define OSSCAR_PACK_LO(F) uint4{(st[0].F & 0xFFFFu) | (st[1].F << 16), (st[2].F & 0xFFFFu) | (st[3].F << 16), \
+                                (st[4].F & 0xFFFFu) | (st[5].F << 16), (st[6].F & 0xFFFFu) | (st[7].F << 16)}
+#define OSSCAR_PACK_HI(F) uint4{(st[0].F >> 16) | (st[1].F & 0xFFFF0000u), (st[2].F >> 16) | (st[3].F & 0xFFFF0000u), \
+                                (st[4].F >> 16) | (st[5].F & 0xFFFF0000u), (st[6].F >> 16) | (st[7].F & 0xFFFF0000u)}
+  out[0] = OSSCAR_PACK_LO(x); out[1] = OSSCAR_PACK_HI(x);
+  out[2] = OSSCAR_PACK_LO(y); out[3] = OSSCAR_PACK_HI(y);
+  out[4] = OSSCAR_PACK_LO(z); out[5] = OSSCAR_PACK_HI(z);
+  out[6] = OSSCAR_PACK_LO(w); out[7] = OSSCAR_PACK_HI(w);
+#undef OSSCAR_PACK_LO
+#undef OSSCAR_PACK_HI
+}
+
+__global__ __launch_bounds__(256, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void gram_packed_kernel(const uint4* __restrict__ Xp, int nstages, int npanels, int d1,
+                                                             double* __restrict__ H64, const int2* __restrict__ tile_list,
+                                                             int stages_per_split, int window) {
+  constexpr int WT = 2, TS = 128;
+  extern __shared__ uint4 lds[];             // [2 buffers][2 panels][PK_SLOTS]
+  const int2 tile = tile_list[blockIdx.x];
+  if (tile.x < 0) return;
+  const int tm = tile.x, tn = tile.y;
+  const bool diag = (tm == tn);
+  const int i0 = tm * TS, j0 = tn * TS;
+  const int s_begin = blockIdx.y * stages_per_split;
+  const int s_end = (s_begin + stages_per_split < nstages) ? s_begin + stages_per_split : nstages;
+  if (s_begin >= s_end) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  f16v acc[WT][WT], acc2[WT][WT];
+#pragma unroll
+  for (int a = 0; a < WT; a++)
+#pragma unroll
+    for (int b = 0; b < WT; b++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) { acc[a][b][r] = 0.f; acc2[a][b][r] = 0.f; }
+
+  const int64_t sstride = (int64_t)npanels * PK_SLOTS;
+  const uint4* ga = Xp + (int64_t)tm * PK_SLOTS + tid;
+  const uint4* gb = Xp + (int64_t)tn * PK_SLOTS + tid;
+  uint4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3;
+  rb0 = rb1 = rb2 = rb3 = uint4{0u, 0u, 0u, 0u};
+#define OSSCAR_GLOAD(st)                                                                         \
+  {                                                                                              \
+    const uint4* pa_ = ga + (st) * sstride;                                                      \
+    ra0 = pa_[0]; ra1 = pa_[256]; ra2 = pa_[512]; ra3 = pa_[768];                                \
+    if (!diag) {                                                                                 \
+      const uint4* pb_ = gb + (st) * sstride;                                                    \
+      rb0 = pb_[0]; rb1 = pb_[256]; rb2 = pb_[512]; rb3 = pb_[768];                              \
+    }                                                                                            \
+  }
+#define OSSCAR_SSTORE(buf)                                                                       \
+  {                                                                                              \
+    uint4* la_ = lds + ((buf) * 2 + 0) * PK_SLOTS + tid;                                         \
+    la_[0] = ra0; la_[256] = ra1; la_[512] = ra2; la_[768] = ra3;                                \
+    if (!diag) {                                                                                 \
+      uint4* lb_ = lds + ((buf) * 2 + 1) * PK_SLOTS + tid;                                       \
+      lb_[0] = rb0; lb_[256] = rb1; lb_[512] = rb2; lb_[768] = rb3;                              \
+    }                                                                                            \
+  }
+  const int oa = wm * 64 + (lane & 31), ob = wn * 64 + (lane & 31);
+
+  OSSCAR_GLOAD(s_begin);
+  OSSCAR_SSTORE(0);
+  __syncthreads();
+  int in_window = 0;
+  int buf = 0;
+  for (int st = s_begin; st < s_end; st++) {
+    const bool more = (st + 1 < s_end);
+    if (more) OSSCAR_GLOAD(st + 1);
+    const uint4* pa = lds + (buf * 2 + 0) * PK_SLOTS;
+    const uint4* pb = diag ? pa : lds + (buf * 2 + 1) * PK_SLOTS;
+#pragma unroll
+    for (int ks = 0; ks < GBK / 16; ks++) {
+      const int kgo = (ks * 2 + (lane >> 5)) * 128;
+      bf8 fa[WT], fb[WT];
+#pragma unroll
+      for (int a = 0; a < WT; a++) {
+        uint4 v = pa[kgo + oa + a * 32];
+        fa[a] = *reinterpret_cast<bf8*>(&v);
+      }
+#pragma unroll
+      for (int b = 0; b < WT; b++) {
+        uint4 v = pb[kgo + ob + b * 32];
+        fb[b] = *reinterpret_cast<bf8*>(&v);
+      }
+#pragma unroll
+      for (int a = 0; a < WT; a++)
+#pragma unroll
+        for (int b = 0; b < WT; b++)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+    }
+    if (++in_window >= window && more) {
+      in_window = 0;
+#pragma unroll
+      for (int a = 0; a < WT; a++)
+#pragma unroll
+        for (int b = 0; b < WT; b++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) { acc2[a][b][r] += acc[a][b][r]; acc[a][b][r] = 0.f; }
+    }
+    if (more) OSSCAR_SSTORE(buf ^ 1);
+    __syncthreads();
+    buf ^= 1;
+  }
+#undef OSSCAR_GLOAD
+#undef OSSCAR_SSTORE
+
+  // C layout of the 32 x 32 MFMA: register r = rr*4 + r3 holds row rr*8 + (lane/32)*4 + r3, column lane%32
+  // (the opaque copy of d1 keeps the compiler from computing the 64 output addresses ahead of the main loop)
+  int d1v = d1;
+  asm volatile("" : "+s"(d1v));
+  const int rbase = i0 + wm * 64 + (lane >> 5) * 4;
+  const int cbase = j0 + wn * 64 + (lane & 31);
+  double* hbase = H64 + (int64_t)rbase * d1v + cbase;
+#pragma unroll
+  for (int a = 0; a < WT; a++)
+#pragma unroll
+    for (int rr = 0; rr < 4; rr++) {
+#pragma unroll
+      for (int r3 = 0; r3 < 4; r3++) {
+        const int ro = a * 32 + rr * 8 + r3;
+        double* hrow = hbase + (int64_t)ro * d1v;
+        const bool rok = (rbase + ro < d1);
+#pragma unroll
+        for (int b = 0; b < WT; b++)
+          if (rok && cbase + b * 32 < d1)
+            unsafeAtomicAdd(hrow + b * 32, (double)acc[a][b][rr * 4 + r3] + (double)acc2[a][b][rr * 4 + r3]);
+      }
+      asm volatile("" ::: "memory");
+    }
+}
+
+hipError_t launch_gram_packed(const void* Xc, int64_t n_c, int64_t ldx, int d1, double* H64, int2* tile_buf,
+                              size_t tile_buf_entries, void* pack_buf, int64_t pack_rows, hipStream_t s) {
+  if (n_c <= 0) return hipSuccess;
+  if (pack_rows < GBK || pack_rows % GBK) return hipErrorInvalidValue;
+  const int npanels = (d1 + 127) / 128;
+  std::vector<int2> tiles;
+  build_tile_list(npanels, tiles);
+  if (tiles.size() > tile_buf_entries) return hipErrorInvalidValue;
+  hipError_t e = hipMemcpyAsync(tile_buf, tiles.data(), tiles.size() * sizeof(int2), hipMemcpyHostToDevice, s);
+  if (e != hipSuccess) return e;
+  e = hipStreamSynchronize(s);   // the host vector dies at return
+  if (e != hipSuccess) return e;
+  const int ntiles = npanels * (npanels + 1) / 2;
+  const int window = env_int("OSSCAR_GRAM_WINDOW", 16);
+  const size_t shmem = (size_t)2 * 2 * PK_SLOTS * 16;
+  for (int64_t r0 = 0; r0 < n_c; r0 += pack_rows) {
+    const int64_t nr = std::min<int64_t>(pack_rows, n_c - r0);
+    const int nstages = (int)((nr + GBK - 1) / GBK);
+    const uint16_t* src = reinterpret_cast<const uint16_t*>(Xc) + r0 * ldx;
+    hipLaunchKernelGGL(gram_pack_kernel, dim3((npanels + 1) / 2, nstages), dim3(256), 0, s, src, nr, ldx, d1, npanels,
+                       reinterpret_cast<uint4*>(pack_buf));
+    int splits = 1;
+    if (ntiles < 1024) splits = std::min(nstages, (2048 + ntiles - 1) / ntiles);
+    int per = (nstages + splits - 1) / splits;
+    per = std::max(per, std::min(nstages, 8));
+    splits = (nstages + per - 1) / per;
+    hipLaunchKernelGGL(gram_packed_kernel, dim3((unsigned)tiles.size(), splits), dim3(256), shmem, s,
+                       reinterpret_cast<const uint4*>(pack_buf), nstages, npanels, d1, H64, tile_buf, per, window);
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
 // Helpers of the generic (any shape, float32 or bfloat16 input) path and of finalize.
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
