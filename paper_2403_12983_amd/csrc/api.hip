@@ -407,7 +407,10 @@ osscar_status osscar_gram(osscar_ctx* c, const void* Xc, int64_t n_c, int64_t ld
     if (fast) {
       const bool unpacked = getenv("OSSCAR_GRAM_VARIANT") != nullptr;
       if (unpacked) HIPCHK(c, launch_gram_bf16(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, s));
-      else HIPCHK(c, launch_gram_packed(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, Xt, PACK_ROWS, s));
+      else {
+        const char* pr = getenv("OSSCAR_GRAM_PACK_ROWS");
+        HIPCHK(c, launch_gram_packed(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, Xt, pr ? std::min<int64_t>(PACK_ROWS, atoi(pr)) : PACK_ROWS, s));
+      }
     } else {
       const size_t esz = bf16 ? 2 : 4;
       for (int64_t r0 = 0; r0 < n_c; r0 += XT_ROWS) {

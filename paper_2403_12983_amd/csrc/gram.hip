@@ -207,14 +207,21 @@ __global__ __launch_bounds__(256, ((WT == 2 && !REGFOLD) ? 2 : 1)) void gram_bf1
   fold(true);
 }
 
+static int env_int(const char* name, int dflt) {
+  const char* e = getenv(name);
+  return e ? atoi(e) : dflt;
+}
+
 // Tile order: strips of 4 tile rows go to the XCDs in turn (block index modulo 8 selects the XCD); within a strip
 // the tiles are walked in 4 x 8 blocks.  Lists are padded with (-1, -1) to equal length.
-static void build_tile_list(int tm_count, std::vector<int2>& out) {
-  constexpr int NX = 8, RB = 4, CB = 8;
+static void build_tile_list(int tm_count, std::vector<int2>& out, int RB = 4, int CB = 8) {
+  constexpr int NX = 8;
   std::vector<std::vector<int2>> lists(NX);
   int strips = (tm_count + RB - 1) / RB;
   for (int sidx = 0; sidx < strips; sidx++) {
-    std::vector<int2>& L = lists[sidx % NX];
+    // boustrophedon deal: strips grow with the row index, so alternate the direction to balance the XCDs
+    const int turn = sidx / NX, pos = sidx % NX;
+    std::vector<int2>& L = lists[(turn & 1) ? NX - 1 - pos : pos];
     int r0 = sidx * RB, r1 = std::min(tm_count, r0 + RB);
     for (int c0 = 0; c0 < r1; c0 += CB)
       for (int r = r0; r < r1; r++)
@@ -225,11 +232,6 @@ static void build_tile_list(int tm_count, std::vector<int2>& out) {
   out.assign(len * NX, int2{-1, -1});
   for (int x = 0; x < NX; x++)
     for (size_t i = 0; i < lists[x].size(); i++) out[i * NX + x] = lists[x][i];
-}
-
-static int env_int(const char* name, int dflt) {
-  const char* e = getenv(name);
-  return e ? atoi(e) : dflt;
 }
 
 template <int WT, bool REGFOLD>
@@ -445,7 +447,7 @@ hipError_t launch_gram_packed(const void* Xc, int64_t n_c, int64_t ldx, int d1, 
   if (pack_rows < GBK || pack_rows % GBK) return hipErrorInvalidValue;
   const int npanels = (d1 + 127) / 128;
   std::vector<int2> tiles;
-  build_tile_list(npanels, tiles);
+  build_tile_list(npanels, tiles, env_int("OSSCAR_GRAM_RB", 4), env_int("OSSCAR_GRAM_CB", 8));
   if (tiles.size() > tile_buf_entries) return hipErrorInvalidValue;
   hipError_t e = hipMemcpyAsync(tile_buf, tiles.data(), tiles.size() * sizeof(int2), hipMemcpyHostToDevice, s);
   if (e != hipSuccess) return e;
