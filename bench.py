@@ -188,7 +188,7 @@ def main():
                                    "bytes_per_swap": bytes_swap_alg, "achieved": bytes_swap_alg / ms_swap / 1e6, "unit": "GB/s",
                                    "frac_of_hbm_peak": bytes_swap_alg / ms_swap / 1e6 / 8000.0},
         "iteration_kernels_ms": 1e3 * upd_z,
-        "roofline_gram": {"kernel": "gram_bf16_kernel", "bound": "mfma", "achieved": gram_flops / phases["gram"] / 1e12,
+        "roofline_gram": {"kernel": "gram_packed_kernel (+ gram_pack_kernel, whole Gram phase)", "bound": "mfma", "achieved": gram_flops / phases["gram"] / 1e12,
                           "peak": 2500.0, "unit": "TFLOP/s", "frac": gram_flops / phases["gram"] / 1e12 / 2500.0,
                           "note": "algorithmic SYRK flops n*d1*(d1+1); the kernel issues 2x that on diagonal tiles only"},
     }

@@ -405,12 +405,7 @@ osscar_status osscar_gram(osscar_ctx* c, const void* Xc, int64_t n_c, int64_t ld
     const bool bf16 = c->desc.x_dtype == OSSCAR_BF16;
     const bool fast = bf16 && (d1 % 8 == 0) && (ldx % 8 == 0) && ((reinterpret_cast<uintptr_t>(Xc) & 15) == 0);
     if (fast) {
-      const bool unpacked = getenv("OSSCAR_GRAM_VARIANT") != nullptr;
-      if (unpacked) HIPCHK(c, launch_gram_bf16(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, s));
-      else {
-        const char* pr = getenv("OSSCAR_GRAM_PACK_ROWS");
-        HIPCHK(c, launch_gram_packed(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, Xt, pr ? std::min<int64_t>(PACK_ROWS, atoi(pr)) : PACK_ROWS, s));
-      }
+      HIPCHK(c, launch_gram_packed(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, Xt, PACK_ROWS, s));
     } else {
       const size_t esz = bf16 ? 2 : 4;
       for (int64_t r0 = 0; r0 < n_c; r0 += XT_ROWS) {

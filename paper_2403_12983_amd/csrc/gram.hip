@@ -1,19 +1,14 @@
 // Quadratic-form construction (Section 3, dense-layer paragraph): H = X^T X accumulated over chunks of
 // calibration rows, then the ridge, G = H W and c0.
 //
-// gram_bf16_kernel: SYRK-style product on the lower-triangle tiles of H with v_mfma_f32_32x32x16_bf16.
-//   Both MFMA operands are column panels of the same row-major chunk Xc (rows = tokens), so every lane
-//   needs 8 consecutive TOKENS of one column in a register quad.  Threads load 8 x 8 blocks (8 tokens x 8
-//   columns, 16-byte row segments), transpose them in registers and store one 16-byte packet per column
-//   into LDS; MFMA operands are then single ds_read_b128.  The packet of (token group kg, column c) lives
-//   in slot kg*8*S + (c % 8)*S + c/8 with S = TS/8 + 2 (= 2 mod 16).  The LDS serves 16 lanes x 16 bytes per
-//   clock from 64 banks; with this stride both the transposing writes (16 neighbouring lanes = 16
-//   neighbouring column groups, same residue) and the operand reads (16 neighbouring lanes = 16
-//   neighbouring columns = 8 residues x 2 groups) touch 16 different bank quads.
-//   Accuracy: the MFMA accumulates in float32 with round-to-nearest; the accumulators are added to the
-//   float64 H (atomics) every `flush_rows` tokens, so at most that many products are summed in float32.
+// gram_pack_kernel + gram_packed_kernel: SYRK-style product on the lower-triangle tiles of H with
+//   v_mfma_f32_32x32x16_bf16.  Both MFMA operands are column panels of the same row-major chunk Xc (rows =
+//   tokens), so every lane needs 8 consecutive TOKENS of one column in a register quad: the chunk is first
+//   rewritten once into that order (8 x 8 register transposes, HBM-bound, a few percent of the product's
+//   time), and the product kernel then only copies contiguous blocks into LDS and issues MFMAs.
 //   Tile order: the host lays the tiles out so that the workgroups that run together on one XCD (block
-//   index modulo 8) form 4 x 8 blocks of tiles sharing their 12 column panels in that XCD's L2.
+//   index modulo 8) form 4 x 8 blocks of tiles sharing their 12 column panels in that XCD's L2, and deals
+//   the strips of tile rows to the XCDs in alternating direction so that all eight get equal work.
 #include "internal.h"
 #include <cstdlib>
 #include <vector>
@@ -25,197 +20,10 @@ typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
 
 constexpr int GBK = 64;            // tokens per LDS stage
 
-template <int WT, bool REGFOLD>  // WT x WT MFMA tiles per wave; workgroup tile = 64*WT; REGFOLD: float64 accumulators in registers
-__global__ __launch_bounds__(256, ((WT == 2 && !REGFOLD) ? 2 : 1)) void gram_bf16_kernel(
-    const uint16_t* __restrict__ X, int64_t n_c, int64_t ldx, int d1, double* __restrict__ H64,
-    const int2* __restrict__ tile_list, int64_t rows_per_split, int flush_rows) {
-  constexpr int TS = 64 * WT;
-  constexpr int CG = TS / 8;                 // column groups of 8 per panel
-  constexpr int S = CG + 2;                  // slot stride between column residues (2 mod 16)
-  constexpr int PANEL = 8 * 8 * S;           // slots (16 bytes) per panel per buffer
-  constexpr int U = CG / 16;                 // 8 x 8 blocks per thread per stage (both panels together)
-  extern __shared__ uint4 lds[];             // [2 buffers][2 panels][PANEL]
-
-  const int2 tile = tile_list[blockIdx.x];
-  if (tile.x < 0) return;
-  const int tm = tile.x, tn = tile.y;
-  const bool diag = (tm == tn);
-  const int i0 = tm * TS, j0 = tn * TS;
-  const int64_t r_begin = (int64_t)blockIdx.y * rows_per_split;
-  const int64_t r_end = (r_begin + rows_per_split < n_c) ? r_begin + rows_per_split : n_c;
-  if (r_begin >= r_end) return;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-
-  f16v acc[WT][WT];
-  double acc64[REGFOLD ? WT : 1][REGFOLD ? WT : 1][16];
-#pragma unroll
-  for (int a = 0; a < WT; a++)
-#pragma unroll
-    for (int b = 0; b < WT; b++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) { acc[a][b][r] = 0.f; if (REGFOLD) acc64[a][b][r] = 0.0; }
-
-  // this thread's 8 x 8 blocks: unit u -> (panel, kg, cg).  Loads are unconditional (addresses clamped into the
-  // chunk, values zeroed afterwards) so that the 8*U loads of a stage are issued back to back.
-  int u_panel[U], u_kg[U], u_cg[U];
-  bool u_live[U];
-  const uint16_t* u_ptr[U];
-#pragma unroll
-  for (int u = 0; u < U; u++) {
-    const int blk = tid + 256 * u;
-    u_panel[u] = blk / (8 * CG);
-    const int rem = blk % (8 * CG);
-    u_kg[u] = rem / CG; u_cg[u] = rem % CG;
-    const int col = (u_panel[u] == 0 ? i0 : j0) + u_cg[u] * 8;
-    u_live[u] = (col < d1);
-    u_ptr[u] = X + (u_live[u] ? col : 0);
-  }
-  uint4 stage[U][8];
-  const int64_t r_last = r_end - 1;
-
-  auto gload = [&](int64_t r0) {
-#pragma unroll
-    for (int u = 0; u < U; u++) {
-      if (u_panel[u] == 1 && diag) continue;          // uniform per workgroup half
-#pragma unroll
-      for (int r = 0; r < 8; r++) {
-        const int64_t row = r0 + u_kg[u] * 8 + r;
-        const int64_t rowc = row < r_last ? row : r_last;
-        stage[u][r] = *reinterpret_cast<const uint4*>(u_ptr[u] + rowc * ldx);
-      }
-    }
-  };
-  // zero what the clamped loads duplicated: tokens past the end of the range, columns past d1 (rare, uniform test)
-  const bool ragged_cols = (i0 + TS > d1) || (j0 + TS > d1);
-  auto mask_stage = [&](int64_t r0) {
-    if (!ragged_cols && r0 + GBK <= r_end) return;
-#pragma unroll
-    for (int u = 0; u < U; u++)
-#pragma unroll
-      for (int r = 0; r < 8; r++) {
-        const bool ok = u_live[u] && (r0 + u_kg[u] * 8 + r < r_end);
-        if (!ok) stage[u][r] = uint4{0u, 0u, 0u, 0u};
-      }
-  };
-  auto sstore = [&](int buf) {
-#pragma unroll
-    for (int u = 0; u < U; u++) {
-      if (u_panel[u] == 1 && diag) continue;
-      uint4* base = lds + (buf * 2 + u_panel[u]) * PANEL + u_kg[u] * (8 * S) + u_cg[u];
-#define OSSCAR_PACK_LO(F) uint4{(stage[u][0].F & 0xFFFFu) | (stage[u][1].F << 16), (stage[u][2].F & 0xFFFFu) | (stage[u][3].F << 16), \
-                                (stage[u][4].F & 0xFFFFu) | (stage[u][5].F << 16), (stage[u][6].F & 0xFFFFu) | (stage[u][7].F << 16)}
-#define OSSCAR_PACK_HI(F) uint4{(stage[u][0].F >> 16) | (stage[u][1].F & 0xFFFF0000u), (stage[u][2].F >> 16) | (stage[u][3].F & 0xFFFF0000u), \
-                                (stage[u][4].F >> 16) | (stage[u][5].F & 0xFFFF0000u), (stage[u][6].F >> 16) | (stage[u][7].F & 0xFFFF0000u)}
-      base[0 * S] = OSSCAR_PACK_LO(x); base[1 * S] = OSSCAR_PACK_HI(x);
-      base[2 * S] = OSSCAR_PACK_LO(y); base[3 * S] = OSSCAR_PACK_HI(y);
-      base[4 * S] = OSSCAR_PACK_LO(z); base[5 * S] = OSSCAR_PACK_HI(z);
-      base[6 * S] = OSSCAR_PACK_LO(w); base[7 * S] = OSSCAR_PACK_HI(w);
-#undef OSSCAR_PACK_LO
-#undef OSSCAR_PACK_HI
-    }
-  };
-  auto fold = [&](bool final) {
-    if (REGFOLD && !final) {
-#pragma unroll
-      for (int a = 0; a < WT; a++)
-#pragma unroll
-        for (int b = 0; b < WT; b++)
-#pragma unroll
-          for (int r = 0; r < 16; r++) { acc64[a][b][r] += (double)acc[a][b][r]; acc[a][b][r] = 0.f; }
-      return;
-    }
-    // the opaque copy of d1 keeps the compiler from hoisting the 16*WT*WT output addresses out of the main loop
-    int d1v = d1;
-    asm volatile("" : "+s"(d1v));
-    const int rbase = i0 + wm * (32 * WT) + (lane >> 5) * 4;
-    const int cbase = j0 + wn * (32 * WT) + (lane & 31);
-    double* hbase = H64 + (int64_t)rbase * d1v + cbase;
-#pragma unroll
-    for (int a = 0; a < WT; a++) {
-#pragma unroll
-      for (int rr = 0; rr < 4; rr++) {
-#pragma unroll
-        for (int r3 = 0; r3 < 4; r3++) {
-          // C layout of the 32 x 32 MFMA: register r = rr*4 + r3 holds row rr*8 + (lane/32)*4 + r3, column lane%32
-          const int ro = a * 32 + rr * 8 + r3;
-          double* hrow = hbase + (int64_t)ro * d1v;
-          const bool rok = (rbase + ro < d1);
-#pragma unroll
-          for (int b = 0; b < WT; b++) {
-            double v = (double)acc[a][b][rr * 4 + r3];
-            if (REGFOLD) v += acc64[a][b][rr * 4 + r3];
-            acc[a][b][rr * 4 + r3] = 0.f;
-            if (rok && cbase + b * 32 < d1) {
-              unsafeAtomicAdd(hrow + b * 32, v);
-            }
-          }
-        }
-        asm volatile("" ::: "memory");
-      }
-    }
-  };
-
-  // operand slots of this lane within a token group: column -> (col % 8) * S + col / 8
-  int sa[WT], sb[WT];
-#pragma unroll
-  for (int a = 0; a < WT; a++) {
-    const int ca = wm * (32 * WT) + a * 32 + (lane & 31);
-    const int cb = wn * (32 * WT) + a * 32 + (lane & 31);
-    sa[a] = (ca & 7) * S + (ca >> 3);
-    sb[a] = (cb & 7) * S + (cb >> 3);
-  }
-
-  gload(r_begin);
-  mask_stage(r_begin);
-  sstore(0);
-  __syncthreads();
-  int since_flush = 0;
-  int buf = 0;
-  for (int64_t r0 = r_begin; r0 < r_end; r0 += GBK) {
-    const bool more = (r0 + GBK < r_end);
-    if (more) gload(r0 + GBK);
-    const uint4* pa = lds + (buf * 2 + 0) * PANEL;
-    const uint4* pb = diag ? pa : lds + (buf * 2 + 1) * PANEL;
-#pragma unroll
-    for (int ks = 0; ks < GBK / 16; ks++) {
-      const int kgo = (ks * 2 + (lane >> 5)) * (8 * S);
-      bf8 fa[WT], fb[WT];
-#pragma unroll
-      for (int a = 0; a < WT; a++) {
-        uint4 v = pa[kgo + sa[a]];
-        fa[a] = *reinterpret_cast<bf8*>(&v);
-      }
-#pragma unroll
-      for (int b = 0; b < WT; b++) {
-        uint4 v = pb[kgo + sb[b]];
-        fb[b] = *reinterpret_cast<bf8*>(&v);
-      }
-#pragma unroll
-      for (int a = 0; a < WT; a++)
-#pragma unroll
-        for (int b = 0; b < WT; b++)
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
-    }
-    since_flush += GBK;
-    if (since_flush >= flush_rows && more) { fold(false); since_flush = 0; }
-    if (more) { mask_stage(r0 + GBK); sstore(buf ^ 1); }
-    __syncthreads();
-    buf ^= 1;
-  }
-  fold(true);
-}
-
-static int env_int(const char* name, int dflt) {
-  const char* e = getenv(name);
-  return e ? atoi(e) : dflt;
-}
-
 // Tile order: strips of 4 tile rows go to the XCDs in turn (block index modulo 8 selects the XCD); within a strip
 // the tiles are walked in 4 x 8 blocks.  Lists are padded with (-1, -1) to equal length.
-static void build_tile_list(int tm_count, std::vector<int2>& out, int RB = 4, int CB = 8) {
-  constexpr int NX = 8;
+static void build_tile_list(int tm_count, std::vector<int2>& out) {
+  constexpr int NX = 8, RB = 4, CB = 8;
   std::vector<std::vector<int2>> lists(NX);
   int strips = (tm_count + RB - 1) / RB;
   for (int sidx = 0; sidx < strips; sidx++) {
@@ -234,50 +42,8 @@ static void build_tile_list(int tm_count, std::vector<int2>& out, int RB = 4, in
     for (size_t i = 0; i < lists[x].size(); i++) out[i * NX + x] = lists[x][i];
 }
 
-template <int WT, bool REGFOLD>
-static hipError_t launch_gram_wt(const void* Xc, int64_t n_c, int64_t ldx, int d1, double* H64, int2* tile_buf,
-                                 size_t tile_buf_entries, hipStream_t s) {
-  constexpr int TS = 64 * WT, CG = TS / 8, S = CG + 2, PANEL = 8 * 8 * S;
-  const int tm = (d1 + TS - 1) / TS;
-  std::vector<int2> tiles;
-  build_tile_list(tm, tiles);
-  if (tiles.size() > tile_buf_entries) return hipErrorInvalidValue;
-  hipError_t e = hipMemcpyAsync(tile_buf, tiles.data(), tiles.size() * sizeof(int2), hipMemcpyHostToDevice, s);
-  if (e != hipSuccess) return e;
-  e = hipStreamSynchronize(s);   // the host vector dies at return
-  if (e != hipSuccess) return e;
-  const int ntiles = tm * (tm + 1) / 2;
-  int splits = 1;
-  if (ntiles < 1024) splits = (2048 + ntiles - 1) / ntiles;
-  int64_t rows_per = (n_c + splits - 1) / splits;
-  rows_per = std::max<int64_t>((rows_per + GBK - 1) / GBK * GBK, 512);
-  splits = (int)((n_c + rows_per - 1) / rows_per);
-  // float32 accumulation window: at most 8192 tokens, and at least 16 windows per split so that the rounding of the
-  // windows averages out (relative error of an entry of H stays below float32 rounding); never below 1024
-  int64_t auto_flush = REGFOLD ? 1024 : std::min<int64_t>(8192, std::max<int64_t>(1024, rows_per / 16 / GBK * GBK));
-  const int flush_rows = env_int("OSSCAR_GRAM_FLUSH", (int)auto_flush);
-  const size_t shmem = (size_t)2 * 2 * PANEL * 16;
-  auto kern = gram_bf16_kernel<WT, REGFOLD>;
-  if (shmem > 65536) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-    if (e != hipSuccess) return e;
-  }
-  hipLaunchKernelGGL(kern, dim3((unsigned)tiles.size(), splits), dim3(256), shmem, s, reinterpret_cast<const uint16_t*>(Xc), n_c,
-                     ldx, d1, H64, tile_buf, rows_per, flush_rows);
-  return hipGetLastError();
-}
-
-hipError_t launch_gram_bf16(const void* Xc, int64_t n_c, int64_t ldx, int d1, double* H64, int2* tile_buf,
-                            size_t tile_buf_entries, hipStream_t s) {
-  if (n_c <= 0) return hipSuccess;
-  const int variant = env_int("OSSCAR_GRAM_VARIANT", 3);
-  if (variant == 4) return launch_gram_wt<4, false>(Xc, n_c, ldx, d1, H64, tile_buf, tile_buf_entries, s);
-  if (variant == 3) return launch_gram_wt<2, true>(Xc, n_c, ldx, d1, H64, tile_buf, tile_buf_entries, s);
-  return launch_gram_wt<2, false>(Xc, n_c, ldx, d1, H64, tile_buf, tile_buf_entries, s);
-}
-
 // ------------------------------------------------------------------------------------------------
-// Packed path.  gram_pack_kernel rewrites a chunk of X once into the operand format of the MFMA: for every stage
+// gram_pack_kernel rewrites a chunk of X once into the operand format of the MFMA: for every stage
 // (64 tokens) and every panel (128 columns) one contiguous 16 KB block of 16-byte packets, packet (kg, c) = the 8
 // tokens kg*8..kg*8+7 of column c, at slot kg*128 + c.  Tokens past the chunk and columns past d1 are zero.
 // gram_packed_kernel then copies whole blocks global -> LDS (linear, no transposes or masks in the hot loop) and
@@ -447,14 +213,14 @@ hipError_t launch_gram_packed(const void* Xc, int64_t n_c, int64_t ldx, int d1, 
   if (pack_rows < GBK || pack_rows % GBK) return hipErrorInvalidValue;
   const int npanels = (d1 + 127) / 128;
   std::vector<int2> tiles;
-  build_tile_list(npanels, tiles, env_int("OSSCAR_GRAM_RB", 4), env_int("OSSCAR_GRAM_CB", 8));
+  build_tile_list(npanels, tiles);
   if (tiles.size() > tile_buf_entries) return hipErrorInvalidValue;
   hipError_t e = hipMemcpyAsync(tile_buf, tiles.data(), tiles.size() * sizeof(int2), hipMemcpyHostToDevice, s);
   if (e != hipSuccess) return e;
   e = hipStreamSynchronize(s);   // the host vector dies at return
   if (e != hipSuccess) return e;
   const int ntiles = npanels * (npanels + 1) / 2;
-  const int window = env_int("OSSCAR_GRAM_WINDOW", 16);
+  const int window = 16;   // 1024 tokens per MFMA accumulation window
   const size_t shmem = (size_t)2 * 2 * PK_SLOTS * 16;
   for (int64_t r0 = 0; r0 < n_c; r0 += pack_rows) {
     const int64_t nr = std::min<int64_t>(pack_rows, n_c - r0);

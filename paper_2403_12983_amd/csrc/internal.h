@@ -25,13 +25,11 @@ struct GemmArgs {
 hipError_t launch_gemm_f64acc(const GemmArgs& a, hipStream_t s);
 
 // ----------------------------------------------------------------------------------------------
-// gram.hip : H64 (+)= Xc^T Xc on the lower-triangle tiles
+// gram.hip : H64 (+)= Xc^T Xc on the lower-triangle tiles (bf16 X, d1 % 8 == 0, ldx % 8 == 0, 16-byte aligned)
 // ----------------------------------------------------------------------------------------------
+// Repacks `pack_rows`-token chunks of Xc into MFMA operand order in pack_buf (pack_rows * 128*ceil(d1/128) * 2 bytes)
+// and accumulates them into H64.
 // tile_buf: device scratch for the tile schedule, tile_buf_entries >= 8 * (ceil(d1/128)^2 / 2 + ceil(d1/128) + 8)
-hipError_t launch_gram_bf16(const void* Xc, int64_t n_c, int64_t ldx, int d1, double* H64, int2* tile_buf,
-                            size_t tile_buf_entries, hipStream_t s);
-// Packed path: repacks `pack_rows`-token chunks of Xc into MFMA operand order in pack_buf (pack_rows * 128*ceil(d1/128) * 2
-// bytes) and accumulates them into H64.
 hipError_t launch_gram_packed(const void* Xc, int64_t n_c, int64_t ldx, int d1, double* H64, int2* tile_buf,
                               size_t tile_buf_entries, void* pack_buf, int64_t pack_rows, hipStream_t s);
 hipError_t launch_transpose_to_f32(const void* X, int is_bf16, int64_t rows, int64_t cols, int64_t ldx, float* Xt,
