@@ -335,6 +335,61 @@ def local_search(H: np.ndarray, G: np.ndarray, c0: float, groups0: Sequence[int]
 
 
 # --------------------------------------------------------------------------------------------------
+# Nested schedule from the dense layer (Algorithm 1 with S_0 empty and t_i = p_i = t-hat: Section 4.2;
+# Appendix B.1 uses t-hat = 2 for channels and heads, 10 for the intermediate dimension of FFN layers)
+# --------------------------------------------------------------------------------------------------
+@dataclasses.dataclass
+class GreedyRecord:
+    removed: List[int]     # groups pruned in this iteration, cheapest first
+    costs: List[float]     # their removal scores at the state the iteration started from
+    gap: float             # relative gap between the costliest chosen score and the cheapest one left out
+    deficit: float         # (costliest chosen - the oracle's own t-th smallest) / |that|; 0 unless choices were forced
+    obj_after: float
+
+
+@dataclasses.dataclass
+class GreedyResult:
+    support: List[int]
+    obj_final: float       # tracked through the f updates (obj of the dense layer is 0)
+    trace: List[GreedyRecord]
+    state: State
+
+
+def greedy_from_dense(H: np.ndarray, G: np.ndarray, c0: float, p: int, q: int, k: int, t_hat: int,
+                      follow: Optional[Sequence[Sequence[int]]] = None) -> GreedyResult:
+    """Starts from the dense layer (every group kept: P = H^-1, What = H^-1 G) and prunes t_hat groups
+    per iteration until k are left (the last iteration takes what remains).  With p-hat = t-hat nothing
+    re-enters (s1 = 0), so an iteration only needs the impact of removing each kept group (eq. (impact),
+    closed form of Case 1), all evaluated at the state the iteration starts from; the t_hat cheapest go
+    (lowest index on ties) and the inverse and the weights follow by Case 1.
+
+    follow: optional list of per-iteration removal lists to apply instead of the oracle's own choice."""
+    if t_hat < 1:
+        raise ValueError("t_hat must be >= 1")
+    st = init_state(H, G, list(range(p)), q)
+    trace: List[GreedyRecord] = []
+    it = 0
+    while len(st.groups) > k:
+        take = min(t_hat, len(st.groups) - k)
+        rem = removal_scores(st, p, q)
+        order = sorted(st.groups, key=lambda g: (rem[g], g))
+        own = order[:take]
+        chosen = list(follow[it]) if follow is not None else own
+        if len(chosen) != take or any(g not in st.groups for g in chosen) or len(set(chosen)) != take:
+            raise ValueError("forced removals must be %d distinct kept groups" % take)
+        edge = float(rem[own[-1]])
+        nxt = float(rem[order[take]]) if take < len(order) else np.inf
+        gap = float(abs(nxt - edge) / max(abs(edge), _TINY)) if np.isfinite(nxt) else np.inf
+        worst = max(float(rem[g]) for g in chosen)
+        deficit = float((worst - edge) / max(abs(edge), _TINY))
+        for g in chosen:
+            st = remove_group(st, st.groups.index(g), q)
+        trace.append(GreedyRecord(list(chosen), [float(rem[g]) for g in chosen], gap, deficit, c0 + 2.0 * st.f))
+        it += 1
+    return GreedyResult(sorted(st.groups), c0 + 2.0 * st.f, trace, st)
+
+
+# --------------------------------------------------------------------------------------------------
 # Whole path: Gram -> magnitude support -> swap search -> fresh solve on the final support
 # --------------------------------------------------------------------------------------------------
 def prune_layer(X: np.ndarray, W: np.ndarray, p: int, q: int, k: int, max_swaps: int,

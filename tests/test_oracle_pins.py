@@ -302,6 +302,96 @@ def test_always_accept_runs_the_printed_algorithm():
     assert np.isclose(o, res.obj_final, rtol=1e-8)
 
 
+# ---------------------------------------------------------------- nested schedule from the dense layer (Algorithm 1)
+def test_dense_start_is_the_dense_layer():
+    # S_0 empty: every group kept, the optimal weights are W itself and the objective is zero
+    X, W, H, G, c0, lam = make_problem(7, 2, 5, 60, 81)
+    st = orc.init_state(H, G, list(range(7)), 2)
+    assert np.allclose(st.What_K, W, atol=1e-9)
+    assert abs(c0 + 2 * st.f) < 1e-9 * c0
+    res = orc.greedy_from_dense(H, G, c0, 7, 2, 7, 3)
+    assert res.trace == [] and res.support == list(range(7))
+
+
+@pytest.mark.parametrize("q,t_hat", [(1, 1), (1, 3), (2, 2), (3, 4)])
+def test_greedy_picks_the_cheapest_removals_by_definition(q, t_hat):
+    # every iteration: the chosen set is the t_hat smallest of obj(K - g) - obj(K) computed by full re-solves,
+    # the tracked objective equals the re-solved one, and the final state equals a fresh state on the final support
+    p, m, n, k = 10, 4, 90, 3
+    X, W, H, G, c0, lam = make_problem(p, q, m, n, 90 + 7 * q + t_hat)
+    res = orc.greedy_from_dense(H, G, c0, p, q, k, t_hat)
+    K = list(range(p))
+    want_iters = math.ceil((p - k) / t_hat)
+    assert len(res.trace) == want_iters
+    prev_obj = 0.0
+    for it, rec in enumerate(res.trace):
+        take = min(t_hat, len(K) - k)
+        _, objK = orc.solve_support(H, G, c0, K, q)
+        cost = {g: orc.solve_support(H, G, c0, [x for x in K if x != g], q)[1] - objK for g in K}
+        order = sorted(K, key=lambda g: (cost[g], g))
+        assert rec.removed == order[:take]
+        assert np.allclose(rec.costs, [cost[g] for g in rec.removed], rtol=1e-7, atol=1e-9 * c0)
+        assert rec.deficit == 0.0 and rec.gap >= 0.0
+        K = [g for g in K if g not in rec.removed]
+        _, objn = orc.solve_support(H, G, c0, K, q)
+        assert np.isclose(rec.obj_after, objn, rtol=1e-9)
+        assert rec.obj_after >= prev_obj - 1e-12 * c0          # pruning never lowers the loss
+        prev_obj = rec.obj_after
+    assert res.support == sorted(K) and len(K) == k
+    fresh = orc.init_state(H, G, res.support, q)
+    order = np.argsort(res.state.groups)
+    rows = np.concatenate([np.arange(s * q, (s + 1) * q) for s in order])
+    assert np.allclose(res.state.P[np.ix_(rows, rows)], fresh.P, rtol=1e-8, atol=1e-10)
+    assert np.allclose(res.state.What_K[rows], fresh.What_K, rtol=1e-8, atol=1e-10)
+
+
+def test_greedy_first_iteration_closed_form_and_one_shot_case():
+    # at the dense layer the cost of pruning row g (q = 1) is ||W_g||^2 / (H^-1)_gg; with t_hat = p - k the
+    # schedule is one iteration that prunes the p - k smallest of these
+    p, m, n, k = 12, 6, 100, 5
+    X, W, H, G, c0, lam = make_problem(p, 1, m, n, 97)
+    cost = np.sum(W * W, axis=1) / np.diag(np.linalg.inv(H))
+    res = orc.greedy_from_dense(H, G, c0, p, 1, k, p - k)
+    assert len(res.trace) == 1
+    assert res.trace[0].removed == [int(i) for i in np.argsort(cost, kind="stable")[:p - k]]
+    assert np.allclose(res.trace[0].costs, np.sort(cost)[:p - k], rtol=1e-9)
+
+
+def test_greedy_on_diagonal_H_reaches_the_optimum_and_is_bounded_by_brute_force():
+    rng = np.random.default_rng(61)
+    p, m, k = 12, 4, 5
+    Qm, _ = np.linalg.qr(rng.standard_normal((40, p)))
+    X = Qm * rng.uniform(0.5, 3.0, size=p)[None, :]
+    W = rng.standard_normal((p, m))
+    H, G, c0, lam = orc.gram(X, W, lam_abs=0.1)
+    imp = np.diag(H) * np.sum(W * W, axis=1)
+    for t_hat in (1, 2, 7):
+        res = orc.greedy_from_dense(H, G, c0, p, 1, k, t_hat)
+        assert res.support == sorted(int(i) for i in np.argsort(-imp)[:k])
+    # correlated columns: greedy is a heuristic, never better than the enumerated optimum
+    X, W, H, G, c0, lam = make_problem(12, 1, 4, 60, 98)
+    _, best_obj, _ = orc.brute_force(H, G, c0, 12, 1, 6)
+    for t_hat in (1, 2, 3):
+        res = orc.greedy_from_dense(H, G, c0, 12, 1, 6, t_hat)
+        _, o = orc.solve_support(H, G, c0, res.support, 1)
+        assert np.isclose(o, res.obj_final, rtol=1e-9) and res.obj_final >= best_obj * (1 - 1e-12)
+
+
+def test_greedy_follow_mode_reports_deficit():
+    X, W, H, G, c0, lam = make_problem(9, 1, 4, 70, 99)
+    free = orc.greedy_from_dense(H, G, c0, 9, 1, 4, 2)
+    again = orc.greedy_from_dense(H, G, c0, 9, 1, 4, 2, follow=[r.removed[::-1] for r in free.trace])
+    assert again.support == free.support and all(r.deficit == 0.0 for r in again.trace)
+    # forcing the costliest removal first shows up as a positive deficit
+    st = orc.init_state(H, G, list(range(9)), 1)
+    rem = orc.removal_scores(st, 9, 1)
+    bad = [int(np.argmax(rem)), int(np.argmin(rem))]
+    forced = orc.greedy_from_dense(H, G, c0, 9, 1, 7, 2, follow=[bad])
+    assert forced.trace[0].deficit > 0.0
+    with pytest.raises(ValueError):
+        orc.greedy_from_dense(H, G, c0, 9, 1, 7, 2, follow=[[0, 0]])
+
+
 def test_prune_layer_end_to_end_on_cfg1():
     cfg = inp.CONFIGS["cfg1"]
     X = inp.gen_X(cfg).double().numpy()
