@@ -60,6 +60,8 @@ typedef struct {
   int32_t max_swaps; /* upper bound on the swap budget of any osscar_local_search call (sizes the trace) */
   int32_t x_dtype;   /* osscar_dtype of X */
   int32_t w_dtype;   /* osscar_dtype of W */
+  int32_t from_dense; /* nonzero: size the workspace for osscar_init_greedy too (it inverts all of H) */
+  int32_t reserved;  /* set to 0 */
 } osscar_desc;
 
 /* Bytes of device workspace osscar_create needs for this description (0 if the description is invalid). */
@@ -96,6 +98,22 @@ osscar_status osscar_set_quadratic(osscar_ctx* ctx, const float* H_dev, const fl
  * (eq. (impact)), and returns obj(K) = c0 - Tr(G_K^T B) in *obj_host (may be NULL). */
 enum { OSSCAR_INIT_MAGNITUDE = 0, OSSCAR_INIT_GIVEN = 1 };
 osscar_status osscar_init_support(osscar_ctx* ctx, int mode, const int32_t* groups_host, double* obj_host);
+
+/* Nested schedule of Algorithm 1 from the dense layer (S_0 empty and t_i = p_i = t_hat for every iteration:
+ * Section 4.2; Appendix B.1 takes t_hat = 2 for channels and attention heads and 10 for the intermediate
+ * dimension of feed-forward layers).  Starts with every group kept (P = H^-1, B = H^-1 G, obj = 0); each
+ * iteration scores every kept group by the cost of removing it (eq. (impact), closed form of
+ * Proposition 4.1 Case 1) at the state the iteration starts from, removes the t_hat cheapest (lowest group
+ * index on ties; the last iteration takes what is left to reach k) and updates inverse, weights and objective
+ * by Case 1.  Leaves the context as osscar_init_support does, so osscar_local_search and osscar_backsolve
+ * can follow.  Needs desc.from_dense != 0.  1 <= t_hat <= 64.
+ * refresh_every > 0 rebuilds the state from H and G after that many removals (at iteration boundaries).
+ * removed_host (host, optional): p - k group ids in the order removed (within an iteration: cheapest first).
+ * gaps_host (host, optional): one float per iteration, ceil((p - k) / t_hat) of them: relative gap between the
+ * costliest removal chosen and the cheapest kept group left out (inf if none was left out).
+ * obj_host (host, optional): the tracked objective of the resulting kept set. */
+osscar_status osscar_init_greedy(osscar_ctx* ctx, int32_t t_hat, int32_t refresh_every, int32_t* removed_host,
+                                 float* gaps_host, double* obj_host);
 
 /* Local search (Section 4.2 and Algorithm 1 with t-hat = 2, p-hat = 0: one group leaves, one enters).
  * Each iteration scores every kept group by the cost of removing it and every outside group by the

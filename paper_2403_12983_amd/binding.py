@@ -17,7 +17,7 @@ T_H, T_G, T_P, T_B, T_V, T_R, T_REM, T_ADD, T_KEPT, T_CAND = range(10)
 _STATUS = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "ENOTPD", 4: "EHIP", 5: "ESTATE"}
 
 EXPORTED_SYMBOLS = ["osscar_workspace_bytes", "osscar_create", "osscar_destroy", "osscar_gram", "osscar_set_quadratic",
-                    "osscar_init_support", "osscar_local_search", "osscar_apply_swap", "osscar_backsolve",
+                    "osscar_init_support", "osscar_init_greedy", "osscar_local_search", "osscar_apply_swap", "osscar_backsolve",
                     "osscar_get_tensor", "osscar_get_scalars", "osscar_get_timers", "osscar_last_error"]
 
 
@@ -29,7 +29,8 @@ class OsscarError(RuntimeError):
 
 class _Desc(C.Structure):
     _fields_ = [("d1", C.c_int64), ("m", C.c_int64), ("p", C.c_int32), ("q", C.c_int32), ("k", C.c_int32),
-                ("max_swaps", C.c_int32), ("x_dtype", C.c_int32), ("w_dtype", C.c_int32)]
+                ("max_swaps", C.c_int32), ("x_dtype", C.c_int32), ("w_dtype", C.c_int32), ("from_dense", C.c_int32),
+                ("reserved", C.c_int32)]
 
 
 class _SearchResult(C.Structure):
@@ -61,6 +62,7 @@ def load_library():
     lib.osscar_gram.argtypes = [vp, vp, i64, i64, C.c_int, vp, i64, dbl, dbl]
     lib.osscar_set_quadratic.argtypes = [vp, vp, vp, dbl, C.POINTER(dbl)]
     lib.osscar_init_support.argtypes = [vp, C.c_int, C.POINTER(i32), C.POINTER(dbl)]
+    lib.osscar_init_greedy.argtypes = [vp, i32, i32, C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(dbl)]
     lib.osscar_local_search.argtypes = [vp, i32, dbl, C.c_uint32, i32, C.POINTER(_SearchResult), C.POINTER(i32),
                                         C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(dbl)]
     lib.osscar_apply_swap.argtypes = [vp, i32, i32]
@@ -89,13 +91,14 @@ class Solver:
     """One layer's context: owns the workspace tensor and forwards every call to the C library."""
 
     def __init__(self, d1: int, m: int, p: int, q: int, k: int, max_swaps: int, x_dtype=torch.bfloat16,
-                 w_dtype=torch.bfloat16, device="cuda:0", stream: Optional[torch.cuda.Stream] = None):
+                 w_dtype=torch.bfloat16, device="cuda:0", stream: Optional[torch.cuda.Stream] = None,
+                 from_dense: bool = False):
         self.lib = load_library()
         self.device = torch.device(device)
         self.d1, self.m, self.p, self.q, self.k = d1, m, p, q, k
         self.kr, self.cr = k * q, d1 - k * q
         self.max_swaps = max_swaps
-        self.desc = _Desc(d1, m, p, q, k, max_swaps, _dtype_code(x_dtype), _dtype_code(w_dtype))
+        self.desc = _Desc(d1, m, p, q, k, max_swaps, _dtype_code(x_dtype), _dtype_code(w_dtype), int(from_dense), 0)
         nbytes = self.lib.osscar_workspace_bytes(C.byref(self.desc))
         if nbytes == 0:
             raise OsscarError(1, "invalid problem description")
@@ -158,6 +161,18 @@ class Solver:
             assert len(groups) == self.k
         self._check(self.lib.osscar_init_support(self.ctx, mode, arr, C.byref(obj)))
         return obj.value
+
+    def osscar_init_greedy(self, t_hat: int, refresh_every: int = 0):
+        """Returns (objective, per-iteration lists of removed groups, per-iteration gaps)."""
+        obj = C.c_double()
+        nrem = self.p - self.k
+        iters = (nrem + t_hat - 1) // t_hat if t_hat > 0 else 0
+        removed = np.full(max(nrem, 1), -1, dtype=np.int32)
+        gaps = np.zeros(max(iters, 1), dtype=np.float32)
+        self._check(self.lib.osscar_init_greedy(self.ctx, t_hat, refresh_every, removed.ctypes.data_as(C.POINTER(C.c_int32)),
+                                                gaps.ctypes.data_as(C.POINTER(C.c_float)), C.byref(obj)))
+        steps = [removed[i * t_hat:min((i + 1) * t_hat, nrem)].tolist() for i in range(iters)]
+        return obj.value, steps, gaps[:iters].copy()
 
     def osscar_local_search(self, max_swaps: int, rel_tol: float = 0.0, flags: int = 0, refresh_every: int = 0):
         res = _SearchResult()

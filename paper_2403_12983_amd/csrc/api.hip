@@ -88,6 +88,7 @@ struct osscar_ctx {
   float *C1, *C2, *Cblk, *rZ1, *rZ2;
   SearchCtrl* ctrl;
   int32_t *trace_out, *trace_in; float* trace_gap; double* trace_obj;
+  int32_t *g_pick, *g_removed; float* g_gap;   // nested schedule from the dense layer
   LazyPtrs lazy;
   // phase-shared scratch
   char* scratch; size_t scratch_bytes;
@@ -137,6 +138,9 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
   int32_t* trace_in = cv.take<int32_t>(ms);
   float* trace_gap = cv.take<float>(2 * ms);
   double* trace_obj = cv.take<double>(ms);
+  int32_t* g_pick = cv.take<int32_t>(64);
+  int32_t* g_removed = cv.take<int32_t>(p);
+  float* g_gap = cv.take<float>(p);
   LazyPtrs L{};
   if (q == 1) {
     const int64_t TM = LAZY_TM;
@@ -152,8 +156,15 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
   // scratch: the larger of the Gram phase and the init / refresh / backsolve phase
   size_t gram_phase = align_up((size_t)d1 * d1 * 8) + align_up((size_t)d1 * m * 4) + align_up(gram_stage_bytes(d1)) +
                       align_up(gram_tile_entries(d1) * 8);
-  size_t init_phase = 4 * align_up((size_t)kr * kr * 4) + 3 * align_up((size_t)kr * cr * 4) + align_up((size_t)cr * cr * 4) +
-                      4 * align_up((size_t)kr * m * 4) + align_up((size_t)cr * m * 4) + 3 * align_up((size_t)kr * 64 * 4) + 4096;
+  auto init_bytes = [&](size_t a, size_t b) {   // kept rows a, candidate rows b
+    return 4 * align_up(a * a * 4) + 3 * align_up(a * b * 4) + align_up(b * b * 4) + 4 * align_up(a * m * 4) + align_up(b * m * 4) +
+           3 * align_up(a * 64 * 4) + 4096;
+  };
+  size_t init_phase = init_bytes(kr, cr);
+  if (ds.from_dense) {   // the nested schedule visits every kept-row count from d1 down to kr
+    init_phase = std::max(init_phase, init_bytes(d1, 0));
+    init_phase = std::max(init_phase, init_bytes(d1 / 2, d1 - d1 / 2));
+  }
   size_t scratch_bytes = std::max(gram_phase, init_phase);
   char* scratch = cv.take<char>(scratch_bytes);
   if (c) {
@@ -161,6 +172,7 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
     c->small = small; c->scal = scal; c->partial = partial; c->kept = kept; c->rowsK = rowsK; c->rowsC = rowsC;
     c->notpd = notpd; c->C1 = C1; c->C2 = C2; c->Cblk = Cblk; c->rZ1 = rZ1; c->rZ2 = rZ2; c->ctrl = ctrl;
     c->trace_out = trace_out; c->trace_in = trace_in; c->trace_gap = trace_gap; c->trace_obj = trace_obj;
+    c->g_pick = g_pick; c->g_removed = g_removed; c->g_gap = g_gap;
     c->scratch = scratch; c->scratch_bytes = scratch_bytes; c->lazy = L;
   }
   Layout lay; lay.total = cv.off; lay.scratch_bytes = scratch_bytes;
@@ -500,6 +512,72 @@ osscar_status osscar_init_support(osscar_ctx* c, int mode, const int32_t* groups
 static osscar_status read_ctrl(osscar_ctx* c, SearchCtrl* h) {
   HIPCHK(c, hipMemcpyAsync(h, c->ctrl, sizeof *h, hipMemcpyDeviceToHost, c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
+  return OSSCAR_OK;
+}
+
+osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_every, int32_t* removed_host, float* gaps_host,
+                                 double* obj_host) {
+  osscar_status st = check_ctx(c);
+  if (st != OSSCAR_OK) return st;
+  if (c->phase != osscar_ctx::FINAL && c->phase != osscar_ctx::READY)
+    return fail(c, OSSCAR_ESTATE, "osscar_init_greedy: no quadratic form yet (call osscar_gram with finalize first)");
+  if (!c->desc.from_dense) return fail(c, OSSCAR_EINVAL, "osscar_init_greedy: the context was created without desc.from_dense");
+  if (t_hat < 1 || t_hat > 64 || refresh_every < 0) return fail(c, OSSCAR_EINVAL, "osscar_init_greedy: t_hat %d outside [1, 64] or refresh_every < 0", t_hat);
+  hipStream_t s = c->stream;
+  const int q = c->q, k = c->k, p = c->p;
+  HIPCHK(c, hipEventRecord(c->ev_a, s));
+  // dense layer: every group kept
+  c->kept_host.assign(p, 1);
+  c->kr = c->d1; c->cr = 0;
+  double obj = 0;
+  st = build_state(c, &obj);
+  if (st != OSSCAR_OK) { c->kr = k * q; c->cr = c->d1 - c->kr; return st; }
+  SearchCtrl h{};
+  h.obj = 0.0;                      // the dense layer reproduces its own output exactly
+  h.g_out = -1; h.g_in = -1;
+  HIPCHK(c, hipMemcpyAsync(c->ctrl, &h, sizeof h, hipMemcpyHostToDevice, s));
+  TabDims d = dims(c);
+  TabPtrs t = ptrs(c);
+  t.trace_out = c->g_removed; t.trace_in = nullptr; t.trace_gap = nullptr; t.trace_obj = nullptr;
+  int kept_now = p, iter = 0, since_refresh = 0, since_check = 0;
+  while (kept_now > k) {
+    const int take = std::min<int>(t_hat, kept_now - k);
+    HIPCHK(c, launch_greedy_pick(d, t, take, c->g_pick, c->g_gap + iter, s));
+    for (int i = 0; i < take; i++) HIPCHK(c, launch_search_iteration(d, t, -1, -1, 1, s, nullptr, c->g_pick + i));
+    kept_now -= take; iter++; since_refresh += take; since_check += take;
+    const bool refresh = refresh_every > 0 && since_refresh >= refresh_every && kept_now > k;
+    if (since_check >= 256 || refresh || kept_now == k) {
+      st = read_ctrl(c, &h);
+      if (st != OSSCAR_OK) return st;
+      if (h.notpd) return fail(c, OSSCAR_ENOTPD, "osscar_init_greedy: a pivot block lost definiteness after %d removals", h.iters);
+      since_check = 0;
+    }
+    if (refresh) {
+      st = read_kept(c);
+      if (st != OSSCAR_OK) return st;
+      c->kr = kept_now * q; c->cr = c->d1 - c->kr;
+      st = build_state(c, &obj);
+      if (st != OSSCAR_OK) return st;
+      HIPCHK(c, hipMemcpyAsync(reinterpret_cast<char*>(c->ctrl) + offsetof(SearchCtrl, obj), &obj, 8, hipMemcpyHostToDevice, s));
+      since_refresh = 0;
+    }
+  }
+  c->kr = k * q; c->cr = c->d1 - c->kr;
+  st = read_ctrl(c, &h);
+  if (st != OSSCAR_OK) return st;
+  st = read_kept(c);
+  if (st != OSSCAR_OK) return st;
+  st = upload_rows(c);
+  if (st != OSSCAR_OK) return st;
+  h.done = 0; h.iters = 0; h.accepted = 0;
+  HIPCHK(c, hipMemcpyAsync(c->ctrl, &h, sizeof h, hipMemcpyHostToDevice, s));
+  if (removed_host && p > k) HIPCHK(c, hipMemcpyAsync(removed_host, c->g_removed, (size_t)(p - k) * 4, hipMemcpyDeviceToHost, s));
+  if (gaps_host && iter > 0) HIPCHK(c, hipMemcpyAsync(gaps_host, c->g_gap, (size_t)iter * 4, hipMemcpyDeviceToHost, s));
+  HIPCHK(c, hipEventRecord(c->ev_b, s));
+  HIPCHK(c, hipStreamSynchronize(s));
+  c->timers[2] = elapsed(c);
+  if (obj_host) *obj_host = h.obj;
+  c->phase = osscar_ctx::READY;
   return OSSCAR_OK;
 }
 

@@ -94,8 +94,11 @@ struct TabPtrs {
 
 hipError_t launch_refresh_scores(const TabDims& d, const TabPtrs& t, hipStream_t s);   // gram, dblk, score from N, Z
 // ev (optional): three events recorded before the bulk update of N, after it, and after the update of Z.
+// single (optional, device): removal of the one group *single instead of a swap (Case 1 alone; no selection kernel).
 hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int forced_out, int forced_in, int always_accept,
-                                   hipStream_t s, hipEvent_t* ev = nullptr);
+                                   hipStream_t s, hipEvent_t* ev = nullptr, const int32_t* single = nullptr);
+// pick[0..take) = the kept groups of smallest removal cost (ascending), *gap = relative gap to the next one; take <= 64
+hipError_t launch_greedy_pick(const TabDims& d, const TabPtrs& t, int take, int32_t* pick, float* gap, hipStream_t s);
 hipError_t launch_select(const TabDims& d, const TabPtrs& t, int forced_out, int forced_in, hipStream_t s);
 
 // ----------------------------------------------------------------------------------------------

@@ -446,9 +446,10 @@ __global__ __launch_bounds__(1024) void select_kernel(TabDims d, const int32_t* 
 __global__ __launch_bounds__(256) void extract_pair_kernel(TabDims d, const float* __restrict__ N, const float* __restrict__ Z,
                                                             const SearchCtrl* __restrict__ ctrl, float* __restrict__ C1,
                                                             float* __restrict__ C2, float* __restrict__ Zg,
-                                                            float* __restrict__ Zj) {
+                                                            float* __restrict__ Zj, const int32_t* __restrict__ single) {
   if (ctrl->done) return;
-  const int q = d.q, g0 = ctrl->g_out * q, j0 = ctrl->g_in * q;
+  // single != nullptr: removal of the one group *single (no group enters); the second pivot then aliases the first
+  const int q = d.q, g0 = (single ? *single : ctrl->g_out) * q, j0 = (single ? *single : ctrl->g_in) * q;
   int i = blockIdx.x * 256 + threadIdx.x;
   if (i < d.d1) {
     for (int c = 0; c < q; c++) {
@@ -468,13 +469,14 @@ __global__ __launch_bounds__(256) void extract_pair_kernel(TabDims d, const floa
 __global__ __launch_bounds__(256) void pair_small_kernel(TabDims d, const float* __restrict__ C1, const float* __restrict__ C2,
                                                           float* __restrict__ Zg, float* __restrict__ Zj, double* __restrict__ small,
                                                           SearchCtrl* ctrl, int always_accept, int32_t* trace_out,
-                                                          int32_t* trace_in, float* trace_gap, double* trace_obj) {
+                                                          int32_t* trace_in, float* trace_gap, double* trace_obj,
+                                                          const int32_t* __restrict__ single) {
   __shared__ double colbuf[64];
   __shared__ double red[4];
   __shared__ int32_t bad;
   if (ctrl->done) return;
   const int q = d.q, qq = q * q, m = d.m, tid = threadIdx.x;
-  const int g0 = ctrl->g_out * q, j0 = ctrl->g_in * q;
+  const int g0 = (single ? *single : ctrl->g_out) * q, j0 = (single ? *single : ctrl->g_in) * q;
   double* Dg = small; double* Njg = small + qq; double* M1 = small + 2 * qq; double* Dj = small + 3 * qq;
   double* W2Dj = small + 4 * qq;
   if (tid == 0) bad = 0;
@@ -486,6 +488,11 @@ __global__ __launch_bounds__(256) void pair_small_kernel(TabDims d, const float*
   }
   __syncthreads();
   small_inverse(Dg, q, -1, &bad, colbuf);                  // kept pivot: N_gg = -P_gg is negative definite
+  if (single) {
+    // Case 1 alone: with M1 = 0 and Dj' = 0 every term of the second sweep below vanishes
+    for (int idx = tid; idx < qq; idx += 256) { M1[idx] = 0.0; Dj[idx] = 0.0; W2Dj[idx] = 0.0; Njg[idx] = 0.0; }
+    __syncthreads();
+  } else {
   for (int idx = tid; idx < qq; idx += 256) {              // M1 = Dg * N_gj, N_gj = Njg^T
     int r = idx / q, c = idx % q;
     double v = 0;
@@ -508,6 +515,7 @@ __global__ __launch_bounds__(256) void pair_small_kernel(TabDims d, const float*
     W2Dj[idx] = v;
   }
   __syncthreads();
+  }
   // rZ1 = Dg Zg ; Z'j = Zj - Njg rZ1 ; rZ2 = Dj' Z'j ; delta = -<Zg, rZ1> - <Z'j, rZ2>   (column by column)
   double part = 0;
   for (int col = tid; col < m; col += 256) {
@@ -537,12 +545,12 @@ __global__ __launch_bounds__(256) void pair_small_kernel(TabDims d, const float*
     int it = ctrl->iters;
     bool ok = !bad && (always_accept || delta < -ctrl->rel_tol * ctrl->obj);
     ctrl->iters = it + 1;
+    if (single) { ctrl->g_out = *single; ctrl->g_in = -1; }
     if (ok) { ctrl->obj += delta; ctrl->accepted += 1; } else { ctrl->done = 1; }
-    if (trace_out) {
-      trace_out[it] = ctrl->g_out; trace_in[it] = ctrl->g_in;
-      trace_gap[2 * it] = (float)ctrl->gap_rem; trace_gap[2 * it + 1] = (float)ctrl->gap_add;
-      trace_obj[it] = ctrl->obj;
-    }
+    if (trace_out) trace_out[it] = ctrl->g_out;
+    if (trace_in) trace_in[it] = ctrl->g_in;
+    if (trace_gap) { trace_gap[2 * it] = (float)ctrl->gap_rem; trace_gap[2 * it + 1] = (float)ctrl->gap_add; }
+    if (trace_obj) trace_obj[it] = ctrl->obj;
   }
 }
 
@@ -552,11 +560,12 @@ __global__ __launch_bounds__(256) void pair_small_kernel(TabDims d, const float*
 __global__ __launch_bounds__(256) void pair_panels_kernel(TabDims d, const float* __restrict__ C1, const float* __restrict__ C2,
                                                            const double* __restrict__ small, const SearchCtrl* __restrict__ ctrl,
                                                            float* __restrict__ P1, float* __restrict__ P2,
-                                                           float* __restrict__ P1D, float* __restrict__ P2D) {
+                                                           float* __restrict__ P1D, float* __restrict__ P2D,
+                                                           const int32_t* __restrict__ single) {
   if (ctrl->done) return;
   extern __shared__ double sm[];   // Dg, M1, Dj : 3*q*q
   const int q = d.q, qq = q * q;
-  const int g0 = ctrl->g_out * q, j0 = ctrl->g_in * q;
+  const int g0 = (single ? *single : ctrl->g_out) * q, j0 = (single ? *single : ctrl->g_in) * q;
   double* Dg = sm; double* M1 = sm + qq; double* Dj = sm + 2 * qq;
   for (int idx = threadIdx.x; idx < qq; idx += 256) { Dg[idx] = small[idx]; M1[idx] = small[2 * qq + idx]; Dj[idx] = small[3 * qq + idx]; }
   __syncthreads();
@@ -594,10 +603,11 @@ __global__ __launch_bounds__(256) void pair_fix_kernel(TabDims d, float* __restr
                                                         const float* __restrict__ P1D, const float* __restrict__ P2D,
                                                         const float* __restrict__ rZ1, const float* __restrict__ rZ2,
                                                         const double* __restrict__ small, const SearchCtrl* __restrict__ ctrl,
-                                                        double* __restrict__ dblk, int32_t* __restrict__ kept) {
+                                                        double* __restrict__ dblk, int32_t* __restrict__ kept,
+                                                        const int32_t* __restrict__ single) {
   if (ctrl->done) return;
   const int q = d.q, qq = q * q, m = d.m;
-  const int g = ctrl->g_out, j = ctrl->g_in, g0 = g * q, j0 = j * q;
+  const int g = single ? *single : ctrl->g_out, j = single ? g : ctrl->g_in, g0 = g * q, j0 = j * q;
   const double* Dg = small; const double* M1 = small + 2 * qq; const double* Dj = small + 3 * qq; const double* W2Dj = small + 4 * qq;
   const int64_t ld = d.d1;
   int l = blockIdx.x * 256 + threadIdx.x;
@@ -610,6 +620,7 @@ __global__ __launch_bounds__(256) void pair_fix_kernel(TabDims d, float* __restr
         float vj = P2D[(int64_t)l * q + r];
         int gr = g0 + r, jr = j0 + r;
         if (l < gr) N[(int64_t)gr * ld + l] = (float)vg; else N[(int64_t)l * ld + gr] = (float)vg;
+        if (single) continue;
         if (l < jr) N[(int64_t)jr * ld + l] = vj; else N[(int64_t)l * ld + jr] = vj;
       }
       // float64 diagonal block of l's group (one thread per group: the one owning its first row)
@@ -635,15 +646,14 @@ __global__ __launch_bounds__(256) void pair_fix_kernel(TabDims d, float* __restr
       double njj = -Dj[idx];
       double ngj = W2Dj[idx];                                                  // N''(g_r, j_c)
       dblk[(int64_t)g * qq + idx] = ngg;
+      if (c <= r) N[(int64_t)(g0 + r) * ld + g0 + c] = (float)ngg;
+      if (single) continue;
       dblk[(int64_t)j * qq + idx] = njj;
-      if (c <= r) {
-        N[(int64_t)(g0 + r) * ld + g0 + c] = (float)ngg;
-        N[(int64_t)(j0 + r) * ld + j0 + c] = (float)njj;
-      }
+      if (c <= r) N[(int64_t)(j0 + r) * ld + j0 + c] = (float)njj;
       if (g0 > j0) N[(int64_t)(g0 + r) * ld + j0 + c] = (float)ngj;
       else N[(int64_t)(j0 + c) * ld + g0 + r] = (float)ngj;
     }
-    if (threadIdx.x == 0) { kept[g] = 0; kept[j] = 1; }
+    if (threadIdx.x == 0) { kept[g] = 0; if (!single) kept[j] = 1; }
   }
   // Z rows of the pivots
   int64_t tot = (int64_t)q * m;
@@ -652,7 +662,7 @@ __global__ __launch_bounds__(256) void pair_fix_kernel(TabDims d, float* __restr
     double vg = -(double)rZ1[idx];
     for (int c = 0; c < q; c++) vg += M1[r * q + c] * (double)rZ2[(int64_t)c * m + col];
     Z[(int64_t)(g0 + r) * m + col] = (float)vg;
-    Z[(int64_t)(j0 + r) * m + col] = rZ2[idx];
+    if (!single) Z[(int64_t)(j0 + r) * m + col] = rZ2[idx];
   }
 }
 
@@ -776,28 +786,78 @@ __global__ __launch_bounds__(256) void update_Z_kernel(TabDims d, float* __restr
   group_gram(Zh, q, m, gram + (int64_t)h * q * q);
 }
 
+// The `take` kept groups with the smallest removal cost (ascending cost, lowest index on ties) -> pick[0..take), and
+// the relative gap between the costliest of them and the cheapest kept group left out -> *gap (inf if none is left).
+// One workgroup; take <= 64.
+__global__ __launch_bounds__(1024) void greedy_pick_kernel(TabDims d, const int32_t* __restrict__ kept,
+                                                            const double* __restrict__ score, int take,
+                                                            int32_t* __restrict__ pick, float* __restrict__ gap,
+                                                            const SearchCtrl* __restrict__ ctrl) {
+  __shared__ double s_v[1024];
+  __shared__ int s_i[1024];
+  __shared__ int chosen[65];
+  __shared__ double chosen_v[65];
+  if (ctrl->done) return;
+  const int tid = threadIdx.x;
+  for (int round = 0; round <= take; round++) {
+    double best = INFINITY;
+    int ib = -1;
+    for (int h = tid; h < d.p; h += 1024) {
+      if (!kept[h]) continue;
+      bool used = false;
+      for (int c = 0; c < round; c++) used |= (chosen[c] == h);
+      if (used) continue;
+      const double v = score[h];
+      if (ib < 0 || v < best) { best = v; ib = h; }        // ascending h per thread: strict comparison keeps the lowest index
+    }
+    s_v[tid] = best; s_i[tid] = ib;
+    __syncthreads();
+    for (int o = 512; o > 0; o >>= 1) {
+      if (tid < o) {
+        const double b1 = s_v[tid + o]; const int ib2 = s_i[tid + o];
+        const double a1 = s_v[tid]; const int ia = s_i[tid];
+        if (ib2 >= 0 && (ia < 0 || b1 < a1 || (b1 == a1 && ib2 < ia))) { s_v[tid] = b1; s_i[tid] = ib2; }
+      }
+      __syncthreads();
+    }
+    if (tid == 0) { chosen[round] = s_i[0]; chosen_v[round] = s_v[0]; }
+    __syncthreads();
+  }
+  if (tid < take) pick[tid] = chosen[tid];
+  if (tid == 0) {
+    const double edge = chosen_v[take - 1];
+    *gap = (chosen[take] >= 0) ? (float)(fabs(chosen_v[take] - edge) / fmax(fabs(edge), 1e-300)) : INFINITY;
+  }
+}
+
+hipError_t launch_greedy_pick(const TabDims& d, const TabPtrs& t, int take, int32_t* pick, float* gap, hipStream_t s) {
+  if (take < 1 || take > 64) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(greedy_pick_kernel, dim3(1), dim3(1024), 0, s, d, t.kept, t.score, take, pick, gap, t.ctrl);
+  return hipGetLastError();
+}
+
 hipError_t launch_select(const TabDims& d, const TabPtrs& t, int forced_out, int forced_in, hipStream_t s) {
   hipLaunchKernelGGL(select_kernel, dim3(1), dim3(1024), 0, s, d, t.kept, t.score, t.ctrl, forced_out, forced_in);
   return hipGetLastError();
 }
 
 hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int forced_out, int forced_in, int always_accept,
-                                   hipStream_t s, hipEvent_t* ev) {
+                                   hipStream_t s, hipEvent_t* ev, const int32_t* single) {
   const int q = d.q;
   const int rb = (d.d1 + 255) / 256;
-  hipLaunchKernelGGL(select_kernel, dim3(1), dim3(1024), 0, s, d, t.kept, t.score, t.ctrl, forced_out, forced_in);
-  hipLaunchKernelGGL(extract_pair_kernel, dim3(rb), dim3(256), 0, s, d, t.N, t.Z, t.ctrl, t.C1, t.C2, t.rZ1, t.rZ2);
+  if (!single) hipLaunchKernelGGL(select_kernel, dim3(1), dim3(1024), 0, s, d, t.kept, t.score, t.ctrl, forced_out, forced_in);
+  hipLaunchKernelGGL(extract_pair_kernel, dim3(rb), dim3(256), 0, s, d, t.N, t.Z, t.ctrl, t.C1, t.C2, t.rZ1, t.rZ2, single);
   hipLaunchKernelGGL(pair_small_kernel, dim3(1), dim3(256), 0, s, d, t.C1, t.C2, t.rZ1, t.rZ2, t.small, t.ctrl, always_accept,
-                     t.trace_out, t.trace_in, t.trace_gap, t.trace_obj);
+                     t.trace_out, t.trace_in, t.trace_gap, t.trace_obj, single);
   // bulk panels go to C1D/C2D (times D) and to two further panels stored behind them
   float* P1 = t.C1D + (int64_t)2 * d.d1 * q;
   float* P2 = P1 + (int64_t)d.d1 * q;
   float* P1D = t.C1D;
   float* P2D = t.C2D;
   hipLaunchKernelGGL(pair_panels_kernel, dim3(rb), dim3(256), (size_t)3 * q * q * 8, s, d, t.C1, t.C2, t.small, t.ctrl, P1, P2,
-                     P1D, P2D);
+                     P1D, P2D, single);
   hipLaunchKernelGGL(pair_fix_kernel, dim3(rb), dim3(256), 0, s, d, t.N, t.Z, P1, P2, P1D, P2D, t.rZ1, t.rZ2, t.small, t.ctrl,
-                     t.dblk, t.kept);
+                     t.dblk, t.kept, single);
   if (ev) hipEventRecord(ev[0], s);
   if (q == 1) {
     dim3 grid((d.d1 + 1023) / 1024, (d.d1 + 31) / 32);

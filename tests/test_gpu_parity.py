@@ -306,6 +306,111 @@ def test_delayed_update_search_equals_eager_search():
 
 
 # ------------------------------------------------------------------------------------------ set_quadratic
+# ------------------------------------------------------------------------------------------ nested schedule from the dense layer
+def dense_solver(c, max_swaps=None):
+    cfg = c.cfg
+    return _pkg().Solver(cfg.d1, cfg.m, cfg.p, cfg.q, cfg.k, max(cfg.swaps if max_swaps is None else max_swaps, 1),
+                         c.X.dtype, c.W.dtype, DEV, from_dense=True)
+
+
+def check_greedy(c, t_hat, obj, steps, gaps):
+    """The oracle replays the library's removals: every iteration's set must be within GAP of the oracle's own choice
+    (identical where the oracle's gap exceeds GAP), and the tracked objective must follow."""
+    cfg = c.cfg
+    free = orc.greedy_from_dense(c.H, c.G, c.c0, cfg.p, cfg.q, cfg.k, t_hat)
+    assert len(steps) == len(free.trace) == -(-(cfg.p - cfg.k) // t_hat)
+    fol = orc.greedy_from_dense(c.H, c.G, c.c0, cfg.p, cfg.q, cfg.k, t_hat, follow=steps)
+    diverged = False
+    for i, (mine, f, x) in enumerate(zip(steps, free.trace, fol.trace)):
+        assert len(set(mine)) == len(mine) == len(x.removed)
+        assert x.deficit <= GAP, (i, x)
+        if not diverged:
+            if f.gap > GAP:
+                assert sorted(mine) == sorted(f.removed), (i, mine, f.removed)
+            elif sorted(mine) != sorted(f.removed):
+                diverged = True
+        if np.isfinite(x.gap) and x.gap > 1e-3:
+            assert abs(gaps[i] - x.gap) <= 1e-2 * x.gap, (i, gaps[i], x.gap)
+    assert abs(obj - fol.obj_final) <= 1e-5 * fol.obj_final
+    return fol
+
+
+@pytest.mark.parametrize("name,t_hat", [("cfg1", 1), ("cfg1", 3), ("cfg1x", 2), ("cfg2s", 2), ("cfg3s", 10), ("cfg4s", 2),
+                                        ("cfg5odd", 7)])
+def test_greedy_from_dense_follows_the_oracle(name, t_hat):
+    c = case(name)
+    cfg = c.cfg
+    s = dense_solver(c)
+    c.gram(s)
+    obj, steps, gaps = s.osscar_init_greedy(t_hat)
+    fol = check_greedy(c, t_hat, obj, steps, gaps)
+    kept = T(s, "T_KEPT").astype(int).tolist()
+    assert kept == fol.support and len(kept) == cfg.k                           # bit-exact bookkeeping
+    # the state left behind is the state of a fresh solve on that support
+    st = orc.init_state(c.H, c.G, fol.support, cfg.q)
+    dp = np.sqrt(np.diag(st.P))
+    assert np.max(np.abs(T(s, "T_P") - st.P) / np.outer(dp, dp)) < 5e-5
+    assert rel(T(s, "T_B"), st.What_K) < 5e-5
+    rem_o = orc.removal_scores(st, cfg.p, cfg.q)
+    add_o = orc.addition_scores(st, c.H, c.G, cfg.p, cfg.q)
+    rem, add = T(s, "T_REM"), T(s, "T_ADD")
+    fin = np.isfinite(rem_o)
+    assert np.array_equal(np.isfinite(rem), fin)
+    assert np.max(np.abs(rem[fin] - rem_o[fin]) / rem_o[fin]) < 5e-5
+    assert np.max(np.abs(add[~fin] - add_o[~fin]) / np.maximum(add_o[~fin], 1e-12 * c.c0)) < 5e-4
+    # the paper's second setting: swaps (t-hat = 2, p-hat = 0) after the nested phase, then the final solve
+    r = s.osscar_local_search(min(cfg.swaps, 10))
+    fs = orc.local_search(c.H, c.G, c.c0, fol.support, cfg.p, cfg.q, min(cfg.swaps, 10),
+                          follow=list(zip(r["trace_out"][: r["accepted"]].tolist(), r["trace_in"][: r["accepted"]].tolist())))
+    for x in fs.trace:
+        assert x.deficit_rem <= GAP and x.deficit_add <= GAP and x.delta < 0
+    What, support, objb = s.osscar_backsolve()
+    assert support.tolist() == fs.support
+    Wo, objo = orc.solve_support(c.H, c.G, c.c0, fs.support, cfg.q)
+    assert rel(What.cpu().double().numpy(), Wo) < 1e-4 and abs(objb - objo) <= 1e-4 * objo
+    s.close()
+
+
+def test_greedy_refresh_and_edges():
+    c = case("cfg3s")
+    cfg = c.cfg
+    s = dense_solver(c)
+    c.gram(s)
+    obj_a, steps_a, _ = s.osscar_init_greedy(10)
+    obj_b, steps_b, gaps_b = s.osscar_init_greedy(10, refresh_every=40)           # rebuilt from H, G every 40 removals
+    check_greedy(c, 10, obj_b, steps_b, gaps_b)
+    assert abs(obj_a - obj_b) <= 1e-5 * obj_b
+    s.close()
+    from paper_2403_12983_amd.binding import OsscarError
+    s = c.solver()                                                               # created without from_dense
+    c.gram(s)
+    with pytest.raises(OsscarError) as e:
+        s.osscar_init_greedy(2)
+    assert e.value.status == 1
+    s.close()
+    s = dense_solver(c)
+    with pytest.raises(OsscarError) as e:
+        s.osscar_init_greedy(2)                                                   # no quadratic form yet
+    assert e.value.status == 5
+    c.gram(s)
+    with pytest.raises(OsscarError) as e:
+        s.osscar_init_greedy(0)
+    assert e.value.status == 1
+    with pytest.raises(OsscarError) as e:
+        s.osscar_init_greedy(65)
+    assert e.value.status == 1
+    s.close()
+    # k = p: nothing to prune, the dense layer comes back
+    c1 = case("cfg1")
+    s = _pkg().Solver(c1.cfg.d1, c1.cfg.m, c1.cfg.p, 1, c1.cfg.p, 1, c1.X.dtype, c1.W.dtype, DEV, from_dense=True)
+    c1.gram(s)
+    obj, steps, gaps = s.osscar_init_greedy(4)
+    assert obj == 0.0 and steps == [] and len(gaps) == 0
+    What, support, objb = s.osscar_backsolve()
+    assert rel(What.cpu().double().numpy(), c1.Wd) < 1e-5 and abs(objb) <= 1e-5 * c1.c0
+    s.close()
+
+
 def test_set_quadratic_and_brute_force_optimum_is_a_fixed_point():
     c = case("cfg1x")
     cfg = c.cfg
