@@ -114,6 +114,72 @@ def test_cfg3_full_width_reduced_rows():
     s.close()
 
 
+@pytest.mark.parametrize("name,t_hat", [("cfg2", 2), ("cfg4", 2)])
+def test_greedy_from_dense_whole_layer(name, t_hat):
+    """Nested schedule of Algorithm 1 on the conv-shaped and the head-shaped layer, every iteration against the oracle."""
+    import paper_2403_12983_amd as pkg
+    cfg = inp.CONFIGS[name]
+    X = gen_on_gpu(cfg)
+    W = inp.gen_W(cfg, DEV)
+    Xd, Wd = X.cpu().double().numpy(), W.cpu().double().numpy()
+    H, G, c0, lam = orc.gram(Xd, Wd, cfg.lam_abs, cfg.lam_rel)
+    del Xd
+    s = pkg.Solver(cfg.d1, cfg.m, cfg.p, cfg.q, cfg.k, cfg.swaps, X.dtype, W.dtype, DEV, from_dense=True)
+    s.osscar_gram(X, True, W, cfg.lam_abs, cfg.lam_rel)
+    obj, steps, gaps = s.osscar_init_greedy(t_hat)
+    free = orc.greedy_from_dense(H, G, c0, cfg.p, cfg.q, cfg.k, t_hat)
+    fol = orc.greedy_from_dense(H, G, c0, cfg.p, cfg.q, cfg.k, t_hat, follow=steps)
+    diverged = False
+    for i, (mine, f, x) in enumerate(zip(steps, free.trace, fol.trace)):
+        assert x.deficit <= GAP, (i, x)
+        if not diverged:
+            if f.gap > GAP:
+                assert sorted(mine) == sorted(f.removed), (i, mine, f.removed)
+            elif sorted(mine) != sorted(f.removed):
+                diverged = True
+    assert abs(obj - fol.obj_final) <= 1e-5 * fol.obj_final
+    assert T(s, "T_KEPT").cpu().tolist() == fol.support
+    What, support, objb = s.osscar_backsolve()
+    Wo, objo = orc.solve_support(H, G, c0, fol.support, cfg.q)
+    assert support.tolist() == fol.support
+    assert rel(What.cpu().double().numpy(), Wo) < 1e-4 and abs(objb - objo) <= 1e-4 * objo
+    print(f"{name}: greedy t_hat={t_hat}: obj {obj:.6g}, min gap {min(gaps):.3g}, init timer {s.osscar_get_timers()[2]:.1f} ms")
+    s.close()
+
+
+def test_greedy_from_dense_cfg3_width():
+    """FFN-shaped layer (d1 = 8192, t-hat = 10): the first iterations against the oracle, then properties of the end state."""
+    import paper_2403_12983_amd as pkg
+    cfg = inp.CONFIGS["cfg3"].replace(n=16384)
+    t_hat, n_follow = 10, 5
+    X = gen_on_gpu(cfg)
+    W = inp.gen_W(cfg, DEV)
+    Xd, Wd = X.cpu().double().numpy(), W.cpu().double().numpy()
+    H, G, c0, lam = orc.gram(Xd, Wd, cfg.lam_abs, cfg.lam_rel)
+    del Xd
+    s = pkg.Solver(cfg.d1, cfg.m, cfg.p, cfg.q, cfg.k, cfg.swaps, X.dtype, W.dtype, DEV, from_dense=True)
+    s.osscar_gram(X, True, W, cfg.lam_abs, cfg.lam_rel)
+    obj, steps, gaps = s.osscar_init_greedy(t_hat)
+    assert len(steps) == -(-(cfg.p - cfg.k) // t_hat)
+    flat = [g for st in steps for g in st]
+    assert len(set(flat)) == len(flat) == cfg.p - cfg.k
+    fol = orc.greedy_from_dense(H, G, c0, cfg.p, cfg.q, cfg.p - n_follow * t_hat, t_hat, follow=steps[:n_follow])
+    for i, x in enumerate(fol.trace):
+        assert x.deficit <= GAP, (i, x)
+        if x.gap > GAP:
+            assert sorted(x.removed) == sorted(steps[i])
+    kept = T(s, "T_KEPT").cpu().tolist()
+    assert kept == sorted(set(range(cfg.p)) - set(flat))
+    What, support, objb = s.osscar_backsolve()
+    Wo, objo = orc.solve_support(H, G, c0, kept, cfg.q)
+    assert rel(What.cpu().double().numpy(), Wo) < 1e-4 and abs(objb - objo) <= 1e-4 * objo
+    assert abs(obj - objo) <= 1e-4 * objo                                          # tracked through 4096 removals
+    # pruning greedily from the dense layer beats the magnitude support this layer's swap search starts from
+    _, obj_mp = orc.solve_support(H, G, c0, orc.magnitude_support(Wd, cfg.p, cfg.q, cfg.k), cfg.q)
+    print(f"cfg3 width: greedy obj {objb:.6g} vs magnitude support {obj_mp:.6g}; init timer {s.osscar_get_timers()[2]:.1f} ms")
+    s.close()
+
+
 def test_cfg5_bench_configuration_sampled():
     cfg = inp.CONFIGS["cfg5"]
     X = gen_on_gpu(cfg)
