@@ -108,12 +108,13 @@ osscar_status osscar_init_support(osscar_ctx* ctx, int mode, const int32_t* grou
  * by Case 1.  Leaves the context as osscar_init_support does, so osscar_local_search and osscar_backsolve
  * can follow.  Needs desc.from_dense != 0.  1 <= t_hat <= 64.
  * refresh_every > 0 rebuilds the state from H and G after that many removals (at iteration boundaries).
+ * flags: 0, or OSSCAR_SEARCH_EAGER to update the state in place after every removal also for q = 1.
  * removed_host (host, optional): p - k group ids in the order removed (within an iteration: cheapest first).
  * gaps_host (host, optional): one float per iteration, ceil((p - k) / t_hat) of them: relative gap between the
  * costliest removal chosen and the cheapest kept group left out (inf if none was left out).
  * obj_host (host, optional): the tracked objective of the resulting kept set. */
-osscar_status osscar_init_greedy(osscar_ctx* ctx, int32_t t_hat, int32_t refresh_every, int32_t* removed_host,
-                                 float* gaps_host, double* obj_host);
+osscar_status osscar_init_greedy(osscar_ctx* ctx, int32_t t_hat, int32_t refresh_every, uint32_t flags,
+                                 int32_t* removed_host, float* gaps_host, double* obj_host);
 
 /* Local search (Section 4.2 and Algorithm 1 with t-hat = 2, p-hat = 0: one group leaves, one enters).
  * Each iteration scores every kept group by the cost of removing it and every outside group by the

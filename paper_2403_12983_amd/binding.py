@@ -62,7 +62,7 @@ def load_library():
     lib.osscar_gram.argtypes = [vp, vp, i64, i64, C.c_int, vp, i64, dbl, dbl]
     lib.osscar_set_quadratic.argtypes = [vp, vp, vp, dbl, C.POINTER(dbl)]
     lib.osscar_init_support.argtypes = [vp, C.c_int, C.POINTER(i32), C.POINTER(dbl)]
-    lib.osscar_init_greedy.argtypes = [vp, i32, i32, C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(dbl)]
+    lib.osscar_init_greedy.argtypes = [vp, i32, i32, C.c_uint32, C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(dbl)]
     lib.osscar_local_search.argtypes = [vp, i32, dbl, C.c_uint32, i32, C.POINTER(_SearchResult), C.POINTER(i32),
                                         C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(dbl)]
     lib.osscar_apply_swap.argtypes = [vp, i32, i32]
@@ -162,14 +162,14 @@ class Solver:
         self._check(self.lib.osscar_init_support(self.ctx, mode, arr, C.byref(obj)))
         return obj.value
 
-    def osscar_init_greedy(self, t_hat: int, refresh_every: int = 0):
+    def osscar_init_greedy(self, t_hat: int, refresh_every: int = 0, flags: int = 0):
         """Returns (objective, per-iteration lists of removed groups, per-iteration gaps)."""
         obj = C.c_double()
         nrem = self.p - self.k
         iters = (nrem + t_hat - 1) // t_hat if t_hat > 0 else 0
         removed = np.full(max(nrem, 1), -1, dtype=np.int32)
         gaps = np.zeros(max(iters, 1), dtype=np.float32)
-        self._check(self.lib.osscar_init_greedy(self.ctx, t_hat, refresh_every, removed.ctypes.data_as(C.POINTER(C.c_int32)),
+        self._check(self.lib.osscar_init_greedy(self.ctx, t_hat, refresh_every, flags, removed.ctypes.data_as(C.POINTER(C.c_int32)),
                                                 gaps.ctypes.data_as(C.POINTER(C.c_float)), C.byref(obj)))
         steps = [removed[i * t_hat:min((i + 1) * t_hat, nrem)].tolist() for i in range(iters)]
         return obj.value, steps, gaps[:iters].copy()

@@ -515,8 +515,8 @@ static osscar_status read_ctrl(osscar_ctx* c, SearchCtrl* h) {
   return OSSCAR_OK;
 }
 
-osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_every, int32_t* removed_host, float* gaps_host,
-                                 double* obj_host) {
+osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_every, uint32_t flags, int32_t* removed_host,
+                                 float* gaps_host, double* obj_host) {
   osscar_status st = check_ctx(c);
   if (st != OSSCAR_OK) return st;
   if (c->phase != osscar_ctx::FINAL && c->phase != osscar_ctx::READY)
@@ -534,22 +534,34 @@ osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_e
   if (st != OSSCAR_OK) { c->kr = k * q; c->cr = c->d1 - c->kr; return st; }
   SearchCtrl h{};
   h.obj = 0.0;                      // the dense layer reproduces its own output exactly
-  h.g_out = -1; h.g_in = -1;
+  h.g_out = -1; h.g_in = -1; h.tau = 0; h.pause = 0;
   HIPCHK(c, hipMemcpyAsync(c->ctrl, &h, sizeof h, hipMemcpyHostToDevice, s));
   TabDims d = dims(c);
   TabPtrs t = ptrs(c);
   t.trace_out = c->g_removed; t.trace_in = nullptr; t.trace_gap = nullptr; t.trace_obj = nullptr;
-  int kept_now = p, iter = 0, since_refresh = 0, since_check = 0;
+  // groups of one row: delayed updates (the removals accumulate as pending pivots and reach N, Z by matrix products
+  // once LAZY_TM of them are pending); larger groups: in-place rank-q updates
+  const bool use_lazy = (q == 1) && !(flags & OSSCAR_SEARCH_EAGER);
+  const LazyPtrs& L = c->lazy;
+  if (use_lazy) HIPCHK(c, launch_lazy_init(d, t, L, s));
+  int kept_now = p, iter = 0, since_refresh = 0, since_check = 0, pending = 0;
   while (kept_now > k) {
     const int take = std::min<int>(t_hat, kept_now - k);
+    if (use_lazy && pending + take > LAZY_TM) { HIPCHK(c, launch_lazy_flush(d, t, L, s)); pending = 0; }
     HIPCHK(c, launch_greedy_pick(d, t, take, c->g_pick, c->g_gap + iter, s));
-    for (int i = 0; i < take; i++) HIPCHK(c, launch_search_iteration(d, t, -1, -1, 1, s, nullptr, c->g_pick + i));
+    for (int i = 0; i < take; i++) {
+      if (use_lazy) HIPCHK(c, launch_lazy_iteration(d, t, L, 1, s, nullptr, c->g_pick + i));
+      else HIPCHK(c, launch_search_iteration(d, t, -1, -1, 1, s, nullptr, c->g_pick + i));
+    }
+    pending += take;
     kept_now -= take; iter++; since_refresh += take; since_check += take;
     const bool refresh = refresh_every > 0 && since_refresh >= refresh_every && kept_now > k;
+    if (use_lazy && (refresh || kept_now == k) && pending > 0) { HIPCHK(c, launch_lazy_flush(d, t, L, s)); pending = 0; }
     if (since_check >= 256 || refresh || kept_now == k) {
       st = read_ctrl(c, &h);
       if (st != OSSCAR_OK) return st;
       if (h.notpd) return fail(c, OSSCAR_ENOTPD, "osscar_init_greedy: a pivot block lost definiteness after %d removals", h.iters);
+      if (h.pause) return fail(c, OSSCAR_ESTATE, "internal: the pending-pivot set overflowed in osscar_init_greedy");
       since_check = 0;
     }
     if (refresh) {

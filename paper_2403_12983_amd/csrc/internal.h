@@ -126,8 +126,9 @@ struct LazyPtrs {
 };
 hipError_t launch_lazy_init(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s);
 // ev (optional): events recorded before and after the pass over Z0, and at the end of the iteration
+// single (optional, device): removal of the one row *single instead of a swap; adds one pending pivot instead of two
 hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, int always_accept, hipStream_t s,
-                                 hipEvent_t* ev = nullptr);
+                                 hipEvent_t* ev = nullptr, const int32_t* single = nullptr);
 hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s);
 
 hipError_t launch_scatter_rows(const float* src, int64_t lds, const int32_t* rows, int nrows, int ncols, void* dst,

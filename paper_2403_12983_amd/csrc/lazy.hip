@@ -71,8 +71,9 @@ __global__ __launch_bounds__(64) void lazy_partials_kernel(LazyPtrs L, int p, co
 }
 
 // ---------------------------------------------------------------------------------------------- prep
+// single != nullptr: removal of the one row *single (Case 1 alone, nothing enters): the second pivot's quantities are zero.
 __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float* __restrict__ N0, int d1, int nrec,
-                                                         SearchCtrl* ctrl) {
+                                                         SearchCtrl* ctrl, const int32_t* __restrict__ single) {
   __shared__ double s_mn1[256], s_mn2[256], s_mx1[256], s_mx2[256];
   __shared__ int s_imn[256], s_imx[256];
   __shared__ double bg[LAZY_TM], bj[LAZY_TM], red[3][4];
@@ -95,13 +96,13 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
     }
     __syncthreads();
   }
-  const int g = s_imn[0], j = s_imx[0], tau = ctrl->tau;
+  const int g = single ? *single : s_imn[0], j = single ? g : s_imx[0], tau = ctrl->tau;
   if (g < 0 || j < 0) { if (tid == 0) { ctrl->done = 1; ctrl->g_out = -1; ctrl->g_in = -1; } return; }
-  if (L.pos[g] >= 0 || L.pos[j] >= 0 || tau + 2 > LAZY_TM) { if (tid == 0) ctrl->pause = 1; return; }
+  if (L.pos[g] >= 0 || L.pos[j] >= 0 || tau + (single ? 1 : 2) > LAZY_TM) { if (tid == 0) ctrl->pause = 1; return; }
   // b = N0[T, {g, j}] (these are rows g, j of C0), x = M^-1 b, zero beyond tau
   for (int s = tid; s < LAZY_TM; s += 256) {
     bg[s] = (s < tau) ? (double)L.C0R[(int64_t)g * LAZY_TM + s] : 0.0;
-    bj[s] = (s < tau) ? (double)L.C0R[(int64_t)j * LAZY_TM + s] : 0.0;
+    bj[s] = (s < tau && !single) ? (double)L.C0R[(int64_t)j * LAZY_TM + s] : 0.0;
   }
   __syncthreads();
   double pgg = 0, pjg = 0, pjj = 0;
@@ -121,11 +122,12 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
     const double njj = (double)nsym1(N0, d1, j, j) - (red[2][0] + red[2][1] + red[2][2] + red[2][3]);
     const bool bad1 = !(ngg < 0.0);                         // kept pivot: N_gg = -P_gg
     const double Dg = 1.0 / (bad1 ? -1.0 : ngg);
-    const double M1 = Dg * njg;
+    double M1 = Dg * njg;
     const double njjp = njj - njg * M1;                     // entering pivot after the first sweep: a Schur complement
-    const bool bad2 = !(njjp > 0.0);
-    const double Dj = 1.0 / (bad2 ? 1.0 : njjp);
-    L.ls[LS_DG] = Dg; L.ls[LS_NJG] = njg; L.ls[LS_M1] = M1; L.ls[LS_DJ] = Dj; L.ls[LS_OBJ] = ctrl->obj;
+    bool bad2 = !(njjp > 0.0);
+    double Dj = 1.0 / (bad2 ? 1.0 : njjp);
+    if (single) { M1 = 0.0; Dj = 0.0; bad2 = false; }
+    L.ls[LS_DG] = Dg; L.ls[LS_NJG] = single ? 0.0 : njg; L.ls[LS_M1] = M1; L.ls[LS_DJ] = Dj; L.ls[LS_OBJ] = ctrl->obj;
     if (bad1 || bad2) ctrl->notpd = 1;
     ctrl->g_out = g; ctrl->g_in = j;
     const double m1 = s_mn1[0], m2 = s_mn2[0], x1 = s_mx1[0], x2 = s_mx2[0];
@@ -239,11 +241,10 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
         const int it = ctrl->iters;
         ctrl->iters = it + 1;
         if (ok) { ctrl->obj = obj + delta; ctrl->accepted += 1; } else { ctrl->done = 1; }
-        if (trace_out) {
-          trace_out[it] = ctrl->g_out; trace_in[it] = ctrl->g_in;
-          trace_gap[2 * it] = (float)ctrl->gap_rem; trace_gap[2 * it + 1] = (float)ctrl->gap_add;
-          trace_obj[it] = ok ? obj + delta : obj;
-        }
+        if (trace_out) trace_out[it] = ctrl->g_out;
+        if (trace_in) trace_in[it] = ctrl->g_in;
+        if (trace_gap) { trace_gap[2 * it] = (float)ctrl->gap_rem; trace_gap[2 * it + 1] = (float)ctrl->gap_add; }
+        if (trace_obj) trace_obj[it] = ok ? obj + delta : obj;
       }
     }
   }
@@ -332,7 +333,7 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
 __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const float* __restrict__ N0, int d1, int m, int row_blocks,
                                                            int col_blocks, SearchCtrl* ctrl, int32_t* __restrict__ kept,
                                                            double* __restrict__ rho, double* __restrict__ diag,
-                                                           double* __restrict__ score) {
+                                                           double* __restrict__ score, int single) {
   __shared__ double sa[LAZY_TM], sb[LAZY_TM];
   __shared__ double w_mn1[4], w_mn2[4], w_mx1[4], w_mx2[4];
   __shared__ int w_imn[4], w_imx[4];
@@ -354,7 +355,7 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
       if (l8 == 0) {
         // the base columns of g and j become columns tau, tau + 1 of C0
         L.C0R[(int64_t)row * LAZY_TM + tau] = nsym1(N0, d1, row, g);
-        L.C0R[(int64_t)row * LAZY_TM + tau + 1] = nsym1(N0, d1, row, j);
+        if (!single) L.C0R[(int64_t)row * LAZY_TM + tau + 1] = nsym1(N0, d1, row, j);
         double r, dn;
         int kp;
         if (row == g) {
@@ -407,7 +408,10 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
     if (col < m) {
       const double y1 = L.y1[col], y2 = L.y2[col];
       for (int s = slice; s < tau; s += 4) L.ZT[(int64_t)s * m + col] -= sa[s] * y1 + sb[s] * y2;
-      if (slice == 0) { L.ZT[(int64_t)tau * m + col] = y1 - M1 * y2; L.ZT[(int64_t)(tau + 1) * m + col] = y2; }
+      if (slice == 0) {
+        L.ZT[(int64_t)tau * m + col] = y1 - M1 * y2;
+        if (!single) L.ZT[(int64_t)(tau + 1) * m + col] = y2;
+      }
     }
   } else {
     const int mb = b - row_blocks - col_blocks, nmb = gridDim.x - row_blocks - col_blocks;
@@ -423,13 +427,16 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
         const double xr = L.xg[r], pr = L.xj[r] - xr * M1;
         const double v = -xr * Dg + pr * M1 * Dj;          // bordered by g, then corrected by the sweep on j
         Mi[r * LAZY_TM + tau] = v; Mi[tau * LAZY_TM + r] = v;
+        if (single) continue;
         const double w = -pr * Dj;
         Mi[r * LAZY_TM + tau + 1] = w; Mi[(tau + 1) * LAZY_TM + r] = w;
       }
       if (tid == 0) {
         Mi[tau * LAZY_TM + tau] = Dg + M1 * M1 * Dj;
-        Mi[tau * LAZY_TM + tau + 1] = -M1 * Dj; Mi[(tau + 1) * LAZY_TM + tau] = -M1 * Dj;
-        Mi[(tau + 1) * LAZY_TM + tau + 1] = Dj;
+        if (!single) {
+          Mi[tau * LAZY_TM + tau + 1] = -M1 * Dj; Mi[(tau + 1) * LAZY_TM + tau] = -M1 * Dj;
+          Mi[(tau + 1) * LAZY_TM + tau + 1] = Dj;
+        }
       }
     }
   }
@@ -441,13 +448,13 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
     s_last = (done_blocks == (int)gridDim.x - 1);
   }
   __syncthreads();
-  if (s_last && tid == 0) { *L.counter = 0; ctrl->tau = tau + 2; }
+  if (s_last && tid == 0) { *L.counter = 0; ctrl->tau = tau + (single ? 1 : 2); }
 }
 
 hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, int always_accept, hipStream_t s,
-                                 hipEvent_t* ev) {
+                                 hipEvent_t* ev, const int32_t* single) {
   const int rb = (d.d1 + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, cb = (d.m + COLS_PER_BLOCK - 1) / COLS_PER_BLOCK;
-  hipLaunchKernelGGL(lazy_prep_kernel, dim3(1), dim3(256), 0, s, L, t.N, d.d1, rb, t.ctrl);
+  hipLaunchKernelGGL(lazy_prep_kernel, dim3(1), dim3(256), 0, s, L, t.N, d.d1, rb, t.ctrl, single);
   hipLaunchKernelGGL(lazy_vectors_kernel, dim3(rb + cb), dim3(256), 0, s, L, t.N, t.Z, d.d1, d.m, rb, t.ctrl);
   const int gb = (d.d1 + GEMV_ROWS - 1) / GEMV_ROWS + LAZY_TM / 4;
   if (ev) hipEventRecord(ev[0], s);
@@ -455,7 +462,7 @@ hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyP
                      t.trace_in, t.trace_gap, t.trace_obj);
   if (ev) hipEventRecord(ev[1], s);
   hipLaunchKernelGGL(lazy_update_kernel, dim3(rb + cb + 16), dim3(256), 0, s, L, t.N, d.d1, d.m, rb, cb, t.ctrl, t.kept, t.gram,
-                     t.dblk, t.score);
+                     t.dblk, t.score, single ? 1 : 0);
   if (ev) hipEventRecord(ev[2], s);
   return hipGetLastError();
 }

@@ -380,6 +380,9 @@ def test_greedy_refresh_and_edges():
     obj_b, steps_b, gaps_b = s.osscar_init_greedy(10, refresh_every=40)           # rebuilt from H, G every 40 removals
     check_greedy(c, 10, obj_b, steps_b, gaps_b)
     assert abs(obj_a - obj_b) <= 1e-5 * obj_b
+    # in-place updates after every removal take the same path as the delayed updates
+    obj_e, steps_e, gaps_e = s.osscar_init_greedy(10, 0, _pkg().OSSCAR_SEARCH_EAGER)
+    assert steps_e == steps_a and abs(obj_e - obj_a) <= 1e-6 * obj_a
     s.close()
     from paper_2403_12983_amd.binding import OsscarError
     s = c.solver()                                                               # created without from_dense
