@@ -82,6 +82,10 @@ def main():
     ap.add_argument("--swaps", type=int, default=None)
     ap.add_argument("--refresh-every", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--init", choices=("magnitude", "greedy"), default="magnitude",
+                    help="magnitude: the benchmark layer's recipe (magnitude support, then swaps); greedy: the nested "
+                         "schedule of Algorithm 1 from the dense layer (t-hat groups pruned per iteration), then swaps")
+    ap.add_argument("--t-hat", type=int, default=10)
     ap.add_argument("--rows", type=int, default=None,
                     help="calibration rows (default: the config's); a short X keeps counter-collection runs brief")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -103,7 +107,7 @@ def main():
     dev = "cuda:0"
     X = gen_on_gpu(inp, torch, cfg, dev)
     W = inp.gen_W(cfg, dev)
-    s = pkg.Solver(cfg.d1, cfg.m, cfg.p, cfg.q, cfg.k, max(swaps, 1), X.dtype, W.dtype, dev)
+    s = pkg.Solver(cfg.d1, cfg.m, cfg.p, cfg.q, cfg.k, max(swaps, 1), X.dtype, W.dtype, dev, from_dense=(a.init == "greedy"))
     torch.cuda.synchronize()
 
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
@@ -118,7 +122,7 @@ def main():
         ev[1].record()
         s.osscar_gram(None, True, W, cfg.lam_abs, cfg.lam_rel)
         ev[2].record()
-        obj0 = s.osscar_init_support()
+        obj0 = s.osscar_init_support() if a.init == "magnitude" else s.osscar_init_greedy(a.t_hat)[0]
         ev[3].record()
         r = s.osscar_local_search(swaps, 0.0, 0, a.refresh_every)
         ev[4].record()
@@ -171,7 +175,8 @@ def main():
         "vs_baseline": None, "dtype": "bf16 inputs, f32 state, f64 accumulate", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: X {n}x{d1} {cfg.x_dtype}, W {d1}x{m} {cfg.w_dtype}, keep {cfg.k} of {cfg.p} groups "
                                f"(q={cfg.q}), {swaps} swaps, lambda = {cfg.lam_rel}*mean diag",
-                   "refresh_every": a.refresh_every, "search": "delayed-update" if lazy else "eager"},
+                   "refresh_every": a.refresh_every, "search": "delayed-update" if lazy else "eager",
+                   "init": a.init if a.init == "magnitude" else f"nested schedule from the dense layer, t_hat = {a.t_hat}"},
         "phases_s": phases,
         "swap_iterations": info["iters"], "accepted_swaps": info["accepted"],
         "swap_evals_per_s": info["iters"] * cfg.p / phases["search"] if phases["search"] > 0 else None,
