@@ -64,6 +64,28 @@ def objective_direct(X: np.ndarray, W: np.ndarray, What: np.ndarray, lam: float)
     return float(np.sum((X @ D) ** 2) + lam * np.sum(D ** 2))
 
 
+def gram_target(X: np.ndarray, Y: np.ndarray, W: np.ndarray, lam_abs: float = 0.0, lam_rel: float = 0.0):
+    """Sequential-pipeline variant (Appendix B.1, "Pruning strategies"): the layer is asked to reproduce the DENSE
+    model's output Y = Xhat W from the pruned model's input X, i.e. obj(What) = ||Y - X What||_F^2 + lam ||W - What||_F^2.
+    Expanding gives the same quadratic form with H = X^T X + lam I, G = X^T Y + lam W, c0 = ||Y||_F^2 + lam ||W||_F^2."""
+    X = np.asarray(X, dtype=np.float64)
+    Y = np.asarray(Y, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    H = X.T @ X
+    lam = float(lam_abs) + float(lam_rel) * float(np.mean(np.diag(H)))
+    H = H + lam * np.eye(H.shape[0])
+    G = X.T @ Y + lam * W
+    c0 = float(np.sum(Y * Y) + lam * np.sum(W * W))
+    return H, G, c0, lam
+
+
+def objective_target(X: np.ndarray, Y: np.ndarray, W: np.ndarray, What: np.ndarray, lam: float) -> float:
+    """||Y - X What||_F^2 + lam ||W - What||_F^2 from its definition."""
+    X = np.asarray(X, dtype=np.float64)
+    What = np.asarray(What, dtype=np.float64)
+    return float(np.sum((np.asarray(Y, dtype=np.float64) - X @ What) ** 2) + lam * np.sum((np.asarray(W, dtype=np.float64) - What) ** 2))
+
+
 def objective_quadratic(H: np.ndarray, G: np.ndarray, c0: float, What: np.ndarray) -> float:
     """c0 + 2 L(What) with L from eq. (MIQP)."""
     return float(c0 + np.sum(What * (H @ What)) - 2.0 * np.sum(G * What))

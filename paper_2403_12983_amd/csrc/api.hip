@@ -768,7 +768,8 @@ osscar_status osscar_backsolve(osscar_ctx* c, void* What, int64_t ldw_hat, int32
   InvBufs b = carve_inv(c, cv);
   // Refine the maintained weights instead of refactorising: B <- B + P (G_K - H_KK B) with the maintained inverse P
   // and a float64-accumulated residual.  One step shrinks the error by |I - P H_KK| (about 1e-3 after thousands of
-  // swaps); a second step is taken if the first correction was not tiny, and a fresh inverse if it was large.
+  // swaps, so after a correction of relative size r the error left is about 1e-3 r); a second step is taken if the
+  // first correction was not small, and a fresh inverse if it was large.
   {
     const int kr = c->kr, m = c->m;
     HIPCHK(c, launch_gather(c->H, c->d1, c->rowsK, kr, c->rowsK, kr, b.HKK, kr, s));
@@ -788,7 +789,7 @@ osscar_status osscar_backsolve(osscar_ctx* c, void* What, int64_t ldw_hat, int32
       HIPCHK(c, hipStreamSynchronize(s));
       const double ratio = std::sqrt(nn[0] / std::max(nn[1], 1e-300));
       if (!(ratio < 1e-2)) break;             // the maintained inverse is not good enough: refactorise
-      if (ratio < 1e-5) ok = true;            // the next correction would be below float32 resolution
+      if (ratio < 1e-4) ok = true;            // what is left is ratio * |I - P H_KK| <= 1e-6: below the float32 storage of B
     }
     if (!ok) {
       st = inverse_and_weights(c, b);

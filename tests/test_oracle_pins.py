@@ -302,6 +302,51 @@ def test_always_accept_runs_the_printed_algorithm():
     assert np.isclose(o, res.obj_final, rtol=1e-8)
 
 
+# ---------------------------------------------------------------- sequential-pipeline target (Appendix B.1)
+def test_target_form_reduces_to_the_plain_form_and_matches_its_definition():
+    rng = np.random.default_rng(31)
+    n, d1, m, lam = 50, 9, 4, 0.3
+    X = rng.standard_normal((n, d1))
+    Xhat = X + 0.2 * rng.standard_normal((n, d1))          # the dense model's input differs from the pruned model's
+    W = rng.standard_normal((d1, m))
+    # same inputs on both sides: the plain quadratic form
+    H0, G0, c00, lam0 = orc.gram(X, W, lam_abs=lam)
+    H1, G1, c01, lam1 = orc.gram_target(X, X @ W, W, lam_abs=lam)
+    assert np.allclose(H0, H1) and np.allclose(G0, G1, rtol=1e-12, atol=1e-12) and np.isclose(c00, c01) and lam0 == lam1
+    # different inputs: the quadratic form equals the loss written out, for any weights
+    Y = Xhat @ W
+    H, G, c0, lam_u = orc.gram_target(X, Y, W, lam_abs=0.1, lam_rel=0.05)
+    assert np.isclose(lam_u, 0.1 + 0.05 * np.mean(np.sum(X * X, axis=0)))
+    for _ in range(3):
+        What = rng.standard_normal((d1, m))
+        What[[1, 4, 7]] = 0
+        assert np.isclose(orc.objective_quadratic(H, G, c0, What), orc.objective_target(X, Y, W, What, lam_u), rtol=1e-10)
+
+
+def test_target_form_optimum_is_ridge_least_squares_onto_the_dense_output():
+    rng = np.random.default_rng(32)
+    n, p, q, m = 60, 6, 2, 3
+    d1 = p * q
+    X = rng.standard_normal((n, d1))
+    Y = (X + 0.3 * rng.standard_normal((n, d1))) @ rng.standard_normal((d1, m))
+    W = rng.standard_normal((d1, m))
+    H, G, c0, lam = orc.gram_target(X, Y, W, lam_abs=0.2)
+    K = [0, 2, 5]
+    rows = orc.rows_of(K, q)
+    What, obj = orc.solve_support(H, G, c0, K, q)
+    A = np.vstack([X[:, rows], math.sqrt(lam) * np.eye(d1)[:, rows]])
+    Bm = np.vstack([Y, math.sqrt(lam) * W])
+    sol, *_ = np.linalg.lstsq(A, Bm, rcond=None)
+    assert np.allclose(What[rows], sol, rtol=1e-8, atol=1e-10)
+    assert np.isclose(obj, orc.objective_target(X, Y, W, What, lam), rtol=1e-10)
+    # the dense layer no longer reproduces the target exactly: the nested schedule starts from a positive objective
+    dense, obj_dense = orc.solve_support(H, G, c0, list(range(p)), q)
+    assert obj_dense > 1e-6 * c0 and np.isclose(obj_dense, orc.objective_target(X, Y, W, dense, lam), rtol=1e-10)
+    res = orc.greedy_from_dense(H, G, c0, p, q, 3, 2)
+    _, o = orc.solve_support(H, G, c0, res.support, q)
+    assert np.isclose(res.obj_final, o, rtol=1e-10)
+
+
 # ---------------------------------------------------------------- nested schedule from the dense layer (Algorithm 1)
 def test_dense_start_is_the_dense_layer():
     # S_0 empty: every group kept, the optimal weights are W itself and the objective is zero
