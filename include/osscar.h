@@ -61,7 +61,7 @@ typedef struct {
   int32_t x_dtype;   /* osscar_dtype of X */
   int32_t w_dtype;   /* osscar_dtype of W */
   int32_t from_dense; /* nonzero: size the workspace for osscar_init_greedy too (it inverts all of H) */
-  int32_t reserved;  /* set to 0 */
+  int32_t target_output; /* nonzero: size the workspace for osscar_gram_target too */
 } osscar_desc;
 
 /* Bytes of device workspace osscar_create needs for this description (0 if the description is invalid). */
@@ -84,6 +84,18 @@ osscar_status osscar_destroy(osscar_ctx* ctx);
 osscar_status osscar_gram(osscar_ctx* ctx, const void* Xc_dev, int64_t n_c, int64_t ldx, int finalize,
                           const void* W_dev, int64_t ldw, double lambda_abs, double lambda_rel);
 
+/* Sequential-pipeline variant of osscar_gram (Appendix B.1, "Pruning strategies": the layer is asked to reproduce
+ * the DENSE model's output from the PRUNED model's input).  Yc_dev: dev, row-major n_c x m, leading dimension
+ * ldy >= m, dtype desc.x_dtype: the dense model's output of this layer for the same calibration rows as Xc.
+ * Accumulates H += Xc^T Xc and X^T Y += Xc^T Yc (float64 across chunks) and ||Y||_F^2.  finalize: lambda as in
+ * osscar_gram; H += lambda I; G = X^T Y + lambda W; c0 = ||Y||_F^2 + lambda ||W||_F^2, so that
+ * obj(What) = ||Y - X What||_F^2 + lambda ||W - What||_F^2 = c0 - 2 Tr(G^T What) + Tr(What^T H What) and every later
+ * call works unchanged.  Needs desc.target_output != 0.  A layer takes all its chunks through this call or all
+ * through osscar_gram (OSSCAR_ESTATE otherwise). */
+osscar_status osscar_gram_target(osscar_ctx* ctx, const void* Xc_dev, const void* Yc_dev, int64_t n_c, int64_t ldx,
+                                 int64_t ldy, int finalize, const void* W_dev, int64_t ldw, double lambda_abs,
+                                 double lambda_rel);
+
 /* Alternative to osscar_gram for callers that already hold the quadratic form: copies H (d1 x d1,
  * symmetric positive definite, ridge included) and G (d1 x m), both dev float32 row-major and dense
  * (ld = d1, m), and takes c0 and the p group norms (host float64) used by the magnitude mode. */
@@ -101,7 +113,8 @@ osscar_status osscar_init_support(osscar_ctx* ctx, int mode, const int32_t* grou
 
 /* Nested schedule of Algorithm 1 from the dense layer (S_0 empty and t_i = p_i = t_hat for every iteration:
  * Section 4.2; Appendix B.1 takes t_hat = 2 for channels and attention heads and 10 for the intermediate
- * dimension of feed-forward layers).  Starts with every group kept (P = H^-1, B = H^-1 G, obj = 0); each
+ * dimension of feed-forward layers).  Starts with every group kept (P = H^-1, B = H^-1 G; obj = 0 after
+ * osscar_gram, c0 - Tr(G^T B) otherwise); each
  * iteration scores every kept group by the cost of removing it (eq. (impact), closed form of
  * Proposition 4.1 Case 1) at the state the iteration starts from, removes the t_hat cheapest (lowest group
  * index on ties; the last iteration takes what is left to reach k) and updates inverse, weights and objective

@@ -16,7 +16,8 @@ OSSCAR_SEARCH_EAGER = 2
 T_H, T_G, T_P, T_B, T_V, T_R, T_REM, T_ADD, T_KEPT, T_CAND = range(10)
 _STATUS = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "ENOTPD", 4: "EHIP", 5: "ESTATE"}
 
-EXPORTED_SYMBOLS = ["osscar_workspace_bytes", "osscar_create", "osscar_destroy", "osscar_gram", "osscar_set_quadratic",
+EXPORTED_SYMBOLS = ["osscar_workspace_bytes", "osscar_create", "osscar_destroy", "osscar_gram", "osscar_gram_target",
+                    "osscar_set_quadratic",
                     "osscar_init_support", "osscar_init_greedy", "osscar_local_search", "osscar_apply_swap", "osscar_backsolve",
                     "osscar_get_tensor", "osscar_get_scalars", "osscar_get_timers", "osscar_last_error"]
 
@@ -30,7 +31,7 @@ class OsscarError(RuntimeError):
 class _Desc(C.Structure):
     _fields_ = [("d1", C.c_int64), ("m", C.c_int64), ("p", C.c_int32), ("q", C.c_int32), ("k", C.c_int32),
                 ("max_swaps", C.c_int32), ("x_dtype", C.c_int32), ("w_dtype", C.c_int32), ("from_dense", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("target_output", C.c_int32)]
 
 
 class _SearchResult(C.Structure):
@@ -60,6 +61,7 @@ def load_library():
     lib.osscar_create.argtypes = [C.POINTER(vp), C.POINTER(_Desc), vp, C.c_size_t, vp]
     lib.osscar_destroy.argtypes = [vp]
     lib.osscar_gram.argtypes = [vp, vp, i64, i64, C.c_int, vp, i64, dbl, dbl]
+    lib.osscar_gram_target.argtypes = [vp, vp, vp, i64, i64, i64, C.c_int, vp, i64, dbl, dbl]
     lib.osscar_set_quadratic.argtypes = [vp, vp, vp, dbl, C.POINTER(dbl)]
     lib.osscar_init_support.argtypes = [vp, C.c_int, C.POINTER(i32), C.POINTER(dbl)]
     lib.osscar_init_greedy.argtypes = [vp, i32, i32, C.c_uint32, C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(dbl)]
@@ -92,13 +94,13 @@ class Solver:
 
     def __init__(self, d1: int, m: int, p: int, q: int, k: int, max_swaps: int, x_dtype=torch.bfloat16,
                  w_dtype=torch.bfloat16, device="cuda:0", stream: Optional[torch.cuda.Stream] = None,
-                 from_dense: bool = False):
+                 from_dense: bool = False, target_output: bool = False):
         self.lib = load_library()
         self.device = torch.device(device)
         self.d1, self.m, self.p, self.q, self.k = d1, m, p, q, k
         self.kr, self.cr = k * q, d1 - k * q
         self.max_swaps = max_swaps
-        self.desc = _Desc(d1, m, p, q, k, max_swaps, _dtype_code(x_dtype), _dtype_code(w_dtype), int(from_dense), 0)
+        self.desc = _Desc(d1, m, p, q, k, max_swaps, _dtype_code(x_dtype), _dtype_code(w_dtype), int(from_dense), int(target_output))
         nbytes = self.lib.osscar_workspace_bytes(C.byref(self.desc))
         if nbytes == 0:
             raise OsscarError(1, "invalid problem description")
@@ -146,6 +148,21 @@ class Solver:
             assert _dtype_code(W.dtype) == self.desc.w_dtype
             wp, ldw = W.data_ptr(), W.stride(0)
         self._check(self.lib.osscar_gram(self.ctx, xp, n_c, ldx, int(finalize), wp, ldw, lambda_abs, lambda_rel))
+
+    def osscar_gram_target(self, Xc: Optional[torch.Tensor], Yc: Optional[torch.Tensor], finalize: bool = False,
+                           W: Optional[torch.Tensor] = None, lambda_abs: float = 0.0, lambda_rel: float = 0.0):
+        xp, yp, n_c, ldx, ldy = None, None, 0, self.d1, self.m
+        if Xc is not None and Xc.shape[0] > 0:
+            assert Xc.is_cuda and Xc.dim() == 2 and Xc.shape[1] == self.d1 and Xc.stride(1) == 1
+            assert Yc is not None and Yc.is_cuda and Yc.shape == (Xc.shape[0], self.m) and Yc.stride(1) == 1
+            assert _dtype_code(Xc.dtype) == self.desc.x_dtype and Yc.dtype == Xc.dtype
+            xp, yp, n_c, ldx, ldy = Xc.data_ptr(), Yc.data_ptr(), Xc.shape[0], Xc.stride(0), Yc.stride(0)
+        wp, ldw = None, self.m
+        if finalize:
+            assert W is not None and W.is_cuda and W.shape == (self.d1, self.m) and W.stride(1) == 1
+            assert _dtype_code(W.dtype) == self.desc.w_dtype
+            wp, ldw = W.data_ptr(), W.stride(0)
+        self._check(self.lib.osscar_gram_target(self.ctx, xp, yp, n_c, ldx, ldy, int(finalize), wp, ldw, lambda_abs, lambda_rel))
 
     def osscar_set_quadratic(self, H: torch.Tensor, G: torch.Tensor, c0: float, group_norms: Sequence[float]):
         assert H.is_cuda and H.dtype == torch.float32 and H.is_contiguous() and H.shape == (self.d1, self.d1)

@@ -18,6 +18,9 @@ namespace {
 constexpr int64_t XT_ROWS = 4096;   // calibration rows per sub-step of the generic (non-MFMA-bf16) Gram path
 constexpr int64_t PACK_ROWS = 16384;   // calibration rows repacked at a time on the bf16 MFMA path
 // staging buffer of the Gram phase: float32 X^T sub-step (generic path) or repacked bf16 rows (MFMA path)
+size_t rect_tile_entries(int64_t d1, int64_t m) { return (size_t)(((d1 + 127) / 128 + 3) / 4 * (((m + 127) / 128 + 7) / 8) + 8) * 32; }
+// staging of a target chunk: repacked bf16 rows (MFMA path) or a float32 sub-step (generic path)
+size_t target_stage_bytes(int64_t m) { return (size_t)std::max<int64_t>(XT_ROWS * m * 4, PACK_ROWS * ((m + 127) / 128 * 128) * 2); }
 size_t gram_stage_bytes(int64_t d1) { return (size_t)std::max<int64_t>(d1 * XT_ROWS * 4, PACK_ROWS * ((d1 + 127) / 128 * 128) * 2); }
 constexpr int EV_SAMPLES = 64;
 
@@ -94,6 +97,8 @@ struct osscar_ctx {
   char* scratch; size_t scratch_bytes;
 
   double lambda = 0, c0 = 0;
+  int accum_target = 0;          // the layer being accumulated takes its chunks through osscar_gram_target
+  bool dense_is_exact = true;    // the dense layer has objective 0 (false for a target output or a caller-supplied quadratic form)
   std::vector<double> norms_host;
   std::vector<int32_t> kept_host;
   double timers[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -156,6 +161,8 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
   // scratch: the larger of the Gram phase and the init / refresh / backsolve phase
   size_t gram_phase = align_up((size_t)d1 * d1 * 8) + align_up((size_t)d1 * m * 4) + align_up(gram_stage_bytes(d1)) +
                       align_up(gram_tile_entries(d1) * 8);
+  if (ds.target_output)
+    gram_phase += align_up((size_t)d1 * m * 8) + align_up(target_stage_bytes(m)) + align_up(rect_tile_entries(d1, m) * 8);
   auto init_bytes = [&](size_t a, size_t b) {   // kept rows a, candidate rows b
     return 4 * align_up(a * a * 4) + 3 * align_up(a * b * 4) + align_up(b * b * 4) + 4 * align_up(a * m * 4) + align_up(b * m * 4) +
            3 * align_up(a * 64 * 4) + 4096;
@@ -393,12 +400,17 @@ osscar_status osscar_destroy(osscar_ctx* c) {
 
 const char* osscar_last_error(const osscar_ctx* c) { return c ? c->err.c_str() : "null context"; }
 
-osscar_status osscar_gram(osscar_ctx* c, const void* Xc, int64_t n_c, int64_t ldx, int finalize, const void* W, int64_t ldw,
-                          double lambda_abs, double lambda_rel) {
+// Shared body of osscar_gram (Yc == nullptr, target == 0) and osscar_gram_target.
+static osscar_status gram_impl(osscar_ctx* c, const char* who, int target, const void* Xc, const void* Yc, int64_t n_c, int64_t ldx,
+                               int64_t ldy, int finalize, const void* W, int64_t ldw, double lambda_abs, double lambda_rel) {
   osscar_status st = check_ctx(c);
   if (st != OSSCAR_OK) return st;
-  if (n_c < 0 || (n_c > 0 && (!Xc || ldx < c->d1))) return fail(c, OSSCAR_EINVAL, "osscar_gram: bad chunk (n_c=%lld, ldx=%lld)", (long long)n_c, (long long)ldx);
-  if (finalize && (!W || ldw < c->m)) return fail(c, OSSCAR_EINVAL, "osscar_gram: finalize needs W with ldw >= m");
+  if (n_c < 0 || (n_c > 0 && (!Xc || ldx < c->d1))) return fail(c, OSSCAR_EINVAL, "%s: bad chunk (n_c=%lld, ldx=%lld)", who, (long long)n_c, (long long)ldx);
+  if (target && n_c > 0 && (!Yc || ldy < c->m)) return fail(c, OSSCAR_EINVAL, "%s: bad target chunk (ldy=%lld)", who, (long long)ldy);
+  if (target && !c->desc.target_output) return fail(c, OSSCAR_EINVAL, "%s: the context was created without desc.target_output", who);
+  if (finalize && (!W || ldw < c->m)) return fail(c, OSSCAR_EINVAL, "%s: finalize needs W with ldw >= m", who);
+  if (c->phase == osscar_ctx::ACCUM && c->accum_target != target)
+    return fail(c, OSSCAR_ESTATE, "%s: a layer takes all its chunks through osscar_gram or all through osscar_gram_target", who);
   hipStream_t s = c->stream;
   const int d1 = c->d1, m = c->m;
   Carve cv(c->scratch);
@@ -407,17 +419,33 @@ osscar_status osscar_gram(osscar_ctx* c, const void* Xc, int64_t n_c, int64_t ld
   float* Xt = reinterpret_cast<float*>(cv.take<char>(gram_stage_bytes(d1)));
   const size_t tile_entries = gram_tile_entries(d1);
   int2* tile_buf = cv.take<int2>(tile_entries);
+  double* G64 = nullptr; float* Ys = nullptr; int2* tile_buf_y = nullptr;
+  const size_t tile_y_entries = rect_tile_entries(d1, m);
+  if (c->desc.target_output) {
+    G64 = cv.take<double>((int64_t)d1 * m);
+    Ys = reinterpret_cast<float*>(cv.take<char>(target_stage_bytes(m)));
+    tile_buf_y = cv.take<int2>(tile_y_entries);
+  }
   if (c->phase != osscar_ctx::ACCUM) {   // first chunk of a layer
     hipLaunchKernelGGL(fill_f64_kernel, dim3(grid_for((int64_t)d1 * d1)), dim3(256), 0, s, H64, (int64_t)d1 * d1, 0.0);
+    if (target) {
+      hipLaunchKernelGGL(fill_f64_kernel, dim3(grid_for((int64_t)d1 * m)), dim3(256), 0, s, G64, (int64_t)d1 * m, 0.0);
+      hipLaunchKernelGGL(fill_f64_kernel, dim3(1), dim3(64), 0, s, c->scal + 12, (int64_t)1, 0.0);
+    }
     c->phase = osscar_ctx::ACCUM;
+    c->accum_target = target;
     c->timers[0] = 0;
   }
   if (n_c > 0) {
     HIPCHK(c, hipEventRecord(c->ev_a, s));
     const bool bf16 = c->desc.x_dtype == OSSCAR_BF16;
-    const bool fast = bf16 && (d1 % 8 == 0) && (ldx % 8 == 0) && ((reinterpret_cast<uintptr_t>(Xc) & 15) == 0);
+    bool fast = bf16 && (d1 % 8 == 0) && (ldx % 8 == 0) && ((reinterpret_cast<uintptr_t>(Xc) & 15) == 0);
+    if (target) fast = fast && (m % 8 == 0) && (ldy % 8 == 0) && ((reinterpret_cast<uintptr_t>(Yc) & 15) == 0);
+    if (target) HIPCHK(c, launch_sumsq(Yc, bf16, n_c, m, ldy, c->scal + 12, s));
     if (fast) {
-      HIPCHK(c, launch_gram_packed(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, Xt, PACK_ROWS, s));
+      if (target) HIPCHK(c, launch_gram_packed(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, Xt, PACK_ROWS, s, Yc, ldy, m, G64,
+                                               tile_buf_y, tile_y_entries, Ys));
+      else HIPCHK(c, launch_gram_packed(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, Xt, PACK_ROWS, s));
     } else {
       const size_t esz = bf16 ? 2 : 4;
       for (int64_t r0 = 0; r0 < n_c; r0 += XT_ROWS) {
@@ -429,6 +457,14 @@ osscar_status osscar_gram(osscar_ctx* c, const void* Xc, int64_t n_c, int64_t ld
         g.Cin = reinterpret_cast<const float*>(H64); g.ldcin = d1; g.C = H64; g.ldc = d1; g.alpha = 1.0; g.beta = 1.0;
         g.c_is_f64 = 1; g.lower_only = 1;
         HIPCHK(c, launch_gemm_f64acc(g, s));
+        if (target) {   // G64 += Xt (d1 x nr) * Yc (nr x m)
+          const char* srcy = reinterpret_cast<const char*>(Yc) + (size_t)r0 * ldy * esz;
+          HIPCHK(c, launch_convert_to_f32(srcy, bf16, nr, m, ldy, Ys, s));
+          GemmArgs y{};
+          y.M = d1; y.N = m; y.K = (int)nr; y.A = Xt; y.lda = XT_ROWS; y.B = Ys; y.ldb = m;
+          y.Cin = reinterpret_cast<const float*>(G64); y.ldcin = m; y.C = G64; y.ldc = m; y.alpha = 1.0; y.beta = 1.0; y.c_is_f64 = 1;
+          HIPCHK(c, launch_gemm_f64acc(y, s));
+        }
       }
     }
     HIPCHK(c, hipEventRecord(c->ev_b, s));
@@ -445,18 +481,38 @@ osscar_status osscar_gram(osscar_ctx* c, const void* Xc, int64_t n_c, int64_t ld
   HIPCHK(c, hipMemcpyAsync(c->scal + 1, &c->lambda, 8, hipMemcpyHostToDevice, s));
   HIPCHK(c, launch_finalize_H(H64, c->H, d1, c->scal + 1, s));
   HIPCHK(c, launch_convert_to_f32(W, c->desc.w_dtype == OSSCAR_BF16, d1, m, ldw, Wf, s));
-  HIPCHK(c, gemm(s, d1, m, d1, c->H, d1, Wf, m, nullptr, 0, c->G, m, 1.0, 0.0));
-  HIPCHK(c, launch_dot64(Wf, c->G, (int64_t)d1 * m, c->scal + 2, c->partial, s));
+  double yy = 0;
+  if (target) {
+    // G = X^T Y + lambda W, c0 = ||Y||^2 + lambda ||W||^2
+    HIPCHK(c, launch_finalize_G(G64, Wf, c->scal + 1, c->G, (int64_t)d1 * m, s));
+    HIPCHK(c, launch_dot64(Wf, Wf, (int64_t)d1 * m, c->scal + 2, c->partial, s));
+    HIPCHK(c, hipMemcpyAsync(&yy, c->scal + 12, 8, hipMemcpyDeviceToHost, s));
+  } else {
+    HIPCHK(c, gemm(s, d1, m, d1, c->H, d1, Wf, m, nullptr, 0, c->G, m, 1.0, 0.0));
+    HIPCHK(c, launch_dot64(Wf, c->G, (int64_t)d1 * m, c->scal + 2, c->partial, s));
+  }
   HIPCHK(c, launch_group_norms(Wf, c->p, c->q, m, c->norms2, s));
   c->norms_host.resize(c->p);
   HIPCHK(c, hipMemcpyAsync(&c->c0, c->scal + 2, 8, hipMemcpyDeviceToHost, s));
   HIPCHK(c, hipMemcpyAsync(c->norms_host.data(), c->norms2, c->p * 8, hipMemcpyDeviceToHost, s));
   HIPCHK(c, hipEventRecord(c->ev_b, s));
   HIPCHK(c, hipStreamSynchronize(s));
+  if (target) c->c0 = yy + c->lambda * c->c0;
+  c->dense_is_exact = !target;
   c->timers[1] = elapsed(c);
   for (auto& v : c->norms_host) v = std::sqrt(v);
   c->phase = osscar_ctx::FINAL;
   return OSSCAR_OK;
+}
+
+osscar_status osscar_gram(osscar_ctx* c, const void* Xc, int64_t n_c, int64_t ldx, int finalize, const void* W, int64_t ldw,
+                          double lambda_abs, double lambda_rel) {
+  return gram_impl(c, "osscar_gram", 0, Xc, nullptr, n_c, ldx, 0, finalize, W, ldw, lambda_abs, lambda_rel);
+}
+
+osscar_status osscar_gram_target(osscar_ctx* c, const void* Xc, const void* Yc, int64_t n_c, int64_t ldx, int64_t ldy, int finalize,
+                                 const void* W, int64_t ldw, double lambda_abs, double lambda_rel) {
+  return gram_impl(c, "osscar_gram_target", 1, Xc, Yc, n_c, ldx, ldy, finalize, W, ldw, lambda_abs, lambda_rel);
 }
 
 osscar_status osscar_set_quadratic(osscar_ctx* c, const float* H_dev, const float* G_dev, double c0, const double* norms) {
@@ -467,7 +523,7 @@ osscar_status osscar_set_quadratic(osscar_ctx* c, const float* H_dev, const floa
   HIPCHK(c, hipMemcpyAsync(c->H, H_dev, (size_t)c->d1 * c->d1 * 4, hipMemcpyDeviceToDevice, s));
   HIPCHK(c, hipMemcpyAsync(c->G, G_dev, (size_t)c->d1 * c->m * 4, hipMemcpyDeviceToDevice, s));
   HIPCHK(c, hipStreamSynchronize(s));
-  c->c0 = c0; c->lambda = 0;
+  c->c0 = c0; c->lambda = 0; c->dense_is_exact = false;
   c->norms_host.assign(norms, norms + c->p);
   c->phase = osscar_ctx::FINAL;
   return OSSCAR_OK;
@@ -533,7 +589,7 @@ osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_e
   st = build_state(c, &obj);
   if (st != OSSCAR_OK) { c->kr = k * q; c->cr = c->d1 - c->kr; return st; }
   SearchCtrl h{};
-  h.obj = 0.0;                      // the dense layer reproduces its own output exactly
+  h.obj = c->dense_is_exact ? 0.0 : obj;   // the dense layer reproduces its own output exactly; a target output it does not
   h.g_out = -1; h.g_in = -1; h.tau = 0; h.pause = 0;
   HIPCHK(c, hipMemcpyAsync(c->ctrl, &h, sizeof h, hipMemcpyHostToDevice, s));
   TabDims d = dims(c);

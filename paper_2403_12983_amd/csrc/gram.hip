@@ -87,15 +87,18 @@ __global__ __launch_bounds__(256) void gram_pack_kernel(const uint16_t* __restri
 #undef OSSCAR_PACK_HI
 }
 
-__global__ __launch_bounds__(256, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void gram_packed_kernel(const uint4* __restrict__ Xp, int nstages, int npanels, int d1,
-                                                             double* __restrict__ H64, const int2* __restrict__ tile_list,
-                                                             int stages_per_split, int window) {
+// Out (+)= A^T B for packed operands Ap (rows of the result) and Bp (columns of the result); symmetric: Ap == Bp and only
+// tiles on or below the diagonal are listed, the diagonal ones loading one panel.
+__global__ __launch_bounds__(256, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void gram_packed_kernel(
+    const uint4* __restrict__ Ap, int64_t a_sstride, const uint4* __restrict__ Bp, int64_t b_sstride, int nstages, int rows_out,
+    int cols_out, int ldo, double* __restrict__ H64, const int2* __restrict__ tile_list, int stages_per_split, int window,
+    int symmetric) {
   constexpr int WT = 2, TS = 128;
   extern __shared__ uint4 lds[];             // [2 buffers][2 panels][PK_SLOTS]
   const int2 tile = tile_list[blockIdx.x];
   if (tile.x < 0) return;
   const int tm = tile.x, tn = tile.y;
-  const bool diag = (tm == tn);
+  const bool diag = symmetric && (tm == tn);
   const int i0 = tm * TS, j0 = tn * TS;
   const int s_begin = blockIdx.y * stages_per_split;
   const int s_end = (s_begin + stages_per_split < nstages) ? s_begin + stages_per_split : nstages;
@@ -111,17 +114,16 @@ __global__ __launch_bounds__(256, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 #pragma unroll
       for (int r = 0; r < 16; r++) { acc[a][b][r] = 0.f; acc2[a][b][r] = 0.f; }
 
-  const int64_t sstride = (int64_t)npanels * PK_SLOTS;
-  const uint4* ga = Xp + (int64_t)tm * PK_SLOTS + tid;
-  const uint4* gb = Xp + (int64_t)tn * PK_SLOTS + tid;
+  const uint4* ga = Ap + (int64_t)tm * PK_SLOTS + tid;
+  const uint4* gb = Bp + (int64_t)tn * PK_SLOTS + tid;
   uint4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3;
   rb0 = rb1 = rb2 = rb3 = uint4{0u, 0u, 0u, 0u};
 #define OSSCAR_GLOAD(st)                                                                         \
   {                                                                                              \
-    const uint4* pa_ = ga + (st) * sstride;                                                      \
+    const uint4* pa_ = ga + (st) * a_sstride;                                                    \
     ra0 = pa_[0]; ra1 = pa_[256]; ra2 = pa_[512]; ra3 = pa_[768];                                \
     if (!diag) {                                                                                 \
-      const uint4* pb_ = gb + (st) * sstride;                                                    \
+      const uint4* pb_ = gb + (st) * b_sstride;                                                  \
       rb0 = pb_[0]; rb1 = pb_[256]; rb2 = pb_[512]; rb3 = pb_[768];                              \
     }                                                                                            \
   }
@@ -184,7 +186,7 @@ __global__ __launch_bounds__(256, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 
   // C layout of the 32 x 32 MFMA: register r = rr*4 + r3 holds row rr*8 + (lane/32)*4 + r3, column lane%32
   // (the opaque copy of d1 keeps the compiler from computing the 64 output addresses ahead of the main loop)
-  int d1v = d1;
+  int d1v = ldo;
   asm volatile("" : "+s"(d1v));
   const int rbase = i0 + wm * 64 + (lane >> 5) * 4;
   const int cbase = j0 + wn * 64 + (lane & 31);
@@ -197,27 +199,59 @@ __global__ __launch_bounds__(256, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
       for (int r3 = 0; r3 < 4; r3++) {
         const int ro = a * 32 + rr * 8 + r3;
         double* hrow = hbase + (int64_t)ro * d1v;
-        const bool rok = (rbase + ro < d1);
+        const bool rok = (rbase + ro < rows_out);
 #pragma unroll
         for (int b = 0; b < WT; b++)
-          if (rok && cbase + b * 32 < d1)
+          if (rok && cbase + b * 32 < cols_out)
             unsafeAtomicAdd(hrow + b * 32, (double)acc[a][b][rr * 4 + r3] + (double)acc2[a][b][rr * 4 + r3]);
       }
       asm volatile("" ::: "memory");
     }
 }
 
+// all tiles of an R x C grid, in 4 x 8 blocks dealt to the XCDs in turn
+static void build_rect_tile_list(int R, int C, std::vector<int2>& out) {
+  constexpr int NX = 8, RB = 4, CB = 8;
+  std::vector<std::vector<int2>> lists(NX);
+  int blk = 0;
+  for (int r0 = 0; r0 < R; r0 += RB)
+    for (int c0 = 0; c0 < C; c0 += CB, blk++)
+      for (int r = r0; r < std::min(R, r0 + RB); r++)
+        for (int c = c0; c < std::min(C, c0 + CB); c++) lists[blk % NX].push_back(int2{r, c});
+  size_t len = 0;
+  for (auto& L : lists) len = std::max(len, L.size());
+  out.assign(len * NX, int2{-1, -1});
+  for (int x = 0; x < NX; x++)
+    for (size_t i = 0; i < lists[x].size(); i++) out[i * NX + x] = lists[x][i];
+}
+
+static int split_stages(int ntiles, int nstages, int* per_out) {
+  int splits = 1;
+  if (ntiles < 1024) splits = std::min(nstages, (2048 + ntiles - 1) / ntiles);
+  int per = (nstages + splits - 1) / splits;
+  per = std::max(per, std::min(nstages, 8));
+  *per_out = per;
+  return (nstages + per - 1) / per;
+}
+
 hipError_t launch_gram_packed(const void* Xc, int64_t n_c, int64_t ldx, int d1, double* H64, int2* tile_buf,
-                              size_t tile_buf_entries, void* pack_buf, int64_t pack_rows, hipStream_t s) {
+                              size_t tile_buf_entries, void* pack_buf, int64_t pack_rows, hipStream_t s, const void* Yc,
+                              int64_t ldy, int m, double* G64, int2* tile_buf_y, size_t tile_buf_y_entries, void* pack_buf_y) {
   if (n_c <= 0) return hipSuccess;
   if (pack_rows < GBK || pack_rows % GBK) return hipErrorInvalidValue;
-  const int npanels = (d1 + 127) / 128;
-  std::vector<int2> tiles;
+  const int npanels = (d1 + 127) / 128, npanels_y = Yc ? (m + 127) / 128 : 0;
+  std::vector<int2> tiles, tiles_y;
   build_tile_list(npanels, tiles);
   if (tiles.size() > tile_buf_entries) return hipErrorInvalidValue;
   hipError_t e = hipMemcpyAsync(tile_buf, tiles.data(), tiles.size() * sizeof(int2), hipMemcpyHostToDevice, s);
   if (e != hipSuccess) return e;
-  e = hipStreamSynchronize(s);   // the host vector dies at return
+  if (Yc) {
+    build_rect_tile_list(npanels, npanels_y, tiles_y);
+    if (tiles_y.size() > tile_buf_y_entries) return hipErrorInvalidValue;
+    e = hipMemcpyAsync(tile_buf_y, tiles_y.data(), tiles_y.size() * sizeof(int2), hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return e;
+  }
+  e = hipStreamSynchronize(s);   // the host vectors die at return
   if (e != hipSuccess) return e;
   const int ntiles = npanels * (npanels + 1) / 2;
   const int window = 16;   // 1024 tokens per MFMA accumulation window
@@ -226,16 +260,59 @@ hipError_t launch_gram_packed(const void* Xc, int64_t n_c, int64_t ldx, int d1, 
     const int64_t nr = std::min<int64_t>(pack_rows, n_c - r0);
     const int nstages = (int)((nr + GBK - 1) / GBK);
     const uint16_t* src = reinterpret_cast<const uint16_t*>(Xc) + r0 * ldx;
+    const uint4* Xp = reinterpret_cast<const uint4*>(pack_buf);
     hipLaunchKernelGGL(gram_pack_kernel, dim3((npanels + 1) / 2, nstages), dim3(256), 0, s, src, nr, ldx, d1, npanels,
                        reinterpret_cast<uint4*>(pack_buf));
-    int splits = 1;
-    if (ntiles < 1024) splits = std::min(nstages, (2048 + ntiles - 1) / ntiles);
-    int per = (nstages + splits - 1) / splits;
-    per = std::max(per, std::min(nstages, 8));
-    splits = (nstages + per - 1) / per;
-    hipLaunchKernelGGL(gram_packed_kernel, dim3((unsigned)tiles.size(), splits), dim3(256), shmem, s,
-                       reinterpret_cast<const uint4*>(pack_buf), nstages, npanels, d1, H64, tile_buf, per, window);
+    int per = 0;
+    int splits = split_stages(ntiles, nstages, &per);
+    const int64_t xs = (int64_t)npanels * PK_SLOTS;
+    hipLaunchKernelGGL(gram_packed_kernel, dim3((unsigned)tiles.size(), splits), dim3(256), shmem, s, Xp, xs, Xp, xs, nstages, d1,
+                       d1, d1, H64, tile_buf, per, window, 1);
+    if (Yc) {
+      const uint16_t* srcy = reinterpret_cast<const uint16_t*>(Yc) + r0 * ldy;
+      const uint4* Yp = reinterpret_cast<const uint4*>(pack_buf_y);
+      hipLaunchKernelGGL(gram_pack_kernel, dim3((npanels_y + 1) / 2, nstages), dim3(256), 0, s, srcy, nr, ldy, m, npanels_y,
+                         reinterpret_cast<uint4*>(pack_buf_y));
+      splits = split_stages(npanels * npanels_y, nstages, &per);
+      hipLaunchKernelGGL(gram_packed_kernel, dim3((unsigned)tiles_y.size(), splits), dim3(256), shmem, s, Xp, xs, Yp,
+                         (int64_t)npanels_y * PK_SLOTS, nstages, d1, m, m, G64, tile_buf_y, per, window, 0);
+    }
   }
+  return hipGetLastError();
+}
+
+// sum of squares of a rows x cols matrix (float32 or bf16), added to *acc
+__global__ __launch_bounds__(256) void sumsq_kernel(const void* __restrict__ A, int is_bf16, int64_t rows, int64_t cols, int64_t ld,
+                                                     double* __restrict__ acc) {
+  __shared__ double red[4];
+  double v = 0;
+  const int64_t tot = rows * cols;
+  for (int64_t idx = blockIdx.x * 256 + threadIdx.x; idx < tot; idx += (int64_t)gridDim.x * 256) {
+    const int64_t r = idx / cols, c = idx % cols;
+    const float x = is_bf16 ? __uint_as_float(((uint32_t)reinterpret_cast<const uint16_t*>(A)[r * ld + c]) << 16)
+                            : reinterpret_cast<const float*>(A)[r * ld + c];
+    v += (double)x * (double)x;
+  }
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  if (threadIdx.x == 0) unsafeAtomicAdd(acc, red[0] + red[1] + red[2] + red[3]);
+}
+hipError_t launch_sumsq(const void* A, int is_bf16, int64_t rows, int64_t cols, int64_t ld, double* acc, hipStream_t s) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  hipLaunchKernelGGL(sumsq_kernel, dim3(1024), dim3(256), 0, s, A, is_bf16, rows, cols, ld, acc);
+  return hipGetLastError();
+}
+
+// G = float32(G64 + lambda W)
+__global__ void finalize_G_kernel(const double* __restrict__ G64, const float* __restrict__ Wf, const double* __restrict__ lambda,
+                                  float* __restrict__ G, int64_t n) {
+  const double lam = *lambda;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+    G[i] = (float)(G64[i] + lam * (double)Wf[i]);
+}
+hipError_t launch_finalize_G(const double* G64, const float* Wf, const double* lambda_dev, float* G, int64_t n, hipStream_t s) {
+  hipLaunchKernelGGL(finalize_G_kernel, dim3(2048), dim3(256), 0, s, G64, Wf, lambda_dev, G, n);
   return hipGetLastError();
 }
 

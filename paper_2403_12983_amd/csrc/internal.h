@@ -31,7 +31,13 @@ hipError_t launch_gemm_f64acc(const GemmArgs& a, hipStream_t s);
 // and accumulates them into H64.
 // tile_buf: device scratch for the tile schedule, tile_buf_entries >= 8 * (ceil(d1/128)^2 / 2 + ceil(d1/128) + 8)
 hipError_t launch_gram_packed(const void* Xc, int64_t n_c, int64_t ldx, int d1, double* H64, int2* tile_buf,
-                              size_t tile_buf_entries, void* pack_buf, int64_t pack_rows, hipStream_t s);
+                              size_t tile_buf_entries, void* pack_buf, int64_t pack_rows, hipStream_t s,
+                              const void* Yc = nullptr, int64_t ldy = 0, int m = 0, double* G64 = nullptr,
+                              int2* tile_buf_y = nullptr, size_t tile_buf_y_entries = 0, void* pack_buf_y = nullptr);
+// Yc (optional, bf16 n_c x m): also G64 (d1 x m, float64) += Xc^T Yc, with its own tile list (>= 8 * (ceil(d1/128) *
+// ceil(m/128) / 8 + 64) entries) and pack buffer (pack_rows * 128*ceil(m/128) * 2 bytes)
+hipError_t launch_sumsq(const void* A, int is_bf16, int64_t rows, int64_t cols, int64_t ld, double* acc, hipStream_t s);
+hipError_t launch_finalize_G(const double* G64, const float* Wf, const double* lambda_dev, float* G, int64_t n, hipStream_t s);
 hipError_t launch_transpose_to_f32(const void* X, int is_bf16, int64_t rows, int64_t cols, int64_t ldx, float* Xt,
                                    int64_t ldxt, hipStream_t s);
 // H = float(mirror(H64) + lam*I); also usable with lam = 0

@@ -180,6 +180,40 @@ def test_greedy_from_dense_cfg3_width():
     s.close()
 
 
+def test_cfg5_target_gram_sampled():
+    """Cross-Gram of the benchmark layer's shape (32768 calibration rows) on sampled rows of G, float64 on the device."""
+    import time
+    import paper_2403_12983_amd as pkg
+    cfg = inp.CONFIGS["cfg5"].replace(n=32768)
+    X = gen_on_gpu(cfg)
+    W = inp.gen_W(cfg, DEV)
+    X2 = gen_on_gpu(cfg.replace(seed=cfg.seed + 101))
+    Y = torch.empty(cfg.n, cfg.m, dtype=torch.bfloat16, device=DEV)
+    for r0 in range(0, cfg.n, 8192):
+        xh = 0.9 * X[r0:r0 + 8192].float() + 0.1 * X2[r0:r0 + 8192].float()
+        Y[r0:r0 + 8192] = (xh @ W.float()).to(torch.bfloat16)
+    del X2
+    s = pkg.Solver(cfg.d1, cfg.m, cfg.p, cfg.q, cfg.k, 1, X.dtype, W.dtype, DEV, target_output=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    s.osscar_gram_target(X[:20000], Y[:20000])
+    s.osscar_gram_target(X[20000:], Y[20000:], True, W, cfg.lam_abs, cfg.lam_rel)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    lam, c0 = s.osscar_get_scalars()
+    rows = torch.arange(5, cfg.d1, 449, device=DEV)
+    Go = X[:, rows].double().T @ Y.double() + lam * W[rows].double()
+    Gg = T(s, "T_G")[rows].double()
+    assert (torch.linalg.norm(Gg - Go) / torch.linalg.norm(Go)).item() < 1e-6
+    c0o = (Y.double() ** 2).sum().item() + lam * (W.double() ** 2).sum().item()
+    assert abs(c0 - c0o) <= 1e-6 * c0o
+    diag = torch.diagonal(T(s, "T_H")).double()
+    assert abs(lam - cfg.lam_rel * (diag.mean().item() - lam)) <= 1e-6 * lam
+    flops = 2.0 * cfg.n * cfg.d1 * (cfg.d1 / 2 + cfg.m)
+    print(f"cfg5 target Gram, n = {cfg.n}: {dt * 1e3:.1f} ms incl. finalize, {flops / dt / 1e12:.0f} TFLOP/s algorithmic")
+    s.close()
+
+
 def test_cfg5_bench_configuration_sampled():
     cfg = inp.CONFIGS["cfg5"]
     X = gen_on_gpu(cfg)

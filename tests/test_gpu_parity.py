@@ -414,6 +414,67 @@ def test_greedy_refresh_and_edges():
     s.close()
 
 
+# ------------------------------------------------------------------------------------------ sequential-pipeline target
+def target_of(c):
+    """Dense model's output for the same rows: Y = Xhat W with Xhat a perturbed copy of X, rounded to the input dtype."""
+    cfg = c.cfg
+    X2 = inp.gen_X(cfg.replace(seed=cfg.seed + 101)).double().numpy()
+    Y = (0.9 * c.Xd + 0.1 * X2) @ c.Wd
+    return torch.from_numpy(Y).to(c.X.dtype)
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2s", "cfg3s", "cfg5odd"])
+def test_target_output_path(name):
+    c = case(name)
+    cfg = c.cfg
+    Y = target_of(c)
+    Yd = Y.double().numpy()
+    H, G, c0, lam = orc.gram_target(c.Xd, Yd, c.Wd, cfg.lam_abs, cfg.lam_rel)
+    s = _pkg().Solver(cfg.d1, cfg.m, cfg.p, cfg.q, cfg.k, max(cfg.swaps, 1), c.X.dtype, c.W.dtype, DEV, from_dense=True,
+                      target_output=True)
+    Xg, Yg, Wg = c.X.to(DEV), Y.to(DEV), c.W.to(DEV)
+    n = cfg.n
+    s.osscar_gram_target(Xg[: n // 3], Yg[: n // 3])
+    s.osscar_gram_target(Xg[:0], Yg[:0])
+    s.osscar_gram_target(Xg[n // 3:], Yg[n // 3:], True, Wg, cfg.lam_abs, cfg.lam_rel)
+    H1, G1 = T(s, "T_H"), T(s, "T_G")
+    lam1, c01 = s.osscar_get_scalars()
+    dsc = np.sqrt(np.diag(H))
+    assert np.max(np.abs(H1 - H) / np.outer(dsc, dsc)) < 1e-6
+    assert rel(G1, G) < 1e-6
+    assert abs(lam1 - lam) <= 1e-6 * lam and abs(c01 - c0) <= 1e-6 * c0
+    # the whole path on this quadratic form: magnitude support, swaps, final solve
+    s.osscar_init_support()
+    r = s.osscar_local_search(min(cfg.swaps, 15))
+    pairs = list(zip(r["trace_out"][: r["accepted"]].tolist(), r["trace_in"][: r["accepted"]].tolist()))
+    fol = orc.local_search(H, G, c0, c.K0, cfg.p, cfg.q, len(pairs), follow=pairs)
+    for x in fol.trace:
+        assert x.deficit_rem <= GAP and x.deficit_add <= GAP and x.delta < 0
+    What, support, obj = s.osscar_backsolve()
+    assert support.tolist() == fol.support
+    Wo, objo = orc.solve_support(H, G, c0, fol.support, cfg.q)
+    assert rel(What.cpu().double().numpy(), Wo) < 1e-4 and abs(obj - objo) <= 1e-4 * objo
+    assert abs(obj - orc.objective_target(c.Xd, Yd, c.Wd, What.cpu().double().numpy(), lam)) <= 1e-4 * objo
+    # the nested schedule starts from a dense layer that does not reproduce the target exactly
+    t_hat = 3
+    objg, steps, gaps = s.osscar_init_greedy(t_hat)
+    folg = orc.greedy_from_dense(H, G, c0, cfg.p, cfg.q, cfg.k, t_hat, follow=steps)
+    assert all(x.deficit <= GAP for x in folg.trace)
+    assert abs(objg - folg.obj_final) <= 1e-5 * folg.obj_final
+    # mixing the two accumulation calls within a layer is refused
+    from paper_2403_12983_amd.binding import OsscarError
+    s.osscar_gram_target(Xg[:5], Yg[:5])
+    with pytest.raises(OsscarError) as e:
+        s.osscar_gram(Xg[5:10])
+    assert e.value.status == 5
+    s.close()
+    s = c.solver()
+    with pytest.raises(OsscarError) as e:
+        s.osscar_gram_target(Xg[:5], Yg[:5])                                     # created without target_output
+    assert e.value.status == 1
+    s.close()
+
+
 def test_set_quadratic_and_brute_force_optimum_is_a_fixed_point():
     c = case("cfg1x")
     cfg = c.cfg
