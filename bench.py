@@ -6,9 +6,9 @@ calibration rows, finalize (ridge, G = H W), magnitude support + state build, th
 final back-solve.  X and W are resident in HBM before the timed region starts.
 
 Prints one JSON line.  `value` is seconds per layer (lower is better).  `roofline` describes the kernel the
-layer time is dominated by: the search's per-swap read-only pass over Z (for q > 1, where the search updates
-the tableau in place, the bulk update of N).  `roofline_gram` describes the bf16 MFMA Gram kernel, and
-`cpu_baseline` the float64 oracle timed on this machine's host cores on a reduced layer of the same recipe."""
+layer time is dominated by, the float64-accumulating MFMA GEMM, on its largest launch (G = H W).
+`roofline_gram` describes the bf16 MFMA Gram kernel, and `cpu_baseline` the float64 oracle timed on this
+box's host cores on a reduced layer of the same recipe."""
 from __future__ import annotations
 
 import argparse
@@ -86,6 +86,8 @@ def main():
                     help="magnitude: the benchmark layer's recipe (magnitude support, then swaps); greedy: the nested "
                          "schedule of Algorithm 1 from the dense layer (t-hat groups pruned per iteration), then swaps")
     ap.add_argument("--t-hat", type=int, default=10)
+    ap.add_argument("--no-lookahead", action="store_true",
+                    help="search without the products computed ahead: every swap then makes one read-only pass over Z")
     ap.add_argument("--rows", type=int, default=None,
                     help="calibration rows (default: the config's); a short X keeps counter-collection runs brief")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -112,11 +114,11 @@ def main():
 
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
     phases = {k: 0.0 for k in ("gram", "finalize", "init", "search", "backsolve")}
-    upd_n = upd_z = 0.0
+    upd_n = upd_z = gemm_ms = 0.0
     info = {}
 
     def step(timed):
-        nonlocal upd_n, upd_z
+        nonlocal upd_n, upd_z, gemm_ms
         ev[0].record()
         s.osscar_gram(X, False)
         ev[1].record()
@@ -124,7 +126,7 @@ def main():
         ev[2].record()
         obj0 = s.osscar_init_support() if a.init == "magnitude" else s.osscar_init_greedy(a.t_hat)[0]
         ev[3].record()
-        r = s.osscar_local_search(swaps, 0.0, 0, a.refresh_every)
+        r = s.osscar_local_search(swaps, 0.0, pkg.OSSCAR_SEARCH_NO_LOOKAHEAD if a.no_lookahead else 0, a.refresh_every)
         ev[4].record()
         What, support, obj = s.osscar_backsolve()
         ev[5].record()
@@ -135,6 +137,7 @@ def main():
             tm = s.osscar_get_timers()
             upd_n += tm[5] / 1e3
             upd_z += tm[7] / 1e3
+            gemm_ms += tm[8]
         info.update(obj0=obj0, obj=obj, iters=r["iters"], accepted=r["accepted"], tracked=r["obj_final"])
 
     for _ in range(a.warmup):
@@ -150,6 +153,7 @@ def main():
         phases[k] /= K
     upd_n /= K
     upd_z /= K
+    gemm_ms /= K
     t_layer = wall / K
 
     d1, m, n = cfg.d1, cfg.m, cfg.n
@@ -158,24 +162,21 @@ def main():
     # Per-swap state update as SURVEY counts it: read + write of P, V (= lower triangle of N) and B, R (= Z)
     bytes_swap_alg = 2 * 4 * (d1 * d1 // 2) + 2 * 4 * d1 * m
     ms_swap = 1e3 * phases["search"] / max(info["iters"], 1)
-    if lazy:
-        # delayed-update search: the per-swap kernel is the read-only pass over Z (w = Z [y1 y2]); upd_n holds its mean
-        # duration (HIP events inside the library, sampled once per batch of iterations)
-        k_bytes = 4 * d1 * m
-        k_name = "lazy_gemv_kernel (per-swap read-only pass over Z: w = Z [y1 y2])"
-        # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/lazy_gemv_cfg5_pmc.md), cfg5 only
-        traffic = 827.8e6 if a.config == "cfg5" else None
-    else:
-        k_bytes = 2 * 4 * (d1 * d1 // 2)
-        k_name = "update_N (bulk rank-2q update of the swept tableau, lower triangle)"
-        traffic = None
+    # Dominant kernel of the layer: the float64-accumulating MFMA GEMM (G = H W, the inverse's refinement, B, V, S, R,
+    # the look-ahead products of the search, the back-solve's residuals).  Its largest launch, G = H W inside finalize, is
+    # timed by HIP events on the library's stream (timer slot 8): 2 d1^2 m flops on v_mfma_f64_16x16x4_f64.
+    g_flops = 2.0 * d1 * d1 * m
+    g_bytes = 4.0 * (d1 * d1 + 2 * d1 * m)                       # read H and W once, write G once
+    # HBM bytes of that launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/gemm_f64acc_cfg5_pmc.md), cfg5 only
+    g_traffic = 130.6e9 if a.config == "cfg5" else None
     out = {
         "metric": "OPT-30B fc2 layer prune time", "value": t_layer, "unit": "s", "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": 1e3 * t_layer, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16 inputs, f32 state, f64 accumulate", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: X {n}x{d1} {cfg.x_dtype}, W {d1}x{m} {cfg.w_dtype}, keep {cfg.k} of {cfg.p} groups "
                                f"(q={cfg.q}), {swaps} swaps, lambda = {cfg.lam_rel}*mean diag",
-                   "refresh_every": a.refresh_every, "search": "delayed-update" if lazy else "eager",
+                   "refresh_every": a.refresh_every,
+                   "search": ("delayed-update" + (", no look-ahead" if a.no_lookahead else "")) if lazy else "eager",
                    "init": a.init if a.init == "magnitude" else f"nested schedule from the dense layer, t_hat = {a.t_hat}"},
         "phases_s": phases,
         "swap_iterations": info["iters"], "accepted_swaps": info["accepted"],
@@ -184,18 +185,22 @@ def main():
         "gram_tflops_syrk": gram_flops / phases["gram"] / 1e12,
         "gram_tflops_full_equiv": 2 * n * d1 * d1 / phases["gram"] / 1e12,
         "objective": {"initial": info["obj0"], "final": info["obj"], "tracked": info["tracked"]},
-        "roofline": {"kernel": k_name, "bound": "hbm", "achieved": k_bytes / upd_n / 1e9 if upd_n > 0 else None, "peak": 8000.0,
-                     "unit": "GB/s", "frac": k_bytes / upd_n / 1e9 / 8000.0 if upd_n > 0 else None, "traffic": traffic,
-                     "bytes_per_launch": k_bytes, "ms_per_launch": 1e3 * upd_n},
-        "swap_update_equivalent": {"note": "bytes an eager in-place up/downdate of P, B, V, R moves per swap, divided by the "
-                                           "measured time per swap (all kernels and amortised flushes); above the HBM peak "
-                                           "because swaps are applied 64 at a time on the matrix cores",
-                                   "bytes_per_swap": bytes_swap_alg, "achieved": bytes_swap_alg / ms_swap / 1e6, "unit": "GB/s",
-                                   "frac_of_hbm_peak": bytes_swap_alg / ms_swap / 1e6 / 8000.0},
-        "iteration_kernels_ms": 1e3 * upd_z,
-        "roofline_gram": {"kernel": "gram_packed_kernel (+ gram_pack_kernel, whole Gram phase)", "bound": "mfma", "achieved": gram_flops / phases["gram"] / 1e12,
-                          "peak": 2500.0, "unit": "TFLOP/s", "frac": gram_flops / phases["gram"] / 1e12 / 2500.0,
+        "roofline": {"kernel": "gemm_f64acc_kernel<float>, launch G = H W (float32 operands, float64 MFMA accumulation)",
+                     "bound": "mfma", "achieved": g_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None, "peak": 78.6,
+                     "unit": "TFLOP/s", "frac": g_flops / (gemm_ms * 1e-3) / 1e12 / 78.6 if gemm_ms > 0 else None,
+                     "traffic": g_traffic, "flops_per_launch": g_flops, "algorithmic_bytes_per_launch": g_bytes,
+                     "ms_per_launch": gemm_ms},
+        "roofline_gram": {"kernel": "gram_packed_kernel (+ gram_pack_kernel, whole Gram phase)", "bound": "mfma",
+                          "achieved": gram_flops / phases["gram"] / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
+                          "frac": gram_flops / phases["gram"] / 1e12 / 2500.0,
                           "note": "algorithmic SYRK flops n*d1*(d1+1); the kernel issues 2x that on diagonal tiles only"},
+        "search_iteration": {"note": "per swap: four small kernels (selection and pivot algebra, current pivot rows/columns, w from the "
+                                     "products computed ahead, update of norms/diagonal/scores); every 64 swaps a flush by matrix "
+                                     "products plus one look-ahead product Zc Z^T.  An eager in-place up/downdate of P, B, V, R would "
+                                     "move bytes_per_swap_eager per swap",
+                             "ms_per_swap": ms_swap, "w_kernels_ms": 1e3 * upd_n, "iteration_kernels_ms": 1e3 * upd_z,
+                             "bytes_per_swap_eager": bytes_swap_alg,
+                             "eager_equivalent_GBps": bytes_swap_alg / ms_swap / 1e6},
     }
     s.close()
     del X

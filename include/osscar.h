@@ -121,7 +121,8 @@ osscar_status osscar_init_support(osscar_ctx* ctx, int mode, const int32_t* grou
  * by Case 1.  Leaves the context as osscar_init_support does, so osscar_local_search and osscar_backsolve
  * can follow.  Needs desc.from_dense != 0.  1 <= t_hat <= 64.
  * refresh_every > 0 rebuilds the state from H and G after that many removals (at iteration boundaries).
- * flags: 0, or OSSCAR_SEARCH_EAGER to update the state in place after every removal also for q = 1.
+ * flags: 0, or OSSCAR_SEARCH_EAGER to update the state in place after every removal also for q = 1, or
+ * OSSCAR_SEARCH_NO_LOOKAHEAD (see osscar_local_search).
  * removed_host (host, optional): p - k group ids in the order removed (within an iteration: cheapest first).
  * gaps_host (host, optional): one float per iteration, ceil((p - k) / t_hat) of them: relative gap between the
  * costliest removal chosen and the cheapest kept group left out (inf if none was left out).
@@ -138,12 +139,14 @@ osscar_status osscar_init_greedy(osscar_ctx* ctx, int32_t t_hat, int32_t refresh
  * flags: OSSCAR_SEARCH_ALWAYS_ACCEPT applies every selected pair (Algorithm 1 as printed).
  * OSSCAR_SEARCH_EAGER applies every swap to the whole state at once (one pass over HBM per swap); by
  * default, layers with q = 1 keep up to 64 swaps pending as a small low-rank correction and apply them
- * together on the matrix cores -- the same swaps, with less traffic.
+ * together on the matrix cores -- the same swaps, with less traffic.  In that mode the products of Z with the
+ * rows most likely to be swapped next are computed ahead by one matrix product per flush;
+ * OSSCAR_SEARCH_NO_LOOKAHEAD turns that off (every swap then reads Z once).
  * refresh_every > 0 recomputes V, R and B from P, H, G by GEMM after that many accepted swaps.
  * Optional host outputs of length max_swaps (entry i describes iteration i, including a final rejected
  * one): trace_out / trace_in = group leaving / entering; trace_gap[2i], trace_gap[2i+1] = relative gap
  * between best and second-best removal cost / addition gain; trace_obj[i] = obj after the iteration. */
-enum { OSSCAR_SEARCH_ALWAYS_ACCEPT = 1u, OSSCAR_SEARCH_EAGER = 2u };
+enum { OSSCAR_SEARCH_ALWAYS_ACCEPT = 1u, OSSCAR_SEARCH_EAGER = 2u, OSSCAR_SEARCH_NO_LOOKAHEAD = 4u };
 typedef struct {
   int32_t iters;     /* iterations run (accepted swaps + at most one rejected) */
   int32_t accepted;  /* swaps applied */
@@ -182,8 +185,9 @@ osscar_status osscar_get_scalars(osscar_ctx* ctx, double* lambda_host, double* c
  * [0] the Gram accumulation of the chunk passed together with finalize, [1] finalize, [2] init_support,
  * [3] local_search, [4] backsolve, [6] total time of the search's refreshes and flushes.  Sampled once
  * per batch of iterations: eager search [5] mean duration of one bulk update of N, [7] of one update of Z;
- * delayed-update search [5] mean duration of the per-swap pass over Z, [7] of the rest of that iteration's
- * kernels including the pass.  out_host: 8 doubles. */
+ * delayed-update search [5] mean duration of the two kernels that produce w = Z [y1 y2] (a pass over Z only for a
+ * pivot whose products were not computed ahead), [7] of all kernels of that iteration from there on.
+ * [8] the product G = H W inside finalize (one GEMM launch).  [9..11] reserved.  out_host: 12 doubles. */
 osscar_status osscar_get_timers(osscar_ctx* ctx, double* out_host);
 
 const char* osscar_last_error(const osscar_ctx* ctx);

@@ -13,6 +13,7 @@ OSSCAR_F32, OSSCAR_BF16 = 0, 1
 OSSCAR_INIT_MAGNITUDE, OSSCAR_INIT_GIVEN = 0, 1
 OSSCAR_SEARCH_ALWAYS_ACCEPT = 1
 OSSCAR_SEARCH_EAGER = 2
+OSSCAR_SEARCH_NO_LOOKAHEAD = 4
 T_H, T_G, T_P, T_B, T_V, T_R, T_REM, T_ADD, T_KEPT, T_CAND = range(10)
 _STATUS = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "ENOTPD", 4: "EHIP", 5: "ESTATE"}
 
@@ -234,6 +235,6 @@ class Solver:
         return lam.value, c0.value
 
     def osscar_get_timers(self):
-        arr = (C.c_double * 8)()
+        arr = (C.c_double * 12)()
         self._check(self.lib.osscar_get_timers(self.ctx, arr))
         return list(arr)

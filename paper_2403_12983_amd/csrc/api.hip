@@ -101,7 +101,7 @@ struct osscar_ctx {
   bool dense_is_exact = true;    // the dense layer has objective 0 (false for a target output or a caller-supplied quadratic form)
   std::vector<double> norms_host;
   std::vector<int32_t> kept_host;
-  double timers[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  double timers[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   hipEvent_t ev_a = nullptr, ev_b = nullptr;
   hipEvent_t ev_s[EV_SAMPLES][3];
   bool ev_ok = false;
@@ -157,6 +157,9 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
     L.y1 = cv.take<double>(m); L.y2 = cv.take<double>(m); L.y1f = cv.take<float>(m); L.y2f = cv.take<float>(m);
     L.part = cv.take<double>(((m + 63) / 64) * 5); L.ls = cv.take<double>(16);
     L.sel = cv.take<SelRec>((d1 + 31) / 32); L.counter = cv.take<int32_t>(4);
+    L.GbT = cv.take<double>((int64_t)(LAZY_NC + LAZY_NS) * d1); L.Zc = cv.take<float>((int64_t)LAZY_NC * m);
+    L.cslot = cv.take<int32_t>(d1); L.cand = cv.take<int32_t>(LAZY_NC + LAZY_NS); L.tslot = cv.take<int32_t>(LAZY_TM);
+    L.misc = cv.take<int32_t>(8); L.lkey = cv.take<double>(2 * 64 * 32); L.lidx = cv.take<int32_t>(2 * 64 * 32);
   }
   // scratch: the larger of the Gram phase and the init / refresh / backsolve phase
   size_t gram_phase = align_up((size_t)d1 * d1 * 8) + align_up((size_t)d1 * m * 4) + align_up(gram_stage_bytes(d1)) +
@@ -488,7 +491,9 @@ static osscar_status gram_impl(osscar_ctx* c, const char* who, int target, const
     HIPCHK(c, launch_dot64(Wf, Wf, (int64_t)d1 * m, c->scal + 2, c->partial, s));
     HIPCHK(c, hipMemcpyAsync(&yy, c->scal + 12, 8, hipMemcpyDeviceToHost, s));
   } else {
+    HIPCHK(c, hipEventRecord(c->ev_s[0][0], s));
     HIPCHK(c, gemm(s, d1, m, d1, c->H, d1, Wf, m, nullptr, 0, c->G, m, 1.0, 0.0));
+    HIPCHK(c, hipEventRecord(c->ev_s[0][1], s));
     HIPCHK(c, launch_dot64(Wf, c->G, (int64_t)d1 * m, c->scal + 2, c->partial, s));
   }
   HIPCHK(c, launch_group_norms(Wf, c->p, c->q, m, c->norms2, s));
@@ -498,6 +503,7 @@ static osscar_status gram_impl(osscar_ctx* c, const char* who, int target, const
   HIPCHK(c, hipEventRecord(c->ev_b, s));
   HIPCHK(c, hipStreamSynchronize(s));
   if (target) c->c0 = yy + c->lambda * c->c0;
+  else { float ms = 0; hipEventElapsedTime(&ms, c->ev_s[0][0], c->ev_s[0][1]); c->timers[8] = ms; }
   c->dense_is_exact = !target;
   c->timers[1] = elapsed(c);
   for (auto& v : c->norms_host) v = std::sqrt(v);
@@ -599,27 +605,56 @@ osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_e
   // once LAZY_TM of them are pending); larger groups: in-place rank-q updates
   const bool use_lazy = (q == 1) && !(flags & OSSCAR_SEARCH_EAGER);
   const LazyPtrs& L = c->lazy;
-  if (use_lazy) HIPCHK(c, launch_lazy_init(d, t, L, s));
-  int kept_now = p, iter = 0, since_refresh = 0, since_check = 0, pending = 0;
+  const int la_mode = (flags & OSSCAR_SEARCH_NO_LOOKAHEAD) ? 2 : 1;
+  if (use_lazy) HIPCHK(c, launch_lazy_init(d, t, L, s, la_mode));
+  // Work is enqueued one batch at a time (a batch = the iterations that fit the pending set, or 256 removals in place) and
+  // then checked: the delayed-update kernels may stop (pause) when a removed row was not among the rows whose products
+  // were computed ahead and the spare slots ran out; the batch is then resumed after a flush from where it stopped.
+  int kept_now = p, iter = 0, since_refresh = 0, pending = 0, expected = 0;
+  std::vector<int> takes;
+  auto step = [&](int i) -> hipError_t {
+    return use_lazy ? launch_lazy_iteration(d, t, L, 1, s, nullptr, c->g_pick + i)
+                    : launch_search_iteration(d, t, -1, -1, 1, s, nullptr, c->g_pick + i);
+  };
   while (kept_now > k) {
-    const int take = std::min<int>(t_hat, kept_now - k);
-    if (use_lazy && pending + take > LAZY_TM) { HIPCHK(c, launch_lazy_flush(d, t, L, s)); pending = 0; }
-    HIPCHK(c, launch_greedy_pick(d, t, take, c->g_pick, c->g_gap + iter, s));
-    for (int i = 0; i < take; i++) {
-      if (use_lazy) HIPCHK(c, launch_lazy_iteration(d, t, L, 1, s, nullptr, c->g_pick + i));
-      else HIPCHK(c, launch_search_iteration(d, t, -1, -1, 1, s, nullptr, c->g_pick + i));
+    takes.clear();
+    int batch = 0, kept_b = kept_now;
+    while (kept_b > k) {
+      const int take = std::min<int>(t_hat, kept_b - k);
+      if (use_lazy ? (pending + batch + take > LAZY_TM) : (batch >= 256)) break;
+      HIPCHK(c, launch_greedy_pick(d, t, take, c->g_pick, c->g_gap + iter + (int)takes.size(), s));
+      for (int i = 0; i < take; i++) HIPCHK(c, step(i));
+      takes.push_back(take); batch += take; kept_b -= take;
     }
-    pending += take;
-    kept_now -= take; iter++; since_refresh += take; since_check += take;
+    if (takes.empty()) {   // the pending set is full: apply it and try again
+      HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode));
+      pending = 0;
+      continue;
+    }
+    st = read_ctrl(c, &h);
+    if (st != OSSCAR_OK) return st;
+    if (h.notpd) return fail(c, OSSCAR_ENOTPD, "osscar_init_greedy: a pivot block lost definiteness after %d removals", h.iters);
+    int done = h.iters - expected;
+    if (done < 0 || done > batch) return fail(c, OSSCAR_ESTATE, "internal: osscar_init_greedy lost count of its removals");
+    if (done < batch) {
+      if (!use_lazy || !h.pause) return fail(c, OSSCAR_ESTATE, "internal: osscar_init_greedy stopped without a reason");
+      int acc = 0, it_idx = 0;
+      while (acc + takes[it_idx] <= done) { acc += takes[it_idx]; it_idx++; }
+      const int off = done - acc;                       // removals of iteration it_idx already applied
+      HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode));       // also clears pause
+      for (int i = off; i < takes[it_idx]; i++) HIPCHK(c, step(i));   // its pick list is still on the device
+      pending = takes[it_idx] - off;
+      batch = acc + takes[it_idx];
+      iter += it_idx + 1;
+    } else {
+      pending += batch;
+      iter += (int)takes.size();
+    }
+    expected += batch;
+    kept_now -= batch;
+    since_refresh += batch;
     const bool refresh = refresh_every > 0 && since_refresh >= refresh_every && kept_now > k;
-    if (use_lazy && (refresh || kept_now == k) && pending > 0) { HIPCHK(c, launch_lazy_flush(d, t, L, s)); pending = 0; }
-    if (since_check >= 256 || refresh || kept_now == k) {
-      st = read_ctrl(c, &h);
-      if (st != OSSCAR_OK) return st;
-      if (h.notpd) return fail(c, OSSCAR_ENOTPD, "osscar_init_greedy: a pivot block lost definiteness after %d removals", h.iters);
-      if (h.pause) return fail(c, OSSCAR_ESTATE, "internal: the pending-pivot set overflowed in osscar_init_greedy");
-      since_check = 0;
-    }
+    if (use_lazy && (refresh || kept_now == k) && pending > 0) { HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode)); pending = 0; }
     if (refresh) {
       st = read_kept(c);
       if (st != OSSCAR_OK) return st;
@@ -627,12 +662,15 @@ osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_e
       st = build_state(c, &obj);
       if (st != OSSCAR_OK) return st;
       HIPCHK(c, hipMemcpyAsync(reinterpret_cast<char*>(c->ctrl) + offsetof(SearchCtrl, obj), &obj, 8, hipMemcpyHostToDevice, s));
+      if (use_lazy) HIPCHK(c, launch_lazy_init(d, t, L, s, la_mode));
       since_refresh = 0;
     }
   }
   c->kr = k * q; c->cr = c->d1 - c->kr;
   st = read_ctrl(c, &h);
   if (st != OSSCAR_OK) return st;
+  if (h.notpd) return fail(c, OSSCAR_ENOTPD, "osscar_init_greedy: a pivot block lost definiteness after %d removals", h.iters);
+  if (h.iters != expected) return fail(c, OSSCAR_ESTATE, "internal: osscar_init_greedy applied %d of %d removals", h.iters, expected);
   st = read_kept(c);
   if (st != OSSCAR_OK) return st;
   st = upload_rows(c);
@@ -676,13 +714,14 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
     // delayed-update search: the tableau in HBM is only touched by a flush every FLUSH iterations
     const LazyPtrs& L = c->lazy;
     const int FLUSH = LAZY_TM / 2, BATCH = 32;
-    HIPCHK(c, launch_lazy_init(d, t, L, s));
+    const int la_mode = (flags & OSSCAR_SEARCH_NO_LOOKAHEAD) ? 2 : 0;
+    HIPCHK(c, launch_lazy_init(d, t, L, s, la_mode));
     int since_flush = 0;
     double flush_ms = 0; int flushes = 0;
     auto flush = [&]() -> osscar_status {
       hipEvent_t f0 = c->ev_s[0][0], f1 = c->ev_s[0][1];
       HIPCHK(c, hipEventRecord(f0, s));
-      HIPCHK(c, launch_lazy_flush(d, t, L, s));
+      HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode));
       HIPCHK(c, hipEventRecord(f1, s));
       HIPCHK(c, hipStreamSynchronize(s));
       float ms = 0; hipEventElapsedTime(&ms, f0, f1); flush_ms += ms; flushes++;
@@ -942,7 +981,7 @@ osscar_status osscar_get_scalars(osscar_ctx* c, double* lambda_host, double* c0_
 
 osscar_status osscar_get_timers(osscar_ctx* c, double* out) {
   if (!c || !out) return OSSCAR_EINVAL;
-  for (int i = 0; i < 8; i++) out[i] = c->timers[i];
+  for (int i = 0; i < 12; i++) out[i] = c->timers[i];
   return OSSCAR_OK;
 }
 

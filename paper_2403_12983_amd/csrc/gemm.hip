@@ -43,6 +43,38 @@ __device__ __forceinline__ Tile8 load8(const float* __restrict__ row, int c0, in
   return t;
 }
 
+// Block -> tile.  Workgroups go to the 8 XCDs in turn (block index modulo 8), each with its own L2; two workgroups fit a
+// CU, so 64 run together per XCD.  The tile grid is cut into 8 x 8 super-blocks, super-block b goes to XCD b % 8 and
+// the 64 workgroups an XCD runs together are the 64 tiles of one super-block: they share 8 row panels of A and 8
+// column panels of B in that L2.  Padding tiles return at once.  lower_only products walk the triangle row by row.
+constexpr int SB = 8;
+__device__ __forceinline__ bool tile_of_block(const GemmArgs& g, int& tile_m, int& tile_n) {
+  if (g.lower_only) {
+    // linear index over the lower-triangle tiles: t = tm*(tm+1)/2 + tn, tn <= tm
+    const int t = blockIdx.x;
+    int r = (int)((sqrtf(8.f * (float)t + 1.f) - 1.f) * 0.5f);
+    while ((r + 1) * (r + 2) / 2 <= t) r++;
+    while (r * (r + 1) / 2 > t) r--;
+    tile_m = r; tile_n = t - r * (r + 1) / 2;
+    return true;
+  }
+  const int tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
+  const int nsb_c = (tn + SB - 1) / SB, nsb = ((tm + SB - 1) / SB) * nsb_c;
+  const int b = blockIdx.x, xcd = b & 7, slot = b >> 3;
+  const int sb = (slot / (SB * SB)) * 8 + xcd, within = slot % (SB * SB);
+  if (sb >= nsb) return false;
+  tile_m = (sb / nsb_c) * SB + within / SB;
+  tile_n = (sb % nsb_c) * SB + within % SB;
+  if (tile_m >= tm || tile_n >= tn) return false;
+  return true;
+}
+static int grid_blocks(const GemmArgs& a) {
+  const int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
+  if (a.lower_only) return tm * (tm + 1) / 2;
+  const int nsb = ((tm + SB - 1) / SB) * ((tn + SB - 1) / SB);
+  return (nsb + 7) / 8 * 8 * SB * SB;
+}
+
 template <typename OutT>
 __global__ __launch_bounds__(256, 2) void gemm_f64acc_kernel(GemmArgs g, int vecA, int vecB, int vecC) {
   // A and B stages; after the main loop the same memory stages the output tile (4 waves x 16 x 66 doubles)
@@ -51,17 +83,7 @@ __global__ __launch_bounds__(256, 2) void gemm_f64acc_kernel(GemmArgs g, int vec
   float (*Bs)[BK][LDT] = reinterpret_cast<float (*)[BK][LDT]>(smem + 2 * BK * LDT);
 
   int tile_m, tile_n;
-  if (g.lower_only) {
-    // linear index over the lower-triangle tiles: t = tm*(tm+1)/2 + tn, tn <= tm
-    int t = blockIdx.x;
-    int tm = (int)((sqrtf(8.f * (float)t + 1.f) - 1.f) * 0.5f);
-    while ((tm + 1) * (tm + 2) / 2 <= t) tm++;
-    while (tm * (tm + 1) / 2 > t) tm--;
-    tile_m = tm; tile_n = t - tm * (tm + 1) / 2;
-  } else {
-    int tiles_n = (g.N + BN - 1) / BN;
-    tile_m = blockIdx.x / tiles_n; tile_n = blockIdx.x % tiles_n;
-  }
+  if (!tile_of_block(g, tile_m, tile_n)) return;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -200,16 +222,7 @@ __global__ __launch_bounds__(256, 2) void gemm_f32acc_kernel(GemmArgs g, int vec
   float (*As)[BK][LDT] = reinterpret_cast<float (*)[BK][LDT]>(smem);
   float (*Bs)[BK][LDT] = reinterpret_cast<float (*)[BK][LDT]>(smem + 2 * BK * LDT);
   int tile_m, tile_n;
-  if (g.lower_only) {
-    int t = blockIdx.x;
-    int tm = (int)((sqrtf(8.f * (float)t + 1.f) - 1.f) * 0.5f);
-    while ((tm + 1) * (tm + 2) / 2 <= t) tm++;
-    while (tm * (tm + 1) / 2 > t) tm--;
-    tile_m = tm; tile_n = t - tm * (tm + 1) / 2;
-  } else {
-    int tiles_n = (g.N + BN - 1) / BN;
-    tile_m = blockIdx.x / tiles_n; tile_n = blockIdx.x % tiles_n;
-  }
+  if (!tile_of_block(g, tile_m, tile_n)) return;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -326,8 +339,7 @@ __global__ __launch_bounds__(256, 2) void gemm_f32acc_kernel(GemmArgs g, int vec
 
 hipError_t launch_gemm_f64acc(const GemmArgs& a, hipStream_t s) {
   if (a.M <= 0 || a.N <= 0) return hipSuccess;
-  int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
-  int blocks = a.lower_only ? tm * (tm + 1) / 2 : tm * tn;
+  const int blocks = grid_blocks(a);
   int vecA = (a.lda % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.A) & 15) == 0);
   int vecB = (a.ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.B) & 15) == 0);
   int vecC = (!a.c_is_f64) && (a.ldc % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.C) & 15) == 0) &&

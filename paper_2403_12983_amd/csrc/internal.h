@@ -111,6 +111,8 @@ hipError_t launch_select(const TabDims& d, const TabPtrs& t, int forced_out, int
 // lazy.hip : delayed-update search for q = 1
 // ----------------------------------------------------------------------------------------------
 constexpr int LAZY_TM = 128;     // capacity of the pending pivot set (two per swap)
+constexpr int LAZY_NC = 256;     // rows of Z0 whose products with all of Z0 are computed ahead, after every flush
+constexpr int LAZY_NS = 64;      // spare slots for pivots that were not among them
 struct SelRec { double mn1, mn2, mx1, mx2; int32_t imn, imx; };   // best / second-best scores of a block of rows
 struct LazyPtrs {
   int32_t* pos;     // d1: position in the pending set or -1
@@ -129,13 +131,23 @@ struct LazyPtrs {
   double* ls;       // 16 scalars
   SelRec* sel;      // ceil(d1/32) per-block score records
   int32_t* counter; // workgroup counter of the update kernel
+  // products of Z0 with the rows of Z0 that are likely to become pivots before the next flush
+  double* GbT;      // (LAZY_NC + LAZY_NS) x d1: row s = Z0 Z0[cand[s], :]^T
+  float* Zc;        // LAZY_NC x m: the gathered rows
+  int32_t* cslot;   // d1: slot of a row in GbT or -1
+  int32_t* cand;    // LAZY_NC + LAZY_NS: row held by a slot or -1
+  int32_t* tslot;   // LAZY_TM: slot of each pending pivot
+  int32_t* misc;    // [0] spare slots in use, [1] miss mask of the current pair (1: g, 2: j), [2] slot of g, [3] slot of j
+  double* lkey; int32_t* lidx;   // 2 x 64 x 32: per-block winners of the candidate selection
 };
-hipError_t launch_lazy_init(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s);
+// mode: which rows get their products with Z0 computed ahead: 0 = LAZY_NC/2 cheapest removals + LAZY_NC/2 largest gains,
+// 1 = LAZY_NC cheapest removals (removal-only loops), 2 = none (every pivot then costs a pass over Z0)
+hipError_t launch_lazy_init(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode = 0);
 // ev (optional): events recorded before and after the pass over Z0, and at the end of the iteration
 // single (optional, device): removal of the one row *single instead of a swap; adds one pending pivot instead of two
 hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, int always_accept, hipStream_t s,
                                  hipEvent_t* ev = nullptr, const int32_t* single = nullptr);
-hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s);
+hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode = 0);
 
 hipError_t launch_scatter_rows(const float* src, int64_t lds, const int32_t* rows, int nrows, int ncols, void* dst,
                                int64_t ldd, int dst_is_bf16, hipStream_t s);

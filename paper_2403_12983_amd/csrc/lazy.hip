@@ -9,16 +9,26 @@
 //     Z_cur[i, :] = Z0[i, :] - C0[i, :] ZT,   Z_cur[T, :] = J ZT,       ZT = M^-1 Z0[T, :]
 // so one iteration needs only two columns of N_cur and two rows of Z_cur (O(tau (d1 + m))), the diagonal
 // and the squared row norms of Z_cur for the scores of eq. (impact) -- both updated incrementally, the
-// norms through one read-only pass over Z0 (w = Z0 [y1 y2]) -- and a bordering update of M^-1.  Every
+// norms through w = Z0 [y1 y2] -- and a bordering update of M^-1.
+// w without a pass over Z0: y1, y2 are combinations of the current rows g, j of Z, and these of base rows:
+//     Z0 z_g^T = Z0 Z0[g, :]^T - sum_r x_g[r] Z0 Z0[T_r, :]^T,     x_g = M^-1 C0[g, :]^T,
+// so it is enough to know the products of Z0 with the base rows of g, j and of the pending pivots.  Which rows
+// will be pivots before the next flush is predictable (the LAZY_NC/2 cheapest removals and largest gains at
+// flush time cover them), so right after each flush one matrix product Zc Z0^T computes those products for
+// LAZY_NC candidate rows (GbT); a pivot outside the candidates costs one read-only pass over Z0 for its column
+// (kept in one of LAZY_NS spare slots).  Every
 // LAZY_TM/2 iterations the pending rank-tau correction is applied to N0 and Z0 by matrix products on the
 // matrix cores.  The sequence of swaps is exactly that of the eager search (Proposition 4.1, Cases 1-3).
 //
 // Four launches per iteration:
 //   prep    (1 workgroup)  : argmin / argmax from per-block partial records; x = M^-1 N0[T, {g, j}]; pivots
 //   vectors (rows | cols)  : current columns g, j of N; current rows g, j of Z scaled to y1, y2; partial sums
-//   gemv    (rows)         : exact change of the objective and the acceptance test; w = Z0 [y1 y2]; u = ZT [y1 y2]
+//   gemv    (rows)         : exact change of the objective and the acceptance test; u = ZT [y1 y2]; for a pivot that is
+//                            not among the candidates, its column Z0 Z0[g, :]^T by a pass over Z0
+//   wcache  (rows)         : w = Z0 [y1 y2] from the cached products
 //   update  (rows|cols|M)  : norms, diagonal, scores and their partial records; C0 append; ZT and M^-1 update
 #include "internal.h"
+#include <algorithm>
 
 namespace osscar {
 
@@ -36,6 +46,8 @@ constexpr int COLS_PER_BLOCK = 64;   // column kernels: 64 columns x 4 slices of
 
 // ls[] slots
 enum { LS_DG = 0, LS_NJG = 1, LS_M1 = 2, LS_DJ = 3, LS_Y11 = 4, LS_Y22 = 5, LS_Y12 = 6, LS_OBJ = 8 };
+// misc[] slots
+enum { MI_SPARE = 0, MI_MISS = 1, MI_SG = 2, MI_SJ = 3 };
 
 // merge of two (best, second, index) records; lowest index wins ties
 __device__ __forceinline__ void merge_min(double& a1, double& a2, int& ia, double b1, double b2, int ib) {
@@ -98,7 +110,12 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
   }
   const int g = single ? *single : s_imn[0], j = single ? g : s_imx[0], tau = ctrl->tau;
   if (g < 0 || j < 0) { if (tid == 0) { ctrl->done = 1; ctrl->g_out = -1; ctrl->g_in = -1; } return; }
-  if (L.pos[g] >= 0 || L.pos[j] >= 0 || tau + (single ? 1 : 2) > LAZY_TM) { if (tid == 0) ctrl->pause = 1; return; }
+  const int sg0 = L.cslot[g], sj0 = L.cslot[j];
+  const int need = (sg0 < 0 ? 1 : 0) + ((!single && sj0 < 0) ? 1 : 0);
+  if (L.pos[g] >= 0 || L.pos[j] >= 0 || tau + (single ? 1 : 2) > LAZY_TM || L.misc[MI_SPARE] + need > LAZY_NS) {
+    if (tid == 0) ctrl->pause = 1;
+    return;
+  }
   // b = N0[T, {g, j}] (these are rows g, j of C0), x = M^-1 b, zero beyond tau
   for (int s = tid; s < LAZY_TM; s += 256) {
     bg[s] = (s < tau) ? (double)L.C0R[(int64_t)g * LAZY_TM + s] : 0.0;
@@ -130,6 +147,12 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
     L.ls[LS_DG] = Dg; L.ls[LS_NJG] = single ? 0.0 : njg; L.ls[LS_M1] = M1; L.ls[LS_DJ] = Dj; L.ls[LS_OBJ] = ctrl->obj;
     if (bad1 || bad2) ctrl->notpd = 1;
     ctrl->g_out = g; ctrl->g_in = j;
+    // slots of the two base columns; a pivot that is not among the candidates takes a spare slot, filled by the next kernel
+    int ns = L.misc[MI_SPARE], miss = 0, sg = sg0, sj = sj0;
+    if (sg < 0) { sg = LAZY_NC + ns++; L.cslot[g] = sg; L.cand[sg] = g; miss |= 1; }
+    if (single) sj = sg;
+    else if (sj < 0) { sj = LAZY_NC + ns++; L.cslot[j] = sj; L.cand[sj] = j; miss |= 2; }
+    L.misc[MI_SPARE] = ns; L.misc[MI_MISS] = miss; L.misc[MI_SG] = sg; L.misc[MI_SJ] = sj;
     const double m1 = s_mn1[0], m2 = s_mn2[0], x1 = s_mx1[0], x2 = s_mx2[0];
     ctrl->gap_rem = isfinite(m2) ? fabs(m2 - m1) / fmax(fabs(m1), 1e-300) : INFINITY;
     ctrl->gap_add = isfinite(x2) ? fabs(x1 - x2) / fmax(fabs(x1), 1e-300) : INFINITY;
@@ -263,8 +286,13 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
     if (lane == 0) { L.u1[row] = a; L.u2[row] = b; }     // zero beyond tau
     return;
   }
-  // Each wave owns GEMV_RPW rows.  Products are summed four at a time in float32 (one float4 of Z0 against one of y)
-  // and the partial sums are accumulated in float64: the rounding this adds is below that of Z0's own float32 storage.
+  // Pivots outside the candidate set: their columns Z0 Z0[g, :]^T, Z0 Z0[j, :]^T by one pass over Z0.  Each wave owns
+  // GEMV_RPW rows.  Products are summed four at a time in float32 (one float4 of Z0 against one of the pivot row) and the
+  // partial sums are accumulated in float64: the rounding this adds is below that of Z0's own float32 storage.
+  const int miss = L.misc[MI_MISS];
+  if (miss == 0) return;
+  const float* yg = Z0 + (int64_t)ctrl->g_out * m;
+  const float* yj = Z0 + (int64_t)ctrl->g_in * m;
   const int row0 = ((int)blockIdx.x - ZTB) * GEMV_ROWS + wave * GEMV_RPW;
   double a1[GEMV_RPW], a2[GEMV_RPW];
   const float* rp[GEMV_RPW];
@@ -279,7 +307,7 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
   for (int c0 = 0; c0 < m; c0 += LAZY_CH) {
     const int cw = (m - c0 < LAZY_CH) ? m - c0 : LAZY_CH;
     __syncthreads();
-    for (int c = tid; c < cw; c += 256) { sy1[c] = L.y1f[c0 + c]; sy2[c] = L.y2f[c0 + c]; }
+    for (int c = tid; c < cw; c += 256) { sy1[c] = yg[c0 + c]; sy2[c] = yj[c0 + c]; }
     __syncthreads();
     if (vec) {
       for (int c = lane * 4; c < cw; c += 256 * GEMV_UNR) {
@@ -317,12 +345,46 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
       }
     }
   }
+  double* colg = L.GbT + (int64_t)L.misc[MI_SG] * d1;
+  double* colj = L.GbT + (int64_t)L.misc[MI_SJ] * d1;
 #pragma unroll
   for (int r = 0; r < GEMV_RPW; r++) {
     double t1 = wsum(a1[r]), t2 = wsum(a2[r]);
     const int row = row0 + r;
-    if (lane == 0 && row < d1) { L.w1[row] = t1; L.w2[row] = t2; }
+    if (lane == 0 && row < d1) {
+      if (miss & 1) colg[row] = t1;
+      if (miss & 2) colj[row] = t2;
+    }
   }
+}
+
+// ---------------------------------------------------------------------------------------------- wcache
+// w1 = Z0 y1, w2 = Z0 y2 from the cached base products: with a_g = col(g) - sum_r x_g[r] col(T_r) (= Z0 z_g^T) and a_j
+// likewise, w1 = Dg a_g and w2 = Dj (a_j - n_jg w1).  64 rows x 4 slices of the pending set per workgroup.
+__global__ __launch_bounds__(256) void lazy_wcache_kernel(LazyPtrs L, int d1, const SearchCtrl* __restrict__ ctrl) {
+  __shared__ double sxg[LAZY_TM], sxj[LAZY_TM];
+  __shared__ int sts[LAZY_TM];
+  __shared__ double red[2][4][64];
+  if (idle(ctrl)) return;
+  const int tid = threadIdx.x, tau = ctrl->tau;
+  for (int s = tid; s < LAZY_TM; s += 256) { sxg[s] = L.xg[s]; sxj[s] = L.xj[s]; sts[s] = (s < tau) ? L.tslot[s] : 0; }
+  __syncthreads();
+  const int slice = tid >> 6, lr = tid & 63, row = blockIdx.x * 64 + lr;
+  const int rc = row < d1 ? row : d1 - 1;
+  double ag = 0, aj = 0;
+  for (int r = slice; r < tau; r += 4) {
+    const double b = L.GbT[(int64_t)sts[r] * d1 + rc];
+    ag += sxg[r] * b; aj += sxj[r] * b;
+  }
+  red[0][slice][lr] = ag; red[1][slice][lr] = aj;
+  __syncthreads();
+  if (slice != 0 || row >= d1) return;
+  const double Dg = L.ls[LS_DG], njg = L.ls[LS_NJG], Dj = L.ls[LS_DJ];
+  const double tg = L.GbT[(int64_t)L.misc[MI_SG] * d1 + row] - (red[0][0][lr] + red[0][1][lr] + red[0][2][lr] + red[0][3][lr]);
+  const double tj = L.GbT[(int64_t)L.misc[MI_SJ] * d1 + row] - (red[1][0][lr] + red[1][1][lr] + red[1][2][lr] + red[1][3][lr]);
+  const double w1 = Dg * tg;
+  L.w1[row] = w1;
+  L.w2[row] = Dj * (tj - njg * w1);
 }
 
 // ---------------------------------------------------------------------------------------------- update
@@ -362,10 +424,10 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
           r = y11 - 2.0 * M1 * y12 + M1 * M1 * y22;          // || -y1 + M1 y2 ||^2
           dn = -Dg - M1 * M1 * Dj;
           kp = 0;
-          L.pos[row] = tau; L.Tidx[tau] = row; L.Jsg[tau] = -1.f;
+          L.pos[row] = tau; L.Tidx[tau] = row; L.Jsg[tau] = -1.f; L.tslot[tau] = L.misc[MI_SG];
         } else if (row == j) {
           r = y22; dn = -Dj; kp = 1;
-          L.pos[row] = tau + 1; L.Tidx[tau + 1] = row; L.Jsg[tau + 1] = 1.f;
+          L.pos[row] = tau + 1; L.Tidx[tau + 1] = row; L.Jsg[tau + 1] = 1.f; L.tslot[tau + 1] = L.misc[MI_SJ];
         } else {
           double zy1, zy2;
           const int ps = L.pos[row];
@@ -460,6 +522,7 @@ hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyP
   if (ev) hipEventRecord(ev[0], s);
   hipLaunchKernelGGL(lazy_gemv_kernel, dim3(gb), dim3(256), 0, s, L, t.Z, d.d1, d.m, cb, t.ctrl, always_accept, t.trace_out,
                      t.trace_in, t.trace_gap, t.trace_obj);
+  hipLaunchKernelGGL(lazy_wcache_kernel, dim3((d.d1 + 63) / 64), dim3(256), 0, s, L, d.d1, t.ctrl);
   if (ev) hipEventRecord(ev[1], s);
   hipLaunchKernelGGL(lazy_update_kernel, dim3(rb + cb + 16), dim3(256), 0, s, L, t.N, d.d1, d.m, rb, cb, t.ctrl, t.kept, t.gram,
                      t.dblk, t.score, single ? 1 : 0);
@@ -521,13 +584,97 @@ __global__ __launch_bounds__(256) void lazy_reset_kernel(LazyPtrs L, SearchCtrl*
   if (threadIdx.x == 0) { ctrl->tau = 0; ctrl->pause = 0; }
 }
 
+// ------------------------------------------------------------------------------------------------
+// candidate rows and their products with Z0 (after every flush)
+// ------------------------------------------------------------------------------------------------
+// ascending bitonic sort of 1024 (key, index) pairs in LDS; equal keys: lower index first
+__device__ __forceinline__ void bitonic1024(double* key, int* idx, int tid) {
+  for (int k = 2; k <= 1024; k <<= 1)
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      const int other = tid ^ j;
+      if (other > tid) {
+        const bool up = ((tid & k) == 0);
+        const double a = key[tid], b = key[other];
+        const int ia = idx[tid], ib = idx[other];
+        const bool a_after_b = (a > b) || (a == b && ia > ib);
+        if (a_after_b == up) { key[tid] = b; key[other] = a; idx[tid] = ib; idx[other] = ia; }
+      }
+      __syncthreads();
+    }
+}
+
+// per block of 1024 groups: the `per_block` cheapest removals among kept rows and the `per_block` largest gains among the others
+__global__ __launch_bounds__(1024) void cand_local_kernel(LazyPtrs L, int p, const int32_t* __restrict__ kept,
+                                                           const double* __restrict__ score, int per_block) {
+  __shared__ double key[1024];
+  __shared__ int idx[1024];
+  const int tid = threadIdx.x, h = blockIdx.x * 1024 + tid, nblk = gridDim.x;
+  for (int side = 0; side < 2; side++) {
+    const bool valid = (h < p) && ((kept[h] != 0) == (side == 0));
+    key[tid] = valid ? (side == 0 ? score[h] : -score[h]) : INFINITY;
+    idx[tid] = valid ? h : 0x7fffffff;
+    __syncthreads();
+    bitonic1024(key, idx, tid);
+    if (tid < per_block) {
+      L.lkey[(side * nblk + blockIdx.x) * 32 + tid] = key[tid];
+      L.lidx[(side * nblk + blockIdx.x) * 32 + tid] = idx[tid];
+    }
+    __syncthreads();
+  }
+}
+
+// merge of the per-block winners: n_k kept rows into slots [0, n_k), n_c others into [n_k, n_k + n_c); unused slots hold -1
+__global__ __launch_bounds__(1024) void cand_merge_kernel(LazyPtrs L, int nblk, int per_block, int n_k, int n_c) {
+  __shared__ double key[1024];
+  __shared__ int idx[1024];
+  const int tid = threadIdx.x, total = nblk * per_block;
+  for (int s = tid; s < LAZY_NC + LAZY_NS; s += 1024) L.cand[s] = -1;
+  if (tid < 8) L.misc[tid] = 0;
+  __syncthreads();
+  for (int side = 0; side < 2; side++) {
+    const int cnt = side == 0 ? n_k : n_c, base = side == 0 ? 0 : n_k;
+    if (tid < total) {
+      key[tid] = L.lkey[(side * nblk + tid / per_block) * 32 + tid % per_block];
+      idx[tid] = L.lidx[(side * nblk + tid / per_block) * 32 + tid % per_block];
+    } else { key[tid] = INFINITY; idx[tid] = 0x7fffffff; }
+    __syncthreads();
+    bitonic1024(key, idx, tid);
+    if (tid < cnt && key[tid] < INFINITY) { L.cand[base + tid] = idx[tid]; L.cslot[idx[tid]] = base + tid; }
+    __syncthreads();
+  }
+}
+
+// Zc[s, :] = Z0[cand[s], :] (zero for unused slots)
+__global__ __launch_bounds__(256) void cand_gather_kernel(LazyPtrs L, const float* __restrict__ Z0, int m) {
+  const int s = blockIdx.x, r = L.cand[s];
+  float* dst = L.Zc + (int64_t)s * m;
+  for (int c = threadIdx.x; c < m; c += 256) dst[c] = (r >= 0) ? Z0[(int64_t)r * m + c] : 0.f;
+}
+
+// mode 0: half of the slots for kept rows, half for the others; 1: all for kept rows (removal-only loops); 2: none
+static hipError_t launch_candidates(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode) {
+  const int nblk = (d.p + 1023) / 1024;               // <= 64 (d1 <= 65536)
+  const int per_block = std::min(32, 1024 / nblk);
+  hipError_t e = hipMemsetAsync(L.cslot, 0xFF, (size_t)d.d1 * 4, s);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(cand_local_kernel, dim3(nblk), dim3(1024), 0, s, L, d.p, t.kept, t.score, per_block);
+  const int n_k = mode == 2 ? 0 : (mode == 1 ? LAZY_NC : LAZY_NC / 2), n_c = mode == 0 ? LAZY_NC / 2 : 0;
+  hipLaunchKernelGGL(cand_merge_kernel, dim3(1), dim3(1024), 0, s, L, nblk, per_block, n_k, n_c);
+  if (mode == 2) return hipGetLastError();
+  hipLaunchKernelGGL(cand_gather_kernel, dim3(LAZY_NC), dim3(256), 0, s, L, t.Z, d.m);
+  GemmArgs g{};                         // GbT[0 .. LAZY_NC) = Zc Z0^T, float64
+  g.M = LAZY_NC; g.N = d.d1; g.K = d.m; g.A = L.Zc; g.lda = d.m; g.B = t.Z; g.ldb = d.m; g.trans_b = 1;
+  g.C = L.GbT; g.ldc = d.d1; g.alpha = 1.0; g.beta = 0.0; g.c_is_f64 = 1;
+  return launch_gemm_f64acc(g, s);
+}
+
 static hipError_t launch_partials(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s) {
   const int rb = (d.d1 + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
   hipLaunchKernelGGL(lazy_partials_kernel, dim3(rb), dim3(64), 0, s, L, d.p, t.kept, t.score);
   return hipGetLastError();
 }
 
-hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s) {
+hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode) {
   const int rb = (d.d1 + 255) / 256, mb = (d.m + 255) / 256;
   hipLaunchKernelGGL(lazy_convert_kernel, dim3(512), dim3(256), 0, s, L, d.m, t.ctrl);
   GemmArgs e{};                         // E = C0 M^-1
@@ -550,10 +697,12 @@ hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs&
   hipLaunchKernelGGL(lazy_reset_kernel, dim3(1), dim3(256), 0, s, L, t.ctrl);
   err = launch_refresh_scores(d, t, s);
   if (err != hipSuccess) return err;
-  return launch_partials(d, t, L, s);
+  err = launch_partials(d, t, L, s);
+  if (err != hipSuccess) return err;
+  return launch_candidates(d, t, L, s, mode);
 }
 
-hipError_t launch_lazy_init(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s) {
+hipError_t launch_lazy_init(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode) {
   hipError_t e = hipMemsetAsync(L.pos, 0xFF, (size_t)d.d1 * 4, s);
   if (e != hipSuccess) return e;
   e = hipMemsetAsync(L.Minv, 0, (size_t)LAZY_TM * LAZY_TM * 8, s);
@@ -562,7 +711,9 @@ hipError_t launch_lazy_init(const TabDims& d, const TabPtrs& t, const LazyPtrs& 
   if (e != hipSuccess) return e;
   e = hipMemsetAsync(L.counter, 0, 4, s);
   if (e != hipSuccess) return e;
-  return launch_partials(d, t, L, s);
+  e = launch_partials(d, t, L, s);
+  if (e != hipSuccess) return e;
+  return launch_candidates(d, t, L, s, mode);
 }
 
 }  // namespace osscar

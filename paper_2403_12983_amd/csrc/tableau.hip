@@ -797,7 +797,7 @@ __global__ __launch_bounds__(1024) void greedy_pick_kernel(TabDims d, const int3
   __shared__ int s_i[1024];
   __shared__ int chosen[65];
   __shared__ double chosen_v[65];
-  if (ctrl->done) return;
+  if (ctrl->done || ctrl->pause) return;
   const int tid = threadIdx.x;
   for (int round = 0; round <= take; round++) {
     double best = INFINITY;

@@ -302,6 +302,17 @@ def test_delayed_update_search_equals_eager_search():
             assert np.max(np.abs(T(s, "T_REM")[fk] - reme[fk]) / reme[fk]) < 1e-4
             assert np.max(np.abs(T(s, "T_ADD")[fc] - adde[fc]) / adde[fc]) < 1e-4
             assert abs(e["obj_final"] - l["obj_final"]) <= 1e-5 * abs(e["obj_final"])
+        # without the products computed ahead every pivot takes the pass over Z and a spare slot; the spare slots run
+        # out every 32 swaps, which forces extra flushes: same swaps again
+        s.osscar_init_support()
+        n = s.osscar_local_search(swaps, 0.0, B.OSSCAR_SEARCH_ALWAYS_ACCEPT | B.OSSCAR_SEARCH_NO_LOOKAHEAD)
+        assert n["iters"] == swaps
+        for i in range(swaps):
+            if (n["trace_out"][i], n["trace_in"][i]) != (l["trace_out"][i], l["trace_in"][i]):
+                assert min(l["trace_gap"][i]) < 1e-4, (i, l["trace_gap"][i])
+                break
+        else:
+            assert abs(n["obj_final"] - l["obj_final"]) <= 1e-6 * abs(l["obj_final"])
         s.close()
 
 
@@ -383,6 +394,10 @@ def test_greedy_refresh_and_edges():
     # in-place updates after every removal take the same path as the delayed updates
     obj_e, steps_e, gaps_e = s.osscar_init_greedy(10, 0, _pkg().OSSCAR_SEARCH_EAGER)
     assert steps_e == steps_a and abs(obj_e - obj_a) <= 1e-6 * obj_a
+    # no products computed ahead: every removal takes a spare slot, they run out in the middle of an iteration
+    # (64 spare slots, 10 removals per iteration), and the loop resumes after a flush
+    obj_n, steps_n, gaps_n = s.osscar_init_greedy(10, 0, _pkg().OSSCAR_SEARCH_NO_LOOKAHEAD)
+    assert steps_n == steps_a and abs(obj_n - obj_a) <= 1e-6 * obj_a
     s.close()
     from paper_2403_12983_amd.binding import OsscarError
     s = c.solver()                                                               # created without from_dense
