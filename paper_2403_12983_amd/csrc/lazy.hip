@@ -244,6 +244,9 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
   __shared__ float sy1[LAZY_CH], sy2[LAZY_CH];
   __shared__ int s_ok;
   if (idle(ctrl)) return;
+  constexpr int ZTB = LAZY_TM;                        // leading workgroups: one pending row of ZT each
+  // the row workgroups have work only when a pivot's products were not computed ahead (workgroup 0 records the decision)
+  if ((int)blockIdx.x >= ZTB && L.misc[MI_MISS] == 0) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (wave == 0) {
     // partial sums in a fixed order: lane l adds the records l, l + 64, ...; then a wave reduction
@@ -273,17 +276,22 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
   }
   __syncthreads();
   if (!s_ok) return;
-  constexpr int ZTB = LAZY_TM / 4;                    // leading workgroups: one pending row of ZT per wave
   if ((int)blockIdx.x < ZTB) {
-    const int row = blockIdx.x * 4 + wave;
+    __shared__ double ured[2][4];
+    const int row = blockIdx.x;
     double a = 0, b = 0;
     if (row < ctrl->tau) {
       const double* zt = L.ZT + (int64_t)row * m;
 #pragma unroll 4
-      for (int c = lane; c < m; c += 64) { const double z = zt[c]; a += z * L.y1[c]; b += z * L.y2[c]; }
-      a = wsum(a); b = wsum(b);
+      for (int c = tid; c < m; c += 256) { const double z = zt[c]; a += z * L.y1[c]; b += z * L.y2[c]; }
     }
-    if (lane == 0) { L.u1[row] = a; L.u2[row] = b; }     // zero beyond tau
+    a = wsum(a); b = wsum(b);
+    if (lane == 0) { ured[0][wave] = a; ured[1][wave] = b; }
+    __syncthreads();
+    if (tid == 0) {                                      // zero beyond tau
+      L.u1[row] = ured[0][0] + ured[0][1] + ured[0][2] + ured[0][3];
+      L.u2[row] = ured[1][0] + ured[1][1] + ured[1][2] + ured[1][3];
+    }
     return;
   }
   // Pivots outside the candidate set: their columns Z0 Z0[g, :]^T, Z0 Z0[j, :]^T by one pass over Z0.  Each wave owns
@@ -518,7 +526,7 @@ hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyP
   const int rb = (d.d1 + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, cb = (d.m + COLS_PER_BLOCK - 1) / COLS_PER_BLOCK;
   hipLaunchKernelGGL(lazy_prep_kernel, dim3(1), dim3(256), 0, s, L, t.N, d.d1, rb, t.ctrl, single);
   hipLaunchKernelGGL(lazy_vectors_kernel, dim3(rb + cb), dim3(256), 0, s, L, t.N, t.Z, d.d1, d.m, rb, t.ctrl);
-  const int gb = (d.d1 + GEMV_ROWS - 1) / GEMV_ROWS + LAZY_TM / 4;
+  const int gb = (d.d1 + GEMV_ROWS - 1) / GEMV_ROWS + LAZY_TM;
   if (ev) hipEventRecord(ev[0], s);
   hipLaunchKernelGGL(lazy_gemv_kernel, dim3(gb), dim3(256), 0, s, L, t.Z, d.d1, d.m, cb, t.ctrl, always_accept, t.trace_out,
                      t.trace_in, t.trace_gap, t.trace_obj);
@@ -658,12 +666,13 @@ static hipError_t launch_candidates(const TabDims& d, const TabPtrs& t, const La
   hipError_t e = hipMemsetAsync(L.cslot, 0xFF, (size_t)d.d1 * 4, s);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(cand_local_kernel, dim3(nblk), dim3(1024), 0, s, L, d.p, t.kept, t.score, per_block);
+  // (the product takes about as long for 128 rows as for 256: one 128-row tile per CU leaves the CU half empty)
   const int n_k = mode == 2 ? 0 : (mode == 1 ? LAZY_NC : LAZY_NC / 2), n_c = mode == 0 ? LAZY_NC / 2 : 0;
   hipLaunchKernelGGL(cand_merge_kernel, dim3(1), dim3(1024), 0, s, L, nblk, per_block, n_k, n_c);
   if (mode == 2) return hipGetLastError();
-  hipLaunchKernelGGL(cand_gather_kernel, dim3(LAZY_NC), dim3(256), 0, s, L, t.Z, d.m);
+  hipLaunchKernelGGL(cand_gather_kernel, dim3(n_k + n_c), dim3(256), 0, s, L, t.Z, d.m);
   GemmArgs g{};                         // GbT[0 .. LAZY_NC) = Zc Z0^T, float64
-  g.M = LAZY_NC; g.N = d.d1; g.K = d.m; g.A = L.Zc; g.lda = d.m; g.B = t.Z; g.ldb = d.m; g.trans_b = 1;
+  g.M = n_k + n_c; g.N = d.d1; g.K = d.m; g.A = L.Zc; g.lda = d.m; g.B = t.Z; g.ldb = d.m; g.trans_b = 1;
   g.C = L.GbT; g.ldc = d.d1; g.alpha = 1.0; g.beta = 0.0; g.c_is_f64 = 1;
   return launch_gemm_f64acc(g, s);
 }
