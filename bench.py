@@ -168,7 +168,7 @@ def main():
     g_flops = 2.0 * d1 * d1 * m
     g_bytes = 4.0 * (d1 * d1 + 2 * d1 * m)                       # read H and W once, write G once
     # HBM bytes of that launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/gemm_f64acc_cfg5_pmc.md), cfg5 only
-    g_traffic = 130.6e9 if a.config == "cfg5" else None
+    g_traffic = 128.2e9 if a.config == "cfg5" else None
     out = {
         "metric": "OPT-30B fc2 layer prune time", "value": t_layer, "unit": "s", "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": 1e3 * t_layer, "higher_is_better": False, "scaling": "weak",
