@@ -92,6 +92,8 @@ struct osscar_ctx {
   SearchCtrl* ctrl;
   int32_t *trace_out, *trace_in; float* trace_gap; double* trace_obj;
   int32_t *g_pick, *g_removed; float* g_gap;   // nested schedule from the dense layer
+  float* Wdense = nullptr;       // from_dense contexts: float32 copy of W kept from finalize (the dense layer's exact weights)
+  bool have_Wdense = false;
   LazyPtrs lazy;
   // phase-shared scratch
   char* scratch; size_t scratch_bytes;
@@ -146,6 +148,7 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
   int32_t* g_pick = cv.take<int32_t>(64);
   int32_t* g_removed = cv.take<int32_t>(p);
   float* g_gap = cv.take<float>(p);
+  float* Wdense = ds.from_dense ? cv.take<float>(d1 * m) : nullptr;
   LazyPtrs L{};
   if (q == 1) {
     const int64_t TM = LAZY_TM;
@@ -182,7 +185,7 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
     c->small = small; c->scal = scal; c->partial = partial; c->kept = kept; c->rowsK = rowsK; c->rowsC = rowsC;
     c->notpd = notpd; c->C1 = C1; c->C2 = C2; c->Cblk = Cblk; c->rZ1 = rZ1; c->rZ2 = rZ2; c->ctrl = ctrl;
     c->trace_out = trace_out; c->trace_in = trace_in; c->trace_gap = trace_gap; c->trace_obj = trace_obj;
-    c->g_pick = g_pick; c->g_removed = g_removed; c->g_gap = g_gap;
+    c->g_pick = g_pick; c->g_removed = g_removed; c->g_gap = g_gap; c->Wdense = Wdense;
     c->scratch = scratch; c->scratch_bytes = scratch_bytes; c->lazy = L;
   }
   Layout lay; lay.total = cv.off; lay.scratch_bytes = scratch_bytes;
@@ -249,7 +252,8 @@ osscar_status upload_rows(osscar_ctx* c) {
 // c->rowsK.  Buffers come from the scratch region: HKK (kept), P, T1, T2 (kr x kr each), GK, B (kr x m), T3, T4.
 struct InvBufs { float *HKK, *P, *T1, *T2, *GK, *B, *T3, *T4, *panels; };
 
-osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b) {
+// B_known (optional, kr x m): the weights are known exactly (dense layer: B = W), only G_K is gathered beside them.
+osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b, const float* B_known = nullptr) {
   hipStream_t s = c->stream;
   const int kr = c->kr, m = c->m;
   HIPCHK(c, launch_gather(c->H, c->d1, c->rowsK, kr, c->rowsK, kr, b.HKK, kr, s));
@@ -275,6 +279,10 @@ osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b) {
   }
   // B = P G_K, then B += P (G_K - H_KK B)
   HIPCHK(c, launch_gather(c->G, m, c->rowsK, kr, nullptr, m, b.GK, m, s));
+  if (B_known) {
+    HIPCHK(c, hipMemcpyAsync(b.B, B_known, (size_t)kr * m * 4, hipMemcpyDeviceToDevice, s));
+    return OSSCAR_OK;
+  }
   HIPCHK(c, gemm(s, kr, m, kr, b.P, kr, b.GK, m, nullptr, 0, b.T3, m, 1.0, 0.0));
   HIPCHK(c, gemm(s, kr, m, kr, b.HKK, kr, b.T3, m, b.GK, m, b.T4, m, -1.0, 1.0));
   HIPCHK(c, gemm(s, kr, m, kr, b.P, kr, b.T4, m, b.T3, m, b.B, m, 1.0, 1.0));
@@ -301,7 +309,7 @@ osscar_status objective_from(osscar_ctx* c, const float* GK, const float* B, dou
 }
 
 // Builds N, Z, the scores and the tracked objective for the kept set in c->kept_host.
-osscar_status build_state(osscar_ctx* c, double* obj_out) {
+osscar_status build_state(osscar_ctx* c, double* obj_out, const float* B_known = nullptr) {
   hipStream_t s = c->stream;
   const int d1 = c->d1, m = c->m, kr = c->kr, cr = c->cr;
   osscar_status st = upload_rows(c);
@@ -315,7 +323,7 @@ osscar_status build_state(osscar_ctx* c, double* obj_out) {
   float* S = cv.take<float>((int64_t)cr * cr);
   float* R = cv.take<float>((int64_t)cr * m);
   if (cv.off > c->scratch_bytes) return fail(c, OSSCAR_ENOMEM, "internal: scratch carve-up exceeds the workspace");
-  st = inverse_and_weights(c, b);
+  st = inverse_and_weights(c, b, B_known);
   if (st != OSSCAR_OK) return st;
   if (cr > 0) {
     HIPCHK(c, launch_gather(c->H, d1, c->rowsK, kr, c->rowsC, cr, HKC, cr, s));
@@ -502,6 +510,12 @@ static osscar_status gram_impl(osscar_ctx* c, const char* who, int target, const
   HIPCHK(c, hipMemcpyAsync(c->norms_host.data(), c->norms2, c->p * 8, hipMemcpyDeviceToHost, s));
   HIPCHK(c, hipEventRecord(c->ev_b, s));
   HIPCHK(c, hipStreamSynchronize(s));
+  c->have_Wdense = false;
+  if (!target && c->Wdense) {
+    HIPCHK(c, hipMemcpyAsync(c->Wdense, Wf, (size_t)d1 * m * 4, hipMemcpyDeviceToDevice, s));
+    HIPCHK(c, hipStreamSynchronize(s));
+    c->have_Wdense = true;
+  }
   if (target) c->c0 = yy + c->lambda * c->c0;
   else { float ms = 0; hipEventElapsedTime(&ms, c->ev_s[0][0], c->ev_s[0][1]); c->timers[8] = ms; }
   c->dense_is_exact = !target;
@@ -529,7 +543,7 @@ osscar_status osscar_set_quadratic(osscar_ctx* c, const float* H_dev, const floa
   HIPCHK(c, hipMemcpyAsync(c->H, H_dev, (size_t)c->d1 * c->d1 * 4, hipMemcpyDeviceToDevice, s));
   HIPCHK(c, hipMemcpyAsync(c->G, G_dev, (size_t)c->d1 * c->m * 4, hipMemcpyDeviceToDevice, s));
   HIPCHK(c, hipStreamSynchronize(s));
-  c->c0 = c0; c->lambda = 0; c->dense_is_exact = false;
+  c->c0 = c0; c->lambda = 0; c->dense_is_exact = false; c->have_Wdense = false;
   c->norms_host.assign(norms, norms + c->p);
   c->phase = osscar_ctx::FINAL;
   return OSSCAR_OK;
@@ -592,7 +606,7 @@ osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_e
   c->kept_host.assign(p, 1);
   c->kr = c->d1; c->cr = 0;
   double obj = 0;
-  st = build_state(c, &obj);
+  st = build_state(c, &obj, (c->dense_is_exact && c->have_Wdense) ? c->Wdense : nullptr);
   if (st != OSSCAR_OK) { c->kr = k * q; c->cr = c->d1 - c->kr; return st; }
   SearchCtrl h{};
   h.obj = c->dense_is_exact ? 0.0 : obj;   // the dense layer reproduces its own output exactly; a target output it does not
