@@ -357,6 +357,91 @@ def local_search(H: np.ndarray, G: np.ndarray, c0: float, groups0: Sequence[int]
 
 
 # --------------------------------------------------------------------------------------------------
+# Block moves (Section 4.2 with t-hat = 2 s, p-hat = 0: s1 = s2 = s groups leave and s enter per iteration)
+# --------------------------------------------------------------------------------------------------
+@dataclasses.dataclass
+class BlockRecord:
+    out: List[int]         # groups leaving, cheapest removal first
+    inn: List[int]         # groups entering, largest gain first
+    delta: float           # exact change of obj for the whole move (Case 1 s times, then Case 2 s times)
+    gap_rem: float         # relative gap between the costliest removal chosen and the cheapest kept group left
+    gap_add: float         # relative gap between the smallest gain chosen and the largest gain left out
+    deficit_rem: float     # how far a forced choice is from the oracle's own s-th best (0 for its own choice)
+    deficit_add: float
+    accepted: bool
+    obj_after: float
+
+
+@dataclasses.dataclass
+class BlockResult:
+    support: List[int]
+    obj_initial: float
+    obj_final: float
+    iters: int
+    accepted: int
+    trace: List[BlockRecord]
+    state: State
+
+
+def block_search(H: np.ndarray, G: np.ndarray, c0: float, groups0: Sequence[int], p: int, q: int, max_iters: int,
+                 s: int, rel_tol: float = 0.0, always_accept: bool = False,
+                 follow: Optional[Sequence[Tuple[Sequence[int], Sequence[int]]]] = None) -> BlockResult:
+    """Local search with s groups out and s in per iteration.  All impacts (eq. (impact)) are evaluated at the state
+    the iteration starts from; the s kept groups that are cheapest to remove leave, the s outside groups with the
+    largest gain enter (lowest index on ties; s is cut to what either side has).  The move is applied only if its
+    exact effect lowers obj by more than rel_tol*obj (always_accept: always), otherwise the search stops.
+    s = 1 is local_search.  follow: per-iteration (out, inn) lists to apply instead of the oracle's own choice."""
+    if s < 1:
+        raise ValueError("s must be >= 1")
+    st = init_state(H, G, sorted(groups0), q)
+    obj0 = c0 + 2.0 * st.f
+    trace: List[BlockRecord] = []
+    accepted = iters = 0
+    n_iter = len(follow) if follow is not None else max_iters
+    for it in range(n_iter):
+        take = min(s, len(st.groups), p - len(st.groups))
+        if take == 0:
+            break
+        rem = removal_scores(st, p, q)
+        add = addition_scores(st, H, G, p, q)
+        kept_order = sorted(st.groups, key=lambda g: (rem[g], g))
+        kept_set = set(st.groups)
+        cand_order = sorted((j for j in range(p) if j not in kept_set), key=lambda j: (-add[j], j))
+        own_out, own_in = kept_order[:take], cand_order[:take]
+        if follow is not None:
+            out, inn = list(follow[it][0]), list(follow[it][1])
+            if (len(out) != take or len(inn) != take or len(set(out)) != take or len(set(inn)) != take
+                    or any(g not in kept_set for g in out) or any(j in kept_set for j in inn)):
+                raise ValueError("forced move must take %d distinct kept groups out and %d distinct others in" % (take, take))
+        else:
+            out, inn = own_out, own_in
+        edge_r, edge_a = float(rem[own_out[-1]]), float(add[own_in[-1]])
+        nxt_r = float(rem[kept_order[take]]) if take < len(kept_order) else np.inf
+        nxt_a = float(add[cand_order[take]]) if take < len(cand_order) else -np.inf
+        gap_r = float(abs(nxt_r - edge_r) / max(abs(edge_r), _TINY)) if np.isfinite(nxt_r) else np.inf
+        gap_a = float(abs(edge_a - nxt_a) / max(abs(edge_a), _TINY)) if np.isfinite(nxt_a) else np.inf
+        def_r = float((max(float(rem[g]) for g in out) - edge_r) / max(abs(edge_r), _TINY))
+        def_a = float((edge_a - min(float(add[j]) for j in inn)) / max(abs(edge_a), _TINY))
+        new = st
+        for g in out:
+            new = remove_group(new, new.groups.index(g), q)
+        for j in inn:
+            new = add_group(new, H, G, j, q)
+        obj = c0 + 2.0 * st.f
+        delta = 2.0 * (new.f - st.f)
+        ok = True if (always_accept or follow is not None) else (delta < -rel_tol * obj)
+        iters += 1
+        rec = BlockRecord(list(out), list(inn), float(delta), gap_r, gap_a, def_r, def_a, ok, obj)
+        trace.append(rec)
+        if not ok:
+            break
+        st = new
+        accepted += 1
+        rec.obj_after = c0 + 2.0 * st.f
+    return BlockResult(sorted(st.groups), obj0, c0 + 2.0 * st.f, iters, accepted, trace, st)
+
+
+# --------------------------------------------------------------------------------------------------
 # Nested schedule from the dense layer (Algorithm 1 with S_0 empty and t_i = p_i = t-hat: Section 4.2;
 # Appendix B.1 uses t-hat = 2 for channels and heads, 10 for the intermediate dimension of FFN layers)
 # --------------------------------------------------------------------------------------------------

@@ -302,6 +302,60 @@ def test_always_accept_runs_the_printed_algorithm():
     assert np.isclose(o, res.obj_final, rtol=1e-8)
 
 
+# ---------------------------------------------------------------- block moves (Section 4.2, t-hat = 2 s, p-hat = 0)
+def test_block_search_with_one_pair_is_the_swap_search():
+    X, W, H, G, c0, lam = make_problem(10, 2, 4, 90, 41)
+    K0 = orc.magnitude_support(W, 10, 2, 5)
+    a = orc.local_search(H, G, c0, K0, 10, 2, 30)
+    b = orc.block_search(H, G, c0, K0, 10, 2, 30, 1)
+    assert a.support == b.support and a.iters == b.iters and a.accepted == b.accepted
+    assert [(r.g_out, r.j_in) for r in a.trace] == [(r.out[0], r.inn[0]) for r in b.trace]
+    assert np.allclose([r.delta for r in a.trace], [r.delta for r in b.trace], rtol=1e-9)
+    assert np.isclose(a.obj_final, b.obj_final, rtol=1e-12)
+
+
+@pytest.mark.parametrize("q,s", [(1, 2), (1, 3), (2, 2)])
+def test_block_moves_by_definition(q, s):
+    # every iteration: the sets are the s best of each side by re-solve differences, delta is the re-solve difference of
+    # the whole move, the objective never rises, and the search ends where no block move of its own choice improves
+    p, m, n, k = 11, 4, 100, 5
+    X, W, H, G, c0, lam = make_problem(p, q, m, n, 50 + 3 * q + s)
+    K0 = orc.magnitude_support(W, p, q, k)
+    res = orc.block_search(H, G, c0, K0, p, q, 40, s)
+    K = sorted(K0)
+    for rec in res.trace:
+        take = min(s, len(K), p - len(K))
+        _, objK = orc.solve_support(H, G, c0, K, q)
+        cost = {g: orc.solve_support(H, G, c0, [x for x in K if x != g], q)[1] - objK for g in K}
+        gain = {j: objK - orc.solve_support(H, G, c0, K + [j], q)[1] for j in range(p) if j not in K}
+        assert rec.out == sorted(K, key=lambda g: (cost[g], g))[:take]
+        assert rec.inn == sorted(gain, key=lambda j: (-gain[j], j))[:take]
+        Kn = sorted([g for g in K if g not in rec.out] + rec.inn)
+        _, objn = orc.solve_support(H, G, c0, Kn, q)
+        assert np.isclose(rec.delta, objn - objK, rtol=1e-7, atol=1e-10 * c0)
+        assert rec.deficit_rem == 0.0 and rec.deficit_add == 0.0
+        if rec.accepted:
+            assert rec.delta < 0 and np.isclose(rec.obj_after, objn, rtol=1e-9)
+            K = Kn
+        else:
+            assert rec.delta >= 0
+    assert res.support == K and len(K) == k
+    assert res.accepted == sum(r.accepted for r in res.trace) and res.iters == len(res.trace)
+    assert res.iters == res.accepted + (0 if res.trace[-1].accepted else 1)
+
+
+def test_block_moves_cut_to_what_is_there_and_follow_mode():
+    X, W, H, G, c0, lam = make_problem(8, 1, 3, 60, 57)
+    K0 = [0, 1, 2, 3, 4, 5]                                  # two groups outside: a move of 4 is cut to 2
+    res = orc.block_search(H, G, c0, K0, 8, 1, 3, 4, always_accept=True)
+    assert all(len(r.out) == 2 and len(r.inn) == 2 for r in res.trace)
+    free = orc.block_search(H, G, c0, K0, 8, 1, 5, 2)
+    again = orc.block_search(H, G, c0, K0, 8, 1, 5, 2, follow=[(r.out[::-1], r.inn[::-1]) for r in free.trace if r.accepted])
+    assert again.support == free.support and all(r.deficit_rem == 0.0 and r.deficit_add == 0.0 for r in again.trace)
+    with pytest.raises(ValueError):
+        orc.block_search(H, G, c0, K0, 8, 1, 1, 2, follow=[([0, 6], [7, 1])])
+
+
 # ---------------------------------------------------------------- sequential-pipeline target (Appendix B.1)
 def test_target_form_reduces_to_the_plain_form_and_matches_its_definition():
     rng = np.random.default_rng(31)
