@@ -86,6 +86,8 @@ def main():
                     help="magnitude: the benchmark layer's recipe (magnitude support, then swaps); greedy: the nested "
                          "schedule of Algorithm 1 from the dense layer (t-hat groups pruned per iteration), then swaps")
     ap.add_argument("--t-hat", type=int, default=10)
+    ap.add_argument("--block", type=int, default=1,
+                    help="groups swapped per iteration (t-hat = 2 * block): swaps // block iterations of block moves")
     ap.add_argument("--no-lookahead", action="store_true",
                     help="search without the products computed ahead: every swap then makes one read-only pass over Z")
     ap.add_argument("--rows", type=int, default=None,
@@ -126,7 +128,12 @@ def main():
         ev[2].record()
         obj0 = s.osscar_init_support() if a.init == "magnitude" else s.osscar_init_greedy(a.t_hat)[0]
         ev[3].record()
-        r = s.osscar_local_search(swaps, 0.0, pkg.OSSCAR_SEARCH_NO_LOOKAHEAD if a.no_lookahead else 0, a.refresh_every)
+        fl = pkg.OSSCAR_SEARCH_NO_LOOKAHEAD if a.no_lookahead else 0
+        if a.block > 1:
+            r = s.osscar_block_search(swaps // a.block, a.block, 0.0, fl)
+            r["iters"] = r["iters"] * a.block
+        else:
+            r = s.osscar_local_search(swaps, 0.0, fl, a.refresh_every)
         ev[4].record()
         What, support, obj = s.osscar_backsolve()
         ev[5].record()
@@ -177,7 +184,8 @@ def main():
                                f"(q={cfg.q}), {swaps} swaps, lambda = {cfg.lam_rel}*mean diag",
                    "refresh_every": a.refresh_every,
                    "search": ("delayed-update" + (", no look-ahead" if a.no_lookahead else "")) if lazy else "eager",
-                   "init": a.init if a.init == "magnitude" else f"nested schedule from the dense layer, t_hat = {a.t_hat}"},
+                   "init": a.init if a.init == "magnitude" else f"nested schedule from the dense layer, t_hat = {a.t_hat}",
+                   "groups_per_move": a.block},
         "phases_s": phases,
         "swap_iterations": info["iters"], "accepted_swaps": info["accepted"],
         "swap_evals_per_s": info["iters"] * cfg.p / phases["search"] if phases["search"] > 0 else None,

@@ -157,6 +157,19 @@ osscar_status osscar_local_search(osscar_ctx* ctx, int32_t max_swaps, double rel
                                   int32_t refresh_every, osscar_search_result* res_host, int32_t* trace_out_host,
                                   int32_t* trace_in_host, float* trace_gap_host, double* trace_obj_host);
 
+/* Block moves (Section 4.2 with t-hat = 2 * block, p-hat = 0: s1 = s2 = block).  Each iteration scores every group
+ * at the current state (eq. (impact)), takes the `block` kept groups that are cheapest to remove and the `block`
+ * outside groups with the largest gain (lowest index on ties; cut to min(block, k, p - k)), applies the whole move
+ * by the low-rank updates of Proposition 4.1 and keeps it if obj dropped by more than rel_tol*obj; otherwise the
+ * move is taken back and the search stops.  block = 1 is osscar_local_search's move.  1 <= block <= 64.
+ * flags as for osscar_local_search.  Optional host outputs: trace_out / trace_in, max_iters * block entries each
+ * (iteration i at [i*block, (i+1)*block), cheapest removal / largest gain first, -1 padding); trace_gap[2i],
+ * trace_gap[2i+1] = relative gap between the last group chosen and the first left out on either side;
+ * trace_obj[i] = obj after iteration i.  res->iters counts iterations, res->accepted the moves kept. */
+osscar_status osscar_block_search(osscar_ctx* ctx, int32_t max_iters, int32_t block, double rel_tol, uint32_t flags,
+                                  osscar_search_result* res_host, int32_t* trace_out_host, int32_t* trace_in_host,
+                                  float* trace_gap_host, double* trace_obj_host);
+
 /* Test hook: applies the swap (group g_out leaves, g_in enters) unconditionally (Case 3). */
 osscar_status osscar_apply_swap(osscar_ctx* ctx, int32_t g_out, int32_t g_in);
 

@@ -19,7 +19,7 @@ _STATUS = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "ENOTPD", 4: "EHIP", 5: "ESTATE
 
 EXPORTED_SYMBOLS = ["osscar_workspace_bytes", "osscar_create", "osscar_destroy", "osscar_gram", "osscar_gram_target",
                     "osscar_set_quadratic",
-                    "osscar_init_support", "osscar_init_greedy", "osscar_local_search", "osscar_apply_swap", "osscar_backsolve",
+                    "osscar_init_support", "osscar_init_greedy", "osscar_local_search", "osscar_block_search", "osscar_apply_swap", "osscar_backsolve",
                     "osscar_get_tensor", "osscar_get_scalars", "osscar_get_timers", "osscar_last_error"]
 
 
@@ -68,6 +68,8 @@ def load_library():
     lib.osscar_init_greedy.argtypes = [vp, i32, i32, C.c_uint32, C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(dbl)]
     lib.osscar_local_search.argtypes = [vp, i32, dbl, C.c_uint32, i32, C.POINTER(_SearchResult), C.POINTER(i32),
                                         C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(dbl)]
+    lib.osscar_block_search.argtypes = [vp, i32, i32, dbl, C.c_uint32, C.POINTER(_SearchResult), C.POINTER(i32), C.POINTER(i32),
+                                        C.POINTER(C.c_float), C.POINTER(dbl)]
     lib.osscar_apply_swap.argtypes = [vp, i32, i32]
     lib.osscar_backsolve.argtypes = [vp, vp, i64, i32, C.POINTER(i32), C.POINTER(dbl)]
     lib.osscar_get_tensor.argtypes = [vp, C.c_int, vp, C.c_size_t]
@@ -207,6 +209,23 @@ class Solver:
         return dict(iters=it, accepted=res.accepted, obj_initial=res.obj_initial, obj_final=res.obj_final,
                     trace_out=t_out[:it].copy(), trace_in=t_in[:it].copy(), trace_gap=t_gap[:2 * it].reshape(-1, 2).copy(),
                     trace_obj=t_obj[:it].copy())
+
+    def osscar_block_search(self, max_iters: int, block: int, rel_tol: float = 0.0, flags: int = 0):
+        res = _SearchResult()
+        n = max(max_iters, 1)
+        t_out = np.full(n * block, -1, dtype=np.int32)
+        t_in = np.full(n * block, -1, dtype=np.int32)
+        t_gap = np.zeros(2 * n, dtype=np.float32)
+        t_obj = np.zeros(n, dtype=np.float64)
+        self._check(self.lib.osscar_block_search(
+            self.ctx, max_iters, block, rel_tol, flags, C.byref(res),
+            t_out.ctypes.data_as(C.POINTER(C.c_int32)), t_in.ctypes.data_as(C.POINTER(C.c_int32)),
+            t_gap.ctypes.data_as(C.POINTER(C.c_float)), t_obj.ctypes.data_as(C.POINTER(C.c_double))))
+        it = res.iters
+        moves = [([g for g in t_out[i * block:(i + 1) * block].tolist() if g >= 0],
+                  [g for g in t_in[i * block:(i + 1) * block].tolist() if g >= 0]) for i in range(it)]
+        return dict(iters=it, accepted=res.accepted, obj_initial=res.obj_initial, obj_final=res.obj_final, moves=moves,
+                    trace_gap=t_gap[:2 * it].reshape(it, 2).copy(), trace_obj=t_obj[:it].copy())
 
     def osscar_apply_swap(self, g_out: int, g_in: int):
         self._check(self.lib.osscar_apply_swap(self.ctx, int(g_out), int(g_in)))

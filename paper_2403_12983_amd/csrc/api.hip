@@ -838,6 +838,96 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
   return OSSCAR_OK;
 }
 
+osscar_status osscar_block_search(osscar_ctx* c, int32_t max_iters, int32_t block, double rel_tol, uint32_t flags,
+                                  osscar_search_result* res, int32_t* t_out, int32_t* t_in, float* t_gap, double* t_obj) {
+  osscar_status st = check_ctx(c);
+  if (st != OSSCAR_OK) return st;
+  if (c->phase != osscar_ctx::READY) return fail(c, OSSCAR_ESTATE, "osscar_block_search: call osscar_init_support first");
+  if (max_iters < 0 || block < 1 || block > 64 || rel_tol < 0)
+    return fail(c, OSSCAR_EINVAL, "osscar_block_search: max_iters %d < 0, block %d outside [1, 64] or rel_tol < 0", max_iters, block);
+  hipStream_t s = c->stream;
+  SearchCtrl h{};
+  st = read_ctrl(c, &h);
+  if (st != OSSCAR_OK) return st;
+  const double obj0 = h.obj;
+  h.done = 0; h.iters = 0; h.accepted = 0; h.notpd = 0; h.rel_tol = rel_tol; h.g_out = h.g_in = -1; h.pause = 0; h.tau = 0;
+  HIPCHK(c, hipMemcpyAsync(c->ctrl, &h, sizeof h, hipMemcpyHostToDevice, s));
+  HIPCHK(c, hipStreamSynchronize(s));
+  const bool always = (flags & OSSCAR_SEARCH_ALWAYS_ACCEPT) != 0;
+  const bool use_lazy = (c->q == 1) && !(flags & OSSCAR_SEARCH_EAGER);
+  const int la_mode = (flags & OSSCAR_SEARCH_NO_LOOKAHEAD) ? 2 : 0;
+  const int take = std::min<int>(block, std::min(c->k, c->p - c->k));
+  TabDims d = dims(c);
+  TabPtrs t = ptrs(c);
+  t.trace_out = nullptr; t.trace_in = nullptr; t.trace_gap = nullptr; t.trace_obj = nullptr;   // pairs are recorded on the host
+  const LazyPtrs& L = c->lazy;
+  HIPCHK(c, hipEventRecord(c->ev_a, s));
+  if (use_lazy) HIPCHK(c, launch_lazy_init(d, t, L, s, la_mode));
+  int pending = 0, done_pairs = 0, blocks = 0, accepted = 0;
+  // applies the pairs one after the other (each unconditionally); resumes after a flush when the kernels had to stop
+  auto run_pairs = [&](const std::vector<int32_t>& out, const std::vector<int32_t>& inn) -> osscar_status {
+    size_t idx = 0;
+    while (idx < out.size()) {
+      for (size_t r = idx; r < out.size(); r++) {
+        if (use_lazy) HIPCHK(c, launch_lazy_iteration(d, t, L, 1, s, nullptr, nullptr, out[r], inn[r]));
+        else HIPCHK(c, launch_search_iteration(d, t, out[r], inn[r], 1, s));
+      }
+      osscar_status q = read_ctrl(c, &h);
+      if (q != OSSCAR_OK) return q;
+      if (h.notpd) return fail(c, OSSCAR_ENOTPD, "osscar_block_search: a pivot lost definiteness in move %d", blocks);
+      const int did = h.iters - done_pairs;
+      if (did < 0 || did > (int)(out.size() - idx)) return fail(c, OSSCAR_ESTATE, "internal: osscar_block_search lost count of its pairs");
+      done_pairs += did; idx += did; pending += 2 * did;
+      if (idx < out.size()) {
+        if (!use_lazy || !h.pause) return fail(c, OSSCAR_ESTATE, "internal: osscar_block_search stopped without a reason");
+        HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode));
+        pending = 0;
+      }
+    }
+    return OSSCAR_OK;
+  };
+  std::vector<int32_t> out(take), inn(take);
+  float gaps[2] = {0, 0};
+  while (take > 0 && blocks < max_iters) {
+    if (use_lazy && pending + 2 * take > LAZY_TM) { HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode)); pending = 0; }
+    HIPCHK(c, launch_greedy_pick(d, t, take, c->g_pick, c->g_gap, s, 0));
+    HIPCHK(c, launch_greedy_pick(d, t, take, c->g_pick + 64, c->g_gap + 1, s, 1));
+    HIPCHK(c, hipMemcpyAsync(out.data(), c->g_pick, (size_t)take * 4, hipMemcpyDeviceToHost, s));
+    HIPCHK(c, hipMemcpyAsync(inn.data(), c->g_pick + 64, (size_t)take * 4, hipMemcpyDeviceToHost, s));
+    HIPCHK(c, hipMemcpyAsync(gaps, c->g_gap, 8, hipMemcpyDeviceToHost, s));
+    HIPCHK(c, hipStreamSynchronize(s));
+    const double obj_before = h.obj;
+    st = run_pairs(out, inn);
+    if (st != OSSCAR_OK) return st;
+    const double delta = h.obj - obj_before;
+    const bool ok = always || delta < -rel_tol * obj_before;
+    if (t_out) std::copy(out.begin(), out.end(), t_out + (size_t)blocks * block);
+    if (t_in) std::copy(inn.begin(), inn.end(), t_in + (size_t)blocks * block);
+    if (t_out) std::fill(t_out + (size_t)blocks * block + take, t_out + (size_t)(blocks + 1) * block, -1);
+    if (t_in) std::fill(t_in + (size_t)blocks * block + take, t_in + (size_t)(blocks + 1) * block, -1);
+    if (t_gap) { t_gap[2 * blocks] = gaps[0]; t_gap[2 * blocks + 1] = gaps[1]; }
+    if (t_obj) t_obj[blocks] = ok ? h.obj : obj_before;
+    blocks++;
+    if (!ok) {
+      // take the move back: the same pairs in reverse (the pending pivots must reach the tableau first)
+      if (use_lazy && pending > 0) { HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode)); pending = 0; }
+      std::vector<int32_t> bo(inn.rbegin(), inn.rend()), bi(out.rbegin(), out.rend());
+      st = run_pairs(bo, bi);
+      if (st != OSSCAR_OK) return st;
+      h.obj = obj_before;
+      HIPCHK(c, hipMemcpyAsync(reinterpret_cast<char*>(c->ctrl) + offsetof(SearchCtrl, obj), &h.obj, 8, hipMemcpyHostToDevice, s));
+      break;
+    }
+    accepted++;
+  }
+  if (use_lazy && pending > 0) HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode));
+  HIPCHK(c, hipEventRecord(c->ev_b, s));
+  HIPCHK(c, hipStreamSynchronize(s));
+  c->timers[3] = elapsed(c);
+  if (res) { res->iters = blocks; res->accepted = accepted; res->obj_initial = obj0; res->obj_final = h.obj; }
+  return OSSCAR_OK;
+}
+
 osscar_status osscar_apply_swap(osscar_ctx* c, int32_t g_out, int32_t g_in) {
   osscar_status st = check_ctx(c);
   if (st != OSSCAR_OK) return st;

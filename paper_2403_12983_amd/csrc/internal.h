@@ -104,7 +104,9 @@ hipError_t launch_refresh_scores(const TabDims& d, const TabPtrs& t, hipStream_t
 hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int forced_out, int forced_in, int always_accept,
                                    hipStream_t s, hipEvent_t* ev = nullptr, const int32_t* single = nullptr);
 // pick[0..take) = the kept groups of smallest removal cost (ascending), *gap = relative gap to the next one; take <= 64
-hipError_t launch_greedy_pick(const TabDims& d, const TabPtrs& t, int take, int32_t* pick, float* gap, hipStream_t s);
+// side 1: the groups outside the kept set with the largest addition gain (descending) instead
+hipError_t launch_greedy_pick(const TabDims& d, const TabPtrs& t, int take, int32_t* pick, float* gap, hipStream_t s,
+                              int side = 0);
 hipError_t launch_select(const TabDims& d, const TabPtrs& t, int forced_out, int forced_in, hipStream_t s);
 
 // ----------------------------------------------------------------------------------------------
@@ -146,7 +148,9 @@ hipError_t launch_lazy_init(const TabDims& d, const TabPtrs& t, const LazyPtrs& 
 // ev (optional): events recorded before and after the pass over Z0, and at the end of the iteration
 // single (optional, device): removal of the one row *single instead of a swap; adds one pending pivot instead of two
 hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, int always_accept, hipStream_t s,
-                                 hipEvent_t* ev = nullptr, const int32_t* single = nullptr);
+                                 hipEvent_t* ev = nullptr, const int32_t* single = nullptr, int forced_out = -1,
+                                 int forced_in = -1);
+// forced_out / forced_in >= 0: that pair instead of the kernel's own selection
 hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode = 0);
 
 hipError_t launch_scatter_rows(const float* src, int64_t lds, const int32_t* rows, int nrows, int ncols, void* dst,

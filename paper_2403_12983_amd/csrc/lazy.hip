@@ -85,7 +85,8 @@ __global__ __launch_bounds__(64) void lazy_partials_kernel(LazyPtrs L, int p, co
 // ---------------------------------------------------------------------------------------------- prep
 // single != nullptr: removal of the one row *single (Case 1 alone, nothing enters): the second pivot's quantities are zero.
 __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float* __restrict__ N0, int d1, int nrec,
-                                                         SearchCtrl* ctrl, const int32_t* __restrict__ single) {
+                                                         const int32_t* __restrict__ kept, SearchCtrl* ctrl, const int32_t* __restrict__ single, int forced_g,
+                                                         int forced_j) {
   __shared__ double s_mn1[256], s_mn2[256], s_mx1[256], s_mx2[256];
   __shared__ int s_imn[256], s_imx[256];
   __shared__ double bg[LAZY_TM], bj[LAZY_TM], red[3][4];
@@ -108,8 +109,13 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
     }
     __syncthreads();
   }
-  const int g = single ? *single : s_imn[0], j = single ? g : s_imx[0], tau = ctrl->tau;
-  if (g < 0 || j < 0) { if (tid == 0) { ctrl->done = 1; ctrl->g_out = -1; ctrl->g_in = -1; } return; }
+  const int g = single ? *single : (forced_g >= 0 ? forced_g : s_imn[0]);
+  const int j = single ? g : (forced_g >= 0 ? forced_j : s_imx[0]);
+  const int tau = ctrl->tau;
+  if (g < 0 || j < 0 || (forced_g >= 0 && (!kept[g] || kept[j]))) {
+    if (tid == 0) { ctrl->done = 1; ctrl->g_out = -1; ctrl->g_in = -1; }
+    return;
+  }
   const int sg0 = L.cslot[g], sj0 = L.cslot[j];
   const int need = (sg0 < 0 ? 1 : 0) + ((!single && sj0 < 0) ? 1 : 0);
   if (L.pos[g] >= 0 || L.pos[j] >= 0 || tau + (single ? 1 : 2) > LAZY_TM || L.misc[MI_SPARE] + need > LAZY_NS) {
@@ -522,9 +528,9 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
 }
 
 hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, int always_accept, hipStream_t s,
-                                 hipEvent_t* ev, const int32_t* single) {
+                                 hipEvent_t* ev, const int32_t* single, int forced_out, int forced_in) {
   const int rb = (d.d1 + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, cb = (d.m + COLS_PER_BLOCK - 1) / COLS_PER_BLOCK;
-  hipLaunchKernelGGL(lazy_prep_kernel, dim3(1), dim3(256), 0, s, L, t.N, d.d1, rb, t.ctrl, single);
+  hipLaunchKernelGGL(lazy_prep_kernel, dim3(1), dim3(256), 0, s, L, t.N, d.d1, rb, t.kept, t.ctrl, single, forced_out, forced_in);
   hipLaunchKernelGGL(lazy_vectors_kernel, dim3(rb + cb), dim3(256), 0, s, L, t.N, t.Z, d.d1, d.m, rb, t.ctrl);
   const int gb = (d.d1 + GEMV_ROWS - 1) / GEMV_ROWS + LAZY_TM;
   if (ev) hipEventRecord(ev[0], s);

@@ -789,10 +789,11 @@ __global__ __launch_bounds__(256) void update_Z_kernel(TabDims d, float* __restr
 // The `take` kept groups with the smallest removal cost (ascending cost, lowest index on ties) -> pick[0..take), and
 // the relative gap between the costliest of them and the cheapest kept group left out -> *gap (inf if none is left).
 // One workgroup; take <= 64.
+// side 1: the same for the groups outside the kept set with the LARGEST addition gain (descending gain).
 __global__ __launch_bounds__(1024) void greedy_pick_kernel(TabDims d, const int32_t* __restrict__ kept,
                                                             const double* __restrict__ score, int take,
                                                             int32_t* __restrict__ pick, float* __restrict__ gap,
-                                                            const SearchCtrl* __restrict__ ctrl) {
+                                                            const SearchCtrl* __restrict__ ctrl, int side) {
   __shared__ double s_v[1024];
   __shared__ int s_i[1024];
   __shared__ int chosen[65];
@@ -803,11 +804,11 @@ __global__ __launch_bounds__(1024) void greedy_pick_kernel(TabDims d, const int3
     double best = INFINITY;
     int ib = -1;
     for (int h = tid; h < d.p; h += 1024) {
-      if (!kept[h]) continue;
+      if ((kept[h] != 0) != (side == 0)) continue;
       bool used = false;
       for (int c = 0; c < round; c++) used |= (chosen[c] == h);
       if (used) continue;
-      const double v = score[h];
+      const double v = side ? -score[h] : score[h];
       if (ib < 0 || v < best) { best = v; ib = h; }        // ascending h per thread: strict comparison keeps the lowest index
     }
     s_v[tid] = best; s_i[tid] = ib;
@@ -830,9 +831,9 @@ __global__ __launch_bounds__(1024) void greedy_pick_kernel(TabDims d, const int3
   }
 }
 
-hipError_t launch_greedy_pick(const TabDims& d, const TabPtrs& t, int take, int32_t* pick, float* gap, hipStream_t s) {
+hipError_t launch_greedy_pick(const TabDims& d, const TabPtrs& t, int take, int32_t* pick, float* gap, hipStream_t s, int side) {
   if (take < 1 || take > 64) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(greedy_pick_kernel, dim3(1), dim3(1024), 0, s, d, t.kept, t.score, take, pick, gap, t.ctrl);
+  hipLaunchKernelGGL(greedy_pick_kernel, dim3(1), dim3(1024), 0, s, d, t.kept, t.score, take, pick, gap, t.ctrl, side);
   return hipGetLastError();
 }
 

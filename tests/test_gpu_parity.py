@@ -429,6 +429,86 @@ def test_greedy_refresh_and_edges():
     s.close()
 
 
+# ------------------------------------------------------------------------------------------ block moves
+def check_blocks(c, block, r, always=False):
+    """The oracle replays the library's moves: every set within GAP of the oracle's own choice, exact deltas negative for
+    the moves kept, the tracked objective following, and the move that ended the search not improving."""
+    cfg = c.cfg
+    kept_moves = r["moves"][: r["accepted"]]
+    fol = orc.block_search(c.H, c.G, c.c0, c.K0, cfg.p, cfg.q, len(kept_moves), block, follow=kept_moves)
+    for i, x in enumerate(fol.trace):
+        assert x.deficit_rem <= GAP and x.deficit_add <= GAP, (i, x)
+        if not always:
+            assert x.delta < 0, (i, x)
+        assert abs(r["trace_obj"][i] - x.obj_after) <= 1e-5 * abs(x.obj_after), (i, r["trace_obj"][i], x.obj_after)
+        for gg, go in ((r["trace_gap"][i][0], x.gap_rem), (r["trace_gap"][i][1], x.gap_add)):
+            if np.isfinite(go) and go > 1e-3:
+                assert abs(gg - go) <= 1e-2 * go
+    if r["iters"] > r["accepted"]:
+        out, inn = r["moves"][-1]
+        last = orc.block_search(c.H, c.G, c.c0, fol.support, cfg.p, cfg.q, 1, block, follow=[(out, inn)])
+        x = last.trace[0]
+        assert x.deficit_rem <= GAP and x.deficit_add <= GAP and x.delta >= -1e-7 * fol.obj_final, x
+        assert abs(r["trace_obj"][-1] - fol.obj_final) <= 1e-5 * fol.obj_final          # taken back
+    assert abs(r["obj_final"] - fol.obj_final) <= 1e-5 * fol.obj_final
+    return fol
+
+
+@pytest.mark.parametrize("name,block", [("cfg1", 2), ("cfg1", 5), ("cfg1x", 3), ("cfg2s", 2), ("cfg3s", 4), ("cfg3s", 40), ("cfg4s", 2),
+                                        ("cfg5odd", 8)])
+def test_block_search_follows_the_oracle(name, block):
+    c = case(name)
+    cfg = c.cfg
+    s = c.solver()
+    c.gram(s)
+    s.osscar_init_support()
+    iters = max(2, min(12, cfg.swaps // block))
+    r = s.osscar_block_search(iters, block)
+    take = min(block, cfg.k, cfg.p - cfg.k)
+    assert all(len(o) == take and len(i) == take for o, i in r["moves"])
+    fol = check_blocks(c, block, r)
+    assert T(s, "T_KEPT").astype(int).tolist() == fol.support
+    st = orc.init_state(c.H, c.G, fol.support, cfg.q)
+    dp = np.sqrt(np.diag(st.P))
+    assert np.max(np.abs(T(s, "T_P") - st.P) / np.outer(dp, dp)) < 5e-5
+    assert rel(T(s, "T_B"), st.What_K) < 5e-5
+    What, support, obj = s.osscar_backsolve()
+    Wo, objo = orc.solve_support(c.H, c.G, c.c0, fol.support, cfg.q)
+    assert support.tolist() == fol.support
+    assert rel(What.cpu().double().numpy(), Wo) < 1e-4 and abs(obj - objo) <= 1e-4 * objo
+    s.close()
+
+
+def test_block_search_variants_agree():
+    # single-row groups: delayed updates, in-place updates and no look-ahead make the same moves; every move applied
+    c = case("cfg3s")
+    pkg = _pkg()
+    s = c.solver()
+    c.gram(s)
+    runs = []
+    for fl in (0, pkg.OSSCAR_SEARCH_EAGER, pkg.OSSCAR_SEARCH_NO_LOOKAHEAD):
+        s.osscar_init_support()
+        runs.append(s.osscar_block_search(6, 20, 0.0, fl | pkg.OSSCAR_SEARCH_ALWAYS_ACCEPT))
+    for r in runs:
+        assert r["iters"] == r["accepted"] == 6
+    check_blocks(c, 20, runs[0], always=True)
+    for r in runs[1:]:
+        for i in range(6):
+            if r["moves"][i] != runs[0]["moves"][i]:
+                assert min(runs[0]["trace_gap"][i]) < 1e-4
+                break
+        else:
+            assert abs(r["obj_final"] - runs[0]["obj_final"]) <= 1e-5 * abs(r["obj_final"])
+    from paper_2403_12983_amd.binding import OsscarError
+    with pytest.raises(OsscarError) as e:
+        s.osscar_block_search(3, 0)
+    assert e.value.status == 1
+    with pytest.raises(OsscarError) as e:
+        s.osscar_block_search(3, 65)
+    assert e.value.status == 1
+    s.close()
+
+
 # ------------------------------------------------------------------------------------------ sequential-pipeline target
 def target_of(c):
     """Dense model's output for the same rows: Y = Xhat W with Xhat a perturbed copy of X, rounded to the input dtype."""
