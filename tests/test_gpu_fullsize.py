@@ -180,6 +180,38 @@ def test_greedy_from_dense_cfg3_width():
     s.close()
 
 
+@pytest.mark.parametrize("name,block,iters", [("cfg2", 4, 25), ("cfg4", 2, 6)])
+def test_block_moves_whole_layer(name, block, iters):
+    """Block moves (t-hat = 2 * block) on the conv-shaped and the head-shaped layer, every move against the oracle."""
+    cfg = inp.CONFIGS[name]
+    X = gen_on_gpu(cfg)
+    W = inp.gen_W(cfg, DEV)
+    Xd, Wd = X.cpu().double().numpy(), W.cpu().double().numpy()
+    H, G, c0, lam = orc.gram(Xd, Wd, cfg.lam_abs, cfg.lam_rel)
+    del Xd
+    s = make_solver(cfg, X, W)
+    s.osscar_gram(X, True, W, cfg.lam_abs, cfg.lam_rel)
+    s.osscar_init_support()
+    K0 = orc.magnitude_support(Wd, cfg.p, cfg.q, cfg.k)
+    r = s.osscar_block_search(iters, block)
+    kept_moves = r["moves"][: r["accepted"]]
+    fol = orc.block_search(H, G, c0, K0, cfg.p, cfg.q, len(kept_moves), block, follow=kept_moves)
+    for i, x in enumerate(fol.trace):
+        assert x.deficit_rem <= GAP and x.deficit_add <= GAP and x.delta < 0, (i, x)
+        assert abs(r["trace_obj"][i] - x.obj_after) <= 1e-5 * abs(x.obj_after)
+    if r["iters"] > r["accepted"]:
+        out, inn = r["moves"][-1]
+        x = orc.block_search(H, G, c0, fol.support, cfg.p, cfg.q, 1, block, follow=[(out, inn)]).trace[0]
+        assert x.deficit_rem <= GAP and x.deficit_add <= GAP and x.delta >= -1e-7 * fol.obj_final
+    What, support, obj = s.osscar_backsolve()
+    assert support.tolist() == fol.support
+    Wo, objo = orc.solve_support(H, G, c0, fol.support, cfg.q)
+    assert rel(What.cpu().double().numpy(), Wo) < 1e-4 and abs(obj - objo) <= 1e-4 * objo
+    print(f"{name}: block {block}: {r['accepted']} of {r['iters']} moves kept, obj {r['obj_initial']:.6g} -> {obj:.6g}, "
+          f"search timer {s.osscar_get_timers()[3]:.1f} ms")
+    s.close()
+
+
 def test_cfg5_target_gram_sampled():
     """Cross-Gram of the benchmark layer's shape (32768 calibration rows) on sampled rows of G, float64 on the device."""
     import time
