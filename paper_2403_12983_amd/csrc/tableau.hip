@@ -323,6 +323,45 @@ __global__ __launch_bounds__(256) void gram_dblk_kernel(TabDims d, const float* 
   }
 }
 
+// gram[h] = Z_h Z_h^T for every group: 16 x 16 outputs per workgroup (lower blocks only, mirrored), Z tiles of 64 columns in LDS
+__global__ __launch_bounds__(256) void group_gram_kernel(TabDims d, const float* __restrict__ Z, double* __restrict__ gram,
+                                                          const SearchCtrl* __restrict__ ctrl) {
+  __shared__ float zr[16][65], zc[16][65];
+  if (ctrl && ctrl->done) return;
+  const int q = d.q, m = d.m, h = blockIdx.x, nb = (q + 15) / 16;
+  int br = 0, bc = blockIdx.y;                      // linear index over the lower block triangle
+  while (bc > br) { bc -= br + 1; br++; }
+  if (br >= nb) return;
+  const int tr = threadIdx.x >> 4, tc = threadIdx.x & 15;
+  const int r = br * 16 + tr, c = bc * 16 + tc;
+  const float* Zh = Z + (int64_t)h * q * m;
+  double acc = 0;
+  for (int c0 = 0; c0 < m; c0 += 64) {
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < 16 * 64; idx += 256) {
+      const int rr = idx >> 6, cc = idx & 63;
+      const bool okc = c0 + cc < m;
+      zr[rr][cc] = (okc && br * 16 + rr < q) ? Zh[(int64_t)(br * 16 + rr) * m + c0 + cc] : 0.f;
+      zc[rr][cc] = (okc && bc * 16 + rr < q) ? Zh[(int64_t)(bc * 16 + rr) * m + c0 + cc] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll 16
+    for (int k = 0; k < 64; k++) acc += (double)zr[tr][k] * (double)zc[tc][k];
+  }
+  if (r < q && c < q) {
+    gram[(int64_t)h * q * q + r * q + c] = acc;
+    gram[(int64_t)h * q * q + c * q + r] = acc;
+  }
+}
+
+__global__ __launch_bounds__(256) void dblk_copy_kernel(TabDims d, const float* __restrict__ N, double* __restrict__ dblk) {
+  const int h = blockIdx.x, q = d.q;
+  for (int idx = threadIdx.x; idx < q * q; idx += 256) {
+    int r = idx / q, c = idx % q;
+    dblk[(int64_t)h * q * q + idx] = (double)nsym(N, d.d1, h * q + r, h * q + c);
+  }
+}
+
 // score[h] = Tr(gram_h * (sigma * dblk_h)^-1), sigma = -1 for kept groups (N_hh = -P_hh), +1 otherwise.
 // One workgroup of 64 threads per group; Cholesky in shared memory, then one column solve per thread.
 __global__ __launch_bounds__(64) void score_kernel(TabDims d, const int32_t* __restrict__ kept,
@@ -377,7 +416,13 @@ __global__ __launch_bounds__(64) void score_kernel(TabDims d, const int32_t* __r
 }
 
 hipError_t launch_refresh_scores(const TabDims& d, const TabPtrs& t, hipStream_t s) {
-  hipLaunchKernelGGL(gram_dblk_kernel, dim3(d.p), dim3(256), 0, s, d, t.N, t.Z, t.gram, t.dblk);
+  if (d.q == 1) {
+    hipLaunchKernelGGL(gram_dblk_kernel, dim3(d.p), dim3(256), 0, s, d, t.N, t.Z, t.gram, t.dblk);
+  } else {
+    const int nb = (d.q + 15) / 16;
+    hipLaunchKernelGGL(group_gram_kernel, dim3(d.p, nb * (nb + 1) / 2), dim3(256), 0, s, d, t.Z, t.gram, (const SearchCtrl*)nullptr);
+    hipLaunchKernelGGL(dblk_copy_kernel, dim3(d.p), dim3(256), 0, s, d, t.N, t.dblk);
+  }
   hipLaunchKernelGGL(score_kernel, dim3(d.p), dim3(64), (size_t)2 * d.q * d.q * 8, s, d, t.kept, t.gram, t.dblk, t.score,
                      t.ctrl);
   return hipGetLastError();
@@ -464,18 +509,16 @@ __global__ __launch_bounds__(256) void extract_pair_kernel(TabDims d, const floa
   }
 }
 
-// q x q algebra of the pair, the exact change of the objective, the acceptance test and the trace.
+// q x q algebra of the pair (the exact change of the objective and the acceptance test follow in pair_cols_kernel and
+// pair_accept_kernel).
 // small layout (doubles, each q*q): [0] Dg, [1] Njg, [2] M1 = Dg Ngj, [3] Dj' , [4] W2Dj = -M1 Dj', [5] scratch
 __global__ __launch_bounds__(256) void pair_small_kernel(TabDims d, const float* __restrict__ C1, const float* __restrict__ C2,
-                                                          float* __restrict__ Zg, float* __restrict__ Zj, double* __restrict__ small,
-                                                          SearchCtrl* ctrl, int always_accept, int32_t* trace_out,
-                                                          int32_t* trace_in, float* trace_gap, double* trace_obj,
+                                                          double* __restrict__ small, SearchCtrl* ctrl,
                                                           const int32_t* __restrict__ single) {
   __shared__ double colbuf[64];
-  __shared__ double red[4];
   __shared__ int32_t bad;
   if (ctrl->done) return;
-  const int q = d.q, qq = q * q, m = d.m, tid = threadIdx.x;
+  const int q = d.q, qq = q * q, tid = threadIdx.x;
   const int g0 = (single ? *single : ctrl->g_out) * q, j0 = (single ? *single : ctrl->g_in) * q;
   double* Dg = small; double* Njg = small + qq; double* M1 = small + 2 * qq; double* Dj = small + 3 * qq;
   double* W2Dj = small + 4 * qq;
@@ -516,42 +559,67 @@ __global__ __launch_bounds__(256) void pair_small_kernel(TabDims d, const float*
   }
   __syncthreads();
   }
-  // rZ1 = Dg Zg ; Z'j = Zj - Njg rZ1 ; rZ2 = Dj' Z'j ; delta = -<Zg, rZ1> - <Z'j, rZ2>   (column by column)
+  if (tid == 0) { ctrl->delta = 0.0; if (bad) ctrl->notpd = 1; }
+}
+
+// Column phase of the pair: rZ1 = Dg Zg ; Z'j = Zj - Njg rZ1 ; rZ2 = Dj' Z'j (both written in place of Zg, Zj) and
+// delta = -<Zg, rZ1> - <Z'j, rZ2>, added up in ctrl->delta.  16 columns x 16 row slots per workgroup; the three q x q
+// matrices and the column tiles live in LDS.
+constexpr int PC_COLS = 16;
+__global__ __launch_bounds__(256) void pair_cols_kernel(TabDims d, float* __restrict__ Zg, float* __restrict__ Zj,
+                                                         const double* __restrict__ small, SearchCtrl* ctrl) {
+  extern __shared__ double pcs[];   // Dg, Njg, Dj (q*q each), ta, tb (q*16 each)
+  __shared__ double red[4];
+  if (ctrl->done) return;
+  const int q = d.q, qq = q * q, m = d.m, tid = threadIdx.x;
+  double* Dg = pcs; double* Njg = pcs + qq; double* Dj = pcs + 2 * qq; double* ta = pcs + 3 * qq; double* tb = ta + q * PC_COLS;
+  for (int idx = tid; idx < qq; idx += 256) { Dg[idx] = small[idx]; Njg[idx] = small[qq + idx]; Dj[idx] = small[3 * qq + idx]; }
+  const int c = tid & 15, slot = tid >> 4, col = blockIdx.x * PC_COLS + c;
+  const bool live = col < m;
+  for (int r = slot; r < q; r += 16) ta[r * PC_COLS + c] = live ? (double)Zg[(int64_t)r * m + col] : 0.0;
+  __syncthreads();
   double part = 0;
-  for (int col = tid; col < m; col += 256) {
-    double zg[64], t1[64];
-    for (int r = 0; r < q; r++) zg[r] = (double)Zg[(int64_t)r * m + col];
-    for (int r = 0; r < q; r++) { double v = 0; for (int k = 0; k < q; k++) v += Dg[r * q + k] * zg[k]; t1[r] = v; part -= zg[r] * v; }
-    for (int r = 0; r < q; r++) {                          // zg := Z'j
-      double v = (double)Zj[(int64_t)r * m + col];
-      for (int k = 0; k < q; k++) v -= Njg[r * q + k] * t1[k];
-      zg[r] = v;
-    }
-    for (int r = 0; r < q; r++) Zg[(int64_t)r * m + col] = (float)t1[r];     // rZ1 in place
-    for (int r = 0; r < q; r++) {
-      double v = 0;
-      for (int k = 0; k < q; k++) v += Dj[r * q + k] * zg[k];
-      part -= zg[r] * v;
-      Zj[(int64_t)r * m + col] = (float)v;                                    // rZ2 in place
-    }
+  for (int r = slot; r < q; r += 16) {                       // tb = Dg zg
+    double v = 0;
+    for (int k = 0; k < q; k++) v += Dg[r * q + k] * ta[k * PC_COLS + c];
+    tb[r * PC_COLS + c] = v;
+    part -= ta[r * PC_COLS + c] * v;
+  }
+  __syncthreads();
+  for (int r = slot; r < q; r += 16) {                       // ta = z'j = zj - Njg tb ; rZ1 out
+    double v = live ? (double)Zj[(int64_t)r * m + col] : 0.0;
+    for (int k = 0; k < q; k++) v -= Njg[r * q + k] * tb[k * PC_COLS + c];
+    ta[r * PC_COLS + c] = v;
+    if (live) Zg[(int64_t)r * m + col] = (float)tb[r * PC_COLS + c];
+  }
+  __syncthreads();
+  for (int r = slot; r < q; r += 16) {                       // rZ2 = Dj' z'j
+    double v = 0;
+    for (int k = 0; k < q; k++) v += Dj[r * q + k] * ta[k * PC_COLS + c];
+    part -= ta[r * PC_COLS + c] * v;
+    if (live) Zj[(int64_t)r * m + col] = (float)v;
   }
   part = wave_sum(part);
   if ((tid & 63) == 0) red[tid >> 6] = part;
   __syncthreads();
-  if (tid == 0) {
-    double delta = red[0] + red[1] + red[2] + red[3];
-    ctrl->delta = delta;
-    if (bad) ctrl->notpd = 1;
-    int it = ctrl->iters;
-    bool ok = !bad && (always_accept || delta < -ctrl->rel_tol * ctrl->obj);
-    ctrl->iters = it + 1;
-    if (single) { ctrl->g_out = *single; ctrl->g_in = -1; }
-    if (ok) { ctrl->obj += delta; ctrl->accepted += 1; } else { ctrl->done = 1; }
-    if (trace_out) trace_out[it] = ctrl->g_out;
-    if (trace_in) trace_in[it] = ctrl->g_in;
-    if (trace_gap) { trace_gap[2 * it] = (float)ctrl->gap_rem; trace_gap[2 * it + 1] = (float)ctrl->gap_add; }
-    if (trace_obj) trace_obj[it] = ctrl->obj;
-  }
+  if (tid == 0) unsafeAtomicAdd(&ctrl->delta, red[0] + red[1] + red[2] + red[3]);
+}
+
+// the acceptance test and the trace
+__global__ void pair_accept_kernel(SearchCtrl* ctrl, int always_accept, int32_t* trace_out, int32_t* trace_in, float* trace_gap,
+                                   double* trace_obj, const int32_t* __restrict__ single) {
+  if (ctrl->done) return;
+  const double delta = ctrl->delta;
+  const int it = ctrl->iters;
+  const bool bad = ctrl->notpd != 0;
+  const bool ok = !bad && (always_accept || delta < -ctrl->rel_tol * ctrl->obj);
+  ctrl->iters = it + 1;
+  if (single) { ctrl->g_out = *single; ctrl->g_in = -1; }
+  if (ok) { ctrl->obj += delta; ctrl->accepted += 1; } else { ctrl->done = 1; }
+  if (trace_out) trace_out[it] = ctrl->g_out;
+  if (trace_in) trace_in[it] = ctrl->g_in;
+  if (trace_gap) { trace_gap[2 * it] = (float)ctrl->gap_rem; trace_gap[2 * it + 1] = (float)ctrl->gap_add; }
+  if (trace_obj) trace_obj[it] = ctrl->obj;
 }
 
 // bulk panels: P1 = C1, P2 = C2 - C1 M1, P1D = P1 Dg, P2D = P2 Dj', with the rows of both pivots zeroed;
@@ -623,18 +691,6 @@ __global__ __launch_bounds__(256) void pair_fix_kernel(TabDims d, float* __restr
         if (single) continue;
         if (l < jr) N[(int64_t)jr * ld + l] = vj; else N[(int64_t)l * ld + jr] = vj;
       }
-      // float64 diagonal block of l's group (one thread per group: the one owning its first row)
-      if (l % q == 0) {
-        int h = l / q;
-        for (int r = 0; r < q; r++)
-          for (int c = 0; c < q; c++) {
-            double v = 0;
-            for (int k = 0; k < q; k++)
-              v += (double)P1D[(int64_t)(l + r) * q + k] * (double)P1[(int64_t)(l + c) * q + k] +
-                   (double)P2D[(int64_t)(l + r) * q + k] * (double)P2[(int64_t)(l + c) * q + k];
-            dblk[(int64_t)h * qq + r * q + c] -= v;
-          }
-      }
     }
   }
   // pivot-pivot blocks and flags: first workgroup
@@ -663,6 +719,28 @@ __global__ __launch_bounds__(256) void pair_fix_kernel(TabDims d, float* __restr
     for (int c = 0; c < q; c++) vg += M1[r * q + c] * (double)rZ2[(int64_t)c * m + col];
     Z[(int64_t)(g0 + r) * m + col] = (float)vg;
     if (!single) Z[(int64_t)(j0 + r) * m + col] = rZ2[idx];
+  }
+}
+
+// float64 diagonal blocks of the groups outside the pivots: dblk[h] -= P1D_h P1_h^T + P2D_h P2_h^T.  One workgroup per group.
+__global__ __launch_bounds__(256) void pair_dblk_kernel(TabDims d, const float* __restrict__ P1, const float* __restrict__ P2,
+                                                         const float* __restrict__ P1D, const float* __restrict__ P2D,
+                                                         const SearchCtrl* __restrict__ ctrl, double* __restrict__ dblk,
+                                                         const int32_t* __restrict__ single) {
+  extern __shared__ float pds[];   // the four q x q panels of this group
+  if (ctrl->done) return;
+  const int q = d.q, qq = q * q, h = blockIdx.x;
+  const int g = single ? *single : ctrl->g_out, j = single ? g : ctrl->g_in;
+  if (h == g || h == j) return;    // pivot groups get their blocks in pair_fix_kernel
+  float* a1 = pds; float* b1 = pds + qq; float* a2 = pds + 2 * qq; float* b2 = pds + 3 * qq;
+  const int64_t base = (int64_t)h * qq;
+  for (int idx = threadIdx.x; idx < qq; idx += 256) { a1[idx] = P1D[base + idx]; b1[idx] = P1[base + idx]; a2[idx] = P2D[base + idx]; b2[idx] = P2[base + idx]; }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < qq; idx += 256) {
+    const int r = idx / q, c = idx % q;
+    double v = 0;
+    for (int k = 0; k < q; k++) v += (double)a1[r * q + k] * (double)b1[c * q + k] + (double)a2[r * q + k] * (double)b2[c * q + k];
+    dblk[base + idx] -= v;
   }
 }
 
@@ -837,6 +915,21 @@ hipError_t launch_greedy_pick(const TabDims& d, const TabPtrs& t, int take, int3
   return hipGetLastError();
 }
 
+// Z[i][:] -= sum_c P1[i][c] rZ1[c][:] + P2[i][c] rZ2[c][:] for groups of more than one row: one row x 256 columns per
+// workgroup (the row's 2q coefficients are uniform loads); the group Grams follow in group_gram_kernel.
+__global__ __launch_bounds__(256) void update_Z_rows_kernel(TabDims d, float* __restrict__ Z, const float* __restrict__ P1,
+                                                             const float* __restrict__ P2, const float* __restrict__ rZ1,
+                                                             const float* __restrict__ rZ2, const SearchCtrl* __restrict__ ctrl) {
+  if (ctrl->done) return;
+  const int q = d.q, m = d.m, i = blockIdx.x, col = blockIdx.y * 256 + threadIdx.x;
+  if (col >= m) return;
+  const float* p1 = P1 + (int64_t)i * q;
+  const float* p2 = P2 + (int64_t)i * q;
+  float acc = 0.f;
+  for (int c = 0; c < q; c++) acc += p1[c] * rZ1[(int64_t)c * m + col] + p2[c] * rZ2[(int64_t)c * m + col];
+  Z[(int64_t)i * m + col] -= acc;
+}
+
 hipError_t launch_select(const TabDims& d, const TabPtrs& t, int forced_out, int forced_in, hipStream_t s) {
   hipLaunchKernelGGL(select_kernel, dim3(1), dim3(1024), 0, s, d, t.kept, t.score, t.ctrl, forced_out, forced_in);
   return hipGetLastError();
@@ -846,10 +939,18 @@ hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int force
                                    hipStream_t s, hipEvent_t* ev, const int32_t* single) {
   const int q = d.q;
   const int rb = (d.d1 + 255) / 256;
+  const size_t pc_lds = (size_t)(3 * q * q + 2 * q * PC_COLS) * 8;
+  if (pc_lds > 65536) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(pair_cols_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)pc_lds);
+    if (e != hipSuccess) return e;
+  }
   if (!single) hipLaunchKernelGGL(select_kernel, dim3(1), dim3(1024), 0, s, d, t.kept, t.score, t.ctrl, forced_out, forced_in);
   hipLaunchKernelGGL(extract_pair_kernel, dim3(rb), dim3(256), 0, s, d, t.N, t.Z, t.ctrl, t.C1, t.C2, t.rZ1, t.rZ2, single);
-  hipLaunchKernelGGL(pair_small_kernel, dim3(1), dim3(256), 0, s, d, t.C1, t.C2, t.rZ1, t.rZ2, t.small, t.ctrl, always_accept,
-                     t.trace_out, t.trace_in, t.trace_gap, t.trace_obj, single);
+  hipLaunchKernelGGL(pair_small_kernel, dim3(1), dim3(256), 0, s, d, t.C1, t.C2, t.small, t.ctrl, single);
+  hipLaunchKernelGGL(pair_cols_kernel, dim3((d.m + PC_COLS - 1) / PC_COLS), dim3(256), pc_lds, s, d,
+                     t.rZ1, t.rZ2, t.small, t.ctrl);
+  hipLaunchKernelGGL(pair_accept_kernel, dim3(1), dim3(1), 0, s, t.ctrl, always_accept, t.trace_out, t.trace_in, t.trace_gap,
+                     t.trace_obj, single);
   // bulk panels go to C1D/C2D (times D) and to two further panels stored behind them
   float* P1 = t.C1D + (int64_t)2 * d.d1 * q;
   float* P2 = P1 + (int64_t)d.d1 * q;
@@ -859,6 +960,7 @@ hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int force
                      P1D, P2D, single);
   hipLaunchKernelGGL(pair_fix_kernel, dim3(rb), dim3(256), 0, s, d, t.N, t.Z, P1, P2, P1D, P2D, t.rZ1, t.rZ2, t.small, t.ctrl,
                      t.dblk, t.kept, single);
+  hipLaunchKernelGGL(pair_dblk_kernel, dim3(d.p), dim3(256), (size_t)4 * q * q * 4, s, d, P1, P2, P1D, P2D, t.ctrl, t.dblk, single);
   if (ev) hipEventRecord(ev[0], s);
   if (q == 1) {
     dim3 grid((d.d1 + 1023) / 1024, (d.d1 + 31) / 32);
@@ -868,7 +970,13 @@ hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int force
     hipLaunchKernelGGL(update_N_kernel, dim3(tiles, tiles), dim3(256), 0, s, d, t.N, P1, P2, P1D, P2D, t.ctrl);
   }
   if (ev) hipEventRecord(ev[1], s);
-  hipLaunchKernelGGL(update_Z_kernel, dim3(d.p), dim3(256), 0, s, d, t.Z, P1, P2, t.rZ1, t.rZ2, t.gram, t.ctrl);
+  if (q == 1) {
+    hipLaunchKernelGGL(update_Z_kernel, dim3(d.p), dim3(256), 0, s, d, t.Z, P1, P2, t.rZ1, t.rZ2, t.gram, t.ctrl);
+  } else {
+    const int nb = (q + 15) / 16;
+    hipLaunchKernelGGL(update_Z_rows_kernel, dim3(d.d1, (d.m + 255) / 256), dim3(256), 0, s, d, t.Z, P1, P2, t.rZ1, t.rZ2, t.ctrl);
+    hipLaunchKernelGGL(group_gram_kernel, dim3(d.p, nb * (nb + 1) / 2), dim3(256), 0, s, d, t.Z, t.gram, t.ctrl);
+  }
   if (ev) hipEventRecord(ev[2], s);
   hipLaunchKernelGGL(score_kernel, dim3(d.p), dim3(64), (size_t)2 * q * q * 8, s, d, t.kept, t.gram, t.dblk, t.score, t.ctrl);
   return hipGetLastError();
