@@ -86,6 +86,30 @@ def objective_target(X: np.ndarray, Y: np.ndarray, W: np.ndarray, What: np.ndarr
     return float(np.sum((np.asarray(Y, dtype=np.float64) - X @ What) ** 2) + lam * np.sum((np.asarray(W, dtype=np.float64) - What) ** 2))
 
 
+def unfold(F: np.ndarray, kh: int, kw: int, stride: int = 1, pad: int = 0) -> np.ndarray:
+    """Rows of X for a convolutional layer (Section 3, "Structured pruning in convolutional layers"): the feature map
+    F (batch, C, Hin, Win), zero-padded by `pad`, is cut into kh x kw patches with the given stride; the patch at
+    output position (b, oy, ox) becomes the row b*Hout*Wout + oy*Wout + ox, and its entry for input channel c and
+    kernel offset (dy, dx) sits in column c*kh*kw + dy*kw + dx, so that the rows of W that act on channel c are the
+    group Q^c of kh*kw consecutive rows."""
+    F = np.asarray(F, dtype=np.float64)
+    B, C, Hin, Win = F.shape
+    Hout = (Hin + 2 * pad - kh) // stride + 1
+    Wout = (Win + 2 * pad - kw) // stride + 1
+    X = np.zeros((B * Hout * Wout, C * kh * kw))
+    for b in range(B):
+        for oy in range(Hout):
+            for ox in range(Wout):
+                row = (b * Hout + oy) * Wout + ox
+                for c in range(C):
+                    for dy in range(kh):
+                        for dx in range(kw):
+                            y, x = oy * stride + dy - pad, ox * stride + dx - pad
+                            if 0 <= y < Hin and 0 <= x < Win:
+                                X[row, (c * kh + dy) * kw + dx] = F[b, c, y, x]
+    return X
+
+
 def objective_quadratic(H: np.ndarray, G: np.ndarray, c0: float, What: np.ndarray) -> float:
     """c0 + 2 L(What) with L from eq. (MIQP)."""
     return float(c0 + np.sum(What * (H @ What)) - 2.0 * np.sum(G * What))

@@ -782,6 +782,7 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
         st = build_state(c, &obj);
         if (st != OSSCAR_OK) return st;
         HIPCHK(c, hipMemcpyAsync(reinterpret_cast<char*>(c->ctrl) + offsetof(SearchCtrl, obj), &obj, 8, hipMemcpyHostToDevice, s));
+        HIPCHK(c, launch_lazy_init(d, t, L, s, la_mode));     // selection records and look-ahead products of the rebuilt state
         HIPCHK(c, hipEventRecord(r1, s));
         HIPCHK(c, hipStreamSynchronize(s));
         float ms = 0; hipEventElapsedTime(&ms, r0, r1); refresh_ms += ms;

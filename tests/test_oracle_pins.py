@@ -302,6 +302,27 @@ def test_always_accept_runs_the_printed_algorithm():
     assert np.isclose(o, res.obj_final, rtol=1e-8)
 
 
+# ---------------------------------------------------------------- convolutional layers (Section 3)
+def test_unfold_matches_the_library_routine_and_reproduces_the_convolution():
+    import torch
+    rng = np.random.default_rng(71)
+    for (B, C, Hin, Win, kh, kw, stride, pad) in ((2, 3, 5, 6, 3, 3, 1, 1), (1, 2, 7, 5, 3, 2, 2, 0), (2, 4, 4, 4, 1, 1, 1, 0)):
+        F = rng.standard_normal((B, C, Hin, Win))
+        X = orc.unfold(F, kh, kw, stride, pad)
+        ref = torch.nn.functional.unfold(torch.from_numpy(F), (kh, kw), padding=pad, stride=stride)   # (B, C*kh*kw, L)
+        ref = ref.permute(0, 2, 1).reshape(-1, C * kh * kw).numpy()
+        assert X.shape == ref.shape and np.array_equal(X, ref)
+        # X W is the convolution with the filters stored as the columns of W
+        Cout = 3
+        Wm = rng.standard_normal((C * kh * kw, Cout))
+        filt = torch.from_numpy(Wm.T.reshape(Cout, C, kh, kw).copy())
+        y = torch.nn.functional.conv2d(torch.from_numpy(F), filt, padding=pad, stride=stride)        # (B, Cout, Hout, Wout)
+        assert np.allclose(X @ Wm, y.permute(0, 2, 3, 1).reshape(-1, Cout).numpy(), atol=1e-12)
+    # a 1 x 1 kernel: the rows are the pixels, the columns the channels
+    F = rng.standard_normal((2, 3, 2, 2))
+    assert np.array_equal(orc.unfold(F, 1, 1), F.transpose(0, 2, 3, 1).reshape(-1, 3))
+
+
 # ---------------------------------------------------------------- block moves (Section 4.2, t-hat = 2 s, p-hat = 0)
 def test_block_search_with_one_pair_is_the_swap_search():
     X, W, H, G, c0, lam = make_problem(10, 2, 4, 90, 41)
