@@ -84,6 +84,17 @@ osscar_status osscar_destroy(osscar_ctx* ctx);
 osscar_status osscar_gram(osscar_ctx* ctx, const void* Xc_dev, int64_t n_c, int64_t ldx, int finalize,
                           const void* W_dev, int64_t ldw, double lambda_abs, double lambda_rel);
 
+/* Convolutional layers (Section 3, "Structured pruning in convolutional layers": W is (C_in * k_H * k_W) x C_out and
+ * the rows of X are the k_H x k_W patches of the layer's input).  Same as osscar_gram, but takes the input feature map
+ * itself and forms the patches on the fly, so that the caller never holds the k_H * k_W times larger patch matrix.
+ * F_dev: dev, contiguous (batch, channels, h_in, w_in), dtype desc.x_dtype, zero padding `pad` on every side.  The
+ * patch at output position (b, oy, ox) is the row (b * h_out + oy) * w_out + ox, and input channel c, kernel offset
+ * (dy, dx) is the column (c * kh + dy) * kw + dx: the rows of W acting on channel c form the group of kh * kw rows c.
+ * channels * kh * kw must equal desc.d1.  Chunks (batches of feature maps) may be mixed with osscar_gram chunks. */
+osscar_status osscar_gram_conv(osscar_ctx* ctx, const void* F_dev, int32_t batch, int32_t channels, int32_t h_in, int32_t w_in,
+                               int32_t kh, int32_t kw, int32_t stride, int32_t pad, int finalize, const void* W_dev,
+                               int64_t ldw, double lambda_abs, double lambda_rel);
+
 /* Sequential-pipeline variant of osscar_gram (Appendix B.1, "Pruning strategies": the layer is asked to reproduce
  * the DENSE model's output from the PRUNED model's input).  Yc_dev: dev, row-major n_c x m, leading dimension
  * ldy >= m, dtype desc.x_dtype: the dense model's output of this layer for the same calibration rows as Xc.

@@ -4,7 +4,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
-from typing import Optional, Sequence
+from typing import Tuple, Optional, Sequence
 
 import numpy as np
 import torch
@@ -17,7 +17,7 @@ OSSCAR_SEARCH_NO_LOOKAHEAD = 4
 T_H, T_G, T_P, T_B, T_V, T_R, T_REM, T_ADD, T_KEPT, T_CAND = range(10)
 _STATUS = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "ENOTPD", 4: "EHIP", 5: "ESTATE"}
 
-EXPORTED_SYMBOLS = ["osscar_workspace_bytes", "osscar_create", "osscar_destroy", "osscar_gram", "osscar_gram_target",
+EXPORTED_SYMBOLS = ["osscar_workspace_bytes", "osscar_create", "osscar_destroy", "osscar_gram", "osscar_gram_target", "osscar_gram_conv",
                     "osscar_set_quadratic",
                     "osscar_init_support", "osscar_init_greedy", "osscar_local_search", "osscar_block_search", "osscar_apply_swap", "osscar_backsolve",
                     "osscar_get_tensor", "osscar_get_scalars", "osscar_get_timers", "osscar_last_error"]
@@ -62,6 +62,7 @@ def load_library():
     lib.osscar_create.argtypes = [C.POINTER(vp), C.POINTER(_Desc), vp, C.c_size_t, vp]
     lib.osscar_destroy.argtypes = [vp]
     lib.osscar_gram.argtypes = [vp, vp, i64, i64, C.c_int, vp, i64, dbl, dbl]
+    lib.osscar_gram_conv.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, C.c_int, vp, i64, dbl, dbl]
     lib.osscar_gram_target.argtypes = [vp, vp, vp, i64, i64, i64, C.c_int, vp, i64, dbl, dbl]
     lib.osscar_set_quadratic.argtypes = [vp, vp, vp, dbl, C.POINTER(dbl)]
     lib.osscar_init_support.argtypes = [vp, C.c_int, C.POINTER(i32), C.POINTER(dbl)]
@@ -151,6 +152,25 @@ class Solver:
             assert _dtype_code(W.dtype) == self.desc.w_dtype
             wp, ldw = W.data_ptr(), W.stride(0)
         self._check(self.lib.osscar_gram(self.ctx, xp, n_c, ldx, int(finalize), wp, ldw, lambda_abs, lambda_rel))
+
+    def osscar_gram_conv(self, F: Optional[torch.Tensor], kh: int, kw: int, stride: int = 1, pad: int = 0, finalize: bool = False,
+                         W: Optional[torch.Tensor] = None, lambda_abs: float = 0.0, lambda_rel: float = 0.0,
+                         shape: Optional[Tuple[int, int, int]] = None):
+        """F: (batch, channels, h_in, w_in) contiguous, or None with shape = (channels, h_in, w_in) for an empty finalize."""
+        fp, batch = None, 0
+        if F is not None:
+            assert F.is_cuda and F.dim() == 4 and F.is_contiguous() and _dtype_code(F.dtype) == self.desc.x_dtype
+            batch, ch, h_in, w_in = F.shape
+            fp = F.data_ptr() if batch > 0 else None
+        else:
+            ch, h_in, w_in = shape
+        wp, ldw = None, self.m
+        if finalize:
+            assert W is not None and W.is_cuda and W.shape == (self.d1, self.m) and W.stride(1) == 1
+            assert _dtype_code(W.dtype) == self.desc.w_dtype
+            wp, ldw = W.data_ptr(), W.stride(0)
+        self._check(self.lib.osscar_gram_conv(self.ctx, fp, batch, ch, h_in, w_in, kh, kw, stride, pad, int(finalize), wp, ldw,
+                                              lambda_abs, lambda_rel))
 
     def osscar_gram_target(self, Xc: Optional[torch.Tensor], Yc: Optional[torch.Tensor], finalize: bool = False,
                            W: Optional[torch.Tensor] = None, lambda_abs: float = 0.0, lambda_rel: float = 0.0):

@@ -422,7 +422,8 @@ const char* osscar_last_error(const osscar_ctx* c) { return c ? c->err.c_str() :
 
 // Shared body of osscar_gram (Yc == nullptr, target == 0) and osscar_gram_target.
 static osscar_status gram_impl(osscar_ctx* c, const char* who, int target, const void* Xc, const void* Yc, int64_t n_c, int64_t ldx,
-                               int64_t ldy, int finalize, const void* W, int64_t ldw, double lambda_abs, double lambda_rel) {
+                               int64_t ldy, int finalize, const void* W, int64_t ldw, double lambda_abs, double lambda_rel,
+                               const ConvSpec* conv = nullptr) {
   osscar_status st = check_ctx(c);
   if (st != OSSCAR_OK) return st;
   if (n_c < 0 || (n_c > 0 && (!Xc || ldx < c->d1))) return fail(c, OSSCAR_EINVAL, "%s: bad chunk (n_c=%lld, ldx=%lld)", who, (long long)n_c, (long long)ldx);
@@ -459,19 +460,21 @@ static osscar_status gram_impl(osscar_ctx* c, const char* who, int target, const
   if (n_c > 0) {
     HIPCHK(c, hipEventRecord(c->ev_a, s));
     const bool bf16 = c->desc.x_dtype == OSSCAR_BF16;
-    bool fast = bf16 && (d1 % 8 == 0) && (ldx % 8 == 0) && ((reinterpret_cast<uintptr_t>(Xc) & 15) == 0);
+    bool fast = bf16 && (d1 % 8 == 0) && (conv || ((ldx % 8 == 0) && ((reinterpret_cast<uintptr_t>(Xc) & 15) == 0)));
     if (target) fast = fast && (m % 8 == 0) && (ldy % 8 == 0) && ((reinterpret_cast<uintptr_t>(Yc) & 15) == 0);
     if (target) HIPCHK(c, launch_sumsq(Yc, bf16, n_c, m, ldy, c->scal + 12, s));
     if (fast) {
       if (target) HIPCHK(c, launch_gram_packed(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, Xt, PACK_ROWS, s, Yc, ldy, m, G64,
                                                tile_buf_y, tile_y_entries, Ys));
-      else HIPCHK(c, launch_gram_packed(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, Xt, PACK_ROWS, s));
+      else HIPCHK(c, launch_gram_packed(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, Xt, PACK_ROWS, s, nullptr, 0, 0, nullptr,
+                                        nullptr, 0, nullptr, conv));
     } else {
       const size_t esz = bf16 ? 2 : 4;
       for (int64_t r0 = 0; r0 < n_c; r0 += XT_ROWS) {
         int64_t nr = std::min<int64_t>(XT_ROWS, n_c - r0);
         const char* src = reinterpret_cast<const char*>(Xc) + (size_t)r0 * ldx * esz;
-        HIPCHK(c, launch_transpose_to_f32(src, bf16, nr, d1, ldx, Xt, XT_ROWS, s));
+        if (conv) HIPCHK(c, launch_im2col_transpose(Xc, bf16, *conv, r0, nr, d1, Xt, XT_ROWS, s));
+        else HIPCHK(c, launch_transpose_to_f32(src, bf16, nr, d1, ldx, Xt, XT_ROWS, s));
         GemmArgs g{};
         g.M = d1; g.N = d1; g.K = (int)nr; g.A = Xt; g.lda = XT_ROWS; g.B = Xt; g.ldb = XT_ROWS; g.trans_b = 1;
         g.Cin = reinterpret_cast<const float*>(H64); g.ldcin = d1; g.C = H64; g.ldc = d1; g.alpha = 1.0; g.beta = 1.0;
@@ -542,6 +545,19 @@ osscar_status osscar_gram(osscar_ctx* c, const void* Xc, int64_t n_c, int64_t ld
 osscar_status osscar_gram_target(osscar_ctx* c, const void* Xc, const void* Yc, int64_t n_c, int64_t ldx, int64_t ldy, int finalize,
                                  const void* W, int64_t ldw, double lambda_abs, double lambda_rel) {
   return gram_impl(c, "osscar_gram_target", 1, Xc, Yc, n_c, ldx, ldy, finalize, W, ldw, lambda_abs, lambda_rel);
+}
+
+osscar_status osscar_gram_conv(osscar_ctx* c, const void* F, int32_t batch, int32_t channels, int32_t h_in, int32_t w_in, int32_t kh,
+                               int32_t kw, int32_t stride, int32_t pad, int finalize, const void* W, int64_t ldw, double lambda_abs,
+                               double lambda_rel) {
+  osscar_status st = check_ctx(c);
+  if (st != OSSCAR_OK) return st;
+  if (batch < 0 || channels < 1 || h_in < 1 || w_in < 1 || kh < 1 || kw < 1 || stride < 1 || pad < 0 ||
+      (int64_t)channels * kh * kw != c->d1 || h_in + 2 * pad < kh || w_in + 2 * pad < kw || (batch > 0 && !F))
+    return fail(c, OSSCAR_EINVAL, "osscar_gram_conv: bad geometry (channels * kh * kw must equal d1 = %d)", c->d1);
+  ConvSpec cs{batch, channels, h_in, w_in, kh, kw, stride, pad, (h_in + 2 * pad - kh) / stride + 1, (w_in + 2 * pad - kw) / stride + 1};
+  const int64_t n_c = (int64_t)batch * cs.Hout * cs.Wout;
+  return gram_impl(c, "osscar_gram_conv", 0, F, nullptr, n_c, c->d1, 0, finalize, W, ldw, lambda_abs, lambda_rel, &cs);
 }
 
 osscar_status osscar_set_quadratic(osscar_ctx* c, const float* H_dev, const float* G_dev, double c0, const double* norms) {

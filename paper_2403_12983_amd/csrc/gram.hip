@@ -87,6 +87,43 @@ __global__ __launch_bounds__(256) void gram_pack_kernel(const uint16_t* __restri
 #undef OSSCAR_PACK_HI
 }
 
+// The same repacking for a convolutional layer: the 8 x 8 blocks are gathered from the feature map, patch by patch.
+__global__ __launch_bounds__(256) void gram_pack_conv_kernel(const uint16_t* __restrict__ F, ConvSpec cs, int64_t r0, int64_t n_c,
+                                                              int d1, int npanels, uint4* __restrict__ Xp) {
+  const int tid = threadIdx.x;
+  const int panel = blockIdx.x * 2 + (tid >> 7);
+  if (panel >= npanels) return;
+  const int kg = (tid & 127) >> 4, cg = tid & 15;
+  const int col0 = panel * 128 + cg * 8;
+  const int64_t row0 = (int64_t)blockIdx.y * GBK + kg * 8;
+  const int kk = cs.kh * cs.kw;
+  uint32_t v[8][4];                       // v[j][r/2]: rows r, r+1 of column j
+#pragma unroll
+  for (int j = 0; j < 8; j++)
+#pragma unroll
+    for (int h = 0; h < 4; h++) v[j][h] = 0u;
+#pragma unroll
+  for (int r = 0; r < 8; r++) {
+    const int64_t row = row0 + r;
+    if (row >= n_c) continue;
+    const int64_t pr = r0 + row;
+    const int ox = (int)(pr % cs.Wout), oy = (int)((pr / cs.Wout) % cs.Hout), b = (int)(pr / ((int64_t)cs.Wout * cs.Hout));
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+      const int col = col0 + j;
+      if (col >= d1) continue;
+      const int c = col / kk, dy = (col % kk) / cs.kw, dx = col % cs.kw;
+      const int y = oy * cs.stride + dy - cs.pad, x = ox * cs.stride + dx - cs.pad;
+      if (y < 0 || y >= cs.Hin || x < 0 || x >= cs.Win) continue;
+      const uint32_t e = F[(((int64_t)b * cs.C + c) * cs.Hin + y) * cs.Win + x];
+      v[j][r >> 1] |= (r & 1) ? (e << 16) : e;
+    }
+  }
+  uint4* out = Xp + ((int64_t)blockIdx.y * npanels + panel) * PK_SLOTS + kg * 128 + cg * 8;
+#pragma unroll
+  for (int j = 0; j < 8; j++) out[j] = uint4{v[j][0], v[j][1], v[j][2], v[j][3]};
+}
+
 // Out (+)= A^T B for packed operands Ap (rows of the result) and Bp (columns of the result); symmetric: Ap == Bp and only
 // tiles on or below the diagonal are listed, the diagonal ones loading one panel.
 __global__ __launch_bounds__(256, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void gram_packed_kernel(
@@ -209,6 +246,43 @@ __global__ __launch_bounds__(256, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     }
 }
 
+// Xt[c][r - r0] = patch matrix entry (r, c) as float32 (32 x 32 tiles through LDS so that the writes are contiguous)
+__global__ __launch_bounds__(256) void im2col_transpose_kernel(const void* __restrict__ F, int is_bf16, ConvSpec cs, int64_t r0,
+                                                                int64_t nr, int d1, float* __restrict__ Xt, int64_t ldxt) {
+  __shared__ float tile[32][33];
+  const int64_t c0 = (int64_t)blockIdx.x * 32, q0 = (int64_t)blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int kk = cs.kh * cs.kw;
+  for (int i = ty; i < 32; i += 8) {
+    const int64_t r = q0 + i;
+    const int col = (int)(c0 + tx);
+    float val = 0.f;
+    if (r < nr && col < d1) {
+      const int64_t pr = r0 + r;
+      const int ox = (int)(pr % cs.Wout), oy = (int)((pr / cs.Wout) % cs.Hout), b = (int)(pr / ((int64_t)cs.Wout * cs.Hout));
+      const int c = col / kk, dy = (col % kk) / cs.kw, dx = col % cs.kw;
+      const int y = oy * cs.stride + dy - cs.pad, x = ox * cs.stride + dx - cs.pad;
+      if (y >= 0 && y < cs.Hin && x >= 0 && x < cs.Win) {
+        const int64_t idx = (((int64_t)b * cs.C + c) * cs.Hin + y) * cs.Win + x;
+        val = is_bf16 ? __uint_as_float(((uint32_t)reinterpret_cast<const uint16_t*>(F)[idx]) << 16) : reinterpret_cast<const float*>(F)[idx];
+      }
+    }
+    tile[i][tx] = val;
+  }
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8) {
+    const int64_t col = c0 + i, r = q0 + tx;
+    if (col < d1 && r < nr) Xt[col * ldxt + r] = tile[tx][i];
+  }
+}
+hipError_t launch_im2col_transpose(const void* F, int is_bf16, const ConvSpec& cs, int64_t r0, int64_t nr, int d1, float* Xt,
+                                   int64_t ldxt, hipStream_t s) {
+  if (nr <= 0) return hipSuccess;
+  hipLaunchKernelGGL(im2col_transpose_kernel, dim3((d1 + 31) / 32, (unsigned)((nr + 31) / 32)), dim3(256), 0, s, F, is_bf16, cs, r0, nr, d1,
+                     Xt, ldxt);
+  return hipGetLastError();
+}
+
 // all tiles of an R x C grid, in 4 x 8 blocks dealt to the XCDs in turn
 static void build_rect_tile_list(int R, int C, std::vector<int2>& out) {
   constexpr int NX = 8, RB = 4, CB = 8;
@@ -236,7 +310,8 @@ static int split_stages(int ntiles, int nstages, int* per_out) {
 
 hipError_t launch_gram_packed(const void* Xc, int64_t n_c, int64_t ldx, int d1, double* H64, int2* tile_buf,
                               size_t tile_buf_entries, void* pack_buf, int64_t pack_rows, hipStream_t s, const void* Yc,
-                              int64_t ldy, int m, double* G64, int2* tile_buf_y, size_t tile_buf_y_entries, void* pack_buf_y) {
+                              int64_t ldy, int m, double* G64, int2* tile_buf_y, size_t tile_buf_y_entries, void* pack_buf_y,
+                              const ConvSpec* conv) {
   if (n_c <= 0) return hipSuccess;
   if (pack_rows < GBK || pack_rows % GBK) return hipErrorInvalidValue;
   const int npanels = (d1 + 127) / 128, npanels_y = Yc ? (m + 127) / 128 : 0;
@@ -261,8 +336,12 @@ hipError_t launch_gram_packed(const void* Xc, int64_t n_c, int64_t ldx, int d1, 
     const int nstages = (int)((nr + GBK - 1) / GBK);
     const uint16_t* src = reinterpret_cast<const uint16_t*>(Xc) + r0 * ldx;
     const uint4* Xp = reinterpret_cast<const uint4*>(pack_buf);
-    hipLaunchKernelGGL(gram_pack_kernel, dim3((npanels + 1) / 2, nstages), dim3(256), 0, s, src, nr, ldx, d1, npanels,
-                       reinterpret_cast<uint4*>(pack_buf));
+    if (conv)
+      hipLaunchKernelGGL(gram_pack_conv_kernel, dim3((npanels + 1) / 2, nstages), dim3(256), 0, s, reinterpret_cast<const uint16_t*>(Xc),
+                         *conv, r0, nr, d1, npanels, reinterpret_cast<uint4*>(pack_buf));
+    else
+      hipLaunchKernelGGL(gram_pack_kernel, dim3((npanels + 1) / 2, nstages), dim3(256), 0, s, src, nr, ldx, d1, npanels,
+                         reinterpret_cast<uint4*>(pack_buf));
     int per = 0;
     int splits = split_stages(ntiles, nstages, &per);
     const int64_t xs = (int64_t)npanels * PK_SLOTS;

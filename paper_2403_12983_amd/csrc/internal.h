@@ -30,10 +30,18 @@ hipError_t launch_gemm_f64acc(const GemmArgs& a, hipStream_t s);
 // Repacks `pack_rows`-token chunks of Xc into MFMA operand order in pack_buf (pack_rows * 128*ceil(d1/128) * 2 bytes)
 // and accumulates them into H64.
 // tile_buf: device scratch for the tile schedule, tile_buf_entries >= 8 * (ceil(d1/128)^2 / 2 + ceil(d1/128) + 8)
+// Patch geometry of a convolutional layer: row (b*Hout + oy)*Wout + ox, column (c*kh + dy)*kw + dx of the patch matrix is
+// F[b][c][oy*stride + dy - pad][ox*stride + dx - pad] (zero outside the map).
+struct ConvSpec { int B, C, Hin, Win, kh, kw, stride, pad, Hout, Wout; };
 hipError_t launch_gram_packed(const void* Xc, int64_t n_c, int64_t ldx, int d1, double* H64, int2* tile_buf,
                               size_t tile_buf_entries, void* pack_buf, int64_t pack_rows, hipStream_t s,
                               const void* Yc = nullptr, int64_t ldy = 0, int m = 0, double* G64 = nullptr,
-                              int2* tile_buf_y = nullptr, size_t tile_buf_y_entries = 0, void* pack_buf_y = nullptr);
+                              int2* tile_buf_y = nullptr, size_t tile_buf_y_entries = 0, void* pack_buf_y = nullptr,
+                              const ConvSpec* conv = nullptr);
+// conv (optional): Xc is a feature map (NCHW, bf16) and the rows are its patches
+// Xt[c][r - r0] = patch matrix entry (r, c) as float32 for rows r0 .. r0 + nr (generic path of convolutional layers)
+hipError_t launch_im2col_transpose(const void* F, int is_bf16, const ConvSpec& cs, int64_t r0, int64_t nr, int d1, float* Xt,
+                                   int64_t ldxt, hipStream_t s);
 // Yc (optional, bf16 n_c x m): also G64 (d1 x m, float64) += Xc^T Yc, with its own tile list (>= 8 * (ceil(d1/128) *
 // ceil(m/128) / 8 + 64) entries) and pack buffer (pack_rows * 128*ceil(m/128) * 2 bytes)
 hipError_t launch_sumsq(const void* A, int is_bf16, int64_t rows, int64_t cols, int64_t ld, double* acc, hipStream_t s);

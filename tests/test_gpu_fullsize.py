@@ -212,6 +212,38 @@ def test_block_moves_whole_layer(name, block, iters):
     s.close()
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_conv_gram_at_the_conv_layer_shape(dtype):
+    """ResNet-style 3 x 3 layer, 256 channels, 64 maps of 14 x 14 (the shape of cfg2): H and G from the feature maps against
+    the oracle's Gram of the patch matrix (patches cut by the library routine the oracle's unfold is pinned to)."""
+    import time
+    import paper_2403_12983_amd as pkg
+    cfg = inp.CONFIGS["cfg2"]
+    B, C, Hin, Win = 64, 256, 14, 14
+    g = torch.Generator().manual_seed(77)
+    F = (torch.relu(torch.randn(B, C, Hin, Win, generator=g)) * torch.exp(0.5 * torch.randn(1, C, 1, 1, generator=g))).to(dtype)
+    W = inp.gen_W(cfg).to(dtype)
+    Xd = torch.nn.functional.unfold(F.double(), (3, 3), padding=1).permute(0, 2, 1).reshape(-1, C * 9).numpy()
+    assert Xd.shape == (cfg.n, cfg.d1)
+    H, G, c0, lam = orc.gram(Xd, W.double().numpy(), cfg.lam_abs, cfg.lam_rel)
+    s = pkg.Solver(cfg.d1, cfg.m, cfg.p, cfg.q, cfg.k, cfg.swaps, dtype, dtype, DEV)
+    Fg, Wg = F.to(DEV), W.to(DEV)
+    s.osscar_gram_conv(Fg, 3, 3, 1, 1, True, Wg, cfg.lam_abs, cfg.lam_rel)      # warm-up
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    s.osscar_gram_conv(Fg[:40], 3, 3, 1, 1)
+    s.osscar_gram_conv(Fg[40:], 3, 3, 1, 1, True, Wg, cfg.lam_abs, cfg.lam_rel)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    dsc = np.sqrt(np.diag(H))
+    assert np.max(np.abs(T(s, "T_H").cpu().double().numpy() - H) / np.outer(dsc, dsc)) < 1e-6
+    assert rel(T(s, "T_G").cpu().double().numpy(), G) < 1e-6
+    lam1, c01 = s.osscar_get_scalars()
+    assert abs(lam1 - lam) <= 1e-6 * lam and abs(c01 - c0) <= 1e-6 * c0
+    print(f"conv Gram {dtype}: {dt * 1e3:.2f} ms incl. finalize for {cfg.n} patches x {cfg.d1} columns from a {F.numel() * F.element_size() / 1e6:.1f} MB map")
+    s.close()
+
+
 def test_cfg5_target_gram_sampled():
     """Cross-Gram of the benchmark layer's shape (32768 calibration rows) on sampled rows of G, float64 on the device."""
     import time

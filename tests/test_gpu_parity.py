@@ -570,6 +570,53 @@ def test_target_output_path(name):
     s.close()
 
 
+# ------------------------------------------------------------------------------------------ convolutional layers
+@pytest.mark.parametrize("dtype,B,C,Hin,Win,kh,kw,stride,pad,m", [
+    (torch.float32, 3, 8, 9, 7, 3, 3, 1, 1, 12),        # float32 features: generic path
+    (torch.bfloat16, 5, 16, 10, 12, 3, 3, 2, 1, 24),    # bf16, d1 = 144: MFMA path, patches gathered while repacking
+    (torch.bfloat16, 4, 3, 8, 8, 3, 3, 1, 0, 10),       # bf16, d1 = 27: generic path
+    (torch.bfloat16, 2, 40, 6, 6, 1, 1, 1, 0, 16),      # 1 x 1 kernel
+])
+def test_conv_gram_from_the_feature_map(dtype, B, C, Hin, Win, kh, kw, stride, pad, m):
+    g = torch.Generator().manual_seed(1234 + C)
+    F = torch.relu(torch.randn(B, C, Hin, Win, generator=g)).to(dtype)
+    q, p, d1 = kh * kw, C, C * kh * kw
+    W = (torch.randn(d1, m, generator=g) / d1 ** 0.5).to(dtype)
+    k = max(1, p // 2)
+    Xo = orc.unfold(F.double().numpy(), kh, kw, stride, pad)
+    H, G, c0, lam = orc.gram(Xo, W.double().numpy(), 0.0, 1e-2)
+    s = _pkg().Solver(d1, m, p, q, k, 10, dtype, dtype, DEV)
+    Fg, Wg = F.to(DEV), W.to(DEV)
+    s.osscar_gram_conv(Fg[:2], kh, kw, stride, pad)                                # two batches of feature maps
+    s.osscar_gram_conv(Fg[2:], kh, kw, stride, pad, True, Wg, 0.0, 1e-2)
+    H1, G1 = T(s, "T_H"), T(s, "T_G")
+    dsc = np.sqrt(np.diag(H))
+    assert np.max(np.abs(H1 - H) / np.outer(dsc, dsc)) < 1e-6 and rel(G1, G) < 1e-6
+    # the same rows handed over as an explicit patch matrix give the same H
+    Xg = torch.from_numpy(Xo).to(dtype).to(DEV)
+    s.osscar_gram(Xg[:7])
+    s.osscar_gram_conv(None, kh, kw, stride, pad, shape=(C, Hin, Win))
+    s.osscar_gram(Xg[7:], True, Wg, 0.0, 1e-2)
+    assert np.max(np.abs(T(s, "T_H") - H1) / np.outer(dsc, dsc)) < 3e-7
+    # channel pruning on it: groups are the kh*kw rows of a channel
+    s.osscar_init_support()
+    K0 = orc.magnitude_support(W.double().numpy(), p, q, k)
+    assert T(s, "T_KEPT").astype(int).tolist() == K0
+    r = s.osscar_local_search(10)
+    pairs = list(zip(r["trace_out"][: r["accepted"]].tolist(), r["trace_in"][: r["accepted"]].tolist()))
+    fol = orc.local_search(H, G, c0, K0, p, q, len(pairs), follow=pairs)
+    assert all(x.deficit_rem <= GAP and x.deficit_add <= GAP and x.delta < 0 for x in fol.trace)
+    What, support, obj = s.osscar_backsolve()
+    Wo, objo = orc.solve_support(H, G, c0, fol.support, q)
+    assert support.tolist() == fol.support
+    assert rel(What.cpu().double().numpy(), Wo) < 1e-4 and abs(obj - objo) <= 1e-4 * objo
+    from paper_2403_12983_amd.binding import OsscarError
+    with pytest.raises(OsscarError) as e:
+        s.osscar_gram_conv(Fg, kh + 1, kw, stride, pad)                            # channels * kh * kw != d1
+    assert e.value.status == 1
+    s.close()
+
+
 def test_set_quadratic_and_brute_force_optimum_is_a_fixed_point():
     c = case("cfg1x")
     cfg = c.cfg
