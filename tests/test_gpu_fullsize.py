@@ -244,6 +244,46 @@ def test_conv_gram_at_the_conv_layer_shape(dtype):
     s.close()
 
 
+def test_cfg5_nested_schedule_properties():
+    """The benchmark layer's shape (32768 calibration rows) through the nested schedule from the dense layer, t-hat = 10:
+    14336 removals on the delayed-update path.  Checked through what holds at any size: bookkeeping, a monotone tracked
+    objective, the tracked objective against the fresh solve, the normal equations of the final weights."""
+    import paper_2403_12983_amd as pkg
+    cfg = inp.CONFIGS["cfg5"].replace(n=32768)
+    X = gen_on_gpu(cfg)
+    W = inp.gen_W(cfg, DEV)
+    s = pkg.Solver(cfg.d1, cfg.m, cfg.p, cfg.q, cfg.k, 64, X.dtype, W.dtype, DEV, from_dense=True)
+    s.osscar_gram(X, True, W, cfg.lam_abs, cfg.lam_rel)
+    del X
+    obj, steps, gaps = s.osscar_init_greedy(10)
+    flat = [g for st in steps for g in st]
+    assert len(steps) == -(-(cfg.p - cfg.k) // 10) and all(len(st) == 10 for st in steps[:-1])
+    assert len(set(flat)) == len(flat) == cfg.p - cfg.k and min(flat) >= 0 and max(flat) < cfg.p
+    kept = T(s, "T_KEPT").cpu().tolist()
+    assert kept == sorted(set(range(cfg.p)) - set(flat))
+    assert np.all(gaps >= 0)
+    # a swap search from there finds next to nothing to improve, and never raises the objective
+    r = s.osscar_local_search(64)
+    assert np.all(np.diff(np.concatenate([[obj], r["trace_obj"][: r["accepted"]]])) < 0)
+    What, support, objb = s.osscar_backsolve()
+    assert abs(objb - r["obj_final"]) <= 1e-4 * objb
+    Kt = torch.from_numpy(support.astype(np.int64)).to(DEV)
+    Hd, Gd = T(s, "T_H"), T(s, "T_G")
+    samp = Kt[torch.arange(0, Kt.numel(), 97, device=DEV)]
+    lhs = Hd[samp][:, Kt].double() @ What[Kt].double()
+    assert (torch.linalg.norm(lhs - Gd[samp].double()) / torch.linalg.norm(Gd[samp].double())).item() < 1e-5
+    pruned = torch.ones(cfg.d1, dtype=torch.bool, device=DEV)
+    pruned[Kt] = False
+    assert torch.count_nonzero(What[pruned]).item() == 0
+    # against the magnitude support with the same number of kept rows: the nested schedule ends far lower
+    s.osscar_init_support()
+    What_m, _, obj_mp = s.osscar_backsolve()
+    assert objb < obj_mp
+    print(f"cfg5 shape, nested schedule: obj {objb:.6g} (magnitude support {obj_mp:.6g}), {r['accepted']} swaps after it, "
+          f"init timer {s.osscar_get_timers()[2]:.1f} ms")
+    s.close()
+
+
 def test_cfg5_target_gram_sampled():
     """Cross-Gram of the benchmark layer's shape (32768 calibration rows) on sampled rows of G, float64 on the device."""
     import time
