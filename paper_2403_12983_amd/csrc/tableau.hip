@@ -366,8 +366,9 @@ __global__ __launch_bounds__(256) void dblk_copy_kernel(TabDims d, const float* 
 // One workgroup of 64 threads per group; Cholesky in shared memory, then one column solve per thread.
 __global__ __launch_bounds__(64) void score_kernel(TabDims d, const int32_t* __restrict__ kept,
                                                     const double* __restrict__ gram, const double* __restrict__ dblk,
-                                                    double* __restrict__ score, SearchCtrl* ctrl) {
+                                                    double* __restrict__ score, SearchCtrl* ctrl, int skip_if_done) {
   extern __shared__ double sh[];   // A: q*q, X: q*q
+  if (skip_if_done && ctrl->done) return;          // a search iteration that changed nothing
   const int h = blockIdx.x, q = d.q, tid = threadIdx.x;
   const double sigma = kept[h] ? -1.0 : 1.0;
   if (q == 1) {
@@ -424,7 +425,7 @@ hipError_t launch_refresh_scores(const TabDims& d, const TabPtrs& t, hipStream_t
     hipLaunchKernelGGL(dblk_copy_kernel, dim3(d.p), dim3(256), 0, s, d, t.N, t.dblk);
   }
   hipLaunchKernelGGL(score_kernel, dim3(d.p), dim3(64), (size_t)2 * d.q * d.q * 8, s, d, t.kept, t.gram, t.dblk, t.score,
-                     t.ctrl);
+                     t.ctrl, 0);
   return hipGetLastError();
 }
 
@@ -630,35 +631,35 @@ __global__ __launch_bounds__(256) void pair_panels_kernel(TabDims d, const float
                                                            float* __restrict__ P1, float* __restrict__ P2,
                                                            float* __restrict__ P1D, float* __restrict__ P2D,
                                                            const int32_t* __restrict__ single) {
+  // one thread per (row, column): 4 rows x 64 columns per workgroup; the q x q matrices are read from global memory
+  // (consecutive threads, consecutive columns), the row's own coefficients go through LDS
+  __shared__ double sc1[4][64], sc2[4][64];
   if (ctrl->done) return;
-  extern __shared__ double sm[];   // Dg, M1, Dj : 3*q*q
   const int q = d.q, qq = q * q;
   const int g0 = (single ? *single : ctrl->g_out) * q, j0 = (single ? *single : ctrl->g_in) * q;
-  double* Dg = sm; double* M1 = sm + qq; double* Dj = sm + 2 * qq;
-  for (int idx = threadIdx.x; idx < qq; idx += 256) { Dg[idx] = small[idx]; M1[idx] = small[2 * qq + idx]; Dj[idx] = small[3 * qq + idx]; }
-  __syncthreads();
-  int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= d.d1) return;
+  const double* Dg = small; const double* M1 = small + 2 * qq; const double* Dj = small + 3 * qq;
+  const int lr = threadIdx.x >> 6, c = threadIdx.x & 63;
+  const int i = blockIdx.x * 4 + lr;
+  const bool live = (i < d.d1) && (c < q);
   const bool piv = (i >= g0 && i < g0 + q) || (i >= j0 && i < j0 + q);
-  if (piv) {
-    for (int c = 0; c < q; c++) { P1[(int64_t)i * q + c] = 0.f; P2[(int64_t)i * q + c] = 0.f; P1D[(int64_t)i * q + c] = 0.f; P2D[(int64_t)i * q + c] = 0.f; }
-    return;
+  sc1[lr][c] = live ? (double)C1[(int64_t)i * q + c] : 0.0;
+  __syncthreads();
+  double v = 0;
+  if (live) {
+    v = (double)C2[(int64_t)i * q + c];
+    for (int k = 0; k < q; k++) v -= sc1[lr][k] * M1[k * q + c];
   }
-  double c1[64], c2[64];
-  for (int c = 0; c < q; c++) c1[c] = (double)C1[(int64_t)i * q + c];
-  for (int c = 0; c < q; c++) {
-    double v = (double)C2[(int64_t)i * q + c];
-    for (int k = 0; k < q; k++) v -= c1[k] * M1[k * q + c];
-    c2[c] = v;
-  }
-  for (int c = 0; c < q; c++) {
-    double v1 = 0, v2 = 0;
-    for (int k = 0; k < q; k++) { v1 += c1[k] * Dg[k * q + c]; v2 += c2[k] * Dj[k * q + c]; }
-    P1[(int64_t)i * q + c] = (float)c1[c];
-    P2[(int64_t)i * q + c] = (float)c2[c];
-    P1D[(int64_t)i * q + c] = (float)v1;
-    P2D[(int64_t)i * q + c] = (float)v2;
-  }
+  sc2[lr][c] = v;
+  __syncthreads();
+  if (!live) return;
+  const int64_t o = (int64_t)i * q + c;
+  if (piv) { P1[o] = 0.f; P2[o] = 0.f; P1D[o] = 0.f; P2D[o] = 0.f; return; }
+  double v1 = 0, v2 = 0;
+  for (int k = 0; k < q; k++) { v1 += sc1[lr][k] * Dg[k * q + c]; v2 += sc2[lr][k] * Dj[k * q + c]; }
+  P1[o] = (float)sc1[lr][c];
+  P2[o] = (float)sc2[lr][c];
+  P1D[o] = (float)v1;
+  P2D[o] = (float)v2;
 }
 
 // New pivot rows (after both sweeps), for every l outside the pivots:
@@ -678,18 +679,18 @@ __global__ __launch_bounds__(256) void pair_fix_kernel(TabDims d, float* __restr
   const int g = single ? *single : ctrl->g_out, j = single ? g : ctrl->g_in, g0 = g * q, j0 = j * q;
   const double* Dg = small; const double* M1 = small + 2 * qq; const double* Dj = small + 3 * qq; const double* W2Dj = small + 4 * qq;
   const int64_t ld = d.d1;
-  int l = blockIdx.x * 256 + threadIdx.x;
-  if (l < d.d1) {
-    const bool in_g = (l >= g0 && l < g0 + q), in_j = (l >= j0 && l < j0 + q);
-    if (!in_g && !in_j) {
-      for (int r = 0; r < q; r++) {
+  {
+    // one thread per (row l, pivot row r): 4 rows x 64 pivot rows per workgroup
+    const int l = blockIdx.x * 4 + (threadIdx.x >> 6), r = threadIdx.x & 63;
+    if (l < d.d1 && r < q) {
+      const bool in_g = (l >= g0 && l < g0 + q), in_j = (l >= j0 && l < j0 + q);
+      if (!in_g && !in_j) {
         double vg = -(double)P1D[(int64_t)l * q + r];
         for (int c = 0; c < q; c++) vg += M1[r * q + c] * (double)P2D[(int64_t)l * q + c];
-        float vj = P2D[(int64_t)l * q + r];
-        int gr = g0 + r, jr = j0 + r;
+        const float vj = P2D[(int64_t)l * q + r];
+        const int gr = g0 + r, jr = j0 + r;
         if (l < gr) N[(int64_t)gr * ld + l] = (float)vg; else N[(int64_t)l * ld + gr] = (float)vg;
-        if (single) continue;
-        if (l < jr) N[(int64_t)jr * ld + l] = vj; else N[(int64_t)l * ld + jr] = vj;
+        if (!single) { if (l < jr) N[(int64_t)jr * ld + l] = vj; else N[(int64_t)l * ld + jr] = vj; }
       }
     }
   }
@@ -956,10 +957,10 @@ hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int force
   float* P2 = P1 + (int64_t)d.d1 * q;
   float* P1D = t.C1D;
   float* P2D = t.C2D;
-  hipLaunchKernelGGL(pair_panels_kernel, dim3(rb), dim3(256), (size_t)3 * q * q * 8, s, d, t.C1, t.C2, t.small, t.ctrl, P1, P2,
-                     P1D, P2D, single);
-  hipLaunchKernelGGL(pair_fix_kernel, dim3(rb), dim3(256), 0, s, d, t.N, t.Z, P1, P2, P1D, P2D, t.rZ1, t.rZ2, t.small, t.ctrl,
-                     t.dblk, t.kept, single);
+  hipLaunchKernelGGL(pair_panels_kernel, dim3((d.d1 + 3) / 4), dim3(256), 0, s, d, t.C1, t.C2, t.small, t.ctrl, P1, P2, P1D, P2D,
+                     single);
+  hipLaunchKernelGGL(pair_fix_kernel, dim3((d.d1 + 3) / 4), dim3(256), 0, s, d, t.N, t.Z, P1, P2, P1D, P2D, t.rZ1, t.rZ2, t.small,
+                     t.ctrl, t.dblk, t.kept, single);
   hipLaunchKernelGGL(pair_dblk_kernel, dim3(d.p), dim3(256), (size_t)4 * q * q * 4, s, d, P1, P2, P1D, P2D, t.ctrl, t.dblk, single);
   if (ev) hipEventRecord(ev[0], s);
   if (q == 1) {
@@ -978,7 +979,7 @@ hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int force
     hipLaunchKernelGGL(group_gram_kernel, dim3(d.p, nb * (nb + 1) / 2), dim3(256), 0, s, d, t.Z, t.gram, t.ctrl);
   }
   if (ev) hipEventRecord(ev[2], s);
-  hipLaunchKernelGGL(score_kernel, dim3(d.p), dim3(64), (size_t)2 * q * q * 8, s, d, t.kept, t.gram, t.dblk, t.score, t.ctrl);
+  hipLaunchKernelGGL(score_kernel, dim3(d.p), dim3(64), (size_t)2 * q * q * 8, s, d, t.kept, t.gram, t.dblk, t.score, t.ctrl, 1);
   return hipGetLastError();
 }
 
