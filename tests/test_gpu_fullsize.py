@@ -284,6 +284,39 @@ def test_cfg5_nested_schedule_properties():
     s.close()
 
 
+def test_cfg5_search_variants_agree():
+    """Benchmark layer's shape (32768 calibration rows), 2000 swaps three ways: delayed updates with look-ahead products,
+    delayed updates with one pass over Z per swap, and in-place updates.  The orders may only part at a tie (relative gap
+    below 1e-5), and the kept sets and objectives must agree at the end."""
+    import paper_2403_12983_amd as pkg
+    cfg = inp.CONFIGS["cfg5"].replace(n=32768)
+    X = gen_on_gpu(cfg)
+    W = inp.gen_W(cfg, DEV)
+    swaps = 2000
+    s = pkg.Solver(cfg.d1, cfg.m, cfg.p, cfg.q, cfg.k, swaps, X.dtype, W.dtype, DEV)
+    s.osscar_gram(X, True, W, cfg.lam_abs, cfg.lam_rel)
+    del X
+    runs = []
+    for fl in (0, pkg.OSSCAR_SEARCH_NO_LOOKAHEAD, pkg.OSSCAR_SEARCH_EAGER):
+        s.osscar_init_support()
+        r = s.osscar_local_search(swaps, 0.0, fl)
+        What, sup, obj = s.osscar_backsolve()
+        runs.append((r, sup, obj, s.osscar_get_timers()[3]))
+    a = runs[0][0]
+    assert a["accepted"] == swaps
+    for r, sup, obj, ms in runs[1:]:
+        assert r["accepted"] == swaps
+        for i in range(swaps):
+            if (a["trace_out"][i], a["trace_in"][i]) != (r["trace_out"][i], r["trace_in"][i]):
+                assert min(a["trace_gap"][i]) < GAP, (i, a["trace_gap"][i])
+                break
+        assert abs(obj - runs[0][2]) <= 1e-6 * obj and abs(r["obj_final"] - obj) <= 1e-4 * obj
+        if min(a["trace_gap"].min(axis=0)) > 1e-9 or np.array_equal(sup, runs[0][1]):
+            assert np.array_equal(sup, runs[0][1])
+    print("cfg5 shape, %d swaps: look-ahead %.0f ms, pass per swap %.0f ms, in place %.0f ms" % (swaps, runs[0][3], runs[1][3], runs[2][3]))
+    s.close()
+
+
 def test_cfg5_target_gram_sampled():
     """Cross-Gram of the benchmark layer's shape (32768 calibration rows) on sampled rows of G, float64 on the device."""
     import time
