@@ -483,7 +483,16 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
     __syncthreads();
     if (col < m) {
       const double y1 = L.y1[col], y2 = L.y2[col];
-      for (int s = slice; s < tau; s += 4) L.ZT[(int64_t)s * m + col] -= sa[s] * y1 + sb[s] * y2;
+      // independent read-modify-writes: issue several before waiting
+      int s = slice;
+      for (; s + 28 < tau; s += 32) {
+        double z[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) z[u] = L.ZT[(int64_t)(s + 4 * u) * m + col];
+#pragma unroll
+        for (int u = 0; u < 8; u++) L.ZT[(int64_t)(s + 4 * u) * m + col] = z[u] - (sa[s + 4 * u] * y1 + sb[s + 4 * u] * y2);
+      }
+      for (; s < tau; s += 4) L.ZT[(int64_t)s * m + col] -= sa[s] * y1 + sb[s] * y2;
       if (slice == 0) {
         L.ZT[(int64_t)tau * m + col] = y1 - M1 * y2;
         if (!single) L.ZT[(int64_t)(tau + 1) * m + col] = y2;
