@@ -214,6 +214,11 @@ osscar_status osscar_get_scalars(osscar_ctx* ctx, double* lambda_host, double* c
  * [8] the product G = H W inside finalize (one GEMM launch).  [9..11] reserved.  out_host: 12 doubles. */
 osscar_status osscar_get_timers(osscar_ctx* ctx, double* out_host);
 
+/* Host-only inspection of the Gram kernel's tile schedule (no device is touched): writes up to `capacity` (row, column)
+ * pairs of 128 x 128 tiles, in workgroup order, to out_host (2 ints each; (-1, -1) = padding) and returns the length of
+ * the schedule, or -1 for a bad d1.  Workgroup i runs on XCD i % 8. */
+int32_t osscar_debug_tile_schedule(int64_t d1, int32_t* out_host, int32_t capacity);
+
 const char* osscar_last_error(const osscar_ctx* ctx);
 
 #ifdef __cplusplus

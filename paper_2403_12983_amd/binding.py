@@ -20,7 +20,7 @@ _STATUS = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "ENOTPD", 4: "EHIP", 5: "ESTATE
 EXPORTED_SYMBOLS = ["osscar_workspace_bytes", "osscar_create", "osscar_destroy", "osscar_gram", "osscar_gram_target", "osscar_gram_conv",
                     "osscar_set_quadratic",
                     "osscar_init_support", "osscar_init_greedy", "osscar_local_search", "osscar_block_search", "osscar_apply_swap", "osscar_backsolve",
-                    "osscar_get_tensor", "osscar_get_scalars", "osscar_get_timers", "osscar_last_error"]
+                    "osscar_get_tensor", "osscar_get_scalars", "osscar_get_timers", "osscar_debug_tile_schedule", "osscar_last_error"]
 
 
 class OsscarError(RuntimeError):
@@ -76,10 +76,12 @@ def load_library():
     lib.osscar_get_tensor.argtypes = [vp, C.c_int, vp, C.c_size_t]
     lib.osscar_get_scalars.argtypes = [vp, C.POINTER(dbl), C.POINTER(dbl)]
     lib.osscar_get_timers.argtypes = [vp, C.POINTER(dbl)]
+    lib.osscar_debug_tile_schedule.restype = C.c_int32
+    lib.osscar_debug_tile_schedule.argtypes = [i64, C.POINTER(i32), i32]
     lib.osscar_last_error.restype = C.c_char_p
     lib.osscar_last_error.argtypes = [vp]
     for name in EXPORTED_SYMBOLS:
-        if name not in ("osscar_workspace_bytes", "osscar_last_error"):
+        if name not in ("osscar_workspace_bytes", "osscar_last_error", "osscar_debug_tile_schedule"):
             getattr(lib, name).restype = C.c_int
     _LIB = lib
     return lib

@@ -1109,6 +1109,11 @@ osscar_status osscar_get_scalars(osscar_ctx* c, double* lambda_host, double* c0_
   return OSSCAR_OK;
 }
 
+int32_t osscar_debug_tile_schedule(int64_t d1, int32_t* out_host, int32_t capacity) {
+  if (d1 <= 0 || d1 > 65536) return -1;
+  return gram_tile_schedule((int)((d1 + 127) / 128), out_host, capacity);
+}
+
 osscar_status osscar_get_timers(osscar_ctx* c, double* out) {
   if (!c || !out) return OSSCAR_EINVAL;
   for (int i = 0; i < 12; i++) out[i] = c->timers[i];

@@ -20,16 +20,25 @@ typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
 
 constexpr int GBK = 64;            // tokens per LDS stage
 
-// Tile order: strips of 4 tile rows go to the XCDs in turn (block index modulo 8 selects the XCD); within a strip
-// the tiles are walked in 4 x 8 blocks.  Lists are padded with (-1, -1) to equal length.
+// Tile order: strips of 4 tile rows are dealt to the 8 XCDs (block index modulo 8 selects the XCD), largest strip first to
+// the XCD with the least work so far, so that all eight finish together; within a strip the tiles are walked in 4 x 8
+// blocks.  Lists are padded with (-1, -1) to equal length.
 static void build_tile_list(int tm_count, std::vector<int2>& out) {
   constexpr int NX = 8, RB = 4, CB = 8;
   std::vector<std::vector<int2>> lists(NX);
-  int strips = (tm_count + RB - 1) / RB;
+  const int strips = (tm_count + RB - 1) / RB;
+  std::vector<int> owner(strips, 0);
+  std::vector<long> load(NX, 0);
+  for (int sidx = strips - 1; sidx >= 0; sidx--) {            // strips grow with the row index: last = largest
+    const int r0 = sidx * RB, r1 = std::min(tm_count, r0 + RB);
+    long tiles = 0;
+    for (int r = r0; r < r1; r++) tiles += r + 1;
+    int best = 0;
+    for (int x = 1; x < NX; x++) if (load[x] < load[best]) best = x;
+    owner[sidx] = best; load[best] += tiles;
+  }
   for (int sidx = 0; sidx < strips; sidx++) {
-    // boustrophedon deal: strips grow with the row index, so alternate the direction to balance the XCDs
-    const int turn = sidx / NX, pos = sidx % NX;
-    std::vector<int2>& L = lists[(turn & 1) ? NX - 1 - pos : pos];
+    std::vector<int2>& L = lists[owner[sidx]];
     int r0 = sidx * RB, r1 = std::min(tm_count, r0 + RB);
     for (int c0 = 0; c0 < r1; c0 += CB)
       for (int r = r0; r < r1; r++)
@@ -281,6 +290,15 @@ hipError_t launch_im2col_transpose(const void* F, int is_bf16, const ConvSpec& c
   hipLaunchKernelGGL(im2col_transpose_kernel, dim3((d1 + 31) / 32, (unsigned)((nr + 31) / 32)), dim3(256), 0, s, F, is_bf16, cs, r0, nr, d1,
                      Xt, ldxt);
   return hipGetLastError();
+}
+
+// host-only view of the schedule for tests: fills out[0 .. 2*count) with (row, column) pairs, returns the list length
+int gram_tile_schedule(int tiles_per_side, int32_t* out, int capacity) {
+  std::vector<int2> t;
+  build_tile_list(tiles_per_side, t);
+  if (out)
+    for (size_t i = 0; i < t.size() && (int)i < capacity; i++) { out[2 * i] = t[i].x; out[2 * i + 1] = t[i].y; }
+  return (int)t.size();
 }
 
 // all tiles of an R x C grid, in 4 x 8 blocks dealt to the XCDs in turn

@@ -58,3 +58,32 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(b, "lib_path", lambda: str(tmp_path / "nope.so"))
     with pytest.raises(FileNotFoundError):
         b.load_library()
+
+
+@pytest.mark.parametrize("d1", [64, 328, 2048, 8192, 28672, 28700])
+def test_gram_tile_schedule_covers_the_lower_triangle_once_and_balances_the_xcds(d1):
+    import numpy as np
+    pkg, lib = _lib()
+    tiles = (d1 + 127) // 128
+    n = lib.osscar_debug_tile_schedule(d1, None, 0)
+    assert n > 0 and n % 8 == 0
+    buf = (C.c_int32 * (2 * n))()
+    assert lib.osscar_debug_tile_schedule(d1, buf, n) == n
+    sched = np.frombuffer(buf, dtype=np.int32).reshape(n, 2)
+    real = sched[sched[:, 0] >= 0]
+    assert np.all(real[:, 1] <= real[:, 0]) and np.all(real >= 0) and np.all(real < tiles)
+    assert len(real) == tiles * (tiles + 1) // 2
+    assert len({(int(r), int(c)) for r, c in real}) == len(real)                      # every tile exactly once
+    # the length the workspace query reserves for it
+    assert n <= 8 * (tiles * tiles // 2 + tiles + 8)
+    # workgroup i runs on XCD i % 8: equal work per XCD up to one strip of tile rows
+    per_xcd = np.array([(sched[x::8, 0] >= 0).sum() for x in range(8)])
+    assert per_xcd.max() - per_xcd.min() <= 4 * tiles
+    if tiles >= 64:
+        assert per_xcd.max() <= 1.05 * per_xcd.mean()
+    # tiles that run together on an XCD (64 consecutive slots) share few column panels
+    if tiles >= 64:
+        x0 = sched[0::8][:64]
+        x0 = x0[x0[:, 0] >= 0]
+        assert len(set(x0[:, 0].tolist()) | set(x0[:, 1].tolist())) <= 24
+    assert lib.osscar_debug_tile_schedule(0, None, 0) == -1
