@@ -42,6 +42,11 @@ SMALL = {
     "cfg4s": lambda: inp.scaled(inp.CONFIGS["cfg4"], p=8, m=96, n=2100, k=5, swaps=10, mix=0.7),
     # bf16 with d1 not a multiple of 8: takes the generic Gram path
     "cfg5odd": lambda: inp.scaled(inp.CONFIGS["cfg5"], p=203, m=50, n=777, k=101, swaps=30),
+    # other seeds of the same recipes
+    "cfg1+1": lambda: inp.CONFIGS["cfg1"].replace(seed=inp.CONFIGS["cfg1"].seed + 1),
+    "cfg2s+1": lambda: inp.scaled(inp.CONFIGS["cfg2"], p=24, m=40, n=1500, k=12, swaps=20, mix=0.5, seed=inp.CONFIGS["cfg2"].seed + 1),
+    "cfg3s+2": lambda: inp.scaled(inp.CONFIGS["cfg3"], p=328, m=136, n=3000, k=160, swaps=60, seed=inp.CONFIGS["cfg3"].seed + 2),
+    "cfg4s+1": lambda: inp.scaled(inp.CONFIGS["cfg4"], p=8, m=96, n=2100, k=5, swaps=10, mix=0.7, seed=inp.CONFIGS["cfg4"].seed + 1),
 }
 
 
