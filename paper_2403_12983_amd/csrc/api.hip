@@ -228,10 +228,11 @@ TabPtrs ptrs(const osscar_ctx* c) {
 
 hipError_t gemm(hipStream_t s, int M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb, const float* Cin,
                 int64_t ldcin, float* C, int64_t ldc, double alpha, double beta, double diag_add = 0.0, int lower_only = 0,
-                int trans_b = 0) {
+                int trans_b = 0, int acc_f32 = 0) {
   GemmArgs g{};
   g.M = M; g.N = N; g.K = K; g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.Cin = Cin; g.ldcin = ldcin; g.C = C; g.ldc = ldc;
   g.alpha = alpha; g.beta = beta; g.diag_add = diag_add; g.c_is_f64 = 0; g.lower_only = lower_only; g.trans_b = trans_b;
+  g.acc_f32 = acc_f32;
   return launch_gemm_f64acc(g, s);
 }
 
@@ -266,7 +267,8 @@ osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b, const float* 
     HIPCHK(c, gemm(s, kr, kr, kr, b.HKK, kr, b.P, kr, nullptr, 0, b.T1, kr, -1.0, 0.0, 1.0));
     HIPCHK(c, launch_absmax(b.T1, (int64_t)kr * kr, c->partial, s));
     // P + P (I - H P) is symmetric up to rounding: compute its lower triangle and mirror it
-    HIPCHK(c, gemm(s, kr, kr, kr, b.P, kr, b.T1, kr, b.P, kr, b.T2, kr, 1.0, 1.0, 0.0, 1));
+    // (the correction P (I - H P) is about 1e-5 of P: float32 accumulation of it is far below P's own rounding)
+    HIPCHK(c, gemm(s, kr, kr, kr, b.P, kr, b.T1, kr, b.P, kr, b.T2, kr, 1.0, 1.0, 0.0, 1, 0, 1));
     hipLaunchKernelGGL(mirror_from_lower_kernel, dim3(grid_for((int64_t)kr * kr)), dim3(256), 0, s, b.T2, b.P, kr);
     double part[256]; int32_t bad = 0;
     HIPCHK(c, hipMemcpyAsync(part, c->partial, sizeof part, hipMemcpyDeviceToHost, s));
@@ -1005,7 +1007,7 @@ osscar_status osscar_backsolve(osscar_ctx* c, void* What, int64_t ldw_hat, int32
     bool ok = false;
     for (int step = 0; step < 3 && !ok; step++) {
       HIPCHK(c, gemm(s, kr, m, kr, b.HKK, kr, b.B, m, b.GK, m, b.T4, m, -1.0, 1.0));      // residual
-      HIPCHK(c, gemm(s, kr, m, kr, b.P, kr, b.T4, m, nullptr, 0, b.T3, m, 1.0, 0.0));      // correction
+      HIPCHK(c, gemm(s, kr, m, kr, b.P, kr, b.T4, m, nullptr, 0, b.T3, m, 1.0, 0.0, 0.0, 0, 0, 1));   // correction (small: float32 accumulation)
       HIPCHK(c, launch_dot64(b.T3, b.T3, (int64_t)kr * m, c->scal + 9, c->partial, s));
       HIPCHK(c, launch_dot64(b.B, b.B, (int64_t)kr * m, c->scal + 10, c->partial + 1024, s));
       hipLaunchKernelGGL(add_inplace_kernel, dim3(grid_for((int64_t)kr * m)), dim3(256), 0, s, b.B, b.T3, (int64_t)kr * m);
