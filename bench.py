@@ -6,7 +6,7 @@ calibration rows, finalize (ridge, G = H W), magnitude support + state build, th
 final back-solve.  X and W are resident in HBM before the timed region starts.
 
 Prints one JSON line.  `value` is seconds per layer (lower is better).  `roofline` describes the kernel the
-layer time is dominated by, the float64-accumulating MFMA GEMM, on its largest launch (G = H W).
+layer time is dominated by, the float64-accumulating MFMA GEMM, on its largest launch (V = P H_{K,Kc}).
 `roofline_gram` describes the bf16 MFMA Gram kernel, and `cpu_baseline` the float64 oracle timed on this
 box's host cores on a reduced layer of the same recipe."""
 from __future__ import annotations
@@ -18,6 +18,7 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
+GEMM_TRAFFIC_CFG5 = 52.7e9   # bytes; see profiles/gemm_f64acc_cfg5_pmc.md
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -144,7 +145,7 @@ def main():
             tm = s.osscar_get_timers()
             upd_n += tm[5] / 1e3
             upd_z += tm[7] / 1e3
-            gemm_ms += tm[8]
+            gemm_ms += tm[9]
         info.update(obj0=obj0, obj=obj, iters=r["iters"], accepted=r["accepted"], tracked=r["obj_final"])
 
     for _ in range(a.warmup):
@@ -169,13 +170,14 @@ def main():
     # Per-swap state update as SURVEY counts it: read + write of P, V (= lower triangle of N) and B, R (= Z)
     bytes_swap_alg = 2 * 4 * (d1 * d1 // 2) + 2 * 4 * d1 * m
     ms_swap = 1e3 * phases["search"] / max(info["iters"], 1)
-    # Dominant kernel of the layer: the float64-accumulating MFMA GEMM (G = H W, the inverse's refinement, B, V, S, R,
-    # the look-ahead products of the search, the back-solve's residuals).  Its largest launch, G = H W inside finalize, is
-    # timed by HIP events on the library's stream (timer slot 8): 2 d1^2 m flops on v_mfma_f64_16x16x4_f64.
-    g_flops = 2.0 * d1 * d1 * m
-    g_bytes = 4.0 * (d1 * d1 + 2 * d1 * m)                       # read H and W once, write G once
+    # Dominant kernel of the layer: the float64-accumulating MFMA GEMM (the inverse's refinement, B, V, S, R, the look-ahead
+    # products of the search, the back-solve's residual).  Its largest launch, V = P H_{K,Kc} in the state build, is timed by
+    # HIP events on the library's stream (timer slot 9): 2 kr^2 cr flops on v_mfma_f64_16x16x4_f64.
+    kr, cr = cfg.k * cfg.q, d1 - cfg.k * cfg.q
+    g_flops = 2.0 * kr * kr * cr
+    g_bytes = 4.0 * (kr * kr + 2 * kr * cr)                      # read P and H_{K,Kc} once, write V once
     # HBM bytes of that launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/gemm_f64acc_cfg5_pmc.md), cfg5 only
-    g_traffic = 128.2e9 if a.config == "cfg5" else None
+    g_traffic = GEMM_TRAFFIC_CFG5 if a.config == "cfg5" else None
     out = {
         "metric": "OPT-30B fc2 layer prune time", "value": t_layer, "unit": "s", "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": 1e3 * t_layer, "higher_is_better": False, "scaling": "weak",
@@ -193,7 +195,7 @@ def main():
         "gram_tflops_syrk": gram_flops / phases["gram"] / 1e12,
         "gram_tflops_full_equiv": 2 * n * d1 * d1 / phases["gram"] / 1e12,
         "objective": {"initial": info["obj0"], "final": info["obj"], "tracked": info["tracked"]},
-        "roofline": {"kernel": "gemm_f64acc_kernel<float>, launch G = H W (float32 operands, float64 MFMA accumulation)",
+        "roofline": {"kernel": "gemm_f64acc_kernel<float>, launch V = P H_{K,Kc} (float32 operands, float64 MFMA accumulation)",
                      "bound": "mfma", "achieved": g_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None, "peak": 78.6,
                      "unit": "TFLOP/s", "frac": g_flops / (gemm_ms * 1e-3) / 1e12 / 78.6 if gemm_ms > 0 else None,
                      "traffic": g_traffic, "flops_per_launch": g_flops, "algorithmic_bytes_per_launch": g_bytes,

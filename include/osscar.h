@@ -211,7 +211,9 @@ osscar_status osscar_get_scalars(osscar_ctx* ctx, double* lambda_host, double* c
  * per batch of iterations: eager search [5] mean duration of one bulk update of N, [7] of one update of Z;
  * delayed-update search [5] mean duration of the two kernels that produce w = Z [y1 y2] (a pass over Z only for a
  * pivot whose products were not computed ahead), [7] of all kernels of that iteration from there on.
- * [8] the product G = H W inside finalize (one GEMM launch).  [9..11] reserved.  out_host: 12 doubles. */
+ * [8] the product G = H W inside finalize (one GEMM launch, or the three bf16 products and their repacking when W is
+ * bf16).  [9] the product V = P H_{K,Kc} of the last state build (one GEMM launch).  [10..11] reserved.
+ * out_host: 12 doubles. */
 osscar_status osscar_get_timers(osscar_ctx* ctx, double* out_host);
 
 /* Host-only inspection of the Gram kernel's tile schedule (no device is touched): writes up to `capacity` (row, column)

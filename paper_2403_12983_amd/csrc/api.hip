@@ -341,7 +341,9 @@ osscar_status build_state(osscar_ctx* c, double* obj_out, const float* B_known =
     HIPCHK(c, launch_gather(c->H, d1, c->rowsC, cr, c->rowsK, kr, HCK, kr, s));
     HIPCHK(c, launch_gather(c->H, d1, c->rowsC, cr, c->rowsC, cr, S, cr, s));
     HIPCHK(c, launch_gather(c->G, m, c->rowsC, cr, nullptr, m, R, m, s));
+    HIPCHK(c, hipEventRecord(c->ev_s[0][0], s));
     HIPCHK(c, gemm(s, kr, cr, kr, b.P, kr, HKC, cr, nullptr, 0, V, cr, 1.0, 0.0));             // V = P H_{K,Kc}
+    HIPCHK(c, hipEventRecord(c->ev_s[0][1], s));
     HIPCHK(c, gemm(s, cr, cr, kr, HCK, kr, V, cr, S, cr, S, cr, -1.0, 1.0, 0.0, 1));            // S = H_cc - H_cK V (lower)
     HIPCHK(c, gemm(s, cr, m, kr, HCK, kr, b.B, m, R, m, R, m, -1.0, 1.0));                      // R = G_c - H_cK B
     HIPCHK(c, launch_scatter(V, cr, c->rowsK, kr, c->rowsC, cr, c->N, d1, 1.f, 0, s));
@@ -352,8 +354,9 @@ osscar_status build_state(osscar_ctx* c, double* obj_out, const float* B_known =
   HIPCHK(c, launch_scatter_rows(b.B, m, c->rowsK, kr, m, c->Z, m, 0, s));
   HIPCHK(c, launch_refresh_scores(dims(c), ptrs(c), s));
   double obj = 0;
-  st = objective_from(c, b.GK, b.B, &obj);
+  st = objective_from(c, b.GK, b.B, &obj);     // synchronises the stream
   if (st != OSSCAR_OK) return st;
+  if (cr > 0) { float ms = 0; hipEventElapsedTime(&ms, c->ev_s[0][0], c->ev_s[0][1]); c->timers[9] = ms; }
   if (obj_out) *obj_out = obj;
   return OSSCAR_OK;
 }
@@ -513,8 +516,28 @@ static osscar_status gram_impl(osscar_ctx* c, const char* who, int target, const
     HIPCHK(c, launch_dot64(Wf, Wf, (int64_t)d1 * m, c->scal + 2, c->partial, s));
     HIPCHK(c, hipMemcpyAsync(&yy, c->scal + 12, 8, hipMemcpyDeviceToHost, s));
   } else {
+    // G = H W.  bf16 W: three bf16-MFMA products with the pieces of H, in the memory the float64 Gram accumulator has
+    // just left; otherwise (or if that memory is too small) the float64-accumulating GEMM.
+    const int64_t prow = std::min<int64_t>(PACK_ROWS, ((int64_t)d1 + 63) / 64 * 64);
+    const size_t ph_bytes = align_up((size_t)prow * ((d1 + 127) / 128 * 128) * 2), pw_bytes = align_up((size_t)prow * ((m + 127) / 128 * 128) * 2);
+    const size_t g64_bytes = align_up((size_t)d1 * m * 8), tl_entries = rect_tile_entries(d1, m);
+    const bool split_ok = c->desc.w_dtype == OSSCAR_BF16 && (d1 % 8 == 0) && (m % 8 == 0) && (ldw % 8 == 0) &&
+                          ((reinterpret_cast<uintptr_t>(W) & 15) == 0) &&
+                          g64_bytes + ph_bytes + pw_bytes + align_up(tl_entries * 8) <= (size_t)d1 * d1 * 8;
     HIPCHK(c, hipEventRecord(c->ev_s[0][0], s));
-    HIPCHK(c, gemm(s, d1, m, d1, c->H, d1, Wf, m, nullptr, 0, c->G, m, 1.0, 0.0));
+    if (split_ok) {
+      char* base = reinterpret_cast<char*>(H64);
+      double* Gacc = reinterpret_cast<double*>(base);
+      void* pack_h = base + g64_bytes;
+      void* pack_w = base + g64_bytes + ph_bytes;
+      int2* tl = reinterpret_cast<int2*>(base + g64_bytes + ph_bytes + pw_bytes);
+      hipLaunchKernelGGL(fill_f64_kernel, dim3(grid_for((int64_t)d1 * m)), dim3(256), 0, s, Gacc, (int64_t)d1 * m, 0.0);
+      hipLaunchKernelGGL(fill_f64_kernel, dim3(1), dim3(64), 0, s, c->scal + 13, (int64_t)1, 0.0);
+      HIPCHK(c, launch_hw_split(c->H, d1, W, ldw, m, Gacc, tl, tl_entries, pack_h, pack_w, prow, s));
+      HIPCHK(c, launch_finalize_G(Gacc, Wf, c->scal + 13, c->G, (int64_t)d1 * m, s));
+    } else {
+      HIPCHK(c, gemm(s, d1, m, d1, c->H, d1, Wf, m, nullptr, 0, c->G, m, 1.0, 0.0));
+    }
     HIPCHK(c, hipEventRecord(c->ev_s[0][1], s));
     HIPCHK(c, launch_dot64(Wf, c->G, (int64_t)d1 * m, c->scal + 2, c->partial, s));
   }

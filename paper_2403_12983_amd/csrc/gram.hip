@@ -378,6 +378,86 @@ hipError_t launch_gram_packed(const void* Xc, int64_t n_c, int64_t ldx, int d1, 
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------
+// G = H W on the bf16 matrix cores for bf16 W: H (float32) is split into three bf16 pieces H = H1 + H2 + H3 (each the
+// round-to-nearest bf16 of what the previous ones left, so the sum is exact to 2^-25), and H_i^T W = H_i W (H is
+// symmetric) runs on the packed kernel above: products of two bf16 numbers are exact in float32, the accumulation is
+// restarted every 1024 rows and ends in float64, as for the Gram.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t bf16_rne_bits(float x) {
+  const uint32_t u = __float_as_uint(x);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+// piece 0, 1, 2 of the split, packed like gram_pack_kernel packs a bf16 matrix (rows = the contraction index)
+__global__ __launch_bounds__(256) void gram_pack_split_kernel(const float* __restrict__ A, int64_t n_c, int64_t lda, int cols,
+                                                               int npanels, int piece, uint4* __restrict__ Xp) {
+  const int tid = threadIdx.x;
+  const int panel = blockIdx.x * 2 + (tid >> 7);
+  if (panel >= npanels) return;
+  const int kg = (tid & 127) >> 4, cg = tid & 15;
+  const int col = panel * 128 + cg * 8;
+  const bool live = col < cols;
+  const int64_t row0 = (int64_t)blockIdx.y * GBK + kg * 8;
+  uint32_t h[8][8];
+#pragma unroll
+  for (int r = 0; r < 8; r++) {
+    const int64_t row = row0 + r;
+    float v[8];
+    if (live && row < n_c) {
+      const float4 a = *reinterpret_cast<const float4*>(A + row * lda + col);
+      const float4 b = *reinterpret_cast<const float4*>(A + row * lda + col + 4);
+      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; j++) v[j] = 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+      float x = v[j];
+      uint32_t bits = bf16_rne_bits(x);
+      for (int p = 0; p < piece; p++) { x -= __uint_as_float(bits << 16); bits = bf16_rne_bits(x); }
+      h[r][j] = bits;
+    }
+  }
+  uint4* out = Xp + ((int64_t)blockIdx.y * npanels + panel) * PK_SLOTS + kg * 128 + cg * 8;
+#pragma unroll
+  for (int j = 0; j < 8; j++)
+    out[j] = uint4{h[0][j] | (h[1][j] << 16), h[2][j] | (h[3][j] << 16), h[4][j] | (h[5][j] << 16), h[6][j] | (h[7][j] << 16)};
+}
+
+// G64 (d1 x m, float64, zeroed by the caller) += H W.  H: d1 x d1 float32 (ld = d1, d1 % 8 == 0, 16-byte aligned), W: d1 x m bf16
+// (m % 8 == 0, ldw % 8 == 0, 16-byte aligned).  pack_h: pack_rows * 128*ceil(d1/128) * 2 bytes, pack_w likewise for m.
+hipError_t launch_hw_split(const float* H, int d1, const void* W, int64_t ldw, int m, double* G64, int2* tile_buf,
+                           size_t tile_buf_entries, void* pack_h, void* pack_w, int64_t pack_rows, hipStream_t s) {
+  if (pack_rows < GBK || pack_rows % GBK) return hipErrorInvalidValue;
+  const int npanels = (d1 + 127) / 128, npanels_w = (m + 127) / 128;
+  std::vector<int2> tiles;
+  build_rect_tile_list(npanels, npanels_w, tiles);
+  if (tiles.size() > tile_buf_entries) return hipErrorInvalidValue;
+  hipError_t e = hipMemcpyAsync(tile_buf, tiles.data(), tiles.size() * sizeof(int2), hipMemcpyHostToDevice, s);
+  if (e != hipSuccess) return e;
+  e = hipStreamSynchronize(s);   // the host vector dies at return
+  if (e != hipSuccess) return e;
+  const int window = 16;
+  const size_t shmem = (size_t)2 * 2 * PK_SLOTS * 16;
+  for (int64_t r0 = 0; r0 < d1; r0 += pack_rows) {
+    const int64_t nr = std::min<int64_t>(pack_rows, d1 - r0);
+    const int nstages = (int)((nr + GBK - 1) / GBK);
+    hipLaunchKernelGGL(gram_pack_kernel, dim3((npanels_w + 1) / 2, nstages), dim3(256), 0, s,
+                       reinterpret_cast<const uint16_t*>(W) + r0 * ldw, nr, ldw, m, npanels_w, reinterpret_cast<uint4*>(pack_w));
+    int per = 0;
+    const int splits = split_stages(npanels * npanels_w, nstages, &per);
+    for (int piece = 0; piece < 3; piece++) {
+      hipLaunchKernelGGL(gram_pack_split_kernel, dim3((npanels + 1) / 2, nstages), dim3(256), 0, s, H + r0 * d1, nr, (int64_t)d1, d1,
+                         npanels, piece, reinterpret_cast<uint4*>(pack_h));
+      hipLaunchKernelGGL(gram_packed_kernel, dim3((unsigned)tiles.size(), splits), dim3(256), shmem, s,
+                         reinterpret_cast<const uint4*>(pack_h), (int64_t)npanels * PK_SLOTS, reinterpret_cast<const uint4*>(pack_w),
+                         (int64_t)npanels_w * PK_SLOTS, nstages, d1, m, m, G64, tile_buf, per, window, 0);
+    }
+  }
+  return hipGetLastError();
+}
+
 // sum of squares of a rows x cols matrix (float32 or bf16), added to *acc
 __global__ __launch_bounds__(256) void sumsq_kernel(const void* __restrict__ A, int is_bf16, int64_t rows, int64_t cols, int64_t ld,
                                                      double* __restrict__ acc) {

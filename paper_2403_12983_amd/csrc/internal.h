@@ -45,6 +45,9 @@ hipError_t launch_im2col_transpose(const void* F, int is_bf16, const ConvSpec& c
 // Yc (optional, bf16 n_c x m): also G64 (d1 x m, float64) += Xc^T Yc, with its own tile list (>= 8 * (ceil(d1/128) *
 // ceil(m/128) / 8 + 64) entries) and pack buffer (pack_rows * 128*ceil(m/128) * 2 bytes)
 int gram_tile_schedule(int tiles_per_side, int32_t* out, int capacity);   // host only: the tile order of the SYRK kernel
+// G64 (zeroed by the caller) += H W for bf16 W through three bf16 pieces of the float32 H (see gram.hip)
+hipError_t launch_hw_split(const float* H, int d1, const void* W, int64_t ldw, int m, double* G64, int2* tile_buf,
+                           size_t tile_buf_entries, void* pack_h, void* pack_w, int64_t pack_rows, hipStream_t s);
 hipError_t launch_sumsq(const void* A, int is_bf16, int64_t rows, int64_t cols, int64_t ld, double* acc, hipStream_t s);
 hipError_t launch_finalize_G(const double* G64, const float* Wf, const double* lambda_dev, float* G, int64_t n, hipStream_t s);
 hipError_t launch_transpose_to_f32(const void* X, int is_bf16, int64_t rows, int64_t cols, int64_t ldx, float* Xt,
