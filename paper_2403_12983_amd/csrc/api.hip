@@ -128,7 +128,7 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
   double* score = cv.take<double>(p);
   double* gram = cv.take<double>(p * q * q);
   double* dblk = cv.take<double>(p * q * q);
-  double* small = cv.take<double>(std::max<int64_t>(16 * q * q, 64 * 64));
+  double* small = cv.take<double>(std::max<int64_t>(16 * q * q, INV_NB * INV_NB));
   double* scal = cv.take<double>(1024);
   double* partial = cv.take<double>(2048);
   int32_t* kept = cv.take<int32_t>(p);
@@ -171,7 +171,7 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
     gram_phase += align_up((size_t)d1 * m * 8) + align_up(target_stage_bytes(m)) + align_up(rect_tile_entries(d1, m) * 8);
   auto init_bytes = [&](size_t a, size_t b) {   // kept rows a, candidate rows b
     return 4 * align_up(a * a * 4) + 3 * align_up(a * b * 4) + align_up(b * b * 4) + 4 * align_up(a * m * 4) + align_up(b * m * 4) +
-           3 * align_up(a * 64 * 4) + 4096;
+           3 * align_up(a * INV_NB * 4) + 4096;
   };
   size_t init_phase = init_bytes(kr, cr);
   if (ds.from_dense) {   // the nested schedule visits every kept-row count from d1 down to kr
@@ -260,7 +260,7 @@ osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b, const float* 
   HIPCHK(c, launch_gather(c->H, c->d1, c->rowsK, kr, c->rowsK, kr, b.HKK, kr, s));
   HIPCHK(c, launch_gather(c->H, c->d1, c->rowsK, kr, c->rowsK, kr, b.P, kr, s));
   HIPCHK(c, hipMemsetAsync(c->notpd, 0, 64 * 4, s));
-  HIPCHK(c, spd_inverse_inplace(b.P, kr, b.panels, b.panels + (int64_t)kr * 64, c->small, c->notpd, s));
+  HIPCHK(c, spd_inverse_inplace(b.P, kr, b.panels, b.panels + (int64_t)kr * INV_NB, c->small, c->notpd, s));
   // Newton-Schulz: P <- P + P (I - H_KK P), residual accumulated in float64
   double last_resid = 1.0;
   for (int step = 0; step < 3; step++) {
@@ -305,7 +305,7 @@ InvBufs carve_inv(osscar_ctx* c, Carve& cv) {
   InvBufs b;
   b.HKK = cv.take<float>(kr * kr); b.P = cv.take<float>(kr * kr); b.T1 = cv.take<float>(kr * kr); b.T2 = cv.take<float>(kr * kr);
   b.GK = cv.take<float>(kr * m); b.B = cv.take<float>(kr * m); b.T3 = cv.take<float>(kr * m); b.T4 = cv.take<float>(kr * m);
-  b.panels = cv.take<float>(3 * kr * 64);
+  b.panels = cv.take<float>(3 * kr * INV_NB);
   return b;
 }
 

@@ -90,9 +90,10 @@ hipError_t launch_scatter(const float* src, int64_t lds, const int32_t* rows, in
 hipError_t launch_mirror_lower(float* A, int n, int64_t lda, hipStream_t s);
 hipError_t launch_absmax(const float* A, int64_t n, double* out, hipStream_t s);
 
+constexpr int INV_NB = 128;   // pivot block width of the sweep inverse
 // In-place inverse of the symmetric positive definite n x n matrix A (full storage on entry and exit)
-// by block sweeps of width nb; panel/work buffers are caller-provided: panel (n*nb), panelD (n*nb),
-// small (8*nb*nb doubles).  notpd_flag (device int) is set if a pivot block is not definite.
+// by block sweeps of width INV_NB; panel/work buffers are caller-provided: panel (n*INV_NB), panelD (2*n*INV_NB),
+// small (INV_NB*INV_NB doubles).  notpd_flag (device int) is set if a pivot block is not definite.
 hipError_t spd_inverse_inplace(float* A, int n, float* panel, float* panelD, double* small, int32_t* notpd_flag,
                                hipStream_t s);
 

@@ -21,26 +21,68 @@ namespace osscar {
 // ------------------------------------------------------------------------------------------------
 // small dense helpers (float64, one workgroup, matrices in global or shared memory)
 // ------------------------------------------------------------------------------------------------
-// In-place inverse of the n x n matrix A (leading dimension n) by Gauss-Jordan without pivoting; valid for
-// definite matrices of either sign.  want_sign = +1 / -1: every pivot must have that sign, else *bad = 1.
-__device__ void small_inverse(double* A, int n, int want_sign, int32_t* bad, double* colbuf) {
-  const int tid = threadIdx.x, nt = blockDim.x;
-  for (int k = 0; k < n; k++) {
-    __syncthreads();
-    double piv = A[k * n + k];
-    if (!(piv * want_sign > 0.0)) { if (tid == 0) *bad = 1; piv = want_sign; }
-    double d = 1.0 / piv;
-    for (int i = tid; i < n; i += nt) colbuf[i] = A[i * n + k];
-    __syncthreads();
-    for (int j = tid; j < n; j += nt) if (j != k) A[k * n + j] *= d;
-    __syncthreads();
-    for (int idx = tid; idx < n * n; idx += nt) {
-      int i = idx / n, j = idx % n;
-      if (i != k && j != k) A[idx] -= colbuf[i] * A[k * n + j];
+// In-place inverse of the n x n matrix A (leading dimension n, n <= 16 T, shared or global memory) by Gauss-Jordan without
+// pivoting; valid for definite matrices of either sign.  want_sign = +1 / -1: every pivot must have that sign, else
+// *bad = 1.  Called by all 256 threads of a workgroup: thread (ti, tj) of a 16 x 16 grid keeps the T x T block with rows
+// ti*T.. and columns tj*T.. in registers (rows and columns past n behave as an identity block); every step broadcasts the
+// pivot row and column through buf (64 T doubles of shared memory, two halves used in turn: one barrier per step).
+template <int T>
+__device__ void small_inverse(double* A, int n, int want_sign, int32_t* bad, double* buf) {
+  const int tid = threadIdx.x, ti = tid >> 4, tj = tid & 15;
+  double r[T][T];
+  __syncthreads();
+#pragma unroll
+  for (int a = 0; a < T; a++)
+#pragma unroll
+    for (int b = 0; b < T; b++) {
+      const int i = ti * T + a, j = tj * T + b;
+      r[a][b] = (i < n && j < n) ? A[i * n + j] : (i == j ? 1.0 : 0.0);
     }
-    __syncthreads();
-    for (int i = tid; i < n; i += nt) A[i * n + k] = (i == k) ? d : -colbuf[i] * d;
+  bool flag = false;
+  for (int k0 = 0; k0 < n; k0 += T) {
+#pragma unroll
+    for (int kk = 0; kk < T; kk++) {
+      const int k = k0 + kk;
+      if (k < n) {                                   // uniform over the workgroup
+        double* rowb = buf + (k & 1) * (32 * T);
+        double* colb = rowb + 16 * T;
+        if (ti == k0 / T) {
+#pragma unroll
+          for (int b = 0; b < T; b++) rowb[tj * T + b] = r[kk][b];
+        }
+        if (tj == k0 / T) {
+#pragma unroll
+          for (int a = 0; a < T; a++) colb[ti * T + a] = r[a][kk];
+        }
+        __syncthreads();
+        double piv = rowb[k];
+        if (!(piv * want_sign > 0.0)) { flag = true; piv = want_sign; }
+        const double d = 1.0 / piv;
+        double rs[T], cs[T];
+#pragma unroll
+        for (int b = 0; b < T; b++) rs[b] = rowb[tj * T + b] * d;
+#pragma unroll
+        for (int a = 0; a < T; a++) cs[a] = colb[ti * T + a];
+#pragma unroll
+        for (int a = 0; a < T; a++)
+#pragma unroll
+          for (int b = 0; b < T; b++) {
+            const int i = ti * T + a, j = tj * T + b;
+            if (i == k) r[a][b] = (j == k) ? d : rs[b];
+            else if (j == k) r[a][b] = -cs[a] * d;
+            else r[a][b] -= cs[a] * rs[b];
+          }
+      }
+    }
   }
+  if (flag && tid == 0) *bad = 1;
+#pragma unroll
+  for (int a = 0; a < T; a++)
+#pragma unroll
+    for (int b = 0; b < T; b++) {
+      const int i = ti * T + a, j = tj * T + b;
+      if (i < n && j < n) A[i * n + j] = r[a][b];
+    }
   __syncthreads();
 }
 
@@ -192,42 +234,51 @@ __global__ __launch_bounds__(256) void extract_panel_kernel(const float* __restr
   for (int c = 0; c < w; c++) C[(int64_t)i * w + c] = nsym(N, ld, i, t0 + c);
 }
 
-// out[i][c] = sum_k C[i][k] * D[k][c]  (D: w x w float64), rows in [t0, t0+w) are written as zero if zero_pivot.
-// Optionally also writes Cb = C with the pivot rows zeroed.
+// out[i][c] = sum_k C[i][k] * D[k][c]  (D: w x w float64, w <= 128), rows in [t0, t0+w) are written as zero if zero_pivot.
+// Optionally also writes Cb = C with the pivot rows zeroed.  16 rows per workgroup: their C values are broadcast from
+// LDS, thread (h, c) sums 8 rows of column c in float64, k ascending.
 __global__ __launch_bounds__(256) void panel_times_small_kernel(const float* __restrict__ C, const double* __restrict__ D,
                                                                  int n, int w, int t0, int zero_pivot,
                                                                  float* __restrict__ out, float* __restrict__ Cb) {
-  extern __shared__ double Dsh[];
-  for (int i = threadIdx.x; i < w * w; i += 256) Dsh[i] = D[i];
+  __shared__ float Csh[16][128];
+  const int r0 = blockIdx.x * 16, tid = threadIdx.x;
+  for (int idx = tid; idx < 16 * w; idx += 256) {
+    const int r = idx / w, k = idx % w;
+    Csh[r][k] = (r0 + r < n) ? C[(int64_t)(r0 + r) * w + k] : 0.f;
+  }
   __syncthreads();
-  int64_t tot = (int64_t)n * w;
-  for (int64_t idx = blockIdx.x * 256 + threadIdx.x; idx < tot; idx += (int64_t)gridDim.x * 256) {
-    int i = (int)(idx / w), c = (int)(idx % w);
-    bool piv = zero_pivot && i >= t0 && i < t0 + w;
-    double v = 0;
-    if (!piv)
-      for (int k = 0; k < w; k++) v += (double)C[(int64_t)i * w + k] * Dsh[k * w + c];
-    out[idx] = (float)v;
-    if (Cb) Cb[idx] = piv ? 0.f : C[idx];
+  const int c = tid & 127, h = tid >> 7;
+  if (c >= w) return;
+  double acc[8];
+#pragma unroll
+  for (int r = 0; r < 8; r++) acc[r] = 0.0;
+  for (int k = 0; k < w; k++) {
+    const double dv = D[k * w + c];
+#pragma unroll
+    for (int r = 0; r < 8; r++) acc[r] += (double)Csh[h * 8 + r][k] * dv;
+  }
+#pragma unroll
+  for (int r = 0; r < 8; r++) {
+    const int i = r0 + h * 8 + r;
+    if (i >= n) continue;
+    const bool piv = zero_pivot && i >= t0 && i < t0 + w;
+    out[(int64_t)i * w + c] = piv ? 0.f : (float)acc[r];
+    if (Cb) Cb[(int64_t)i * w + c] = piv ? 0.f : Csh[h * 8 + r][c];
   }
 }
 
 // ------------------------------------------------------------------------------------------------
 // blocked in-place inverse of an SPD matrix by sweeping nb columns at a time (lower triangle storage)
 // ------------------------------------------------------------------------------------------------
-constexpr int INV_NB = 64;
-
+// D = inverse of the w x w pivot block (rows t0.. of the extracted panel), float64
 __global__ __launch_bounds__(256) void inv_block_kernel(const float* __restrict__ C, int w, int t0, double* __restrict__ D,
                                                          int32_t* notpd) {
-  __shared__ double colbuf[INV_NB];
-  __shared__ double Dsh[INV_NB * INV_NB];
+  __shared__ double buf[64 * (INV_NB / 16)];
   for (int idx = threadIdx.x; idx < w * w; idx += 256) {
     int r = idx / w, c = idx % w;
-    Dsh[idx] = (double)C[(int64_t)(t0 + r) * w + c];
+    D[idx] = (double)C[(int64_t)(t0 + r) * w + c];
   }
-  __syncthreads();
-  small_inverse(Dsh, w, +1, notpd, colbuf);
-  for (int idx = threadIdx.x; idx < w * w; idx += 256) D[idx] = Dsh[idx];
+  small_inverse<INV_NB / 16>(D, w, +1, notpd, buf);
 }
 
 // pivot rows after a forward sweep: N(t0+r, l) = CD[l][r] for l outside the pivot, N(tt) = -D
@@ -273,10 +324,9 @@ hipError_t spd_inverse_inplace(float* A, int n, float* panel, float* panelD, dou
     int rb = (n + 255) / 256;
     hipLaunchKernelGGL(extract_panel_kernel, dim3(rb), dim3(256), 0, s, A, (int64_t)n, n, t0, w, panel);
     hipLaunchKernelGGL(inv_block_kernel, dim3(1), dim3(256), 0, s, panel, w, t0, small, notpd_flag);
-    int pb = (int)(((int64_t)n * w + 255) / 256); if (pb > 4096) pb = 4096;
     // true C*D for the pivot-row fix, and zeroed copies for the bulk update
-    hipLaunchKernelGGL(panel_times_small_kernel, dim3(pb), dim3(256), (size_t)w * w * 8, s, panel, small, n, w, t0, 1,
-                       panelD, panelB);
+    hipLaunchKernelGGL(panel_times_small_kernel, dim3((n + 15) / 16), dim3(256), 0, s, panel, small, n, w, t0, 1, panelD,
+                       panelB);
     GemmArgs g{};
     g.M = n; g.N = n; g.K = w; g.A = panelD; g.lda = w; g.B = panelB; g.ldb = w; g.trans_b = 1;
     g.Cin = A; g.ldcin = n; g.C = A; g.ldc = n; g.alpha = -1.0; g.beta = 1.0; g.diag_add = 0.0; g.c_is_f64 = 0;
@@ -516,7 +566,7 @@ __global__ __launch_bounds__(256) void extract_pair_kernel(TabDims d, const floa
 __global__ __launch_bounds__(256) void pair_small_kernel(TabDims d, const float* __restrict__ C1, const float* __restrict__ C2,
                                                           double* __restrict__ small, SearchCtrl* ctrl,
                                                           const int32_t* __restrict__ single) {
-  __shared__ double colbuf[64];
+  __shared__ double colbuf[256];
   __shared__ int32_t bad;
   if (ctrl->done) return;
   const int q = d.q, qq = q * q, tid = threadIdx.x;
@@ -531,7 +581,7 @@ __global__ __launch_bounds__(256) void pair_small_kernel(TabDims d, const float*
     Dj[idx] = (double)C2[(int64_t)(j0 + r) * q + c];       // N_jj
   }
   __syncthreads();
-  small_inverse(Dg, q, -1, &bad, colbuf);                  // kept pivot: N_gg = -P_gg is negative definite
+  small_inverse<4>(Dg, q, -1, &bad, colbuf);                  // kept pivot: N_gg = -P_gg is negative definite
   if (single) {
     // Case 1 alone: with M1 = 0 and Dj' = 0 every term of the second sweep below vanishes
     for (int idx = tid; idx < qq; idx += 256) { M1[idx] = 0.0; Dj[idx] = 0.0; W2Dj[idx] = 0.0; Njg[idx] = 0.0; }
@@ -551,7 +601,7 @@ __global__ __launch_bounds__(256) void pair_small_kernel(TabDims d, const float*
     Dj[idx] -= v;
   }
   __syncthreads();
-  small_inverse(Dj, q, +1, &bad, colbuf);                  // entering pivot: Schur complement, positive definite
+  small_inverse<4>(Dj, q, +1, &bad, colbuf);                  // entering pivot: Schur complement, positive definite
   for (int idx = tid; idx < qq; idx += 256) {              // W2Dj = W2 * Dj', W2 = N'_gj = -M1
     int r = idx / q, c = idx % q;
     double v = 0;
