@@ -106,6 +106,7 @@ struct osscar_ctx {
   double timers[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   hipEvent_t ev_a = nullptr, ev_b = nullptr;
   hipEvent_t ev_s[EV_SAMPLES][3];
+  SideStream side;   // the flush of the delayed-update search overlaps two of its products
   bool ev_ok = false;
 };
 
@@ -407,7 +408,10 @@ osscar_status osscar_create(osscar_ctx** out, const osscar_desc* desc, void* wor
   c->ev_ok = (hipEventCreate(&c->ev_a) == hipSuccess) && (hipEventCreate(&c->ev_b) == hipSuccess);
   for (int i = 0; i < EV_SAMPLES && c->ev_ok; i++)
     for (int j = 0; j < 3; j++) c->ev_ok = c->ev_ok && (hipEventCreate(&c->ev_s[i][j]) == hipSuccess);
-  if (!c->ev_ok) { delete c; return OSSCAR_EHIP; }
+  c->ev_ok = c->ev_ok && hipStreamCreateWithFlags(&c->side.stream, hipStreamNonBlocking) == hipSuccess &&
+             hipEventCreateWithFlags(&c->side.fork, hipEventDisableTiming) == hipSuccess &&
+             hipEventCreateWithFlags(&c->side.join, hipEventDisableTiming) == hipSuccess;
+  if (!c->ev_ok) { osscar_destroy(c); return OSSCAR_EHIP; }
   *out = c;
   return OSSCAR_OK;
 }
@@ -415,6 +419,9 @@ osscar_status osscar_create(osscar_ctx** out, const osscar_desc* desc, void* wor
 osscar_status osscar_destroy(osscar_ctx* c) {
   if (!c) return OSSCAR_EINVAL;
   hipStreamSynchronize(c->stream);
+  if (c->side.stream) { hipStreamSynchronize(c->side.stream); hipStreamDestroy(c->side.stream); }
+  if (c->side.fork) hipEventDestroy(c->side.fork);
+  if (c->side.join) hipEventDestroy(c->side.join);
   if (c->ev_a) hipEventDestroy(c->ev_a);
   if (c->ev_b) hipEventDestroy(c->ev_b);
   for (int i = 0; i < EV_SAMPLES; i++)
@@ -691,7 +698,7 @@ osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_e
       takes.push_back(take); batch += take; kept_b -= take;
     }
     if (takes.empty()) {   // the pending set is full: apply it and try again
-      HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode));
+      HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, &c->side));
       pending = 0;
       continue;
     }
@@ -705,7 +712,7 @@ osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_e
       int acc = 0, it_idx = 0;
       while (acc + takes[it_idx] <= done) { acc += takes[it_idx]; it_idx++; }
       const int off = done - acc;                       // removals of iteration it_idx already applied
-      HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode));       // also clears pause
+      HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, &c->side));       // also clears pause
       for (int i = off; i < takes[it_idx]; i++) HIPCHK(c, step(i));   // its pick list is still on the device
       pending = takes[it_idx] - off;
       batch = acc + takes[it_idx];
@@ -718,7 +725,7 @@ osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_e
     kept_now -= batch;
     since_refresh += batch;
     const bool refresh = refresh_every > 0 && since_refresh >= refresh_every && kept_now > k;
-    if (use_lazy && (refresh || kept_now == k) && pending > 0) { HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode)); pending = 0; }
+    if (use_lazy && (refresh || kept_now == k) && pending > 0) { HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, &c->side)); pending = 0; }
     if (refresh) {
       st = read_kept(c);
       if (st != OSSCAR_OK) return st;
@@ -785,7 +792,7 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
     auto flush = [&]() -> osscar_status {
       hipEvent_t f0 = c->ev_s[0][0], f1 = c->ev_s[0][1];
       HIPCHK(c, hipEventRecord(f0, s));
-      HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode));
+      HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, &c->side));
       HIPCHK(c, hipEventRecord(f1, s));
       HIPCHK(c, hipStreamSynchronize(s));
       float ms = 0; hipEventElapsedTime(&ms, f0, f1); flush_ms += ms; flushes++;
@@ -931,7 +938,7 @@ osscar_status osscar_block_search(osscar_ctx* c, int32_t max_iters, int32_t bloc
       done_pairs += did; idx += did; pending += 2 * did;
       if (idx < out.size()) {
         if (!use_lazy || !h.pause) return fail(c, OSSCAR_ESTATE, "internal: osscar_block_search stopped without a reason");
-        HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode));
+        HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, &c->side));
         pending = 0;
       }
     }
@@ -940,7 +947,7 @@ osscar_status osscar_block_search(osscar_ctx* c, int32_t max_iters, int32_t bloc
   std::vector<int32_t> out(take), inn(take);
   float gaps[2] = {0, 0};
   while (take > 0 && blocks < max_iters) {
-    if (use_lazy && pending + 2 * take > LAZY_TM) { HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode)); pending = 0; }
+    if (use_lazy && pending + 2 * take > LAZY_TM) { HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, &c->side)); pending = 0; }
     HIPCHK(c, launch_greedy_pick(d, t, take, c->g_pick, c->g_gap, s, 0));
     HIPCHK(c, launch_greedy_pick(d, t, take, c->g_pick + 64, c->g_gap + 1, s, 1));
     HIPCHK(c, hipMemcpyAsync(out.data(), c->g_pick, (size_t)take * 4, hipMemcpyDeviceToHost, s));
@@ -961,7 +968,7 @@ osscar_status osscar_block_search(osscar_ctx* c, int32_t max_iters, int32_t bloc
     blocks++;
     if (!ok) {
       // take the move back: the same pairs in reverse (the pending pivots must reach the tableau first)
-      if (use_lazy && pending > 0) { HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode)); pending = 0; }
+      if (use_lazy && pending > 0) { HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, &c->side)); pending = 0; }
       std::vector<int32_t> bo(inn.rbegin(), inn.rend()), bi(out.rbegin(), out.rend());
       st = run_pairs(bo, bi);
       if (st != OSSCAR_OK) return st;
@@ -971,7 +978,7 @@ osscar_status osscar_block_search(osscar_ctx* c, int32_t max_iters, int32_t bloc
     }
     accepted++;
   }
-  if (use_lazy && pending > 0) HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode));
+  if (use_lazy && pending > 0) HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, &c->side));
   HIPCHK(c, hipEventRecord(c->ev_b, s));
   HIPCHK(c, hipStreamSynchronize(s));
   c->timers[3] = elapsed(c);

@@ -163,8 +163,12 @@ hipError_t launch_lazy_init(const TabDims& d, const TabPtrs& t, const LazyPtrs& 
 hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, int always_accept, hipStream_t s,
                                  hipEvent_t* ev = nullptr, const int32_t* single = nullptr, int forced_out = -1,
                                  int forced_in = -1);
-// forced_out / forced_in >= 0: that pair instead of the kernel's own selection
-hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode = 0);
+// A second stream and two events: the flush runs its update of N0 there, beside the candidate selection and the look-ahead
+// product on the main stream (they touch disjoint data), and joins before the scores are refreshed.
+struct SideStream { hipStream_t stream = nullptr; hipEvent_t fork = nullptr, join = nullptr; };
+// side == nullptr (or no stream in it): everything in order on s
+hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode = 0,
+                             const SideStream* side = nullptr);
 
 hipError_t launch_scatter_rows(const float* src, int64_t lds, const int32_t* rows, int nrows, int ncols, void* dst,
                                int64_t ldd, int dst_is_bf16, hipStream_t s);

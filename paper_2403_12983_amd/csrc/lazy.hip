@@ -698,32 +698,47 @@ static hipError_t launch_partials(const TabDims& d, const TabPtrs& t, const Lazy
   return hipGetLastError();
 }
 
-hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode) {
+hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode,
+                             const SideStream* side) {
   const int rb = (d.d1 + 255) / 256, mb = (d.m + 255) / 256;
+  const bool two = side && side->stream;
+  hipStream_t sn = two ? side->stream : s;          // stream of the N0 update
   hipLaunchKernelGGL(lazy_convert_kernel, dim3(512), dim3(256), 0, s, L, d.m, t.ctrl);
   GemmArgs e{};                         // E = C0 M^-1
   e.M = d.d1; e.N = LAZY_TM; e.K = LAZY_TM; e.A = L.C0R; e.lda = LAZY_TM; e.B = L.Minv32; e.ldb = LAZY_TM;
   e.C = L.E; e.ldc = LAZY_TM; e.alpha = 1.0; e.beta = 0.0;
   hipError_t err = launch_gemm_f64acc(e, s);
   if (err != hipSuccess) return err;
+  if (two) {
+    if ((err = hipEventRecord(side->fork, s)) != hipSuccess) return err;
+    if ((err = hipStreamWaitEvent(sn, side->fork, 0)) != hipSuccess) return err;
+  }
   GemmArgs g{};                         // N0 -= E C0^T on the lower triangle (pivot rows and columns are rewritten below)
   g.M = d.d1; g.N = d.d1; g.K = LAZY_TM; g.A = L.E; g.lda = LAZY_TM; g.B = L.C0R; g.ldb = LAZY_TM; g.trans_b = 1;
   g.Cin = t.N; g.ldcin = d.d1; g.C = t.N; g.ldc = d.d1; g.alpha = -1.0; g.beta = 1.0; g.lower_only = 1; g.acc_f32 = 1;
-  err = launch_gemm_f64acc(g, s);
+  err = launch_gemm_f64acc(g, sn);
   if (err != hipSuccess) return err;
+  hipLaunchKernelGGL(lazy_fix_kernel, dim3(rb), dim3(256), 0, sn, L, t.N, d.d1, t.ctrl);
+  if (two && (err = hipEventRecord(side->join, sn)) != hipSuccess) return err;
   GemmArgs z{};                         // Z0 -= C0 ZT
   z.M = d.d1; z.N = d.m; z.K = LAZY_TM; z.A = L.C0R; z.lda = LAZY_TM; z.B = L.ZT32; z.ldb = d.m;
   z.Cin = t.Z; z.ldcin = d.m; z.C = t.Z; z.ldc = d.m; z.alpha = -1.0; z.beta = 1.0; z.acc_f32 = 1;
   err = launch_gemm_f64acc(z, s);
   if (err != hipSuccess) return err;
-  hipLaunchKernelGGL(lazy_fix_kernel, dim3(rb), dim3(256), 0, s, L, t.N, d.d1, t.ctrl);
   hipLaunchKernelGGL(lazy_fix_z_kernel, dim3(mb), dim3(256), 0, s, L, t.Z, d.m, t.ctrl);
+  if (two) {
+    // Candidates from the scores as the swaps left them (the refresh below changes them in the last digits only, and the
+    // choice of candidates decides what is computed ahead, not any result), products with the new Z0; meanwhile N0.
+    err = launch_candidates(d, t, L, s, mode);
+    if (err != hipSuccess) return err;
+    if ((err = hipStreamWaitEvent(s, side->join, 0)) != hipSuccess) return err;
+  }
   hipLaunchKernelGGL(lazy_reset_kernel, dim3(1), dim3(256), 0, s, L, t.ctrl);
   err = launch_refresh_scores(d, t, s);
   if (err != hipSuccess) return err;
   err = launch_partials(d, t, L, s);
   if (err != hipSuccess) return err;
-  return launch_candidates(d, t, L, s, mode);
+  return two ? hipGetLastError() : launch_candidates(d, t, L, s, mode);
 }
 
 hipError_t launch_lazy_init(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode) {
