@@ -19,8 +19,10 @@
  *   - The library allocates no device memory.  The caller hands one workspace of at least
  *     osscar_workspace_bytes() bytes (256-byte aligned) to osscar_create and owns it, X, W and What.
  *     The context keeps pointers into the workspace only; W is read only during osscar_gram.
- *   - All work is enqueued on the stream given to osscar_create.  Calls that return host values
- *     synchronise that stream; osscar_gram without finalize does not.
+ *   - All work is ordered on the stream given to osscar_create.  Calls that return host values
+ *     synchronise that stream; osscar_gram without finalize does not.  The context owns one more stream (default
+ *     priority) for a product of the search that overlaps with others; it forks from and joins the caller's stream
+ *     through events inside a call, so the caller sees the ordering of a single stream.
  *   - Every call returns an osscar_status.  No exception crosses this boundary and nothing aborts.
  *     After a failure other than OSSCAR_EINVAL the context refuses further compute calls
  *     (OSSCAR_ESTATE) until it is destroyed and re-created.  osscar_last_error() describes the failure.
