@@ -244,6 +244,56 @@ def test_conv_gram_at_the_conv_layer_shape(dtype):
     s.close()
 
 
+@pytest.mark.parametrize("keep", [48, 32, 16])
+def test_single_conv_layer_at_several_ratios(keep):
+    """The single-layer workload of the ablation on one convolutional layer (Section B.2.1, the figure on ResNet50's
+    layer1.0.conv2): 64 input channels, 3 x 3 kernels, 64 filters, 56 x 56 maps, pruned to 64 / keep of its channels.
+    Synthetic feature maps stand in for the network's activations.  The quadratic form comes from the feature maps
+    (osscar_gram_conv), magnitude start, local search, back-solve: every step against the oracle on the patch matrix."""
+    import time
+    import paper_2403_12983_amd as pkg
+    B, C, Hin, Win, m, q = 4, 64, 56, 56, 64, 9
+    g = torch.Generator().manual_seed(2050 + keep)
+    mix = torch.eye(C) + 0.5 * torch.diag(torch.ones(C - 1), 1) + 0.25 * torch.diag(torch.ones(C - 2), 2)   # correlated channels
+    F = torch.relu(torch.einsum("dc,bchw->bdhw", mix, torch.randn(B, C, Hin, Win, generator=g)))
+    F = (F * torch.exp(0.5 * torch.randn(1, C, 1, 1, generator=g))).float().contiguous()
+    W = (torch.randn(C * q, m, generator=g) * (2.0 / (C * q)) ** 0.5).float()
+    Xd = torch.nn.functional.unfold(F.double(), (3, 3), padding=1).permute(0, 2, 1).reshape(-1, C * q).numpy()
+    Wd = W.double().numpy()
+    H, G, c0, lam = orc.gram(Xd, Wd, 0.0, 1e-2)
+    swaps = 40
+    s = pkg.Solver(C * q, m, C, q, keep, swaps, torch.float32, torch.float32, DEV)
+    Fg, Wg = F.to(DEV), W.to(DEV)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    s.osscar_gram_conv(Fg, 3, 3, 1, 1, True, Wg, 0.0, 1e-2)
+    obj0 = s.osscar_init_support()
+    r = s.osscar_local_search(swaps)
+    What, support, obj = s.osscar_backsolve()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    dsc = np.sqrt(np.diag(H))
+    assert np.max(np.abs(T(s, "T_H").cpu().double().numpy() - H) / np.outer(dsc, dsc)) < 1e-6
+    assert rel(T(s, "T_G").cpu().double().numpy(), G) < 1e-6
+    K0 = orc.magnitude_support(Wd, C, q, keep)
+
+    class Shape:            # what follow_check reads
+        p = C
+    Shape.q = q
+    fol = follow_check(Shape, H, G, c0, K0, r, swaps)
+    assert abs(obj0 - fol.obj_initial) <= 1e-5 * fol.obj_initial
+    assert support.tolist() == fol.support
+    Wo, objo = orc.solve_support(H, G, c0, fol.support, q)
+    assert rel(What.cpu().double().numpy(), Wo) < 1e-4 and abs(obj - objo) <= 1e-4 * objo
+    # the search stopped because no swap improves: the oracle agrees at the final support
+    if r["accepted"] < swaps:
+        nxt = orc.local_search(H, G, c0, fol.support, C, q, 1)
+        assert nxt.accepted == 0 or nxt.trace[0].delta > -1e-5 * objo
+    print(f"conv layer 64 -> keep {keep} channels: {r['accepted']} swaps, obj {obj0:.6g} -> {obj:.6g} "
+          f"(dense {c0:.6g}), {dt * 1e3:.1f} ms for the layer incl. Gram from a {F.numel() * 4 / 1e6:.1f} MB map")
+    s.close()
+
+
 def test_cfg5_nested_schedule_properties():
     """The benchmark layer's shape (32768 calibration rows) through the nested schedule from the dense layer, t-hat = 10:
     14336 removals on the delayed-update path.  Checked through what holds at any size: bookkeeping, a monotone tracked
