@@ -340,8 +340,13 @@ def swap_delta(st: State, H: np.ndarray, G: np.ndarray, g: int, j: int, q: int):
 
 def local_search(H: np.ndarray, G: np.ndarray, c0: float, groups0: Sequence[int], p: int, q: int,
                  max_swaps: int, rel_tol: float = 0.0, always_accept: bool = False,
-                 follow: Optional[Sequence[Tuple[int, int]]] = None) -> SearchResult:
+                 follow: Optional[Sequence[Tuple[int, int]]] = None, exact_in: bool = False) -> SearchResult:
     """Swap search from the kept set groups0.
+
+    exact_in: a stronger rule for the entering group than the separable scores of eq. (impact): with the leaving
+    group g fixed (lowest removal score), every candidate j is scored at the state reached by removing g
+    (Case 1 applied, then eq. (impact) there), which is the exact gain of the pair (g, j); the record's add, gap_add
+    and deficit_add then refer to these scores.
 
     follow: optional list of (g_out, j_in) pairs to apply instead of the oracle's own selection (used to
     validate another implementation's trajectory step by step: the record then holds how far each forced
@@ -357,11 +362,18 @@ def local_search(H: np.ndarray, G: np.ndarray, c0: float, groups0: Sequence[int]
         if len(st.groups) == 0 or len(st.groups) == p:
             break
         rem = removal_scores(st, p, q)
-        add = addition_scores(st, H, G, p, q)
-        if follow is not None:
-            g, j = follow[it]
+        if exact_in:
+            g = follow[it][0] if follow is not None else int(np.argmin(rem))
+            mid_g = remove_group(st, st.groups.index(g), q)
+            add = addition_scores(mid_g, H, G, p, q)
+            add[g] = -np.inf                      # g itself is a candidate at that state; putting it back is no swap
+            j = follow[it][1] if follow is not None else int(np.argmax(add))
         else:
-            g, j = int(np.argmin(rem)), int(np.argmax(add))
+            add = addition_scores(st, H, G, p, q)
+            if follow is not None:
+                g, j = follow[it]
+            else:
+                g, j = int(np.argmin(rem)), int(np.argmax(add))
         rmin, amax = float(np.min(rem)), float(np.max(add))
         delta, mid = swap_delta(st, H, G, g, j, q)
         obj = c0 + 2.0 * st.f

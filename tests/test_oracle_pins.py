@@ -234,6 +234,41 @@ def test_search_objective_is_monotone_and_tracked_exactly(q, seed):
     assert res.iters == res.accepted or (res.iters == res.accepted + 1 and not res.trace[-1].accepted)
 
 
+@pytest.mark.parametrize("q,seed", [(1, 60), (3, 61), (1, 62)])
+def test_exact_entering_rule_is_the_best_pair_by_brute_force(q, seed):
+    """With the leaving group fixed, the exact rule must pick the j that minimises obj(K - g + j) solved from scratch,
+    its score must be that objective's drop from the state without g, and its first move can only be at least as
+    good as the separable rule's."""
+    p, m, n, k = 12, 4, 120, 5
+    X, W, H, G, c0, lam = make_problem(p, q, m, n, seed, corr=1.5)
+    K0 = orc.magnitude_support(W, p, q, k)
+    st = orc.init_state(H, G, sorted(K0), q)
+    g = int(np.argmin(orc.removal_scores(st, p, q)))
+    res = orc.local_search(H, G, c0, K0, p, q, 1, exact_in=True, always_accept=True)
+    r = res.trace[0]
+    assert r.g_out == g
+    Kg = [x for x in sorted(K0) if x != g]
+    _, obj_mid = orc.solve_support(H, G, c0, Kg, q)
+    objs = {j: orc.solve_support(H, G, c0, sorted(Kg + [j]), q)[1] for j in range(p) if j not in K0}
+    best = min(objs, key=objs.get)
+    assert r.j_in == best
+    assert np.isclose(r.add, obj_mid - objs[best], rtol=1e-8)
+    _, objK = orc.solve_support(H, G, c0, sorted(K0), q)
+    assert np.isclose(r.delta, objs[best] - objK, rtol=1e-7, atol=1e-9 * objK)
+    sep = orc.local_search(H, G, c0, K0, p, q, 1, always_accept=True).trace[0]
+    assert sep.g_out == g and r.delta <= sep.delta + 1e-12 * objK
+    # a whole run: monotone, and the tracked objective is the fresh solve's
+    run = orc.local_search(H, G, c0, K0, p, q, 30, exact_in=True)
+    o = [run.obj_initial] + [x.obj_after for x in run.trace if x.accepted]
+    assert all(b < a for a, b in zip(o, o[1:]))
+    assert np.isclose(orc.solve_support(H, G, c0, run.support, q)[1], run.obj_final, rtol=1e-9)
+    # follow mode on its own trajectory: zero deficits
+    pairs = [(x.g_out, x.j_in) for x in run.trace if x.accepted]
+    fol = orc.local_search(H, G, c0, K0, p, q, len(pairs), follow=pairs, exact_in=True)
+    assert all(x.deficit_rem == 0 and x.deficit_add == 0 for x in fol.trace)
+    assert fol.support == run.support
+
+
 def test_follow_mode_reproduces_free_run_with_zero_deficit():
     p, q, m, n, k = 20, 1, 5, 150, 8
     X, W, H, G, c0, lam = make_problem(p, q, m, n, 50, corr=1.5)
