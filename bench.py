@@ -91,6 +91,8 @@ def main():
                     help="groups swapped per iteration (t-hat = 2 * block): swaps // block iterations of block moves")
     ap.add_argument("--no-lookahead", action="store_true",
                     help="search without the products computed ahead: every swap then makes one read-only pass over Z")
+    ap.add_argument("--exact-in", action="store_true",
+                    help="entering group by the exact gain of the pair (OSSCAR_SEARCH_EXACT_IN); runs on the in-place path")
     ap.add_argument("--rows", type=int, default=None,
                     help="calibration rows (default: the config's); a short X keeps counter-collection runs brief")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -130,6 +132,8 @@ def main():
         obj0 = s.osscar_init_support() if a.init == "magnitude" else s.osscar_init_greedy(a.t_hat)[0]
         ev[3].record()
         fl = pkg.OSSCAR_SEARCH_NO_LOOKAHEAD if a.no_lookahead else 0
+        if a.exact_in:
+            fl |= pkg.OSSCAR_SEARCH_EXACT_IN
         if a.block > 1:
             r = s.osscar_block_search(swaps // a.block, a.block, 0.0, fl)
             r["iters"] = r["iters"] * a.block
@@ -166,7 +170,7 @@ def main():
 
     d1, m, n = cfg.d1, cfg.m, cfg.n
     gram_flops = n * d1 * (d1 + 1)
-    lazy = (cfg.q == 1)
+    lazy = (cfg.q == 1) and not a.exact_in
     # Per-swap state update as SURVEY counts it: read + write of P, V (= lower triangle of N) and B, R (= Z)
     bytes_swap_alg = 2 * 4 * (d1 * d1 // 2) + 2 * 4 * d1 * m
     ms_swap = 1e3 * phases["search"] / max(info["iters"], 1)
@@ -185,7 +189,8 @@ def main():
         "config": {"workload": f"{cfg.name}: X {n}x{d1} {cfg.x_dtype}, W {d1}x{m} {cfg.w_dtype}, keep {cfg.k} of {cfg.p} groups "
                                f"(q={cfg.q}), {swaps} swaps, lambda = {cfg.lam_rel}*mean diag",
                    "refresh_every": a.refresh_every,
-                   "search": ("delayed-update" + (", no look-ahead" if a.no_lookahead else "")) if lazy else "eager",
+                   "search": (("delayed-update" + (", no look-ahead" if a.no_lookahead else "")) if lazy else "eager") +
+                             (", exact entering rule" if a.exact_in else ""),
                    "init": a.init if a.init == "magnitude" else f"nested schedule from the dense layer, t_hat = {a.t_hat}",
                    "groups_per_move": a.block},
         "phases_s": phases,

@@ -155,11 +155,15 @@ osscar_status osscar_init_greedy(osscar_ctx* ctx, int32_t t_hat, int32_t refresh
  * together on the matrix cores -- the same swaps, with less traffic.  In that mode the products of Z with the
  * rows most likely to be swapped next are computed ahead by one matrix product per flush;
  * OSSCAR_SEARCH_NO_LOOKAHEAD turns that off (every swap then reads Z once).
+ * OSSCAR_SEARCH_EXACT_IN (a stronger rule than the separable scores of eq. (impact), not in the paper): with the
+ * leaving group fixed as above, the entering group is the one with the largest exact gain of the pair, i.e. every
+ * candidate is scored at the state without the leaving group (Case 1 applied to the blocks its score needs); costs one
+ * more pass over Z per iteration and runs on the in-place path; trace_gap[2i+1] then refers to these scores.
  * refresh_every > 0 recomputes V, R and B from P, H, G by GEMM after that many accepted swaps.
  * Optional host outputs of length max_swaps (entry i describes iteration i, including a final rejected
  * one): trace_out / trace_in = group leaving / entering; trace_gap[2i], trace_gap[2i+1] = relative gap
  * between best and second-best removal cost / addition gain; trace_obj[i] = obj after the iteration. */
-enum { OSSCAR_SEARCH_ALWAYS_ACCEPT = 1u, OSSCAR_SEARCH_EAGER = 2u, OSSCAR_SEARCH_NO_LOOKAHEAD = 4u };
+enum { OSSCAR_SEARCH_ALWAYS_ACCEPT = 1u, OSSCAR_SEARCH_EAGER = 2u, OSSCAR_SEARCH_NO_LOOKAHEAD = 4u, OSSCAR_SEARCH_EXACT_IN = 8u };
 typedef struct {
   int32_t iters;     /* iterations run (accepted swaps + at most one rejected) */
   int32_t accepted;  /* swaps applied */

@@ -14,6 +14,7 @@ OSSCAR_INIT_MAGNITUDE, OSSCAR_INIT_GIVEN = 0, 1
 OSSCAR_SEARCH_ALWAYS_ACCEPT = 1
 OSSCAR_SEARCH_EAGER = 2
 OSSCAR_SEARCH_NO_LOOKAHEAD = 4
+OSSCAR_SEARCH_EXACT_IN = 8
 T_H, T_G, T_P, T_B, T_V, T_R, T_REM, T_ADD, T_KEPT, T_CAND = range(10)
 _STATUS = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "ENOTPD", 4: "EHIP", 5: "ESTATE"}
 

@@ -87,6 +87,7 @@ struct osscar_ctx {
   // persistent device arrays
   float *H, *G, *N, *Z;
   double *norms2, *score, *gram, *dblk, *small, *scal, *partial;
+  double *cross, *xgram, *xdblk, *xscore;   // exact entering rule
   int32_t *kept, *rowsK, *rowsC, *notpd;
   float *C1, *C2, *Cblk, *rZ1, *rZ2;
   SearchCtrl* ctrl;
@@ -130,6 +131,10 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
   double* gram = cv.take<double>(p * q * q);
   double* dblk = cv.take<double>(p * q * q);
   double* small = cv.take<double>(std::max<int64_t>(16 * q * q, INV_NB * INV_NB));
+  double* cross = cv.take<double>(d1 * q);
+  double* xgram = cv.take<double>(p * q * q);
+  double* xdblk = cv.take<double>(p * q * q);
+  double* xscore = cv.take<double>(p);
   double* scal = cv.take<double>(1024);
   double* partial = cv.take<double>(2048);
   int32_t* kept = cv.take<int32_t>(p);
@@ -183,6 +188,7 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
   char* scratch = cv.take<char>(scratch_bytes);
   if (c) {
     c->H = H; c->G = G; c->N = N; c->Z = Z; c->norms2 = norms2; c->score = score; c->gram = gram; c->dblk = dblk;
+    c->cross = cross; c->xgram = xgram; c->xdblk = xdblk; c->xscore = xscore;
     c->small = small; c->scal = scal; c->partial = partial; c->kept = kept; c->rowsK = rowsK; c->rowsC = rowsC;
     c->notpd = notpd; c->C1 = C1; c->C2 = C2; c->Cblk = Cblk; c->rZ1 = rZ1; c->rZ2 = rZ2; c->ctrl = ctrl;
     c->trace_out = trace_out; c->trace_in = trace_in; c->trace_gap = trace_gap; c->trace_obj = trace_obj;
@@ -223,6 +229,7 @@ TabPtrs ptrs(const osscar_ctx* c) {
   t.N = c->N; t.Z = c->Z; t.kept = c->kept; t.score = c->score; t.gram = c->gram; t.dblk = c->dblk;
   t.C1 = c->C1; t.C2 = c->C2; t.C1D = c->Cblk; t.C2D = c->Cblk + (int64_t)c->d1 * c->q;
   t.rZ1 = c->rZ1; t.rZ2 = c->rZ2; t.small = c->small; t.ctrl = c->ctrl;
+  t.cross = c->cross; t.xgram = c->xgram; t.xdblk = c->xdblk; t.xscore = c->xscore;
   t.trace_out = c->trace_out; t.trace_in = c->trace_in; t.trace_gap = c->trace_gap; t.trace_obj = c->trace_obj;
   return t;
 }
@@ -780,7 +787,8 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
   HIPCHK(c, hipEventRecord(c->ev_a, s));
   int launched = 0, since_refresh_base = 0, samples = 0;
   double refresh_ms = 0, upd_n_ms = 0, upd_z_ms = 0;
-  const bool use_lazy = (c->q == 1) && !(flags & OSSCAR_SEARCH_EAGER);
+  const int exact_in = (flags & OSSCAR_SEARCH_EXACT_IN) ? 1 : 0;      // runs on the in-place path
+  const bool use_lazy = (c->q == 1) && !(flags & OSSCAR_SEARCH_EAGER) && !exact_in;
   if (use_lazy) {
     // delayed-update search: the tableau in HBM is only touched by a flush every FLUSH iterations
     const LazyPtrs& L = c->lazy;
@@ -848,7 +856,8 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
     if (refresh_every > 0) nb = std::min(nb, std::max(1, refresh_every - (h.accepted - since_refresh_base)));
     const bool sample = samples + 1 < EV_SAMPLES;
     for (int i = 0; i < nb; i++) {
-      HIPCHK(c, launch_search_iteration(d, t, -1, -1, always, s, (i == 0 && sample) ? c->ev_s[samples + 1] : nullptr));
+      HIPCHK(c, launch_search_iteration(d, t, -1, -1, always, s, (i == 0 && sample) ? c->ev_s[samples + 1] : nullptr, nullptr,
+                                        exact_in));
     }
     launched += nb;
     st = read_ctrl(c, &h);

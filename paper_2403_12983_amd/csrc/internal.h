@@ -107,6 +107,7 @@ struct TabPtrs {
   float* C1D; float* C2D;          // d1 x q panels times D
   float* rZ1; float* rZ2;          // q x m
   double* small;                   // scratch for q x q algebra (>= 16*q*q doubles)
+  double* cross; double* xgram; double* xdblk; double* xscore;   // exact entering rule: d1*q, p*q*q, p*q*q, p
   SearchCtrl* ctrl;
   int32_t* trace_out; int32_t* trace_in; float* trace_gap; double* trace_obj;
 };
@@ -114,8 +115,9 @@ struct TabPtrs {
 hipError_t launch_refresh_scores(const TabDims& d, const TabPtrs& t, hipStream_t s);   // gram, dblk, score from N, Z
 // ev (optional): three events recorded before the bulk update of N, after it, and after the update of Z.
 // single (optional, device): removal of the one group *single instead of a swap (Case 1 alone; no selection kernel).
+// exact_in: the entering group is the argmax of the exact gain of the pair with the selected leaving group.
 hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int forced_out, int forced_in, int always_accept,
-                                   hipStream_t s, hipEvent_t* ev = nullptr, const int32_t* single = nullptr);
+                                   hipStream_t s, hipEvent_t* ev = nullptr, const int32_t* single = nullptr, int exact_in = 0);
 // pick[0..take) = the kept groups of smallest removal cost (ascending), *gap = relative gap to the next one; take <= 64
 // side 1: the groups outside the kept set with the largest addition gain (descending) instead
 hipError_t launch_greedy_pick(const TabDims& d, const TabPtrs& t, int take, int32_t* pick, float* gap, hipStream_t s,

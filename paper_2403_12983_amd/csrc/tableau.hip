@@ -538,6 +538,136 @@ __global__ __launch_bounds__(1024) void select_kernel(TabDims d, const int32_t* 
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Exact entering rule: with the leaving group g fixed, every candidate j is scored at the state WITHOUT g (Case 1 of
+// Proposition 4.1 applied to the blocks the score needs, then eq. (impact) there), i.e. by the exact gain of the pair.
+// Sweeping g out changes   N_jj -> N_jj - Y N_gj,   Z_j -> Z_j - Y Z_g,   Y = N_jg N_gg^-1,
+// so with C_j = Z_j Z_g^T (exact_cross_kernel) the Gram of the new rows is
+//   M_j = Z_j Z_j^T - Y C_j^T - C_j Y^T + Y (Z_g Z_g^T) Y^T          and the score is Tr(S'_j^-1 M_j).
+// ------------------------------------------------------------------------------------------------
+// cross[i][c] = <Z_i, Z_{g, c}> for every row i; one wave per row, Zg = the copy of the rows of g (q x m)
+__global__ __launch_bounds__(256) void exact_cross_kernel(TabDims d, const float* __restrict__ Z, const float* __restrict__ Zg,
+                                                           const SearchCtrl* __restrict__ ctrl, double* __restrict__ cross) {
+  if (ctrl->done) return;
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= d.d1) return;
+  const float* zi = Z + (int64_t)row * d.m;
+  for (int c = 0; c < d.q; c++) {
+    const float* zg = Zg + (int64_t)c * d.m;
+    double v = 0;
+    for (int col = lane; col < d.m; col += 64) v += (double)zi[col] * (double)zg[col];
+    v = wave_sum(v);
+    if (lane == 0) cross[(int64_t)row * d.q + c] = v;
+  }
+}
+
+// groups of one row: the score itself, one thread per group
+__global__ __launch_bounds__(256) void exact_q1_kernel(TabDims d, const float* __restrict__ C1, const double* __restrict__ cross,
+                                                        const double* __restrict__ gram, const double* __restrict__ dblk,
+                                                        const int32_t* __restrict__ kept, SearchCtrl* ctrl,
+                                                        double* __restrict__ xscore) {
+  if (ctrl->done) return;
+  const int h = blockIdx.x * 256 + threadIdx.x;
+  if (h >= d.p) return;
+  if (kept[h]) { xscore[h] = 0.0; return; }
+  const int g = ctrl->g_out;
+  const double x = (double)C1[h], y = x / dblk[g];
+  double sp = dblk[h] - y * x;
+  const double mj = gram[h] - 2.0 * y * cross[h] + y * y * gram[g];
+  if (!(sp > 0.0)) { ctrl->notpd = 1; sp = 1.0; }
+  xscore[h] = mj / sp;
+}
+
+// groups of q rows: the blocks S'_j -> xdblk[j], M_j -> xgram[j] (kept groups: -I and 0, which score_kernel turns into 0)
+__global__ __launch_bounds__(256) void exact_blocks_kernel(TabDims d, const float* __restrict__ C1, const double* __restrict__ cross,
+                                                            const double* __restrict__ gram, const double* __restrict__ dblk,
+                                                            const int32_t* __restrict__ kept, SearchCtrl* ctrl,
+                                                            double* __restrict__ xgram, double* __restrict__ xdblk) {
+  extern __shared__ double xsh[];      // Dg (later T = Y Gg), X, Y: q*q each; then 256 doubles for the inverse
+  __shared__ int32_t bad;
+  if (ctrl->done) return;
+  const int q = d.q, qq = q * q, tid = threadIdx.x, j = blockIdx.x, g = ctrl->g_out, j0 = j * q;
+  double* outS = xdblk + (int64_t)j * qq;
+  double* outM = xgram + (int64_t)j * qq;
+  if (kept[j]) {
+    for (int idx = tid; idx < qq; idx += 256) { outS[idx] = (idx / q == idx % q) ? -1.0 : 0.0; outM[idx] = 0.0; }
+    return;
+  }
+  double* Dg = xsh; double* X = xsh + qq; double* Y = xsh + 2 * qq; double* buf = xsh + 3 * qq;
+  if (tid == 0) bad = 0;
+  for (int idx = tid; idx < qq; idx += 256) {
+    Dg[idx] = dblk[(int64_t)g * qq + idx];                                   // N_gg, negative definite
+    X[idx] = (double)C1[(int64_t)(j0 + idx / q) * q + idx % q];              // N(j_r, g_c)
+  }
+  small_inverse<4>(Dg, q, -1, &bad, buf);
+  for (int idx = tid; idx < qq; idx += 256) {                                // Y = X Dg
+    const int r = idx / q, c = idx % q;
+    double v = 0;
+    for (int k = 0; k < q; k++) v += X[r * q + k] * Dg[k * q + c];
+    Y[idx] = v;
+  }
+  __syncthreads();
+  const double* Gg = gram + (int64_t)g * qq;
+  const double* Gj = gram + (int64_t)j * qq;
+  const double* Sj = dblk + (int64_t)j * qq;
+  const double* Cj = cross + (int64_t)j0 * q;                               // C_j[r][c] = <Z_{j,r}, Z_{g,c}>
+  double* Tm = Dg;                                                           // T = Y Gg overwrites Dg
+  for (int idx = tid; idx < qq; idx += 256) {
+    const int r = idx / q, c = idx % q;
+    double sv = 0;
+    for (int k = 0; k < q; k++) sv += Y[r * q + k] * X[c * q + k];
+    outS[idx] = Sj[idx] - sv;                                                // S' = N_jj - Y N_gj
+  }
+  __syncthreads();
+  for (int idx = tid; idx < qq; idx += 256) {
+    const int r = idx / q, c = idx % q;
+    double v = 0;
+    for (int k = 0; k < q; k++) v += Y[r * q + k] * Gg[k * q + c];
+    Tm[idx] = v;
+  }
+  __syncthreads();
+  for (int idx = tid; idx < qq; idx += 256) {
+    const int r = idx / q, c = idx % q;
+    double v = Gj[idx];
+    for (int k = 0; k < q; k++) v += -Y[r * q + k] * Cj[c * q + k] - Cj[r * q + k] * Y[c * q + k] + Tm[r * q + k] * Y[c * q + k];
+    outM[idx] = v;
+  }
+  if (tid == 0 && bad) ctrl->notpd = 1;
+}
+
+// entering group = argmax of the exact scores over the groups outside the kept set (lowest index on ties)
+__global__ __launch_bounds__(1024) void select_in_kernel(TabDims d, const int32_t* __restrict__ kept,
+                                                          const double* __restrict__ xscore, SearchCtrl* ctrl) {
+  __shared__ double s1[1024], s2[1024];
+  __shared__ int si[1024];
+  if (ctrl->done) return;
+  const int tid = threadIdx.x;
+  double mx1 = -INFINITY, mx2 = -INFINITY;
+  int imx = -1;
+  for (int h = tid; h < d.p; h += 1024) {
+    if (kept[h]) continue;
+    const double v = xscore[h];
+    if (v > mx1) { mx2 = mx1; mx1 = v; imx = h; } else if (v > mx2) mx2 = v;
+  }
+  s1[tid] = mx1; s2[tid] = mx2; si[tid] = imx;
+  __syncthreads();
+  for (int o = 512; o > 0; o >>= 1) {
+    if (tid < o) {
+      const double a1 = s1[tid], a2 = s2[tid], b1 = s1[tid + o], b2 = s2[tid + o];
+      const int ia = si[tid], ib = si[tid + o];
+      const bool takeb = (ib >= 0) && (ia < 0 || b1 > a1 || (b1 == a1 && ib < ia));
+      s1[tid] = takeb ? b1 : a1; si[tid] = takeb ? ib : ia;
+      s2[tid] = fmax(fmax(a2, b2), takeb ? a1 : b1);
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    if (si[0] < 0) { ctrl->done = 1; ctrl->g_out = -1; ctrl->g_in = -1; return; }
+    ctrl->g_in = si[0];
+    ctrl->gap_add = isfinite(s2[0]) ? fabs(s1[0] - s2[0]) / fmax(fabs(s1[0]), 1e-300) : INFINITY;
+  }
+}
+
 // panels of both pivots and copies of their Z rows
 __global__ __launch_bounds__(256) void extract_pair_kernel(TabDims d, const float* __restrict__ N, const float* __restrict__ Z,
                                                             const SearchCtrl* __restrict__ ctrl, float* __restrict__ C1,
@@ -987,7 +1117,7 @@ hipError_t launch_select(const TabDims& d, const TabPtrs& t, int forced_out, int
 }
 
 hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int forced_out, int forced_in, int always_accept,
-                                   hipStream_t s, hipEvent_t* ev, const int32_t* single) {
+                                   hipStream_t s, hipEvent_t* ev, const int32_t* single, int exact_in) {
   const int q = d.q;
   const int rb = (d.d1 + 255) / 256;
   const size_t pc_lds = (size_t)(3 * q * q + 2 * q * PC_COLS) * 8;
@@ -997,6 +1127,25 @@ hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int force
   }
   if (!single) hipLaunchKernelGGL(select_kernel, dim3(1), dim3(1024), 0, s, d, t.kept, t.score, t.ctrl, forced_out, forced_in);
   hipLaunchKernelGGL(extract_pair_kernel, dim3(rb), dim3(256), 0, s, d, t.N, t.Z, t.ctrl, t.C1, t.C2, t.rZ1, t.rZ2, single);
+  if (exact_in && !single && forced_out < 0) {
+    // the leaving group stands; choose the entering one by the exact gain of the pair and extract its panel again
+    hipLaunchKernelGGL(exact_cross_kernel, dim3((d.d1 + 3) / 4), dim3(256), 0, s, d, t.Z, t.rZ1, t.ctrl, t.cross);
+    if (q == 1) {
+      hipLaunchKernelGGL(exact_q1_kernel, dim3((d.p + 255) / 256), dim3(256), 0, s, d, t.C1, t.cross, t.gram, t.dblk, t.kept, t.ctrl,
+                         t.xscore);
+    } else {
+      const size_t xb_lds = (size_t)(3 * q * q + 256) * 8;
+      if (xb_lds > 65536) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(exact_blocks_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)xb_lds);
+        if (e != hipSuccess) return e;
+      }
+      hipLaunchKernelGGL(exact_blocks_kernel, dim3(d.p), dim3(256), xb_lds, s, d, t.C1, t.cross, t.gram, t.dblk, t.kept, t.ctrl,
+                         t.xgram, t.xdblk);
+      hipLaunchKernelGGL(score_kernel, dim3(d.p), dim3(64), (size_t)2 * q * q * 8, s, d, t.kept, t.xgram, t.xdblk, t.xscore, t.ctrl, 1);
+    }
+    hipLaunchKernelGGL(select_in_kernel, dim3(1), dim3(1024), 0, s, d, t.kept, t.xscore, t.ctrl);
+    hipLaunchKernelGGL(extract_pair_kernel, dim3(rb), dim3(256), 0, s, d, t.N, t.Z, t.ctrl, t.C1, t.C2, t.rZ1, t.rZ2, single);
+  }
   hipLaunchKernelGGL(pair_small_kernel, dim3(1), dim3(256), 0, s, d, t.C1, t.C2, t.small, t.ctrl, single);
   hipLaunchKernelGGL(pair_cols_kernel, dim3((d.m + PC_COLS - 1) / PC_COLS), dim3(256), pc_lds, s, d,
                      t.rZ1, t.rZ2, t.small, t.ctrl);

@@ -40,9 +40,9 @@ def T(s, which):
     return s.osscar_get_tensor(getattr(B, which))
 
 
-def follow_check(cfg, H, G, c0, K0, r, max_follow):
+def follow_check(cfg, H, G, c0, K0, r, max_follow, exact_in=False):
     pairs = list(zip(r["trace_out"].tolist(), r["trace_in"].tolist()))[: min(r["accepted"], max_follow)]
-    fol = orc.local_search(H, G, c0, K0, cfg.p, cfg.q, len(pairs), follow=pairs)
+    fol = orc.local_search(H, G, c0, K0, cfg.p, cfg.q, len(pairs), follow=pairs, exact_in=exact_in)
     for i, x in enumerate(fol.trace):
         assert x.deficit_rem <= GAP and x.deficit_add <= GAP, (i, x)
         assert x.delta < 0, (i, x)
@@ -77,6 +77,36 @@ def test_whole_layer_against_oracle(name, max_follow):
     assert abs(obj - objo) <= 1e-4 * objo
     assert abs(r["obj_final"] - objo) <= 1e-4 * objo
     print(f"{name}: {r['accepted']} swaps, obj {r['obj_initial']:.6g} -> {obj:.6g}, min gaps {r['trace_gap'].min(axis=0)}")
+    s.close()
+
+
+@pytest.mark.parametrize("name,max_follow", [("cfg2", 60), ("cfg4", 40)])
+def test_exact_entering_rule_whole_layer(name, max_follow):
+    """The exact entering rule (OSSCAR_SEARCH_EXACT_IN) on whole layers with groups of 9 and of 64 rows, replayed by the
+    oracle's same rule; its end point is compared with the separable rule's."""
+    import paper_2403_12983_amd as pkg
+    cfg = inp.CONFIGS[name]
+    X = gen_on_gpu(cfg)
+    W = inp.gen_W(cfg, DEV)
+    Xd, Wd = X.cpu().double().numpy(), W.cpu().double().numpy()
+    H, G, c0, lam = orc.gram(Xd, Wd, cfg.lam_abs, cfg.lam_rel)
+    del Xd
+    s = make_solver(cfg, X, W)
+    s.osscar_gram(X, True, W, cfg.lam_abs, cfg.lam_rel)
+    s.osscar_init_support()
+    K0 = orc.magnitude_support(Wd, cfg.p, cfg.q, cfg.k)
+    base = s.osscar_local_search(cfg.swaps)
+    s.osscar_init_support()
+    r = s.osscar_local_search(cfg.swaps, flags=pkg.OSSCAR_SEARCH_EXACT_IN)
+    fol = follow_check(cfg, H, G, c0, K0, r, max_follow, exact_in=True)
+    What, support, obj = s.osscar_backsolve()
+    if r["accepted"] <= max_follow:
+        assert support.tolist() == fol.support
+    Wo, objo = orc.solve_support(H, G, c0, support.tolist(), cfg.q)
+    assert rel(What.cpu().double().numpy(), Wo) < 1e-4 and abs(obj - objo) <= 1e-4 * objo
+    assert abs(r["obj_final"] - objo) <= 1e-4 * objo
+    print(f"{name}: exact entering rule {r['accepted']} swaps -> obj {obj:.6g} in {s.osscar_get_timers()[3]:.1f} ms; "
+          f"separable rule {base['accepted']} swaps -> obj {base['obj_final']:.6g}")
     s.close()
 
 

@@ -147,13 +147,14 @@ def test_initial_state_and_scores(name):
 
 
 # ------------------------------------------------------------------------------------------ search
-def check_trajectory(c, r, rel_tol=0.0, always=False):
+def check_trajectory(c, r, rel_tol=0.0, always=False, exact_in=False):
     """The library's trajectory replayed by the oracle: every choice within GAP of the oracle's best, every
     applied swap improving, the stop justified, the objective trace equal to 1e-6."""
     cfg = c.cfg
     pairs = list(zip(r["trace_out"].tolist(), r["trace_in"].tolist()))
     acc = pairs[: r["accepted"]]
-    free = orc.local_search(c.H, c.G, c.c0, c.K0, cfg.p, cfg.q, len(pairs) if always else cfg.swaps, rel_tol, always)
+    free = orc.local_search(c.H, c.G, c.c0, c.K0, cfg.p, cfg.q, len(pairs) if always else cfg.swaps, rel_tol, always,
+                            exact_in=exact_in)
     fpairs = [(x.g_out, x.j_in) for x in free.trace]
     # identical choices as long as no gap fell below GAP (afterwards trajectories may legitimately differ)
     for i, (a, b) in enumerate(zip(pairs, fpairs)):
@@ -163,7 +164,7 @@ def check_trajectory(c, r, rel_tol=0.0, always=False):
     else:
         assert len(pairs) == len(fpairs)
         assert r["accepted"] == free.accepted
-    fol = orc.local_search(c.H, c.G, c.c0, c.K0, cfg.p, cfg.q, cfg.swaps, follow=acc)
+    fol = orc.local_search(c.H, c.G, c.c0, c.K0, cfg.p, cfg.q, cfg.swaps, follow=acc, exact_in=exact_in)
     for i, x in enumerate(fol.trace):
         assert x.deficit_rem <= GAP and x.deficit_add <= GAP, (i, x)
         if not always:
@@ -205,6 +206,36 @@ def test_search_follows_the_oracle(name):
     dp = np.sqrt(np.diag(st.P))
     assert np.max(np.abs(T(s, "T_P") - st.P) / np.outer(dp, dp)) < 5e-5
     assert rel(T(s, "T_B"), st.What_K) < 5e-5
+    s.close()
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg1x", "cfg2s", "cfg3s", "cfg4s", "cfg5odd", "cfg3s+2"])
+def test_exact_entering_rule_follows_the_oracle(name):
+    """OSSCAR_SEARCH_EXACT_IN: the entering group by the exact gain of the pair; replayed by the oracle's same rule."""
+    c = case(name)
+    pkg = _pkg()
+    s = c.solver()
+    c.gram(s)
+    s.osscar_init_support()
+    r = s.osscar_local_search(c.cfg.swaps, flags=pkg.OSSCAR_SEARCH_EXACT_IN)
+    assert np.all(np.diff(np.concatenate([[r["obj_initial"]], r["trace_obj"][: r["accepted"]]])) < 0)
+    fol = check_trajectory(c, r, exact_in=True)
+    What, support, obj = s.osscar_backsolve()
+    assert support.tolist() == fol.support
+    Wo, objo = orc.solve_support(c.H, c.G, c.c0, fol.support, c.cfg.q)
+    assert rel(What.cpu().double().numpy(), Wo) < 1e-4 and abs(obj - objo) <= 1e-4 * objo
+    # with the same leaving group, the exact rule's first move is at least as good as the separable rule's
+    if r["accepted"] >= 1:
+        s.osscar_init_support()
+        b = s.osscar_local_search(1, flags=pkg.OSSCAR_SEARCH_ALWAYS_ACCEPT)
+        assert b["trace_out"][0] == r["trace_out"][0]
+        assert r["trace_obj"][0] <= b["trace_obj"][0] + 1e-6 * abs(b["trace_obj"][0])
+    # Algorithm 1's variant that applies every pair, under the exact rule
+    s.osscar_init_support()
+    n = min(6, c.cfg.swaps)
+    ra = s.osscar_local_search(n, flags=pkg.OSSCAR_SEARCH_EXACT_IN | pkg.OSSCAR_SEARCH_ALWAYS_ACCEPT)
+    assert ra["iters"] == n and ra["accepted"] == n
+    check_trajectory(c, ra, always=True, exact_in=True)
     s.close()
 
 
