@@ -414,10 +414,12 @@ __global__ __launch_bounds__(256) void dblk_copy_kernel(TabDims d, const float* 
 
 // score[h] = Tr(gram_h * (sigma * dblk_h)^-1), sigma = -1 for kept groups (N_hh = -P_hh), +1 otherwise.
 // One workgroup of 64 threads per group; Cholesky in shared memory, then one column solve per thread.
-__global__ __launch_bounds__(64) void score_kernel(TabDims d, const int32_t* __restrict__ kept,
-                                                    const double* __restrict__ gram, const double* __restrict__ dblk,
-                                                    double* __restrict__ score, SearchCtrl* ctrl, int skip_if_done) {
-  extern __shared__ double sh[];   // A: q*q, X: q*q
+__global__ __launch_bounds__(256) void score_kernel(TabDims d, const int32_t* __restrict__ kept,
+                                                     const double* __restrict__ gram, const double* __restrict__ dblk,
+                                                     double* __restrict__ score, SearchCtrl* ctrl, int skip_if_done) {
+  extern __shared__ double sh[];   // A: q*q, then 256 doubles for the inverse
+  __shared__ int32_t bad;
+  __shared__ double red[4];
   if (skip_if_done && ctrl->done) return;          // a search iteration that changed nothing
   const int h = blockIdx.x, q = d.q, tid = threadIdx.x;
   const double sigma = kept[h] ? -1.0 : 1.0;
@@ -429,41 +431,41 @@ __global__ __launch_bounds__(64) void score_kernel(TabDims d, const int32_t* __r
     }
     return;
   }
+  // Tr(|N_hh|^-1 Z_h Z_h^T): inverse of the q x q block by Gauss-Jordan in registers, then the sum of the products with
+  // the Gram block (both symmetric)
   double* A = sh;
-  double* X = sh + q * q;
-  for (int idx = tid; idx < q * q; idx += 64) { A[idx] = sigma * dblk[(int64_t)h * q * q + idx]; X[idx] = gram[(int64_t)h * q * q + idx]; }
-  __syncthreads();
-  // Cholesky, lower, in place (right-looking, column at a time)
-  for (int k = 0; k < q; k++) {
-    double piv = A[k * q + k];
-    if (!(piv > 0.0)) { if (tid == 0) ctrl->notpd = 1; piv = 1.0; }
-    double lkk = sqrt(piv);
-    __syncthreads();
-    for (int i = k + tid; i < q; i += 64) A[i * q + k] = (i == k) ? lkk : A[i * q + k] / lkk;
-    __syncthreads();
-    for (int idx = tid; idx < (q - k - 1) * (q - k - 1); idx += 64) {
-      int i = k + 1 + idx / (q - k - 1), j = k + 1 + idx % (q - k - 1);
-      if (j <= i) A[i * q + j] -= A[i * q + k] * A[j * q + k];
-    }
-    __syncthreads();
-  }
-  // thread c solves A x = gram[:, c]; contributes x[c]
+  double* buf = sh + q * q;
+  if (tid == 0) bad = 0;
+  for (int idx = tid; idx < q * q; idx += 256) A[idx] = sigma * dblk[(int64_t)h * q * q + idx];
+  small_inverse<4>(A, q, +1, &bad, buf);
   double contrib = 0;
-  for (int c = tid; c < q; c += 64) {
-    for (int i = 0; i < q; i++) {              // forward: L y = b
-      double v = X[i * q + c];
-      for (int k = 0; k < i; k++) v -= A[i * q + k] * X[k * q + c];
-      X[i * q + c] = v / A[i * q + i];
-    }
-    for (int i = q - 1; i >= 0; i--) {         // backward: L^T x = y
-      double v = X[i * q + c];
-      for (int k = i + 1; k < q; k++) v -= A[k * q + i] * X[k * q + c];
-      X[i * q + c] = v / A[i * q + i];
-    }
-    contrib += X[c * q + c];
-  }
+  for (int idx = tid; idx < q * q; idx += 256) contrib += A[idx] * gram[(int64_t)h * q * q + idx];
   contrib = wave_sum(contrib);
-  if (tid == 0) score[h] = contrib;
+  if ((tid & 63) == 0) red[tid >> 6] = contrib;
+  __syncthreads();
+  if (tid == 0) {
+    score[h] = red[0] + red[1] + red[2] + red[3];
+    if (bad) ctrl->notpd = 1;
+  }
+}
+// groups of one row: one thread per group
+__global__ __launch_bounds__(256) void score_q1_kernel(int p, const int32_t* __restrict__ kept, const double* __restrict__ gram,
+                                                        const double* __restrict__ dblk, double* __restrict__ score,
+                                                        SearchCtrl* ctrl, int skip_if_done) {
+  if (skip_if_done && ctrl->done) return;
+  const int h = blockIdx.x * 256 + threadIdx.x;
+  if (h >= p) return;
+  double a = (kept[h] ? -1.0 : 1.0) * dblk[h];
+  if (!(a > 0.0)) { ctrl->notpd = 1; a = 1.0; }
+  score[h] = gram[h] / a;
+}
+static void launch_score(const TabDims& d, const int32_t* kept, const double* gram, const double* dblk, double* score,
+                         SearchCtrl* ctrl, int skip_if_done, hipStream_t s) {
+  if (d.q == 1)
+    hipLaunchKernelGGL(score_q1_kernel, dim3((d.p + 255) / 256), dim3(256), 0, s, d.p, kept, gram, dblk, score, ctrl, skip_if_done);
+  else
+    hipLaunchKernelGGL(score_kernel, dim3(d.p), dim3(256), (size_t)(d.q * d.q + 256) * 8, s, d, kept, gram, dblk, score, ctrl,
+                       skip_if_done);
 }
 
 hipError_t launch_refresh_scores(const TabDims& d, const TabPtrs& t, hipStream_t s) {
@@ -474,8 +476,7 @@ hipError_t launch_refresh_scores(const TabDims& d, const TabPtrs& t, hipStream_t
     hipLaunchKernelGGL(group_gram_kernel, dim3(d.p, nb * (nb + 1) / 2), dim3(256), 0, s, d, t.Z, t.gram, (const SearchCtrl*)nullptr);
     hipLaunchKernelGGL(dblk_copy_kernel, dim3(d.p), dim3(256), 0, s, d, t.N, t.dblk);
   }
-  hipLaunchKernelGGL(score_kernel, dim3(d.p), dim3(64), (size_t)2 * d.q * d.q * 8, s, d, t.kept, t.gram, t.dblk, t.score,
-                     t.ctrl, 0);
+  launch_score(d, t.kept, t.gram, t.dblk, t.score, t.ctrl, 0, s);
   return hipGetLastError();
 }
 
@@ -696,50 +697,57 @@ __global__ __launch_bounds__(256) void extract_pair_kernel(TabDims d, const floa
 __global__ __launch_bounds__(256) void pair_small_kernel(TabDims d, const float* __restrict__ C1, const float* __restrict__ C2,
                                                           double* __restrict__ small, SearchCtrl* ctrl,
                                                           const int32_t* __restrict__ single) {
-  __shared__ double colbuf[256];
+  extern __shared__ double psm[];      // three q x q matrices, then 256 doubles for the inverses
   __shared__ int32_t bad;
   if (ctrl->done) return;
   const int q = d.q, qq = q * q, tid = threadIdx.x;
   const int g0 = (single ? *single : ctrl->g_out) * q, j0 = (single ? *single : ctrl->g_in) * q;
   double* Dg = small; double* Njg = small + qq; double* M1 = small + 2 * qq; double* Dj = small + 3 * qq;
   double* W2Dj = small + 4 * qq;
+  double* X0 = psm; double* X1 = psm + qq; double* X2 = psm + 2 * qq; double* buf = psm + 3 * qq;
   if (tid == 0) bad = 0;
   for (int idx = tid; idx < qq; idx += 256) {
-    int r = idx / q, c = idx % q;
-    Dg[idx] = (double)C1[(int64_t)(g0 + r) * q + c];       // N_gg
-    Njg[idx] = (double)C1[(int64_t)(j0 + r) * q + c];      // N(j_r, g_c)
-    Dj[idx] = (double)C2[(int64_t)(j0 + r) * q + c];       // N_jj
+    const int r = idx / q, c = idx % q;
+    X0[idx] = (double)C1[(int64_t)(g0 + r) * q + c];          // N_gg
+    const double njg = (double)C1[(int64_t)(j0 + r) * q + c]; // N(j_r, g_c)
+    Njg[idx] = njg;
+    X1[c * q + r] = njg;                                      // N_gj = Njg^T
   }
-  __syncthreads();
-  small_inverse<4>(Dg, q, -1, &bad, colbuf);                  // kept pivot: N_gg = -P_gg is negative definite
+  small_inverse<4>(X0, q, -1, &bad, buf);                    // kept pivot: N_gg = -P_gg is negative definite
+  for (int idx = tid; idx < qq; idx += 256) Dg[idx] = X0[idx];
   if (single) {
     // Case 1 alone: with M1 = 0 and Dj' = 0 every term of the second sweep below vanishes
     for (int idx = tid; idx < qq; idx += 256) { M1[idx] = 0.0; Dj[idx] = 0.0; W2Dj[idx] = 0.0; Njg[idx] = 0.0; }
-    __syncthreads();
   } else {
-  for (int idx = tid; idx < qq; idx += 256) {              // M1 = Dg * N_gj, N_gj = Njg^T
-    int r = idx / q, c = idx % q;
-    double v = 0;
-    for (int k = 0; k < q; k++) v += Dg[r * q + k] * Njg[c * q + k];
-    M1[idx] = v;
+    for (int idx = tid; idx < qq; idx += 256) {              // M1 = Dg N_gj
+      const int r = idx / q, c = idx % q;
+      double v = 0;
+      for (int k = 0; k < q; k++) v += X0[r * q + k] * X1[k * q + c];
+      X2[idx] = v; M1[idx] = v;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < qq; idx += 256) {              // X0 = N_jg
+      const int r = idx / q, c = idx % q;
+      X0[idx] = X1[c * q + r];
+    }
+    __syncthreads();
+    for (int idx = tid; idx < qq; idx += 256) {              // N'_jj = N_jj - N_jg M1  (into X1, N_gj being spent)
+      const int r = idx / q, c = idx % q;
+      double v = 0;
+      for (int k = 0; k < q; k++) v += X0[r * q + k] * X2[k * q + c];
+      Dj[idx] = (double)C2[(int64_t)(j0 + r) * q + c] - v;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < qq; idx += 256) X1[idx] = Dj[idx];
+    small_inverse<4>(X1, q, +1, &bad, buf);                  // entering pivot: Schur complement, positive definite
+    for (int idx = tid; idx < qq; idx += 256) {              // W2Dj = W2 Dj', W2 = N'_gj = -M1
+      const int r = idx / q, c = idx % q;
+      double v = 0;
+      for (int k = 0; k < q; k++) v -= X2[r * q + k] * X1[k * q + c];
+      W2Dj[idx] = v; Dj[idx] = X1[idx];
+    }
   }
   __syncthreads();
-  for (int idx = tid; idx < qq; idx += 256) {              // N'_jj = N_jj - N_jg M1
-    int r = idx / q, c = idx % q;
-    double v = 0;
-    for (int k = 0; k < q; k++) v += Njg[r * q + k] * M1[k * q + c];
-    Dj[idx] -= v;
-  }
-  __syncthreads();
-  small_inverse<4>(Dj, q, +1, &bad, colbuf);                  // entering pivot: Schur complement, positive definite
-  for (int idx = tid; idx < qq; idx += 256) {              // W2Dj = W2 * Dj', W2 = N'_gj = -M1
-    int r = idx / q, c = idx % q;
-    double v = 0;
-    for (int k = 0; k < q; k++) v -= M1[r * q + k] * Dj[k * q + c];
-    W2Dj[idx] = v;
-  }
-  __syncthreads();
-  }
   if (tid == 0) { ctrl->delta = 0.0; if (bad) ctrl->notpd = 1; }
 }
 
@@ -1141,12 +1149,17 @@ hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int force
       }
       hipLaunchKernelGGL(exact_blocks_kernel, dim3(d.p), dim3(256), xb_lds, s, d, t.C1, t.cross, t.gram, t.dblk, t.kept, t.ctrl,
                          t.xgram, t.xdblk);
-      hipLaunchKernelGGL(score_kernel, dim3(d.p), dim3(64), (size_t)2 * q * q * 8, s, d, t.kept, t.xgram, t.xdblk, t.xscore, t.ctrl, 1);
+      launch_score(d, t.kept, t.xgram, t.xdblk, t.xscore, t.ctrl, 1, s);
     }
     hipLaunchKernelGGL(select_in_kernel, dim3(1), dim3(1024), 0, s, d, t.kept, t.xscore, t.ctrl);
     hipLaunchKernelGGL(extract_pair_kernel, dim3(rb), dim3(256), 0, s, d, t.N, t.Z, t.ctrl, t.C1, t.C2, t.rZ1, t.rZ2, single);
   }
-  hipLaunchKernelGGL(pair_small_kernel, dim3(1), dim3(256), 0, s, d, t.C1, t.C2, t.small, t.ctrl, single);
+  const size_t ps_lds = (size_t)(3 * q * q + 256) * 8;
+  if (ps_lds > 65536) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(pair_small_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ps_lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(pair_small_kernel, dim3(1), dim3(256), ps_lds, s, d, t.C1, t.C2, t.small, t.ctrl, single);
   hipLaunchKernelGGL(pair_cols_kernel, dim3((d.m + PC_COLS - 1) / PC_COLS), dim3(256), pc_lds, s, d,
                      t.rZ1, t.rZ2, t.small, t.ctrl);
   hipLaunchKernelGGL(pair_accept_kernel, dim3(1), dim3(1), 0, s, t.ctrl, always_accept, t.trace_out, t.trace_in, t.trace_gap,
@@ -1178,7 +1191,7 @@ hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int force
     hipLaunchKernelGGL(group_gram_kernel, dim3(d.p, nb * (nb + 1) / 2), dim3(256), 0, s, d, t.Z, t.gram, t.ctrl);
   }
   if (ev) hipEventRecord(ev[2], s);
-  hipLaunchKernelGGL(score_kernel, dim3(d.p), dim3(64), (size_t)2 * q * q * 8, s, d, t.kept, t.gram, t.dblk, t.score, t.ctrl, 1);
+  launch_score(d, t.kept, t.gram, t.dblk, t.score, t.ctrl, 1, s);
   return hipGetLastError();
 }
 
