@@ -921,14 +921,19 @@ __global__ __launch_bounds__(256) void pair_dblk_kernel(TabDims d, const float* 
   const int q = d.q, qq = q * q, h = blockIdx.x;
   const int g = single ? *single : ctrl->g_out, j = single ? g : ctrl->g_in;
   if (h == g || h == j) return;    // pivot groups get their blocks in pair_fix_kernel
-  float* a1 = pds; float* b1 = pds + qq; float* a2 = pds + 2 * qq; float* b2 = pds + 3 * qq;
+  // rows of b1, b2 are read by neighbouring threads: stride q + 1 keeps them in different LDS banks
+  const int qs = q + 1;
+  float* a1 = pds; float* a2 = pds + qq; float* b1 = pds + 2 * qq; float* b2 = b1 + q * qs;
   const int64_t base = (int64_t)h * qq;
-  for (int idx = threadIdx.x; idx < qq; idx += 256) { a1[idx] = P1D[base + idx]; b1[idx] = P1[base + idx]; a2[idx] = P2D[base + idx]; b2[idx] = P2[base + idx]; }
+  for (int idx = threadIdx.x; idx < qq; idx += 256) {
+    const int r = idx / q, c = idx % q;
+    a1[idx] = P1D[base + idx]; a2[idx] = P2D[base + idx]; b1[r * qs + c] = P1[base + idx]; b2[r * qs + c] = P2[base + idx];
+  }
   __syncthreads();
   for (int idx = threadIdx.x; idx < qq; idx += 256) {
     const int r = idx / q, c = idx % q;
     double v = 0;
-    for (int k = 0; k < q; k++) v += (double)a1[r * q + k] * (double)b1[c * q + k] + (double)a2[r * q + k] * (double)b2[c * q + k];
+    for (int k = 0; k < q; k++) v += (double)a1[r * q + k] * (double)b1[c * qs + k] + (double)a2[r * q + k] * (double)b2[c * qs + k];
     dblk[base + idx] -= v;
   }
 }
@@ -1173,7 +1178,7 @@ hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int force
                      single);
   hipLaunchKernelGGL(pair_fix_kernel, dim3((d.d1 + 3) / 4), dim3(256), 0, s, d, t.N, t.Z, P1, P2, P1D, P2D, t.rZ1, t.rZ2, t.small,
                      t.ctrl, t.dblk, t.kept, single);
-  hipLaunchKernelGGL(pair_dblk_kernel, dim3(d.p), dim3(256), (size_t)4 * q * q * 4, s, d, P1, P2, P1D, P2D, t.ctrl, t.dblk, single);
+  hipLaunchKernelGGL(pair_dblk_kernel, dim3(d.p), dim3(256), (size_t)(4 * q * q + 2 * q) * 4, s, d, P1, P2, P1D, P2D, t.ctrl, t.dblk, single);
   if (ev) hipEventRecord(ev[0], s);
   if (q == 1) {
     dim3 grid((d.d1 + 1023) / 1024, (d.d1 + 31) / 32);
