@@ -63,15 +63,20 @@ __device__ void small_inverse(double* A, int n, int want_sign, int32_t* bad, dou
         for (int b = 0; b < T; b++) rs[b] = rowb[tj * T + b] * d;
 #pragma unroll
         for (int a = 0; a < T; a++) cs[a] = colb[ti * T + a];
+        // rank-one step on the whole block; the pivot row and column (meaningless after it) are rewritten by their owners
 #pragma unroll
         for (int a = 0; a < T; a++)
 #pragma unroll
-          for (int b = 0; b < T; b++) {
-            const int i = ti * T + a, j = tj * T + b;
-            if (i == k) r[a][b] = (j == k) ? d : rs[b];
-            else if (j == k) r[a][b] = -cs[a] * d;
-            else r[a][b] -= cs[a] * rs[b];
-          }
+          for (int b = 0; b < T; b++) r[a][b] -= cs[a] * rs[b];
+        if (tj == k0 / T) {
+#pragma unroll
+          for (int a = 0; a < T; a++) r[a][kk] = -cs[a] * d;
+        }
+        if (ti == k0 / T) {
+#pragma unroll
+          for (int b = 0; b < T; b++) r[kk][b] = rs[b];
+          if (tj == k0 / T) r[kk][kk] = d;
+        }
       }
     }
   }
