@@ -699,6 +699,11 @@ def test_keep_everything_and_keep_one():
     free = orc.local_search(H, G, c0, orc.magnitude_support(W.double().numpy(), 20, 1, 1), 20, 1, 30)
     assert support.tolist() == free.support
     assert obj >= best_obj * (1 - 1e-6)
+    # with one kept group the exact entering rule scores every other single group exactly: one move reaches the optimum
+    s.osscar_init_support()
+    rx = s.osscar_local_search(30, flags=pkg.OSSCAR_SEARCH_EXACT_IN)
+    What, support, obj = s.osscar_backsolve()
+    assert support.tolist() == sorted(best) and abs(obj - best_obj) <= 1e-5 * best_obj and rx["accepted"] <= 1
     s.close()
 
 
