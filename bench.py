@@ -209,13 +209,17 @@ def main():
                           "achieved": gram_flops / phases["gram"] / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
                           "frac": gram_flops / phases["gram"] / 1e12 / 2500.0,
                           "note": "algorithmic SYRK flops n*d1*(d1+1); the kernel issues 2x that on diagonal tiles only"},
-        "search_iteration": {"note": "per swap: four small kernels (selection and pivot algebra, current pivot rows/columns, w from the "
-                                     "products computed ahead, update of norms/diagonal/scores); every 64 swaps a flush by matrix "
-                                     "products plus one look-ahead product Zc Z^T.  An eager in-place up/downdate of P, B, V, R would "
-                                     "move bytes_per_swap_eager per swap",
-                             "ms_per_swap": ms_swap, "w_kernels_ms": 1e3 * upd_n, "iteration_kernels_ms": 1e3 * upd_z,
-                             "bytes_per_swap_eager": bytes_swap_alg,
-                             "eager_equivalent_GBps": bytes_swap_alg / ms_swap / 1e6},
+        "search_iteration": ({"note": "per swap: four small kernels (selection and pivot algebra, current pivot rows/columns, w from the "
+                                      "products computed ahead, update of norms/diagonal/scores); every 64 swaps a flush by matrix "
+                                      "products plus one look-ahead product Zc Z^T.  An eager in-place up/downdate of P, B, V, R would "
+                                      "move bytes_per_swap_eager per swap",
+                              "ms_per_swap": ms_swap, "w_kernels_ms": 1e3 * upd_n, "iteration_kernels_ms": 1e3 * upd_z,
+                              "bytes_per_swap_eager": bytes_swap_alg,
+                              "eager_equivalent_GBps": bytes_swap_alg / ms_swap / 1e6} if lazy else
+                             {"note": "in-place search: every swap is one rank-2q pass over the tableau (N: lower triangle, Z)",
+                              "ms_per_swap": ms_swap, "update_N_ms": 1e3 * upd_n, "update_Z_ms": 1e3 * upd_z,
+                              "bytes_per_swap": bytes_swap_alg,
+                              "update_GBps": bytes_swap_alg / max(upd_n + upd_z, 1e-12) / 1e9}),
     }
     s.close()
     del X

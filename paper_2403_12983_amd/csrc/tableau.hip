@@ -1039,10 +1039,23 @@ __global__ __launch_bounds__(256) void update_Z_kernel(TabDims d, float* __restr
   if (q == 1) {
     const float a1 = P1[h], a2 = P2[h];
     double v = 0;
-    for (int col = threadIdx.x; col < m; col += 256) {
-      float z = Zh[col] - (a1 * rZ1[col] + a2 * rZ2[col]);
-      Zh[col] = z;
-      v += (double)z * (double)z;
+    if ((m & 3) == 0) {                        // rows are 16-byte aligned: four columns per load
+      float4* Z4 = reinterpret_cast<float4*>(Zh);
+      const float4* r1 = reinterpret_cast<const float4*>(rZ1);
+      const float4* r2 = reinterpret_cast<const float4*>(rZ2);
+      for (int c4 = threadIdx.x; c4 < (m >> 2); c4 += 256) {
+        float4 z = Z4[c4];
+        const float4 x = r1[c4], y = r2[c4];
+        z.x -= a1 * x.x + a2 * y.x; z.y -= a1 * x.y + a2 * y.y; z.z -= a1 * x.z + a2 * y.z; z.w -= a1 * x.w + a2 * y.w;
+        Z4[c4] = z;
+        v += (double)z.x * (double)z.x + (double)z.y * (double)z.y + (double)z.z * (double)z.z + (double)z.w * (double)z.w;
+      }
+    } else {
+      for (int col = threadIdx.x; col < m; col += 256) {
+        float z = Zh[col] - (a1 * rZ1[col] + a2 * rZ2[col]);
+        Zh[col] = z;
+        v += (double)z * (double)z;
+      }
     }
     __shared__ double red[4];
     v = wave_sum(v);
