@@ -217,7 +217,10 @@ __global__ __launch_bounds__(256, 2) void gemm_f64acc_kernel(GemmArgs g, int vec
 // the delayed-update search.  Same tiling; each wave owns 64 x 64 as 2 x 2 tiles of 32 x 32.  float output only.
 typedef float f16v __attribute__((ext_vector_type(16)));
 
-__global__ __launch_bounds__(256, 2) void gemm_f32acc_kernel(GemmArgs g, int vecA, int vecB, int vecC) {
+// SPLITK: blockIdx.y selects a range of kper values of K; the partial product (float32 accumulation over that range only)
+// is added to the float64 C by atomics, alpha applied, Cin / beta / diag_add ignored: C must hold zeros (or the addend).
+template <bool SPLITK>
+__global__ __launch_bounds__(256, 2) void gemm_f32acc_kernel(GemmArgs g, int vecA, int vecB, int vecC, int kper) {
   __shared__ __attribute__((aligned(16))) float smem[2 * 2 * BK * LDT];
   float (*As)[BK][LDT] = reinterpret_cast<float (*)[BK][LDT]>(smem);
   float (*Bs)[BK][LDT] = reinterpret_cast<float (*)[BK][LDT]>(smem + 2 * BK * LDT);
@@ -238,7 +241,9 @@ __global__ __launch_bounds__(256, 2) void gemm_f32acc_kernel(GemmArgs g, int vec
     for (int j = 0; j < 2; j++)
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
-  const int ktiles = (g.K + BK - 1) / BK;
+  const int kt_begin = SPLITK ? (int)blockIdx.y * (kper / BK) : 0;
+  const int kt_all = (g.K + BK - 1) / BK;
+  const int ktiles = SPLITK ? ((kt_begin + kper / BK < kt_all) ? kt_begin + kper / BK : kt_all) : kt_all;
   Tile8 ra, rb;
   auto gload = [&](int kt) {
     int k0 = kt * BK;
@@ -261,9 +266,9 @@ __global__ __launch_bounds__(256, 2) void gemm_f32acc_kernel(GemmArgs g, int vec
       for (int i = 0; i < 8; i++) Bs[buf][b_k][b_n + i] = rb.v[i];
     }
   };
-  if (ktiles > 0) { gload(0); sstore(0); }
+  if (ktiles > kt_begin) { gload(kt_begin); sstore(kt_begin & 1); }
   __syncthreads();
-  for (int kt = 0; kt < ktiles; kt++) {
+  for (int kt = kt_begin; kt < ktiles; kt++) {
     int buf = kt & 1;
     if (kt + 1 < ktiles) gload(kt + 1);
 #pragma unroll
@@ -283,6 +288,21 @@ __global__ __launch_bounds__(256, 2) void gemm_f32acc_kernel(GemmArgs g, int vec
     __syncthreads();
   }
   // epilogue: lane holds rows (r/4)*8 + (lane/32)*4 + r%4, column lane%32 of each 32 x 32 tile; staged per 32 rows
+  if (SPLITK) {
+    double* Cd = reinterpret_cast<double*>(g.C);
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+#pragma unroll
+      for (int j = 0; j < 2; j++) {
+        const int col = n0 + wn * 64 + j * 32 + (lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const int row = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+          if (row < g.M && col < g.N) unsafeAtomicAdd(Cd + (int64_t)row * g.ldc + col, g.alpha * (double)acc[i][j][r]);
+        }
+      }
+    return;
+  }
   float* C = reinterpret_cast<float*>(g.C);
   const float* Cin = g.Cin;
   const bool use_cin = (Cin != nullptr && g.beta != 0.0);
@@ -344,8 +364,12 @@ hipError_t launch_gemm_f64acc(const GemmArgs& a, hipStream_t s) {
   int vecB = (a.ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.B) & 15) == 0);
   int vecC = (!a.c_is_f64) && (a.ldc % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.C) & 15) == 0) &&
              (a.Cin == nullptr || ((a.ldcin % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.Cin) & 15) == 0)));
-  if (a.acc_f32 && !a.c_is_f64)
-    hipLaunchKernelGGL(gemm_f32acc_kernel, dim3(blocks), dim3(256), 0, s, a, vecA, vecB, vecC);
+  if (a.acc_f32 && a.c_is_f64) {
+    // float32 accumulation over windows of `kper` of K, float64 across the windows (atomics into C, which holds the addend)
+    const int kper = 1024;
+    hipLaunchKernelGGL(gemm_f32acc_kernel<true>, dim3(blocks, (a.K + kper - 1) / kper), dim3(256), 0, s, a, vecA, vecB, 0, kper);
+  } else if (a.acc_f32)
+    hipLaunchKernelGGL(gemm_f32acc_kernel<false>, dim3(blocks), dim3(256), 0, s, a, vecA, vecB, vecC, 0);
   else if (a.c_is_f64)
     hipLaunchKernelGGL(gemm_f64acc_kernel<double>, dim3(blocks), dim3(256), 0, s, a, vecA, vecB, 0);
   else

@@ -20,7 +20,8 @@ struct GemmArgs {
   int c_is_f64;                  // output (and Cin) element type: 0 float, 1 double
   int lower_only;                // 1: compute only tiles that touch the lower triangle (row >= col)
   int trans_b;                   // 1: B is given as N x K row-major (C = alpha * A * B^T + ...)
-  int acc_f32;                   // 1: accumulate in float32 (v_mfma_f32_32x32x2_f32), float output only
+  int acc_f32;                   // 1: accumulate in float32 (v_mfma_f32_32x32x2_f32).  With c_is_f64: float32 over windows of
+                                 // 1024 of K, added to the float64 C by atomics (C holds the addend; alpha only)
 };
 hipError_t launch_gemm_f64acc(const GemmArgs& a, hipStream_t s);
 

@@ -689,6 +689,11 @@ static hipError_t launch_candidates(const TabDims& d, const TabPtrs& t, const La
   GemmArgs g{};                         // GbT[0 .. LAZY_NC) = Zc Z0^T, float64
   g.M = n_k + n_c; g.N = d.d1; g.K = d.m; g.A = L.Zc; g.lda = d.m; g.B = t.Z; g.ldb = d.m; g.trans_b = 1;
   g.C = L.GbT; g.ldc = d.d1; g.alpha = 1.0; g.beta = 0.0; g.c_is_f64 = 1;
+  // float32 matrix-core accumulation over 1024-long windows of the m columns, float64 across windows (the products are
+  // exact either way; the windowed sum is accurate to ~1e-7 of |z_c| |z_i|, which the per-flush refresh of the scores bounds)
+  g.acc_f32 = 1;
+  e = hipMemsetAsync(L.GbT, 0, (size_t)(n_k + n_c) * d.d1 * 8, s);
+  if (e != hipSuccess) return e;
   return launch_gemm_f64acc(g, s);
 }
 
