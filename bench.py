@@ -18,7 +18,7 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
-GEMM_TRAFFIC_CFG5 = 39.75e9   # bytes; see profiles/gemm_f64acc_cfg5_pmc.md
+GEMM_TRAFFIC_CFG5 = 43.37e9   # bytes; see profiles/gemm_f64acc_cfg5_pmc.md
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -119,11 +119,11 @@ def main():
 
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
     phases = {k: 0.0 for k in ("gram", "finalize", "init", "search", "backsolve")}
-    upd_n = upd_z = gemm_ms = 0.0
+    upd_n = upd_z = gemm_ms = gemm32_ms = 0.0
     info = {}
 
     def step(timed):
-        nonlocal upd_n, upd_z, gemm_ms
+        nonlocal upd_n, upd_z, gemm_ms, gemm32_ms
         ev[0].record()
         s.osscar_gram(X, False)
         ev[1].record()
@@ -150,6 +150,7 @@ def main():
             upd_n += tm[5] / 1e3
             upd_z += tm[7] / 1e3
             gemm_ms += tm[9]
+            gemm32_ms += tm[10]
         info.update(obj0=obj0, obj=obj, iters=r["iters"], accepted=r["accepted"], tracked=r["obj_final"])
 
     for _ in range(a.warmup):
@@ -166,6 +167,7 @@ def main():
     upd_n /= K
     upd_z /= K
     gemm_ms /= K
+    gemm32_ms /= K
     t_layer = wall / K
 
     d1, m, n = cfg.d1, cfg.m, cfg.n
@@ -205,6 +207,14 @@ def main():
                      "unit": "TFLOP/s", "frac": g_flops / (gemm_ms * 1e-3) / 1e12 / 78.6 if gemm_ms > 0 else None,
                      "traffic": g_traffic, "flops_per_launch": g_flops, "algorithmic_bytes_per_launch": g_bytes,
                      "ms_per_launch": gemm_ms},
+        # The float32-accumulating MFMA GEMM (v_mfma_f32_32x32x2_f32: flushes of the search, sweeps of the inverse, small
+        # corrections) takes about as long per layer as the float64-accumulating one; its largest launch is the lower triangle
+        # of P (I - H_KK P) in the Newton-Schulz step: kr^3 flops (timer slot 10).
+        "roofline_gemm_f32acc": {"kernel": "gemm_f32acc_kernel<false>, launch tril(P (I - H_KK P))", "bound": "mfma",
+                                 "achieved": float(kr) ** 3 / (gemm32_ms * 1e-3) / 1e12 if gemm32_ms > 0 else None,
+                                 "peak": 157.3, "unit": "TFLOP/s",
+                                 "frac": float(kr) ** 3 / (gemm32_ms * 1e-3) / 1e12 / 157.3 if gemm32_ms > 0 else None,
+                                 "ms_per_launch": gemm32_ms},
         "roofline_gram": {"kernel": "gram_packed_kernel (+ gram_pack_kernel, whole Gram phase)", "bound": "mfma",
                           "achieved": gram_flops / phases["gram"] / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
                           "frac": gram_flops / phases["gram"] / 1e12 / 2500.0,

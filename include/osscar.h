@@ -218,7 +218,8 @@ osscar_status osscar_get_scalars(osscar_ctx* ctx, double* lambda_host, double* c
  * delayed-update search [5] mean duration of the two kernels that produce w = Z [y1 y2] (a pass over Z only for a
  * pivot whose products were not computed ahead), [7] of all kernels of that iteration from there on.
  * [8] the product G = H W inside finalize (one GEMM launch, or the three bf16 products and their repacking when W is
- * bf16).  [9] the product V = P H_{K,Kc} of the last state build (one GEMM launch).  [10..11] reserved.
+ * bf16).  [9] the product V = P H_{K,Kc} of the last state build (one GEMM launch).  [10] the lower-triangle product
+ * P (I - H_KK P) of the last Newton-Schulz step (one launch of the float32-accumulating GEMM).  [11] reserved.
  * out_host: 12 doubles. */
 osscar_status osscar_get_timers(osscar_ctx* ctx, double* out_host);
 

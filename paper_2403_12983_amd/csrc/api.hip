@@ -276,12 +276,15 @@ osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b, const float* 
     HIPCHK(c, launch_absmax(b.T1, (int64_t)kr * kr, c->partial, s));
     // P + P (I - H P) is symmetric up to rounding: compute its lower triangle and mirror it
     // (the correction P (I - H P) is about 1e-5 of P: float32 accumulation of it is far below P's own rounding)
+    HIPCHK(c, hipEventRecord(c->ev_s[1][0], s));
     HIPCHK(c, gemm(s, kr, kr, kr, b.P, kr, b.T1, kr, b.P, kr, b.T2, kr, 1.0, 1.0, 0.0, 1, 0, 1));
+    HIPCHK(c, hipEventRecord(c->ev_s[1][1], s));
     hipLaunchKernelGGL(mirror_from_lower_kernel, dim3(grid_for((int64_t)kr * kr)), dim3(256), 0, s, b.T2, b.P, kr);
     double part[256]; int32_t bad = 0;
     HIPCHK(c, hipMemcpyAsync(part, c->partial, sizeof part, hipMemcpyDeviceToHost, s));
     HIPCHK(c, hipMemcpyAsync(&bad, c->notpd, 4, hipMemcpyDeviceToHost, s));
     HIPCHK(c, hipStreamSynchronize(s));
+    { float ms = 0; hipEventElapsedTime(&ms, c->ev_s[1][0], c->ev_s[1][1]); c->timers[10] = ms; }
     double resid = 0; for (double v : part) resid = std::max(resid, v);
     if (bad || !(resid < 0.9))
       return fail(c, OSSCAR_ENOTPD, "H restricted to the kept rows is not positive definite to working precision "
