@@ -42,6 +42,10 @@ SMALL = {
     "cfg4s": lambda: inp.scaled(inp.CONFIGS["cfg4"], p=8, m=96, n=2100, k=5, swaps=10, mix=0.7),
     # bf16 with d1 not a multiple of 8: takes the generic Gram path
     "cfg5odd": lambda: inp.scaled(inp.CONFIGS["cfg5"], p=203, m=50, n=777, k=101, swaps=30),
+    # mixed dtypes: bf16 activations with float32 weights (G = H W on the float64-accumulating GEMM), and float32
+    # activations with bf16 weights (generic Gram path, G = H W as three bf16 products)
+    "mix_bf16_f32": lambda: inp.scaled(inp.CONFIGS["cfg3"], p=264, m=72, n=1100, k=120, swaps=25, mix=0.4).replace(w_dtype="f32"),
+    "mix_f32_bf16": lambda: inp.scaled(inp.CONFIGS["cfg3"], p=264, m=72, n=1100, k=120, swaps=25, mix=0.4).replace(x_dtype="f32"),
     # other seeds of the same recipes
     "cfg1+1": lambda: inp.CONFIGS["cfg1"].replace(seed=inp.CONFIGS["cfg1"].seed + 1),
     "cfg2s+1": lambda: inp.scaled(inp.CONFIGS["cfg2"], p=24, m=40, n=1500, k=12, swaps=20, mix=0.5, seed=inp.CONFIGS["cfg2"].seed + 1),
@@ -139,7 +143,15 @@ def test_initial_state_and_scores(name):
     fk, fc = np.isfinite(rem_o), np.isfinite(add_o)
     assert np.array_equal(np.isfinite(rem_g), fk) and np.array_equal(np.isfinite(add_g), fc)
     assert np.max(np.abs(rem_g[fk] - rem_o[fk]) / rem_o[fk]) < 2e-5
-    assert np.max(np.abs(add_g[fc] - add_o[fc]) / add_o[fc]) < 2e-5
+    # An addition gain is Tr(R_j^T S_j^-1 R_j) with R_j = G_j - H_jK B a difference: where the kept groups explain group j
+    # well, |R_j| << |G_j| and the rounding of the float32 inputs of that difference (6e-8; 2.5e-7 for H from the bf16
+    # matrix-core Gram) is magnified by |G_j| / |R_j|, twice over in the square.  On the benchmark recipes that factor
+    # stays below 3; the correlated cases reach 100.
+    eps_h = 2.5e-7 if cfg.x_dtype == "bf16" else 6e-8
+    q = cfg.q
+    amp = np.array([np.linalg.norm(c.G[crow[t * q:(t + 1) * q]]) / np.linalg.norm(R[t * q:(t + 1) * q]) for t in range(len(cand))])
+    tol = 2e-5 + 4 * eps_h * amp
+    assert np.all(np.abs(add_g[cand] - add_o[cand]) / add_o[cand] < tol)
     # a given support in scrambled order gives the same state
     s.osscar_init_support(_pkg().OSSCAR_INIT_GIVEN, list(reversed(c.K0)))
     assert np.allclose(T(s, "T_P"), Pg, rtol=0, atol=0)
