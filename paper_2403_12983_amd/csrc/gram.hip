@@ -547,24 +547,44 @@ hipError_t launch_convert_to_f32(const void* src, int is_bf16, int64_t rows, int
   return hipGetLastError();
 }
 
-// H[i][j] = float(H64[max(i,j)][min(i,j)] + (i == j ? lam : 0))
-__global__ void finalize_H_kernel(const double* __restrict__ H64, float* __restrict__ H, int d1,
-                                  const double* __restrict__ lam_dev) {
+// H[i][j] = float(H64[max(i,j)][min(i,j)] + (i == j ? lam : 0)).  One workgroup per 64 x 64 tile on or below the
+// diagonal: it reads the tile of H64 along its rows, writes it to H, and writes the mirrored tile from LDS, so that both
+// the reads and the writes run along rows.
+__global__ __launch_bounds__(256) void finalize_H_kernel(const double* __restrict__ H64, float* __restrict__ H, int d1,
+                                                          const double* __restrict__ lam_dev) {
+  __shared__ float tile[64][65];
   const double lam = lam_dev ? lam_dev[0] : 0.0;
-  int64_t n = (int64_t)d1 * d1;
-  for (int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; idx < n; idx += (int64_t)gridDim.x * blockDim.x) {
-    int i = (int)(idx / d1), j = (int)(idx % d1);
-    double v = (i >= j) ? H64[idx] : H64[(int64_t)j * d1 + i];
-    if (i == j) v += lam;
-    H[idx] = (float)v;
+  // tile index -> (tr, tc), tc <= tr
+  const int t = blockIdx.x;
+  int tr = (int)((sqrtf(8.f * (float)t + 1.f) - 1.f) * 0.5f);
+  while ((int64_t)(tr + 1) * (tr + 2) / 2 <= t) tr++;
+  while ((int64_t)tr * (tr + 1) / 2 > t) tr--;
+  const int tc = t - tr * (tr + 1) / 2;
+  const int r0 = tr * 64, c0 = tc * 64;
+  const int lx = threadIdx.x & 63, ly = threadIdx.x >> 6;
+  for (int k = 0; k < 16; k++) {
+    const int i = r0 + ly + 4 * k, j = c0 + lx;
+    float v = 0.f;
+    if (i < d1 && j < d1) {
+      // on a diagonal tile the entries above the diagonal come from their mirror images
+      double x = (i >= j) ? H64[(int64_t)i * d1 + j] : H64[(int64_t)j * d1 + i];
+      if (i == j) x += lam;
+      v = (float)x;
+      H[(int64_t)i * d1 + j] = v;
+    }
+    tile[ly + 4 * k][lx] = v;
+  }
+  if (tr == tc) return;
+  __syncthreads();
+  for (int k = 0; k < 16; k++) {
+    const int i = c0 + ly + 4 * k, j = r0 + lx;      // row of the mirrored tile, column along the lanes
+    if (i < d1 && j < d1) H[(int64_t)i * d1 + j] = tile[lx][ly + 4 * k];
   }
 }
 
 hipError_t launch_finalize_H(const double* H64, float* H, int d1, const double* lam_dev, hipStream_t s) {
-  int64_t n = (int64_t)d1 * d1;
-  int blocks = (int)((n + 1023) / 1024);
-  if (blocks > 131072) blocks = 131072;
-  hipLaunchKernelGGL(finalize_H_kernel, dim3(blocks), dim3(256), 0, s, H64, H, d1, lam_dev);
+  const int64_t nt = (d1 + 63) / 64;
+  hipLaunchKernelGGL(finalize_H_kernel, dim3((unsigned)(nt * (nt + 1) / 2)), dim3(256), 0, s, H64, H, d1, lam_dev);
   return hipGetLastError();
 }
 
