@@ -119,11 +119,11 @@ def main():
 
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
     phases = {k: 0.0 for k in ("gram", "finalize", "init", "search", "backsolve")}
-    upd_n = upd_z = gemm_ms = gemm32_ms = 0.0
+    upd_n = upd_z = gemm_ms = gemm32_ms = flush_ms = 0.0
     info = {}
 
     def step(timed):
-        nonlocal upd_n, upd_z, gemm_ms, gemm32_ms
+        nonlocal upd_n, upd_z, gemm_ms, gemm32_ms, flush_ms
         ev[0].record()
         s.osscar_gram(X, False)
         ev[1].record()
@@ -151,6 +151,7 @@ def main():
             upd_z += tm[7] / 1e3
             gemm_ms += tm[9]
             gemm32_ms += tm[10]
+            flush_ms += tm[6]
         info.update(obj0=obj0, obj=obj, iters=r["iters"], accepted=r["accepted"], tracked=r["obj_final"])
 
     for _ in range(a.warmup):
@@ -168,6 +169,7 @@ def main():
     upd_z /= K
     gemm_ms /= K
     gemm32_ms /= K
+    flush_ms /= K
     t_layer = wall / K
 
     d1, m, n = cfg.d1, cfg.m, cfg.n
@@ -224,7 +226,7 @@ def main():
                                       "products plus one look-ahead product Zc Z^T.  An eager in-place up/downdate of P, B, V, R would "
                                       "move bytes_per_swap_eager per swap",
                               "ms_per_swap": ms_swap, "w_kernels_ms": 1e3 * upd_n, "iteration_kernels_ms": 1e3 * upd_z,
-                              "bytes_per_swap_eager": bytes_swap_alg,
+                              "flushes_total_ms": flush_ms, "bytes_per_swap_eager": bytes_swap_alg,
                               "eager_equivalent_GBps": bytes_swap_alg / ms_swap / 1e6} if lazy else
                              {"note": "in-place search: every swap is one rank-2q pass over the tableau (N: lower triangle, Z)",
                               "ms_per_swap": ms_swap, "update_N_ms": 1e3 * upd_n, "update_Z_ms": 1e3 * upd_z,
