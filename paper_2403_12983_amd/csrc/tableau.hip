@@ -368,14 +368,24 @@ __device__ void group_gram(const float* __restrict__ Zg, int q, int m, double* _
   }
 }
 
-__global__ __launch_bounds__(256) void gram_dblk_kernel(TabDims d, const float* __restrict__ N, const float* __restrict__ Z,
-                                                         double* __restrict__ gram, double* __restrict__ dblk) {
-  int h = blockIdx.x, q = d.q;
-  group_gram(Z + (int64_t)h * q * d.m, q, d.m, gram + (int64_t)h * q * q);
-  for (int idx = threadIdx.x; idx < q * q; idx += 256) {
-    int r = idx / q, c = idx % q;
-    dblk[(int64_t)h * q * q + idx] = (double)nsym(N, d.d1, h * q + r, h * q + c);
+// groups of one row: gram[h] = |Z_h|^2 and dblk[h] = N_hh, one wave per row (four rows per workgroup), 16-byte loads
+__global__ __launch_bounds__(256) void gram_dblk_q1_kernel(int d1, int m, const float* __restrict__ N, const float* __restrict__ Z,
+                                                            double* __restrict__ gram, double* __restrict__ dblk) {
+  const int h = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (h >= d1) return;
+  const float* z = Z + (int64_t)h * m;
+  double v = 0;
+  if ((m & 3) == 0) {
+    const float4* z4 = reinterpret_cast<const float4*>(z);
+    for (int c = lane; c < (m >> 2); c += 64) {
+      const float4 x = z4[c];
+      v += (double)x.x * (double)x.x + (double)x.y * (double)x.y + (double)x.z * (double)x.z + (double)x.w * (double)x.w;
+    }
+  } else {
+    for (int c = lane; c < m; c += 64) v += (double)z[c] * (double)z[c];
   }
+  v = wave_sum(v);
+  if (lane == 0) { gram[h] = v; dblk[h] = (double)N[(int64_t)h * d1 + h]; }
 }
 
 // gram[h] = Z_h Z_h^T for every group: 16 x 16 outputs per workgroup (lower blocks only, mirrored), Z tiles of 64 columns in LDS
@@ -475,7 +485,7 @@ static void launch_score(const TabDims& d, const int32_t* kept, const double* gr
 
 hipError_t launch_refresh_scores(const TabDims& d, const TabPtrs& t, hipStream_t s) {
   if (d.q == 1) {
-    hipLaunchKernelGGL(gram_dblk_kernel, dim3(d.p), dim3(256), 0, s, d, t.N, t.Z, t.gram, t.dblk);
+    hipLaunchKernelGGL(gram_dblk_q1_kernel, dim3((d.d1 + 3) / 4), dim3(256), 0, s, d.d1, d.m, t.N, t.Z, t.gram, t.dblk);
   } else {
     const int nb = (d.q + 15) / 16;
     hipLaunchKernelGGL(group_gram_kernel, dim3(d.p, nb * (nb + 1) / 2), dim3(256), 0, s, d, t.Z, t.gram, (const SearchCtrl*)nullptr);
