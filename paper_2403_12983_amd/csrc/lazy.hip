@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
   for (int r = tid; r < LAZY_TM; r += 256) {
     double a = 0, b = 0;
     if (r < tau)
-      for (int s = 0; s < tau; s++) { const double mv = L.Minv[s * LAZY_TM + r]; a += mv * bg[s]; b += mv * bj[s]; }   // M^-1 is symmetric (bit for bit): read down the column so that neighbouring threads share cache lines
+      for (int s = 0; s < tau; s++) { const double mv = L.Minv[r * LAZY_TM + s]; a += mv * bg[s]; b += mv * bj[s]; }
     L.xg[r] = a; L.xj[r] = b;
     pgg += bg[r] * a; pjg += bj[r] * a; pjj += bj[r] * b;
   }
