@@ -175,7 +175,7 @@ def main():
     d1, m, n = cfg.d1, cfg.m, cfg.n
     gram_flops = n * d1 * (d1 + 1)
     lazy = (cfg.q == 1) and not a.exact_in
-    # Per-swap state update as SURVEY counts it: read + write of P, V (= lower triangle of N) and B, R (= Z)
+    # Per-swap state update of an in-place search (Proposition 4.1): read + write of P, V (= lower triangle of N) and B, R (= Z)
     bytes_swap_alg = 2 * 4 * (d1 * d1 // 2) + 2 * 4 * d1 * m
     ms_swap = 1e3 * phases["search"] / max(info["iters"], 1)
     # Dominant kernel of the layer: the float64-accumulating MFMA GEMM (the inverse's refinement, B, V, S, R, the look-ahead
