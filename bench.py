@@ -182,6 +182,7 @@ def main():
     # products of the search, the back-solve's residual).  Its largest launch, V = P H_{K,Kc} in the state build, is timed by
     # HIP events on the library's stream (timer slot 9): 2 kr^2 cr flops on v_mfma_f64_16x16x4_f64.
     kr, cr = cfg.k * cfg.q, d1 - cfg.k * cfg.q
+    n_inv = d1 if a.init == "greedy" else kr       # order of the matrix the support initialisation inverts
     g_flops = 2.0 * kr * kr * cr
     g_bytes = 4.0 * (kr * kr + 2 * kr * cr)                      # read P and H_{K,Kc} once, write V once
     # HBM bytes of that launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/gemm_f64acc_cfg5_pmc.md), cfg5 only
@@ -208,14 +209,14 @@ def main():
                      "bound": "mfma", "achieved": g_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None, "peak": 78.6,
                      "unit": "TFLOP/s", "frac": g_flops / (gemm_ms * 1e-3) / 1e12 / 78.6 if gemm_ms > 0 else None,
                      "traffic": g_traffic, "flops_per_launch": g_flops, "algorithmic_bytes_per_launch": g_bytes,
-                     "ms_per_launch": gemm_ms},
+                     "ms_per_launch": gemm_ms if gemm_ms > 0 else None},
         # The float32-accumulating MFMA GEMM (v_mfma_f32_32x32x2_f32: flushes of the search, sweeps of the inverse, small
         # corrections) takes about as long per layer as the float64-accumulating one; its largest launch is the lower triangle
         # of P (I - H_KK P) in the Newton-Schulz step: kr^3 flops (timer slot 10).
         "roofline_gemm_f32acc": {"kernel": "gemm_f32acc_kernel<false>, launch tril(P (I - H_KK P))", "bound": "mfma",
-                                 "achieved": float(kr) ** 3 / (gemm32_ms * 1e-3) / 1e12 if gemm32_ms > 0 else None,
+                                 "achieved": float(n_inv) ** 3 / (gemm32_ms * 1e-3) / 1e12 if gemm32_ms > 0 else None,
                                  "peak": 157.3, "unit": "TFLOP/s",
-                                 "frac": float(kr) ** 3 / (gemm32_ms * 1e-3) / 1e12 / 157.3 if gemm32_ms > 0 else None,
+                                 "frac": float(n_inv) ** 3 / (gemm32_ms * 1e-3) / 1e12 / 157.3 if gemm32_ms > 0 else None,
                                  "ms_per_launch": gemm32_ms},
         "roofline_gram": {"kernel": "gram_packed_kernel (+ gram_pack_kernel, whole Gram phase)", "bound": "mfma",
                           "achieved": gram_flops / phases["gram"] / 1e12, "peak": 2500.0, "unit": "TFLOP/s",

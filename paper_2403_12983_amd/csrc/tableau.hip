@@ -1131,9 +1131,69 @@ __global__ __launch_bounds__(1024) void greedy_pick_kernel(TabDims d, const int3
   }
 }
 
+// The same selection for p <= 1024 * KMAX groups with the eligible scores held in registers: every round is a local scan, a
+// shuffle reduction per wave and one more over the 16 wave records, instead of another pass over memory.
+template <int KMAX>
+__global__ __launch_bounds__(1024) void greedy_pick_reg_kernel(TabDims d, const int32_t* __restrict__ kept,
+                                                                const double* __restrict__ score, int take,
+                                                                int32_t* __restrict__ pick, float* __restrict__ gap,
+                                                                const SearchCtrl* __restrict__ ctrl, int side) {
+  __shared__ double w_v[16];
+  __shared__ int w_i[16];
+  __shared__ int chosen[65];
+  __shared__ double chosen_v[65];
+  if (ctrl->done || ctrl->pause) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  double v[KMAX];
+#pragma unroll
+  for (int k = 0; k < KMAX; k++) {
+    const int h = tid + 1024 * k;
+    v[k] = INFINITY;
+    if (h < d.p && ((kept[h] != 0) == (side == 0))) v[k] = side ? -score[h] : score[h];
+  }
+  for (int round = 0; round <= take; round++) {
+    double best = INFINITY;
+    int ib = -1;
+#pragma unroll
+    for (int k = 0; k < KMAX; k++)
+      if (v[k] < best) { best = v[k]; ib = tid + 1024 * k; }      // ascending index per thread: strict comparison keeps the lowest
+    for (int o = 32; o > 0; o >>= 1) {
+      const double b1 = __shfl_down(best, o, 64);
+      const int i2 = __shfl_down(ib, o, 64);
+      if (i2 >= 0 && (ib < 0 || b1 < best || (b1 == best && i2 < ib))) { best = b1; ib = i2; }
+    }
+    if (lane == 0) { w_v[wave] = best; w_i[wave] = ib; }
+    __syncthreads();
+    if (wave == 0) {
+      best = lane < 16 ? w_v[lane] : INFINITY;
+      ib = lane < 16 ? w_i[lane] : -1;
+      for (int o = 8; o > 0; o >>= 1) {
+        const double b1 = __shfl_down(best, o, 64);
+        const int i2 = __shfl_down(ib, o, 64);
+        if (i2 >= 0 && (ib < 0 || b1 < best || (b1 == best && i2 < ib))) { best = b1; ib = i2; }
+      }
+      if (lane == 0) { chosen[round] = ib; chosen_v[round] = best; }
+    }
+    __syncthreads();
+    const int c = chosen[round];
+    if (c >= 0 && (c & 1023) == tid) {
+#pragma unroll
+      for (int k = 0; k < KMAX; k++) if (k == (c >> 10)) v[k] = INFINITY;
+    }
+  }
+  if (tid < take) pick[tid] = chosen[tid];
+  if (tid == 0) {
+    const double edge = chosen_v[take - 1];
+    *gap = (chosen[take] >= 0) ? (float)(fabs(chosen_v[take] - edge) / fmax(fabs(edge), 1e-300)) : INFINITY;
+  }
+}
+
 hipError_t launch_greedy_pick(const TabDims& d, const TabPtrs& t, int take, int32_t* pick, float* gap, hipStream_t s, int side) {
   if (take < 1 || take > 64) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(greedy_pick_kernel, dim3(1), dim3(1024), 0, s, d, t.kept, t.score, take, pick, gap, t.ctrl, side);
+  if (d.p <= 1024 * 32)
+    hipLaunchKernelGGL(greedy_pick_reg_kernel<32>, dim3(1), dim3(1024), 0, s, d, t.kept, t.score, take, pick, gap, t.ctrl, side);
+  else
+    hipLaunchKernelGGL(greedy_pick_kernel, dim3(1), dim3(1024), 0, s, d, t.kept, t.score, take, pick, gap, t.ctrl, side);
   return hipGetLastError();
 }
 
