@@ -35,7 +35,7 @@ def cpu_baseline(inp, cfg_full):
     """The oracle as it stands on a reduced layer (same recipe), projected to the full layer by work ratios."""
     import numpy as np
     from oracle import osscar_oracle as orc
-    p, m, n, k, swaps = 4096, 1024, 16384, 2048, 24
+    p, m, n, k, swaps = 4096, 1024, 16384, 2048, 48     # about 15 s of host work
     cfg = inp.scaled(cfg_full, p=p, m=m, n=n, k=k, swaps=swaps)
     X = inp.gen_X(cfg).double().numpy()
     W = inp.gen_W(cfg).double().numpy()
