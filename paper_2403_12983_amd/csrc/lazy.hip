@@ -166,6 +166,7 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
 }
 
 // ---------------------------------------------------------------------------------------------- vectors
+__device__ __forceinline__ void wcache_block(const LazyPtrs& L, int d1, const SearchCtrl* __restrict__ ctrl, int block);
 // 8 lanes of a row: sum_s C0R[row][s] * (xa[s], xb[s]) over the LAZY_TM columns (x is zero beyond tau)
 __device__ __forceinline__ void row_dots(const float* __restrict__ crow, const double* __restrict__ xa,
                                          const double* __restrict__ xb, int l8, double& a, double& b) {
@@ -183,10 +184,15 @@ __device__ __forceinline__ void row_dots(const float* __restrict__ crow, const d
 }
 
 __global__ __launch_bounds__(256) void lazy_vectors_kernel(LazyPtrs L, const float* __restrict__ N0, const float* __restrict__ Z0,
-                                                            int d1, int m, int row_blocks, const SearchCtrl* __restrict__ ctrl) {
+                                                            int d1, int m, int row_blocks, int col_blocks,
+                                                            const SearchCtrl* __restrict__ ctrl) {
   __shared__ double sa[LAZY_TM], sb[LAZY_TM];
   __shared__ double zred[2][4][COLS_PER_BLOCK];
   if (idle(ctrl)) return;
+  if ((int)blockIdx.x >= row_blocks + col_blocks) {   // w from the cached products (see lazy_wcache_kernel)
+    if (L.misc[MI_MISS] == 0) wcache_block(L, d1, ctrl, blockIdx.x - row_blocks - col_blocks);
+    return;
+  }
   const int tid = threadIdx.x, g = ctrl->g_out, j = ctrl->g_in, tau = ctrl->tau;
   if ((int)blockIdx.x < row_blocks) {
     // current columns g and j of N
@@ -375,15 +381,14 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
 // ---------------------------------------------------------------------------------------------- wcache
 // w1 = Z0 y1, w2 = Z0 y2 from the cached base products: with a_g = col(g) - sum_r x_g[r] col(T_r) (= Z0 z_g^T) and a_j
 // likewise, w1 = Dg a_g and w2 = Dj (a_j - n_jg w1).  64 rows x 4 slices of the pending set per workgroup.
-__global__ __launch_bounds__(256) void lazy_wcache_kernel(LazyPtrs L, int d1, const SearchCtrl* __restrict__ ctrl) {
+__device__ __forceinline__ void wcache_block(const LazyPtrs& L, int d1, const SearchCtrl* __restrict__ ctrl, int block) {
   __shared__ double sxg[LAZY_TM], sxj[LAZY_TM];
   __shared__ int sts[LAZY_TM];
   __shared__ double red[2][4][64];
-  if (idle(ctrl)) return;
   const int tid = threadIdx.x, tau = ctrl->tau;
   for (int s = tid; s < LAZY_TM; s += 256) { sxg[s] = L.xg[s]; sxj[s] = L.xj[s]; sts[s] = (s < tau) ? L.tslot[s] : 0; }
   __syncthreads();
-  const int slice = tid >> 6, lr = tid & 63, row = blockIdx.x * 64 + lr;
+  const int slice = tid >> 6, lr = tid & 63, row = block * 64 + lr;
   const int rc = row < d1 ? row : d1 - 1;
   double ag = 0, aj = 0;
   for (int r = slice; r < tau; r += 4) {
@@ -399,6 +404,13 @@ __global__ __launch_bounds__(256) void lazy_wcache_kernel(LazyPtrs L, int d1, co
   const double w1 = Dg * tg;
   L.w1[row] = w1;
   L.w2[row] = Dj * (tj - njg * w1);
+}
+// w = Z0 [y1 y2] from the cached products.  When both pivots' products were computed ahead (the usual case) this runs inside
+// lazy_vectors_kernel's launch, beside the work it does not depend on; after a miss the column of the missing pivot exists
+// only once lazy_gemv_kernel has made its pass over Z0, and this kernel, launched after it, does the work.
+__global__ __launch_bounds__(256) void lazy_wcache_kernel(LazyPtrs L, int d1, const SearchCtrl* __restrict__ ctrl) {
+  if (idle(ctrl) || L.misc[MI_MISS] == 0) return;
+  wcache_block(L, d1, ctrl, blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------------------------- update
@@ -540,7 +552,7 @@ hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyP
                                  hipEvent_t* ev, const int32_t* single, int forced_out, int forced_in) {
   const int rb = (d.d1 + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, cb = (d.m + COLS_PER_BLOCK - 1) / COLS_PER_BLOCK;
   hipLaunchKernelGGL(lazy_prep_kernel, dim3(1), dim3(256), 0, s, L, t.N, d.d1, rb, t.kept, t.ctrl, single, forced_out, forced_in);
-  hipLaunchKernelGGL(lazy_vectors_kernel, dim3(rb + cb), dim3(256), 0, s, L, t.N, t.Z, d.d1, d.m, rb, t.ctrl);
+  hipLaunchKernelGGL(lazy_vectors_kernel, dim3(rb + cb + (d.d1 + 63) / 64), dim3(256), 0, s, L, t.N, t.Z, d.d1, d.m, rb, cb, t.ctrl);
   const int gb = (d.d1 + GEMV_ROWS - 1) / GEMV_ROWS + LAZY_TM;
   if (ev) hipEventRecord(ev[0], s);
   hipLaunchKernelGGL(lazy_gemv_kernel, dim3(gb), dim3(256), 0, s, L, t.Z, d.d1, d.m, cb, t.ctrl, always_accept, t.trace_out,
