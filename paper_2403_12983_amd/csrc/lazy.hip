@@ -22,11 +22,12 @@
 //
 // Four launches per iteration:
 //   prep    (1 workgroup)  : argmin / argmax from per-block partial records; x = M^-1 N0[T, {g, j}]; pivots
-//   vectors (rows | cols)  : current columns g, j of N; current rows g, j of Z scaled to y1, y2; partial sums
+//   vectors (rows | cols | rows) : current columns g, j of N; current rows g, j of Z scaled to y1, y2; partial sums;
+//                            and, independent of these, w = Z0 [y1 y2] from the cached products
 //   gemv    (rows)         : exact change of the objective and the acceptance test; u = ZT [y1 y2]; for a pivot that is
 //                            not among the candidates, its column Z0 Z0[g, :]^T by a pass over Z0
-//   wcache  (rows)         : w = Z0 [y1 y2] from the cached products
 //   update  (rows|cols|M)  : norms, diagonal, scores and their partial records; C0 append; ZT and M^-1 update
+//                            (after a miss also w, whose missing column exists only since gemv)
 #include "internal.h"
 #include <algorithm>
 
@@ -189,7 +190,7 @@ __global__ __launch_bounds__(256) void lazy_vectors_kernel(LazyPtrs L, const flo
   __shared__ double sa[LAZY_TM], sb[LAZY_TM];
   __shared__ double zred[2][4][COLS_PER_BLOCK];
   if (idle(ctrl)) return;
-  if ((int)blockIdx.x >= row_blocks + col_blocks) {   // w from the cached products (see lazy_wcache_kernel)
+  if ((int)blockIdx.x >= row_blocks + col_blocks) {   // w from the cached products (see wcache_block)
     if (L.misc[MI_MISS] == 0) wcache_block(L, d1, ctrl, blockIdx.x - row_blocks - col_blocks);
     return;
   }
@@ -405,13 +406,8 @@ __device__ __forceinline__ void wcache_block(const LazyPtrs& L, int d1, const Se
   L.w1[row] = w1;
   L.w2[row] = Dj * (tj - njg * w1);
 }
-// w = Z0 [y1 y2] from the cached products.  When both pivots' products were computed ahead (the usual case) this runs inside
-// lazy_vectors_kernel's launch, beside the work it does not depend on; after a miss the column of the missing pivot exists
-// only once lazy_gemv_kernel has made its pass over Z0, and this kernel, launched after it, does the work.
-__global__ __launch_bounds__(256) void lazy_wcache_kernel(LazyPtrs L, int d1, const SearchCtrl* __restrict__ ctrl) {
-  if (idle(ctrl) || L.misc[MI_MISS] == 0) return;
-  wcache_block(L, d1, ctrl, blockIdx.x);
-}
+// w = Z0 [y1 y2] from the cached products runs inside lazy_vectors_kernel's launch, beside the work it does not depend on, when
+// both pivots' products were computed ahead (the usual case); after a miss the update kernel forms the sums itself.
 
 // ---------------------------------------------------------------------------------------------- update
 // rows    : squared row norms, diagonal, scores (and their per-block records), the two new columns of C0
@@ -434,12 +430,30 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
     for (int s = tid; s < LAZY_TM; s += 256) { sa[s] = L.u1[s]; sb[s] = L.u2[s]; }
     __syncthreads();
     const double y11 = L.ls[LS_Y11], y22 = L.ls[LS_Y22], y12 = L.ls[LS_Y12];
+    const bool miss = L.misc[MI_MISS] != 0;
     const int row = b * ROWS_PER_BLOCK + (tid >> 3), l8 = tid & 7;
     double mn1 = INFINITY, mx1 = -INFINITY;
     int imn = -1, imx = -1;
     if (row < d1) {
       double da, db;
       row_dots(L.C0R + (int64_t)row * LAZY_TM, sa, sb, l8, da, db);
+      // w = Z0 [y1 y2] of this row: computed ahead in lazy_vectors_kernel's launch, unless a pivot's products with Z0 were
+      // not among the candidates; its column has existed only since lazy_gemv_kernel's pass, so the sum is formed here
+      double w1r, w2r;
+      if (miss) {
+        double ag = 0, aj = 0;
+        for (int r = l8; r < tau; r += 8) {
+          const double b = L.GbT[(int64_t)L.tslot[r] * d1 + row];
+          ag += L.xg[r] * b; aj += L.xj[r] * b;
+        }
+        ag += __shfl_xor(ag, 1, 64); aj += __shfl_xor(aj, 1, 64);
+        ag += __shfl_xor(ag, 2, 64); aj += __shfl_xor(aj, 2, 64);
+        ag += __shfl_xor(ag, 4, 64); aj += __shfl_xor(aj, 4, 64);
+        const double tg = L.GbT[(int64_t)L.misc[MI_SG] * d1 + row] - ag;
+        const double tj = L.GbT[(int64_t)L.misc[MI_SJ] * d1 + row] - aj;
+        w1r = Dg * tg;
+        w2r = Dj * (tj - L.ls[LS_NJG] * w1r);
+      } else { w1r = L.w1[row]; w2r = L.w2[row]; }
       if (l8 == 0) {
         // the base columns of g and j become columns tau, tau + 1 of C0
         L.C0R[(int64_t)row * LAZY_TM + tau] = nsym1(N0, d1, row, g);
@@ -458,7 +472,7 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
           double zy1, zy2;
           const int ps = L.pos[row];
           if (ps >= 0) { const double sg = (double)L.Jsg[ps]; zy1 = sg * sa[ps]; zy2 = sg * sb[ps]; }
-          else { zy1 = L.w1[row] - da; zy2 = L.w2[row] - db; }
+          else { zy1 = w1r - da; zy2 = w2r - db; }
           const double c1 = L.cg[row];
           const double c2 = L.cj[row] - c1 * M1;
           r = rho[row] - 2.0 * c1 * zy1 + c1 * c1 * y11;       // after the reverse sweep on g
@@ -557,7 +571,6 @@ hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyP
   if (ev) hipEventRecord(ev[0], s);
   hipLaunchKernelGGL(lazy_gemv_kernel, dim3(gb), dim3(256), 0, s, L, t.Z, d.d1, d.m, cb, t.ctrl, always_accept, t.trace_out,
                      t.trace_in, t.trace_gap, t.trace_obj);
-  hipLaunchKernelGGL(lazy_wcache_kernel, dim3((d.d1 + 63) / 64), dim3(256), 0, s, L, d.d1, t.ctrl);
   if (ev) hipEventRecord(ev[1], s);
   hipLaunchKernelGGL(lazy_update_kernel, dim3(rb + cb + 16), dim3(256), 0, s, L, t.N, d.d1, d.m, rb, cb, t.ctrl, t.kept, t.gram,
                      t.dblk, t.score, single ? 1 : 0);
