@@ -18,7 +18,7 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
-GEMM_TRAFFIC_CFG5 = 40.57e9   # bytes; see profiles/gemm_f64acc_cfg5_pmc.md
+GEMM_TRAFFIC_CFG5 = 40.53e9   # bytes; see profiles/gemm_f64acc_cfg5_pmc.md
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
