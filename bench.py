@@ -222,11 +222,11 @@ def main():
                           "achieved": gram_flops / phases["gram"] / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
                           "frac": gram_flops / phases["gram"] / 1e12 / 2500.0,
                           "note": "algorithmic SYRK flops n*d1*(d1+1); the kernel issues 2x that on diagonal tiles only"},
-        "search_iteration": ({"note": "per swap: four small kernels (selection and pivot algebra, current pivot rows/columns, w from the "
-                                      "products computed ahead, update of norms/diagonal/scores); every 64 swaps a flush by matrix "
+        "search_iteration": ({"note": "per swap: four small kernels (selection and pivot algebra; current pivot rows/columns and w from the "
+                                      "products computed ahead; acceptance test and u; update of norms/diagonal/scores); every 64 swaps a flush by matrix "
                                       "products plus one look-ahead product Zc Z^T.  An eager in-place up/downdate of P, B, V, R would "
                                       "move bytes_per_swap_eager per swap",
-                              "ms_per_swap": ms_swap, "w_kernels_ms": 1e3 * upd_n, "iteration_kernels_ms": 1e3 * upd_z,
+                              "ms_per_swap": ms_swap, "accept_and_u_kernel_ms": 1e3 * upd_n, "iteration_kernels_ms": 1e3 * upd_z,
                               "flushes_total_ms": flush_ms, "bytes_per_swap_eager": bytes_swap_alg,
                               "eager_equivalent_GBps": bytes_swap_alg / ms_swap / 1e6} if lazy else
                              {"note": "in-place search: every swap is one rank-2q pass over the tableau (N: lower triangle, Z)",

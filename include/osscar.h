@@ -215,8 +215,8 @@ osscar_status osscar_get_scalars(osscar_ctx* ctx, double* lambda_host, double* c
  * [0] the Gram accumulation of the chunk passed together with finalize, [1] finalize, [2] init_support,
  * [3] local_search, [4] backsolve, [6] total time of the search's refreshes and flushes.  Sampled once
  * per batch of iterations: eager search [5] mean duration of one bulk update of N, [7] of one update of Z;
- * delayed-update search [5] mean duration of the two kernels that produce w = Z [y1 y2] (a pass over Z only for a
- * pivot whose products were not computed ahead), [7] of all kernels of that iteration from there on.
+ * delayed-update search [5] mean duration of the kernel with the acceptance test and u = ZT [y1 y2] (it also makes a pass
+ * over Z for a pivot whose products were not computed ahead), [7] of all kernels of that iteration from there on.
  * [8] the product G = H W inside finalize (one GEMM launch, or the three bf16 products and their repacking when W is
  * bf16).  [9] the product V = P H_{K,Kc} of the last state build (one GEMM launch).  [10] the lower-triangle product
  * P (I - H_KK P) of the last Newton-Schulz step (one launch of the float32-accumulating GEMM).  [11] reserved.
