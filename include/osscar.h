@@ -219,7 +219,8 @@ osscar_status osscar_get_scalars(osscar_ctx* ctx, double* lambda_host, double* c
  * over Z for a pivot whose products were not computed ahead), [7] of all kernels of that iteration from there on.
  * [8] the product G = H W inside finalize (one GEMM launch, or the three bf16 products and their repacking when W is
  * bf16).  [9] the product V = P H_{K,Kc} of the last state build (one GEMM launch).  [10] the lower-triangle product
- * P (I - H_KK P) of the last Newton-Schulz step (one launch of the float32-accumulating GEMM).  [11] reserved.
+ * P (I - H_KK P) of the last Newton-Schulz step (one launch of the float32-accumulating GEMM).  [11] not a time: max |I - H_KK P| of the sweep inverse before that
+ * step, a measure of the conditioning of H_KK.
  * out_host: 12 doubles. */
 osscar_status osscar_get_timers(osscar_ctx* ctx, double* out_host);
 
