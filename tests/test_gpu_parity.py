@@ -280,6 +280,10 @@ def test_search_variants(name):
     s.osscar_init_support()
     r0 = s.osscar_local_search(c.cfg.swaps, rel_tol=0.9)
     assert r0["accepted"] == 0 and r0["iters"] == 1
+    # the diagnostics: twelve slots, times of the calls made are positive, slot 11 is the residual of the sweep inverse
+    tm = s.osscar_get_timers()
+    assert len(tm) == 12 and all(np.isfinite(tm)) and all(t >= 0 for t in tm)
+    assert tm[1] > 0 and tm[2] > 0 and tm[3] > 0 and 0 <= tm[11] < 1e-3
     s.close()
 
 
