@@ -169,6 +169,10 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
     L.GbT = cv.take<double>((int64_t)(LAZY_NC + LAZY_NS) * d1); L.Zc = cv.take<float>((int64_t)LAZY_NC * m);
     L.cslot = cv.take<int32_t>(d1); L.cand = cv.take<int32_t>(LAZY_NC + LAZY_NS); L.tslot = cv.take<int32_t>(LAZY_TM);
     L.misc = cv.take<int32_t>(8); L.lkey = cv.take<double>(2 * 64 * 32); L.lidx = cv.take<int32_t>(2 * 64 * 32);
+    L.bB = cv.take<double>(TM * LAZY_BT); L.bX = cv.take<double>(TM * LAZY_BT); L.bU = cv.take<double>(TM * LAZY_BT);
+    L.bD = cv.take<double>(LAZY_BT * LAZY_BT); L.bYY = cv.take<double>(LAZY_BT * LAZY_BT); L.bY = cv.take<double>((int64_t)LAZY_BT * m);
+    L.bpart = cv.take<double>(((m + 63) / 64) * (LAZY_BT * LAZY_BT + LAZY_BT)); L.bdl = cv.take<double>(LAZY_BT);
+    L.bG = cv.take<int32_t>(LAZY_BT);
   }
   // scratch: the larger of the Gram phase and the init / refresh / backsolve phase
   size_t gram_phase = align_up((size_t)d1 * d1 * 8) + align_up((size_t)d1 * m * 4) + align_up(gram_stage_bytes(d1)) +
@@ -694,6 +698,10 @@ osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_e
   // Work is enqueued one batch at a time (a batch = the iterations that fit the pending set, or 256 removals in place) and
   // then checked: the delayed-update kernels may stop (pause) when a removed row was not among the rows whose products
   // were computed ahead and the spare slots ran out; the batch is then resumed after a flush from where it stopped.
+  // With the products computed ahead, the rows of one iteration leave as one block pivot (four launches per iteration
+  // instead of four per row); an iteration whose rows are not all among those products stops the batch like a miss does
+  // and is then applied row by row, which can fetch the missing products.
+  const bool use_block = use_lazy && la_mode == 1 && t_hat <= LAZY_BT;
   int kept_now = p, iter = 0, since_refresh = 0, pending = 0, expected = 0;
   std::vector<int> takes;
   auto step = [&](int i) -> hipError_t {
@@ -707,7 +715,8 @@ osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_e
       const int take = std::min<int>(t_hat, kept_b - k);
       if (use_lazy ? (pending + batch + take > LAZY_TM) : (batch >= 256)) break;
       HIPCHK(c, launch_greedy_pick(d, t, take, c->g_pick, c->g_gap + iter + (int)takes.size(), s));
-      for (int i = 0; i < take; i++) HIPCHK(c, step(i));
+      if (use_block) HIPCHK(c, launch_lazy_block_remove(d, t, L, take, c->g_pick, s));
+      else for (int i = 0; i < take; i++) HIPCHK(c, step(i));
       takes.push_back(take); batch += take; kept_b -= take;
     }
     if (takes.empty()) {   // the pending set is full: apply it and try again

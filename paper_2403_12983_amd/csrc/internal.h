@@ -131,6 +131,7 @@ hipError_t launch_select(const TabDims& d, const TabPtrs& t, int forced_out, int
 constexpr int LAZY_TM = 128;     // capacity of the pending pivot set (two per swap)
 constexpr int LAZY_NC = 256;     // rows of Z0 whose products with all of Z0 are computed ahead, after every flush
 constexpr int LAZY_NS = 64;      // spare slots for pivots that were not among them
+constexpr int LAZY_BT = 16;      // rows that one block removal of the nested schedule takes at most
 struct SelRec { double mn1, mn2, mx1, mx2; int32_t imn, imx; };   // best / second-best scores of a block of rows
 struct LazyPtrs {
   int32_t* pos;     // d1: position in the pending set or -1
@@ -157,6 +158,9 @@ struct LazyPtrs {
   int32_t* tslot;   // LAZY_TM: slot of each pending pivot
   int32_t* misc;    // [0] spare slots in use, [1] miss mask of the current pair (1: g, 2: j), [2] slot of g, [3] slot of j
   double* lkey; int32_t* lidx;   // 2 x 64 x 32: per-block winners of the candidate selection
+  // block removal (nested schedule): b = N0[T, G], X = M^-1 b, U = ZT Y^T (LAZY_TM x LAZY_BT each), D, Y Y^T (LAZY_BT^2),
+  // Y (LAZY_BT x m), per-column-block partial sums, the changes of the objective, the picks
+  double* bB; double* bX; double* bU; double* bD; double* bYY; double* bY; double* bpart; double* bdl; int32_t* bG;
 };
 // mode: which rows get their products with Z0 computed ahead: 0 = LAZY_NC/2 cheapest removals + LAZY_NC/2 largest gains,
 // 1 = LAZY_NC cheapest removals (removal-only loops), 2 = none (every pivot then costs a pass over Z0)
@@ -168,6 +172,12 @@ hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyP
                                  int forced_in = -1);
 // A second stream and two events: the flush runs its update of N0 there, beside the candidate selection and the look-ahead
 // product on the main stream (they touch disjoint data), and joins before the scores are refreshed.
+// The `take` <= LAZY_BT rows in pick (device) leave the kept set as one block pivot (nested schedule, q = 1); does nothing
+// but set ctrl->pause if a pick is pending, is not among the rows whose products were computed ahead, or the pending set
+// has no room for all of them.
+hipError_t launch_lazy_block_remove(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, int take, const int32_t* pick,
+                                    hipStream_t s);
+
 struct SideStream { hipStream_t stream = nullptr; hipEvent_t fork = nullptr, join = nullptr; };
 // side == nullptr (or no stream in it): everything in order on s
 hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode = 0,

@@ -771,6 +771,352 @@ hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs&
   return two ? hipGetLastError() : launch_candidates(d, t, L, s, mode);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Block removal: the t <= LAZY_BT rows that one iteration of the nested schedule prunes (Algorithm 1 with p-hat = t-hat:
+// all of them scored at the state the iteration starts from) leave as ONE block pivot instead of t pivots in a row.
+// With G the picks, b = N0[T, G] (tau x t), X = M^-1 b, the current block N_GG = N0[G, G] - b^T X and D = N_GG^-1:
+//   Y = D Z_G (t x m), Z_G = Z0[G, :] - b^T ZT the current rows;       obj rises by -sum_a <Z_G[a], Y[a]>
+//   every other row i: c_i = N[i, G] = N0[i, G] - C0[i, :] X,  Z_i -= c_i Y,  N_ii -= c_i D c_i^T
+//   |Z_i|^2 changes by -2 c_i (Y Z_i^T) + c_i (Y Y^T) c_i^T,  Y Z_i^T = W_i - (ZT Y^T)^T C0[i, :]^T,
+//   W_i = Z0_i Y^T = D (GbT[G, i] - X^T GbT[T, i])  from the products computed ahead
+//   M^-1 grows by the block [[X D X^T, -X D], [-D X^T, D]],  ZT <- [ZT - X Y; Y].
+// Four launches per iteration of t removals (prep, cols, gemv, update) instead of four per removal.
+// ------------------------------------------------------------------------------------------------
+constexpr int BT = LAZY_BT;
+
+// n x n inverse (n <= BT) in shared memory by Gauss-Jordan without pivoting; every pivot must be negative (the block is
+// minus a principal block of a positive definite inverse), else *bad is set.  All threads of the workgroup call it.
+__device__ void blk_inverse(double* A, int n, int* bad) {
+  __shared__ double col[BT], rowk[BT];
+  const int tid = threadIdx.x;
+  for (int k = 0; k < n; k++) {
+    __syncthreads();
+    double piv = A[k * n + k];
+    if (!(piv < 0.0)) { if (tid == 0) *bad = 1; piv = -1.0; }
+    const double dinv = 1.0 / piv;
+    if (tid < n) { col[tid] = A[tid * n + k]; rowk[tid] = A[k * n + tid] * dinv; }
+    __syncthreads();
+    for (int idx = tid; idx < n * n; idx += blockDim.x) {
+      const int i = idx / n, j = idx % n;
+      double v;
+      if (i == k) v = (j == k) ? dinv : rowk[j];
+      else if (j == k) v = -col[i] * dinv;
+      else v = A[idx] - col[i] * rowk[j];
+      A[idx] = v;
+    }
+  }
+  __syncthreads();
+}
+
+__global__ __launch_bounds__(256) void blk_prep_kernel(LazyPtrs L, const float* __restrict__ N0, int d1, int t,
+                                                        const int32_t* __restrict__ pick, const int32_t* __restrict__ kept,
+                                                        SearchCtrl* ctrl) {
+  __shared__ double sb[LAZY_TM * BT], sX[LAZY_TM * BT], sD[BT * BT];
+  __shared__ int sG[BT], s_bad, s_notpd;
+  if (idle(ctrl)) return;
+  const int tid = threadIdx.x, tau = ctrl->tau;
+  if (tid == 0) { s_bad = 0; s_notpd = 0; }
+  __syncthreads();
+  if (tid < t) {
+    const int g = pick[tid];
+    sG[tid] = g;
+    if (g < 0 || g >= d1 || !kept[g] || L.pos[g] >= 0 || L.cslot[g] < 0) s_bad = 1;
+  }
+  if (tid == 0 && tau + t > LAZY_TM) s_bad = 1;
+  __syncthreads();
+  if (s_bad) { if (tid == 0) ctrl->pause = 1; return; }
+  for (int idx = tid; idx < tau * t; idx += 256) { const int r = idx / t, a = idx % t; sb[r * BT + a] = (double)L.C0R[(int64_t)sG[a] * LAZY_TM + r]; }
+  __syncthreads();
+  for (int idx = tid; idx < tau * t; idx += 256) {
+    const int r = idx / t, a = idx % t;
+    double v = 0;
+    for (int q = 0; q < tau; q++) v += L.Minv[r * LAZY_TM + q] * sb[q * BT + a];
+    sX[r * BT + a] = v;
+  }
+  __syncthreads();
+  for (int idx = tid; idx < t * t; idx += 256) {
+    const int a = idx / t, b = idx % t;
+    double v = (double)nsym1(N0, d1, sG[a], sG[b]);
+    for (int r = 0; r < tau; r++) v -= sb[r * BT + a] * sX[r * BT + b];
+    sD[idx] = v;
+  }
+  blk_inverse(sD, t, &s_notpd);
+  for (int idx = tid; idx < LAZY_TM * BT; idx += 256) {
+    const int r = idx / BT, a = idx % BT;
+    const bool in = (r < tau && a < t);
+    L.bB[idx] = in ? sb[idx] : 0.0; L.bX[idx] = in ? sX[idx] : 0.0;
+  }
+  for (int idx = tid; idx < BT * BT; idx += 256) { const int a = idx / BT, b = idx % BT; L.bD[idx] = (a < t && b < t) ? sD[a * t + b] : 0.0; }
+  if (tid < BT) L.bG[tid] = tid < t ? sG[tid] : -1;
+  if (tid == 0 && s_notpd) ctrl->notpd = 1;
+}
+
+// current rows of the picks, Y = D Z_G, and per column block the partial sums of Y Y^T and <Z_G[a], Y[a]>
+__global__ __launch_bounds__(256) void blk_cols_kernel(LazyPtrs L, const float* __restrict__ Z0, int m, int t,
+                                                        const SearchCtrl* __restrict__ ctrl) {
+  __shared__ double sb[LAZY_TM * BT], sD[BT * BT];
+  __shared__ double zred[3][COLS_PER_BLOCK][BT];
+  if (idle(ctrl)) return;
+  const int tid = threadIdx.x, tau = ctrl->tau, cb = blockIdx.x;
+  const int slice = tid >> 6, lc = tid & 63, col = cb * COLS_PER_BLOCK + lc;
+  for (int idx = tid; idx < LAZY_TM * BT; idx += 256) sb[idx] = L.bB[idx];
+  for (int idx = tid; idx < BT * BT; idx += 256) sD[idx] = L.bD[idx];
+  __syncthreads();
+  double acc[BT];
+#pragma unroll
+  for (int a = 0; a < BT; a++) acc[a] = 0.0;
+  if (col < m)
+    for (int r = slice; r < tau; r += 4) {
+      const double zt = L.ZT[(int64_t)r * m + col];
+#pragma unroll
+      for (int a = 0; a < BT; a++) acc[a] += sb[r * BT + a] * zt;
+    }
+  if (slice > 0) {
+#pragma unroll
+    for (int a = 0; a < BT; a++) zred[slice - 1][lc][a] = acc[a];
+  }
+  __syncthreads();
+  if (slice != 0) return;
+  double zg[BT], y[BT];
+#pragma unroll
+  for (int a = 0; a < BT; a++) {
+    zg[a] = 0.0;
+    if (a < t && col < m) zg[a] = (double)Z0[(int64_t)L.bG[a] * m + col] - (acc[a] + zred[0][lc][a] + zred[1][lc][a] + zred[2][lc][a]);
+  }
+#pragma unroll
+  for (int a = 0; a < BT; a++) {
+    double v = 0;
+#pragma unroll
+    for (int b = 0; b < BT; b++) v += sD[a * BT + b] * zg[b];
+    y[a] = v;
+    if (a < t && col < m) L.bY[(int64_t)a * m + col] = v;
+  }
+  double* part = L.bpart + (int64_t)cb * (BT * BT + BT);
+  for (int a = 0; a < t; a++) {
+    for (int b = 0; b <= a; b++) { const double v = wsum(y[a] * y[b]); if (lc == 0) part[a * BT + b] = v; }
+    const double v = wsum(zg[a] * y[a]);
+    if (lc == 0) part[BT * BT + a] = v;
+  }
+}
+
+// U = ZT Y^T (one workgroup per pending pivot); the last workgroup adds up the column blocks' sums and books the move
+__global__ __launch_bounds__(256) void blk_gemv_kernel(LazyPtrs L, int m, int t, int col_blocks, SearchCtrl* ctrl,
+                                                        int32_t* __restrict__ trace_out) {
+  __shared__ double red[4][BT];
+  if (idle(ctrl)) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, tau = ctrl->tau;
+  if ((int)blockIdx.x < LAZY_TM) {
+    const int r = blockIdx.x;
+    double acc[BT];
+#pragma unroll
+    for (int a = 0; a < BT; a++) acc[a] = 0.0;
+    if (r < tau) {
+      const double* zt = L.ZT + (int64_t)r * m;
+      for (int c = tid; c < m; c += 256) {
+        const double z = zt[c];
+#pragma unroll
+        for (int a = 0; a < BT; a++) if (a < t) acc[a] += z * L.bY[(int64_t)a * m + c];
+      }
+    }
+#pragma unroll
+    for (int a = 0; a < BT; a++) { const double v = wsum(acc[a]); if (lane == 0) red[wave][a] = v; }
+    __syncthreads();
+    if (tid < BT) L.bU[r * BT + tid] = red[0][tid] + red[1][tid] + red[2][tid] + red[3][tid];
+    return;
+  }
+  // sums in a fixed order: thread (a, b) walks the column blocks
+  for (int idx = tid; idx < BT * BT + BT; idx += 256) {
+    double v = 0;
+    for (int cb = 0; cb < col_blocks; cb++) v += L.bpart[(int64_t)cb * (BT * BT + BT) + idx];
+    if (idx < BT * BT) { const int a = idx / BT, b = idx % BT; if (b <= a && a < t) { L.bYY[a * BT + b] = v; L.bYY[b * BT + a] = v; } }
+    else if (idx - BT * BT < t) L.bdl[idx - BT * BT] = v;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    double dsum = 0;
+    for (int a = 0; a < t; a++) dsum += L.bdl[a];
+    const int it = ctrl->iters;
+    ctrl->obj = ctrl->obj - dsum;            // D is negative definite: -sum <Z_G[a], Y[a]> >= 0
+    ctrl->iters = it + t; ctrl->accepted += t;
+    if (trace_out) for (int a = 0; a < t; a++) trace_out[it + a] = L.bG[a];
+  }
+}
+
+__global__ __launch_bounds__(256) void blk_update_kernel(LazyPtrs L, const float* __restrict__ N0, int d1, int m, int t, int row_blocks,
+                                                          int col_blocks, SearchCtrl* ctrl, int32_t* __restrict__ kept,
+                                                          double* __restrict__ rho, double* __restrict__ diag,
+                                                          double* __restrict__ score) {
+  __shared__ double sX[LAZY_TM * BT], sU[LAZY_TM * BT], sD[BT * BT], sYY[BT * BT];
+  __shared__ int sts[LAZY_TM], sG[BT], sSlot[BT];
+  __shared__ double w_mn1[4], w_mn2[4], w_mx1[4], w_mx2[4];
+  __shared__ int w_imn[4], w_imx[4];
+  __shared__ int s_last;
+  if (idle(ctrl)) return;
+  const int tid = threadIdx.x, tau = ctrl->tau, b = blockIdx.x;
+  if (b < row_blocks) {
+    for (int idx = tid; idx < LAZY_TM * BT; idx += 256) { sX[idx] = L.bX[idx]; sU[idx] = L.bU[idx]; }
+    for (int idx = tid; idx < BT * BT; idx += 256) { sD[idx] = L.bD[idx]; sYY[idx] = L.bYY[idx]; }
+    for (int s = tid; s < LAZY_TM; s += 256) sts[s] = (s < tau) ? L.tslot[s] : 0;
+    if (tid < BT) { const int g = L.bG[tid]; sG[tid] = g; sSlot[tid] = (tid < t) ? L.cslot[g] : 0; }
+    __syncthreads();
+    const int row = b * ROWS_PER_BLOCK + (tid >> 3), l8 = tid & 7;
+    double mn1 = INFINITY, mx1 = -INFINITY;
+    int imn = -1, imx = -1;
+    if (row < d1) {
+      // eight lanes share a row: lane l8 takes the pending pivots r = 4 (l8 + 8 k) .. + 3
+      double dx[BT], du[BT], dw[BT];
+#pragma unroll
+      for (int a = 0; a < BT; a++) { dx[a] = 0.0; du[a] = 0.0; dw[a] = 0.0; }
+      const float* crow = L.C0R + (int64_t)row * LAZY_TM;
+      for (int k = 0; k < LAZY_TM / 32; k++) {
+        const int r0 = (l8 + 8 * k) * 4;
+        if (r0 >= tau) break;
+        const float4 c4 = *reinterpret_cast<const float4*>(crow + r0);
+        const float cv[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          const int r = r0 + e;
+          if (r < tau) {
+            const double c = (double)cv[e];
+            const double gb = L.GbT[(int64_t)sts[r] * d1 + row];
+#pragma unroll
+            for (int a = 0; a < BT; a++) { dx[a] += c * sX[r * BT + a]; du[a] += c * sU[r * BT + a]; dw[a] += gb * sX[r * BT + a]; }
+          }
+        }
+      }
+#pragma unroll
+      for (int a = 0; a < BT; a++) {
+        dx[a] += __shfl_xor(dx[a], 1, 64); du[a] += __shfl_xor(du[a], 1, 64); dw[a] += __shfl_xor(dw[a], 1, 64);
+        dx[a] += __shfl_xor(dx[a], 2, 64); du[a] += __shfl_xor(du[a], 2, 64); dw[a] += __shfl_xor(dw[a], 2, 64);
+        dx[a] += __shfl_xor(dx[a], 4, 64); du[a] += __shfl_xor(du[a], 4, 64); dw[a] += __shfl_xor(dw[a], 4, 64);
+      }
+      if (l8 == 0) {
+        int mine = -1;
+        for (int a = 0; a < t; a++) if (sG[a] == row) mine = a;
+        const int ps = L.pos[row];
+        double nrow[BT];
+#pragma unroll
+        for (int a = 0; a < BT; a++) nrow[a] = (a < t) ? (double)nsym1(N0, d1, row, sG[a]) : 0.0;
+        for (int a = 0; a < t; a++) L.C0R[(int64_t)row * LAZY_TM + tau + a] = (float)nrow[a];
+        double r, dn;
+        int kp;
+        if (mine >= 0) {
+          r = sYY[mine * BT + mine]; dn = -sD[mine * BT + mine]; kp = 0;
+          L.pos[row] = tau + mine; L.Tidx[tau + mine] = row; L.Jsg[tau + mine] = -1.f; L.tslot[tau + mine] = sSlot[mine];
+        } else {
+          double cg[BT], zy[BT];
+          if (ps >= 0) {
+            const double sg = (double)L.Jsg[ps];
+#pragma unroll
+            for (int a = 0; a < BT; a++) { cg[a] = sg * sX[ps * BT + a]; zy[a] = sg * sU[ps * BT + a]; }
+          } else {
+            double wt[BT];
+#pragma unroll
+            for (int a = 0; a < BT; a++) wt[a] = (a < t) ? L.GbT[(int64_t)sSlot[a] * d1 + row] - dw[a] : 0.0;
+#pragma unroll
+            for (int a = 0; a < BT; a++) {
+              double w = 0;
+#pragma unroll
+              for (int bb = 0; bb < BT; bb++) w += sD[a * BT + bb] * wt[bb];
+              cg[a] = nrow[a] - dx[a];
+              zy[a] = w - du[a];
+            }
+          }
+          double lin = 0, quadY = 0, quadD = 0;
+#pragma unroll
+          for (int a = 0; a < BT; a++) {
+            lin += cg[a] * zy[a];
+            double sy = 0, sd = 0;
+#pragma unroll
+            for (int bb = 0; bb < BT; bb++) { sy += sYY[a * BT + bb] * cg[bb]; sd += sD[a * BT + bb] * cg[bb]; }
+            quadY += cg[a] * sy; quadD += cg[a] * sd;
+          }
+          r = rho[row] - 2.0 * lin + quadY;
+          if (r < 0.0) r = 0.0;
+          dn = diag[row] - quadD;
+          kp = kept[row];
+        }
+        rho[row] = r; diag[row] = dn; kept[row] = kp;
+        const double sc = r / fabs(dn);
+        score[row] = sc;
+        if (kp) { mn1 = sc; imn = row; } else { mx1 = sc; imx = row; }
+      }
+    }
+    double mn2 = INFINITY, mx2 = -INFINITY;
+    for (int o = 32; o >= 8; o >>= 1) {
+      double b1 = __shfl_down(mn1, o, 64), b2 = __shfl_down(mn2, o, 64); int ib = __shfl_down(imn, o, 64);
+      merge_min(mn1, mn2, imn, b1, b2, ib);
+      b1 = __shfl_down(mx1, o, 64); b2 = __shfl_down(mx2, o, 64); ib = __shfl_down(imx, o, 64);
+      merge_max(mx1, mx2, imx, b1, b2, ib);
+    }
+    if ((tid & 63) == 0) { const int w = tid >> 6; w_mn1[w] = mn1; w_mn2[w] = mn2; w_imn[w] = imn; w_mx1[w] = mx1; w_mx2[w] = mx2; w_imx[w] = imx; }
+    __syncthreads();
+    if (tid == 0) {
+      for (int w = 1; w < 4; w++) { merge_min(mn1, mn2, imn, w_mn1[w], w_mn2[w], w_imn[w]); merge_max(mx1, mx2, imx, w_mx1[w], w_mx2[w], w_imx[w]); }
+      SelRec rec; rec.mn1 = mn1; rec.mn2 = mn2; rec.mx1 = mx1; rec.mx2 = mx2; rec.imn = imn; rec.imx = imx;
+      L.sel[b] = rec;
+    }
+  } else if (b < row_blocks + col_blocks) {
+    const int cb = b - row_blocks, slice = tid >> 6, col = cb * COLS_PER_BLOCK + (tid & 63);
+    for (int idx = tid; idx < LAZY_TM * BT; idx += 256) sX[idx] = L.bX[idx];
+    __syncthreads();
+    if (col < m) {
+      double y[BT];
+#pragma unroll
+      for (int a = 0; a < BT; a++) y[a] = (a < t) ? L.bY[(int64_t)a * m + col] : 0.0;
+      for (int r = slice; r < tau; r += 4) {
+        double v = 0;
+#pragma unroll
+        for (int a = 0; a < BT; a++) v += sX[r * BT + a] * y[a];
+        L.ZT[(int64_t)r * m + col] -= v;
+      }
+      for (int a = slice; a < t; a += 4) L.ZT[(int64_t)(tau + a) * m + col] = y[a];
+    }
+  } else {
+    const int mb = b - row_blocks - col_blocks, nmb = gridDim.x - row_blocks - col_blocks;
+    double* Mi = L.Minv;
+    for (int idx = mb * 256 + tid; idx < tau * tau; idx += nmb * 256) {
+      const int r = idx / tau, s = idx % tau;
+      double v = 0;
+      for (int a = 0; a < t; a++) {
+        double xd = 0;
+        for (int bb = 0; bb < t; bb++) xd += L.bX[r * BT + bb] * L.bD[bb * BT + a];
+        v += xd * L.bX[s * BT + a];
+      }
+      Mi[r * LAZY_TM + s] += v;
+    }
+    if (mb == 0) {
+      for (int idx = tid; idx < tau * t; idx += 256) {
+        const int r = idx / t, a = idx % t;
+        double v = 0;
+        for (int bb = 0; bb < t; bb++) v -= L.bX[r * BT + bb] * L.bD[bb * BT + a];
+        Mi[r * LAZY_TM + tau + a] = v; Mi[(tau + a) * LAZY_TM + r] = v;
+      }
+      for (int idx = tid; idx < t * t; idx += 256) { const int a = idx / t, bb = idx % t; Mi[(tau + a) * LAZY_TM + tau + bb] = L.bD[a * BT + bb]; }
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    __threadfence();
+    const int done_blocks = atomicAdd(L.counter, 1);
+    s_last = (done_blocks == (int)gridDim.x - 1);
+  }
+  __syncthreads();
+  if (s_last && tid == 0) { *L.counter = 0; ctrl->tau = tau + t; }
+}
+
+hipError_t launch_lazy_block_remove(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, int take, const int32_t* pick,
+                                    hipStream_t s) {
+  if (take < 1 || take > BT) return hipErrorInvalidValue;
+  const int rb = (d.d1 + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, cb = (d.m + COLS_PER_BLOCK - 1) / COLS_PER_BLOCK;
+  hipLaunchKernelGGL(blk_prep_kernel, dim3(1), dim3(256), 0, s, L, t.N, d.d1, take, pick, t.kept, t.ctrl);
+  hipLaunchKernelGGL(blk_cols_kernel, dim3(cb), dim3(256), 0, s, L, t.Z, d.m, take, t.ctrl);
+  hipLaunchKernelGGL(blk_gemv_kernel, dim3(LAZY_TM + 1), dim3(256), 0, s, L, d.m, take, cb, t.ctrl, t.trace_out);
+  hipLaunchKernelGGL(blk_update_kernel, dim3(rb + cb + 16), dim3(256), 0, s, L, t.N, d.d1, d.m, take, rb, cb, t.ctrl, t.kept, t.gram,
+                     t.dblk, t.score);
+  return hipGetLastError();
+}
+
 hipError_t launch_lazy_init(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode) {
   hipError_t e = hipMemsetAsync(L.pos, 0xFF, (size_t)d.d1 * 4, s);
   if (e != hipSuccess) return e;
