@@ -169,7 +169,7 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
     L.GbT = cv.take<double>((int64_t)(LAZY_NC + LAZY_NS) * d1); L.Zc = cv.take<float>((int64_t)LAZY_NC * m);
     L.cslot = cv.take<int32_t>(d1); L.cand = cv.take<int32_t>(LAZY_NC + LAZY_NS); L.tslot = cv.take<int32_t>(LAZY_TM);
     L.misc = cv.take<int32_t>(8); L.lkey = cv.take<double>(2 * 64 * 32); L.lidx = cv.take<int32_t>(2 * 64 * 32);
-    L.bB = cv.take<double>(TM * LAZY_BT); L.bX = cv.take<double>(TM * LAZY_BT); L.bU = cv.take<double>(TM * LAZY_BT);
+    L.bB = cv.take<double>(TM * LAZY_BT); L.bX = cv.take<double>(TM * LAZY_BT); L.bU = cv.take<double>(4 * TM * LAZY_BT);
     L.bD = cv.take<double>(LAZY_BT * LAZY_BT); L.bYY = cv.take<double>(LAZY_BT * LAZY_BT); L.bY = cv.take<double>((int64_t)LAZY_BT * m);
     L.bpart = cv.take<double>(((m + 63) / 64) * (LAZY_BT * LAZY_BT + LAZY_BT)); L.bdl = cv.take<double>(LAZY_BT);
     L.bG = cv.take<int32_t>(LAZY_BT);

@@ -158,7 +158,8 @@ struct LazyPtrs {
   int32_t* tslot;   // LAZY_TM: slot of each pending pivot
   int32_t* misc;    // [0] spare slots in use, [1] miss mask of the current pair (1: g, 2: j), [2] slot of g, [3] slot of j
   double* lkey; int32_t* lidx;   // 2 x 64 x 32: per-block winners of the candidate selection
-  // block removal (nested schedule): b = N0[T, G], X = M^-1 b, U = ZT Y^T (LAZY_TM x LAZY_BT each), D, Y Y^T (LAZY_BT^2),
+  // block removal (nested schedule): b = N0[T, G], X = M^-1 b (LAZY_TM x LAZY_BT each), U = ZT Y^T (four partial sums of that
+  // shape, one per quarter of the columns), D, Y Y^T (LAZY_BT^2),
   // Y (LAZY_BT x m), per-column-block partial sums, the changes of the objective, the picks
   double* bB; double* bX; double* bU; double* bD; double* bYY; double* bY; double* bpart; double* bdl; int32_t* bG;
 };

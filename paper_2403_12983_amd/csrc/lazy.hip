@@ -899,35 +899,55 @@ __global__ __launch_bounds__(256) void blk_cols_kernel(LazyPtrs L, const float* 
   }
 }
 
-// U = ZT Y^T (one workgroup per pending pivot); the last workgroup adds up the column blocks' sums and books the move
+// U = ZT Y^T: workgroup (rg, slab) takes four pending pivots and a quarter of the columns and leaves its part in
+// bU[slab] (the reader adds the four up); the last workgroup adds up the column blocks' sums and books the move
+constexpr int BU_SLABS = 4;
 __global__ __launch_bounds__(256) void blk_gemv_kernel(LazyPtrs L, int m, int t, int col_blocks, SearchCtrl* ctrl,
                                                         int32_t* __restrict__ trace_out) {
-  __shared__ double red[4][BT];
+  __shared__ double red[4][4 * BT];
   if (idle(ctrl)) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, tau = ctrl->tau;
   if ((int)blockIdx.x < LAZY_TM) {
-    const int r = blockIdx.x;
-    double acc[BT];
+    const int r0 = ((int)blockIdx.x / BU_SLABS) * 4, slab = (int)blockIdx.x % BU_SLABS;
+    const int cs = (m + BU_SLABS - 1) / BU_SLABS, c0 = slab * cs, c1 = min(m, c0 + cs);
+    double acc[4][BT];
 #pragma unroll
-    for (int a = 0; a < BT; a++) acc[a] = 0.0;
-    if (r < tau) {
-      const double* zt = L.ZT + (int64_t)r * m;
-      for (int c = tid; c < m; c += 256) {
-        const double z = zt[c];
+    for (int e = 0; e < 4; e++)
 #pragma unroll
-        for (int a = 0; a < BT; a++) if (a < t) acc[a] += z * L.bY[(int64_t)a * m + c];
+      for (int a = 0; a < BT; a++) acc[e][a] = 0.0;
+    if (r0 < tau) {
+      for (int c = c0 + tid; c < c1; c += 256) {
+        double z[4], y[BT];
+#pragma unroll
+        for (int e = 0; e < 4; e++) z[e] = (r0 + e < tau) ? L.ZT[(int64_t)(r0 + e) * m + c] : 0.0;
+#pragma unroll
+        for (int a = 0; a < BT; a++) y[a] = (a < t) ? L.bY[(int64_t)a * m + c] : 0.0;
+#pragma unroll
+        for (int e = 0; e < 4; e++)
+#pragma unroll
+          for (int a = 0; a < BT; a++) acc[e][a] += z[e] * y[a];
       }
     }
 #pragma unroll
-    for (int a = 0; a < BT; a++) { const double v = wsum(acc[a]); if (lane == 0) red[wave][a] = v; }
+    for (int e = 0; e < 4; e++)
+#pragma unroll
+      for (int a = 0; a < BT; a++) { const double v = wsum(acc[e][a]); if (lane == 0) red[wave][e * BT + a] = v; }
     __syncthreads();
-    if (tid < BT) L.bU[r * BT + tid] = red[0][tid] + red[1][tid] + red[2][tid] + red[3][tid];
+    if (tid < 4 * BT) L.bU[(int64_t)slab * LAZY_TM * BT + r0 * BT + tid] = red[0][tid] + red[1][tid] + red[2][tid] + red[3][tid];
     return;
   }
   // sums in a fixed order: thread (a, b) walks the column blocks
   for (int idx = tid; idx < BT * BT + BT; idx += 256) {
     double v = 0;
-    for (int cb = 0; cb < col_blocks; cb++) v += L.bpart[(int64_t)cb * (BT * BT + BT) + idx];
+    int cb = 0;
+    for (; cb + 8 <= col_blocks; cb += 8) {     // eight loads in flight; the order of the sum stays fixed
+      double pv[8];
+#pragma unroll
+      for (int u = 0; u < 8; u++) pv[u] = L.bpart[(int64_t)(cb + u) * (BT * BT + BT) + idx];
+#pragma unroll
+      for (int u = 0; u < 8; u++) v += pv[u];
+    }
+    for (; cb < col_blocks; cb++) v += L.bpart[(int64_t)cb * (BT * BT + BT) + idx];
     if (idx < BT * BT) { const int a = idx / BT, b = idx % BT; if (b <= a && a < t) { L.bYY[a * BT + b] = v; L.bYY[b * BT + a] = v; } }
     else if (idx - BT * BT < t) L.bdl[idx - BT * BT] = v;
   }
@@ -943,7 +963,7 @@ __global__ __launch_bounds__(256) void blk_gemv_kernel(LazyPtrs L, int m, int t,
 }
 
 __global__ __launch_bounds__(256) void blk_update_kernel(LazyPtrs L, const float* __restrict__ N0, int d1, int m, int t, int row_blocks,
-                                                          int col_blocks, SearchCtrl* ctrl, int32_t* __restrict__ kept,
+                                                          int row_wgs, int col_blocks, SearchCtrl* ctrl, int32_t* __restrict__ kept,
                                                           double* __restrict__ rho, double* __restrict__ diag,
                                                           double* __restrict__ score) {
   __shared__ double sX[LAZY_TM * BT], sU[LAZY_TM * BT], sD[BT * BT], sYY[BT * BT];
@@ -953,35 +973,36 @@ __global__ __launch_bounds__(256) void blk_update_kernel(LazyPtrs L, const float
   __shared__ int s_last;
   if (idle(ctrl)) return;
   const int tid = threadIdx.x, tau = ctrl->tau, b = blockIdx.x;
-  if (b < row_blocks) {
-    for (int idx = tid; idx < LAZY_TM * BT; idx += 256) { sX[idx] = L.bX[idx]; sU[idx] = L.bU[idx]; }
+  if (b < row_wgs) {
+    // sX, sU transposed to [a][r]: the eight lanes of a row read eight consecutive r
+    for (int idx = tid; idx < LAZY_TM * BT; idx += 256) {
+      const int r = idx / BT, a = idx % BT;
+      double u = 0;
+#pragma unroll
+      for (int sl = 0; sl < BU_SLABS; sl++) u += L.bU[(int64_t)sl * LAZY_TM * BT + idx];
+      sX[a * LAZY_TM + r] = L.bX[idx]; sU[a * LAZY_TM + r] = u;
+    }
     for (int idx = tid; idx < BT * BT; idx += 256) { sD[idx] = L.bD[idx]; sYY[idx] = L.bYY[idx]; }
     for (int s = tid; s < LAZY_TM; s += 256) sts[s] = (s < tau) ? L.tslot[s] : 0;
     if (tid < BT) { const int g = L.bG[tid]; sG[tid] = g; sSlot[tid] = (tid < t) ? L.cslot[g] : 0; }
     __syncthreads();
-    const int row = b * ROWS_PER_BLOCK + (tid >> 3), l8 = tid & 7;
+    // a workgroup walks blocks of 32 rows (one selection record each), so the tables above are loaded once for several
+    for (int rbk = b; rbk < row_blocks; rbk += row_wgs) {
+    const int row = rbk * ROWS_PER_BLOCK + (tid >> 3), l8 = tid & 7;
     double mn1 = INFINITY, mx1 = -INFINITY;
     int imn = -1, imx = -1;
     if (row < d1) {
-      // eight lanes share a row: lane l8 takes the pending pivots r = 4 (l8 + 8 k) .. + 3
       double dx[BT], du[BT], dw[BT];
 #pragma unroll
       for (int a = 0; a < BT; a++) { dx[a] = 0.0; du[a] = 0.0; dw[a] = 0.0; }
       const float* crow = L.C0R + (int64_t)row * LAZY_TM;
-      for (int k = 0; k < LAZY_TM / 32; k++) {
-        const int r0 = (l8 + 8 * k) * 4;
-        if (r0 >= tau) break;
-        const float4 c4 = *reinterpret_cast<const float4*>(crow + r0);
-        const float cv[4] = {c4.x, c4.y, c4.z, c4.w};
+      for (int r = l8; r < tau; r += 8) {
+        const double c = (double)crow[r];
+        const double gb = L.GbT[(int64_t)sts[r] * d1 + row];
 #pragma unroll
-        for (int e = 0; e < 4; e++) {
-          const int r = r0 + e;
-          if (r < tau) {
-            const double c = (double)cv[e];
-            const double gb = L.GbT[(int64_t)sts[r] * d1 + row];
-#pragma unroll
-            for (int a = 0; a < BT; a++) { dx[a] += c * sX[r * BT + a]; du[a] += c * sU[r * BT + a]; dw[a] += gb * sX[r * BT + a]; }
-          }
+        for (int a = 0; a < BT; a++) {
+          const double x = sX[a * LAZY_TM + r];
+          dx[a] += c * x; du[a] += c * sU[a * LAZY_TM + r]; dw[a] += gb * x;
         }
       }
 #pragma unroll
@@ -990,14 +1011,23 @@ __global__ __launch_bounds__(256) void blk_update_kernel(LazyPtrs L, const float
         dx[a] += __shfl_xor(dx[a], 2, 64); du[a] += __shfl_xor(du[a], 2, 64); dw[a] += __shfl_xor(dw[a], 2, 64);
         dx[a] += __shfl_xor(dx[a], 4, 64); du[a] += __shfl_xor(du[a], 4, 64); dw[a] += __shfl_xor(dw[a], 4, 64);
       }
+      // the base entries N0[row, G] (new columns of C0) and the products GbT[G, row]: lane l8 fetches a = l8 and l8 + 8
+      static_assert(BT == 16, "two picks per lane");
+      float n_lo = 0.f, n_hi = 0.f;
+      double g_lo = 0.0, g_hi = 0.0;
+      if (l8 < t) { n_lo = nsym1(N0, d1, row, sG[l8]); g_lo = L.GbT[(int64_t)sSlot[l8] * d1 + row]; L.C0R[(int64_t)row * LAZY_TM + tau + l8] = n_lo; }
+      if (l8 + 8 < t) { n_hi = nsym1(N0, d1, row, sG[l8 + 8]); g_hi = L.GbT[(int64_t)sSlot[l8 + 8] * d1 + row]; L.C0R[(int64_t)row * LAZY_TM + tau + l8 + 8] = n_hi; }
+      double nrow[BT], grow[BT];
+      const int lane0 = (tid & 63) & ~7;
+#pragma unroll
+      for (int a = 0; a < BT; a++) {
+        nrow[a] = (double)__shfl(a < 8 ? n_lo : n_hi, lane0 + (a & 7), 64);
+        grow[a] = __shfl(a < 8 ? g_lo : g_hi, lane0 + (a & 7), 64);
+      }
       if (l8 == 0) {
         int mine = -1;
         for (int a = 0; a < t; a++) if (sG[a] == row) mine = a;
         const int ps = L.pos[row];
-        double nrow[BT];
-#pragma unroll
-        for (int a = 0; a < BT; a++) nrow[a] = (a < t) ? (double)nsym1(N0, d1, row, sG[a]) : 0.0;
-        for (int a = 0; a < t; a++) L.C0R[(int64_t)row * LAZY_TM + tau + a] = (float)nrow[a];
         double r, dn;
         int kp;
         if (mine >= 0) {
@@ -1008,11 +1038,11 @@ __global__ __launch_bounds__(256) void blk_update_kernel(LazyPtrs L, const float
           if (ps >= 0) {
             const double sg = (double)L.Jsg[ps];
 #pragma unroll
-            for (int a = 0; a < BT; a++) { cg[a] = sg * sX[ps * BT + a]; zy[a] = sg * sU[ps * BT + a]; }
+            for (int a = 0; a < BT; a++) { cg[a] = sg * sX[a * LAZY_TM + ps]; zy[a] = sg * sU[a * LAZY_TM + ps]; }
           } else {
             double wt[BT];
 #pragma unroll
-            for (int a = 0; a < BT; a++) wt[a] = (a < t) ? L.GbT[(int64_t)sSlot[a] * d1 + row] - dw[a] : 0.0;
+            for (int a = 0; a < BT; a++) wt[a] = (a < t) ? grow[a] - dw[a] : 0.0;
 #pragma unroll
             for (int a = 0; a < BT; a++) {
               double w = 0;
@@ -1054,10 +1084,12 @@ __global__ __launch_bounds__(256) void blk_update_kernel(LazyPtrs L, const float
     if (tid == 0) {
       for (int w = 1; w < 4; w++) { merge_min(mn1, mn2, imn, w_mn1[w], w_mn2[w], w_imn[w]); merge_max(mx1, mx2, imx, w_mx1[w], w_mx2[w], w_imx[w]); }
       SelRec rec; rec.mn1 = mn1; rec.mn2 = mn2; rec.mx1 = mx1; rec.mx2 = mx2; rec.imn = imn; rec.imx = imx;
-      L.sel[b] = rec;
+      L.sel[rbk] = rec;
     }
-  } else if (b < row_blocks + col_blocks) {
-    const int cb = b - row_blocks, slice = tid >> 6, col = cb * COLS_PER_BLOCK + (tid & 63);
+    __syncthreads();
+    }
+  } else if (b < row_wgs + col_blocks) {
+    const int cb = b - row_wgs, slice = tid >> 6, col = cb * COLS_PER_BLOCK + (tid & 63);
     for (int idx = tid; idx < LAZY_TM * BT; idx += 256) sX[idx] = L.bX[idx];
     __syncthreads();
     if (col < m) {
@@ -1073,7 +1105,7 @@ __global__ __launch_bounds__(256) void blk_update_kernel(LazyPtrs L, const float
       for (int a = slice; a < t; a += 4) L.ZT[(int64_t)(tau + a) * m + col] = y[a];
     }
   } else {
-    const int mb = b - row_blocks - col_blocks, nmb = gridDim.x - row_blocks - col_blocks;
+    const int mb = b - row_wgs - col_blocks, nmb = gridDim.x - row_wgs - col_blocks;
     double* Mi = L.Minv;
     for (int idx = mb * 256 + tid; idx < tau * tau; idx += nmb * 256) {
       const int r = idx / tau, s = idx % tau;
@@ -1112,8 +1144,9 @@ hipError_t launch_lazy_block_remove(const TabDims& d, const TabPtrs& t, const La
   hipLaunchKernelGGL(blk_prep_kernel, dim3(1), dim3(256), 0, s, L, t.N, d.d1, take, pick, t.kept, t.ctrl);
   hipLaunchKernelGGL(blk_cols_kernel, dim3(cb), dim3(256), 0, s, L, t.Z, d.m, take, t.ctrl);
   hipLaunchKernelGGL(blk_gemv_kernel, dim3(LAZY_TM + 1), dim3(256), 0, s, L, d.m, take, cb, t.ctrl, t.trace_out);
-  hipLaunchKernelGGL(blk_update_kernel, dim3(rb + cb + 16), dim3(256), 0, s, L, t.N, d.d1, d.m, take, rb, cb, t.ctrl, t.kept, t.gram,
-                     t.dblk, t.score);
+  const int row_wgs = std::min(rb, 256);
+  hipLaunchKernelGGL(blk_update_kernel, dim3(row_wgs + cb + 16), dim3(256), 0, s, L, t.N, d.d1, d.m, take, rb, row_wgs, cb, t.ctrl,
+                     t.kept, t.gram, t.dblk, t.score);
   return hipGetLastError();
 }
 
