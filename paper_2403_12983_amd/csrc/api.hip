@@ -807,18 +807,23 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
   if (use_lazy) {
     // delayed-update search: the tableau in HBM is only touched by a flush every FLUSH iterations
     const LazyPtrs& L = c->lazy;
-    const int FLUSH = LAZY_TM / 2, BATCH = 32;
+    // The host waits once per flush interval (to read the control block); the flush and the next interval's iterations are
+    // enqueued behind it without another wait, and the flush's time is read at the next wait.
+    const int FLUSH = LAZY_TM / 2, BATCH = FLUSH;
     const int la_mode = (flags & OSSCAR_SEARCH_NO_LOOKAHEAD) ? 2 : 0;
     HIPCHK(c, launch_lazy_init(d, t, L, s, la_mode));
     int since_flush = 0;
     double flush_ms = 0; int flushes = 0;
+    bool flush_open = false;                 // a flush whose events have not been read yet
+    auto collect = [&]() {                   // only after the stream has been waited for
+      if (!flush_open) return;
+      float ms = 0; hipEventElapsedTime(&ms, c->ev_s[0][0], c->ev_s[0][1]); flush_ms += ms; flush_open = false;
+    };
     auto flush = [&]() -> osscar_status {
-      hipEvent_t f0 = c->ev_s[0][0], f1 = c->ev_s[0][1];
-      HIPCHK(c, hipEventRecord(f0, s));
+      HIPCHK(c, hipEventRecord(c->ev_s[0][0], s));
       HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, &c->side));
-      HIPCHK(c, hipEventRecord(f1, s));
-      HIPCHK(c, hipStreamSynchronize(s));
-      float ms = 0; hipEventElapsedTime(&ms, f0, f1); flush_ms += ms; flushes++;
+      HIPCHK(c, hipEventRecord(c->ev_s[0][1], s));
+      flush_open = true; flushes++;
       since_flush = 0;
       return OSSCAR_OK;
     };
@@ -831,6 +836,7 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
       const int before = h.iters;
       st = read_ctrl(c, &h);
       if (st != OSSCAR_OK) return st;
+      collect();
       if (h.notpd) return fail(c, OSSCAR_ENOTPD, "osscar_local_search: a pivot lost definiteness at iteration %d", h.iters);
       since_flush += h.iters - before;
       if (sample && h.iters > before) {
@@ -845,6 +851,7 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
         h.pause = 0; h.tau = 0;
       }
       if (want_refresh) {
+        if (flush_open) { HIPCHK(c, hipStreamSynchronize(s)); collect(); }      // the refresh times itself with the same events
         hipEvent_t r0 = c->ev_s[0][0], r1 = c->ev_s[0][1];
         HIPCHK(c, hipEventRecord(r0, s));
         st = read_kept(c);
@@ -862,6 +869,7 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
       }
     }
     if (h.tau > 0) { st = flush(); if (st != OSSCAR_OK) return st; }
+    if (flush_open) { HIPCHK(c, hipStreamSynchronize(s)); collect(); }
     c->timers[6] = refresh_ms + flush_ms;
     (void)flushes;
   } else {
