@@ -231,12 +231,37 @@ hipError_t launch_absmax(const float* A, int64_t n, double* out, hipStream_t s) 
 // ------------------------------------------------------------------------------------------------
 // pivot panels
 // ------------------------------------------------------------------------------------------------
-// C[i][c] = Nsym(i, t0 + c), c < w, for all rows i < n
+// C[i][c] = Nsym(i, t0 + c), c < w <= 128, for all rows i < n.  One workgroup per 64 rows: below the pivot rows the panel
+// is a column block of N (read along c); above them it lies transposed in the rows t0 + c of N (read along i and turned
+// in shared memory); the few blocks that meet the pivot rows take either side element by element.
+constexpr int PANEL_ROWS = 64;
 __global__ __launch_bounds__(256) void extract_panel_kernel(const float* __restrict__ N, int64_t ld, int n, int t0,
                                                              int w, float* __restrict__ C) {
-  int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= n) return;
-  for (int c = 0; c < w; c++) C[(int64_t)i * w + c] = nsym(N, ld, i, t0 + c);
+  __shared__ float T[PANEL_ROWS][129];
+  const int i0 = blockIdx.x * PANEL_ROWS, tid = threadIdx.x;
+  if (i0 >= t0 + w) {
+    for (int idx = tid; idx < PANEL_ROWS * w; idx += 256) {
+      const int r = idx / w, c = idx % w;
+      if (i0 + r < n) C[(int64_t)(i0 + r) * w + c] = N[(int64_t)(i0 + r) * ld + t0 + c];
+    }
+    return;
+  }
+  if (i0 + PANEL_ROWS <= t0) {
+    for (int idx = tid; idx < PANEL_ROWS * w; idx += 256) {
+      const int c = idx / PANEL_ROWS, r = idx % PANEL_ROWS;
+      T[r][c] = N[(int64_t)(t0 + c) * ld + i0 + r];
+    }
+  } else {
+    for (int idx = tid; idx < PANEL_ROWS * w; idx += 256) {
+      const int r = idx / w, c = idx % w;
+      T[r][c] = (i0 + r < n) ? nsym(N, ld, i0 + r, t0 + c) : 0.f;
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < PANEL_ROWS * w; idx += 256) {
+    const int r = idx / w, c = idx % w;
+    if (i0 + r < n) C[(int64_t)(i0 + r) * w + c] = T[r][c];
+  }
 }
 
 // out[i][c] = sum_k C[i][k] * D[k][c]  (D: w x w float64, w <= 128), rows in [t0, t0+w) are written as zero if zero_pivot.
@@ -289,17 +314,33 @@ __global__ __launch_bounds__(256) void inv_block_kernel(const float* __restrict_
 // pivot rows after a forward sweep: N(t0+r, l) = CD[l][r] for l outside the pivot, N(tt) = -D
 __global__ __launch_bounds__(256) void inv_fix_kernel(float* __restrict__ N, int64_t ld, int n, int t0, int w,
                                                        const float* __restrict__ CD, const double* __restrict__ D) {
-  int l = blockIdx.x * 256 + threadIdx.x;
-  if (l >= n) return;
-  if (l >= t0 && l < t0 + w) {
-    int r = l - t0;
-    for (int c = 0; c <= r; c++) N[(int64_t)l * ld + t0 + c] = (float)(-D[r * w + c]);
+  __shared__ float T[PANEL_ROWS][129];
+  const int i0 = blockIdx.x * PANEL_ROWS, tid = threadIdx.x;
+  if (i0 >= t0 + w) {                         // below the pivot rows: a column block of N
+    for (int idx = tid; idx < PANEL_ROWS * w; idx += 256) {
+      const int r = idx / w, c = idx % w;
+      if (i0 + r < n) N[(int64_t)(i0 + r) * ld + t0 + c] = CD[(int64_t)(i0 + r) * w + c];
+    }
     return;
   }
-  for (int r = 0; r < w; r++) {
-    float v = CD[(int64_t)l * w + r];
-    if (l < t0) N[(int64_t)(t0 + r) * ld + l] = v;
-    else N[(int64_t)l * ld + t0 + r] = v;
+  for (int idx = tid; idx < PANEL_ROWS * w; idx += 256) {
+    const int r = idx / w, c = idx % w;
+    T[r][c] = (i0 + r < n) ? CD[(int64_t)(i0 + r) * w + c] : 0.f;
+  }
+  __syncthreads();
+  if (i0 + PANEL_ROWS <= t0) {                // above: the rows t0 + c of N, written along i
+    for (int idx = tid; idx < PANEL_ROWS * w; idx += 256) {
+      const int c = idx / PANEL_ROWS, r = idx % PANEL_ROWS;
+      N[(int64_t)(t0 + c) * ld + i0 + r] = T[r][c];
+    }
+    return;
+  }
+  for (int idx = tid; idx < PANEL_ROWS * w; idx += 256) {     // a block that meets the pivot rows
+    const int r = idx / w, c = idx % w, l = i0 + r;
+    if (l >= n) continue;
+    if (l < t0) N[(int64_t)(t0 + c) * ld + l] = T[r][c];
+    else if (l >= t0 + w) N[(int64_t)l * ld + t0 + c] = T[r][c];
+    else if (c <= l - t0) N[(int64_t)l * ld + t0 + c] = (float)(-D[(l - t0) * w + c]);
   }
 }
 
@@ -326,7 +367,7 @@ hipError_t spd_inverse_inplace(float* A, int n, float* panel, float* panelD, dou
   float* panelB = panelD + (int64_t)n * INV_NB;   // caller provides 2*n*nb floats behind panelD
   for (int t0 = 0; t0 < n; t0 += INV_NB) {
     int w = (n - t0 < INV_NB) ? n - t0 : INV_NB;
-    int rb = (n + 255) / 256;
+    int rb = (n + PANEL_ROWS - 1) / PANEL_ROWS;
     hipLaunchKernelGGL(extract_panel_kernel, dim3(rb), dim3(256), 0, s, A, (int64_t)n, n, t0, w, panel);
     hipLaunchKernelGGL(inv_block_kernel, dim3(1), dim3(256), 0, s, panel, w, t0, small, notpd_flag);
     // true C*D for the pivot-row fix, and zeroed copies for the bulk update
