@@ -699,9 +699,10 @@ osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_e
   // then checked: the delayed-update kernels may stop (pause) when a removed row was not among the rows whose products
   // were computed ahead and the spare slots ran out; the batch is then resumed after a flush from where it stopped.
   // With the products computed ahead, the rows of one iteration leave as one block pivot (four launches per iteration
-  // instead of four per row); an iteration whose rows are not all among those products stops the batch like a miss does
-  // and is then applied row by row, which can fetch the missing products.
-  const bool use_block = use_lazy && la_mode == 1 && t_hat <= LAZY_BT;
+  // instead of four per row; LAZY_BT rows per pivot at most); a block whose rows are not all among those products stops
+  // the batch like a miss does, and the rest of its iteration is then applied row by row, which can fetch the missing
+  // products.
+  const bool use_block = use_lazy && la_mode == 1;
   int kept_now = p, iter = 0, since_refresh = 0, pending = 0, expected = 0;
   std::vector<int> takes;
   auto step = [&](int i) -> hipError_t {
@@ -715,8 +716,12 @@ osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_e
       const int take = std::min<int>(t_hat, kept_b - k);
       if (use_lazy ? (pending + batch + take > LAZY_TM) : (batch >= 256)) break;
       HIPCHK(c, launch_greedy_pick(d, t, take, c->g_pick, c->g_gap + iter + (int)takes.size(), s));
-      if (use_block) HIPCHK(c, launch_lazy_block_remove(d, t, L, take, c->g_pick, s));
-      else for (int i = 0; i < take; i++) HIPCHK(c, step(i));
+      if (use_block) {
+        for (int off = 0; off < take; off += LAZY_BT)      // more than LAZY_BT rows: several block pivots, same result
+          HIPCHK(c, launch_lazy_block_remove(d, t, L, std::min(LAZY_BT, take - off), c->g_pick + off, s));
+      } else {
+        for (int i = 0; i < take; i++) HIPCHK(c, step(i));
+      }
       takes.push_back(take); batch += take; kept_b -= take;
     }
     if (takes.empty()) {   // the pending set is full: apply it and try again

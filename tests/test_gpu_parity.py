@@ -399,7 +399,7 @@ def check_greedy(c, t_hat, obj, steps, gaps):
 
 
 @pytest.mark.parametrize("name,t_hat", [("cfg1", 1), ("cfg1", 3), ("cfg1x", 2), ("cfg2s", 2), ("cfg3s", 10), ("cfg4s", 2),
-                                        ("cfg5odd", 7), ("cfg3s", 16), ("cfg5odd", 20)])   # 16: the widest block removal
+                                        ("cfg5odd", 7), ("cfg3s", 16), ("cfg5odd", 20), ("cfg3s", 40)])   # block removals of 16 rows at most: 16, 16 + 4, 16 + 16 + 8
 def test_greedy_from_dense_follows_the_oracle(name, t_hat):
     c = case(name)
     cfg = c.cfg
