@@ -165,7 +165,7 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
     L.cg = cv.take<double>(d1); L.cj = cv.take<double>(d1); L.w1 = cv.take<double>(d1); L.w2 = cv.take<double>(d1);
     L.y1 = cv.take<double>(m); L.y2 = cv.take<double>(m); L.y1f = cv.take<float>(m); L.y2f = cv.take<float>(m);
     L.part = cv.take<double>(((m + 63) / 64) * 5); L.ls = cv.take<double>(16);
-    L.sel = cv.take<SelRec>((d1 + 31) / 32); L.counter = cv.take<int32_t>(4);
+    L.sel = cv.take<SelRec>((d1 + 31) / 32);
     L.GbT = cv.take<double>((int64_t)(LAZY_NC + LAZY_NS) * d1); L.Zc = cv.take<float>((int64_t)LAZY_NC * m);
     L.cslot = cv.take<int32_t>(d1); L.cand = cv.take<int32_t>(LAZY_NC + LAZY_NS); L.tslot = cv.take<int32_t>(LAZY_TM);
     L.misc = cv.take<int32_t>(8); L.lkey = cv.take<double>(2 * 64 * 32); L.lidx = cv.take<int32_t>(2 * 64 * 32);
@@ -684,7 +684,7 @@ osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_e
   if (st != OSSCAR_OK) { c->kr = k * q; c->cr = c->d1 - c->kr; return st; }
   SearchCtrl h{};
   h.obj = c->dense_is_exact ? 0.0 : obj;   // the dense layer reproduces its own output exactly; a target output it does not
-  h.g_out = -1; h.g_in = -1; h.tau = 0; h.pause = 0;
+  h.g_out = -1; h.g_in = -1; h.tau = 0; h.tau_inc = 0; h.pause = 0;
   HIPCHK(c, hipMemcpyAsync(c->ctrl, &h, sizeof h, hipMemcpyHostToDevice, s));
   TabDims d = dims(c);
   TabPtrs t = ptrs(c);
@@ -798,7 +798,7 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
   if (st != OSSCAR_OK) return st;
   const double obj0 = h.obj;
   h.done = (c->cr == 0) ? 1 : 0; h.iters = 0; h.accepted = 0; h.notpd = 0; h.rel_tol = rel_tol; h.g_out = h.g_in = -1;
-  h.pause = 0; h.tau = 0;
+  h.pause = 0; h.tau = 0; h.tau_inc = 0;
   HIPCHK(c, hipMemcpyAsync(c->ctrl, &h, sizeof h, hipMemcpyHostToDevice, s));
   HIPCHK(c, hipStreamSynchronize(s));
   const int always = (flags & OSSCAR_SEARCH_ALWAYS_ACCEPT) ? 1 : 0;
@@ -852,8 +852,8 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
       }
       const bool want_refresh = !h.done && refresh_every > 0 && h.accepted - since_refresh_base >= refresh_every && h.iters < max_swaps;
       if (h.pause || since_flush >= FLUSH || h.done || want_refresh || h.iters >= max_swaps) {
-        if (h.tau > 0 || h.pause) { st = flush(); if (st != OSSCAR_OK) return st; }
-        h.pause = 0; h.tau = 0;
+        if (h.tau + h.tau_inc > 0 || h.pause) { st = flush(); if (st != OSSCAR_OK) return st; }
+        h.pause = 0; h.tau = 0; h.tau_inc = 0;
       }
       if (want_refresh) {
         if (flush_open) { HIPCHK(c, hipStreamSynchronize(s)); collect(); }      // the refresh times itself with the same events
@@ -873,7 +873,7 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
         h.obj = obj;
       }
     }
-    if (h.tau > 0) { st = flush(); if (st != OSSCAR_OK) return st; }
+    if (h.tau + h.tau_inc > 0) { st = flush(); if (st != OSSCAR_OK) return st; }
     if (flush_open) { HIPCHK(c, hipStreamSynchronize(s)); collect(); }
     c->timers[6] = refresh_ms + flush_ms;
     (void)flushes;
@@ -945,7 +945,7 @@ osscar_status osscar_block_search(osscar_ctx* c, int32_t max_iters, int32_t bloc
   st = read_ctrl(c, &h);
   if (st != OSSCAR_OK) return st;
   const double obj0 = h.obj;
-  h.done = 0; h.iters = 0; h.accepted = 0; h.notpd = 0; h.rel_tol = rel_tol; h.g_out = h.g_in = -1; h.pause = 0; h.tau = 0;
+  h.done = 0; h.iters = 0; h.accepted = 0; h.notpd = 0; h.rel_tol = rel_tol; h.g_out = h.g_in = -1; h.pause = 0; h.tau = 0; h.tau_inc = 0;
   HIPCHK(c, hipMemcpyAsync(c->ctrl, &h, sizeof h, hipMemcpyHostToDevice, s));
   HIPCHK(c, hipStreamSynchronize(s));
   const bool always = (flags & OSSCAR_SEARCH_ALWAYS_ACCEPT) != 0;
@@ -1034,7 +1034,7 @@ osscar_status osscar_apply_swap(osscar_ctx* c, int32_t g_out, int32_t g_in) {
   SearchCtrl h{};
   st = read_ctrl(c, &h);
   if (st != OSSCAR_OK) return st;
-  h.done = 0; h.iters = 0; h.notpd = 0; h.pause = 0; h.tau = 0;
+  h.done = 0; h.iters = 0; h.notpd = 0; h.pause = 0; h.tau = 0; h.tau_inc = 0;
   HIPCHK(c, hipMemcpyAsync(c->ctrl, &h, sizeof h, hipMemcpyHostToDevice, c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
   TabPtrs t = ptrs(c);

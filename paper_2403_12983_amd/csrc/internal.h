@@ -74,7 +74,9 @@ struct SearchCtrl {          // lives in device memory
   int32_t notpd;             // a pivot block was not definite
   int32_t g_out, g_in;       // current selection (group ids), -1 if none
   int32_t pause;             // delayed-update search: the host must flush before the search can go on
-  int32_t tau;               // delayed-update search: number of pending pivots
+  int32_t tau;               // delayed-update search: number of pending pivots that every kernel of an iteration works with
+  int32_t tau_inc;           // pivots that the iteration just applied adds to it: folded into tau by the next one-workgroup
+  int32_t pad_;              // kernel (prep), so that no kernel changes tau while its own workgroups read it
   double obj;                // tracked objective
   double rel_tol;
   double delta;              // exact change of the current pair
@@ -149,7 +151,6 @@ struct LazyPtrs {
   double* part;     // ceil(m/64) * 5 partial sums
   double* ls;       // 16 scalars
   SelRec* sel;      // ceil(d1/32) per-block score records
-  int32_t* counter; // workgroup counter of the update kernel
   // products of Z0 with the rows of Z0 that are likely to become pivots before the next flush
   double* GbT;      // (LAZY_NC + LAZY_NS) x d1: row s = Z0 Z0[cand[s], :]^T
   float* Zc;        // LAZY_NC x m: the gathered rows

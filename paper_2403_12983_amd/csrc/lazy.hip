@@ -41,6 +41,8 @@ __device__ __forceinline__ double wsum(double v) {
   return v;
 }
 __device__ __forceinline__ bool idle(const SearchCtrl* c) { return c->done || c->pause; }
+// pending pivots including those of the iteration that ran last (for kernels outside an iteration)
+__device__ __forceinline__ int tau_all(const SearchCtrl* c) { return c->tau + c->tau_inc; }
 
 constexpr int ROWS_PER_BLOCK = 32;   // row kernels: 8 lanes per row, 256 threads
 constexpr int COLS_PER_BLOCK = 64;   // column kernels: 64 columns x 4 slices of the pending set
@@ -93,6 +95,7 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
   __shared__ double bg[LAZY_TM], bj[LAZY_TM], red[3][4];
   if (idle(ctrl)) return;
   const int tid = threadIdx.x;
+  const int tau = tau_all(ctrl);           // every thread reads before thread 0 folds the increment in (after the barrier)
   // argmin of the removal costs / argmax of the addition gains from the per-block records (fixed order)
   double mn1 = INFINITY, mn2 = INFINITY, mx1 = -INFINITY, mx2 = -INFINITY;
   int imn = -1, imx = -1;
@@ -103,6 +106,7 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
   }
   s_mn1[tid] = mn1; s_mn2[tid] = mn2; s_imn[tid] = imn; s_mx1[tid] = mx1; s_mx2[tid] = mx2; s_imx[tid] = imx;
   __syncthreads();
+  if (tid == 0) { ctrl->tau = tau; ctrl->tau_inc = 0; }
   for (int o = 128; o > 0; o >>= 1) {
     if (tid < o) {
       merge_min(s_mn1[tid], s_mn2[tid], s_imn[tid], s_mn1[tid + o], s_mn2[tid + o], s_imn[tid + o]);
@@ -112,7 +116,6 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
   }
   const int g = single ? *single : (forced_g >= 0 ? forced_g : s_imn[0]);
   const int j = single ? g : (forced_g >= 0 ? forced_j : s_imx[0]);
-  const int tau = ctrl->tau;
   if (g < 0 || j < 0 || (forced_g >= 0 && (!kept[g] || kept[j]))) {
     if (tid == 0) { ctrl->done = 1; ctrl->g_out = -1; ctrl->g_in = -1; }
     return;
@@ -253,7 +256,7 @@ constexpr int GEMV_ROWS = 4 * GEMV_RPW;
 
 __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float* __restrict__ Z0, int d1, int m, int col_blocks,
                                                          SearchCtrl* ctrl, int always_accept, int32_t* trace_out,
-                                                         int32_t* trace_in, float* trace_gap, double* trace_obj) {
+                                                         int32_t* trace_in, float* trace_gap, double* trace_obj, int npiv) {
   __shared__ float sy1[LAZY_CH], sy2[LAZY_CH];
   __shared__ int s_ok;
   if (idle(ctrl)) return;
@@ -279,7 +282,7 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
         ctrl->delta = delta;
         const int it = ctrl->iters;
         ctrl->iters = it + 1;
-        if (ok) { ctrl->obj = obj + delta; ctrl->accepted += 1; } else { ctrl->done = 1; }
+        if (ok) { ctrl->obj = obj + delta; ctrl->accepted += 1; ctrl->tau_inc = npiv; } else { ctrl->done = 1; }
         if (trace_out) trace_out[it] = ctrl->g_out;
         if (trace_in) trace_in[it] = ctrl->g_in;
         if (trace_gap) { trace_gap[2 * it] = (float)ctrl->gap_rem; trace_gap[2 * it + 1] = (float)ctrl->gap_add; }
@@ -413,7 +416,7 @@ __device__ __forceinline__ void wcache_block(const LazyPtrs& L, int d1, const Se
 // rows    : squared row norms, diagonal, scores (and their per-block records), the two new columns of C0
 // columns : ZT <- M'^-1 Z0[T', :] for T' = T + {g, j}
 // M       : bordering of M^-1 by g then j
-// The last workgroup to finish advances tau.
+// tau itself is not touched here: the acceptance step has recorded the increment and the next iteration's prep folds it in.
 __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const float* __restrict__ N0, int d1, int m, int row_blocks,
                                                            int col_blocks, SearchCtrl* ctrl, int32_t* __restrict__ kept,
                                                            double* __restrict__ rho, double* __restrict__ diag,
@@ -421,7 +424,6 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
   __shared__ double sa[LAZY_TM], sb[LAZY_TM];
   __shared__ double w_mn1[4], w_mn2[4], w_mx1[4], w_mx2[4];
   __shared__ int w_imn[4], w_imx[4];
-  __shared__ int s_last;
   if (idle(ctrl)) return;
   const int tid = threadIdx.x, g = ctrl->g_out, j = ctrl->g_in, tau = ctrl->tau;
   const double Dg = L.ls[LS_DG], M1 = L.ls[LS_M1], Dj = L.ls[LS_DJ];
@@ -551,15 +553,6 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
       }
     }
   }
-  // the last workgroup to get here advances tau (all others have finished with the old value)
-  __syncthreads();
-  if (tid == 0) {
-    __threadfence();
-    const int done_blocks = atomicAdd(L.counter, 1);
-    s_last = (done_blocks == (int)gridDim.x - 1);
-  }
-  __syncthreads();
-  if (s_last && tid == 0) { *L.counter = 0; ctrl->tau = tau + (single ? 1 : 2); }
 }
 
 hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, int always_accept, hipStream_t s,
@@ -570,7 +563,7 @@ hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyP
   const int gb = (d.d1 + GEMV_ROWS - 1) / GEMV_ROWS + LAZY_TM;
   if (ev) hipEventRecord(ev[0], s);
   hipLaunchKernelGGL(lazy_gemv_kernel, dim3(gb), dim3(256), 0, s, L, t.Z, d.d1, d.m, cb, t.ctrl, always_accept, t.trace_out,
-                     t.trace_in, t.trace_gap, t.trace_obj);
+                     t.trace_in, t.trace_gap, t.trace_obj, single ? 1 : 2);
   if (ev) hipEventRecord(ev[1], s);
   hipLaunchKernelGGL(lazy_update_kernel, dim3(rb + cb + 16), dim3(256), 0, s, L, t.N, d.d1, d.m, rb, cb, t.ctrl, t.kept, t.gram,
                      t.dblk, t.score, single ? 1 : 0);
@@ -583,7 +576,7 @@ hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyP
 // ------------------------------------------------------------------------------------------------
 // float32 copies of M^-1 and ZT, zero beyond tau (so that stale columns of C0 drop out of the products)
 __global__ __launch_bounds__(256) void lazy_convert_kernel(LazyPtrs L, int m, const SearchCtrl* __restrict__ ctrl) {
-  const int tau = ctrl->tau;
+  const int tau = tau_all(ctrl);
   const int64_t nz = (int64_t)LAZY_TM * m, nm = (int64_t)LAZY_TM * LAZY_TM;
   for (int64_t idx = blockIdx.x * 256 + threadIdx.x; idx < nz + nm; idx += (int64_t)gridDim.x * 256) {
     if (idx < nz) {
@@ -602,7 +595,7 @@ __global__ __launch_bounds__(256) void lazy_fix_kernel(LazyPtrs L, float* __rest
                                                         const SearchCtrl* __restrict__ ctrl) {
   const int l = blockIdx.x * 256 + threadIdx.x;
   if (l >= d1) return;
-  const int tau = ctrl->tau;
+  const int tau = tau_all(ctrl);
   const int pr = L.pos[l];
   if (pr < 0) {
     const float* El = L.E + (int64_t)l * LAZY_TM;
@@ -622,14 +615,14 @@ __global__ __launch_bounds__(256) void lazy_fix_z_kernel(LazyPtrs L, float* __re
                                                           const SearchCtrl* __restrict__ ctrl) {
   const int col = blockIdx.x * 256 + threadIdx.x;
   if (col >= m) return;
-  const int tau = ctrl->tau;
+  const int tau = tau_all(ctrl);
   for (int s = 0; s < tau; s++) Z0[(int64_t)L.Tidx[s] * m + col] = (float)((double)L.Jsg[s] * L.ZT[(int64_t)s * m + col]);
 }
 __global__ __launch_bounds__(256) void lazy_reset_kernel(LazyPtrs L, SearchCtrl* ctrl) {
-  const int tau = ctrl->tau;
+  const int tau = tau_all(ctrl);
   for (int s = threadIdx.x; s < tau; s += 256) L.pos[L.Tidx[s]] = -1;
   __syncthreads();
-  if (threadIdx.x == 0) { ctrl->tau = 0; ctrl->pause = 0; }
+  if (threadIdx.x == 0) { ctrl->tau = 0; ctrl->tau_inc = 0; ctrl->pause = 0; }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -814,9 +807,10 @@ __global__ __launch_bounds__(256) void blk_prep_kernel(LazyPtrs L, const float* 
   __shared__ double sb[LAZY_TM * BT], sX[LAZY_TM * BT], sD[BT * BT];
   __shared__ int sG[BT], s_bad, s_notpd;
   if (idle(ctrl)) return;
-  const int tid = threadIdx.x, tau = ctrl->tau;
+  const int tid = threadIdx.x, tau = tau_all(ctrl);      // every thread reads before thread 0 folds the increment in
   if (tid == 0) { s_bad = 0; s_notpd = 0; }
   __syncthreads();
+  if (tid == 0) { ctrl->tau = tau; ctrl->tau_inc = 0; }
   if (tid < t) {
     const int g = pick[tid];
     sG[tid] = g;
@@ -957,7 +951,7 @@ __global__ __launch_bounds__(256) void blk_gemv_kernel(LazyPtrs L, int m, int t,
     for (int a = 0; a < t; a++) dsum += L.bdl[a];
     const int it = ctrl->iters;
     ctrl->obj = ctrl->obj - dsum;            // D is negative definite: -sum <Z_G[a], Y[a]> >= 0
-    ctrl->iters = it + t; ctrl->accepted += t;
+    ctrl->iters = it + t; ctrl->accepted += t; ctrl->tau_inc = t;
     if (trace_out) for (int a = 0; a < t; a++) trace_out[it + a] = L.bG[a];
   }
 }
@@ -970,7 +964,6 @@ __global__ __launch_bounds__(256) void blk_update_kernel(LazyPtrs L, const float
   __shared__ int sts[LAZY_TM], sG[BT], sSlot[BT];
   __shared__ double w_mn1[4], w_mn2[4], w_mx1[4], w_mx2[4];
   __shared__ int w_imn[4], w_imx[4];
-  __shared__ int s_last;
   if (idle(ctrl)) return;
   const int tid = threadIdx.x, tau = ctrl->tau, b = blockIdx.x;
   if (b < row_wgs) {
@@ -1127,14 +1120,6 @@ __global__ __launch_bounds__(256) void blk_update_kernel(LazyPtrs L, const float
       for (int idx = tid; idx < t * t; idx += 256) { const int a = idx / t, bb = idx % t; Mi[(tau + a) * LAZY_TM + tau + bb] = L.bD[a * BT + bb]; }
     }
   }
-  __syncthreads();
-  if (tid == 0) {
-    __threadfence();
-    const int done_blocks = atomicAdd(L.counter, 1);
-    s_last = (done_blocks == (int)gridDim.x - 1);
-  }
-  __syncthreads();
-  if (s_last && tid == 0) { *L.counter = 0; ctrl->tau = tau + t; }
 }
 
 hipError_t launch_lazy_block_remove(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, int take, const int32_t* pick,
@@ -1156,8 +1141,6 @@ hipError_t launch_lazy_init(const TabDims& d, const TabPtrs& t, const LazyPtrs& 
   e = hipMemsetAsync(L.Minv, 0, (size_t)LAZY_TM * LAZY_TM * 8, s);
   if (e != hipSuccess) return e;
   e = hipMemsetAsync(L.C0R, 0, (size_t)d.d1 * LAZY_TM * 4, s);
-  if (e != hipSuccess) return e;
-  e = hipMemsetAsync(L.counter, 0, 4, s);
   if (e != hipSuccess) return e;
   e = launch_partials(d, t, L, s);
   if (e != hipSuccess) return e;
