@@ -90,13 +90,15 @@ __global__ __launch_bounds__(64) void lazy_partials_kernel(LazyPtrs L, int p, co
 __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float* __restrict__ N0, int d1, int nrec,
                                                          const int32_t* __restrict__ kept, SearchCtrl* ctrl, const int32_t* __restrict__ single, int forced_g,
                                                          int forced_j) {
-  __shared__ double s_mn1[256], s_mn2[256], s_mx1[256], s_mx2[256];
-  __shared__ int s_imn[256], s_imx[256];
-  __shared__ double bg[LAZY_TM], bj[LAZY_TM], red[3][4];
+  __shared__ double s_mn1[4], s_mn2[4], s_mx1[4], s_mx2[4];
+  __shared__ int s_imn[4], s_imx[4];
+  __shared__ double bg[LAZY_TM], bj[LAZY_TM], red[3][4], s_n0[3];
   if (idle(ctrl)) return;
   const int tid = threadIdx.x;
   const int tau = tau_all(ctrl);           // every thread reads before thread 0 folds the increment in (after the barrier)
-  // argmin of the removal costs / argmax of the addition gains from the per-block records (fixed order)
+  // argmin of the removal costs / argmax of the addition gains from the per-block records: each thread merges its
+  // records, the waves reduce by shuffles, every thread merges the four wave results (lowest index wins ties, so the
+  // result does not depend on the order)
   double mn1 = INFINITY, mn2 = INFINITY, mx1 = -INFINITY, mx2 = -INFINITY;
   int imn = -1, imx = -1;
   for (int r = tid; r < nrec; r += 256) {
@@ -104,22 +106,27 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
     merge_min(mn1, mn2, imn, c.mn1, c.mn2, c.imn);
     merge_max(mx1, mx2, imx, c.mx1, c.mx2, c.imx);
   }
-  s_mn1[tid] = mn1; s_mn2[tid] = mn2; s_imn[tid] = imn; s_mx1[tid] = mx1; s_mx2[tid] = mx2; s_imx[tid] = imx;
+  for (int o = 32; o > 0; o >>= 1) {
+    double b1 = __shfl_down(mn1, o, 64), b2 = __shfl_down(mn2, o, 64); int ib = __shfl_down(imn, o, 64);
+    merge_min(mn1, mn2, imn, b1, b2, ib);
+    b1 = __shfl_down(mx1, o, 64); b2 = __shfl_down(mx2, o, 64); ib = __shfl_down(imx, o, 64);
+    merge_max(mx1, mx2, imx, b1, b2, ib);
+  }
+  if ((tid & 63) == 0) { const int w = tid >> 6; s_mn1[w] = mn1; s_mn2[w] = mn2; s_imn[w] = imn; s_mx1[w] = mx1; s_mx2[w] = mx2; s_imx[w] = imx; }
   __syncthreads();
   if (tid == 0) { ctrl->tau = tau; ctrl->tau_inc = 0; }
-  for (int o = 128; o > 0; o >>= 1) {
-    if (tid < o) {
-      merge_min(s_mn1[tid], s_mn2[tid], s_imn[tid], s_mn1[tid + o], s_mn2[tid + o], s_imn[tid + o]);
-      merge_max(s_mx1[tid], s_mx2[tid], s_imx[tid], s_mx1[tid + o], s_mx2[tid + o], s_imx[tid + o]);
-    }
-    __syncthreads();
-  }
-  const int g = single ? *single : (forced_g >= 0 ? forced_g : s_imn[0]);
-  const int j = single ? g : (forced_g >= 0 ? forced_j : s_imx[0]);
+  mn1 = s_mn1[0]; mn2 = s_mn2[0]; imn = s_imn[0]; mx1 = s_mx1[0]; mx2 = s_mx2[0]; imx = s_imx[0];
+  for (int w = 1; w < 4; w++) { merge_min(mn1, mn2, imn, s_mn1[w], s_mn2[w], s_imn[w]); merge_max(mx1, mx2, imx, s_mx1[w], s_mx2[w], s_imx[w]); }
+  const int g = single ? *single : (forced_g >= 0 ? forced_g : imn);
+  const int j = single ? g : (forced_g >= 0 ? forced_j : imx);
   if (g < 0 || j < 0 || (forced_g >= 0 && (!kept[g] || kept[j]))) {
     if (tid == 0) { ctrl->done = 1; ctrl->g_out = -1; ctrl->g_in = -1; }
     return;
   }
+  // the three base entries of the pivot block: requested now by otherwise idle threads, used by thread 0 at the end
+  if (tid == 192) s_n0[0] = (double)nsym1(N0, d1, g, g);
+  if (tid == 193) s_n0[1] = (double)nsym1(N0, d1, j, g);
+  if (tid == 194) s_n0[2] = (double)nsym1(N0, d1, j, j);
   const int sg0 = L.cslot[g], sj0 = L.cslot[j];
   const int need = (sg0 < 0 ? 1 : 0) + ((!single && sj0 < 0) ? 1 : 0);
   if (L.pos[g] >= 0 || L.pos[j] >= 0 || tau + (single ? 1 : 2) > LAZY_TM || L.misc[MI_SPARE] + need > LAZY_NS) {
@@ -132,21 +139,30 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
     bj[s] = (s < tau && !single) ? (double)L.C0R[(int64_t)j * LAZY_TM + s] : 0.0;
   }
   __syncthreads();
+  // two threads per row of M^-1, one half of the columns each
   double pgg = 0, pjg = 0, pjj = 0;
-  for (int r = tid; r < LAZY_TM; r += 256) {
+  {
+    const int r = tid >> 1, half = tid & 1;
     double a = 0, b = 0;
-    if (r < tau)
-      for (int s = 0; s < tau; s++) { const double mv = L.Minv[r * LAZY_TM + s]; a += mv * bg[s]; b += mv * bj[s]; }
-    L.xg[r] = a; L.xj[r] = b;
-    pgg += bg[r] * a; pjg += bj[r] * a; pjj += bj[r] * b;
+    if (r < tau) {
+      const double* mrow = L.Minv + r * LAZY_TM;
+      const int s1 = half ? tau : (tau < LAZY_TM / 2 ? tau : LAZY_TM / 2);
+#pragma unroll 8
+      for (int s = half * (LAZY_TM / 2); s < s1; s++) { const double mv = mrow[s]; a += mv * bg[s]; b += mv * bj[s]; }
+    }
+    a += __shfl_xor(a, 1, 64); b += __shfl_xor(b, 1, 64);
+    if (half == 0) {
+      L.xg[r] = a; L.xj[r] = b;
+      pgg = bg[r] * a; pjg = bj[r] * a; pjj = bj[r] * b;
+    }
   }
   pgg = wsum(pgg); pjg = wsum(pjg); pjj = wsum(pjj);
   if ((tid & 63) == 0) { red[0][tid >> 6] = pgg; red[1][tid >> 6] = pjg; red[2][tid >> 6] = pjj; }
   __syncthreads();
   if (tid == 0) {
-    const double ngg = (double)nsym1(N0, d1, g, g) - (red[0][0] + red[0][1] + red[0][2] + red[0][3]);
-    const double njg = (double)nsym1(N0, d1, j, g) - (red[1][0] + red[1][1] + red[1][2] + red[1][3]);
-    const double njj = (double)nsym1(N0, d1, j, j) - (red[2][0] + red[2][1] + red[2][2] + red[2][3]);
+    const double ngg = s_n0[0] - (red[0][0] + red[0][1] + red[0][2] + red[0][3]);
+    const double njg = s_n0[1] - (red[1][0] + red[1][1] + red[1][2] + red[1][3]);
+    const double njj = s_n0[2] - (red[2][0] + red[2][1] + red[2][2] + red[2][3]);
     const bool bad1 = !(ngg < 0.0);                         // kept pivot: N_gg = -P_gg
     const double Dg = 1.0 / (bad1 ? -1.0 : ngg);
     double M1 = Dg * njg;
@@ -163,7 +179,7 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
     if (single) sj = sg;
     else if (sj < 0) { sj = LAZY_NC + ns++; L.cslot[j] = sj; L.cand[sj] = j; miss |= 2; }
     L.misc[MI_SPARE] = ns; L.misc[MI_MISS] = miss; L.misc[MI_SG] = sg; L.misc[MI_SJ] = sj;
-    const double m1 = s_mn1[0], m2 = s_mn2[0], x1 = s_mx1[0], x2 = s_mx2[0];
+    const double m1 = mn1, m2 = mn2, x1 = mx1, x2 = mx2;
     ctrl->gap_rem = isfinite(m2) ? fabs(m2 - m1) / fmax(fabs(m1), 1e-300) : INFINITY;
     ctrl->gap_add = isfinite(x2) ? fabs(x1 - x2) / fmax(fabs(x1), 1e-300) : INFINITY;
   }
@@ -221,6 +237,9 @@ __global__ __launch_bounds__(256) void lazy_vectors_kernel(LazyPtrs L, const flo
   // current rows g and j of Z, scaled: y1 = Dg z_g, y2 = Dj (z_j - n_jg y1)
   const int cb = blockIdx.x - row_blocks;
   const int slice = tid >> 6, lc = tid & 63, col = cb * COLS_PER_BLOCK + lc;
+  // the base rows g, j of Z are requested first: their latency passes while ZT is read
+  float z0g = 0.f, z0j = 0.f;
+  if (slice == 0 && col < m) { z0g = Z0[(int64_t)g * m + col]; z0j = Z0[(int64_t)j * m + col]; }
   for (int s = tid; s < LAZY_TM; s += 256) {
     sa[s] = (s < tau) ? (double)L.C0R[(int64_t)g * LAZY_TM + s] : 0.0;
     sb[s] = (s < tau) ? (double)L.C0R[(int64_t)j * LAZY_TM + s] : 0.0;
@@ -235,8 +254,8 @@ __global__ __launch_bounds__(256) void lazy_vectors_kernel(LazyPtrs L, const flo
   double v[5] = {0, 0, 0, 0, 0};
   if (col < m) {
     const double Dg = L.ls[LS_DG], njg = L.ls[LS_NJG], Dj = L.ls[LS_DJ];
-    const double zg = (double)Z0[(int64_t)g * m + col] - (zred[0][0][lc] + zred[0][1][lc] + zred[0][2][lc] + zred[0][3][lc]);
-    const double zj = (double)Z0[(int64_t)j * m + col] - (zred[1][0][lc] + zred[1][1][lc] + zred[1][2][lc] + zred[1][3][lc]);
+    const double zg = (double)z0g - (zred[0][0][lc] + zred[0][1][lc] + zred[0][2][lc] + zred[0][3][lc]);
+    const double zj = (double)z0j - (zred[1][0][lc] + zred[1][1][lc] + zred[1][2][lc] + zred[1][3][lc]);
     const double y1 = Dg * zg, zjp = zj - njg * y1, y2 = Dj * zjp;
     L.y1[col] = y1; L.y2[col] = y2; L.y1f[col] = (float)y1; L.y2f[col] = (float)y2;
     v[0] = zg * y1; v[1] = zjp * y2; v[2] = y1 * y1; v[3] = y2 * y2; v[4] = y1 * y2;
@@ -264,6 +283,14 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
   // the row workgroups have work only when a pivot's products were not computed ahead (workgroup 0 records the decision)
   if ((int)blockIdx.x >= ZTB && L.misc[MI_MISS] == 0) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // u = ZT [y1 y2], one pending row per leading workgroup: started before the acceptance sums (it does not depend on them;
+  // a rejected swap, which ends the search, just discards it)
+  double ua = 0, ub = 0;
+  if ((int)blockIdx.x < ZTB && (int)blockIdx.x < ctrl->tau) {
+    const double* zt = L.ZT + (int64_t)blockIdx.x * m;
+#pragma unroll 4
+    for (int c = tid; c < m; c += 256) { const double z = zt[c]; ua += z * L.y1[c]; ub += z * L.y2[c]; }
+  }
   if (wave == 0) {
     // partial sums in a fixed order: lane l adds the records l, l + 64, ...; then a wave reduction
     double sk[5] = {0, 0, 0, 0, 0};
@@ -295,13 +322,7 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
   if ((int)blockIdx.x < ZTB) {
     __shared__ double ured[2][4];
     const int row = blockIdx.x;
-    double a = 0, b = 0;
-    if (row < ctrl->tau) {
-      const double* zt = L.ZT + (int64_t)row * m;
-#pragma unroll 4
-      for (int c = tid; c < m; c += 256) { const double z = zt[c]; a += z * L.y1[c]; b += z * L.y2[c]; }
-    }
-    a = wsum(a); b = wsum(b);
+    const double a = wsum(ua), b = wsum(ub);
     if (lane == 0) { ured[0][wave] = a; ured[1][wave] = b; }
     __syncthreads();
     if (tid == 0) {                                      // zero beyond tau
@@ -390,10 +411,13 @@ __device__ __forceinline__ void wcache_block(const LazyPtrs& L, int d1, const Se
   __shared__ int sts[LAZY_TM];
   __shared__ double red[2][4][64];
   const int tid = threadIdx.x, tau = ctrl->tau;
-  for (int s = tid; s < LAZY_TM; s += 256) { sxg[s] = L.xg[s]; sxj[s] = L.xj[s]; sts[s] = (s < tau) ? L.tslot[s] : 0; }
-  __syncthreads();
   const int slice = tid >> 6, lr = tid & 63, row = block * 64 + lr;
   const int rc = row < d1 ? row : d1 - 1;
+  // the pivots' own products are requested first: their latency passes while the pending pivots' are summed
+  double bgv = 0, bjv = 0;
+  if (slice == 0) { bgv = L.GbT[(int64_t)L.misc[MI_SG] * d1 + rc]; bjv = L.GbT[(int64_t)L.misc[MI_SJ] * d1 + rc]; }
+  for (int s = tid; s < LAZY_TM; s += 256) { sxg[s] = L.xg[s]; sxj[s] = L.xj[s]; sts[s] = (s < tau) ? L.tslot[s] : 0; }
+  __syncthreads();
   double ag = 0, aj = 0;
   for (int r = slice; r < tau; r += 4) {
     const double b = L.GbT[(int64_t)sts[r] * d1 + rc];
@@ -403,8 +427,8 @@ __device__ __forceinline__ void wcache_block(const LazyPtrs& L, int d1, const Se
   __syncthreads();
   if (slice != 0 || row >= d1) return;
   const double Dg = L.ls[LS_DG], njg = L.ls[LS_NJG], Dj = L.ls[LS_DJ];
-  const double tg = L.GbT[(int64_t)L.misc[MI_SG] * d1 + row] - (red[0][0][lr] + red[0][1][lr] + red[0][2][lr] + red[0][3][lr]);
-  const double tj = L.GbT[(int64_t)L.misc[MI_SJ] * d1 + row] - (red[1][0][lr] + red[1][1][lr] + red[1][2][lr] + red[1][3][lr]);
+  const double tg = bgv - (red[0][0][lr] + red[0][1][lr] + red[0][2][lr] + red[0][3][lr]);
+  const double tj = bjv - (red[1][0][lr] + red[1][1][lr] + red[1][2][lr] + red[1][3][lr]);
   const double w1 = Dg * tg;
   L.w1[row] = w1;
   L.w2[row] = Dj * (tj - njg * w1);
