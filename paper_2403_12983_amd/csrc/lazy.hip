@@ -101,10 +101,16 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
   // result does not depend on the order)
   double mn1 = INFINITY, mn2 = INFINITY, mx1 = -INFINITY, mx2 = -INFINITY;
   int imn = -1, imx = -1;
-  for (int r = tid; r < nrec; r += 256) {
-    const SelRec c = L.sel[r];
-    merge_min(mn1, mn2, imn, c.mn1, c.mn2, c.imn);
-    merge_max(mx1, mx2, imx, c.mx1, c.mx2, c.imx);
+  for (int r0 = tid; r0 < nrec; r0 += 1024) {          // four records in flight per thread
+    SelRec c[4];
+#pragma unroll
+    for (int k = 0; k < 4; k++) { const int r = r0 + 256 * k; c[k] = L.sel[r < nrec ? r : r0]; }
+#pragma unroll
+    for (int k = 0; k < 4; k++)
+      if (r0 + 256 * k < nrec) {
+        merge_min(mn1, mn2, imn, c[k].mn1, c[k].mn2, c[k].imn);
+        merge_max(mx1, mx2, imx, c[k].mx1, c[k].mx2, c[k].imx);
+      }
   }
   for (int o = 32; o > 0; o >>= 1) {
     double b1 = __shfl_down(mn1, o, 64), b2 = __shfl_down(mn2, o, 64); int ib = __shfl_down(imn, o, 64);
@@ -145,10 +151,18 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
     const int r = tid >> 1, half = tid & 1;
     double a = 0, b = 0;
     if (r < tau) {
-      const double* mrow = L.Minv + r * LAZY_TM;
-      const int s1 = half ? tau : (tau < LAZY_TM / 2 ? tau : LAZY_TM / 2);
-#pragma unroll 8
-      for (int s = half * (LAZY_TM / 2); s < s1; s++) { const double mv = mrow[s]; a += mv * bg[s]; b += mv * bj[s]; }
+      // the whole half row is requested at once (bg, bj are zero beyond tau, M^-1 is finite there)
+      const double* mrow = L.Minv + r * LAZY_TM + half * (LAZY_TM / 2);
+      const double* pg = bg + half * (LAZY_TM / 2);
+      const double* pj = bj + half * (LAZY_TM / 2);
+      const int cnt = min(tau - half * (LAZY_TM / 2), LAZY_TM / 2);      // columns of this half below tau (may be <= 0)
+      for (int s0 = 0; s0 < cnt; s0 += 32) {
+        double mv[32];
+#pragma unroll
+        for (int u = 0; u < 32; u++) mv[u] = mrow[s0 + u];
+#pragma unroll
+        for (int u = 0; u < 32; u++) { a += mv[u] * pg[s0 + u]; b += mv[u] * pj[s0 + u]; }
+      }
     }
     a += __shfl_xor(a, 1, 64); b += __shfl_xor(b, 1, 64);
     if (half == 0) {
@@ -247,7 +261,13 @@ __global__ __launch_bounds__(256) void lazy_vectors_kernel(LazyPtrs L, const flo
   __syncthreads();
   double pg = 0, pj = 0;
   if (col < m)
-    for (int s = slice; s < tau; s += 4) { const double zt = L.ZT[(int64_t)s * m + col]; pg += sa[s] * zt; pj += sb[s] * zt; }
+    for (int s = slice; s < tau; s += 32) {               // eight loads in flight (sa, sb are zero beyond tau)
+      double zt[8];
+#pragma unroll
+      for (int u = 0; u < 8; u++) { const int ss = s + 4 * u; zt[u] = L.ZT[(int64_t)(ss < tau ? ss : s) * m + col]; }
+#pragma unroll
+      for (int u = 0; u < 8; u++) { const int ss = s + 4 * u; if (ss < tau) { pg += sa[ss] * zt[u]; pj += sb[ss] * zt[u]; } }
+    }
   zred[0][slice][lc] = pg; zred[1][slice][lc] = pj;
   __syncthreads();
   if (slice != 0) return;
@@ -288,8 +308,13 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
   double ua = 0, ub = 0;
   if ((int)blockIdx.x < ZTB && (int)blockIdx.x < ctrl->tau) {
     const double* zt = L.ZT + (int64_t)blockIdx.x * m;
-#pragma unroll 4
-    for (int c = tid; c < m; c += 256) { const double z = zt[c]; ua += z * L.y1[c]; ub += z * L.y2[c]; }
+    for (int c0 = tid; c0 < m; c0 += 2048) {             // eight columns in flight per thread
+      double z[8], p1[8], p2[8];
+#pragma unroll
+      for (int u = 0; u < 8; u++) { const int c = c0 + 256 * u, cc = c < m ? c : c0; z[u] = zt[cc]; p1[u] = L.y1[cc]; p2[u] = L.y2[cc]; }
+#pragma unroll
+      for (int u = 0; u < 8; u++) if (c0 + 256 * u < m) { ua += z[u] * p1[u]; ub += z[u] * p2[u]; }
+    }
   }
   if (wave == 0) {
     // partial sums in a fixed order: lane l adds the records l, l + 64, ...; then a wave reduction
@@ -419,9 +444,12 @@ __device__ __forceinline__ void wcache_block(const LazyPtrs& L, int d1, const Se
   for (int s = tid; s < LAZY_TM; s += 256) { sxg[s] = L.xg[s]; sxj[s] = L.xj[s]; sts[s] = (s < tau) ? L.tslot[s] : 0; }
   __syncthreads();
   double ag = 0, aj = 0;
-  for (int r = slice; r < tau; r += 4) {
-    const double b = L.GbT[(int64_t)sts[r] * d1 + rc];
-    ag += sxg[r] * b; aj += sxj[r] * b;
+  for (int r = slice; r < tau; r += 32) {                 // eight loads in flight
+    double bv[8];
+#pragma unroll
+    for (int u = 0; u < 8; u++) { const int rr = r + 4 * u; bv[u] = L.GbT[(int64_t)sts[rr < tau ? rr : r] * d1 + rc]; }
+#pragma unroll
+    for (int u = 0; u < 8; u++) { const int rr = r + 4 * u; if (rr < tau) { ag += sxg[rr] * bv[u]; aj += sxj[rr] * bv[u]; } }
   }
   red[0][slice][lr] = ag; red[1][slice][lr] = aj;
   __syncthreads();
@@ -461,6 +489,16 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
     double mn1 = INFINITY, mx1 = -INFINITY;
     int imn = -1, imx = -1;
     if (row < d1) {
+      // what the row's leader needs from memory is requested before the dot products, not after them
+      float n0g = 0.f, n0j = 0.f;
+      double c1 = 0, cjv = 0, rho0 = 0, diag0 = 0, w1c = 0, w2c = 0;
+      int ps = -1, kp0 = 0;
+      if (l8 == 0) {
+        n0g = nsym1(N0, d1, row, g);
+        if (!single) n0j = nsym1(N0, d1, row, j);
+        ps = L.pos[row]; c1 = L.cg[row]; cjv = L.cj[row]; rho0 = rho[row]; diag0 = diag[row]; kp0 = kept[row];
+        if (!miss) { w1c = L.w1[row]; w2c = L.w2[row]; }
+      }
       double da, db;
       row_dots(L.C0R + (int64_t)row * LAZY_TM, sa, sb, l8, da, db);
       // w = Z0 [y1 y2] of this row: computed ahead in lazy_vectors_kernel's launch, unless a pivot's products with Z0 were
@@ -479,11 +517,11 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
         const double tj = L.GbT[(int64_t)L.misc[MI_SJ] * d1 + row] - aj;
         w1r = Dg * tg;
         w2r = Dj * (tj - L.ls[LS_NJG] * w1r);
-      } else { w1r = L.w1[row]; w2r = L.w2[row]; }
+      } else { w1r = w1c; w2r = w2c; }
       if (l8 == 0) {
         // the base columns of g and j become columns tau, tau + 1 of C0
-        L.C0R[(int64_t)row * LAZY_TM + tau] = nsym1(N0, d1, row, g);
-        if (!single) L.C0R[(int64_t)row * LAZY_TM + tau + 1] = nsym1(N0, d1, row, j);
+        L.C0R[(int64_t)row * LAZY_TM + tau] = n0g;
+        if (!single) L.C0R[(int64_t)row * LAZY_TM + tau + 1] = n0j;
         double r, dn;
         int kp;
         if (row == g) {
@@ -496,17 +534,15 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
           L.pos[row] = tau + 1; L.Tidx[tau + 1] = row; L.Jsg[tau + 1] = 1.f; L.tslot[tau + 1] = L.misc[MI_SJ];
         } else {
           double zy1, zy2;
-          const int ps = L.pos[row];
           if (ps >= 0) { const double sg = (double)L.Jsg[ps]; zy1 = sg * sa[ps]; zy2 = sg * sb[ps]; }
           else { zy1 = w1r - da; zy2 = w2r - db; }
-          const double c1 = L.cg[row];
-          const double c2 = L.cj[row] - c1 * M1;
-          r = rho[row] - 2.0 * c1 * zy1 + c1 * c1 * y11;       // after the reverse sweep on g
+          const double c2 = cjv - c1 * M1;
+          r = rho0 - 2.0 * c1 * zy1 + c1 * c1 * y11;           // after the reverse sweep on g
           const double zy2p = zy2 - c1 * y12;                  // (Z_i - c1 y1) . y2
           r += -2.0 * c2 * zy2p + c2 * c2 * y22;               // after the forward sweep on j
           if (r < 0.0) r = 0.0;
-          dn = diag[row] - c1 * c1 * Dg - c2 * c2 * Dj;
-          kp = kept[row];
+          dn = diag0 - c1 * c1 * Dg - c2 * c2 * Dj;
+          kp = kp0;
         }
         rho[row] = r; diag[row] = dn; kept[row] = kp;
         const double sc = r / fabs(dn);
