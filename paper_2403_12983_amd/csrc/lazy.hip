@@ -36,9 +36,26 @@ namespace osscar {
 __device__ __forceinline__ float nsym1(const float* __restrict__ N, int64_t ld, int i, int t) {
   return (i >= t) ? N[(int64_t)i * ld + t] : N[(int64_t)t * ld + i];
 }
+// Sum over the 64 lanes of a wave by data-parallel-primitive moves (no trip through the LDS crossbar, which costs a
+// shuffle about 40 ns here and made the reductions the longest part of the small kernels): pairs and quads by quad
+// permutations, the four quads of a row of 16 by row rotations, then row 0 -> 1 and 2 -> 3 (row_bcast:15) and
+// rows 0-1 -> 3 (row_bcast:31); lane 63 holds the total, which every lane receives.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_get(double v) {
+  int lo = __double2loint(v), hi = __double2hiint(v);
+  lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, ROW_MASK, 0xf, false);
+  hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, ROW_MASK, 0xf, false);
+  return __hiloint2double(hi, lo);
+}
 __device__ __forceinline__ double wsum(double v) {
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
-  return v;
+  v += dpp_get<0xb1, 0xf>(v);        // quad_perm [1, 0, 3, 2]
+  v += dpp_get<0x4e, 0xf>(v);        // quad_perm [2, 3, 0, 1]
+  v += dpp_get<0x124, 0xf>(v);       // row_ror:4
+  v += dpp_get<0x128, 0xf>(v);       // row_ror:8
+  v += dpp_get<0x142, 0xa>(v);       // row_bcast:15 into rows 1 and 3 (other rows add zero)
+  v += dpp_get<0x143, 0xc>(v);       // row_bcast:31 into rows 2 and 3
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63), hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
+  return __hiloint2double(hi, lo);
 }
 __device__ __forceinline__ bool idle(const SearchCtrl* c) { return c->done || c->pause; }
 // pending pivots including those of the iteration that ran last (for kernels outside an iteration)
