@@ -21,6 +21,11 @@ typedef double d4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 128, BN = 128, BK = 16, LDT = BM + 4;
 
+// Workgroup barrier that waits for this wave's LDS traffic only.  __syncthreads() also waits until every global load and
+// store of the wave has completed, which in an epilogue that stages through LDS pass by pass makes each pass wait for the
+// previous pass's stores to reach memory.  Only for hazards on LDS data.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 struct Tile8 { float v[8]; };
 
 // 8 consecutive floats of a row starting at column c0 (element stride 1), zero beyond `ncols`.
@@ -309,11 +314,28 @@ __global__ __launch_bounds__(256, 2) void gemm_f32acc_kernel(GemmArgs g, int vec
   const float alpha = (float)g.alpha, beta = (float)g.beta, dadd = (float)g.diag_add;
   constexpr int SLD = 68;
   float* st = smem + wave * 32 * SLD;          // 4 waves x 32 x 68 floats = 34816 bytes > smem: stage 16 rows at a time
+  // This thread's Cin values are all requested before the first staging pass, and the passes are separated by barriers
+  // that wait for LDS only: the loads' latency is paid once and no pass waits for the stores of the one before
+  // (measured per workgroup on the rank-128 update of a 28672^2 triangle: epilogue 22.7 us, as long as the main loop,
+  // 5.3 us of it in each of the four passes between its barriers).
+  float4 cpre[2][2][4];
+  const bool pre = use_cin && vecC;
+  auto load_cin = [&](int i) {                   // the 32 rows i of this wave's 64: requested while the rows before them are
+#pragma unroll                                   // still being staged, when the accumulators they replace are no longer live
+    for (int half = 0; half < 2; half++)
+#pragma unroll
+      for (int k = 0; k < 4; k++) {
+        const int row = m0 + wm * 64 + i * 32 + half * 16 + (lane >> 4) + 4 * k, col = n0 + wn * 64 + (lane & 15) * 4;
+        cpre[i][half][k] = (row < g.M && col + 3 < g.N) ? *reinterpret_cast<const float4*>(Cin + (int64_t)row * g.ldcin + col)
+                                                        : float4{0.f, 0.f, 0.f, 0.f};
+      }
+  };
+  if (pre) load_cin(0);
 #pragma unroll
   for (int i = 0; i < 2; i++) {
 #pragma unroll
     for (int half = 0; half < 2; half++) {       // rows (r/4)*8 + ... with r/4 in {2*half, 2*half+1}
-      __syncthreads();
+      lds_barrier();
       float* sth = smem + wave * 16 * SLD;
 #pragma unroll
       for (int j = 0; j < 2; j++)
@@ -324,7 +346,8 @@ __global__ __launch_bounds__(256, 2) void gemm_f32acc_kernel(GemmArgs g, int vec
             const int r = (2 * half + rq) * 4 + r3;
             sth[(rq * 8 + (lane >> 5) * 4 + r3) * SLD + j * 32 + (lane & 31)] = alpha * acc[i][j][r];
           }
-      __syncthreads();
+      lds_barrier();
+      if (pre && i == 0 && half == 1) load_cin(1);
 #pragma unroll
       for (int k = 0; k < 4; k++) {
         const int lr = (lane >> 4) + 4 * k, lc = (lane & 15) * 4;     // 16 staged rows x 64 columns
@@ -336,7 +359,7 @@ __global__ __launch_bounds__(256, 2) void gemm_f32acc_kernel(GemmArgs g, int vec
           for (int e = 0; e < 4; e++) v[e] = sth[lr * SLD + lc + e];
           if (vecC && col + 3 < g.N) {
             if (use_cin) {
-              const float4 ci = *reinterpret_cast<const float4*>(Cin + (int64_t)row * g.ldcin + col);
+              const float4 ci = cpre[i][half][k];
               v[0] += beta * ci.x; v[1] += beta * ci.y; v[2] += beta * ci.z; v[3] += beta * ci.w;
             }
 #pragma unroll
