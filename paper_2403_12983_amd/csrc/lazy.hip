@@ -47,6 +47,15 @@ __device__ __forceinline__ double dpp_get(double v) {
   hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, ROW_MASK, 0xf, false);
   return __hiloint2double(hi, lo);
 }
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_get_or(double v, double dflt) {
+  int lo = __double2loint(v), hi = __double2hiint(v);
+  lo = __builtin_amdgcn_update_dpp(__double2loint(dflt), lo, CTRL, ROW_MASK, 0xf, false);
+  hi = __builtin_amdgcn_update_dpp(__double2hiint(dflt), hi, CTRL, ROW_MASK, 0xf, false);
+  return __hiloint2double(hi, lo);
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_get_or(int v, int dflt) { return __builtin_amdgcn_update_dpp(dflt, v, CTRL, ROW_MASK, 0xf, false); }
 __device__ __forceinline__ double wsum(double v) {
   v += dpp_get<0xb1, 0xf>(v);        // quad_perm [1, 0, 3, 2]
   v += dpp_get<0x4e, 0xf>(v);        // quad_perm [2, 3, 0, 1]
@@ -79,6 +88,27 @@ __device__ __forceinline__ void merge_max(double& a1, double& a2, int& ia, doubl
   const bool takeb = (ib >= 0) && (ia < 0 || b1 > a1 || (b1 == a1 && ib < ia));
   const double n1 = takeb ? b1 : a1, other = takeb ? a1 : b1;
   a2 = fmax(fmax(a2, b2), other); a1 = n1; ia = takeb ? ib : ia;
+}
+
+// The (best, second, index) records of the 64 lanes of a wave merged into lane 63, by the same data-parallel moves as
+// wsum (each step joins disjoint sets of lanes, so no record meets itself; lanes that a row mask leaves out see the
+// neutral record).  Lanes without a candidate hold the neutral record (+-inf, index -1).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ void dpp_merge_step(double& mn1, double& mn2, int& imn, double& mx1, double& mx2, int& imx) {
+  const double b1 = dpp_get_or<CTRL, ROW_MASK>(mn1, INFINITY), b2 = dpp_get_or<CTRL, ROW_MASK>(mn2, INFINITY);
+  const int ib = dpp_get_or<CTRL, ROW_MASK>(imn, -1);
+  const double c1 = dpp_get_or<CTRL, ROW_MASK>(mx1, -INFINITY), c2 = dpp_get_or<CTRL, ROW_MASK>(mx2, -INFINITY);
+  const int ic = dpp_get_or<CTRL, ROW_MASK>(imx, -1);
+  merge_min(mn1, mn2, imn, b1, b2, ib);
+  merge_max(mx1, mx2, imx, c1, c2, ic);
+}
+__device__ __forceinline__ void wave_merge(double& mn1, double& mn2, int& imn, double& mx1, double& mx2, int& imx) {
+  dpp_merge_step<0xb1, 0xf>(mn1, mn2, imn, mx1, mx2, imx);
+  dpp_merge_step<0x4e, 0xf>(mn1, mn2, imn, mx1, mx2, imx);
+  dpp_merge_step<0x124, 0xf>(mn1, mn2, imn, mx1, mx2, imx);
+  dpp_merge_step<0x128, 0xf>(mn1, mn2, imn, mx1, mx2, imx);
+  dpp_merge_step<0x142, 0xa>(mn1, mn2, imn, mx1, mx2, imx);
+  dpp_merge_step<0x143, 0xc>(mn1, mn2, imn, mx1, mx2, imx);
 }
 
 // per-block record of the scores of rows [32 b, 32 b + 32): used after a flush; the update kernel writes the same records
@@ -114,8 +144,8 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
   const int tid = threadIdx.x;
   const int tau = tau_all(ctrl);           // every thread reads before thread 0 folds the increment in (after the barrier)
   // argmin of the removal costs / argmax of the addition gains from the per-block records: each thread merges its
-  // records, the waves reduce by shuffles, every thread merges the four wave results (lowest index wins ties, so the
-  // result does not depend on the order)
+  // records, the waves reduce by data-parallel moves, every thread merges the four wave results (lowest index wins
+  // ties, so the result does not depend on the order)
   double mn1 = INFINITY, mn2 = INFINITY, mx1 = -INFINITY, mx2 = -INFINITY;
   int imn = -1, imx = -1;
   for (int r0 = tid; r0 < nrec; r0 += 1024) {          // four records in flight per thread
@@ -129,13 +159,8 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
         merge_max(mx1, mx2, imx, c[k].mx1, c[k].mx2, c[k].imx);
       }
   }
-  for (int o = 32; o > 0; o >>= 1) {
-    double b1 = __shfl_down(mn1, o, 64), b2 = __shfl_down(mn2, o, 64); int ib = __shfl_down(imn, o, 64);
-    merge_min(mn1, mn2, imn, b1, b2, ib);
-    b1 = __shfl_down(mx1, o, 64); b2 = __shfl_down(mx2, o, 64); ib = __shfl_down(imx, o, 64);
-    merge_max(mx1, mx2, imx, b1, b2, ib);
-  }
-  if ((tid & 63) == 0) { const int w = tid >> 6; s_mn1[w] = mn1; s_mn2[w] = mn2; s_imn[w] = imn; s_mx1[w] = mx1; s_mx2[w] = mx2; s_imx[w] = imx; }
+  wave_merge(mn1, mn2, imn, mx1, mx2, imx);
+  if ((tid & 63) == 63) { const int w = tid >> 6; s_mn1[w] = mn1; s_mn2[w] = mn2; s_imn[w] = imn; s_mx1[w] = mx1; s_mx2[w] = mx2; s_imx[w] = imx; }
   __syncthreads();
   if (tid == 0) { ctrl->tau = tau; ctrl->tau_inc = 0; }
   mn1 = s_mn1[0]; mn2 = s_mn2[0]; imn = s_imn[0]; mx1 = s_mx1[0]; mx2 = s_mx2[0]; imx = s_imx[0];
@@ -569,15 +594,11 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
     }
     // per-block record (the row leaders are lanes 0, 8, 16, ... of each wave)
     double mn2 = INFINITY, mx2 = -INFINITY;
-    for (int o = 32; o >= 8; o >>= 1) {
-      double b1 = __shfl_down(mn1, o, 64), b2 = __shfl_down(mn2, o, 64); int ib = __shfl_down(imn, o, 64);
-      merge_min(mn1, mn2, imn, b1, b2, ib);
-      b1 = __shfl_down(mx1, o, 64); b2 = __shfl_down(mx2, o, 64); ib = __shfl_down(imx, o, 64);
-      merge_max(mx1, mx2, imx, b1, b2, ib);
-    }
-    if ((tid & 63) == 0) { const int w = tid >> 6; w_mn1[w] = mn1; w_mn2[w] = mn2; w_imn[w] = imn; w_mx1[w] = mx1; w_mx2[w] = mx2; w_imx[w] = imx; }
+    wave_merge(mn1, mn2, imn, mx1, mx2, imx);          // lanes that lead no row hold the neutral record
+    if ((tid & 63) == 63) { const int w = tid >> 6; w_mn1[w] = mn1; w_mn2[w] = mn2; w_imn[w] = imn; w_mx1[w] = mx1; w_mx2[w] = mx2; w_imx[w] = imx; }
     __syncthreads();
     if (tid == 0) {
+      mn1 = w_mn1[0]; mn2 = w_mn2[0]; imn = w_imn[0]; mx1 = w_mx1[0]; mx2 = w_mx2[0]; imx = w_imx[0];
       for (int w = 1; w < 4; w++) { merge_min(mn1, mn2, imn, w_mn1[w], w_mn2[w], w_imn[w]); merge_max(mx1, mx2, imx, w_mx1[w], w_mx2[w], w_imx[w]); }
       SelRec rec; rec.mn1 = mn1; rec.mn2 = mn2; rec.mx1 = mx1; rec.mx2 = mx2; rec.imn = imn; rec.imx = imx;
       L.sel[b] = rec;
@@ -1143,15 +1164,11 @@ __global__ __launch_bounds__(256) void blk_update_kernel(LazyPtrs L, const float
       }
     }
     double mn2 = INFINITY, mx2 = -INFINITY;
-    for (int o = 32; o >= 8; o >>= 1) {
-      double b1 = __shfl_down(mn1, o, 64), b2 = __shfl_down(mn2, o, 64); int ib = __shfl_down(imn, o, 64);
-      merge_min(mn1, mn2, imn, b1, b2, ib);
-      b1 = __shfl_down(mx1, o, 64); b2 = __shfl_down(mx2, o, 64); ib = __shfl_down(imx, o, 64);
-      merge_max(mx1, mx2, imx, b1, b2, ib);
-    }
-    if ((tid & 63) == 0) { const int w = tid >> 6; w_mn1[w] = mn1; w_mn2[w] = mn2; w_imn[w] = imn; w_mx1[w] = mx1; w_mx2[w] = mx2; w_imx[w] = imx; }
+    wave_merge(mn1, mn2, imn, mx1, mx2, imx);          // lanes that lead no row hold the neutral record
+    if ((tid & 63) == 63) { const int w = tid >> 6; w_mn1[w] = mn1; w_mn2[w] = mn2; w_imn[w] = imn; w_mx1[w] = mx1; w_mx2[w] = mx2; w_imx[w] = imx; }
     __syncthreads();
     if (tid == 0) {
+      mn1 = w_mn1[0]; mn2 = w_mn2[0]; imn = w_imn[0]; mx1 = w_mx1[0]; mx2 = w_mx2[0]; imx = w_imx[0];
       for (int w = 1; w < 4; w++) { merge_min(mn1, mn2, imn, w_mn1[w], w_mn2[w], w_imn[w]); merge_max(mx1, mx2, imx, w_mx1[w], w_mx2[w], w_imx[w]); }
       SelRec rec; rec.mn1 = mn1; rec.mn2 = mn2; rec.mx1 = mx1; rec.mx2 = mx2; rec.imn = imn; rec.imx = imx;
       L.sel[rbk] = rec;
