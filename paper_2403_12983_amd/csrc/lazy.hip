@@ -797,8 +797,11 @@ static hipError_t launch_candidates(const TabDims& d, const TabPtrs& t, const La
   hipError_t e = hipMemsetAsync(L.cslot, 0xFF, (size_t)d.d1 * 4, s);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(cand_local_kernel, dim3(nblk), dim3(1024), 0, s, L, d.p, t.kept, t.score, per_block);
-  // (the product takes about as long for 128 rows as for 256: one 128-row tile per CU leaves the CU half empty)
-  const int n_k = mode == 2 ? 0 : (mode == 1 ? LAZY_NC : LAZY_NC / 2), n_c = mode == 0 ? LAZY_NC / 2 : 0;
+  // Swap search: 64 + 64 rows.  They cover about 97 % of the next 64 swaps' pivots; the rest take a spare slot and a pass
+  // over Z0 each (0.155 ms on the 28672 x 7168 layer), which costs less than the second 128-row tile of the product
+  // (0.85 ms): measured 0.33 ms per flush in favour of the smaller set.  The removal-only loops take all LAZY_NC rows:
+  // their block pivots cannot fetch a missing product.
+  const int n_k = mode == 2 ? 0 : (mode == 1 ? LAZY_NC : LAZY_NC / 4), n_c = mode == 0 ? LAZY_NC / 4 : 0;
   hipLaunchKernelGGL(cand_merge_kernel, dim3(1), dim3(1024), 0, s, L, nblk, per_block, n_k, n_c);
   if (mode == 2) return hipGetLastError();
   hipLaunchKernelGGL(cand_gather_kernel, dim3(n_k + n_c), dim3(256), 0, s, L, t.Z, d.m);
