@@ -268,8 +268,12 @@ def test_search_variants(name):
     s.osscar_init_support()
     part = s.osscar_local_search(2)
     assert part["iters"] == 2 and part["accepted"] == 2
-    rest = s.osscar_local_search(c.cfg.swaps - 2)
-    assert part["trace_out"].tolist() + rest["trace_out"].tolist() == base["trace_out"].tolist()
+    one = s.osscar_local_search(1)                       # a single swap: its pivots are pending when the call ends
+    assert one["iters"] == 1
+    rest = s.osscar_local_search(c.cfg.swaps - 3)
+    assert part["trace_out"].tolist() + one["trace_out"].tolist() + rest["trace_out"].tolist() == base["trace_out"].tolist()
+    assert part["trace_in"].tolist() + one["trace_in"].tolist() + rest["trace_in"].tolist() == base["trace_in"].tolist()
+    assert abs(rest["obj_final"] - base["obj_final"]) <= 1e-6 * base["obj_final"]
     # Algorithm 1 as printed: every selected pair is applied
     s.osscar_init_support()
     n = min(8, c.cfg.swaps)
