@@ -90,6 +90,16 @@ __device__ __forceinline__ void merge_max(double& a1, double& a2, int& ia, doubl
   a2 = fmax(fmax(a2, b2), other); a1 = n1; ia = takeb ? ib : ia;
 }
 
+// Sum over each group of eight consecutive lanes (every lane of the group receives it): pairs and quads by quad
+// permutations, the two quads of a half row by row_half_mirror (lane i of the half row reads lane 7 - i, which by then
+// holds the other quad's sum).
+__device__ __forceinline__ double sum8(double v) {
+  v += dpp_get<0xb1, 0xf>(v);
+  v += dpp_get<0x4e, 0xf>(v);
+  v += dpp_get<0x141, 0xf>(v);
+  return v;
+}
+
 // The (best, second, index) records of the 64 lanes of a wave merged into lane 63, by the same data-parallel moves as
 // wsum (each step joins disjoint sets of lanes, so no record meets itself; lanes that a row mask leaves out see the
 // neutral record).  Lanes without a candidate hold the neutral record (+-inf, index -1).
@@ -254,9 +264,7 @@ __device__ __forceinline__ void row_dots(const float* __restrict__ crow, const d
     a += (double)c.x * xa[s] + (double)c.y * xa[s + 1] + (double)c.z * xa[s + 2] + (double)c.w * xa[s + 3];
     b += (double)c.x * xb[s] + (double)c.y * xb[s + 1] + (double)c.z * xb[s + 2] + (double)c.w * xb[s + 3];
   }
-  a += __shfl_xor(a, 1, 64); b += __shfl_xor(b, 1, 64);
-  a += __shfl_xor(a, 2, 64); b += __shfl_xor(b, 2, 64);
-  a += __shfl_xor(a, 4, 64); b += __shfl_xor(b, 4, 64);
+  a = sum8(a); b = sum8(b);
 }
 
 __global__ __launch_bounds__(256) void lazy_vectors_kernel(LazyPtrs L, const float* __restrict__ N0, const float* __restrict__ Z0,
@@ -552,9 +560,7 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
           const double b = L.GbT[(int64_t)L.tslot[r] * d1 + row];
           ag += L.xg[r] * b; aj += L.xj[r] * b;
         }
-        ag += __shfl_xor(ag, 1, 64); aj += __shfl_xor(aj, 1, 64);
-        ag += __shfl_xor(ag, 2, 64); aj += __shfl_xor(aj, 2, 64);
-        ag += __shfl_xor(ag, 4, 64); aj += __shfl_xor(aj, 4, 64);
+        ag = sum8(ag); aj = sum8(aj);
         const double tg = L.GbT[(int64_t)L.misc[MI_SG] * d1 + row] - ag;
         const double tj = L.GbT[(int64_t)L.misc[MI_SJ] * d1 + row] - aj;
         w1r = Dg * tg;
@@ -1101,9 +1107,7 @@ __global__ __launch_bounds__(256) void blk_update_kernel(LazyPtrs L, const float
       }
 #pragma unroll
       for (int a = 0; a < BT; a++) {
-        dx[a] += __shfl_xor(dx[a], 1, 64); du[a] += __shfl_xor(du[a], 1, 64); dw[a] += __shfl_xor(dw[a], 1, 64);
-        dx[a] += __shfl_xor(dx[a], 2, 64); du[a] += __shfl_xor(du[a], 2, 64); dw[a] += __shfl_xor(dw[a], 2, 64);
-        dx[a] += __shfl_xor(dx[a], 4, 64); du[a] += __shfl_xor(du[a], 4, 64); dw[a] += __shfl_xor(dw[a], 4, 64);
+        dx[a] = sum8(dx[a]); du[a] = sum8(du[a]); dw[a] = sum8(dw[a]);
       }
       // the base entries N0[row, G] (new columns of C0) and the products GbT[G, row]: lane l8 fetches a = l8 and l8 + 8
       static_assert(BT == 16, "two picks per lane");
