@@ -311,12 +311,12 @@ __global__ __launch_bounds__(256) void lazy_vectors_kernel(LazyPtrs L, const flo
   __syncthreads();
   double pg = 0, pj = 0;
   if (col < m)
-    for (int s = slice; s < tau; s += 32) {               // eight loads in flight (sa, sb are zero beyond tau)
-      double zt[8];
+    for (int s = slice; s < tau; s += 64) {               // sixteen loads in flight
+      double zt[16];
 #pragma unroll
-      for (int u = 0; u < 8; u++) { const int ss = s + 4 * u; zt[u] = L.ZT[(int64_t)(ss < tau ? ss : s) * m + col]; }
+      for (int u = 0; u < 16; u++) { const int ss = s + 4 * u; zt[u] = L.ZT[(int64_t)(ss < tau ? ss : s) * m + col]; }
 #pragma unroll
-      for (int u = 0; u < 8; u++) { const int ss = s + 4 * u; if (ss < tau) { pg += sa[ss] * zt[u]; pj += sb[ss] * zt[u]; } }
+      for (int u = 0; u < 16; u++) { const int ss = s + 4 * u; if (ss < tau) { pg += sa[ss] * zt[u]; pj += sb[ss] * zt[u]; } }
     }
   zred[0][slice][lc] = pg; zred[1][slice][lc] = pj;
   __syncthreads();
@@ -494,12 +494,12 @@ __device__ __forceinline__ void wcache_block(const LazyPtrs& L, int d1, const Se
   for (int s = tid; s < LAZY_TM; s += 256) { sxg[s] = L.xg[s]; sxj[s] = L.xj[s]; sts[s] = (s < tau) ? L.tslot[s] : 0; }
   __syncthreads();
   double ag = 0, aj = 0;
-  for (int r = slice; r < tau; r += 32) {                 // eight loads in flight
-    double bv[8];
+  for (int r = slice; r < tau; r += 64) {                 // sixteen loads in flight
+    double bv[16];
 #pragma unroll
-    for (int u = 0; u < 8; u++) { const int rr = r + 4 * u; bv[u] = L.GbT[(int64_t)sts[rr < tau ? rr : r] * d1 + rc]; }
+    for (int u = 0; u < 16; u++) { const int rr = r + 4 * u; bv[u] = L.GbT[(int64_t)sts[rr < tau ? rr : r] * d1 + rc]; }
 #pragma unroll
-    for (int u = 0; u < 8; u++) { const int rr = r + 4 * u; if (rr < tau) { ag += sxg[rr] * bv[u]; aj += sxj[rr] * bv[u]; } }
+    for (int u = 0; u < 16; u++) { const int rr = r + 4 * u; if (rr < tau) { ag += sxg[rr] * bv[u]; aj += sxj[rr] * bv[u]; } }
   }
   red[0][slice][lr] = ag; red[1][slice][lr] = aj;
   __syncthreads();
