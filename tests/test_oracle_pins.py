@@ -557,3 +557,98 @@ def test_prune_layer_end_to_end_on_cfg1():
     assert np.isclose(out["obj"], orc.objective_direct(X, W, out["What"], out["lam"]), rtol=1e-9)
     pruned = np.setdiff1d(np.arange(cfg.d1), orc.rows_of(out["support"], cfg.q))
     assert np.all(out["What"][pruned] == 0)
+
+
+# ---------------------------------------------------------------- gaps and deficits (the quantities the GPU parity rule reads)
+def _diagonal_form(scores, m=1):
+    """A quadratic form with H = I and one weight column scaled so that the impact of group g (eq. (impact), doubled by the
+    missing 1/2) is exactly scores[g] whether it is kept or not: H_gg ||W_g||^2 with orthogonal columns
+    (pinned to re-solves in test_diagonal_H_closed_form)."""
+    s = np.asarray(scores, dtype=np.float64)
+    p = len(s)
+    W = np.zeros((p, m))
+    W[:, 0] = np.sqrt(s)
+    H = np.eye(p)
+    G = H @ W
+    return H, G, float(np.sum(W * G)), p
+
+
+def test_gap_helpers_on_hand_values():
+    inf = np.inf
+    # best and second-best of the finite entries, relative to the best
+    assert orc._gap_low(np.array([1.0, 1.5, 4.0])) == pytest.approx(0.5, rel=1e-15)
+    assert orc._gap_low(np.array([inf, 4.0, inf, 1.5, 1.0])) == pytest.approx(0.5, rel=1e-15)
+    assert orc._gap_high(np.array([1.0, 1.5, 4.0])) == pytest.approx(0.625, rel=1e-15)
+    assert orc._gap_high(np.array([-inf, 8.0, 6.0, -inf, 2.0])) == pytest.approx(0.25, rel=1e-15)
+    assert orc._gap_low(np.array([2.0, 2.0, 9.0])) == 0.0 and orc._gap_high(np.array([3.0, 7.0, 7.0])) == 0.0
+    # fewer than two finite values: no second-best, the gap is infinite
+    assert orc._gap_low(np.array([inf, 3.0])) == inf and orc._gap_high(np.array([-inf, 3.0])) == inf
+    assert orc._gap_low(np.array([inf, inf])) == inf and orc._gap_high(np.array([])) == inf
+
+
+def test_swap_record_gaps_and_deficits_on_a_diagonal_form():
+    # kept {0, 1, 2} with removal costs 1, 1.5, 4; outside {3, 4, 5} with gains 8, 6, 2 (Section 4.2 selection rule)
+    H, G, c0, p = _diagonal_form([1.0, 1.5, 4.0, 8.0, 6.0, 2.0])
+    free = orc.local_search(H, G, c0, [0, 1, 2], p, 1, 1)
+    x = free.trace[0]
+    assert (x.g_out, x.j_in) == (0, 3) and x.accepted
+    assert x.rem == pytest.approx(1.0) and x.add == pytest.approx(8.0) and x.delta == pytest.approx(1.0 - 8.0)
+    assert x.gap_rem == pytest.approx(0.5) and x.gap_add == pytest.approx(0.25)
+    assert x.deficit_rem == 0.0 and x.deficit_add == 0.0
+    # forced second-best on both sides: shortfalls (1.5 - 1) / 1 and (8 - 6) / 8; the gaps still describe the oracle's own best
+    y = orc.local_search(H, G, c0, [0, 1, 2], p, 1, 1, follow=[(1, 4)]).trace[0]
+    assert y.deficit_rem == pytest.approx(0.5) and y.deficit_add == pytest.approx(0.25)
+    assert y.gap_rem == pytest.approx(0.5) and y.gap_add == pytest.approx(0.25)
+    assert y.delta == pytest.approx(1.5 - 6.0)
+    # forced worst on the entering side only
+    z = orc.local_search(H, G, c0, [0, 1, 2], p, 1, 1, follow=[(0, 5)]).trace[0]
+    assert z.deficit_rem == 0.0 and z.deficit_add == pytest.approx(0.75)
+    # the exact entering rule scores the candidates at the state without the leaving group; on a diagonal form the same numbers
+    w = orc.local_search(H, G, c0, [0, 1, 2], p, 1, 1, follow=[(0, 4)], exact_in=True).trace[0]
+    assert w.deficit_add == pytest.approx(0.25) and w.gap_add == pytest.approx(0.25)
+    # a correlated form: the deficit of a forced second-best entering group, from scores obtained by full re-solves
+    X, W, Hc, Gc, c0c, lam = make_problem(10, 1, 3, 80, 123, corr=1.2)
+    K0 = [0, 2, 4, 6, 8]
+    base = orc.solve_support(Hc, Gc, c0c, K0, 1)[1]
+    gains = {j: base - orc.solve_support(Hc, Gc, c0c, K0 + [j], 1)[1] for j in range(10) if j not in K0}
+    order = sorted(gains, key=lambda j: -gains[j])
+    costs = {g: orc.solve_support(Hc, Gc, c0c, [h for h in K0 if h != g], 1)[1] - base for g in K0}
+    gmin = min(costs, key=lambda g: costs[g])
+    r = orc.local_search(Hc, Gc, c0c, K0, 10, 1, 1, follow=[(gmin, order[1])]).trace[0]
+    assert r.deficit_add == pytest.approx((gains[order[0]] - gains[order[1]]) / gains[order[0]], rel=1e-8)
+    assert r.gap_add == pytest.approx((gains[order[0]] - gains[order[1]]) / gains[order[0]], rel=1e-8)
+    assert r.deficit_rem == 0.0
+    rs = sorted(costs.values())
+    assert r.gap_rem == pytest.approx((rs[1] - rs[0]) / rs[0], rel=1e-8)
+
+
+def test_block_record_gaps_and_deficits_on_a_diagonal_form():
+    # kept {0..3} with costs 1, 1.5, 4, 7; outside {4..7} with gains 8, 6, 2, 1; two out, two in
+    H, G, c0, p = _diagonal_form([1.0, 1.5, 4.0, 7.0, 8.0, 6.0, 2.0, 1.0])
+    own = orc.block_search(H, G, c0, [0, 1, 2, 3], p, 1, 1, 2).trace[0]
+    assert own.out == [0, 1] and own.inn == [4, 5]
+    assert own.gap_rem == pytest.approx((4.0 - 1.5) / 1.5) and own.gap_add == pytest.approx((6.0 - 2.0) / 6.0)
+    assert own.deficit_rem == 0.0 and own.deficit_add == 0.0
+    assert own.delta == pytest.approx((1.0 + 1.5) - (8.0 + 6.0))
+    forced = orc.block_search(H, G, c0, [0, 1, 2, 3], p, 1, 1, 2, follow=[([0, 2], [4, 6])]).trace[0]
+    assert forced.deficit_rem == pytest.approx((4.0 - 1.5) / 1.5) and forced.deficit_add == pytest.approx((6.0 - 2.0) / 6.0)
+    assert forced.gap_rem == pytest.approx((4.0 - 1.5) / 1.5) and forced.gap_add == pytest.approx((6.0 - 2.0) / 6.0)
+    # every group of a side taken: nothing is left out, the gap is infinite
+    allof = orc.block_search(H, G, c0, [0, 1], p, 1, 1, 2).trace[0]
+    assert allof.gap_rem == np.inf and np.isfinite(allof.gap_add)
+
+
+def test_greedy_record_gap_and_deficit_on_a_diagonal_form():
+    # dense start, removal costs 3, 1, 2, 5, 4; two per iteration down to two kept
+    H, G, c0, p = _diagonal_form([3.0, 1.0, 2.0, 5.0, 4.0])
+    own = orc.greedy_from_dense(H, G, c0, p, 1, 2, 2)
+    assert [r.removed for r in own.trace] == [[1, 2], [0]]
+    assert own.trace[0].gap == pytest.approx((3.0 - 2.0) / 2.0) and own.trace[0].deficit == 0.0
+    assert own.trace[1].gap == pytest.approx((4.0 - 3.0) / 3.0)
+    assert own.trace[0].costs == pytest.approx([1.0, 2.0])
+    assert own.obj_final == pytest.approx(1.0 + 2.0 + 3.0)
+    forced = orc.greedy_from_dense(H, G, c0, p, 1, 2, 2, follow=[[1, 0], [2]])
+    assert forced.trace[0].deficit == pytest.approx((3.0 - 2.0) / 2.0) and forced.trace[0].gap == pytest.approx(0.5)
+    assert forced.trace[1].deficit == 0.0                       # 2 is now the cheapest of what is left
+    last = orc.greedy_from_dense(H, G, c0, p, 1, 0, 5).trace[0]
+    assert last.gap == np.inf                                   # nothing left out
