@@ -6,9 +6,13 @@ calibration rows, finalize (ridge, G = H W), magnitude support + state build, th
 final back-solve.  X and W are resident in HBM before the timed region starts.
 
 Prints one JSON line.  `value` is seconds per layer (lower is better).  `roofline` describes the kernel the
-layer time is dominated by, the float64-accumulating MFMA GEMM, on its largest launch (V = P H_{K,Kc}).
-`roofline_gram` describes the bf16 MFMA Gram kernel, and `cpu_baseline` the float64 oracle timed on this
-box's host cores on a reduced layer of the same recipe."""
+layer time is dominated by, the bf16 MFMA Gram kernel (it also carries G = H W and the products of the state
+build): algorithmic flops of one launch (16384 calibration rows) over the mean launch duration, measured by
+HIP events on the library's stream inside the timed steps.  `roofline_gemm_f64acc` / `roofline_gemm_f32acc`
+give the two general matrix-product kernels: their largest launch, and the time-weighted rate over ALL their
+launches of one layer (from the library's launch log, collected on one extra untimed layer).  `cpu_baseline`
+is the float64 oracle timed on this machine's host cores on a reduced layer of the same recipe: `value` is what
+the clock measured on that reduced layer; the projection to the full layer is a separate, labelled key."""
 from __future__ import annotations
 
 import argparse
@@ -18,7 +22,7 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
-GEMM_TRAFFIC_CFG5 = 40.53e9   # bytes; see profiles/gemm_f64acc_cfg5_pmc.md
+GRAM_TRAFFIC_CFG5 = None      # HBM bytes of one Gram kernel launch on cfg5 from rocprofv3 --pmc (profiles/gram_packed_cfg5_pmc.md)
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -32,7 +36,8 @@ def gen_on_gpu(inp, torch, cfg, dev, rows_per=4096):
 
 
 def cpu_baseline(inp, cfg_full):
-    """The oracle as it stands on a reduced layer (same recipe), projected to the full layer by work ratios."""
+    """The oracle as it stands, timed on a reduced layer of the same recipe (the full layer would take the host days: one
+    oracle iteration at d1 = 28672 is a minute of float64 matrix products, and there are 5000).  value = measured seconds."""
     import numpy as np
     from oracle import osscar_oracle as orc
     p, m, n, k, swaps = 4096, 1024, 16384, 2048, 48     # about 15 s of host work
@@ -66,12 +71,16 @@ def cpu_baseline(inp, cfg_full):
         cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
     except Exception:
         pass
-    return {"value": projected, "unit": "s", "cores": cores, "kind": "oracle",
-            "sample": (f"float64 numpy oracle on the cfg5 recipe reduced to p={p}, m={m}, n={n}, k={k}, {res.iters} swap "
-                       f"iterations: gram {t_gram:.2f}s, init {t_init:.2f}s, search {t_search:.2f}s, backsolve {t_back:.2f}s "
-                       f"measured; projected to the full layer by work ratios (gram x{r_gram:.0f}, cubic phases x{r_cube:.0f}, "
-                       f"{f.swaps} swaps)"),
-            "measured_s": t_gram + t_init + t_search + t_back}
+    measured = t_gram + t_init + t_search + t_back
+    return {"value": measured, "unit": "s", "cores": cores, "kind": "oracle",
+            "sample": (f"the float64 oracle (numpy with its BLAS / LAPACK, {cores} threads) on ONE reduced layer of the "
+                       f"{cfg_full.name} recipe: p={p}, m={m}, n={n}, k={k}, {res.iters} swap iterations; measured gram {t_gram:.2f} s, "
+                       f"state {t_init:.2f} s, search {t_search:.2f} s, final solve {t_back:.2f} s.  This is the whole-layer path on "
+                       f"a layer with 1/{f.d1 // p} of the rows of W and {res.iters} of {f.swaps} swaps, not the full layer"),
+            "reduced_layer": {"p": p, "m": m, "n": n, "k": k, "swaps": res.iters},
+            "projected_full_layer_s": projected,
+            "projection": (f"NOT measured: reduced-layer phases scaled by work ratios (gram x{r_gram:.0f}, cubic phases "
+                           f"x{r_cube:.0f}, per-iteration cost x{r_cube:.0f} for {f.swaps} swaps)")}
 
 
 def main():
@@ -91,6 +100,10 @@ def main():
                     help="groups swapped per iteration (t-hat = 2 * block): swaps // block iterations of block moves")
     ap.add_argument("--no-lookahead", action="store_true",
                     help="search without the products computed ahead: every swap then makes one read-only pass over Z")
+    ap.add_argument("--eager", action="store_true",
+                    help="in-place search (OSSCAR_SEARCH_EAGER): one rank-2 pass over the whole state per swap, the HBM-bound form")
+    ap.add_argument("--gemm-table", default=None,
+                    help="write the per-shape table of the general matrix-product launches of one layer (markdown) to this file")
     ap.add_argument("--exact-in", action="store_true",
                     help="entering group by the exact gain of the pair (OSSCAR_SEARCH_EXACT_IN); runs on the in-place path")
     ap.add_argument("--rows", type=int, default=None,
@@ -119,11 +132,11 @@ def main():
 
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
     phases = {k: 0.0 for k in ("gram", "finalize", "init", "search", "backsolve")}
-    upd_n = upd_z = gemm_ms = gemm32_ms = flush_ms = 0.0
+    upd_n = upd_z = gemm_ms = gemm32_ms = flush_ms = gram_launch_ms = cand_ms = 0.0
     info = {}
 
     def step(timed):
-        nonlocal upd_n, upd_z, gemm_ms, gemm32_ms, flush_ms
+        nonlocal upd_n, upd_z, gemm_ms, gemm32_ms, flush_ms, gram_launch_ms, cand_ms
         ev[0].record()
         s.osscar_gram(X, False)
         ev[1].record()
@@ -132,6 +145,8 @@ def main():
         obj0 = s.osscar_init_support() if a.init == "magnitude" else s.osscar_init_greedy(a.t_hat)[0]
         ev[3].record()
         fl = pkg.OSSCAR_SEARCH_NO_LOOKAHEAD if a.no_lookahead else 0
+        if a.eager:
+            fl |= pkg.OSSCAR_SEARCH_EAGER
         if a.exact_in:
             fl |= pkg.OSSCAR_SEARCH_EXACT_IN
         if a.block > 1:
@@ -152,6 +167,8 @@ def main():
             gemm_ms += tm[9]
             gemm32_ms += tm[10]
             flush_ms += tm[6]
+            gram_launch_ms += tm[13]
+            cand_ms += tm[12]
         info.update(obj0=obj0, obj=obj, iters=r["iters"], accepted=r["accepted"], tracked=r["obj_final"])
 
     for _ in range(a.warmup):
@@ -170,27 +187,64 @@ def main():
     gemm_ms /= K
     gemm32_ms /= K
     flush_ms /= K
+    gram_launch_ms /= K
+    cand_ms /= K
     t_layer = wall / K
+
+    # one more layer, untimed, with the library's launch log on: every general matrix product with its shape and duration
+    from paper_2403_12983_amd import binding as B
+    B.gemm_log(True)
+    step(False)
+    log = B.gemm_log_read()
+    B.gemm_log(False)
+
+    def weighted(rows):
+        """time-weighted rate over launches: total flops / total time (lower-triangle launches count half the square)"""
+        fl_ = sum(2.0 * r[0] * r[1] * r[2] * (0.5 if int(r[3]) & 4 else 1.0) for r in rows)
+        ms_ = sum(r[4] for r in rows if r[4] > 0)
+        return (fl_ / (ms_ * 1e-3) / 1e12 if ms_ > 0 else None), ms_, len(rows)
+    w64, ms64, n64 = weighted([r for r in log if not int(r[3]) & 1])
+    w32, ms32, n32 = weighted([r for r in log if int(r[3]) & 1])
+    if a.gemm_table:
+        groups = {}
+        for r in log:
+            key = (int(r[0]), int(r[1]), int(r[2]), int(r[3]))
+            g = groups.setdefault(key, [0, 0.0])
+            g[0] += 1
+            g[1] += r[4]
+        with open(a.gemm_table, "w") as f:
+            f.write("| M | N | K | accumulate | output | tiles | count | total ms | ms per launch | TFLOP/s | fraction of that pipe's peak |\n|---|---|---|---|---|---|---|---|---|---|---|\n")
+            for (M_, N_, K_, kind), (cnt, ms_) in sorted(groups.items(), key=lambda kv: -kv[1][1]):
+                fl_ = 2.0 * M_ * N_ * K_ * (0.5 if kind & 4 else 1.0) * cnt
+                tf = fl_ / (ms_ * 1e-3) / 1e12 if ms_ > 0 else 0.0
+                peak = 157.3 if kind & 1 else 78.6
+                f.write(f"| {M_} | {N_} | {K_} | {'float32' if kind & 1 else 'float64'} | {'float64' if kind & 2 else 'float32'} | "
+                        f"{'lower triangle' if kind & 4 else 'all'} | {cnt} | {ms_:.3f} | {ms_ / cnt:.4f} | {tf:.1f} | {tf / peak:.3f} |\n")
+            f.write(f"\nfloat64-accumulating kernel: {n64} launches, {ms64:.1f} ms, time-weighted {w64 or 0:.1f} TFLOP/s = {(w64 or 0) / 78.6:.3f} of 78.6\n")
+            f.write(f"float32-accumulating kernel: {n32} launches, {ms32:.1f} ms, time-weighted {w32 or 0:.1f} TFLOP/s = {(w32 or 0) / 157.3:.3f} of 157.3\n")
 
     d1, m, n = cfg.d1, cfg.m, cfg.n
     gram_flops = n * d1 * (d1 + 1)
-    lazy = (cfg.q == 1) and not a.exact_in
+    lazy = (cfg.q == 1) and not a.exact_in and not a.eager
     # Per-swap state update of an in-place search (Proposition 4.1): read + write of P, V (= lower triangle of N) and B, R (= Z)
     bytes_swap_alg = 2 * 4 * (d1 * d1 // 2) + 2 * 4 * d1 * m
     ms_swap = 1e3 * phases["search"] / max(info["iters"], 1)
-    # Dominant kernel of the layer: the float64-accumulating MFMA GEMM (the inverse's refinement, B, V, S, R, the look-ahead
-    # products of the search, the back-solve's residual).  Its largest launch, V = P H_{K,Kc} in the state build, is timed by
-    # HIP events on the library's stream (timer slot 9): 2 kr^2 cr flops on v_mfma_f64_16x16x4_f64.
+    # Dominant kernel of the layer: the bf16 MFMA Gram kernel (Gram phase, G = H W, and the six-product forms of the state
+    # build's products).  Unit of the roofline: one launch of the Gram phase = one chunk of up to 16384 calibration rows,
+    # algorithmic SYRK flops rows * d1 * (d1 + 1) (the lower block triangle), duration = mean over the launches of the timed
+    # steps, bracketed by HIP events on the library's stream (timer slot 13).
     kr, cr = cfg.k * cfg.q, d1 - cfg.k * cfg.q
     n_inv = d1 if a.init == "greedy" else kr       # order of the matrix the support initialisation inverts
-    g_flops = 2.0 * kr * kr * cr
-    g_bytes = 4.0 * (kr * kr + 2 * kr * cr)                      # read P and H_{K,Kc} once, write V once
-    # HBM bytes of that launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/gemm_f64acc_cfg5_pmc.md), cfg5 only
-    g_traffic = GEMM_TRAFFIC_CFG5 if a.config == "cfg5" else None
+    rows_per_launch = min(16384, n)
+    gl_flops = float(rows_per_launch) * d1 * (d1 + 1)
+    gl_bytes = 2.0 * rows_per_launch * d1 + 8.0 * d1 * (d1 + 1)       # the packed chunk read once; the float64 lower triangle read and written
+    gram_traffic = GRAM_TRAFFIC_CFG5 if (a.config == "cfg5" and a.rows is None) else None
+    g_flops = 2.0 * n_inv ** 3                                         # largest float64-accumulating launch: I - H_KK P
+    g_bytes = 4.0 * 3 * n_inv * n_inv
     out = {
         "metric": "OPT-30B fc2 layer prune time", "value": t_layer, "unit": "s", "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": 1e3 * t_layer, "higher_is_better": False, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16 inputs, f32 state, f64 accumulate", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: X {n}x{d1} {cfg.x_dtype}, W {d1}x{m} {cfg.w_dtype}, keep {cfg.k} of {cfg.p} groups "
                                f"(q={cfg.q}), {swaps} swaps, lambda = {cfg.lam_rel}*mean diag",
                    "refresh_every": a.refresh_every,
@@ -205,34 +259,44 @@ def main():
         "gram_tflops_syrk": gram_flops / phases["gram"] / 1e12,
         "gram_tflops_full_equiv": 2 * n * d1 * d1 / phases["gram"] / 1e12,
         "objective": {"initial": info["obj0"], "final": info["obj"], "tracked": info["tracked"]},
-        "roofline": {"kernel": "gemm_f64acc_kernel<float>, launch V = P H_{K,Kc} (float32 operands, float64 MFMA accumulation)",
-                     "bound": "mfma", "achieved": g_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None, "peak": 78.6,
-                     "unit": "TFLOP/s", "frac": g_flops / (gemm_ms * 1e-3) / 1e12 / 78.6 if gemm_ms > 0 else None,
-                     "traffic": g_traffic, "flops_per_launch": g_flops, "algorithmic_bytes_per_launch": g_bytes,
-                     "ms_per_launch": gemm_ms if gemm_ms > 0 else None},
+        "roofline": {"kernel": "gram_packed_kernel (bf16 MFMA SYRK on the lower block triangle), one launch = one chunk of "
+                               f"{rows_per_launch} calibration rows",
+                     "bound": "mfma", "achieved": gl_flops / (gram_launch_ms * 1e-3) / 1e12 if gram_launch_ms > 0 else None,
+                     "peak": 2500.0, "unit": "TFLOP/s",
+                     "frac": gl_flops / (gram_launch_ms * 1e-3) / 1e12 / 2500.0 if gram_launch_ms > 0 else None,
+                     "traffic": gram_traffic, "flops_per_launch": gl_flops, "algorithmic_bytes_per_launch": gl_bytes,
+                     "ms_per_launch": gram_launch_ms if gram_launch_ms > 0 else None},
+        "roofline_gemm_f64acc": {"kernel": "gemm_f64acc_kernel (float32 operands, float64 MFMA accumulation): the residuals that refine "
+                                           "the inverse and the weights", "bound": "mfma", "peak": 78.6, "unit": "TFLOP/s",
+                                 "largest_launch": {"what": "I - H_KK P of the Newton-Schulz step", "flops": g_flops,
+                                                    "algorithmic_bytes": g_bytes, "ms": gemm_ms if gemm_ms > 0 else None,
+                                                    "achieved": g_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None,
+                                                    "frac": g_flops / (gemm_ms * 1e-3) / 1e12 / 78.6 if gemm_ms > 0 else None},
+                                 "all_launches_of_a_layer": {"launches": n64, "ms": ms64, "achieved": w64,
+                                                             "frac": (w64 / 78.6) if w64 else None}},
         # The float32-accumulating MFMA GEMM (v_mfma_f32_32x32x2_f32: flushes of the search, sweeps of the inverse, small
         # corrections) takes about as long per layer as the float64-accumulating one; its largest launch is the lower triangle
         # of P (I - H_KK P) in the Newton-Schulz step: kr^3 flops (timer slot 10).
-        "roofline_gemm_f32acc": {"kernel": "gemm_f32acc_kernel<false>, launch tril(P (I - H_KK P))", "bound": "mfma",
-                                 "achieved": float(n_inv) ** 3 / (gemm32_ms * 1e-3) / 1e12 if gemm32_ms > 0 else None,
-                                 "peak": 157.3, "unit": "TFLOP/s",
-                                 "frac": float(n_inv) ** 3 / (gemm32_ms * 1e-3) / 1e12 / 157.3 if gemm32_ms > 0 else None,
-                                 "ms_per_launch": gemm32_ms},
-        "roofline_gram": {"kernel": "gram_packed_kernel (+ gram_pack_kernel, whole Gram phase)", "bound": "mfma",
-                          "achieved": gram_flops / phases["gram"] / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
-                          "frac": gram_flops / phases["gram"] / 1e12 / 2500.0,
-                          "note": "algorithmic SYRK flops n*d1*(d1+1); the kernel issues 2x that on diagonal tiles only"},
+        "roofline_gemm_f32acc": {"kernel": "gemm_f32acc_kernel (float32 MFMA accumulation): rank-128 flushes of the search, sweeps of "
+                                           "the inverse", "bound": "mfma", "peak": 157.3, "unit": "TFLOP/s",
+                                 "all_launches_of_a_layer": {"launches": n32, "ms": ms32, "achieved": w32,
+                                                             "frac": (w32 / 157.3) if w32 else None}},
+        "state_build": {"candidate_side_products_ms": cand_ms, "inverse_correction_product_ms": gemm32_ms},
+        "roofline_gram_phase": {"kernel": "gram_pack_kernel + gram_packed_kernel, the whole Gram phase (repacking included)",
+                                "bound": "mfma", "achieved": gram_flops / phases["gram"] / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
+                                "frac": gram_flops / phases["gram"] / 1e12 / 2500.0,
+                                "note": "algorithmic SYRK flops n*d1*(d1+1); the kernel issues 2x that on diagonal tiles only"},
         "search_iteration": ({"note": "per swap: four small kernels (selection and pivot algebra; current pivot rows/columns and w from the "
                                       "products computed ahead; acceptance test and u; update of norms/diagonal/scores); every 64 swaps a flush by matrix "
                                       "products plus one look-ahead product Zc Z^T.  An eager in-place up/downdate of P, B, V, R would "
                                       "move bytes_per_swap_eager per swap",
                               "ms_per_swap": ms_swap, "accept_and_u_kernel_ms": 1e3 * upd_n, "iteration_kernels_ms": 1e3 * upd_z,
-                              "flushes_total_ms": flush_ms, "bytes_per_swap_eager": bytes_swap_alg,
-                              "eager_equivalent_GBps": bytes_swap_alg / ms_swap / 1e6} if lazy else
+                              "flushes_total_ms": flush_ms, "bytes_per_swap_eager": bytes_swap_alg} if lazy else
                              {"note": "in-place search: every swap is one rank-2q pass over the tableau (N: lower triangle, Z)",
                               "ms_per_swap": ms_swap, "update_N_ms": 1e3 * upd_n, "update_Z_ms": 1e3 * upd_z,
                               "bytes_per_swap": bytes_swap_alg,
-                              "update_GBps": bytes_swap_alg / max(upd_n + upd_z, 1e-12) / 1e9}),
+                              "update_GBps": bytes_swap_alg / max(upd_n + upd_z, 1e-12) / 1e9,
+                              "frac_of_hbm_peak": bytes_swap_alg / max(upd_n + upd_z, 1e-12) / 1e9 / 8000.0}),
     }
     s.close()
     del X

@@ -20,13 +20,21 @@
  *     osscar_workspace_bytes() bytes (256-byte aligned) to osscar_create and owns it, X, W and What.
  *     The context keeps pointers into the workspace only; W is read only during osscar_gram.
  *   - All work is ordered on the stream given to osscar_create.  Calls that return host values
- *     synchronise that stream; osscar_gram without finalize does not.  The context owns one more stream (default
+ *     synchronise that stream; osscar_gram without finalize does not (bf16 chunks on the matrix-core path; other chunks
+ *     may).  The context owns one more stream (default
  *     priority) for a product of the search that overlaps with others; it forks from and joins the caller's stream
  *     through events inside a call, so the caller sees the ordering of a single stream.
  *   - Every call returns an osscar_status.  No exception crosses this boundary and nothing aborts.
  *     After a failure other than OSSCAR_EINVAL the context refuses further compute calls
  *     (OSSCAR_ESTATE) until it is destroyed and re-created.  osscar_last_error() describes the failure.
- *   - Groups are equal-sized and contiguous (the three cases of Section 3; Prop. 4.2 assumes equal size).
+ *   - Groups are equal-sized and contiguous (the three cases of Section 3; Prop. 4.2 assumes equal size).  There is no
+ *     group map argument: a caller whose groups are scattered permutes the rows of W (and the columns of X) first.
+ *   - Precision.  H, G and the search state are stored in float32 (products accumulated in float64 where it matters).
+ *     Choices, kept sets, final weights and final objective follow a float64 evaluation of the same method for any H the
+ *     inverse converges on.  Quantities tracked through many updates (the objective trace of a search) follow it to about
+ *     1e-5 relative while the diagonally scaled H restricted to the kept rows has a condition number below about 1e4; above
+ *     that the float32 rounding of H alone moves them by up to 6e-8 * cond, and refresh_every (a rebuild from H and G every so
+ *     many swaps) bounds the drift.
  *   - Calls on one context must not overlap; contexts sharing a workspace must not be used concurrently.
  */
 #ifndef OSSCAR_H
@@ -218,17 +226,38 @@ osscar_status osscar_get_scalars(osscar_ctx* ctx, double* lambda_host, double* c
  * delayed-update search [5] mean duration of the kernel with the acceptance test and u = ZT [y1 y2] (it also makes a pass
  * over Z for a pivot whose products were not computed ahead), [7] of all kernels of that iteration from there on.
  * [8] the product G = H W inside finalize (one GEMM launch, or the three bf16 products and their repacking when W is
- * bf16).  [9] the product V = P H_{K,Kc} of the last state build (one GEMM launch).  [10] the lower-triangle product
- * P (I - H_KK P) of the last Newton-Schulz step (one launch of the float32-accumulating GEMM).  [11] not a time: max |I - H_KK P| of the sweep inverse before that
- * step, a measure of the conditioning of H_KK.
- * out_host: 12 doubles. */
+ * bf16).  [9] the residual I - H_KK P of the last Newton-Schulz step (one launch of the float64-accumulating GEMM, 2 kr^3
+ * flops).  [10] the lower-triangle product P (I - H_KK P) of that step (three bf16 matrix-core products with their
+ * repacking, or one launch of the float32-accumulating GEMM when kr or m is not a multiple of 8).  [11] not a time: max |I - H_KK P| of the sweep inverse before that step, a
+ * measure of the conditioning of H_KK.  [12] the candidate-side products V, S, R of the last state build together.
+ * [13] mean duration of one launch of the bf16 Gram kernel (one launch per 16384 calibration rows) in the last
+ * osscar_gram call that added rows on that path before the last finalize, [14] the number of launches averaged, [15] the rows
+ * that call added.  out_host: 16 doubles. */
 osscar_status osscar_get_timers(osscar_ctx* ctx, double* out_host);
+
+/* Diagnostics of the last osscar_local_search call on the delayed-update path (all zero otherwise), 8 values:
+ * [0] flushes (the pending low-rank correction applied to the stored state by matrix products), [1] how many of them the
+ * kernels asked for by stopping early (a selected group was still pending, or the spare slots for products not computed
+ * ahead ran out), [2] pivots whose products with Z had not been computed ahead (each costs one pass over Z), [3] iterations
+ * run; [4..7] reserved (zero).  out_host: 8 int64. */
+osscar_status osscar_get_counters(osscar_ctx* ctx, int64_t* out_host);
+
+/* Diagnostic log of the library's general matrix-product launches (all contexts of the process; not thread-safe).
+ * osscar_debug_gemm_log(1) clears the log and starts recording: every launch is bracketed by two events on its stream.
+ * osscar_debug_gemm_log(0) stops and clears.  osscar_debug_gemm_log_read waits for the recorded launches and writes up to
+ * `capacity` rows of five float64 {M, N, K, kind, milliseconds} (kind: 1 = float32 accumulation, + 2 = float64 output,
+ * + 4 = lower-triangle tiles only, + 8 = second operand transposed) to out_host; returns the number of rows, -1 on a bad
+ * argument.  At most 16384 launches are kept. */
+osscar_status osscar_debug_gemm_log(int32_t enable);
+int32_t osscar_debug_gemm_log_read(double* out_host, int32_t capacity);
 
 /* Host-only inspection of the Gram kernel's tile schedule (no device is touched): writes up to `capacity` (row, column)
  * pairs of 128 x 128 tiles, in workgroup order, to out_host (2 ints each; (-1, -1) = padding) and returns the length of
  * the schedule, or -1 for a bad d1.  Workgroup i runs on XCD i % 8. */
 int32_t osscar_debug_tile_schedule(int64_t d1, int32_t* out_host, int32_t capacity);
 
+/* Description of the last failure: of a context, or (ctx == NULL) of the last failed call on this host thread that takes
+ * no context. */
 const char* osscar_last_error(const osscar_ctx* ctx);
 
 #ifdef __cplusplus

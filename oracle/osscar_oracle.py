@@ -302,6 +302,8 @@ class SwapRecord:
     deficit_add: float  # (max add - add[j_in]) / |max add|
     accepted: bool
     obj_after: float
+    rem_all: Optional[np.ndarray] = None   # with keep_scores: every removal score at the state the iteration started from
+    add_all: Optional[np.ndarray] = None   # and every addition score (indexed by group id, +-inf where not applicable)
 
 
 @dataclasses.dataclass
@@ -340,7 +342,8 @@ def swap_delta(st: State, H: np.ndarray, G: np.ndarray, g: int, j: int, q: int):
 
 def local_search(H: np.ndarray, G: np.ndarray, c0: float, groups0: Sequence[int], p: int, q: int,
                  max_swaps: int, rel_tol: float = 0.0, always_accept: bool = False,
-                 follow: Optional[Sequence[Tuple[int, int]]] = None, exact_in: bool = False) -> SearchResult:
+                 follow: Optional[Sequence[Tuple[int, int]]] = None, exact_in: bool = False,
+                 start: Optional[State] = None, keep_scores: bool = False) -> SearchResult:
     """Swap search from the kept set groups0.
 
     exact_in: a stronger rule for the entering group than the separable scores of eq. (impact): with the leaving
@@ -351,8 +354,14 @@ def local_search(H: np.ndarray, G: np.ndarray, c0: float, groups0: Sequence[int]
     follow: optional list of (g_out, j_in) pairs to apply instead of the oracle's own selection (used to
     validate another implementation's trajectory step by step: the record then holds how far each forced
     choice was from the oracle's best, and the oracle's exact delta for it).  With follow, the loop runs
-    len(follow) iterations and applies every pair."""
-    st = init_state(H, G, sorted(groups0), q)
+    len(follow) iterations and applies every pair.
+
+    start: optional State of groups0 that the caller already holds (what init_state(H, G, sorted(groups0), q) returns);
+    saves building it again, changes nothing else.  keep_scores: every record also keeps the two score arrays of its
+    iteration."""
+    if start is not None and list(start.groups) != sorted(groups0):
+        raise ValueError("start must be the state of sorted(groups0)")
+    st = start.copy() if start is not None else init_state(H, G, sorted(groups0), q)
     obj0 = c0 + 2.0 * st.f
     trace: List[SwapRecord] = []
     accepted = 0
@@ -382,6 +391,8 @@ def local_search(H: np.ndarray, G: np.ndarray, c0: float, groups0: Sequence[int]
         rec = SwapRecord(g, j, float(rem[g]), float(add[j]), float(delta), _gap_low(rem), _gap_high(add),
                          float((rem[g] - rmin) / max(abs(rmin), _TINY)),
                          float((amax - add[j]) / max(abs(amax), _TINY)), ok, obj)
+        if keep_scores:
+            rec.rem_all, rec.add_all = rem, add
         if not ok:
             trace.append(rec)
             break

@@ -21,7 +21,9 @@ _STATUS = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "ENOTPD", 4: "EHIP", 5: "ESTATE
 EXPORTED_SYMBOLS = ["osscar_workspace_bytes", "osscar_create", "osscar_destroy", "osscar_gram", "osscar_gram_target", "osscar_gram_conv",
                     "osscar_set_quadratic",
                     "osscar_init_support", "osscar_init_greedy", "osscar_local_search", "osscar_block_search", "osscar_apply_swap", "osscar_backsolve",
-                    "osscar_get_tensor", "osscar_get_scalars", "osscar_get_timers", "osscar_debug_tile_schedule", "osscar_last_error"]
+                    "osscar_get_tensor", "osscar_get_scalars", "osscar_get_timers", "osscar_get_counters", "osscar_debug_tile_schedule",
+                    "osscar_debug_gemm_log", "osscar_debug_gemm_log_read",
+                    "osscar_last_error"]
 
 
 class OsscarError(RuntimeError):
@@ -77,12 +79,16 @@ def load_library():
     lib.osscar_get_tensor.argtypes = [vp, C.c_int, vp, C.c_size_t]
     lib.osscar_get_scalars.argtypes = [vp, C.POINTER(dbl), C.POINTER(dbl)]
     lib.osscar_get_timers.argtypes = [vp, C.POINTER(dbl)]
+    lib.osscar_get_counters.argtypes = [vp, C.POINTER(i64)]
+    lib.osscar_debug_gemm_log.argtypes = [i32]
+    lib.osscar_debug_gemm_log_read.restype = C.c_int32
+    lib.osscar_debug_gemm_log_read.argtypes = [C.POINTER(dbl), i32]
     lib.osscar_debug_tile_schedule.restype = C.c_int32
     lib.osscar_debug_tile_schedule.argtypes = [i64, C.POINTER(i32), i32]
     lib.osscar_last_error.restype = C.c_char_p
     lib.osscar_last_error.argtypes = [vp]
     for name in EXPORTED_SYMBOLS:
-        if name not in ("osscar_workspace_bytes", "osscar_last_error", "osscar_debug_tile_schedule"):
+        if name not in ("osscar_workspace_bytes", "osscar_last_error", "osscar_debug_tile_schedule", "osscar_debug_gemm_log_read"):
             getattr(lib, name).restype = C.c_int
     _LIB = lib
     return lib
@@ -277,6 +283,23 @@ class Solver:
         return lam.value, c0.value
 
     def osscar_get_timers(self):
-        arr = (C.c_double * 12)()
+        arr = (C.c_double * 16)()
         self._check(self.lib.osscar_get_timers(self.ctx, arr))
         return list(arr)
+
+    def osscar_get_counters(self):
+        arr = (C.c_int64 * 8)()
+        self._check(self.lib.osscar_get_counters(self.ctx, arr))
+        return dict(flushes=arr[0], pauses=arr[1], lookahead_misses=arr[2], iters=arr[3])
+
+
+def gemm_log(enable: bool):
+    """Switches the library's log of its matrix-product launches on (cleared first) or off."""
+    load_library().osscar_debug_gemm_log(1 if enable else 0)
+
+
+def gemm_log_read(capacity: int = 16384) -> np.ndarray:
+    """Rows of (M, N, K, kind, ms) for every matrix-product launch since the log was switched on."""
+    buf = np.zeros((capacity, 5), dtype=np.float64)
+    n = load_library().osscar_debug_gemm_log_read(buf.ctypes.data_as(C.POINTER(C.c_double)), capacity)
+    return buf[:max(n, 0)].copy()

@@ -25,7 +25,16 @@ size_t gram_stage_bytes(int64_t d1) { return (size_t)std::max<int64_t>(d1 * XT_R
 constexpr int EV_SAMPLES = 64;
 
 size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+// buffers of the two corrections that run on the bf16 matrix cores: packed pieces of P and of the residual (a x a for the
+// inverse, a x m for the weights), and the float64 accumulator of the result (kept rows a, m columns)
+size_t split_acc_elems(size_t a, size_t b, size_t m) { (void)b; return std::max(a * a, a * m); }
+size_t split_x_cols(size_t a, size_t b, size_t m) { (void)b; return std::max(a, m); }
+size_t split_bytes(size_t a, size_t b, size_t m) {
+  return align_up(split_pack_bytes(a, a)) + align_up(split_pack_bytes(a, split_x_cols(a, b, m))) + align_up(split_acc_elems(a, b, m) * 8);
+}
 size_t gram_tile_entries(int64_t d1) { size_t t = (size_t)(d1 + 127) / 128; return 8 * (t * t / 2 + t + 8); }
+// room for any tile list of the state build: shapes up to d1 x max(d1, m), rectangular or lower triangle
+size_t state_tile_entries(int64_t d1, int64_t m) { return std::max(rect_tile_entries(d1, std::max(d1, m)), gram_tile_entries(d1)); }
 
 struct Carve {
   char* base; size_t off;
@@ -76,6 +85,9 @@ int grid_for(int64_t n) { int64_t b = (n + 1023) / 1024; return (int)std::min<in
 
 }  // namespace
 
+static thread_local std::string g_contextless_error = "no error recorded";
+namespace osscar { void set_contextless_error(const char* msg) { g_contextless_error = msg ? msg : ""; } }
+
 struct osscar_ctx {
   osscar_desc desc;
   hipStream_t stream;
@@ -86,15 +98,20 @@ struct osscar_ctx {
 
   // persistent device arrays
   float *H, *G, *N, *Z;
-  double *norms2, *score, *gram, *dblk, *small, *scal, *partial;
+  double *norms2, *score, *gram, *dblk, *small, *scal, *partial, *dpart;
   double *cross, *xgram, *xdblk, *xscore;   // exact entering rule
   int32_t *kept, *rowsK, *rowsC, *notpd;
   float *C1, *C2, *Cblk, *rZ1, *rZ2;
   SearchCtrl* ctrl;
   int32_t *trace_out, *trace_in; float* trace_gap; double* trace_obj;
   int32_t *g_pick, *g_removed; float* g_gap;   // nested schedule from the dense layer
-  float* Wdense = nullptr;       // from_dense contexts: float32 copy of W kept from finalize (the dense layer's exact weights)
-  bool have_Wdense = false;
+  int2 *tiles_sym, *tiles_rect;                // tile schedules of the bf16 matrix-core products (uploaded once at create)
+  size_t n_tiles_sym = 0, n_tiles_rect = 0;
+  int2* tiles_state;                           // two schedules of the corrections' products (shapes follow the kept count)
+  std::vector<int2> tl_host[2];                // their host copies stay alive while the copies to the device are in flight
+  int64_t counters[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  float* Wdense = nullptr;       // float32 copy of W kept from finalize: the dense layer's exact weights (nested schedule), and
+  bool have_Wdense = false;      // the pruned rows' weights for the objective of a kept set (build_state)
   LazyPtrs lazy;
   // phase-shared scratch
   char* scratch; size_t scratch_bytes;
@@ -104,9 +121,11 @@ struct osscar_ctx {
   bool dense_is_exact = true;    // the dense layer has objective 0 (false for a target output or a caller-supplied quadratic form)
   std::vector<double> norms_host;
   std::vector<int32_t> kept_host;
-  double timers[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  double timers[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   hipEvent_t ev_a = nullptr, ev_b = nullptr;
   hipEvent_t ev_s[EV_SAMPLES][3];
+  hipEvent_t ev_g[2 * EV_SAMPLES];   // pairs around the launches of the Gram kernel of the last chunk call
+  int ev_g_used = 0; int64_t ev_g_rows = 0;
   SideStream side;   // the flush of the delayed-update search overlaps two of its products
   bool ev_ok = false;
 };
@@ -137,6 +156,7 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
   double* xscore = cv.take<double>(p);
   double* scal = cv.take<double>(1024);
   double* partial = cv.take<double>(2048);
+  double* dpart = cv.take<double>((m + 15) / 16 + 64);
   int32_t* kept = cv.take<int32_t>(p);
   int32_t* rowsK = cv.take<int32_t>(d1);
   int32_t* rowsC = cv.take<int32_t>(d1);
@@ -151,10 +171,13 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
   int32_t* trace_in = cv.take<int32_t>(ms);
   float* trace_gap = cv.take<float>(2 * ms);
   double* trace_obj = cv.take<double>(ms);
-  int32_t* g_pick = cv.take<int32_t>(64);
+  int32_t* g_pick = cv.take<int32_t>(128);      // 64 leaving + 64 entering picks of a block move
   int32_t* g_removed = cv.take<int32_t>(p);
   float* g_gap = cv.take<float>(p);
-  float* Wdense = ds.from_dense ? cv.take<float>(d1 * m) : nullptr;
+  float* Wdense = cv.take<float>(d1 * m);
+  int2* tiles_sym = cv.take<int2>(gram_tile_entries(d1));
+  int2* tiles_rect = cv.take<int2>(rect_tile_entries(d1, m));
+  int2* tiles_state = cv.take<int2>(2 * state_tile_entries(d1, m));
   LazyPtrs L{};
   if (q == 1) {
     const int64_t TM = LAZY_TM;
@@ -167,6 +190,7 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
     L.part = cv.take<double>(((m + 63) / 64) * 5); L.ls = cv.take<double>(16);
     L.sel = cv.take<SelRec>((d1 + 31) / 32);
     L.GbT = cv.take<double>((int64_t)(LAZY_NC + LAZY_NS) * d1); L.Zc = cv.take<float>((int64_t)LAZY_NC * m);
+    L.ZcP = cv.take<char>((int64_t)LAZY_NC * ((m + 31) / 32 * 32) * 6);
     L.cslot = cv.take<int32_t>(d1); L.cand = cv.take<int32_t>(LAZY_NC + LAZY_NS); L.tslot = cv.take<int32_t>(LAZY_TM);
     L.misc = cv.take<int32_t>(8); L.lkey = cv.take<double>(2 * 64 * 32); L.lidx = cv.take<int32_t>(2 * 64 * 32);
     L.bB = cv.take<double>(TM * LAZY_BT); L.bX = cv.take<double>(TM * LAZY_BT); L.bU = cv.take<double>(4 * TM * LAZY_BT);
@@ -175,13 +199,11 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
     L.bG = cv.take<int32_t>(LAZY_BT);
   }
   // scratch: the larger of the Gram phase and the init / refresh / backsolve phase
-  size_t gram_phase = align_up((size_t)d1 * d1 * 8) + align_up((size_t)d1 * m * 4) + align_up(gram_stage_bytes(d1)) +
-                      align_up(gram_tile_entries(d1) * 8);
-  if (ds.target_output)
-    gram_phase += align_up((size_t)d1 * m * 8) + align_up(target_stage_bytes(m)) + align_up(rect_tile_entries(d1, m) * 8);
+  size_t gram_phase = align_up((size_t)d1 * d1 * 8) + align_up((size_t)d1 * m * 4) + align_up(gram_stage_bytes(d1));
+  if (ds.target_output) gram_phase += align_up((size_t)d1 * m * 8) + align_up(target_stage_bytes(m));
   auto init_bytes = [&](size_t a, size_t b) {   // kept rows a, candidate rows b
     return 4 * align_up(a * a * 4) + 3 * align_up(a * b * 4) + align_up(b * b * 4) + 4 * align_up(a * m * 4) + align_up(b * m * 4) +
-           3 * align_up(a * INV_NB * 4) + 4096;
+           3 * align_up(a * INV_NB * 4) + split_bytes(a, b, m) + 4096;
   };
   size_t init_phase = init_bytes(kr, cr);
   if (ds.from_dense) {   // the nested schedule visits every kept-row count from d1 down to kr
@@ -193,10 +215,11 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
   if (c) {
     c->H = H; c->G = G; c->N = N; c->Z = Z; c->norms2 = norms2; c->score = score; c->gram = gram; c->dblk = dblk;
     c->cross = cross; c->xgram = xgram; c->xdblk = xdblk; c->xscore = xscore;
-    c->small = small; c->scal = scal; c->partial = partial; c->kept = kept; c->rowsK = rowsK; c->rowsC = rowsC;
+    c->small = small; c->scal = scal; c->partial = partial; c->dpart = dpart; c->kept = kept; c->rowsK = rowsK; c->rowsC = rowsC;
     c->notpd = notpd; c->C1 = C1; c->C2 = C2; c->Cblk = Cblk; c->rZ1 = rZ1; c->rZ2 = rZ2; c->ctrl = ctrl;
     c->trace_out = trace_out; c->trace_in = trace_in; c->trace_gap = trace_gap; c->trace_obj = trace_obj;
     c->g_pick = g_pick; c->g_removed = g_removed; c->g_gap = g_gap; c->Wdense = Wdense;
+    c->tiles_sym = tiles_sym; c->tiles_rect = tiles_rect; c->tiles_state = tiles_state;
     c->scratch = scratch; c->scratch_bytes = scratch_bytes; c->lazy = L;
   }
   Layout lay; lay.total = cv.off; lay.scratch_bytes = scratch_bytes;
@@ -232,7 +255,7 @@ TabPtrs ptrs(const osscar_ctx* c) {
   TabPtrs t{};
   t.N = c->N; t.Z = c->Z; t.kept = c->kept; t.score = c->score; t.gram = c->gram; t.dblk = c->dblk;
   t.C1 = c->C1; t.C2 = c->C2; t.C1D = c->Cblk; t.C2D = c->Cblk + (int64_t)c->d1 * c->q;
-  t.rZ1 = c->rZ1; t.rZ2 = c->rZ2; t.small = c->small; t.ctrl = c->ctrl;
+  t.rZ1 = c->rZ1; t.rZ2 = c->rZ2; t.small = c->small; t.dpart = c->dpart; t.ctrl = c->ctrl;
   t.cross = c->cross; t.xgram = c->xgram; t.xdblk = c->xdblk; t.xscore = c->xscore;
   t.trace_out = c->trace_out; t.trace_in = c->trace_in; t.trace_gap = c->trace_gap; t.trace_obj = c->trace_obj;
   return t;
@@ -263,7 +286,47 @@ osscar_status upload_rows(osscar_ctx* c) {
 
 // P = (H_KK)^-1 (full, symmetric) and B = P G_K (with one float64-residual refinement step if P is not yet exact), for the rows in
 // c->rowsK.  Buffers come from the scratch region: HKK (kept), P, T1, T2 (kr x kr each), GK, B (kr x m), T3, T4.
-struct InvBufs { float *HKK, *P, *T1, *T2, *GK, *B, *T3, *T4, *panels; };
+// sp != nullptr: the two small corrections (P (I - H_KK P) of the inverse, P (G_K - H_KK B) of the weights) run on the bf16
+// matrix cores through three-piece splits.  The products that define the state -- B = P G_K, V, S, R -- do not: with
+// float32 sums inside the matrix cores they came out 3e-5 (B, V) and 1e-3 (R) away from the float64-accumulated
+// results on the 28672-row layer, whose H has large entries of one sign that cancel in these products.
+struct SplitBufs { void *packP, *packX; double* acc; size_t capP, capX, cap_acc; };   // capacities in bytes / elements
+struct InvBufs { float *HKK, *P, *T1, *T2, *GK, *B, *T3, *T4, *panels; const SplitBufs* sp = nullptr; };
+
+// Are the shapes fit for the packed bf16 products (8-element packets)?
+bool split_ok(const osscar_ctx* c) { return c->kr % 8 == 0 && c->m % 8 == 0; }
+
+// Tile schedule `slot` of the state build for an M x N result (lower: the lower triangle of a square result): built on the
+// host, copied behind the stream's earlier work.
+struct TileRef { const int2* dev; size_t entries; int ntiles; };
+osscar_status stage_tiles(osscar_ctx* c, int slot, int M, int N, bool lower, TileRef* out) {
+  std::vector<int2>& v = c->tl_host[slot];
+  if (lower) gram_tile_list_host(M, v); else rect_tile_list_host(M, N, v);
+  const size_t cap = state_tile_entries(c->d1, c->m);
+  if (v.size() > cap) return fail(c, OSSCAR_ENOMEM, "internal: tile schedule of a %d x %d product exceeds its buffer", M, N);
+  int2* dev = c->tiles_state + (size_t)slot * cap;
+  HIPCHK(c, hipMemcpyAsync(dev, v.data(), v.size() * sizeof(int2), hipMemcpyHostToDevice, c->stream));
+  const int tm = (M + 127) / 128, tn = (N + 127) / 128;
+  out->dev = dev; out->entries = v.size(); out->ntiles = lower ? tm * (tm + 1) / 2 : tm * tn;
+  return OSSCAR_OK;
+}
+
+// the three bf16 pieces of A (K x cols, contraction along the rows) into one of the pack buffers, capacity checked
+osscar_status pack_into(osscar_ctx* c, const SplitBufs& sp, void* pack, const float* A, int64_t lda, int K, int cols) {
+  const size_t cap = pack == sp.packP ? sp.capP : pack == sp.packX ? sp.capX : 0;
+  if (split_pack_bytes(K, cols) > cap) return fail(c, OSSCAR_ENOMEM, "internal: packed operand %d x %d exceeds its buffer", K, cols);
+  HIPCHK(c, launch_pack_pieces(A, lda, K, cols, pack, c->stream));
+  return OSSCAR_OK;
+}
+
+// C = beta Cin + alpha A^T B from packed pieces (see gram.hip: launch_split_product)
+osscar_status split_gemm(osscar_ctx* c, const SplitBufs& sp, const void* packA, int M, const void* packB, int N, int K, int nprod,
+                         const TileRef& t, const float* Cin, int64_t ldcin, float* C, int64_t ldc, double alpha, double beta) {
+  if ((size_t)M * N > sp.cap_acc) return fail(c, OSSCAR_ENOMEM, "internal: %d x %d product exceeds the accumulator", M, N);
+  HIPCHK(c, launch_split_product(packA, M, packB, N, K, nprod, sp.acc, t.dev, t.entries, t.ntiles, c->stream));
+  HIPCHK(c, launch_split_epilogue(sp.acc, M, N, Cin, ldcin, C, ldc, alpha, beta, c->stream));
+  return OSSCAR_OK;
+}
 
 // B_known (optional, kr x m): the weights are known exactly (dense layer: B = W), only G_K is gathered beside them.
 osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b, const float* B_known = nullptr) {
@@ -274,14 +337,30 @@ osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b, const float* 
   HIPCHK(c, hipMemsetAsync(c->notpd, 0, 64 * 4, s));
   HIPCHK(c, spd_inverse_inplace(b.P, kr, b.panels, b.panels + (int64_t)kr * INV_NB, c->small, c->notpd, s));
   // Newton-Schulz: P <- P + P (I - H_KK P), residual accumulated in float64
+  const SplitBufs* sp = b.sp;
+  osscar_status st = OSSCAR_OK;
+  TileRef t_low{}, t_b{};
+  if (sp) {
+    if ((st = stage_tiles(c, 0, kr, kr, true, &t_low)) != OSSCAR_OK) return st;
+    if ((st = stage_tiles(c, 1, kr, m, false, &t_b)) != OSSCAR_OK) return st;
+  }
   double last_resid = 1.0;
   for (int step = 0; step < 3; step++) {
+    HIPCHK(c, hipEventRecord(c->ev_s[2][0], s));
     HIPCHK(c, gemm(s, kr, kr, kr, b.HKK, kr, b.P, kr, nullptr, 0, b.T1, kr, -1.0, 0.0, 1.0));
+    HIPCHK(c, hipEventRecord(c->ev_s[2][1], s));
     HIPCHK(c, launch_absmax(b.T1, (int64_t)kr * kr, c->partial, s));
-    // P + P (I - H P) is symmetric up to rounding: compute its lower triangle and mirror it
-    // (the correction P (I - H P) is about 1e-5 of P: float32 accumulation of it is far below P's own rounding)
+    // P + P (I - H P) is symmetric up to rounding: compute its lower triangle and mirror it.  The correction P (I - H P) is
+    // about 1e-5 of P, so it needs only a few digits: float32 accumulation, or the three leading products of the bf16
+    // pieces (2^-16 of the correction), are far below P's own rounding.
     HIPCHK(c, hipEventRecord(c->ev_s[1][0], s));
-    HIPCHK(c, gemm(s, kr, kr, kr, b.P, kr, b.T1, kr, b.P, kr, b.T2, kr, 1.0, 1.0, 0.0, 1, 0, 1));
+    if (sp) {
+      if ((st = pack_into(c, *sp, sp->packP, b.P, kr, kr, kr)) != OSSCAR_OK) return st;
+      if ((st = pack_into(c, *sp, sp->packX, b.T1, kr, kr, kr)) != OSSCAR_OK) return st;
+      if ((st = split_gemm(c, *sp, sp->packP, kr, sp->packX, kr, kr, 3, t_low, b.P, kr, b.T2, kr, 1.0, 1.0)) != OSSCAR_OK) return st;
+    } else {
+      HIPCHK(c, gemm(s, kr, kr, kr, b.P, kr, b.T1, kr, b.P, kr, b.T2, kr, 1.0, 1.0, 0.0, 1, 0, 1));
+    }
     HIPCHK(c, hipEventRecord(c->ev_s[1][1], s));
     hipLaunchKernelGGL(mirror_from_lower_kernel, dim3(grid_for((int64_t)kr * kr)), dim3(256), 0, s, b.T2, b.P, kr);
     double part[256]; int32_t bad = 0;
@@ -289,13 +368,18 @@ osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b, const float* 
     HIPCHK(c, hipMemcpyAsync(&bad, c->notpd, 4, hipMemcpyDeviceToHost, s));
     HIPCHK(c, hipStreamSynchronize(s));
     { float ms = 0; hipEventElapsedTime(&ms, c->ev_s[1][0], c->ev_s[1][1]); c->timers[10] = ms; }
-    double resid = 0; for (double v : part) resid = std::max(resid, v);
+    { float ms = 0; hipEventElapsedTime(&ms, c->ev_s[2][0], c->ev_s[2][1]); c->timers[9] = ms; }
+    double resid = 0;
+    for (double v : part) if (v > resid || v != v) resid = v;      // a NaN anywhere in I - H P makes resid NaN
     if (bad || !(resid < 0.9))
       return fail(c, OSSCAR_ENOTPD, "H restricted to the kept rows is not positive definite to working precision "
                                      "(pivot flag %d, |I - H P|_max = %.3g)", bad, resid);
     last_resid = resid;
     c->timers[11] = resid;
-    if (resid < 1e-3) break;     // one more step squares it below float32 resolution
+    if (resid < 1e-3) break;     // the step just taken squares it below float32 resolution
+    if (step == 2)                // three steps and still above: the last one leaves about resid^2, not good enough to call P exact
+      return fail(c, OSSCAR_ENOTPD, "the inverse of H on the kept rows did not converge (|I - H P|_max = %.3g after three "
+                                     "Newton-Schulz steps): H_KK is too ill-conditioned for float32 storage", resid);
   }
 
   // B = P G_K, then B += P (G_K - H_KK B)
@@ -308,14 +392,30 @@ osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b, const float* 
   // still costs B = P G_K about 6e-8 times the cancellation in the product, which grows with the conditioning of H_KK; the
   // residual before the step is a cheap measure of it (2e-5 on the OPT-shaped benchmark layers, 1e-4 and more on layers
   // where B = P G_K alone left the objective off by 1e-3), and above 4e-5 B is corrected against the float64 residual.
-  if (last_resid < 4e-5) {
-    HIPCHK(c, gemm(s, kr, m, kr, b.P, kr, b.GK, m, nullptr, 0, b.B, m, 1.0, 0.0));
-    return OSSCAR_OK;
+  const bool correct = !(last_resid < 4e-5);
+  float* B0 = correct ? b.T3 : b.B;
+  HIPCHK(c, gemm(s, kr, m, kr, b.P, kr, b.GK, m, nullptr, 0, B0, m, 1.0, 0.0));
+  if (!correct) return OSSCAR_OK;
+  HIPCHK(c, gemm(s, kr, m, kr, b.HKK, kr, b.T3, m, b.GK, m, b.T4, m, -1.0, 1.0));      // the residual: float64 accumulation
+  if (sp) {
+    if ((st = pack_into(c, *sp, sp->packP, b.P, kr, kr, kr)) != OSSCAR_OK) return st;      // the refined inverse
+    if ((st = pack_into(c, *sp, sp->packX, b.T4, m, kr, m)) != OSSCAR_OK) return st;
+    if ((st = split_gemm(c, *sp, sp->packP, kr, sp->packX, m, kr, 3, t_b, b.T3, m, b.B, m, 1.0, 1.0)) != OSSCAR_OK) return st;
+  } else {
+    HIPCHK(c, gemm(s, kr, m, kr, b.P, kr, b.T4, m, b.T3, m, b.B, m, 1.0, 1.0));
   }
-  HIPCHK(c, gemm(s, kr, m, kr, b.P, kr, b.GK, m, nullptr, 0, b.T3, m, 1.0, 0.0));
-  HIPCHK(c, gemm(s, kr, m, kr, b.HKK, kr, b.T3, m, b.GK, m, b.T4, m, -1.0, 1.0));
-  HIPCHK(c, gemm(s, kr, m, kr, b.P, kr, b.T4, m, b.T3, m, b.B, m, 1.0, 1.0));
   return OSSCAR_OK;
+}
+
+SplitBufs carve_split(osscar_ctx* c, Carve& cv) {
+  const size_t a = c->kr, bb = c->cr, m = c->m;
+  SplitBufs sp;
+  sp.capP = split_pack_bytes(a, a); sp.capX = split_pack_bytes(a, split_x_cols(a, bb, m));
+  sp.cap_acc = split_acc_elems(a, bb, m);
+  sp.packP = cv.take<char>(sp.capP);
+  sp.packX = cv.take<char>(sp.capX);
+  sp.acc = cv.take<double>(sp.cap_acc);
+  return sp;
 }
 
 InvBufs carve_inv(osscar_ctx* c, Carve& cv) {
@@ -351,19 +451,22 @@ osscar_status build_state(osscar_ctx* c, double* obj_out, const float* B_known =
   float* HCK = cv.take<float>((int64_t)cr * kr);
   float* S = cv.take<float>((int64_t)cr * cr);
   float* R = cv.take<float>((int64_t)cr * m);
+  SplitBufs sp = carve_split(c, cv);
   if (cv.off > c->scratch_bytes) return fail(c, OSSCAR_ENOMEM, "internal: scratch carve-up exceeds the workspace");
+  const bool split = split_ok(c);
+  if (split) b.sp = &sp;
   st = inverse_and_weights(c, b, B_known);
   if (st != OSSCAR_OK) return st;
   if (cr > 0) {
     HIPCHK(c, launch_gather(c->H, d1, c->rowsK, kr, c->rowsC, cr, HKC, cr, s));
-    HIPCHK(c, launch_gather(c->H, d1, c->rowsC, cr, c->rowsK, kr, HCK, kr, s));
     HIPCHK(c, launch_gather(c->H, d1, c->rowsC, cr, c->rowsC, cr, S, cr, s));
     HIPCHK(c, launch_gather(c->G, m, c->rowsC, cr, nullptr, m, R, m, s));
     HIPCHK(c, hipEventRecord(c->ev_s[0][0], s));
+    HIPCHK(c, launch_gather(c->H, d1, c->rowsC, cr, c->rowsK, kr, HCK, kr, s));
     HIPCHK(c, gemm(s, kr, cr, kr, b.P, kr, HKC, cr, nullptr, 0, V, cr, 1.0, 0.0));             // V = P H_{K,Kc}
-    HIPCHK(c, hipEventRecord(c->ev_s[0][1], s));
     HIPCHK(c, gemm(s, cr, cr, kr, HCK, kr, V, cr, S, cr, S, cr, -1.0, 1.0, 0.0, 1));            // S = H_cc - H_cK V (lower)
     HIPCHK(c, gemm(s, cr, m, kr, HCK, kr, b.B, m, R, m, R, m, -1.0, 1.0));                      // R = G_c - H_cK B
+    HIPCHK(c, hipEventRecord(c->ev_s[0][1], s));
     HIPCHK(c, launch_scatter(V, cr, c->rowsK, kr, c->rowsC, cr, c->N, d1, 1.f, 0, s));
     HIPCHK(c, launch_scatter(S, cr, c->rowsC, cr, c->rowsC, cr, c->N, d1, 1.f, 1, s));
     HIPCHK(c, launch_scatter_rows(R, m, c->rowsC, cr, m, c->Z, m, 0, s));
@@ -372,9 +475,20 @@ osscar_status build_state(osscar_ctx* c, double* obj_out, const float* B_known =
   HIPCHK(c, launch_scatter_rows(b.B, m, c->rowsK, kr, m, c->Z, m, 0, s));
   HIPCHK(c, launch_refresh_scores(dims(c), ptrs(c), s));
   double obj = 0;
-  st = objective_from(c, b.GK, b.B, &obj);     // synchronises the stream
-  if (st != OSSCAR_OK) return st;
-  if (cr > 0) { float ms = 0; hipEventElapsedTime(&ms, c->ev_s[0][0], c->ev_s[0][1]); c->timers[9] = ms; }
+  if (c->have_Wdense && c->dense_is_exact) {
+    // obj(K) = c0 - <G_K, B> = <W_c, R_c> over the pruned rows c (B = W_K + V W_c, so <G_K, B> = <G_K, W_K> + <V^T G_K, W_c>).
+    // The first form subtracts two numbers of the size of c0 and inherits the float32 rounding of B at that size; the
+    // second has terms of the size of the loss itself, which matters when the kept rows carry most of Tr(W^T H W).
+    if (cr > 0) {
+      HIPCHK(c, launch_dot64_rows(c->Wdense, c->rowsC, R, cr, m, c->scal + 8, c->partial, s));
+      HIPCHK(c, hipMemcpyAsync(&obj, c->scal + 8, 8, hipMemcpyDeviceToHost, s));
+    }
+    HIPCHK(c, hipStreamSynchronize(s));
+  } else {
+    st = objective_from(c, b.GK, b.B, &obj);     // synchronises the stream
+    if (st != OSSCAR_OK) return st;
+  }
+  if (cr > 0) { float ms = 0; hipEventElapsedTime(&ms, c->ev_s[0][0], c->ev_s[0][1]); c->timers[12] = ms; }
   if (obj_out) *obj_out = obj;
   return OSSCAR_OK;
 }
@@ -422,9 +536,19 @@ osscar_status osscar_create(osscar_ctx** out, const osscar_desc* desc, void* wor
   c->d1 = (int)desc->d1; c->m = (int)desc->m; c->p = desc->p; c->q = desc->q; c->k = desc->k;
   c->kr = desc->k * desc->q; c->cr = c->d1 - c->kr;
   carve_all(*desc, workspace_dev, c);
+  {   // tile schedules of the packed matrix-core products: built and uploaded once, so that no chunk call waits for the stream
+    std::vector<int2> ts, tr;
+    gram_tile_list_host(c->d1, ts);
+    rect_tile_list_host(c->d1, c->m, tr);
+    if (ts.size() > gram_tile_entries(c->d1) || tr.size() > rect_tile_entries(c->d1, c->m)) { delete c; return OSSCAR_ENOMEM; }
+    if (hipMemcpy(c->tiles_sym, ts.data(), ts.size() * sizeof(int2), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(c->tiles_rect, tr.data(), tr.size() * sizeof(int2), hipMemcpyHostToDevice) != hipSuccess) { delete c; return OSSCAR_EHIP; }
+    c->n_tiles_sym = ts.size(); c->n_tiles_rect = tr.size();
+  }
   c->ev_ok = (hipEventCreate(&c->ev_a) == hipSuccess) && (hipEventCreate(&c->ev_b) == hipSuccess);
   for (int i = 0; i < EV_SAMPLES && c->ev_ok; i++)
     for (int j = 0; j < 3; j++) c->ev_ok = c->ev_ok && (hipEventCreate(&c->ev_s[i][j]) == hipSuccess);
+  for (int i = 0; i < 2 * EV_SAMPLES && c->ev_ok; i++) c->ev_ok = c->ev_ok && (hipEventCreate(&c->ev_g[i]) == hipSuccess);
   c->ev_ok = c->ev_ok && hipStreamCreateWithFlags(&c->side.stream, hipStreamNonBlocking) == hipSuccess &&
              hipEventCreateWithFlags(&c->side.fork, hipEventDisableTiming) == hipSuccess &&
              hipEventCreateWithFlags(&c->side.join, hipEventDisableTiming) == hipSuccess;
@@ -442,12 +566,13 @@ osscar_status osscar_destroy(osscar_ctx* c) {
   if (c->ev_a) hipEventDestroy(c->ev_a);
   if (c->ev_b) hipEventDestroy(c->ev_b);
   for (int i = 0; i < EV_SAMPLES; i++)
-    for (int j = 0; j < 3; j++) hipEventDestroy(c->ev_s[i][j]);
+    for (int j = 0; j < 3; j++) if (c->ev_s[i][j]) hipEventDestroy(c->ev_s[i][j]);
+  for (int i = 0; i < 2 * EV_SAMPLES; i++) if (c->ev_g[i]) hipEventDestroy(c->ev_g[i]);
   delete c;
   return OSSCAR_OK;
 }
 
-const char* osscar_last_error(const osscar_ctx* c) { return c ? c->err.c_str() : "null context"; }
+const char* osscar_last_error(const osscar_ctx* c) { return c ? c->err.c_str() : g_contextless_error.c_str(); }
 
 // Shared body of osscar_gram (Yc == nullptr, target == 0) and osscar_gram_target.
 static osscar_status gram_impl(osscar_ctx* c, const char* who, int target, const void* Xc, const void* Yc, int64_t n_c, int64_t ldx,
@@ -467,14 +592,10 @@ static osscar_status gram_impl(osscar_ctx* c, const char* who, int target, const
   double* H64 = cv.take<double>((int64_t)d1 * d1);
   float* Wf = cv.take<float>((int64_t)d1 * m);
   float* Xt = reinterpret_cast<float*>(cv.take<char>(gram_stage_bytes(d1)));
-  const size_t tile_entries = gram_tile_entries(d1);
-  int2* tile_buf = cv.take<int2>(tile_entries);
-  double* G64 = nullptr; float* Ys = nullptr; int2* tile_buf_y = nullptr;
-  const size_t tile_y_entries = rect_tile_entries(d1, m);
+  double* G64 = nullptr; float* Ys = nullptr;
   if (c->desc.target_output) {
     G64 = cv.take<double>((int64_t)d1 * m);
     Ys = reinterpret_cast<float*>(cv.take<char>(target_stage_bytes(m)));
-    tile_buf_y = cv.take<int2>(tile_y_entries);
   }
   if (c->phase != osscar_ctx::ACCUM) {   // first chunk of a layer
     hipLaunchKernelGGL(fill_f64_kernel, dim3(grid_for((int64_t)d1 * d1)), dim3(256), 0, s, H64, (int64_t)d1 * d1, 0.0);
@@ -491,12 +612,15 @@ static osscar_status gram_impl(osscar_ctx* c, const char* who, int target, const
     const bool bf16 = c->desc.x_dtype == OSSCAR_BF16;
     bool fast = bf16 && (d1 % 8 == 0) && (conv || ((ldx % 8 == 0) && ((reinterpret_cast<uintptr_t>(Xc) & 15) == 0)));
     if (target) fast = fast && (m % 8 == 0) && (ldy % 8 == 0) && ((reinterpret_cast<uintptr_t>(Yc) & 15) == 0);
-    if (target) HIPCHK(c, launch_sumsq(Yc, bf16, n_c, m, ldy, c->scal + 12, s));
+    if (target) HIPCHK(c, launch_sumsq(Yc, bf16, n_c, m, ldy, c->scal + 12, c->partial, s));
     if (fast) {
-      if (target) HIPCHK(c, launch_gram_packed(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, Xt, PACK_ROWS, s, Yc, ldy, m, G64,
-                                               tile_buf_y, tile_y_entries, Ys));
-      else HIPCHK(c, launch_gram_packed(Xc, n_c, ldx, d1, H64, tile_buf, tile_entries, Xt, PACK_ROWS, s, nullptr, 0, 0, nullptr,
-                                        nullptr, 0, nullptr, conv));
+      if (target) HIPCHK(c, launch_gram_packed(Xc, n_c, ldx, d1, H64, c->tiles_sym, c->n_tiles_sym, Xt, PACK_ROWS, s, Yc, ldy, m, G64,
+                                               c->tiles_rect, c->n_tiles_rect, Ys));
+      else {
+        HIPCHK(c, launch_gram_packed(Xc, n_c, ldx, d1, H64, c->tiles_sym, c->n_tiles_sym, Xt, PACK_ROWS, s, nullptr, 0, 0, nullptr,
+                                     nullptr, 0, nullptr, conv, c->ev_g, EV_SAMPLES, &c->ev_g_used));
+        c->ev_g_rows = n_c;
+      }
     } else {
       const size_t esz = bf16 ? 2 : 4;
       for (int64_t r0 = 0; r0 < n_c; r0 += XT_ROWS) {
@@ -544,20 +668,19 @@ static osscar_status gram_impl(osscar_ctx* c, const char* who, int target, const
     // just left; otherwise (or if that memory is too small) the float64-accumulating GEMM.
     const int64_t prow = std::min<int64_t>(PACK_ROWS, ((int64_t)d1 + 63) / 64 * 64);
     const size_t ph_bytes = align_up((size_t)prow * ((d1 + 127) / 128 * 128) * 2), pw_bytes = align_up((size_t)prow * ((m + 127) / 128 * 128) * 2);
-    const size_t g64_bytes = align_up((size_t)d1 * m * 8), tl_entries = rect_tile_entries(d1, m);
+    const size_t g64_bytes = align_up((size_t)d1 * m * 8);
     const bool split_ok = c->desc.w_dtype == OSSCAR_BF16 && (d1 % 8 == 0) && (m % 8 == 0) && (ldw % 8 == 0) &&
                           ((reinterpret_cast<uintptr_t>(W) & 15) == 0) &&
-                          g64_bytes + ph_bytes + pw_bytes + align_up(tl_entries * 8) <= (size_t)d1 * d1 * 8;
+                          g64_bytes + ph_bytes + pw_bytes <= (size_t)d1 * d1 * 8;
     HIPCHK(c, hipEventRecord(c->ev_s[0][0], s));
     if (split_ok) {
       char* base = reinterpret_cast<char*>(H64);
       double* Gacc = reinterpret_cast<double*>(base);
       void* pack_h = base + g64_bytes;
       void* pack_w = base + g64_bytes + ph_bytes;
-      int2* tl = reinterpret_cast<int2*>(base + g64_bytes + ph_bytes + pw_bytes);
       hipLaunchKernelGGL(fill_f64_kernel, dim3(grid_for((int64_t)d1 * m)), dim3(256), 0, s, Gacc, (int64_t)d1 * m, 0.0);
       hipLaunchKernelGGL(fill_f64_kernel, dim3(1), dim3(64), 0, s, c->scal + 13, (int64_t)1, 0.0);
-      HIPCHK(c, launch_hw_split(c->H, d1, W, ldw, m, Gacc, tl, tl_entries, pack_h, pack_w, prow, s));
+      HIPCHK(c, launch_hw_split(c->H, d1, W, ldw, m, Gacc, c->tiles_rect, c->n_tiles_rect, pack_h, pack_w, prow, s));
       HIPCHK(c, launch_finalize_G(Gacc, Wf, c->scal + 13, c->G, (int64_t)d1 * m, s));
     } else {
       HIPCHK(c, gemm(s, d1, m, d1, c->H, d1, Wf, m, nullptr, 0, c->G, m, 1.0, 0.0));
@@ -572,7 +695,7 @@ static osscar_status gram_impl(osscar_ctx* c, const char* who, int target, const
   HIPCHK(c, hipEventRecord(c->ev_b, s));
   HIPCHK(c, hipStreamSynchronize(s));
   c->have_Wdense = false;
-  if (!target && c->Wdense) {
+  if (!target) {
     HIPCHK(c, hipMemcpyAsync(c->Wdense, Wf, (size_t)d1 * m * 4, hipMemcpyDeviceToDevice, s));
     HIPCHK(c, hipStreamSynchronize(s));
     c->have_Wdense = true;
@@ -581,6 +704,15 @@ static osscar_status gram_impl(osscar_ctx* c, const char* who, int target, const
   else { float ms = 0; hipEventElapsedTime(&ms, c->ev_s[0][0], c->ev_s[0][1]); c->timers[8] = ms; }
   c->dense_is_exact = !target;
   c->timers[1] = elapsed(c);
+  {   // mean duration of the Gram kernel's launches in the last chunk call that took the matrix-core path
+    double tot = 0; int n = 0;
+    for (int i = 0; i < c->ev_g_used; i++) {
+      float ms = 0;
+      if (hipEventElapsedTime(&ms, c->ev_g[2 * i], c->ev_g[2 * i + 1]) == hipSuccess) { tot += ms; n++; }
+    }
+    c->timers[13] = n ? tot / n : 0; c->timers[14] = n; c->timers[15] = (double)c->ev_g_rows;
+    c->ev_g_used = 0;
+  }
   for (auto& v : c->norms_host) v = std::sqrt(v);
   c->phase = osscar_ctx::FINAL;
   return OSSCAR_OK;
@@ -675,13 +807,16 @@ osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_e
   if (t_hat < 1 || t_hat > 64 || refresh_every < 0) return fail(c, OSSCAR_EINVAL, "osscar_init_greedy: t_hat %d outside [1, 64] or refresh_every < 0", t_hat);
   hipStream_t s = c->stream;
   const int q = c->q, k = c->k, p = c->p;
+  // the loop below visits every kept-row count from d1 down to k q; whatever way this call ends, the context's counts
+  // are those of the description again
+  struct RestoreCounts { osscar_ctx* c; int kr, cr; ~RestoreCounts() { c->kr = kr; c->cr = cr; } } restore{c, k * q, c->d1 - k * q};
   HIPCHK(c, hipEventRecord(c->ev_a, s));
   // dense layer: every group kept
   c->kept_host.assign(p, 1);
   c->kr = c->d1; c->cr = 0;
   double obj = 0;
   st = build_state(c, &obj, (c->dense_is_exact && c->have_Wdense) ? c->Wdense : nullptr);
-  if (st != OSSCAR_OK) { c->kr = k * q; c->cr = c->d1 - c->kr; return st; }
+  if (st != OSSCAR_OK) return st;
   SearchCtrl h{};
   h.obj = c->dense_is_exact ? 0.0 : obj;   // the dense layer reproduces its own output exactly; a target output it does not
   h.g_out = -1; h.g_in = -1; h.tau = 0; h.tau_inc = 0; h.pause = 0;
@@ -798,7 +933,8 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
   if (st != OSSCAR_OK) return st;
   const double obj0 = h.obj;
   h.done = (c->cr == 0) ? 1 : 0; h.iters = 0; h.accepted = 0; h.notpd = 0; h.rel_tol = rel_tol; h.g_out = h.g_in = -1;
-  h.pause = 0; h.tau = 0; h.tau_inc = 0;
+  h.pause = 0; h.tau = 0; h.tau_inc = 0; h.misses = 0;
+  for (auto& v : c->counters) v = 0;
   HIPCHK(c, hipMemcpyAsync(c->ctrl, &h, sizeof h, hipMemcpyHostToDevice, s));
   HIPCHK(c, hipStreamSynchronize(s));
   const int always = (flags & OSSCAR_SEARCH_ALWAYS_ACCEPT) ? 1 : 0;
@@ -818,7 +954,7 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
     const int la_mode = (flags & OSSCAR_SEARCH_NO_LOOKAHEAD) ? 2 : 0;
     HIPCHK(c, launch_lazy_init(d, t, L, s, la_mode));
     int since_flush = 0;
-    double flush_ms = 0; int flushes = 0;
+    double flush_ms = 0; int flushes = 0, pauses = 0;
     bool flush_open = false;                 // a flush whose events have not been read yet
     auto collect = [&]() {                   // only after the stream has been waited for
       if (!flush_open) return;
@@ -851,6 +987,7 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
         upd_n_ms += a; upd_z_ms += b; samples++;
       }
       const bool want_refresh = !h.done && refresh_every > 0 && h.accepted - since_refresh_base >= refresh_every && h.iters < max_swaps;
+      if (h.pause) pauses++;
       if (h.pause || since_flush >= FLUSH || h.done || want_refresh || h.iters >= max_swaps) {
         if (h.tau + h.tau_inc > 0 || h.pause) { st = flush(); if (st != OSSCAR_OK) return st; }
         h.pause = 0; h.tau = 0; h.tau_inc = 0;
@@ -876,7 +1013,7 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
     if (h.tau + h.tau_inc > 0) { st = flush(); if (st != OSSCAR_OK) return st; }
     if (flush_open) { HIPCHK(c, hipStreamSynchronize(s)); collect(); }
     c->timers[6] = refresh_ms + flush_ms;
-    (void)flushes;
+    c->counters[0] = flushes; c->counters[1] = pauses; c->counters[2] = h.misses; c->counters[3] = h.iters;
   } else {
   const int BATCH = 32;
   while (launched < max_swaps && !h.done) {
@@ -1060,6 +1197,10 @@ osscar_status osscar_backsolve(osscar_ctx* c, void* What, int64_t ldw_hat, int32
   if (st != OSSCAR_OK) return st;
   Carve cv(c->scratch);
   InvBufs b = carve_inv(c, cv);
+  SplitBufs sp = carve_split(c, cv);
+  if (cv.off > c->scratch_bytes) return fail(c, OSSCAR_ENOMEM, "internal: scratch carve-up exceeds the workspace");
+  const bool split = split_ok(c);
+  if (split) b.sp = &sp;
   // Refine the maintained weights instead of refactorising: B <- B + P (G_K - H_KK B) with the maintained inverse P
   // and a float64-accumulated residual.  One step shrinks the error by |I - P H_KK| (about 1e-3 after thousands of
   // swaps, so after a correction of relative size r the error left is about 1e-3 r); a second step is taken if the
@@ -1071,10 +1212,22 @@ osscar_status osscar_backsolve(osscar_ctx* c, void* What, int64_t ldw_hat, int32
     hipLaunchKernelGGL(gather_sym_kernel, dim3(grid_for((int64_t)kr * kr)), dim3(256), 0, s, c->N, (int64_t)c->d1, c->rowsK, kr,
                        c->rowsK, kr, b.P, -1.f);
     HIPCHK(c, launch_gather(c->Z, m, c->rowsK, kr, nullptr, m, b.B, m, s));
+    TileRef t_b{};
+    if (split) {
+      if ((st = stage_tiles(c, 1, kr, m, false, &t_b)) != OSSCAR_OK) return st;
+      if ((st = pack_into(c, sp, sp.packP, b.P, kr, kr, kr)) != OSSCAR_OK) return st;
+    }
     bool ok = false;
     for (int step = 0; step < 3 && !ok; step++) {
       HIPCHK(c, gemm(s, kr, m, kr, b.HKK, kr, b.B, m, b.GK, m, b.T4, m, -1.0, 1.0));      // residual
-      HIPCHK(c, gemm(s, kr, m, kr, b.P, kr, b.T4, m, nullptr, 0, b.T3, m, 1.0, 0.0, 0.0, 0, 0, 1));   // correction (small: float32 accumulation)
+      // the correction is small, a few digits of it are enough: float32 accumulation, or the three leading products of
+      // the bf16 pieces
+      if (split) {
+        if ((st = pack_into(c, sp, sp.packX, b.T4, m, kr, m)) != OSSCAR_OK) return st;
+        if ((st = split_gemm(c, sp, sp.packP, kr, sp.packX, m, kr, 3, t_b, nullptr, 0, b.T3, m, 1.0, 0.0)) != OSSCAR_OK) return st;
+      } else {
+        HIPCHK(c, gemm(s, kr, m, kr, b.P, kr, b.T4, m, nullptr, 0, b.T3, m, 1.0, 0.0, 0.0, 0, 0, 1));
+      }
       HIPCHK(c, launch_dot64(b.T3, b.T3, (int64_t)kr * m, c->scal + 9, c->partial, s));
       HIPCHK(c, launch_dot64(b.B, b.B, (int64_t)kr * m, c->scal + 10, c->partial + 1024, s));
       hipLaunchKernelGGL(add_inplace_kernel, dim3(grid_for((int64_t)kr * m)), dim3(256), 0, s, b.B, b.T3, (int64_t)kr * m);
@@ -1183,9 +1336,21 @@ int32_t osscar_debug_tile_schedule(int64_t d1, int32_t* out_host, int32_t capaci
   return gram_tile_schedule((int)((d1 + 127) / 128), out_host, capacity);
 }
 
+osscar_status osscar_debug_gemm_log(int32_t enable) { gemm_log_enable(enable); return OSSCAR_OK; }
+int32_t osscar_debug_gemm_log_read(double* out_host, int32_t capacity) {
+  if (!out_host || capacity < 0) return -1;
+  return gemm_log_read(out_host, capacity);
+}
+
+osscar_status osscar_get_counters(osscar_ctx* c, int64_t* out) {
+  if (!c || !out) return OSSCAR_EINVAL;
+  for (int i = 0; i < 8; i++) out[i] = c->counters[i];
+  return OSSCAR_OK;
+}
+
 osscar_status osscar_get_timers(osscar_ctx* c, double* out) {
   if (!c || !out) return OSSCAR_EINVAL;
-  for (int i = 0; i < 12; i++) out[i] = c->timers[i];
+  for (int i = 0; i < 16; i++) out[i] = c->timers[i];
   return OSSCAR_OK;
 }
 

@@ -14,6 +14,7 @@
 // column read consecutive LDS words.  Global loads for the next k-tile are issued before the MFMAs of
 // the current one (register double buffering).
 #include "internal.h"
+#include <vector>
 
 namespace osscar {
 
@@ -222,10 +223,7 @@ __global__ __launch_bounds__(256, 2) void gemm_f64acc_kernel(GemmArgs g, int vec
 // the delayed-update search.  Same tiling; each wave owns 64 x 64 as 2 x 2 tiles of 32 x 32.  float output only.
 typedef float f16v __attribute__((ext_vector_type(16)));
 
-// SPLITK: blockIdx.y selects a range of kper values of K; the partial product (float32 accumulation over that range only)
-// is added to the float64 C by atomics, alpha applied, Cin / beta / diag_add ignored: C must hold zeros (or the addend).
-template <bool SPLITK>
-__global__ __launch_bounds__(256, 2) void gemm_f32acc_kernel(GemmArgs g, int vecA, int vecB, int vecC, int kper) {
+__global__ __launch_bounds__(256, 2) void gemm_f32acc_kernel(GemmArgs g, int vecA, int vecB, int vecC) {
   __shared__ __attribute__((aligned(16))) float smem[2 * 2 * BK * LDT];
   float (*As)[BK][LDT] = reinterpret_cast<float (*)[BK][LDT]>(smem);
   float (*Bs)[BK][LDT] = reinterpret_cast<float (*)[BK][LDT]>(smem + 2 * BK * LDT);
@@ -246,9 +244,8 @@ __global__ __launch_bounds__(256, 2) void gemm_f32acc_kernel(GemmArgs g, int vec
     for (int j = 0; j < 2; j++)
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
-  const int kt_begin = SPLITK ? (int)blockIdx.y * (kper / BK) : 0;
-  const int kt_all = (g.K + BK - 1) / BK;
-  const int ktiles = SPLITK ? ((kt_begin + kper / BK < kt_all) ? kt_begin + kper / BK : kt_all) : kt_all;
+  const int kt_begin = 0;
+  const int ktiles = (g.K + BK - 1) / BK;
   Tile8 ra, rb;
   auto gload = [&](int kt) {
     int k0 = kt * BK;
@@ -293,21 +290,6 @@ __global__ __launch_bounds__(256, 2) void gemm_f32acc_kernel(GemmArgs g, int vec
     __syncthreads();
   }
   // epilogue: lane holds rows (r/4)*8 + (lane/32)*4 + r%4, column lane%32 of each 32 x 32 tile; staged per 32 rows
-  if (SPLITK) {
-    double* Cd = reinterpret_cast<double*>(g.C);
-#pragma unroll
-    for (int i = 0; i < 2; i++)
-#pragma unroll
-      for (int j = 0; j < 2; j++) {
-        const int col = n0 + wn * 64 + j * 32 + (lane & 31);
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-          const int row = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-          if (row < g.M && col < g.N) unsafeAtomicAdd(Cd + (int64_t)row * g.ldc + col, g.alpha * (double)acc[i][j][r]);
-        }
-      }
-    return;
-  }
   float* C = reinterpret_cast<float*>(g.C);
   const float* Cin = g.Cin;
   const bool use_cin = (Cin != nullptr && g.beta != 0.0);
@@ -380,19 +362,53 @@ __global__ __launch_bounds__(256, 2) void gemm_f32acc_kernel(GemmArgs g, int vec
   (void)st;
 }
 
+// Optional log of every launch (shape, variant, duration by a pair of events on the launch's stream): a diagnostic that
+// bench.py switches on for one untimed layer to report the time-weighted matrix-core rate over all launches.
+namespace {
+struct GemmLogEntry { int M, N, K, kind; hipEvent_t a, b; };
+std::vector<GemmLogEntry> g_log;
+bool g_log_on = false;
+constexpr size_t GEMM_LOG_CAP = 16384;
+}  // namespace
+void gemm_log_enable(int on) {
+  for (auto& e : g_log) { hipEventDestroy(e.a); hipEventDestroy(e.b); }
+  g_log.clear();
+  g_log_on = on != 0;
+}
+int gemm_log_read(double* out, int capacity) {
+  int n = 0;
+  for (auto& e : g_log) {
+    if (n >= capacity) break;
+    float ms = 0.f;
+    if (hipEventSynchronize(e.b) != hipSuccess || hipEventElapsedTime(&ms, e.a, e.b) != hipSuccess) ms = -1.f;
+    double* r = out + 5 * (size_t)n++;
+    r[0] = e.M; r[1] = e.N; r[2] = e.K; r[3] = e.kind; r[4] = ms;
+  }
+  return n;
+}
+
+static hipError_t launch_gemm_impl(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_f64acc(const GemmArgs& a, hipStream_t s) {
+  if (!g_log_on || g_log.size() >= GEMM_LOG_CAP || a.M <= 0 || a.N <= 0) return launch_gemm_impl(a, s);
+  GemmLogEntry e{a.M, a.N, a.K, (a.acc_f32 ? 1 : 0) | (a.c_is_f64 ? 2 : 0) | (a.lower_only ? 4 : 0) | (a.trans_b ? 8 : 0), nullptr, nullptr};
+  if (hipEventCreate(&e.a) != hipSuccess || hipEventCreate(&e.b) != hipSuccess) return launch_gemm_impl(a, s);
+  hipEventRecord(e.a, s);
+  const hipError_t r = launch_gemm_impl(a, s);
+  hipEventRecord(e.b, s);
+  g_log.push_back(e);
+  return r;
+}
+
+static hipError_t launch_gemm_impl(const GemmArgs& a, hipStream_t s) {
   if (a.M <= 0 || a.N <= 0) return hipSuccess;
   const int blocks = grid_blocks(a);
   int vecA = (a.lda % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.A) & 15) == 0);
   int vecB = (a.ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.B) & 15) == 0);
   int vecC = (!a.c_is_f64) && (a.ldc % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.C) & 15) == 0) &&
              (a.Cin == nullptr || ((a.ldcin % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.Cin) & 15) == 0)));
-  if (a.acc_f32 && a.c_is_f64) {
-    // float32 accumulation over windows of `kper` of K, float64 across the windows (atomics into C, which holds the addend)
-    const int kper = 1024;
-    hipLaunchKernelGGL(gemm_f32acc_kernel<true>, dim3(blocks, (a.K + kper - 1) / kper), dim3(256), 0, s, a, vecA, vecB, 0, kper);
-  } else if (a.acc_f32)
-    hipLaunchKernelGGL(gemm_f32acc_kernel<false>, dim3(blocks), dim3(256), 0, s, a, vecA, vecB, vecC, 0);
+  if (a.acc_f32 && a.c_is_f64) return hipErrorInvalidValue;      // float32 accumulation has float32 output only
+  if (a.acc_f32)
+    hipLaunchKernelGGL(gemm_f32acc_kernel, dim3(blocks), dim3(256), 0, s, a, vecA, vecB, vecC);
   else if (a.c_is_f64)
     hipLaunchKernelGGL(gemm_f64acc_kernel<double>, dim3(blocks), dim3(256), 0, s, a, vecA, vecB, 0);
   else

@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256) void gram_pack_conv_kernel(const uint16_t* __r
 __global__ __launch_bounds__(256, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void gram_packed_kernel(
     const uint4* __restrict__ Ap, int64_t a_sstride, const uint4* __restrict__ Bp, int64_t b_sstride, int nstages, int rows_out,
     int cols_out, int ldo, double* __restrict__ H64, const int2* __restrict__ tile_list, int stages_per_split, int window,
-    int symmetric) {
+    int symmetric, int split) {
   constexpr int WT = 2, TS = 128;
   extern __shared__ uint4 lds[];             // [2 buffers][2 panels][PK_SLOTS]
   const int2 tile = tile_list[blockIdx.x];
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   const int tm = tile.x, tn = tile.y;
   const bool diag = symmetric && (tm == tn);
   const int i0 = tm * TS, j0 = tn * TS;
-  const int s_begin = blockIdx.y * stages_per_split;
+  const int s_begin = split * stages_per_split;
   const int s_end = (s_begin + stages_per_split < nstages) ? s_begin + stages_per_split : nstages;
   if (s_begin >= s_end) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -326,26 +326,32 @@ static int split_stages(int ntiles, int nstages, int* per_out) {
   return (nstages + per - 1) / per;
 }
 
-hipError_t launch_gram_packed(const void* Xc, int64_t n_c, int64_t ldx, int d1, double* H64, int2* tile_buf,
-                              size_t tile_buf_entries, void* pack_buf, int64_t pack_rows, hipStream_t s, const void* Yc,
-                              int64_t ldy, int m, double* G64, int2* tile_buf_y, size_t tile_buf_y_entries, void* pack_buf_y,
-                              const ConvSpec* conv) {
+void gram_tile_list_host(int d1, std::vector<int2>& out) { build_tile_list((d1 + 127) / 128, out); }
+void rect_tile_list_host(int d1, int m, std::vector<int2>& out) { build_rect_tile_list((d1 + 127) / 128, (m + 127) / 128, out); }
+
+// Out += A^T B over all stages.  When the contraction is cut into several ranges (few tiles: small layers), the ranges run
+// as launches one after the other, so that every element of Out receives its additions in one fixed order (each launch
+// adds once per element: the atomic adds never meet).
+static void launch_packed_splits(const uint4* Ap, int64_t a_ss, const uint4* Bp, int64_t b_ss, int nstages, int rows_out, int cols_out,
+                                 int ldo, double* Out, const int2* tiles, size_t tile_entries, int ntiles, int window, int symmetric,
+                                 hipStream_t s) {
+  int per = 0;
+  const int splits = split_stages(ntiles, nstages, &per);
+  const size_t shmem = (size_t)2 * 2 * PK_SLOTS * 16;
+  for (int sp = 0; sp < splits; sp++)
+    hipLaunchKernelGGL(gram_packed_kernel, dim3((unsigned)tile_entries), dim3(256), shmem, s, Ap, a_ss, Bp, b_ss, nstages, rows_out,
+                       cols_out, ldo, Out, tiles, per, window, symmetric, sp);
+}
+
+hipError_t launch_gram_packed(const void* Xc, int64_t n_c, int64_t ldx, int d1, double* H64, const int2* tiles,
+                              size_t tile_entries, void* pack_buf, int64_t pack_rows, hipStream_t s, const void* Yc,
+                              int64_t ldy, int m, double* G64, const int2* tiles_y, size_t tile_y_entries, void* pack_buf_y,
+                              const ConvSpec* conv, hipEvent_t* ev, int ev_pairs, int* ev_used) {
+  if (ev_used) *ev_used = 0;
   if (n_c <= 0) return hipSuccess;
-  if (pack_rows < GBK || pack_rows % GBK) return hipErrorInvalidValue;
+  if (pack_rows < GBK || pack_rows % GBK || !tiles || tile_entries == 0) return hipErrorInvalidValue;
+  if (Yc && (!tiles_y || tile_y_entries == 0)) return hipErrorInvalidValue;
   const int npanels = (d1 + 127) / 128, npanels_y = Yc ? (m + 127) / 128 : 0;
-  std::vector<int2> tiles, tiles_y;
-  build_tile_list(npanels, tiles);
-  if (tiles.size() > tile_buf_entries) return hipErrorInvalidValue;
-  hipError_t e = hipMemcpyAsync(tile_buf, tiles.data(), tiles.size() * sizeof(int2), hipMemcpyHostToDevice, s);
-  if (e != hipSuccess) return e;
-  if (Yc) {
-    build_rect_tile_list(npanels, npanels_y, tiles_y);
-    if (tiles_y.size() > tile_buf_y_entries) return hipErrorInvalidValue;
-    e = hipMemcpyAsync(tile_buf_y, tiles_y.data(), tiles_y.size() * sizeof(int2), hipMemcpyHostToDevice, s);
-    if (e != hipSuccess) return e;
-  }
-  e = hipStreamSynchronize(s);   // the host vectors die at return
-  if (e != hipSuccess) return e;
   const int ntiles = npanels * (npanels + 1) / 2;
   const int window = 16;   // 1024 tokens per MFMA accumulation window
   const size_t shmem = (size_t)2 * 2 * PK_SLOTS * 16;
@@ -360,19 +366,18 @@ hipError_t launch_gram_packed(const void* Xc, int64_t n_c, int64_t ldx, int d1, 
     else
       hipLaunchKernelGGL(gram_pack_kernel, dim3((npanels + 1) / 2, nstages), dim3(256), 0, s, src, nr, ldx, d1, npanels,
                          reinterpret_cast<uint4*>(pack_buf));
-    int per = 0;
-    int splits = split_stages(ntiles, nstages, &per);
     const int64_t xs = (int64_t)npanels * PK_SLOTS;
-    hipLaunchKernelGGL(gram_packed_kernel, dim3((unsigned)tiles.size(), splits), dim3(256), shmem, s, Xp, xs, Xp, xs, nstages, d1,
-                       d1, d1, H64, tile_buf, per, window, 1);
+    const bool timed = ev && ev_used && *ev_used < ev_pairs;
+    if (timed) hipEventRecord(ev[2 * *ev_used], s);
+    launch_packed_splits(Xp, xs, Xp, xs, nstages, d1, d1, d1, H64, tiles, tile_entries, ntiles, window, 1, s);
+    if (timed) { hipEventRecord(ev[2 * *ev_used + 1], s); ++*ev_used; }
     if (Yc) {
       const uint16_t* srcy = reinterpret_cast<const uint16_t*>(Yc) + r0 * ldy;
       const uint4* Yp = reinterpret_cast<const uint4*>(pack_buf_y);
       hipLaunchKernelGGL(gram_pack_kernel, dim3((npanels_y + 1) / 2, nstages), dim3(256), 0, s, srcy, nr, ldy, m, npanels_y,
                          reinterpret_cast<uint4*>(pack_buf_y));
-      splits = split_stages(npanels * npanels_y, nstages, &per);
-      hipLaunchKernelGGL(gram_packed_kernel, dim3((unsigned)tiles_y.size(), splits), dim3(256), shmem, s, Xp, xs, Yp,
-                         (int64_t)npanels_y * PK_SLOTS, nstages, d1, m, m, G64, tile_buf_y, per, window, 0);
+      launch_packed_splits(Xp, xs, Yp, (int64_t)npanels_y * PK_SLOTS, nstages, d1, m, m, G64, tiles_y, tile_y_entries,
+                           npanels * npanels_y, window, 0, s);
     }
   }
   return hipGetLastError();
@@ -427,17 +432,10 @@ __global__ __launch_bounds__(256) void gram_pack_split_kernel(const float* __res
 
 // G64 (d1 x m, float64, zeroed by the caller) += H W.  H: d1 x d1 float32 (ld = d1, d1 % 8 == 0, 16-byte aligned), W: d1 x m bf16
 // (m % 8 == 0, ldw % 8 == 0, 16-byte aligned).  pack_h: pack_rows * 128*ceil(d1/128) * 2 bytes, pack_w likewise for m.
-hipError_t launch_hw_split(const float* H, int d1, const void* W, int64_t ldw, int m, double* G64, int2* tile_buf,
-                           size_t tile_buf_entries, void* pack_h, void* pack_w, int64_t pack_rows, hipStream_t s) {
-  if (pack_rows < GBK || pack_rows % GBK) return hipErrorInvalidValue;
+hipError_t launch_hw_split(const float* H, int d1, const void* W, int64_t ldw, int m, double* G64, const int2* tiles,
+                           size_t tile_entries, void* pack_h, void* pack_w, int64_t pack_rows, hipStream_t s) {
+  if (pack_rows < GBK || pack_rows % GBK || !tiles || tile_entries == 0) return hipErrorInvalidValue;
   const int npanels = (d1 + 127) / 128, npanels_w = (m + 127) / 128;
-  std::vector<int2> tiles;
-  build_rect_tile_list(npanels, npanels_w, tiles);
-  if (tiles.size() > tile_buf_entries) return hipErrorInvalidValue;
-  hipError_t e = hipMemcpyAsync(tile_buf, tiles.data(), tiles.size() * sizeof(int2), hipMemcpyHostToDevice, s);
-  if (e != hipSuccess) return e;
-  e = hipStreamSynchronize(s);   // the host vector dies at return
-  if (e != hipSuccess) return e;
   const int window = 16;
   const size_t shmem = (size_t)2 * 2 * PK_SLOTS * 16;
   for (int64_t r0 = 0; r0 < d1; r0 += pack_rows) {
@@ -445,22 +443,77 @@ hipError_t launch_hw_split(const float* H, int d1, const void* W, int64_t ldw, i
     const int nstages = (int)((nr + GBK - 1) / GBK);
     hipLaunchKernelGGL(gram_pack_kernel, dim3((npanels_w + 1) / 2, nstages), dim3(256), 0, s,
                        reinterpret_cast<const uint16_t*>(W) + r0 * ldw, nr, ldw, m, npanels_w, reinterpret_cast<uint4*>(pack_w));
-    int per = 0;
-    const int splits = split_stages(npanels * npanels_w, nstages, &per);
     for (int piece = 0; piece < 3; piece++) {
       hipLaunchKernelGGL(gram_pack_split_kernel, dim3((npanels + 1) / 2, nstages), dim3(256), 0, s, H + r0 * d1, nr, (int64_t)d1, d1,
                          npanels, piece, reinterpret_cast<uint4*>(pack_h));
-      hipLaunchKernelGGL(gram_packed_kernel, dim3((unsigned)tiles.size(), splits), dim3(256), shmem, s,
-                         reinterpret_cast<const uint4*>(pack_h), (int64_t)npanels * PK_SLOTS, reinterpret_cast<const uint4*>(pack_w),
-                         (int64_t)npanels_w * PK_SLOTS, nstages, d1, m, m, G64, tile_buf, per, window, 0);
+      launch_packed_splits(reinterpret_cast<const uint4*>(pack_h), (int64_t)npanels * PK_SLOTS, reinterpret_cast<const uint4*>(pack_w),
+                           (int64_t)npanels_w * PK_SLOTS, nstages, d1, m, m, G64, tiles, tile_entries, npanels * npanels_w, window, 0, s);
     }
   }
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------
+// General products of float32 matrices on the bf16 matrix cores: C = beta Cin + alpha A^T B with A (K x M) and B (K x N)
+// row-major, the contraction running over their rows.  Each operand is cut into three bf16 pieces (a = a1 + a2 + a3, each the
+// round-to-nearest bf16 of what the pieces before it leave: together 24 significand bits), and the six products whose
+// weight is at least 2^-16 of the leading one -- a1 b1, a1 b2, a2 b1, a2 b2, a1 b3, a3 b1 -- run on the packed kernel above:
+// products of bf16 numbers are exact in float32, sums restart every 1024 rows and end in float64.  What is dropped (a2 b3,
+// a3 b2, a3 b3) is below 2^-24 of |a| |b| term by term, the size of the operands' own float32 rounding.
+// ------------------------------------------------------------------------------------------------
+static int64_t split_kpad(int64_t K) { return (K + GBK - 1) / GBK * GBK; }
+size_t split_pack_bytes(int64_t K, int64_t cols) { return (size_t)3 * split_kpad(K) * ((cols + 127) / 128 * 128) * 2; }
+
+hipError_t launch_pack_pieces(const float* A, int64_t lda, int64_t K, int cols, void* pack, hipStream_t s) {
+  if (K <= 0 || cols <= 0) return hipSuccess;
+  if (cols % 8 || lda % 4 || (reinterpret_cast<uintptr_t>(A) & 15)) return hipErrorInvalidValue;
+  const int npanels = (cols + 127) / 128, nstages = (int)(split_kpad(K) / GBK);
+  const size_t piece = (size_t)nstages * npanels * PK_SLOTS;      // uint4 packets per piece
+  for (int pc = 0; pc < 3; pc++)
+    hipLaunchKernelGGL(gram_pack_split_kernel, dim3((npanels + 1) / 2, nstages), dim3(256), 0, s, A, K, lda, cols, npanels, pc,
+                       reinterpret_cast<uint4*>(pack) + pc * piece);
+  return hipGetLastError();
+}
+
+__global__ void split_epilogue_kernel(const double* __restrict__ acc, int M, int N, const float* __restrict__ Cin, int64_t ldcin,
+                                      float* __restrict__ C, int64_t ldc, double alpha, double beta) {
+  const int64_t tot = (int64_t)M * N;
+  for (int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; idx < tot; idx += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t i = idx / N, j = idx % N;
+    double v = alpha * acc[idx];
+    if (Cin) v += beta * (double)Cin[i * ldcin + j];
+    C[i * ldc + j] = (float)v;
+  }
+}
+
+// acc (M x N float64, dense) = A^T B from packed pieces; nprod = 6 (full float32 accuracy) or 3 (a1 b1 + a1 b2 + a2 b1: 2^-16)
+hipError_t launch_split_product(const void* packA, int M, const void* packB, int N, int64_t K, int nprod, double* acc,
+                                const int2* tiles, size_t tile_entries, int ntiles, hipStream_t s) {
+  if (M <= 0 || N <= 0) return hipSuccess;
+  if (!tiles || tile_entries == 0 || (nprod != 6 && nprod != 3)) return hipErrorInvalidValue;
+  const int npa = (M + 127) / 128, npb = (N + 127) / 128, nstages = (int)(split_kpad(K) / GBK);
+  const size_t pieceA = (size_t)nstages * npa * PK_SLOTS, pieceB = (size_t)nstages * npb * PK_SLOTS;
+  hipError_t e = hipMemsetAsync(acc, 0, (size_t)M * N * 8, s);
+  if (e != hipSuccess) return e;
+  if (K <= 0) return hipSuccess;
+  static const int combo[6][2] = {{0, 0}, {0, 1}, {1, 0}, {1, 1}, {0, 2}, {2, 0}};
+  for (int c = 0; c < nprod; c++)
+    launch_packed_splits(reinterpret_cast<const uint4*>(packA) + combo[c][0] * pieceA, (int64_t)npa * PK_SLOTS,
+                         reinterpret_cast<const uint4*>(packB) + combo[c][1] * pieceB, (int64_t)npb * PK_SLOTS, nstages, M, N, N, acc,
+                         tiles, tile_entries, ntiles, 16, 0, s);
+  return hipGetLastError();
+}
+
+hipError_t launch_split_epilogue(const double* acc, int M, int N, const float* Cin, int64_t ldcin, float* C, int64_t ldc, double alpha,
+                                 double beta, hipStream_t s) {
+  if (M <= 0 || N <= 0) return hipSuccess;
+  hipLaunchKernelGGL(split_epilogue_kernel, dim3(2048), dim3(256), 0, s, acc, M, N, (beta != 0.0) ? Cin : nullptr, ldcin, C, ldc, alpha, beta);
+  return hipGetLastError();
+}
+
 // sum of squares of a rows x cols matrix (float32 or bf16), added to *acc
 __global__ __launch_bounds__(256) void sumsq_kernel(const void* __restrict__ A, int is_bf16, int64_t rows, int64_t cols, int64_t ld,
-                                                     double* __restrict__ acc) {
+                                                     double* __restrict__ part) {
   __shared__ double red[4];
   double v = 0;
   const int64_t tot = rows * cols;
@@ -473,11 +526,14 @@ __global__ __launch_bounds__(256) void sumsq_kernel(const void* __restrict__ A, 
   for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
   __syncthreads();
-  if (threadIdx.x == 0) unsafeAtomicAdd(acc, red[0] + red[1] + red[2] + red[3]);
+  if (threadIdx.x == 0) part[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
 }
-hipError_t launch_sumsq(const void* A, int is_bf16, int64_t rows, int64_t cols, int64_t ld, double* acc, hipStream_t s) {
+// *acc += the 1024 partial sums, in a fixed order
+__global__ __launch_bounds__(1024) void sumsq_add_kernel(const double* __restrict__ part, double* __restrict__ acc);
+hipError_t launch_sumsq(const void* A, int is_bf16, int64_t rows, int64_t cols, int64_t ld, double* acc, double* partial, hipStream_t s) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
-  hipLaunchKernelGGL(sumsq_kernel, dim3(1024), dim3(256), 0, s, A, is_bf16, rows, cols, ld, acc);
+  hipLaunchKernelGGL(sumsq_kernel, dim3(1024), dim3(256), 0, s, A, is_bf16, rows, cols, ld, partial);
+  hipLaunchKernelGGL(sumsq_add_kernel, dim3(1), dim3(1024), 0, s, partial, acc);
   return hipGetLastError();
 }
 
@@ -644,6 +700,32 @@ __global__ __launch_bounds__(1024) void dot64_stage2(const double* __restrict__ 
   double v = (threadIdx.x < (unsigned)n) ? partial[threadIdx.x] : 0.0;
   double t = block_sum(v, sh);
   if (threadIdx.x == 0) out[0] = t;
+}
+
+// out = sum_i <a[rows[i], :], b[i, :]> (a: row-major with leading dimension m, b: dense nrows x m), float64, fixed order
+__global__ __launch_bounds__(256) void dot64_rows_stage1(const float* __restrict__ a, const int32_t* __restrict__ rows,
+                                                          const float* __restrict__ b, int nrows, int m, double* __restrict__ partial) {
+  __shared__ double sh[4];
+  double v = 0;
+  for (int i = blockIdx.x; i < nrows; i += gridDim.x) {
+    const float* ar = a + (int64_t)rows[i] * m;
+    const float* br = b + (int64_t)i * m;
+    for (int c = threadIdx.x; c < m; c += 256) v += (double)ar[c] * (double)br[c];
+  }
+  double t = block_sum(v, sh);
+  if (threadIdx.x == 0) partial[blockIdx.x] = t;
+}
+hipError_t launch_dot64_rows(const float* a, const int32_t* rows, const float* b, int nrows, int m, double* out, double* partial,
+                             hipStream_t s) {
+  hipLaunchKernelGGL(dot64_rows_stage1, dim3(1024), dim3(256), 0, s, a, rows, b, nrows, m, partial);
+  hipLaunchKernelGGL(dot64_stage2, dim3(1), dim3(1024), 0, s, partial, 1024, out);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(1024) void sumsq_add_kernel(const double* __restrict__ part, double* __restrict__ acc) {
+  __shared__ double sh[16];
+  double t = block_sum(part[threadIdx.x], sh);
+  if (threadIdx.x == 0) acc[0] += t;
 }
 
 hipError_t launch_dot64(const float* a, const float* b, int64_t n, double* out, double* partial, hipStream_t s) {

@@ -3,8 +3,12 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <vector>
 
 namespace osscar {
+
+// message of the last failure of a call that takes no context, per host thread (returned by osscar_last_error(NULL))
+void set_contextless_error(const char* msg);
 
 // ----------------------------------------------------------------------------------------------
 // gemm.hip : C = alpha * A * B + beta * Cin (+ diag_add on the diagonal), all row-major float32
@@ -20,25 +24,34 @@ struct GemmArgs {
   int c_is_f64;                  // output (and Cin) element type: 0 float, 1 double
   int lower_only;                // 1: compute only tiles that touch the lower triangle (row >= col)
   int trans_b;                   // 1: B is given as N x K row-major (C = alpha * A * B^T + ...)
-  int acc_f32;                   // 1: accumulate in float32 (v_mfma_f32_32x32x2_f32).  With c_is_f64: float32 over windows of
-                                 // 1024 of K, added to the float64 C by atomics (C holds the addend; alpha only)
+  int acc_f32;                   // 1: accumulate in float32 (v_mfma_f32_32x32x2_f32); float32 output only
 };
 hipError_t launch_gemm_f64acc(const GemmArgs& a, hipStream_t s);
+// diagnostic log of the launches above: enable (1) / disable and clear (0); read = rows of {M, N, K, kind, ms} with
+// kind = 1 float32 accumulation | 2 float64 output | 4 lower triangle only | 8 B transposed; returns the number of rows
+void gemm_log_enable(int on);
+int gemm_log_read(double* out, int capacity);
 
 // ----------------------------------------------------------------------------------------------
 // gram.hip : H64 (+)= Xc^T Xc on the lower-triangle tiles (bf16 X, d1 % 8 == 0, ldx % 8 == 0, 16-byte aligned)
 // ----------------------------------------------------------------------------------------------
 // Repacks `pack_rows`-token chunks of Xc into MFMA operand order in pack_buf (pack_rows * 128*ceil(d1/128) * 2 bytes)
 // and accumulates them into H64.
-// tile_buf: device scratch for the tile schedule, tile_buf_entries >= 8 * (ceil(d1/128)^2 / 2 + ceil(d1/128) + 8)
+// tiles: the tile schedule on the device (gram_tile_list_host for the symmetric product, rect_tile_list_host for a
+// rectangular one), uploaded once by the caller; no call here waits for the stream.
 // Patch geometry of a convolutional layer: row (b*Hout + oy)*Wout + ox, column (c*kh + dy)*kw + dx of the patch matrix is
 // F[b][c][oy*stride + dy - pad][ox*stride + dx - pad] (zero outside the map).
 struct ConvSpec { int B, C, Hin, Win, kh, kw, stride, pad, Hout, Wout; };
-hipError_t launch_gram_packed(const void* Xc, int64_t n_c, int64_t ldx, int d1, double* H64, int2* tile_buf,
-                              size_t tile_buf_entries, void* pack_buf, int64_t pack_rows, hipStream_t s,
+hipError_t launch_gram_packed(const void* Xc, int64_t n_c, int64_t ldx, int d1, double* H64, const int2* tiles,
+                              size_t tile_entries, void* pack_buf, int64_t pack_rows, hipStream_t s,
                               const void* Yc = nullptr, int64_t ldy = 0, int m = 0, double* G64 = nullptr,
-                              int2* tile_buf_y = nullptr, size_t tile_buf_y_entries = 0, void* pack_buf_y = nullptr,
-                              const ConvSpec* conv = nullptr);
+                              const int2* tiles_y = nullptr, size_t tile_y_entries = 0, void* pack_buf_y = nullptr,
+                              const ConvSpec* conv = nullptr, hipEvent_t* ev = nullptr, int ev_pairs = 0, int* ev_used = nullptr);
+// ev (optional, 2 * ev_pairs events): recorded before and after each launch of the symmetric product kernel (one per
+// pack_rows chunk), *ev_used = pairs recorded
+// host-side schedules: lower-triangle tiles of a d1 x d1 result / all tiles of a d1 x m result (128 x 128 tiles)
+void gram_tile_list_host(int d1, std::vector<int2>& out);
+void rect_tile_list_host(int d1, int m, std::vector<int2>& out);
 // conv (optional): Xc is a feature map (NCHW, bf16) and the rows are its patches
 // Xt[c][r - r0] = patch matrix entry (r, c) as float32 for rows r0 .. r0 + nr (generic path of convolutional layers)
 hipError_t launch_im2col_transpose(const void* F, int is_bf16, const ConvSpec& cs, int64_t r0, int64_t nr, int d1, float* Xt,
@@ -47,9 +60,21 @@ hipError_t launch_im2col_transpose(const void* F, int is_bf16, const ConvSpec& c
 // ceil(m/128) / 8 + 64) entries) and pack buffer (pack_rows * 128*ceil(m/128) * 2 bytes)
 int gram_tile_schedule(int tiles_per_side, int32_t* out, int capacity);   // host only: the tile order of the SYRK kernel
 // G64 (zeroed by the caller) += H W for bf16 W through three bf16 pieces of the float32 H (see gram.hip)
-hipError_t launch_hw_split(const float* H, int d1, const void* W, int64_t ldw, int m, double* G64, int2* tile_buf,
-                           size_t tile_buf_entries, void* pack_h, void* pack_w, int64_t pack_rows, hipStream_t s);
-hipError_t launch_sumsq(const void* A, int is_bf16, int64_t rows, int64_t cols, int64_t ld, double* acc, hipStream_t s);
+hipError_t launch_hw_split(const float* H, int d1, const void* W, int64_t ldw, int m, double* G64, const int2* tiles,
+                           size_t tile_entries, void* pack_h, void* pack_w, int64_t pack_rows, hipStream_t s);
+// Products of float32 matrices on the bf16 matrix cores through three bf16 pieces per operand (see gram.hip).  Operands are
+// row-major with the contraction along their rows (C = A^T B).  pack: split_pack_bytes(K, cols) bytes, 256-byte aligned.
+size_t split_pack_bytes(int64_t K, int64_t cols);
+hipError_t launch_pack_pieces(const float* A, int64_t lda, int64_t K, int cols, void* pack, hipStream_t s);   // cols % 8 == 0, lda % 4 == 0
+// acc (M x N float64, dense; cleared here) = A^T B.  tiles: rect_tile_list_host(M, N), or gram_tile_list_host(M) for the lower
+// triangle of a square result (ntiles = number of real tiles in the list, for the split of the contraction over workgroups)
+hipError_t launch_split_product(const void* packA, int M, const void* packB, int N, int64_t K, int nprod, double* acc,
+                                const int2* tiles, size_t tile_entries, int ntiles, hipStream_t s);
+// C = float(beta * Cin + alpha * acc)
+hipError_t launch_split_epilogue(const double* acc, int M, int N, const float* Cin, int64_t ldcin, float* C, int64_t ldc, double alpha,
+                                 double beta, hipStream_t s);
+hipError_t launch_sumsq(const void* A, int is_bf16, int64_t rows, int64_t cols, int64_t ld, double* acc, double* partial,
+                        hipStream_t s);   // partial: 1024 doubles
 hipError_t launch_finalize_G(const double* G64, const float* Wf, const double* lambda_dev, float* G, int64_t n, hipStream_t s);
 hipError_t launch_transpose_to_f32(const void* X, int is_bf16, int64_t rows, int64_t cols, int64_t ldx, float* Xt,
                                    int64_t ldxt, hipStream_t s);
@@ -62,6 +87,9 @@ hipError_t launch_convert_to_f32(const void* src, int is_bf16, int64_t rows, int
 // norms2[j] = sum over group j of W^2 (float64); c0 = sum W*G
 hipError_t launch_group_norms(const float* Wf, int p, int q, int m, double* norms2, hipStream_t s);
 hipError_t launch_dot64(const float* a, const float* b, int64_t n, double* out, double* partial, hipStream_t s);
+// out = sum_i <a[rows[i], :], b[i, :]>, a with leading dimension m, b dense nrows x m (partial: 1024 doubles)
+hipError_t launch_dot64_rows(const float* a, const int32_t* rows, const float* b, int nrows, int m, double* out, double* partial,
+                             hipStream_t s);
 
 // ----------------------------------------------------------------------------------------------
 // tableau.hip : the swept tableau N (d1 x d1, lower triangle valid) and Z (d1 x m)
@@ -76,7 +104,8 @@ struct SearchCtrl {          // lives in device memory
   int32_t pause;             // delayed-update search: the host must flush before the search can go on
   int32_t tau;               // delayed-update search: number of pending pivots that every kernel of an iteration works with
   int32_t tau_inc;           // pivots that the iteration just applied adds to it: folded into tau by the next one-workgroup
-  int32_t pad_;              // kernel (prep), so that no kernel changes tau while its own workgroups read it
+  int32_t misses;            // kernel (prep), so that no kernel changes tau while its own workgroups read it.
+                             // misses: delayed-update search, pivots so far whose products with Z0 had not been computed ahead
   double obj;                // tracked objective
   double rel_tol;
   double delta;              // exact change of the current pair
@@ -110,6 +139,7 @@ struct TabPtrs {
   float* C1D; float* C2D;          // d1 x q panels times D
   float* rZ1; float* rZ2;          // q x m
   double* small;                   // scratch for q x q algebra (>= 16*q*q doubles)
+  double* dpart;                   // ceil(m / 16) partial sums of the exact change of a pair (column blocks, fixed order)
   double* cross; double* xgram; double* xdblk; double* xscore;   // exact entering rule: d1*q, p*q*q, p*q*q, p
   SearchCtrl* ctrl;
   int32_t* trace_out; int32_t* trace_in; float* trace_gap; double* trace_obj;
@@ -153,7 +183,8 @@ struct LazyPtrs {
   SelRec* sel;      // ceil(d1/32) per-block score records
   // products of Z0 with the rows of Z0 that are likely to become pivots before the next flush
   double* GbT;      // (LAZY_NC + LAZY_NS) x d1: row s = Z0 Z0[cand[s], :]^T
-  float* Zc;        // LAZY_NC x m: the gathered rows
+  float* Zc;        // LAZY_NC x m: the gathered rows (shapes that take the general matrix-product kernel)
+  void* ZcP;        // LAZY_NC x 32*ceil(m/32) x 3 bf16: the candidate rows cut into three bf16 pieces, in matrix-core operand order
   int32_t* cslot;   // d1: slot of a row in GbT or -1
   int32_t* cand;    // LAZY_NC + LAZY_NS: row held by a slot or -1
   int32_t* tslot;   // LAZY_TM: slot of each pending pivot

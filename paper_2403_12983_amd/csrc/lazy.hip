@@ -245,6 +245,7 @@ __global__ __launch_bounds__(256) void lazy_prep_kernel(LazyPtrs L, const float*
     if (single) sj = sg;
     else if (sj < 0) { sj = LAZY_NC + ns++; L.cslot[j] = sj; L.cand[sj] = j; miss |= 2; }
     L.misc[MI_SPARE] = ns; L.misc[MI_MISS] = miss; L.misc[MI_SG] = sg; L.misc[MI_SJ] = sj;
+    ctrl->misses += (miss & 1) + (miss >> 1);
     const double m1 = mn1, m2 = mn2, x1 = mx1, x2 = mx2;
     ctrl->gap_rem = isfinite(m2) ? fabs(m2 - m1) / fmax(fabs(m1), 1e-300) : INFINITY;
     ctrl->gap_add = isfinite(x2) ? fabs(x1 - x2) / fmax(fabs(x1), 1e-300) : INFINITY;
@@ -796,6 +797,151 @@ __global__ __launch_bounds__(256) void cand_gather_kernel(LazyPtrs L, const floa
   for (int c = threadIdx.x; c < m; c += 256) dst[c] = (r >= 0) ? Z0[(int64_t)r * m + c] : 0.f;
 }
 
+// ------------------------------------------------------------------------------------------------
+// The look-ahead product GbT[s, i] = <Z0[cand[s], :], Z0[i, :]> on the bf16 matrix cores, bound by one read of Z0.
+// Every float32 number is cut into three bf16 pieces (each the round-to-nearest bf16 of what the pieces before it leave;
+// together 24 significand bits) and the six products of weight >= 2^-16 run as v_mfma_f32_32x32x16_bf16: products of bf16
+// numbers are exact in float32, sums run in float32 over 1024 columns and in float64 registers across them, and every
+// element of GbT is written once by the one wave that owns it (no atomics: the result does not depend on scheduling).
+// The candidate rows are cut and laid out in operand order once per flush (la_pack_kernel, a few MB that stay in L2);
+// the rows of Z0 are cut in registers as they stream in, each lane holding 8 consecutive columns of one row, which is
+// the operand layout as it stands: Z0 never passes through shared memory.
+//   one workgroup = 128 rows of Z0 x 128 candidates; wave w owns rows 32 w .. 32 w + 31 as four 32 x 32 tiles.
+// ------------------------------------------------------------------------------------------------
+typedef float la_f16v __attribute__((ext_vector_type(16)));
+typedef __bf16 la_bf8 __attribute__((ext_vector_type(8)));
+constexpr int LA_STG = 32;                   // columns of Z per stage (two 16-deep matrix-core steps)
+constexpr int LA_PK = 3 * 4 * 128;           // 16-byte packets per stage: 3 pieces x 4 groups of 8 columns x 128 candidates
+
+__device__ __forceinline__ uint32_t la_rne(float x) {
+  const uint32_t u = __float_as_uint(x);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+// v[0..8) -> three packets of 8 bf16 each
+__device__ __forceinline__ void la_split3(const float* v, uint4& p1, uint4& p2, uint4& p3) {
+  uint32_t h1[8], h2[8], h3[8];
+#pragma unroll
+  for (int j = 0; j < 8; j++) {
+    const uint32_t b1 = la_rne(v[j]);
+    const float r1 = v[j] - __uint_as_float(b1 << 16);
+    const uint32_t b2 = la_rne(r1);
+    const float r2 = r1 - __uint_as_float(b2 << 16);
+    h1[j] = b1; h2[j] = b2; h3[j] = la_rne(r2);
+  }
+  p1 = uint4{h1[0] | (h1[1] << 16), h1[2] | (h1[3] << 16), h1[4] | (h1[5] << 16), h1[6] | (h1[7] << 16)};
+  p2 = uint4{h2[0] | (h2[1] << 16), h2[2] | (h2[3] << 16), h2[4] | (h2[5] << 16), h2[6] | (h2[7] << 16)};
+  p3 = uint4{h3[0] | (h3[1] << 16), h3[2] | (h3[3] << 16), h3[4] | (h3[5] << 16), h3[6] | (h3[7] << 16)};
+}
+
+// ZcP[(sb * nstg + stage) * LA_PK + piece * 512 + kg * 128 + s] = columns stage*32 + kg*8 .. +8 of candidate sb*128 + s, piece
+// `piece` (zero for unused slots and beyond column m).  grid (nstg, ns / 128), 256 threads, two packets' worth of columns each.
+__global__ __launch_bounds__(256) void la_pack_kernel(LazyPtrs L, const float* __restrict__ Z0, int m, int nstg, uint4* __restrict__ ZcP) {
+  const int stage = blockIdx.x, sb = blockIdx.y, tid = threadIdx.x;
+  uint4* out = ZcP + ((int64_t)sb * nstg + stage) * LA_PK;
+#pragma unroll
+  for (int h = 0; h < 2; h++) {
+    const int pk = tid + 256 * h, kg = pk >> 7, sl = pk & 127;
+    const int r = L.cand[sb * 128 + sl], c0 = stage * LA_STG + kg * 8;
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) v[j] = 0.f;
+    if (r >= 0 && c0 + 8 <= m) {
+      const float4 a = *reinterpret_cast<const float4*>(Z0 + (int64_t)r * m + c0);
+      const float4 b = *reinterpret_cast<const float4*>(Z0 + (int64_t)r * m + c0 + 4);
+      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+    uint4 p1, p2, p3;
+    la_split3(v, p1, p2, p3);
+    out[pk] = p1; out[512 + pk] = p2; out[1024 + pk] = p3;
+  }
+}
+
+// GbT[(sb * 128 + s) * d1 + i] for i in [128 blockIdx.x, +128), s in [0, 128), sb = blockIdx.y.  m % 8 == 0.
+__global__ __launch_bounds__(256, 1) void la_product_kernel(const uint4* __restrict__ ZcP, const float* __restrict__ Z0, int d1, int m,
+                                                             int nstg, double* __restrict__ GbT) {
+  __shared__ uint4 lds[2][LA_PK];            // 2 x 24 KB
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, sb = blockIdx.y;
+  const int i_lane = blockIdx.x * 128 + wave * 32 + (lane & 31);
+  const float* zrow = Z0 + (int64_t)(i_lane < d1 ? i_lane : d1 - 1) * m + (lane >> 5) * 8;      // rows past the end: clamped, never stored
+  const uint4* src = ZcP + (int64_t)sb * nstg * LA_PK + tid;
+  la_f16v acc[4];
+  double dacc[4][16];
+#pragma unroll
+  for (int t = 0; t < 4; t++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) { acc[t][r] = 0.f; dacc[t][r] = 0.0; }
+  uint4 zc[6];
+  float4 z0[4];
+  auto gload = [&](int stage) {
+    const uint4* p = src + (int64_t)stage * LA_PK;
+#pragma unroll
+    for (int u = 0; u < 6; u++) zc[u] = p[256 * u];
+#pragma unroll
+    for (int ks = 0; ks < 2; ks++) {
+      const int c = stage * LA_STG + ks * 16 + (lane >> 5) * 8;
+      if (c + 8 <= m) {
+        z0[2 * ks] = *reinterpret_cast<const float4*>(zrow + stage * LA_STG + ks * 16);
+        z0[2 * ks + 1] = *reinterpret_cast<const float4*>(zrow + stage * LA_STG + ks * 16 + 4);
+      } else {
+        z0[2 * ks] = float4{0.f, 0.f, 0.f, 0.f}; z0[2 * ks + 1] = float4{0.f, 0.f, 0.f, 0.f};
+      }
+    }
+  };
+  gload(0);
+  int since = 0;
+  for (int stage = 0; stage < nstg; stage++) {
+    const int buf = stage & 1;
+    uint4* dst = &lds[buf][tid];
+#pragma unroll
+    for (int u = 0; u < 6; u++) dst[256 * u] = zc[u];
+    // this stage's rows of Z0 leave the load registers before the next stage's loads are issued into them
+    uint4 b1[2], b2[2], b3[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ks++) {
+      const float v[8] = {z0[2 * ks].x, z0[2 * ks].y, z0[2 * ks].z, z0[2 * ks].w, z0[2 * ks + 1].x, z0[2 * ks + 1].y, z0[2 * ks + 1].z, z0[2 * ks + 1].w};
+      la_split3(v, b1[ks], b2[ks], b3[ks]);
+    }
+    __syncthreads();
+    if (stage + 1 < nstg) gload(stage + 1);
+    const uint4* pa = lds[buf];
+#pragma unroll
+    for (int ks = 0; ks < 2; ks++) {
+      const int off = (ks * 2 + (lane >> 5)) * 128 + (lane & 31);
+      const la_bf8 f1 = *reinterpret_cast<const la_bf8*>(&b1[ks]), f2 = *reinterpret_cast<const la_bf8*>(&b2[ks]),
+                   f3 = *reinterpret_cast<const la_bf8*>(&b3[ks]);
+#pragma unroll
+      for (int t = 0; t < 4; t++) {
+        uint4 q1 = pa[off + t * 32], q2 = pa[512 + off + t * 32], q3 = pa[1024 + off + t * 32];
+        const la_bf8 a1 = *reinterpret_cast<la_bf8*>(&q1), a2 = *reinterpret_cast<la_bf8*>(&q2), a3 = *reinterpret_cast<la_bf8*>(&q3);
+        // smallest terms first
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a3, f1, acc[t], 0, 0, 0);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, f3, acc[t], 0, 0, 0);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, f2, acc[t], 0, 0, 0);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, f1, acc[t], 0, 0, 0);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, f2, acc[t], 0, 0, 0);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, f1, acc[t], 0, 0, 0);
+      }
+    }
+    if (++since == 1024 / LA_STG || stage + 1 == nstg) {
+      since = 0;
+#pragma unroll
+      for (int t = 0; t < 4; t++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) { dacc[t][r] += (double)acc[t][r]; acc[t][r] = 0.f; }
+    }
+  }
+  // C layout of the 32 x 32 tile: register r = rr*4 + r3 holds row rr*8 + (lane/32)*4 + r3 (a candidate), column lane%32 (a row of Z0)
+  if (i_lane < d1) {
+#pragma unroll
+    for (int t = 0; t < 4; t++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int sl = t * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        GbT[(int64_t)(sb * 128 + sl) * d1 + i_lane] = dacc[t][r];
+      }
+  }
+}
+
 // mode 0: half of the slots for kept rows, half for the others; 1: all for kept rows (removal-only loops); 2: none
 static hipError_t launch_candidates(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode) {
   const int nblk = (d.p + 1023) / 1024;               // <= 64 (d1 <= 65536)
@@ -810,15 +956,18 @@ static hipError_t launch_candidates(const TabDims& d, const TabPtrs& t, const La
   const int n_k = mode == 2 ? 0 : (mode == 1 ? LAZY_NC : LAZY_NC / 4), n_c = mode == 0 ? LAZY_NC / 4 : 0;
   hipLaunchKernelGGL(cand_merge_kernel, dim3(1), dim3(1024), 0, s, L, nblk, per_block, n_k, n_c);
   if (mode == 2) return hipGetLastError();
+  if (d.m % 8 == 0 && (n_k + n_c) % 128 == 0) {
+    const int nstg = (d.m + LA_STG - 1) / LA_STG, nsb = (n_k + n_c) / 128;
+    hipLaunchKernelGGL(la_pack_kernel, dim3(nstg, nsb), dim3(256), 0, s, L, t.Z, d.m, nstg, reinterpret_cast<uint4*>(L.ZcP));
+    hipLaunchKernelGGL(la_product_kernel, dim3((d.d1 + 127) / 128, nsb), dim3(256), 0, s, reinterpret_cast<const uint4*>(L.ZcP), t.Z,
+                       d.d1, d.m, nstg, L.GbT);
+    return hipGetLastError();
+  }
+  // other shapes: the general matrix-product kernel on the gathered rows
   hipLaunchKernelGGL(cand_gather_kernel, dim3(n_k + n_c), dim3(256), 0, s, L, t.Z, d.m);
-  GemmArgs g{};                         // GbT[0 .. LAZY_NC) = Zc Z0^T, float64
+  GemmArgs g{};                         // GbT[0 .. LAZY_NC) = Zc Z0^T, float64 accumulation and output
   g.M = n_k + n_c; g.N = d.d1; g.K = d.m; g.A = L.Zc; g.lda = d.m; g.B = t.Z; g.ldb = d.m; g.trans_b = 1;
   g.C = L.GbT; g.ldc = d.d1; g.alpha = 1.0; g.beta = 0.0; g.c_is_f64 = 1;
-  // float32 matrix-core accumulation over 1024-long windows of the m columns, float64 across windows (the products are
-  // exact either way; the windowed sum is accurate to ~1e-7 of |z_c| |z_i|, which the per-flush refresh of the scores bounds)
-  g.acc_f32 = 1;
-  e = hipMemsetAsync(L.GbT, 0, (size_t)(n_k + n_c) * d.d1 * 8, s);
-  if (e != hipSuccess) return e;
   return launch_gemm_f64acc(g, s);
 }
 

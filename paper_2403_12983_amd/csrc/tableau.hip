@@ -202,26 +202,18 @@ hipError_t launch_mirror_lower(float* A, int n, int64_t lda, hipStream_t s) {
   return hipGetLastError();
 }
 
-__global__ __launch_bounds__(1024) void absmax_kernel(const float* __restrict__ A, int64_t n, double* out) {
-  __shared__ double sh[16];
-  double v = 0;
-  for (int64_t i = threadIdx.x; i < n; i += 1024) { double x = fabs((double)A[i]); v = x > v ? x : v; }
-  for (int o = 32; o > 0; o >>= 1) { double w = __shfl_down(v, o, 64); v = w > v ? w : v; }
-  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
-  __syncthreads();
-  if (threadIdx.x == 0) { double t = 0; for (int i = 0; i < 16; i++) t = sh[i] > t ? sh[i] : t; out[0] = t; }
-}
 // out[b] for 256 blocks, then the caller reduces on the host (256 doubles)
 __global__ __launch_bounds__(256) void absmax_partial_kernel(const float* __restrict__ A, int64_t n, double* out) {
   __shared__ double sh[4];
+  // a NaN is taken (x != x) and then stays (nothing compares greater than it), so a NaN anywhere reaches the result
   double v = 0;
   for (int64_t i = blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    double x = fabs((double)A[i]); v = x > v ? x : v;
+    double x = fabs((double)A[i]); v = (x > v || x != x) ? x : v;
   }
-  for (int o = 32; o > 0; o >>= 1) { double w = __shfl_down(v, o, 64); v = w > v ? w : v; }
+  for (int o = 32; o > 0; o >>= 1) { double w = __shfl_down(v, o, 64); v = (w > v || w != w) ? w : v; }
   if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
   __syncthreads();
-  if (threadIdx.x == 0) { double t = 0; for (int i = 0; i < 4; i++) t = sh[i] > t ? sh[i] : t; out[blockIdx.x] = t; }
+  if (threadIdx.x == 0) { double t = 0; for (int i = 0; i < 4; i++) t = (sh[i] > t || sh[i] != sh[i]) ? sh[i] : t; out[blockIdx.x] = t; }
 }
 hipError_t launch_absmax(const float* A, int64_t n, double* out, hipStream_t s) {  // out: 256 doubles
   hipLaunchKernelGGL(absmax_partial_kernel, dim3(256), dim3(256), 0, s, A, n, out);
@@ -808,11 +800,12 @@ __global__ __launch_bounds__(256) void pair_small_kernel(TabDims d, const float*
 }
 
 // Column phase of the pair: rZ1 = Dg Zg ; Z'j = Zj - Njg rZ1 ; rZ2 = Dj' Z'j (both written in place of Zg, Zj) and
-// delta = -<Zg, rZ1> - <Z'j, rZ2>, added up in ctrl->delta.  16 columns x 16 row slots per workgroup; the three q x q
+// delta = -<Zg, rZ1> - <Z'j, rZ2>, one partial sum per workgroup in dpart (added up in a fixed order by the acceptance
+// kernel, so that the result does not depend on scheduling).  16 columns x 16 row slots per workgroup; the three q x q
 // matrices and the column tiles live in LDS.
 constexpr int PC_COLS = 16;
 __global__ __launch_bounds__(256) void pair_cols_kernel(TabDims d, float* __restrict__ Zg, float* __restrict__ Zj,
-                                                         const double* __restrict__ small, SearchCtrl* ctrl) {
+                                                         const double* __restrict__ small, SearchCtrl* ctrl, double* __restrict__ dpart) {
   extern __shared__ double pcs[];   // Dg, Njg, Dj (q*q each), ta, tb (q*16 each)
   __shared__ double red[4];
   if (ctrl->done) return;
@@ -847,14 +840,21 @@ __global__ __launch_bounds__(256) void pair_cols_kernel(TabDims d, float* __rest
   part = wave_sum(part);
   if ((tid & 63) == 0) red[tid >> 6] = part;
   __syncthreads();
-  if (tid == 0) unsafeAtomicAdd(&ctrl->delta, red[0] + red[1] + red[2] + red[3]);
+  if (tid == 0) dpart[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
 }
 
 // the acceptance test and the trace
-__global__ void pair_accept_kernel(SearchCtrl* ctrl, int always_accept, int32_t* trace_out, int32_t* trace_in, float* trace_gap,
-                                   double* trace_obj, const int32_t* __restrict__ single) {
+__global__ __launch_bounds__(64) void pair_accept_kernel(SearchCtrl* ctrl, int always_accept, int32_t* trace_out, int32_t* trace_in,
+                                                         float* trace_gap, double* trace_obj, const int32_t* __restrict__ single,
+                                                         const double* __restrict__ dpart, int nparts) {
   if (ctrl->done) return;
-  const double delta = ctrl->delta;
+  // lane l adds the partial sums l, l + 64, ... in that order; then the fixed tree of the wave sum
+  double dsum = 0;
+  for (int b = threadIdx.x; b < nparts; b += 64) dsum += dpart[b];
+  dsum = wave_sum(dsum);
+  if (threadIdx.x != 0) return;
+  const double delta = dsum;
+  ctrl->delta = delta;
   const int it = ctrl->iters;
   const bool bad = ctrl->notpd != 0;
   const bool ok = !bad && (always_accept || delta < -ctrl->rel_tol * ctrl->obj);
@@ -1294,10 +1294,10 @@ hipError_t launch_search_iteration(const TabDims& d, const TabPtrs& t, int force
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(pair_small_kernel, dim3(1), dim3(256), ps_lds, s, d, t.C1, t.C2, t.small, t.ctrl, single);
-  hipLaunchKernelGGL(pair_cols_kernel, dim3((d.m + PC_COLS - 1) / PC_COLS), dim3(256), pc_lds, s, d,
-                     t.rZ1, t.rZ2, t.small, t.ctrl);
-  hipLaunchKernelGGL(pair_accept_kernel, dim3(1), dim3(1), 0, s, t.ctrl, always_accept, t.trace_out, t.trace_in, t.trace_gap,
-                     t.trace_obj, single);
+  const int ncb = (d.m + PC_COLS - 1) / PC_COLS;
+  hipLaunchKernelGGL(pair_cols_kernel, dim3(ncb), dim3(256), pc_lds, s, d, t.rZ1, t.rZ2, t.small, t.ctrl, t.dpart);
+  hipLaunchKernelGGL(pair_accept_kernel, dim3(1), dim3(64), 0, s, t.ctrl, always_accept, t.trace_out, t.trace_in, t.trace_gap,
+                     t.trace_obj, single, t.dpart, ncb);
   // bulk panels go to C1D/C2D (times D) and to two further panels stored behind them
   float* P1 = t.C1D + (int64_t)2 * d.d1 * q;
   float* P2 = P1 + (int64_t)d.d1 * q;

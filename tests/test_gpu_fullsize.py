@@ -50,6 +50,166 @@ def follow_check(cfg, H, G, c0, K0, r, max_follow, exact_in=False):
     return fol
 
 
+def sampled_tiles_of_gram(cfg, X, H, lam, nblocks=6, seed=5):
+    """Tiles of H against the float64 Gram of the same bf16 data made by the generator on the CPU: `nblocks` column blocks
+    of 32 columns, all block pairs (Section 3: H = X^T X)."""
+    rng = np.random.default_rng(seed)
+    starts = sorted(int(v) for v in rng.choice(cfg.d1 // 32, size=nblocks, replace=False) * 32)
+    cols = torch.cat([torch.arange(a, a + 32) for a in starts])
+    Xs = torch.cat([inp.gen_X(cfg, r0, min(32768, cfg.n - r0), cols=cols).double() for r0 in range(0, cfg.n, 32768)]).numpy()
+    Hs = Xs.T @ Xs
+    assert torch.equal(X[:, cols.to(DEV)].cpu().double(), torch.from_numpy(Xs))   # same bits on both devices
+    Hg = H[cols.to(DEV)][:, cols.to(DEV)].cpu().double().numpy()
+    ds = np.sqrt(np.diag(Hs))
+    assert np.max(np.abs(Hg - Hs - lam * np.eye(len(cols))) / np.outer(ds, ds)) < 1e-6
+    return cols
+
+
+def progress(msg):
+    """A line per finished step of a long test, to stdout and to gpurun_out/pytest_progress.log (the oracle's steps at the
+    size of the benchmark layer take a minute each)."""
+    import os
+    import time
+    line = f"[{time.strftime('%H:%M:%S')}] {msg}"
+    print(line, flush=True)
+    try:
+        os.makedirs("gpurun_out", exist_ok=True)
+        with open(os.path.join("gpurun_out", "pytest_progress.log"), "a") as f:
+            f.write(line + "\n")
+    except OSError:
+        pass
+
+
+def scores_of(s):
+    return T(s, "T_REM").cpu().numpy(), T(s, "T_ADD").cpu().numpy()
+
+
+def check_scores(rem_g, add_g, rem_o, add_o, tol=2e-5, tol_add=None):
+    """Every removal cost and addition gain (eq. (impact)) of the library against the oracle's at the same state.
+    tol_add: optional per-group bar for the gains (indexed like add_o)."""
+    fk, fc = np.isfinite(rem_o), np.isfinite(add_o)
+    assert np.array_equal(np.isfinite(rem_g), fk) and np.array_equal(np.isfinite(add_g), fc)
+    err_r = float(np.max(np.abs(rem_g[fk] - rem_o[fk]) / rem_o[fk]))
+    rel_a = np.abs(add_g[fc] - add_o[fc]) / add_o[fc]
+    err_a = float(np.max(rel_a))
+    assert err_r < tol, err_r
+    assert np.all(rel_a < (tol if tol_add is None else tol_add[fc])), (err_a, int(np.argmax(rel_a)))
+    assert int(np.argmin(rem_g)) == int(np.argmin(rem_o)) or orc._gap_low(rem_o) <= GAP
+    assert int(np.argmax(add_g)) == int(np.argmax(add_o)) or orc._gap_high(add_o) <= GAP
+    return err_r, err_a
+
+
+def search_in_legs_against_oracle(cfg, s, Hh, Gh, c0, K0, obj0, n_follow, name):
+    """The library's state right after osscar_init_support and its first n_follow swaps, taken one osscar_local_search call
+    at a time so that ALL its scores can be read between them, against the oracle started from the SAME quadratic form (the
+    library's H and G widened to float64: only the state build, the scores, the choices and the updates are compared).
+    Weights and sampled rows of the inverse at the start; every removal cost and addition gain (eq. (impact)) at every one
+    of the n_follow states; every choice within GAP of the oracle's best (Section 4.2), its exact change negative
+    (Proposition 4.1 Case 3) and the tracked objective equal to 1e-5.  Returns the pairs and the oracle's state after them."""
+    st = orc.init_state(Hh, Gh, K0, cfg.q)
+    progress(f"{name}: oracle state built")
+    assert abs(obj0 - (c0 + 2 * st.f)) <= 1e-5 * obj0
+    assert rel(T(s, "T_B").cpu().double().numpy(), st.What_K) < 2e-5
+    Pg = T(s, "T_P")
+    rows = np.arange(0, st.P.shape[0], 211)
+    dp = np.sqrt(np.diag(st.P))
+    assert np.max(np.abs(Pg[torch.from_numpy(rows).to(DEV)].cpu().double().numpy() - st.P[rows]) / np.outer(dp[rows], dp)) < 2e-5
+    del Pg
+    # An addition gain is |R_j|^2 / S_jj with R_j = G_j - H_jK B a difference; the library stores B and R in float32, and the
+    # rounding of B (6e-8) reaches R_j magnified by |G_j| / |R_j|, twice over in the square: the same bar as in the small
+    # parity cases, with the rounding of the stored state in place of the rounding of H (the oracle starts from the same H here)
+    assert cfg.q == 1
+    cand0 = np.setdiff1d(np.arange(cfg.p), np.asarray(K0))
+    R0 = Gh[cand0] - Hh[np.ix_(cand0, np.asarray(K0))] @ st.What_K
+    tol_add0 = np.full(cfg.p, 2e-5)
+    tol_add0[cand0] += 4 * 6e-8 * np.linalg.norm(Gh[cand0], axis=1) / np.linalg.norm(R0, axis=1)
+    del R0
+    progress(f"{name}: oracle residual rows, largest |G_j| / |R_j| = {np.max((tol_add0[cand0] - 2e-5) / 2.4e-7):.1f}")
+    gpu_scores, pairs, objs = [scores_of(s)], [], []
+    for i in range(n_follow):
+        r = s.osscar_local_search(1)
+        assert r["accepted"] == 1
+        pairs.append((int(r["trace_out"][0]), int(r["trace_in"][0])))
+        objs.append(float(r["trace_obj"][0]))
+        if i + 1 < n_follow:
+            gpu_scores.append(scores_of(s))
+    fol = None
+    errs = []
+    for i in range(n_follow):     # one oracle iteration at a time, so that each finished step is reported
+        fol = orc.local_search(Hh, Gh, c0, sorted(st.groups), cfg.p, cfg.q, 1, follow=[pairs[i]], start=st, keep_scores=True)
+        x = fol.trace[0]
+        # at the start: 2e-5 (+ the magnified rounding of the stored weights); after swaps 5e-5, the bar of every state that
+        # the low-rank updates have touched
+        errs.append(check_scores(gpu_scores[i][0], gpu_scores[i][1], x.rem_all, x.add_all, tol=2e-5 if i == 0 else 5e-5,
+                                 tol_add=tol_add0 if i == 0 else None))
+        assert x.deficit_rem <= GAP and x.deficit_add <= GAP, (i, x)
+        assert x.delta < 0, (i, x)
+        assert abs(objs[i] - x.obj_after) <= 1e-5 * abs(x.obj_after), (i, objs[i], x.obj_after)
+        st = fol.state
+        st.groups, order = sorted(st.groups), np.argsort(st.groups)
+        rows_o = orc.rows_of(order, cfg.q)
+        st.P, st.What_K = st.P[np.ix_(rows_o, rows_o)], st.What_K[rows_o]
+        progress(f"{name}: swap {i} {pairs[i]} follows the oracle, scores off by {errs[-1][0]:.2e} / {errs[-1][1]:.2e}")
+    return pairs, st, errs
+
+
+def sampled_iterations(cfg, Hh, Gh, c0, K0, r, sampled, name):
+    """Single iterations further along the library's trajectory, each from a fresh oracle state of the kept set it had at
+    that point (Section 4.2 selection rule; Proposition 4.1 Case 3 for the exact change)."""
+    pairs = list(zip(r["trace_out"].tolist(), r["trace_in"].tolist()))
+    kept, done = set(K0), 0
+    for i in sampled:
+        for g, j in pairs[done:i]:
+            kept.remove(g)
+            kept.add(j)
+        done = i
+        x = orc.local_search(Hh, Gh, c0, sorted(kept), cfg.p, cfg.q, 1, follow=[pairs[i]]).trace[0]
+        assert x.deficit_rem <= GAP and x.deficit_add <= GAP, (i, x)
+        assert x.delta < 0, (i, x)
+        assert abs(r["trace_obj"][i] - x.obj_after) <= 1e-5 * abs(x.obj_after), (i, r["trace_obj"][i], x.obj_after)
+        if i > 0:
+            assert abs(r["trace_obj"][i - 1] - (x.obj_after - x.delta)) <= 1e-5 * abs(x.obj_after)      # the objective it started from
+        progress(f"{name}: iteration {i} {pairs[i]} follows the oracle")
+
+
+def test_cfg3_full_layer_search_against_oracle():
+    """cfg3 whole: all 262144 calibration rows, the full budget of 2000 swaps.  The Gram is checked on sampled tiles; the
+    oracle then starts from the library's H and G widened to float64 (its own Gram of 262144 x 8192 would take minutes) and
+    checks the state, every score at the first states, the first swaps one after the other and single swaps up to the last."""
+    cfg = inp.CONFIGS["cfg3"]
+    X = gen_on_gpu(cfg)
+    W = inp.gen_W(cfg, DEV)
+    s = make_solver(cfg, X, W)
+    s.osscar_gram(X[:100000])
+    s.osscar_gram(X[100000:], True, W, cfg.lam_abs, cfg.lam_rel)
+    lam, c0 = s.osscar_get_scalars()
+    H = T(s, "T_H")
+    sampled_tiles_of_gram(cfg, X, H, lam)
+    del X
+    Hh, Gh = H.cpu().double().numpy(), T(s, "T_G").cpu().double().numpy()
+    assert rel(Gh, Hh @ W.cpu().double().numpy()) < 1e-6
+    del H
+    K0 = orc.magnitude_support(W.cpu().double().numpy(), cfg.p, cfg.q, cfg.k)
+    obj0 = s.osscar_init_support()
+    assert T(s, "T_KEPT").cpu().tolist() == K0
+    pairs, _, errs = search_in_legs_against_oracle(cfg, s, Hh, Gh, c0, K0, obj0, 6, "cfg3")
+    # the whole budget in one call, as the benchmark runs it: the same first swaps, then sampled iterations up to the last
+    obj0b = s.osscar_init_support()
+    assert obj0b == obj0
+    r = s.osscar_local_search(cfg.swaps)
+    assert r["accepted"] == cfg.swaps and np.all(np.diff(np.concatenate([[obj0], r["trace_obj"]])) < 0)
+    assert list(zip(r["trace_out"].tolist(), r["trace_in"].tolist()))[:len(pairs)] == pairs
+    cnt = s.osscar_get_counters()
+    sampled_iterations(cfg, Hh, Gh, c0, K0, r, [500, 1000, 1500, cfg.swaps - 1], "cfg3")
+    What, support, obj = s.osscar_backsolve()
+    Wo, objo = orc.solve_support(Hh, Gh, c0, support.tolist(), cfg.q)
+    assert rel(What.cpu().double().numpy(), Wo) < 1e-4
+    assert abs(obj - objo) <= 1e-4 * objo and abs(r["obj_final"] - objo) <= 1e-4 * objo
+    print(f"cfg3 whole: scores vs oracle {max(e[0] for e in errs):.2e} / {max(e[1] for e in errs):.2e}; {cfg.swaps} swaps, "
+          f"obj {obj0:.6g} -> {obj:.6g}; counters {cnt}; tracked vs solved {abs(r['obj_final'] - objo) / objo:.2e}")
+    s.close()
+
+
 @pytest.mark.parametrize("name,max_follow", [("cfg2", 500), ("cfg4", 200)])
 def test_whole_layer_against_oracle(name, max_follow):
     cfg = inp.CONFIGS[name]
@@ -440,16 +600,7 @@ def test_cfg5_bench_configuration_sampled():
     lam, c0 = s.osscar_get_scalars()
     H = T(s, "T_H")
     # (1) tiles of H: 6 column blocks of 32 columns from the generator on the CPU, all 36 block pairs, float64
-    rng = np.random.default_rng(5)
-    starts = sorted(int(v) for v in rng.choice(cfg.d1 // 32, size=6, replace=False) * 32)
-    cols = torch.cat([torch.arange(a, a + 32) for a in starts])
-    Xs = torch.cat([inp.gen_X(cfg, r0, 32768, cols=cols).double() for r0 in range(0, cfg.n, 32768)]).numpy()
-    Hs = Xs.T @ Xs
-    assert torch.equal(X[:, cols.to(DEV)].cpu().double(), torch.from_numpy(Xs))   # same bits on both devices
-    Hg = H[cols.to(DEV)][:, cols.to(DEV)].cpu().double().numpy()
-    ds = np.sqrt(np.diag(Hs))
-    off = Hg - Hs - lam * np.eye(len(cols))
-    assert np.max(np.abs(off) / np.outer(ds, ds)) < 1e-6
+    cols = sampled_tiles_of_gram(cfg, X, H, lam)
     # lambda: mean diag of X^T X from the GPU's own diagonal, and the sampled diagonal agrees with the oracle
     diag = torch.diagonal(H).double()
     assert abs(lam - cfg.lam_rel * (diag.mean().item() - lam)) <= 1e-6 * lam
@@ -463,9 +614,18 @@ def test_cfg5_bench_configuration_sampled():
     K0 = orc.magnitude_support(W.cpu().double().numpy(), cfg.p, cfg.q, cfg.k)
     obj0 = s.osscar_init_support()
     assert T(s, "T_KEPT").cpu().tolist() == K0
-    # (3) search: monotone objective, all indices valid, tracked objective equals the fresh solve
-    r = s.osscar_local_search(400)
-    assert r["accepted"] == 400
+    # (2b) the state, all 28672 scores and the first swaps against the oracle, which starts from the library's H and G widened
+    # to float64 (one oracle iteration at this size is a minute of float64 matrix products on the host)
+    Hh, Gh = T(s, "T_H").cpu().double().numpy(), T(s, "T_G").cpu().double().numpy()
+    pairs, _, errs = search_in_legs_against_oracle(cfg, s, Hh, Gh, c0, K0, obj0, 3, "cfg5")
+    del Hh, Gh
+    # (3) search, the whole budget in one call as the benchmark runs it: the same first swaps, monotone objective, all
+    # indices valid, tracked objective equals the fresh solve
+    assert s.osscar_init_support() == obj0
+    r = s.osscar_local_search(cfg.swaps)
+    assert r["accepted"] == cfg.swaps
+    assert list(zip(r["trace_out"].tolist(), r["trace_in"].tolist()))[:len(pairs)] == pairs
+    progress(f"cfg5: {cfg.swaps} swaps, counters {s.osscar_get_counters()}")
     trace = np.concatenate([[obj0], r["trace_obj"]])
     assert np.all(np.diff(trace) < 0)
     kept = set(K0)
@@ -500,5 +660,5 @@ def test_cfg5_bench_configuration_sampled():
     eye = torch.zeros_like(I_s)
     eye[torch.arange(rows_s.numel(), device=DEV), rows_s] = 1.0
     assert (I_s - eye).abs().max().item() < 1e-3
-    print(f"cfg5: obj {obj0:.6g} -> {obj:.6g} after 400 swaps; timers {s.osscar_get_timers()}")
+    print(f"cfg5: obj {obj0:.6g} -> {obj:.6g} after {cfg.swaps} swaps; timers {s.osscar_get_timers()}")
     s.close()

@@ -56,7 +56,7 @@ SMALL = {
 
 class Case:
     def __init__(self, name):
-        self.cfg = cfg = SMALL[name]()
+        self.cfg = cfg = SMALL[name]() if isinstance(name, str) else name
         self.X, self.W = inp.gen_X(cfg), inp.gen_W(cfg)
         self.Xd, self.Wd = self.X.double().numpy(), self.W.double().numpy()
         self.H, self.G, self.c0, self.lam = orc.gram(self.Xd, self.Wd, cfg.lam_abs, cfg.lam_rel)
@@ -159,9 +159,10 @@ def test_initial_state_and_scores(name):
 
 
 # ------------------------------------------------------------------------------------------ search
-def check_trajectory(c, r, rel_tol=0.0, always=False, exact_in=False):
+def check_trajectory(c, r, rel_tol=0.0, always=False, exact_in=False, tol_obj=1e-5, tol_score=0.0):
     """The library's trajectory replayed by the oracle: every choice within GAP of the oracle's best, every
-    applied swap improving, the stop justified, the objective trace equal to 1e-6."""
+    applied swap improving, the stop justified, the objective trace equal to tol_obj.  tol_score: relative error granted to
+    the scores behind the gaps that the library reports (a gap is the difference of two scores over one of them)."""
     cfg = c.cfg
     pairs = list(zip(r["trace_out"].tolist(), r["trace_in"].tolist()))
     acc = pairs[: r["accepted"]]
@@ -181,11 +182,11 @@ def check_trajectory(c, r, rel_tol=0.0, always=False, exact_in=False):
         assert x.deficit_rem <= GAP and x.deficit_add <= GAP, (i, x)
         if not always:
             assert x.delta < 0, (i, x)
-        assert abs(r["trace_obj"][i] - x.obj_after) <= 1e-5 * abs(x.obj_after), (i, r["trace_obj"][i], x.obj_after)
+        assert abs(r["trace_obj"][i] - x.obj_after) <= tol_obj * abs(x.obj_after), (i, r["trace_obj"][i], x.obj_after)
         # the gaps the library reports are the oracle's gaps (loosely: they are differences of close numbers)
         for gg, go in ((r["trace_gap"][i][0], x.gap_rem), (r["trace_gap"][i][1], x.gap_add)):
             if np.isfinite(go) and go > 1e-3:
-                assert abs(gg - go) <= 1e-2 * go
+                assert abs(gg - go) <= 1e-2 * go + 2 * tol_score
     if not always and r["iters"] > r["accepted"]:
         # the rejected pair: the oracle, at the same state, also finds that its best pair does not improve
         # (or the library's rejected pair was within GAP of the oracle's best and its delta is >= 0)
@@ -193,7 +194,7 @@ def check_trajectory(c, r, rel_tol=0.0, always=False, exact_in=False):
         delta, _ = orc.swap_delta(fol.state, c.H, c.G, g, j, cfg.q)
         obj = c.c0 + 2 * fol.state.f
         assert delta >= -1e-7 * obj, (delta, obj)
-    assert abs(r["obj_final"] - fol.obj_final) <= 1e-5 * fol.obj_final
+    assert abs(r["obj_final"] - fol.obj_final) <= tol_obj * fol.obj_final
     return fol
 
 
@@ -218,6 +219,41 @@ def test_search_follows_the_oracle(name):
     dp = np.sqrt(np.diag(st.P))
     assert np.max(np.abs(T(s, "T_P") - st.P) / np.outer(dp, dp)) < 5e-5
     assert rel(T(s, "T_B"), st.What_K) < 5e-5
+    s.close()
+
+
+def scaled_condition(c):
+    rows = orc.rows_of(c.K0, c.cfg.q)
+    d = np.sqrt(np.diag(c.H))[rows]
+    return float(np.linalg.cond(c.H[np.ix_(rows, rows)] / np.outer(d, d)))
+
+
+@pytest.mark.parametrize("xd,seed", [("bf16", 1000), ("bf16", 1017), ("bf16", 1034), ("f32", 1000), ("f32", 1051), ("f32", 1085)])
+def test_ill_conditioned_layers_follow_the_oracle(xd, seed):
+    """A harsher recipe than the benchmark layers: FFN-shaped with heavy columns AND mix = 0.3, so that a heavy column
+    leaks into its neighbour and the diagonally scaled H_KK reaches condition numbers of 1e3 to 1.4e5 (the benchmark recipes
+    stay below 1e3).  The bars on the choices (within 1e-5 of the oracle's best at every state), on the final kept set and
+    on the final weights and objective (1e-4) are those of every other case.  The library's float32 copy of H (relative
+    rounding eps: 6e-8, or 2.5e-7 from the bf16 matrix-core Gram) is itself a perturbation that moves every solution of the
+    kept system, and with it every score, by up to eps * cond relative: that is what the reported gaps are granted here.  The
+    objective TRACKED through the swaps, which is stationary in the weights, is still held to 1e-5 while the condition
+    number stays below 1e4, and to eps * cond beyond."""
+    cfg = inp.scaled(inp.CONFIGS["cfg3"], p=328, m=136, n=3000, k=160, swaps=60, mix=0.3, seed=seed).replace(x_dtype=xd)
+    c = Case(cfg)
+    s = c.solver()
+    c.gram(s)
+    s.osscar_init_support()
+    r = s.osscar_local_search(cfg.swaps)
+    cond = scaled_condition(c)
+    eps_h = 2.5e-7 if xd == "bf16" else 6e-8
+    tol_obj = 1e-5 if cond < 1e4 else eps_h * cond
+    print(f"ill-conditioned {xd} seed {seed}: scaled cond {cond:.2e}, {r['accepted']} swaps, sweep residual {s.osscar_get_timers()[11]:.2e}, "
+          f"tracked-objective bar {tol_obj:.1e}")
+    fol = check_trajectory(c, r, tol_obj=tol_obj, tol_score=eps_h * cond)
+    What, support, obj = s.osscar_backsolve()
+    assert support.tolist() == fol.support
+    Wo, objo = orc.solve_support(c.H, c.G, c.c0, fol.support, cfg.q)
+    assert rel(What.cpu().double().numpy(), Wo) < 1e-4 and abs(obj - objo) <= 1e-4 * objo
     s.close()
 
 
@@ -284,9 +320,9 @@ def test_search_variants(name):
     s.osscar_init_support()
     r0 = s.osscar_local_search(c.cfg.swaps, rel_tol=0.9)
     assert r0["accepted"] == 0 and r0["iters"] == 1
-    # the diagnostics: twelve slots, times of the calls made are positive, slot 11 is the residual of the sweep inverse
+    # the diagnostics: sixteen slots, times of the calls made are positive, slot 11 is the residual of the sweep inverse
     tm = s.osscar_get_timers()
-    assert len(tm) == 12 and all(np.isfinite(tm)) and all(t >= 0 for t in tm)
+    assert len(tm) == 16 and all(np.isfinite(tm)) and all(t >= 0 for t in tm)
     assert tm[1] > 0 and tm[2] > 0 and tm[3] > 0 and 0 <= tm[11] < 1e-3
     s.close()
 
@@ -328,6 +364,46 @@ def test_forced_swaps_keep_the_state_exact(name):
     s.close()
 
 
+def test_long_searches_cross_flushes_misses_and_pauses_under_oracle_control():
+    """Single-row groups on the default (delayed-update) path, every swap replayed by the oracle: a medium layer whose 300
+    swaps span several flush intervals (64 swaps each) and meet pivots whose products were not computed ahead, and a small
+    layer under Algorithm 1's apply-every-pair rule, where groups come back while still pending and the kernels must stop
+    for a flush ('pause').  The library's own counters show that these paths were taken."""
+    pkg = _pkg()
+    # (1) 300 accepted swaps, acceptance test on
+    c = Case(inp.scaled(inp.CONFIGS["cfg3"], p=1024, m=260, n=6000, k=512, swaps=300))
+    s = c.solver()
+    c.gram(s)
+    s.osscar_init_support()
+    r = s.osscar_local_search(c.cfg.swaps)
+    cnt = s.osscar_get_counters()
+    print("p=1024, 300 swaps:", r["accepted"], "accepted;", cnt)
+    assert r["accepted"] >= 200
+    assert cnt["flushes"] >= 3 and cnt["lookahead_misses"] >= 1 and cnt["iters"] == r["iters"]
+    fol = check_trajectory(c, r)
+    What, support, obj = s.osscar_backsolve()
+    assert support.tolist() == fol.support
+    Wo, objo = orc.solve_support(c.H, c.G, c.c0, fol.support, c.cfg.q)
+    assert rel(What.cpu().double().numpy(), Wo) < 1e-4 and abs(obj - objo) <= 1e-4 * objo
+    st = orc.init_state(c.H, c.G, fol.support, c.cfg.q)
+    dp = np.sqrt(np.diag(st.P))
+    assert np.max(np.abs(T(s, "T_P") - st.P) / np.outer(dp, dp)) < 5e-5
+    assert rel(T(s, "T_B"), st.What_K) < 5e-5
+    s.close()
+    # (2) every selected pair applied, 80 iterations on 24 groups: groups return while pending
+    c = Case(inp.scaled(inp.CONFIGS["cfg1"], p=24, m=16, n=200, k=12, swaps=80, mix=0.8))
+    s = c.solver()
+    c.gram(s)
+    s.osscar_init_support()
+    r = s.osscar_local_search(80, flags=pkg.OSSCAR_SEARCH_ALWAYS_ACCEPT)
+    cnt = s.osscar_get_counters()
+    print("p=24, 80 forced swaps:", cnt)
+    assert r["iters"] == r["accepted"] == 80
+    assert cnt["pauses"] >= 1 and cnt["flushes"] >= cnt["pauses"]
+    check_trajectory(c, r, always=True)
+    s.close()
+
+
 def test_delayed_update_search_equals_eager_search():
     # groups of one row: the delayed-update search must take exactly the swaps of the eager search and leave the
     # same state (the flush interval of 64 swaps is crossed several times, and 'pause' flushes are exercised by the
@@ -346,10 +422,12 @@ def test_delayed_update_search_equals_eager_search():
         s.osscar_init_support()
         l = s.osscar_local_search(swaps, 0.0, B.OSSCAR_SEARCH_ALWAYS_ACCEPT)
         assert e["iters"] == l["iters"] == swaps
-        # identical choices while both searches see a clear winner (the two accumulate rounding differently)
+        # identical choices while both searches see a clear winner (the two accumulate rounding differently); if they part
+        # at a tie, everything up to there must still agree
         for i in range(swaps):
             if (e["trace_out"][i], e["trace_in"][i]) != (l["trace_out"][i], l["trace_in"][i]):
-                assert min(e["trace_gap"][i]) < 1e-4, (i, e["trace_gap"][i])
+                assert min(e["trace_gap"][i]) <= GAP, (i, e["trace_gap"][i])
+                assert np.allclose(e["trace_obj"][:i], l["trace_obj"][:i], rtol=1e-6, atol=0)
                 break
         else:
             assert rel(T(s, "T_P"), Pe) < 1e-5 and rel(T(s, "T_B"), Be) < 1e-5
@@ -365,11 +443,49 @@ def test_delayed_update_search_equals_eager_search():
         assert n["iters"] == swaps
         for i in range(swaps):
             if (n["trace_out"][i], n["trace_in"][i]) != (l["trace_out"][i], l["trace_in"][i]):
-                assert min(l["trace_gap"][i]) < 1e-4, (i, l["trace_gap"][i])
+                assert min(l["trace_gap"][i]) <= GAP, (i, l["trace_gap"][i])
+                assert np.allclose(n["trace_obj"][:i], l["trace_obj"][:i], rtol=1e-6, atol=0)
                 break
         else:
             assert abs(n["obj_final"] - l["obj_final"]) <= 1e-6 * abs(l["obj_final"])
         s.close()
+
+
+# ------------------------------------------------------------------------------------------ run-to-run reproducibility
+def _full_run(c, swaps, target=None):
+    """Everything the path returns, as raw bytes: H, G, scalars, initial state and scores, the search's traces, the state
+    after it, the final weights."""
+    cfg = c.cfg
+    s = c.solver(swaps)
+    n = cfg.n
+    c.gram(s, cuts=[0, n // 3 + 1, n // 2, n])                 # several chunks: the float64 accumulation across them too
+    out = [T(s, "T_H").tobytes(), T(s, "T_G").tobytes(), np.array(s.osscar_get_scalars()).tobytes()]
+    out.append(np.float64(s.osscar_init_support()).tobytes())
+    out += [T(s, k).tobytes() for k in ("T_P", "T_B", "T_V", "T_R", "T_REM", "T_ADD")]
+    r = s.osscar_local_search(swaps)
+    out += [r[k].tobytes() for k in ("trace_out", "trace_in", "trace_gap", "trace_obj")]
+    out += [T(s, k).tobytes() for k in ("T_P", "T_B", "T_REM", "T_ADD")]
+    What, support, obj = s.osscar_backsolve()
+    out += [What.cpu().numpy().tobytes(), support.tobytes(), np.float64(obj).tobytes()]
+    s.close()
+    return out, r["accepted"]
+
+
+@pytest.mark.parametrize("name", ["cfg2s", "cfg3s", "cfg4s", "cfg5odd", "long"])
+def test_two_runs_give_identical_bits(name):
+    """No result depends on the order in which workgroups happen to run: sums are taken in fixed orders, and where atomic
+    adds are used every element receives one addition per launch.  Two complete runs of the path on the same inputs must
+    therefore agree bit for bit -- the Gram over several chunks, the state, every score, the search's choices, gaps and
+    objective trace (across flushes on two streams for the long case), and the final weights.  A difference here means a
+    race or an order-dependent reduction."""
+    c = Case(inp.scaled(inp.CONFIGS["cfg3"], p=1024, m=264, n=6000, k=512, swaps=200)) if name == "long" else case(name)
+    a, na = _full_run(c, c.cfg.swaps)
+    b, nb = _full_run(c, c.cfg.swaps)
+    assert na == nb and na >= 1
+    names = ["H", "G", "scalars", "obj0", "P", "B", "V", "R", "REM", "ADD", "trace_out", "trace_in", "trace_gap", "trace_obj",
+             "P after", "B after", "REM after", "ADD after", "What", "support", "obj"]
+    for label, x, y in zip(names, a, b):
+        assert x == y, label
 
 
 # ------------------------------------------------------------------------------------------ set_quadratic

@@ -652,3 +652,26 @@ def test_greedy_record_gap_and_deficit_on_a_diagonal_form():
     assert forced.trace[1].deficit == 0.0                       # 2 is now the cheapest of what is left
     last = orc.greedy_from_dense(H, G, c0, p, 1, 0, 5).trace[0]
     assert last.gap == np.inf                                   # nothing left out
+
+
+def test_search_from_a_given_start_state_is_the_same_search():
+    p, q, m, n, k = 14, 1, 4, 90, 6
+    X, W, H, G, c0, lam = make_problem(p, q, m, n, 77, corr=1.3)
+    K0 = orc.magnitude_support(W, p, q, k)
+    a = orc.local_search(H, G, c0, K0, p, q, 10)
+    st = orc.init_state(H, G, sorted(K0), q)
+    b = orc.local_search(H, G, c0, K0, p, q, 10, start=st)
+    assert [(x.g_out, x.j_in, x.delta) for x in a.trace] == [(x.g_out, x.j_in, x.delta) for x in b.trace]
+    assert st.groups == sorted(K0) and np.array_equal(st.P, orc.init_state(H, G, sorted(K0), q).P)      # the caller's state is not touched
+    # keep_scores: the arrays of each record are the scores at the state its iteration started from
+    c = orc.local_search(H, G, c0, K0, p, q, 10, keep_scores=True)
+    assert [(x.g_out, x.j_in) for x in c.trace] == [(x.g_out, x.j_in) for x in a.trace]
+    kept = sorted(K0)
+    for x in c.trace:
+        stx = orc.init_state(H, G, kept, q)
+        assert np.allclose(x.rem_all, orc.removal_scores(stx, p, q), rtol=1e-9) and np.allclose(x.add_all, orc.addition_scores(stx, H, G, p, q), rtol=1e-9)
+        assert x.rem_all[x.g_out] == x.rem and x.add_all[x.j_in] == x.add
+        if x.accepted:
+            kept = sorted(set(kept) - {x.g_out} | {x.j_in})
+    with pytest.raises(ValueError):
+        orc.local_search(H, G, c0, K0[:-1] + [max(set(range(p)) - set(K0))], p, q, 1, start=st)
