@@ -801,11 +801,11 @@ __global__ __launch_bounds__(256) void cand_gather_kernel(LazyPtrs L, const floa
 // The look-ahead product GbT[s, i] = <Z0[cand[s], :], Z0[i, :]> on the bf16 matrix cores, bound by one read of Z0.
 // Every float32 number is cut into three bf16 pieces (each the round-to-nearest bf16 of what the pieces before it leave;
 // together 24 significand bits) and the six products of weight >= 2^-16 run as v_mfma_f32_32x32x16_bf16: products of bf16
-// numbers are exact in float32, sums run in float32 over 1024 columns and in float64 registers across them, and every
-// element of GbT is written once by the one wave that owns it (no atomics: the result does not depend on scheduling).
-// The candidate rows are cut and laid out in operand order once per flush (la_pack_kernel, a few MB that stay in L2);
-// the rows of Z0 are cut in registers as they stream in, each lane holding 8 consecutive columns of one row, which is
-// the operand layout as it stands: Z0 never passes through shared memory.
+// numbers are exact in float32, the sums inside the matrix cores restart every 1024 columns (added, round to nearest,
+// to a second float32 set), and every element of GbT is written once by the one wave that owns it (no atomics: the
+// result does not depend on scheduling).  The candidate rows are cut and laid out in operand order once per flush
+// (la_pack_kernel, a few MB that stay in L2); the rows of Z0 are cut in registers, each lane taking 8 consecutive
+// columns of one row from the tile in shared memory, which is the operand layout as it stands.
 //   one workgroup = 128 rows of Z0 x 128 candidates; wave w owns rows 32 w .. 32 w + 31 as four 32 x 32 tiles.
 // ------------------------------------------------------------------------------------------------
 typedef float la_f16v __attribute__((ext_vector_type(16)));
@@ -857,61 +857,62 @@ __global__ __launch_bounds__(256) void la_pack_kernel(LazyPtrs L, const float* _
 }
 
 // GbT[(sb * 128 + s) * d1 + i] for i in [128 blockIdx.x, +128), s in [0, 128), sb = blockIdx.y.  m % 8 == 0.
-__global__ __launch_bounds__(256, 1) void la_product_kernel(const uint4* __restrict__ ZcP, const float* __restrict__ Z0, int d1, int m,
+// Per stage of 32 columns the workgroup copies its 128 x 32 tile of Z0 (each row's 128 bytes by eight neighbouring lanes)
+// and the candidates' packed pieces into shared memory; the next stage's loads are in flight while this one is
+// multiplied.  Two workgroups share a compute unit.
+constexpr int LA_ZLD = LA_STG + 4;           // row stride of the Z0 tile in shared memory (floats)
+__global__ __launch_bounds__(256, 2) void la_product_kernel(const uint4* __restrict__ ZcP, const float* __restrict__ Z0, int d1, int m,
                                                              int nstg, double* __restrict__ GbT) {
-  __shared__ uint4 lds[2][LA_PK];            // 2 x 24 KB
+  __shared__ uint4 lzc[LA_PK];                                 // 24 KB
+  __shared__ __attribute__((aligned(16))) float lz0[128 * LA_ZLD];   // 18 KB
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, sb = blockIdx.y;
-  const int i_lane = blockIdx.x * 128 + wave * 32 + (lane & 31);
-  const float* zrow = Z0 + (int64_t)(i_lane < d1 ? i_lane : d1 - 1) * m + (lane >> 5) * 8;      // rows past the end: clamped, never stored
+  const int i0 = blockIdx.x * 128;
   const uint4* src = ZcP + (int64_t)sb * nstg * LA_PK + tid;
-  la_f16v acc[4];
-  double dacc[4][16];
+  // global -> shared assignment of the Z0 tile: thread t takes 4 columns (t % 8) * 4 of rows t / 8 + 32 j, j < 4
+  const int lr = tid >> 3, lk = (tid & 7) * 4;
+  auto rowp = [&](int j) { const int row = i0 + lr + 32 * j; return Z0 + (int64_t)(row < d1 ? row : d1 - 1) * m + lk; };
+  const float *zsrc0 = rowp(0), *zsrc1 = rowp(1), *zsrc2 = rowp(2), *zsrc3 = rowp(3);      // rows past the end: clamped, never stored
+  la_f16v acc[4], acc2[4];
 #pragma unroll
   for (int t = 0; t < 4; t++)
 #pragma unroll
-    for (int r = 0; r < 16; r++) { acc[t][r] = 0.f; dacc[t][r] = 0.0; }
-  uint4 zc[6];
-  float4 z0[4];
-  auto gload = [&](int stage) {
-    const uint4* p = src + (int64_t)stage * LA_PK;
-#pragma unroll
-    for (int u = 0; u < 6; u++) zc[u] = p[256 * u];
-#pragma unroll
-    for (int ks = 0; ks < 2; ks++) {
-      const int c = stage * LA_STG + ks * 16 + (lane >> 5) * 8;
-      if (c + 8 <= m) {
-        z0[2 * ks] = *reinterpret_cast<const float4*>(zrow + stage * LA_STG + ks * 16);
-        z0[2 * ks + 1] = *reinterpret_cast<const float4*>(zrow + stage * LA_STG + ks * 16 + 4);
-      } else {
-        z0[2 * ks] = float4{0.f, 0.f, 0.f, 0.f}; z0[2 * ks + 1] = float4{0.f, 0.f, 0.f, 0.f};
-      }
-    }
-  };
-  gload(0);
+    for (int r = 0; r < 16; r++) { acc[t][r] = 0.f; acc2[t][r] = 0.f; }
+  uint4 zc0, zc1, zc2, zc3, zc4, zc5;
+  float4 zt0, zt1, zt2, zt3;
+#define OSSCAR_LA_GLOAD(stage_)                                                                              \
+  {                                                                                                          \
+    const uint4* p_ = src + (int64_t)(stage_) * LA_PK;                                                       \
+    zc0 = p_[0]; zc1 = p_[256]; zc2 = p_[512]; zc3 = p_[768]; zc4 = p_[1024]; zc5 = p_[1280];                \
+    const bool in_ = (stage_) * LA_STG + lk + 4 <= m;                                                        \
+    const float4 z_ = float4{0.f, 0.f, 0.f, 0.f};                                                            \
+    zt0 = in_ ? *reinterpret_cast<const float4*>(zsrc0 + (stage_) * LA_STG) : z_;                            \
+    zt1 = in_ ? *reinterpret_cast<const float4*>(zsrc1 + (stage_) * LA_STG) : z_;                            \
+    zt2 = in_ ? *reinterpret_cast<const float4*>(zsrc2 + (stage_) * LA_STG) : z_;                            \
+    zt3 = in_ ? *reinterpret_cast<const float4*>(zsrc3 + (stage_) * LA_STG) : z_;                            \
+  }
+  OSSCAR_LA_GLOAD(0);
   int since = 0;
+  const float* myrow = lz0 + (wave * 32 + (lane & 31)) * LA_ZLD + (lane >> 5) * 8;
   for (int stage = 0; stage < nstg; stage++) {
-    const int buf = stage & 1;
-    uint4* dst = &lds[buf][tid];
-#pragma unroll
-    for (int u = 0; u < 6; u++) dst[256 * u] = zc[u];
-    // this stage's rows of Z0 leave the load registers before the next stage's loads are issued into them
-    uint4 b1[2], b2[2], b3[2];
-#pragma unroll
-    for (int ks = 0; ks < 2; ks++) {
-      const float v[8] = {z0[2 * ks].x, z0[2 * ks].y, z0[2 * ks].z, z0[2 * ks].w, z0[2 * ks + 1].x, z0[2 * ks + 1].y, z0[2 * ks + 1].z, z0[2 * ks + 1].w};
-      la_split3(v, b1[ks], b2[ks], b3[ks]);
-    }
+    __syncthreads();                                           // the previous stage has been read by every wave
+    lzc[tid] = zc0; lzc[tid + 256] = zc1; lzc[tid + 512] = zc2; lzc[tid + 768] = zc3; lzc[tid + 1024] = zc4; lzc[tid + 1280] = zc5;
+    *reinterpret_cast<float4*>(lz0 + lr * LA_ZLD + lk) = zt0;
+    *reinterpret_cast<float4*>(lz0 + (lr + 32) * LA_ZLD + lk) = zt1;
+    *reinterpret_cast<float4*>(lz0 + (lr + 64) * LA_ZLD + lk) = zt2;
+    *reinterpret_cast<float4*>(lz0 + (lr + 96) * LA_ZLD + lk) = zt3;
     __syncthreads();
-    if (stage + 1 < nstg) gload(stage + 1);
-    const uint4* pa = lds[buf];
+    if (stage + 1 < nstg) OSSCAR_LA_GLOAD(stage + 1);
 #pragma unroll
     for (int ks = 0; ks < 2; ks++) {
+      const float4 va = *reinterpret_cast<const float4*>(myrow + ks * 16), vb = *reinterpret_cast<const float4*>(myrow + ks * 16 + 4);
+      const float v[8] = {va.x, va.y, va.z, va.w, vb.x, vb.y, vb.z, vb.w};
+      uint4 b1, b2, b3;
+      la_split3(v, b1, b2, b3);
+      const la_bf8 f1 = *reinterpret_cast<const la_bf8*>(&b1), f2 = *reinterpret_cast<const la_bf8*>(&b2), f3 = *reinterpret_cast<const la_bf8*>(&b3);
       const int off = (ks * 2 + (lane >> 5)) * 128 + (lane & 31);
-      const la_bf8 f1 = *reinterpret_cast<const la_bf8*>(&b1[ks]), f2 = *reinterpret_cast<const la_bf8*>(&b2[ks]),
-                   f3 = *reinterpret_cast<const la_bf8*>(&b3[ks]);
 #pragma unroll
       for (int t = 0; t < 4; t++) {
-        uint4 q1 = pa[off + t * 32], q2 = pa[512 + off + t * 32], q3 = pa[1024 + off + t * 32];
+        uint4 q1 = lzc[off + t * 32], q2 = lzc[512 + off + t * 32], q3 = lzc[1024 + off + t * 32];
         const la_bf8 a1 = *reinterpret_cast<la_bf8*>(&q1), a2 = *reinterpret_cast<la_bf8*>(&q2), a3 = *reinterpret_cast<la_bf8*>(&q3);
         // smallest terms first
         acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a3, f1, acc[t], 0, 0, 0);
@@ -922,24 +923,26 @@ __global__ __launch_bounds__(256, 1) void la_product_kernel(const uint4* __restr
         acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, f1, acc[t], 0, 0, 0);
       }
     }
-    if (++since == 1024 / LA_STG || stage + 1 == nstg) {
+    if (++since == 1024 / LA_STG && stage + 1 < nstg) {       // the sums inside the matrix cores never span more than 1024 columns
       since = 0;
 #pragma unroll
       for (int t = 0; t < 4; t++)
 #pragma unroll
-        for (int r = 0; r < 16; r++) { dacc[t][r] += (double)acc[t][r]; acc[t][r] = 0.f; }
+        for (int r = 0; r < 16; r++) { acc2[t][r] += acc[t][r]; acc[t][r] = 0.f; }
     }
   }
   // C layout of the 32 x 32 tile: register r = rr*4 + r3 holds row rr*8 + (lane/32)*4 + r3 (a candidate), column lane%32 (a row of Z0)
+  const int i_lane = i0 + wave * 32 + (lane & 31);
   if (i_lane < d1) {
 #pragma unroll
     for (int t = 0; t < 4; t++)
 #pragma unroll
       for (int r = 0; r < 16; r++) {
         const int sl = t * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        GbT[(int64_t)(sb * 128 + sl) * d1 + i_lane] = dacc[t][r];
+        GbT[(int64_t)(sb * 128 + sl) * d1 + i_lane] = (double)acc[t][r] + (double)acc2[t][r];
       }
   }
+#undef OSSCAR_LA_GLOAD
 }
 
 // mode 0: half of the slots for kept rows, half for the others; 1: all for kept rows (removal-only loops); 2: none
