@@ -256,6 +256,26 @@ int32_t osscar_debug_gemm_log_read(double* out_host, int32_t capacity);
  * the schedule, or -1 for a bad d1.  Workgroup i runs on XCD i % 8. */
 int32_t osscar_debug_tile_schedule(int64_t d1, int32_t* out_host, int32_t capacity);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): the quadratic form of one small layer in one call, with no context and no workspace.  Same result
+ * as osscar_gram(ctx, X, n, ldx, finalize = 1, W, ...) followed by reading H, G, lambda and c0 back:
+ *   H = X^T X + lambda I (float32, d1 x d1, both triangles), lambda = lambda_abs + lambda_rel * mean(diag(X^T X)),
+ *   G = H W (float32, d1 x m), c0 = Tr(W^T G); products accumulated in float64.
+ * X_dev: dev, row-major n x d1 (leading dimension ldx), dtype x_dtype; W_dev: dev, d1 x m (ldw), dtype w_dtype;
+ * H_dev, G_dev: dev outputs, dense (leading dimensions d1 and m); scalars_dev: dev, 2 float64 = {lambda, c0}.
+ * Everything is enqueued on hip_stream (a hipStream_t, NULL = default stream); the call does not wait for it and
+ * calls no hipMalloc, hipFree or other allocating routine.  What osscar_gram keeps in the caller's workspace meanwhile
+ * (float64 accumulator, float32 W, transposed staging of X) lives in a device array of OSSCAR_STATIC_SCRATCH_BYTES that
+ * every GPU the library runs on holds until the process ends.  Limits: d1, m <= OSSCAR_STATIC_MAX_DIM, any n >= 0;
+ * larger sizes return OSSCAR_ENOMEM.  All calls on one GPU share that array: calls that overlap in time on one GPU
+ * (different streams or host threads) race and must be serialised by the caller.  After a failure
+ * osscar_last_error(NULL) describes it (per host thread). */
+#define OSSCAR_STATIC_MAX_DIM 1024
+#define OSSCAR_STATIC_SCRATCH_BYTES 21037056
+osscar_status osscar_gram_static(const void* X_dev, int64_t n, int64_t ldx, int32_t x_dtype, const void* W_dev, int64_t ldw,
+                                 int32_t w_dtype, int64_t d1, int64_t m, double lambda_abs, double lambda_rel, float* H_dev,
+                                 float* G_dev, double* scalars_dev, void* hip_stream);
+
 /* Description of the last failure: of a context, or (ctx == NULL) of the last failed call on this host thread that takes
  * no context. */
 const char* osscar_last_error(const osscar_ctx* ctx);

@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = ["osscar_workspace_bytes", "osscar_create", "osscar_destroy",
                     "osscar_init_support", "osscar_init_greedy", "osscar_local_search", "osscar_block_search", "osscar_apply_swap", "osscar_backsolve",
                     "osscar_get_tensor", "osscar_get_scalars", "osscar_get_timers", "osscar_get_counters", "osscar_debug_tile_schedule",
                     "osscar_debug_gemm_log", "osscar_debug_gemm_log_read",
-                    "osscar_last_error"]
+                    "osscar_gram_static", "osscar_last_error"]
 
 
 class OsscarError(RuntimeError):
@@ -83,6 +83,7 @@ def load_library():
     lib.osscar_debug_gemm_log.argtypes = [i32]
     lib.osscar_debug_gemm_log_read.restype = C.c_int32
     lib.osscar_debug_gemm_log_read.argtypes = [C.POINTER(dbl), i32]
+    lib.osscar_gram_static.argtypes = [vp, i64, i64, i32, vp, i64, i32, i64, i64, dbl, dbl, vp, vp, vp, vp]
     lib.osscar_debug_tile_schedule.restype = C.c_int32
     lib.osscar_debug_tile_schedule.argtypes = [i64, C.POINTER(i32), i32]
     lib.osscar_last_error.restype = C.c_char_p
@@ -303,3 +304,24 @@ def gemm_log_read(capacity: int = 16384) -> np.ndarray:
     buf = np.zeros((capacity, 5), dtype=np.float64)
     n = load_library().osscar_debug_gemm_log_read(buf.ctypes.data_as(C.POINTER(C.c_double)), capacity)
     return buf[:max(n, 0)].copy()
+
+
+def osscar_gram_static(X: torch.Tensor, W: torch.Tensor, H: torch.Tensor, G: torch.Tensor, scalars: torch.Tensor,
+                       lambda_abs: float = 0.0, lambda_rel: float = 0.0, stream: Optional[torch.cuda.Stream] = None):
+    """The allocation-free Gram of one small layer: X (n x d1), W (d1 x m) in; H (d1 x d1 float32), G (d1 x m float32) and
+    scalars (2 float64: lambda, c0) out, all device tensors the caller made.  Enqueues on `stream` and does not wait."""
+    lib = load_library()
+    assert X.is_cuda and W.is_cuda and X.dim() == 2 and W.dim() == 2 and X.stride(1) == 1 and W.stride(1) == 1
+    d1, m = W.shape
+    assert X.shape[1] == d1
+    assert H.is_cuda and H.dtype == torch.float32 and H.is_contiguous() and tuple(H.shape) == (d1, d1)
+    assert G.is_cuda and G.dtype == torch.float32 and G.is_contiguous() and tuple(G.shape) == (d1, m)
+    assert scalars.is_cuda and scalars.dtype == torch.float64 and scalars.is_contiguous() and scalars.numel() >= 2
+    st = stream if stream is not None else torch.cuda.current_stream(X.device)
+    n = X.shape[0]
+    with torch.cuda.device(X.device):
+        rc = lib.osscar_gram_static(X.data_ptr() if n > 0 else None, n, X.stride(0) if n > 0 else d1, _dtype_code(X.dtype), W.data_ptr(),
+                                    W.stride(0), _dtype_code(W.dtype), d1, m, float(lambda_abs), float(lambda_rel), H.data_ptr(),
+                                    G.data_ptr(), scalars.data_ptr(), C.c_void_p(st.cuda_stream))
+    if rc != 0:
+        raise OsscarError(rc, lib.osscar_last_error(None).decode())
