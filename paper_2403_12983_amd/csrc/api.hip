@@ -191,6 +191,8 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
     L.sel = cv.take<SelRec>((d1 + 31) / 32);
     L.GbT = cv.take<double>((int64_t)(LAZY_NC + LAZY_NS) * d1); L.Zc = cv.take<float>((int64_t)LAZY_NC * m);
     L.ZcP = cv.take<char>((int64_t)LAZY_NC * ((m + 31) / 32 * 32) * 6);
+    L.Epk = cv.take<char>((int64_t)768 * ((d1 + 127) / 128 * 128)); L.Cpk = cv.take<char>((int64_t)768 * ((d1 + 127) / 128 * 128));
+    L.Zpk = cv.take<char>((int64_t)768 * ((m + 127) / 128 * 128));
     L.cslot = cv.take<int32_t>(d1); L.cand = cv.take<int32_t>(LAZY_NC + LAZY_NS); L.tslot = cv.take<int32_t>(LAZY_TM);
     L.misc = cv.take<int32_t>(8); L.lkey = cv.take<double>(2 * 64 * 32); L.lidx = cv.take<int32_t>(2 * 64 * 32);
     L.bB = cv.take<double>(TM * LAZY_BT); L.bX = cv.take<double>(TM * LAZY_BT); L.bU = cv.take<double>(4 * TM * LAZY_BT);
@@ -544,6 +546,7 @@ osscar_status osscar_create(osscar_ctx** out, const osscar_desc* desc, void* wor
     if (hipMemcpy(c->tiles_sym, ts.data(), ts.size() * sizeof(int2), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(c->tiles_rect, tr.data(), tr.size() * sizeof(int2), hipMemcpyHostToDevice) != hipSuccess) { delete c; return OSSCAR_EHIP; }
     c->n_tiles_sym = ts.size(); c->n_tiles_rect = tr.size();
+    c->lazy.tiles_sym = c->tiles_sym; c->lazy.n_tiles_sym = ts.size(); c->lazy.tiles_rect = c->tiles_rect; c->lazy.n_tiles_rect = tr.size();
   }
   c->ev_ok = (hipEventCreate(&c->ev_a) == hipSuccess) && (hipEventCreate(&c->ev_b) == hipSuccess);
   for (int i = 0; i < EV_SAMPLES && c->ev_ok; i++)

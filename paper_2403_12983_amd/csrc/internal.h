@@ -184,6 +184,10 @@ struct LazyPtrs {
   // products of Z0 with the rows of Z0 that are likely to become pivots before the next flush
   double* GbT;      // (LAZY_NC + LAZY_NS) x d1: row s = Z0 Z0[cand[s], :]^T
   float* Zc;        // LAZY_NC x m: the gathered rows (shapes that take the general matrix-product kernel)
+  // flush: E, C0 and ZT cut into three bf16 pieces in matrix-core operand order (768 bytes per padded row / column), and the
+  // tile schedules of the two updates (the Gram kernel's: lower triangle of d1 x d1, all of d1 x m), uploaded at create
+  void* Epk; void* Cpk; void* Zpk;
+  const int2* tiles_sym; size_t n_tiles_sym; const int2* tiles_rect; size_t n_tiles_rect;
   void* ZcP;        // LAZY_NC x 32*ceil(m/32) x 3 bf16: the candidate rows cut into three bf16 pieces, in matrix-core operand order
   int32_t* cslot;   // d1: slot of a row in GbT or -1
   int32_t* cand;    // LAZY_NC + LAZY_NS: row held by a slot or -1

@@ -980,6 +980,156 @@ static hipError_t launch_partials(const TabDims& d, const TabPtrs& t, const Lazy
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------
+// The two rank-LAZY_TM updates of a flush, C -= A B^T with A (M x 128) and B (N x 128): N0 -= E C0^T on the lower block
+// triangle and Z0 -= C0 ZT.  Both are bound by the read and write of C once the product itself is cheap, so the three
+// thin operands (E, C0, ZT: a few MB) are cut into three bf16 pieces once per flush and laid out in matrix-core operand
+// order (rk_pack_*), and the six products of weight >= 2^-16 run as v_mfma_f32_32x32x16_bf16 (exact products, float32
+// sums over the 128 terms): a sixth of the matrix-core time of the float32 instruction for the same accuracy.
+// Layout of a packed operand: packet (piece, kg, row) = columns 8 kg .. 8 kg + 7 of `row`, at (piece * 16 + kg) * rpad + row.
+// One workgroup per 128 x 128 tile of C (the Gram kernel's tile schedules), four quarters of the contraction through
+// 48 KB of shared memory, two workgroups per compute unit so that one's read-modify-write of C overlaps the other's products.
+// ------------------------------------------------------------------------------------------------
+// X: rows x 128 row-major (ld = 128): thread = one packet
+__global__ __launch_bounds__(256) void rk_pack_rows_kernel(const float* __restrict__ X, int rows, int rpad, uint4* __restrict__ out) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;          // (kg, row), row fastest
+  if (idx >= 16 * rpad) return;
+  const int kg = idx / rpad, row = idx % rpad;
+  float v[8];
+#pragma unroll
+  for (int j = 0; j < 8; j++) v[j] = 0.f;
+  if (row < rows) {
+    const float4 a = *reinterpret_cast<const float4*>(X + (int64_t)row * LAZY_TM + kg * 8);
+    const float4 b = *reinterpret_cast<const float4*>(X + (int64_t)row * LAZY_TM + kg * 8 + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+  uint4 p1, p2, p3;
+  la_split3(v, p1, p2, p3);
+  out[(int64_t)kg * rpad + row] = p1;
+  out[(int64_t)(16 + kg) * rpad + row] = p2;
+  out[(int64_t)(32 + kg) * rpad + row] = p3;
+}
+// X: 128 x cols row-major (the contraction runs along the rows): packet (kg, c) = X[8 kg .. 8 kg + 7][c]
+__global__ __launch_bounds__(256) void rk_pack_cols_kernel(const float* __restrict__ X, int cols, int cpad, uint4* __restrict__ out) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= 16 * cpad) return;
+  const int kg = idx / cpad, c = idx % cpad;
+  float v[8];
+#pragma unroll
+  for (int j = 0; j < 8; j++) v[j] = (c < cols) ? X[(int64_t)(kg * 8 + j) * cols + c] : 0.f;
+  uint4 p1, p2, p3;
+  la_split3(v, p1, p2, p3);
+  out[(int64_t)kg * cpad + c] = p1;
+  out[(int64_t)(16 + kg) * cpad + c] = p2;
+  out[(int64_t)(32 + kg) * cpad + c] = p3;
+}
+
+__global__ __launch_bounds__(256, 2) void rk_update_kernel(const uint4* __restrict__ Apk, int apad, const uint4* __restrict__ Bpk, int bpad,
+                                                            float* __restrict__ C, int64_t ldc, int M, int N,
+                                                            const int2* __restrict__ tiles) {
+  __shared__ uint4 la[3 * 4 * 128], lb[3 * 4 * 128];          // 24 KB each: [piece][kg of this quarter][row]
+  const int2 tile = tiles[blockIdx.x];
+  if (tile.x < 0) return;
+  const int i0 = tile.x * 128, j0 = tile.y * 128;
+  if (i0 >= M || j0 >= N) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+  la_f16v acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; a++)
+#pragma unroll
+    for (int b = 0; b < 2; b++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[a][b][r] = 0.f;
+  // packet tid + 256 u of a quarter's 1536: piece = idx / 512, kg = (idx / 128) % 4, row = idx % 128
+  uint4 ra0, ra1, ra2, ra3, ra4, ra5, rb0, rb1, rb2, rb3, rb4, rb5;
+#define OSSCAR_RK_ADDR(P_, pad_, base_, u_, kq_) \
+  ((P_) + (int64_t)((((tid + 256 * (u_)) >> 9) * 16 + (kq_) * 4 + (((tid + 256 * (u_)) >> 7) & 3))) * (pad_) + (base_) + ((tid + 256 * (u_)) & 127))
+#define OSSCAR_RK_GLOAD(kq_)                                                                                       \
+  {                                                                                                                \
+    ra0 = *OSSCAR_RK_ADDR(Apk, apad, i0, 0, kq_); ra1 = *OSSCAR_RK_ADDR(Apk, apad, i0, 1, kq_);                    \
+    ra2 = *OSSCAR_RK_ADDR(Apk, apad, i0, 2, kq_); ra3 = *OSSCAR_RK_ADDR(Apk, apad, i0, 3, kq_);                    \
+    ra4 = *OSSCAR_RK_ADDR(Apk, apad, i0, 4, kq_); ra5 = *OSSCAR_RK_ADDR(Apk, apad, i0, 5, kq_);                    \
+    rb0 = *OSSCAR_RK_ADDR(Bpk, bpad, j0, 0, kq_); rb1 = *OSSCAR_RK_ADDR(Bpk, bpad, j0, 1, kq_);                    \
+    rb2 = *OSSCAR_RK_ADDR(Bpk, bpad, j0, 2, kq_); rb3 = *OSSCAR_RK_ADDR(Bpk, bpad, j0, 3, kq_);                    \
+    rb4 = *OSSCAR_RK_ADDR(Bpk, bpad, j0, 4, kq_); rb5 = *OSSCAR_RK_ADDR(Bpk, bpad, j0, 5, kq_);                    \
+  }
+  OSSCAR_RK_GLOAD(0);
+#pragma unroll 1
+  for (int kq = 0; kq < 4; kq++) {
+    __syncthreads();
+    la[tid] = ra0; la[tid + 256] = ra1; la[tid + 512] = ra2; la[tid + 768] = ra3; la[tid + 1024] = ra4; la[tid + 1280] = ra5;
+    lb[tid] = rb0; lb[tid + 256] = rb1; lb[tid + 512] = rb2; lb[tid + 768] = rb3; lb[tid + 1024] = rb4; lb[tid + 1280] = rb5;
+    __syncthreads();
+    if (kq + 1 < 4) OSSCAR_RK_GLOAD(kq + 1);
+#pragma unroll
+    for (int ks = 0; ks < 2; ks++) {
+      const int off = (ks * 2 + (lane >> 5)) * 128 + (lane & 31);
+      la_bf8 fa[2][3], fb[2][3];
+#pragma unroll
+      for (int a = 0; a < 2; a++)
+#pragma unroll
+        for (int p = 0; p < 3; p++) { uint4 q = la[p * 512 + off + wm * 64 + a * 32]; fa[a][p] = *reinterpret_cast<la_bf8*>(&q); }
+#pragma unroll
+      for (int b = 0; b < 2; b++)
+#pragma unroll
+        for (int p = 0; p < 3; p++) { uint4 q = lb[p * 512 + off + wn * 64 + b * 32]; fb[b][p] = *reinterpret_cast<la_bf8*>(&q); }
+#pragma unroll
+      for (int a = 0; a < 2; a++)
+#pragma unroll
+        for (int b = 0; b < 2; b++) {
+          // smallest terms first
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][2], fb[b][0], acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][0], fb[b][2], acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][1], fb[b][1], acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][1], fb[b][0], acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][0], fb[b][1], acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][0], fb[b][0], acc[a][b], 0, 0, 0);
+        }
+    }
+  }
+#undef OSSCAR_RK_GLOAD
+#undef OSSCAR_RK_ADDR
+  // C layout of a 32 x 32 tile: register r = rr*4 + r3 holds row rr*8 + (lane/32)*4 + r3, column lane%32.
+  // All of a thread's loads of C are issued before the first store (a load-subtract-store chain per element would pay the
+  // memory latency 64 times over).
+  float* cbase = C + (int64_t)(i0 + wm * 64 + (lane >> 5) * 4) * ldc + j0 + wn * 64 + (lane & 31);
+  if (i0 + 128 <= M && j0 + 128 <= N) {
+#pragma unroll
+    for (int a = 0; a < 2; a++) {
+      float cv[2][16];
+      float* ca = cbase + (int64_t)(a * 32) * ldc;
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const float* pr = ca + (int64_t)((r >> 2) * 8 + (r & 3)) * ldc;
+        cv[0][r] = pr[0]; cv[1][r] = pr[32];
+      }
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        float* pr = ca + (int64_t)((r >> 2) * 8 + (r & 3)) * ldc;
+        pr[0] = cv[0][r] - acc[a][0][r]; pr[32] = cv[1][r] - acc[a][1][r];
+      }
+    }
+  } else {
+#pragma unroll
+    for (int a = 0; a < 2; a++)
+#pragma unroll
+      for (int b = 0; b < 2; b++) {
+        const int col = j0 + wn * 64 + b * 32 + (lane & 31);
+        float cv[16];
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const int row = i0 + wm * 64 + a * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+          cv[r] = (row < M && col < N) ? C[(int64_t)row * ldc + col] : 0.f;
+        }
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const int row = i0 + wm * 64 + a * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+          if (row < M && col < N) C[(int64_t)row * ldc + col] = cv[r] - acc[a][b][r];
+        }
+      }
+  }
+}
+
 hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode,
                              const SideStream* side) {
   const int rb = (d.d1 + 255) / 256, mb = (d.m + 255) / 256;
@@ -991,22 +1141,24 @@ hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs&
   e.C = L.E; e.ldc = LAZY_TM; e.alpha = 1.0; e.beta = 0.0;
   hipError_t err = launch_gemm_f64acc(e, s);
   if (err != hipSuccess) return err;
+  // the three thin operands in matrix-core order (C0's pieces serve both updates)
+  const int dpad = (d.d1 + 127) / 128 * 128, mpad = (d.m + 127) / 128 * 128;
+  uint4* Epk = reinterpret_cast<uint4*>(L.Epk); uint4* Cpk = reinterpret_cast<uint4*>(L.Cpk); uint4* Zpk = reinterpret_cast<uint4*>(L.Zpk);
+  hipLaunchKernelGGL(rk_pack_rows_kernel, dim3((16 * dpad + 255) / 256), dim3(256), 0, s, L.C0R, d.d1, dpad, Cpk);
+  hipLaunchKernelGGL(rk_pack_rows_kernel, dim3((16 * dpad + 255) / 256), dim3(256), 0, s, L.E, d.d1, dpad, Epk);
+  hipLaunchKernelGGL(rk_pack_cols_kernel, dim3((16 * mpad + 255) / 256), dim3(256), 0, s, L.ZT32, d.m, mpad, Zpk);
   if (two) {
     if ((err = hipEventRecord(side->fork, s)) != hipSuccess) return err;
     if ((err = hipStreamWaitEvent(sn, side->fork, 0)) != hipSuccess) return err;
   }
-  GemmArgs g{};                         // N0 -= E C0^T on the lower triangle (pivot rows and columns are rewritten below)
-  g.M = d.d1; g.N = d.d1; g.K = LAZY_TM; g.A = L.E; g.lda = LAZY_TM; g.B = L.C0R; g.ldb = LAZY_TM; g.trans_b = 1;
-  g.Cin = t.N; g.ldcin = d.d1; g.C = t.N; g.ldc = d.d1; g.alpha = -1.0; g.beta = 1.0; g.lower_only = 1; g.acc_f32 = 1;
-  err = launch_gemm_f64acc(g, sn);
-  if (err != hipSuccess) return err;
+  // N0 -= E C0^T on the lower block triangle (pivot rows and columns are rewritten below)
+  hipLaunchKernelGGL(rk_update_kernel, dim3((unsigned)L.n_tiles_sym), dim3(256), 0, sn, Epk, dpad, Cpk, dpad, t.N, (int64_t)d.d1, d.d1, d.d1,
+                     L.tiles_sym);
   hipLaunchKernelGGL(lazy_fix_kernel, dim3(rb), dim3(256), 0, sn, L, t.N, d.d1, t.ctrl);
   if (two && (err = hipEventRecord(side->join, sn)) != hipSuccess) return err;
-  GemmArgs z{};                         // Z0 -= C0 ZT
-  z.M = d.d1; z.N = d.m; z.K = LAZY_TM; z.A = L.C0R; z.lda = LAZY_TM; z.B = L.ZT32; z.ldb = d.m;
-  z.Cin = t.Z; z.ldcin = d.m; z.C = t.Z; z.ldc = d.m; z.alpha = -1.0; z.beta = 1.0; z.acc_f32 = 1;
-  err = launch_gemm_f64acc(z, s);
-  if (err != hipSuccess) return err;
+  // Z0 -= C0 ZT
+  hipLaunchKernelGGL(rk_update_kernel, dim3((unsigned)L.n_tiles_rect), dim3(256), 0, s, Cpk, dpad, Zpk, mpad, t.Z, (int64_t)d.m, d.d1, d.m,
+                     L.tiles_rect);
   hipLaunchKernelGGL(lazy_fix_z_kernel, dim3(mb), dim3(256), 0, s, L, t.Z, d.m, t.ctrl);
   if (two) {
     // Candidates from the scores as the swaps left them (the refresh below changes them in the last digits only, and the
