@@ -5,14 +5,15 @@ One "step" is one pass of the whole hot path over one synthetic OPT-30B-shaped f
 calibration rows, finalize (ridge, G = H W), magnitude support + state build, the local search, and the
 final back-solve.  X and W are resident in HBM before the timed region starts.
 
-Prints one JSON line.  `value` is seconds per layer (lower is better).  `roofline` describes the kernel the
-layer time is dominated by, the bf16 MFMA Gram kernel (it also carries G = H W and the products of the state
-build): algorithmic flops of one launch (16384 calibration rows) over the mean launch duration, measured by
-HIP events on the library's stream inside the timed steps.  `roofline_gemm_f64acc` / `roofline_gemm_f32acc`
-give the two general matrix-product kernels: their largest launch, and the time-weighted rate over ALL their
-launches of one layer (from the library's launch log, collected on one extra untimed layer).  `cpu_baseline`
-is the float64 oracle timed on this machine's host cores on a reduced layer of the same recipe: `value` is what
-the clock measured on that reduced layer; the projection to the full layer is a separate, labelled key."""
+Prints one JSON line.  `value` is seconds per layer (lower is better).  `roofline` describes the kernel with the
+largest share of the layer time, the float64-accumulating matrix product (float32 operands, v_mfma_f64_16x16x4_f64)
+that builds the state: `achieved` = algorithmic flops per launch over the mean launch duration, both taken over ALL
+its launches inside the timed steps (the library brackets every launch with HIP events on its own stream; total flops /
+total time is the same number), `largest_launch` the one launch the rate is usually quoted on.  `roofline_gram` is the
+bf16 MFMA Gram kernel per launch (one chunk of 16384 calibration rows), `roofline_gemm_f32acc` the float32-accumulating
+matrix product.  `cpu_baseline` is the float64 oracle timed on this machine's host cores on a reduced layer of the same
+recipe: `value` is what the clock measured on that reduced layer; the projection to the full layer is a separate,
+labelled key."""
 from __future__ import annotations
 
 import argparse
@@ -22,7 +23,10 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
-GRAM_TRAFFIC_CFG5 = None      # HBM bytes of one Gram kernel launch on cfg5 from rocprofv3 --pmc (profiles/gram_packed_cfg5_pmc.md)
+# HBM-side bytes per launch on cfg5 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a 1 GiB copy
+# (profiles/gemm_f64acc_cfg5_pmc.md: mean over the launches of one layer; profiles/gram_packed_cfg5_pmc.md: one chunk)
+GEMM64_TRAFFIC_CFG5 = 2.421e9
+GRAM_TRAFFIC_CFG5 = 94.85e9
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -171,9 +175,11 @@ def main():
             cand_ms += tm[12]
         info.update(obj0=obj0, obj=obj, iters=r["iters"], accepted=r["accepted"], tracked=r["obj_final"])
 
+    from paper_2403_12983_amd import binding as B
     for _ in range(a.warmup):
         step(False)
     torch.cuda.synchronize()
+    B.gemm_log(True)            # two event records around every general matrix product of the timed steps
     t0 = time.perf_counter()
     for _ in range(a.steps):
         step(True)
@@ -191,11 +197,7 @@ def main():
     cand_ms /= K
     t_layer = wall / K
 
-    # one more layer, untimed, with the library's launch log on: every general matrix product with its shape and duration
-    from paper_2403_12983_amd import binding as B
-    B.gemm_log(True)
-    step(False)
-    log = B.gemm_log_read()
+    log = B.gemm_log_read()     # every general matrix product of the timed steps: shape, kind, duration
     B.gemm_log(False)
 
     def weighted(rows):
@@ -205,6 +207,7 @@ def main():
         return (fl_ / (ms_ * 1e-3) / 1e12 if ms_ > 0 else None), ms_, len(rows)
     w64, ms64, n64 = weighted([r for r in log if not int(r[3]) & 1])
     w32, ms32, n32 = weighted([r for r in log if int(r[3]) & 1])
+    ms64, ms32, n64, n32 = ms64 / K, ms32 / K, n64 / K, n32 / K          # per layer
     if a.gemm_table:
         groups = {}
         for r in log:
@@ -213,13 +216,14 @@ def main():
             g[0] += 1
             g[1] += r[4]
         with open(a.gemm_table, "w") as f:
+            f.write(f"launches of {K} layer(s); count and total ms are per layer\n\n")
             f.write("| M | N | K | accumulate | output | tiles | count | total ms | ms per launch | TFLOP/s | fraction of that pipe's peak |\n|---|---|---|---|---|---|---|---|---|---|---|\n")
             for (M_, N_, K_, kind), (cnt, ms_) in sorted(groups.items(), key=lambda kv: -kv[1][1]):
                 fl_ = 2.0 * M_ * N_ * K_ * (0.5 if kind & 4 else 1.0) * cnt
                 tf = fl_ / (ms_ * 1e-3) / 1e12 if ms_ > 0 else 0.0
                 peak = 157.3 if kind & 1 else 78.6
                 f.write(f"| {M_} | {N_} | {K_} | {'float32' if kind & 1 else 'float64'} | {'float64' if kind & 2 else 'float32'} | "
-                        f"{'lower triangle' if kind & 4 else 'all'} | {cnt} | {ms_:.3f} | {ms_ / cnt:.4f} | {tf:.1f} | {tf / peak:.3f} |\n")
+                        f"{'lower triangle' if kind & 4 else 'all'} | {cnt / K:g} | {ms_ / K:.3f} | {ms_ / cnt:.4f} | {tf:.1f} | {tf / peak:.3f} |\n")
             f.write(f"\nfloat64-accumulating kernel: {n64} launches, {ms64:.1f} ms, time-weighted {w64 or 0:.1f} TFLOP/s = {(w64 or 0) / 78.6:.3f} of 78.6\n")
             f.write(f"float32-accumulating kernel: {n32} launches, {ms32:.1f} ms, time-weighted {w32 or 0:.1f} TFLOP/s = {(w32 or 0) / 157.3:.3f} of 157.3\n")
 
@@ -241,6 +245,10 @@ def main():
     gram_traffic = GRAM_TRAFFIC_CFG5 if (a.config == "cfg5" and a.rows is None) else None
     g_flops = 2.0 * n_inv ** 3                                         # largest float64-accumulating launch: I - H_KK P
     g_bytes = 4.0 * 3 * n_inv * n_inv
+    # mean algorithmic bytes of a float64-accumulating launch: A and B read once, C written once (float32; 8 bytes for a float64 output)
+    rows64 = [r for r in log if not int(r[3]) & 1]
+    alg64 = (sum(4.0 * (r[0] * r[2] + r[2] * r[1]) + (8.0 if int(r[3]) & 2 else 4.0) * r[0] * r[1] * (0.5 if int(r[3]) & 4 else 1.0)
+                 for r in rows64) / len(rows64)) if rows64 else None
     out = {
         "metric": "OPT-30B fc2 layer prune time", "value": t_layer, "unit": "s", "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": 1e3 * t_layer, "higher_is_better": False, "scaling": "weak",
@@ -259,28 +267,36 @@ def main():
         "gram_tflops_syrk": gram_flops / phases["gram"] / 1e12,
         "gram_tflops_full_equiv": 2 * n * d1 * d1 / phases["gram"] / 1e12,
         "objective": {"initial": info["obj0"], "final": info["obj"], "tracked": info["tracked"]},
-        "roofline": {"kernel": "gram_packed_kernel (bf16 MFMA SYRK on the lower block triangle), one launch = one chunk of "
-                               f"{rows_per_launch} calibration rows",
-                     "bound": "mfma", "achieved": gl_flops / (gram_launch_ms * 1e-3) / 1e12 if gram_launch_ms > 0 else None,
-                     "peak": 2500.0, "unit": "TFLOP/s",
-                     "frac": gl_flops / (gram_launch_ms * 1e-3) / 1e12 / 2500.0 if gram_launch_ms > 0 else None,
-                     "traffic": gram_traffic, "flops_per_launch": gl_flops, "algorithmic_bytes_per_launch": gl_bytes,
-                     "ms_per_launch": gram_launch_ms if gram_launch_ms > 0 else None},
-        "roofline_gemm_f64acc": {"kernel": "gemm_f64acc_kernel (float32 operands, float64 MFMA accumulation): the residuals that refine "
-                                           "the inverse and the weights", "bound": "mfma", "peak": 78.6, "unit": "TFLOP/s",
-                                 "largest_launch": {"what": "I - H_KK P of the Newton-Schulz step", "flops": g_flops,
-                                                    "algorithmic_bytes": g_bytes, "ms": gemm_ms if gemm_ms > 0 else None,
-                                                    "achieved": g_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None,
-                                                    "frac": g_flops / (gemm_ms * 1e-3) / 1e12 / 78.6 if gemm_ms > 0 else None},
-                                 "all_launches_of_a_layer": {"launches": n64, "ms": ms64, "achieved": w64,
-                                                             "frac": (w64 / 78.6) if w64 else None}},
-        # The float32-accumulating MFMA GEMM (v_mfma_f32_32x32x2_f32: flushes of the search, sweeps of the inverse, small
-        # corrections) takes about as long per layer as the float64-accumulating one; its largest launch is the lower triangle
-        # of P (I - H_KK P) in the Newton-Schulz step: kr^3 flops (timer slot 10).
-        "roofline_gemm_f32acc": {"kernel": "gemm_f32acc_kernel (float32 MFMA accumulation): rank-128 flushes of the search, sweeps of "
-                                           "the inverse", "bound": "mfma", "peak": 157.3, "unit": "TFLOP/s",
-                                 "all_launches_of_a_layer": {"launches": n32, "ms": ms32, "achieved": w32,
-                                                             "frac": (w32 / 157.3) if w32 else None}},
+        # Largest share of the layer time: the float64-accumulating product (B, V, S, R of the state build, the residuals that
+        # refine the inverse and the weights).  Unit of the roofline: one launch, averaged over every launch of the timed steps:
+        # mean algorithmic flops per launch (2 M N K, half of it for a lower-triangle launch) / mean launch duration.
+        "roofline": {"kernel": "gemm_f64acc_kernel (float32 operands, float64 MFMA accumulation): state build and residuals; "
+                               f"{n64:g} launches per layer",
+                     "bound": "mfma", "achieved": w64, "peak": 78.6, "unit": "TFLOP/s", "frac": (w64 / 78.6) if w64 else None,
+                     "traffic": GEMM64_TRAFFIC_CFG5 if (a.config == "cfg5" and a.rows is None) else None,
+                     "launches_per_layer": n64, "ms_per_layer": ms64,
+                     "flops_per_launch": (w64 * 1e12 * ms64 * 1e-3 / n64) if (w64 and n64) else None,
+                     "ms_per_launch": (ms64 / n64) if n64 else None,
+                     "algorithmic_bytes_per_launch": alg64,
+                     "largest_launch": {"what": "I - H_KK P of the Newton-Schulz step", "flops": g_flops,
+                                        "algorithmic_bytes": g_bytes, "ms": gemm_ms if gemm_ms > 0 else None,
+                                        "achieved": g_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None,
+                                        "frac": g_flops / (gemm_ms * 1e-3) / 1e12 / 78.6 if gemm_ms > 0 else None}},
+        # The bf16 MFMA Gram kernel, per launch = one chunk of up to 16384 calibration rows: algorithmic SYRK flops
+        # rows * d1 * (d1 + 1) (the lower block triangle), duration = mean over the launches of the timed steps, bracketed by
+        # HIP events on the library's stream (timer slot 13).
+        "roofline_gram": {"kernel": "gram_packed_kernel (bf16 MFMA SYRK on the lower block triangle), one launch = one chunk of "
+                                    f"{rows_per_launch} calibration rows",
+                          "bound": "mfma", "achieved": gl_flops / (gram_launch_ms * 1e-3) / 1e12 if gram_launch_ms > 0 else None,
+                          "peak": 2500.0, "unit": "TFLOP/s",
+                          "frac": gl_flops / (gram_launch_ms * 1e-3) / 1e12 / 2500.0 if gram_launch_ms > 0 else None,
+                          "traffic": gram_traffic, "flops_per_launch": gl_flops, "algorithmic_bytes_per_launch": gl_bytes,
+                          "ms_per_launch": gram_launch_ms if gram_launch_ms > 0 else None},
+        # The float32-accumulating MFMA GEMM (v_mfma_f32_32x32x2_f32): the panel sweeps of the blocked inverse and E = C0 M^-1 of
+        # every flush; total flops / total time over all its launches of the timed steps.
+        "roofline_gemm_f32acc": {"kernel": "gemm_f32acc_kernel (float32 MFMA accumulation): sweeps of the inverse (bound by the "
+                                           "read and write of C), E = C0 M^-1 of the flushes", "bound": "mfma", "peak": 157.3, "unit": "TFLOP/s",
+                                 "achieved": w32, "frac": (w32 / 157.3) if w32 else None, "launches_per_layer": n32, "ms_per_layer": ms32},
         "state_build": {"candidate_side_products_ms": cand_ms, "inverse_correction_product_ms": gemm32_ms},
         "roofline_gram_phase": {"kernel": "gram_pack_kernel + gram_packed_kernel, the whole Gram phase (repacking included)",
                                 "bound": "mfma", "achieved": gram_flops / phases["gram"] / 1e12, "peak": 2500.0, "unit": "TFLOP/s",

@@ -52,17 +52,23 @@ __device__ __forceinline__ Tile8 load8(const float* __restrict__ row, int c0, in
 // Block -> tile.  Workgroups go to the 8 XCDs in turn (block index modulo 8), each with its own L2; two workgroups fit a
 // CU, so 64 run together per XCD.  The tile grid is cut into 8 x 8 super-blocks, super-block b goes to XCD b % 8 and
 // the 64 workgroups an XCD runs together are the 64 tiles of one super-block: they share 8 row panels of A and 8
-// column panels of B in that L2.  Padding tiles return at once.  lower_only products walk the triangle row by row.
+// column panels of B in that L2.  Padding tiles return at once.  lower_only products take the super-blocks on or below
+// the diagonal.
 constexpr int SB = 8;
 __device__ __forceinline__ bool tile_of_block(const GemmArgs& g, int& tile_m, int& tile_n) {
   if (g.lower_only) {
-    // linear index over the lower-triangle tiles: t = tm*(tm+1)/2 + tn, tn <= tm
-    const int t = blockIdx.x;
-    int r = (int)((sqrtf(8.f * (float)t + 1.f) - 1.f) * 0.5f);
-    while ((r + 1) * (r + 2) / 2 <= t) r++;
-    while (r * (r + 1) / 2 > t) r--;
-    tile_m = r; tile_n = t - r * (r + 1) / 2;
-    return true;
+    // the super-blocks on or below the diagonal, row by row: sb = R (R + 1) / 2 + C, C <= R; in a diagonal super-block the
+    // tiles above the diagonal return at once
+    const int tm = (g.M + BM - 1) / BM, nr = (tm + SB - 1) / SB;
+    const int b = blockIdx.x, xcd = b & 7, slot = b >> 3;
+    const int sb = (slot / (SB * SB)) * 8 + xcd, within = slot % (SB * SB);
+    if (sb >= nr * (nr + 1) / 2) return false;
+    int r = (int)((sqrtf(8.f * (float)sb + 1.f) - 1.f) * 0.5f);
+    while ((r + 1) * (r + 2) / 2 <= sb) r++;
+    while (r * (r + 1) / 2 > sb) r--;
+    tile_m = r * SB + within / SB;
+    tile_n = (sb - r * (r + 1) / 2) * SB + within % SB;
+    return tile_m < tm && tile_n <= tile_m;
   }
   const int tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
   const int nsb_c = (tn + SB - 1) / SB, nsb = ((tm + SB - 1) / SB) * nsb_c;
@@ -76,7 +82,10 @@ __device__ __forceinline__ bool tile_of_block(const GemmArgs& g, int& tile_m, in
 }
 static int grid_blocks(const GemmArgs& a) {
   const int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
-  if (a.lower_only) return tm * (tm + 1) / 2;
+  if (a.lower_only) {
+    const int nr = (tm + SB - 1) / SB;
+    return (nr * (nr + 1) / 2 + 7) / 8 * 8 * SB * SB;
+  }
   const int nsb = ((tm + SB - 1) / SB) * ((tn + SB - 1) / SB);
   return (nsb + 7) / 8 * 8 * SB * SB;
 }
