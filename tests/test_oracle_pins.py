@@ -62,6 +62,25 @@ def test_quadratic_objective_equals_reconstruction_loss():
     assert abs(orc.objective_quadratic(H, G, c0, W)) < 1e-9 * c0
 
 
+def test_objective_of_a_state_equals_the_pruned_rows_form():
+    """With G = H W the optimum on a support K (Appendix A.1) can be written without the constant: obj(K) = <W_c, R_c>,
+    R_c = G_c - H_cK B over the pruned rows, instead of c0 - <G_K, B>, a difference of two numbers of the size of c0.
+    The library reports the first form; here both are held against the reconstruction loss of the solved weights."""
+    for q, seed in ((1, 11), (3, 12)):
+        p, m, n = 7, 5, 50
+        X, W, H, G, c0, lam = make_problem(p, q, m, n, seed, lam=0.2)
+        groups = [1, 2, 4, 6]
+        What, obj = orc.solve_support(H, G, c0, groups, q)
+        K = orc.rows_of(groups, q)
+        Cc = np.setdiff1d(np.arange(p * q), K)
+        B = np.linalg.solve(H[np.ix_(K, K)], G[K])
+        R = G[Cc] - H[np.ix_(Cc, K)] @ B
+        pruned_form = float(np.sum(W[Cc] * R))
+        assert np.isclose(pruned_form, obj, rtol=1e-10)
+        assert np.isclose(pruned_form, c0 - float(np.sum(G[K] * B)), rtol=1e-10)
+        assert np.isclose(pruned_form, orc.objective_direct(X, W, What, lam), rtol=1e-10)
+
+
 # ---------------------------------------------------------------- optimum for a fixed support (eq. (optf))
 @pytest.mark.parametrize("q", [1, 3])
 def test_solve_support_matches_ridge_least_squares(q):
