@@ -246,10 +246,18 @@ osscar_status osscar_get_counters(osscar_ctx* ctx, int64_t* out_host);
  * osscar_debug_gemm_log(1) clears the log and starts recording: every launch is bracketed by two events on its stream.
  * osscar_debug_gemm_log(0) stops and clears.  osscar_debug_gemm_log_read waits for the recorded launches and writes up to
  * `capacity` rows of five float64 {M, N, K, kind, milliseconds} (kind: 1 = float32 accumulation, + 2 = float64 output,
- * + 4 = lower-triangle tiles only, + 8 = second operand transposed) to out_host; returns the number of rows, -1 on a bad
+ * + 4 = lower-triangle tiles only, + 8 = second operand transposed, 16 = int8-digit product, packing included) to out_host; returns the number of rows, -1 on a bad
  * argument.  At most 16384 launches are kept. */
 osscar_status osscar_debug_gemm_log(int32_t enable);
 int32_t osscar_debug_gemm_log_read(double* out_host, int32_t capacity);
+
+/* The large products that define the state of a support (every dimension >= 1024: B = P G_K, V = P H_{K,Kc}, the Schur
+ * complement S and R of Proposition 4.1's closed forms) run on the int8 matrix cores from five 7-bit digits per float32
+ * operand, with exact integer sums (kind 16 in the log above); smaller ones, and the three residuals that refine the inverse,
+ * the weights and the back-solve, on the float64-accumulating kernel.  osscar_debug_int_products(0) sends all of them to the
+ * float64-accumulating kernel, osscar_debug_int_products(1) restores the default.  Process-wide, for tests that hold the two
+ * against each other. */
+osscar_status osscar_debug_int_products(int32_t enable);
 
 /* Host-only inspection of the Gram kernel's tile schedule (no device is touched): writes up to `capacity` (row, column)
  * pairs of 128 x 128 tiles, in workgroup order, to out_host (2 ints each; (-1, -1) = padding) and returns the length of

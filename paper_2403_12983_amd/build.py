@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libosscar.so")
-SOURCES = ["gemm.hip", "gram.hip", "tableau.hip", "lazy.hip", "api.hip", "noalloc.hip"]
+SOURCES = ["gemm.hip", "i8gemm.hip", "gram.hip", "tableau.hip", "lazy.hip", "api.hip", "noalloc.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-result", "-Wno-unused-value"]
 

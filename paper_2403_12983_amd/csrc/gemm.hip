@@ -396,6 +396,21 @@ int gemm_log_read(double* out, int capacity) {
   return n;
 }
 
+// the same log for launches made elsewhere (the int8 product): open records the first event, close the second
+void gemm_log_open(int M, int N, int K, int kind, hipStream_t s, int* slot) {
+  *slot = -1;
+  if (!g_log_on || g_log.size() >= GEMM_LOG_CAP) return;
+  GemmLogEntry e{M, N, K, kind, nullptr, nullptr};
+  if (hipEventCreate(&e.a) != hipSuccess) return;
+  if (hipEventCreate(&e.b) != hipSuccess) { hipEventDestroy(e.a); return; }
+  hipEventRecord(e.a, s);
+  g_log.push_back(e);
+  *slot = (int)g_log.size() - 1;
+}
+void gemm_log_close(int slot, hipStream_t s) {
+  if (slot >= 0 && slot < (int)g_log.size()) hipEventRecord(g_log[slot].b, s);
+}
+
 static hipError_t launch_gemm_impl(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_f64acc(const GemmArgs& a, hipStream_t s) {
   if (!g_log_on || g_log.size() >= GEMM_LOG_CAP || a.M <= 0 || a.N <= 0) return launch_gemm_impl(a, s);

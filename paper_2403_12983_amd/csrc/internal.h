@@ -25,12 +25,33 @@ struct GemmArgs {
   int lower_only;                // 1: compute only tiles that touch the lower triangle (row >= col)
   int trans_b;                   // 1: B is given as N x K row-major (C = alpha * A * B^T + ...)
   int acc_f32;                   // 1: accumulate in float32 (v_mfma_f32_32x32x2_f32); float32 output only
+  // hints for the int8-digit product only (i8gemm.hip; any other kernel ignores them): A (B) is square with a diagonal far
+  // above the rest of its rows (columns), to be kept out of the fixed-point digits and added in float64
+  int i8_diag_a, i8_diag_b;
+  // and a levelling of the contraction index: A is used as A 2^(ksign kexp[k]), B as 2^(-ksign kexp[k]) B (nullptr: none)
+  const int* i8_kexp; int i8_ksign;
 };
 hipError_t launch_gemm_f64acc(const GemmArgs& a, hipStream_t s);
 // diagnostic log of the launches above: enable (1) / disable and clear (0); read = rows of {M, N, K, kind, ms} with
 // kind = 1 float32 accumulation | 2 float64 output | 4 lower triangle only | 8 B transposed; returns the number of rows
+// kind also carries 16 = the int8-digit product of i8gemm.hip
 void gemm_log_enable(int on);
 int gemm_log_read(double* out, int capacity);
+void gemm_log_open(int M, int N, int K, int kind, hipStream_t s, int* slot);
+void gemm_log_close(int slot, hipStream_t s);
+
+// ----------------------------------------------------------------------------------------------
+// i8gemm.hip : the same product C = alpha A B + beta Cin (+ diag_add on the diagonal; lower_only) for float32 A, B, Cin, C
+// with the accuracy of float64 accumulation, computed on the int8 matrix cores from I8_S seven-bit digits per operand
+// ----------------------------------------------------------------------------------------------
+constexpr int I8_S = 5;
+size_t i8_pack_bytes(int64_t rows, int64_t K);          // packed size of an operand with `rows` rows (A) or columns (B)
+bool i8_gemm_fits(const GemmArgs& g);
+// kexp[k] = round(log2 sqrt(D_kk)) from the diagonal of a Gram block (device, n ints)
+hipError_t launch_i8_kexp(const float* D, int n, int64_t ld, int* kexp, hipStream_t s);
+// packA / packB: scratch for the two packed operands (capacities in bytes), mx: M + N words for the scaling exponents
+hipError_t launch_i8_gemm(const GemmArgs& g, void* packA, size_t capA, void* packB, size_t capB, unsigned* mx, size_t mx_entries,
+                          hipStream_t s);
 
 // ----------------------------------------------------------------------------------------------
 // gram.hip : H64 (+)= Xc^T Xc on the lower-triangle tiles (bf16 X, d1 % 8 == 0, ldx % 8 == 0, 16-byte aligned)

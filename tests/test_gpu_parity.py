@@ -54,9 +54,19 @@ SMALL = {
 }
 
 
+# Layers whose state-build products have every dimension >= 1024, so that they run on the int8 matrix cores (five 7-bit
+# digits per operand, exact integer sums) instead of the float64-accumulating kernel that the small cases above use
+MEDIUM = {
+    # kept rows 1100, candidates 1210, m = 1030: no dimension a multiple of 128, 32 or 16; float32 activations
+    "i8ragged": lambda: inp.scaled(inp.CONFIGS["cfg3"], p=2310, m=1030, n=6000, k=1100, swaps=40).replace(x_dtype="f32"),
+    # 1280 + 1280 rows, m = 1024, bf16 activations
+    "i8even": lambda: inp.scaled(inp.CONFIGS["cfg3"], p=2560, m=1024, n=8192, k=1280, swaps=40),
+}
+
+
 class Case:
     def __init__(self, name):
-        self.cfg = cfg = SMALL[name]() if isinstance(name, str) else name
+        self.cfg = cfg = (SMALL.get(name) or MEDIUM[name])() if isinstance(name, str) else name
         self.X, self.W = inp.gen_X(cfg), inp.gen_W(cfg)
         self.Xd, self.Wd = self.X.double().numpy(), self.W.double().numpy()
         self.H, self.G, self.c0, self.lam = orc.gram(self.Xd, self.Wd, cfg.lam_abs, cfg.lam_rel)
@@ -117,7 +127,7 @@ def test_gram_matches_oracle_and_is_chunk_invariant(name):
 
 
 # ------------------------------------------------------------------------------------------ state + scores
-@pytest.mark.parametrize("name", list(SMALL))
+@pytest.mark.parametrize("name", list(SMALL) + list(MEDIUM))
 def test_initial_state_and_scores(name):
     c = case(name)
     cfg = c.cfg
@@ -159,6 +169,48 @@ def test_initial_state_and_scores(name):
 
 
 # ------------------------------------------------------------------------------------------ search
+@pytest.mark.parametrize("name", list(MEDIUM))
+def test_int8_digit_products_match_float64_accumulation(name):
+    """The large products of the state build and the back-solve on the int8 matrix cores (operands cut into five 7-bit
+    digits, integer sums) against the same products on the float64-accumulating kernel: both are exact sums of exact
+    products, the first up to 2^-34 of row maximum times column maximum per term.  The layers have outlier channels
+    (8 columns of X 20 times the rest), which is what the levelling of the contraction index is for."""
+    from paper_2403_12983_amd import binding as B
+    c = case(name)
+    cfg = c.cfg
+    out, kinds = [], []
+    try:
+        for on in (True, False):
+            B.i8_products(on)
+            B.gemm_log(True)
+            s = c.solver()
+            c.gram(s)
+            obj0 = s.osscar_init_support()
+            state = [T(s, w) for w in ("T_P", "T_B", "T_V", "T_R", "T_REM", "T_ADD")]
+            r = s.osscar_local_search(cfg.swaps)
+            What, support, obj = s.osscar_backsolve()
+            kinds.append([int(k) for k in B.gemm_log_read()[:, 3]])
+            out.append((obj0, r["trace_out"][:r["accepted"]].tolist(), r["trace_in"][:r["accepted"]].tolist(), state,
+                        What.float().cpu().numpy().astype(np.float64), obj))
+            s.close()
+    finally:
+        B.gemm_log(False)
+        B.i8_products(True)
+    assert sum(1 for k in kinds[0] if k & 16) >= 4 and not any(k & 16 for k in kinds[1])      # the paths really differed
+    (o1, out1, in1, st1, W1, f1), (o2, out2, in2, st2, W2, f2) = out
+    assert abs(o1 - o2) <= 1e-7 * abs(o2)
+    assert out1 == out2 and in1 == in2 and len(out1) > 0
+    # P, B, V, R.  The digits are fixed-point within a row (column), so entries far below the row's maximum keep fewer
+    # bits, and B = P G_K and V = P H_{K,Kc} cancel by the condition number of H_KK: 3e-7 here, against the 2e-6 .. 7e-6 by
+    # which either path differs from the oracle (float32 storage of H and P)
+    for (a, b), bar in zip(zip(st1[:4], st2[:4]), (1e-7, 1e-6, 1e-6, 3e-7)):
+        assert rel(a, b) < bar
+    for a, b in zip(st1[4:], st2[4:]):
+        f = np.isfinite(b)
+        assert np.array_equal(np.isfinite(a), f) and np.max(np.abs(a[f] - b[f]) / b[f]) < 2e-6
+    assert rel(W1, W2) < 1e-6 and abs(f1 - f2) <= 1e-7 * abs(f2)
+
+
 def check_trajectory(c, r, rel_tol=0.0, always=False, exact_in=False, tol_obj=1e-5, tol_score=0.0):
     """The library's trajectory replayed by the oracle: every choice within GAP of the oracle's best, every
     applied swap improving, the stop justified, the objective trace equal to tol_obj.  tol_score: relative error granted to
