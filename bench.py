@@ -6,14 +6,13 @@ calibration rows, finalize (ridge, G = H W), magnitude support + state build, th
 final back-solve.  X and W are resident in HBM before the timed region starts.
 
 Prints one JSON line.  `value` is seconds per layer (lower is better).  `roofline` describes the kernel with the
-largest share of the layer time, the float64-accumulating matrix product (float32 operands, v_mfma_f64_16x16x4_f64)
-that builds the state: `achieved` = algorithmic flops per launch over the mean launch duration, both taken over ALL
-its launches inside the timed steps (the library brackets every launch with HIP events on its own stream; total flops /
-total time is the same number), `largest_launch` the one launch the rate is usually quoted on.  `roofline_gram` is the
-bf16 MFMA Gram kernel per launch (one chunk of 16384 calibration rows), `roofline_gemm_f32acc` the float32-accumulating
-matrix product.  `cpu_baseline` is the float64 oracle timed on this machine's host cores on a reduced layer of the same
-recipe: `value` is what the clock measured on that reduced layer; the projection to the full layer is a separate,
-labelled key."""
+largest share of the layer time, the bf16 MFMA Gram kernel: algorithmic SYRK flops of one launch (16384 calibration
+rows) over the mean launch duration, measured by HIP events on the library's stream inside the timed steps.
+`roofline_gemm_f64acc`, `roofline_gemm_int8` and `roofline_gemm_f32acc` give the three matrix-product kernels of the state
+build and the back-solve: total algorithmic flops / total time over ALL their launches of the timed steps (the library
+brackets every launch with HIP events on its own stream), and for the first its largest launch.  `cpu_baseline` is the
+float64 oracle timed on this machine's host cores on a reduced layer of the same recipe: `value` is what the clock measured
+on that reduced layer; the projection to the full layer is a separate, labelled key."""
 from __future__ import annotations
 
 import argparse
@@ -25,8 +24,8 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 # HBM-side bytes per launch on cfg5 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a 1 GiB copy
 # (profiles/gemm_f64acc_cfg5_pmc.md: mean over the launches of one layer; profiles/gram_packed_cfg5_pmc.md: one chunk)
-GEMM64_TRAFFIC_CFG5 = 2.421e9
-GRAM_TRAFFIC_CFG5 = 94.85e9
+GEMM64_TRAFFIC_CFG5 = 0.948e9
+GRAM_TRAFFIC_CFG5 = 97.25e9
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -205,9 +204,10 @@ def main():
         fl_ = sum(2.0 * r[0] * r[1] * r[2] * (0.5 if int(r[3]) & 4 else 1.0) for r in rows)
         ms_ = sum(r[4] for r in rows if r[4] > 0)
         return (fl_ / (ms_ * 1e-3) / 1e12 if ms_ > 0 else None), ms_, len(rows)
-    w64, ms64, n64 = weighted([r for r in log if not int(r[3]) & 1])
+    w64, ms64, n64 = weighted([r for r in log if not int(r[3]) & 17])
     w32, ms32, n32 = weighted([r for r in log if int(r[3]) & 1])
-    ms64, ms32, n64, n32 = ms64 / K, ms32 / K, n64 / K, n32 / K          # per layer
+    w8, ms8, n8 = weighted([r for r in log if int(r[3]) & 16])          # int8-digit products (packing included in the duration)
+    ms64, ms32, ms8, n64, n32, n8 = ms64 / K, ms32 / K, ms8 / K, n64 / K, n32 / K, n8 / K          # per layer
     if a.gemm_table:
         groups = {}
         for r in log:
@@ -222,10 +222,16 @@ def main():
                 fl_ = 2.0 * M_ * N_ * K_ * (0.5 if kind & 4 else 1.0) * cnt
                 tf = fl_ / (ms_ * 1e-3) / 1e12 if ms_ > 0 else 0.0
                 peak = 157.3 if kind & 1 else 78.6
+                if kind & 16:       # fifteen int8 products per float product, against the 5.0 POP/s int8 peak
+                    f.write(f"| {M_} | {N_} | {K_} | int8 digits | float32 | {'lower triangle' if kind & 4 else 'all'} | {cnt / K:g} | "
+                            f"{ms_ / K:.3f} | {ms_ / cnt:.4f} | {tf:.1f} | {15 * tf / 5000.0:.3f} of the int8 peak |\n")
+                    continue
                 f.write(f"| {M_} | {N_} | {K_} | {'float32' if kind & 1 else 'float64'} | {'float64' if kind & 2 else 'float32'} | "
                         f"{'lower triangle' if kind & 4 else 'all'} | {cnt / K:g} | {ms_ / K:.3f} | {ms_ / cnt:.4f} | {tf:.1f} | {tf / peak:.3f} |\n")
             f.write(f"\nfloat64-accumulating kernel: {n64} launches, {ms64:.1f} ms, time-weighted {w64 or 0:.1f} TFLOP/s = {(w64 or 0) / 78.6:.3f} of 78.6\n")
             f.write(f"float32-accumulating kernel: {n32} launches, {ms32:.1f} ms, time-weighted {w32 or 0:.1f} TFLOP/s = {(w32 or 0) / 157.3:.3f} of 157.3\n")
+            f.write(f"int8-digit products: {n8} launches, {ms8:.1f} ms, time-weighted {w8 or 0:.1f} TFLOP/s of float products = "
+                    f"{15 * (w8 or 0) / 1000.0:.2f} POP/s on the int8 pipe = {15 * (w8 or 0) / 5000.0:.3f} of 5.0\n")
 
     d1, m, n = cfg.d1, cfg.m, cfg.n
     gram_flops = n * d1 * (d1 + 1)
@@ -246,7 +252,7 @@ def main():
     g_flops = 2.0 * n_inv ** 3                                         # largest float64-accumulating launch: I - H_KK P
     g_bytes = 4.0 * 3 * n_inv * n_inv
     # mean algorithmic bytes of a float64-accumulating launch: A and B read once, C written once (float32; 8 bytes for a float64 output)
-    rows64 = [r for r in log if not int(r[3]) & 1]
+    rows64 = [r for r in log if not int(r[3]) & 17]
     alg64 = (sum(4.0 * (r[0] * r[2] + r[2] * r[1]) + (8.0 if int(r[3]) & 2 else 4.0) * r[0] * r[1] * (0.5 if int(r[3]) & 4 else 1.0)
                  for r in rows64) / len(rows64)) if rows64 else None
     out = {
@@ -267,31 +273,37 @@ def main():
         "gram_tflops_syrk": gram_flops / phases["gram"] / 1e12,
         "gram_tflops_full_equiv": 2 * n * d1 * d1 / phases["gram"] / 1e12,
         "objective": {"initial": info["obj0"], "final": info["obj"], "tracked": info["tracked"]},
-        # Largest share of the layer time: the float64-accumulating product (B, V, S, R of the state build, the residuals that
-        # refine the inverse and the weights).  Unit of the roofline: one launch, averaged over every launch of the timed steps:
-        # mean algorithmic flops per launch (2 M N K, half of it for a lower-triangle launch) / mean launch duration.
-        "roofline": {"kernel": "gemm_f64acc_kernel (float32 operands, float64 MFMA accumulation): state build and residuals; "
-                               f"{n64:g} launches per layer",
-                     "bound": "mfma", "achieved": w64, "peak": 78.6, "unit": "TFLOP/s", "frac": (w64 / 78.6) if w64 else None,
-                     "traffic": GEMM64_TRAFFIC_CFG5 if (a.config == "cfg5" and a.rows is None) else None,
-                     "launches_per_layer": n64, "ms_per_layer": ms64,
-                     "flops_per_launch": (w64 * 1e12 * ms64 * 1e-3 / n64) if (w64 and n64) else None,
-                     "ms_per_launch": (ms64 / n64) if n64 else None,
-                     "algorithmic_bytes_per_launch": alg64,
-                     "largest_launch": {"what": "I - H_KK P of the Newton-Schulz step", "flops": g_flops,
-                                        "algorithmic_bytes": g_bytes, "ms": gemm_ms if gemm_ms > 0 else None,
-                                        "achieved": g_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None,
-                                        "frac": g_flops / (gemm_ms * 1e-3) / 1e12 / 78.6 if gemm_ms > 0 else None}},
-        # The bf16 MFMA Gram kernel, per launch = one chunk of up to 16384 calibration rows: algorithmic SYRK flops
-        # rows * d1 * (d1 + 1) (the lower block triangle), duration = mean over the launches of the timed steps, bracketed by
-        # HIP events on the library's stream (timer slot 13).
-        "roofline_gram": {"kernel": "gram_packed_kernel (bf16 MFMA SYRK on the lower block triangle), one launch = one chunk of "
-                                    f"{rows_per_launch} calibration rows",
-                          "bound": "mfma", "achieved": gl_flops / (gram_launch_ms * 1e-3) / 1e12 if gram_launch_ms > 0 else None,
-                          "peak": 2500.0, "unit": "TFLOP/s",
-                          "frac": gl_flops / (gram_launch_ms * 1e-3) / 1e12 / 2500.0 if gram_launch_ms > 0 else None,
-                          "traffic": gram_traffic, "flops_per_launch": gl_flops, "algorithmic_bytes_per_launch": gl_bytes,
-                          "ms_per_launch": gram_launch_ms if gram_launch_ms > 0 else None},
+        # Largest share of the layer time: the bf16 MFMA Gram kernel.  Unit of the roofline: one launch = one chunk of up to 16384
+        # calibration rows: algorithmic SYRK flops rows * d1 * (d1 + 1) (the lower block triangle) over the mean duration of the
+        # launches of the timed steps, each bracketed by HIP events on the library's stream (timer slot 13).
+        "roofline": {"kernel": "gram_packed_kernel (bf16 MFMA SYRK on the lower block triangle), one launch = one chunk of "
+                               f"{rows_per_launch} calibration rows",
+                     "bound": "mfma", "achieved": gl_flops / (gram_launch_ms * 1e-3) / 1e12 if gram_launch_ms > 0 else None,
+                     "peak": 2500.0, "unit": "TFLOP/s",
+                     "frac": gl_flops / (gram_launch_ms * 1e-3) / 1e12 / 2500.0 if gram_launch_ms > 0 else None,
+                     "traffic": gram_traffic, "flops_per_launch": gl_flops, "algorithmic_bytes_per_launch": gl_bytes,
+                     "ms_per_launch": gram_launch_ms if gram_launch_ms > 0 else None},
+        # The float64-accumulating product (the residuals that refine the inverse, the weights and the back-solve; small
+        # products): mean algorithmic flops per launch (2 M N K) / mean launch duration over every launch of the timed steps.
+        "roofline_gemm_f64acc": {"kernel": "gemm_f64acc_kernel (float32 operands, float64 MFMA accumulation): residuals; "
+                                           f"{n64:g} launches per layer",
+                                 "bound": "mfma", "achieved": w64, "peak": 78.6, "unit": "TFLOP/s", "frac": (w64 / 78.6) if w64 else None,
+                                 "traffic": GEMM64_TRAFFIC_CFG5 if (a.config == "cfg5" and a.rows is None) else None,
+                                 "launches_per_layer": n64, "ms_per_layer": ms64,
+                                 "flops_per_launch": (w64 * 1e12 * ms64 * 1e-3 / n64) if (w64 and n64) else None,
+                                 "ms_per_launch": (ms64 / n64) if n64 else None,
+                                 "algorithmic_bytes_per_launch": alg64,
+                                 "largest_launch": {"what": "I - H_KK P of the Newton-Schulz step", "flops": g_flops,
+                                                    "algorithmic_bytes": g_bytes, "ms": gemm_ms if gemm_ms > 0 else None,
+                                                    "achieved": g_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None,
+                                                    "frac": g_flops / (gemm_ms * 1e-3) / 1e12 / 78.6 if gemm_ms > 0 else None}},
+        # The state-build products B, V, S, R on the int8 matrix cores: fifteen digit products per float product, so the pipe
+        # runs 15 x the float rate; durations include the scaling and cutting of both operands.
+        "roofline_gemm_int8": {"kernel": "i8_gemm_kernel (+ its packing kernels): float32 operands as five 7-bit digits, exact int32 sums; "
+                                         f"{n8:g} launches per layer",
+                               "bound": "mfma", "achieved": (15 * w8 / 1000.0) if w8 else None, "peak": 5.0, "unit": "POP/s",
+                               "frac": (15 * w8 / 5000.0) if w8 else None, "float_equivalent_TFLOPs": w8,
+                               "launches_per_layer": n8, "ms_per_layer": ms8},
         # The float32-accumulating MFMA GEMM (v_mfma_f32_32x32x2_f32): the panel sweeps of the blocked inverse and E = C0 M^-1 of
         # every flush; total flops / total time over all its launches of the timed steps.
         "roofline_gemm_f32acc": {"kernel": "gemm_f32acc_kernel (float32 MFMA accumulation): sweeps of the inverse (bound by the "
