@@ -226,9 +226,9 @@ osscar_status osscar_get_scalars(osscar_ctx* ctx, double* lambda_host, double* c
  * delayed-update search [5] mean duration of the kernel with the acceptance test and u = ZT [y1 y2] (it also makes a pass
  * over Z for a pivot whose products were not computed ahead), [7] of all kernels of that iteration from there on.
  * [8] the product G = H W inside finalize (one GEMM launch, or the three bf16 products and their repacking when W is
- * bf16).  [9] the residual I - H_KK P of the last Newton-Schulz step (one launch of the float64-accumulating GEMM, 2 kr^3
- * flops).  [10] the lower-triangle product P (I - H_KK P) of that step (three bf16 matrix-core products with their
- * repacking, or one launch of the float32-accumulating GEMM when kr or m is not a multiple of 8).  [11] not a time: max |I - H_KK P| of the sweep inverse before that step, a
+ * bf16).  [9] the inverse of H on the kept rows in the last state build: the blocked sweep on a float64 copy of H_KK
+ * (about 2 kr^3 flops on the float64 matrix cores).  [10] zero.  [11] not a time: the largest P_ii H_ii over the kept rows
+ * (the variance inflation factor 1 / (1 - R_i^2): how much of a kept row the other kept rows explain), a
  * measure of the conditioning of H_KK.  [12] the candidate-side products V, S, R of the last state build together.
  * [13] mean duration of one launch of the bf16 Gram kernel (one launch per 16384 calibration rows) in the last
  * osscar_gram call that added rows on that path before the last finalize, [14] the number of launches averaged, [15] the rows
@@ -258,6 +258,13 @@ int32_t osscar_debug_gemm_log_read(double* out_host, int32_t capacity);
  * float64-accumulating kernel, osscar_debug_int_products(1) restores the default.  Process-wide, for tests that hold the two
  * against each other. */
 osscar_status osscar_debug_int_products(int32_t enable);
+
+/* The inverse of H on the kept rows (P of Proposition 4.1) is computed by a blocked sweep on a float64 copy of H_KK and
+ * rounded to float32 once.  osscar_debug_refined_inverse(1) switches to the other route - the sweep in float32 storage,
+ * then Newton-Schulz steps P <- P + P (I - H_KK P) with a float64-accumulated residual - and (0) back.  Process-wide, for
+ * tests that hold the two against each other.  Timer slot 9 is the duration of the float64 sweep (of the residual product
+ * on the other route), slot 11 the largest P_ii H_ii (the residual |I - H_KK P| before the last step on the other route). */
+osscar_status osscar_debug_refined_inverse(int32_t enable);
 
 /* Host-only inspection of the Gram kernel's tile schedule (no device is touched): writes up to `capacity` (row, column)
  * pairs of 128 x 128 tiles, in workgroup order, to out_host (2 ints each; (-1, -1) = padding) and returns the length of

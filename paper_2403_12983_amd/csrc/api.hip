@@ -213,7 +213,7 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
   if (ds.target_output) gram_phase += align_up((size_t)d1 * m * 8) + align_up(target_stage_bytes(m));
   auto init_bytes = [&](size_t a, size_t b) {   // kept rows a, candidate rows b
     return 4 * align_up(a * a * 4) + 3 * align_up(a * b * 4) + align_up(b * b * 4) + 4 * align_up(a * m * 4) + align_up(b * m * 4) +
-           3 * align_up(a * INV_NB * 4) + split_bytes(a, b, m) + i8_bytes(a, b, m) + 4096;
+           align_up(6 * a * INV_NB * 4) + split_bytes(a, b, m) + i8_bytes(a, b, m) + 4096;
   };
   size_t init_phase = init_bytes(kr, cr);
   if (ds.from_dense) {   // the nested schedule visits every kept-row count from d1 down to kr
@@ -361,23 +361,72 @@ osscar_status split_gemm(osscar_ctx* c, const SplitBufs& sp, const void* packA, 
   return OSSCAR_OK;
 }
 
+// out[0] = max_i P_ii H_ii (the largest variance inflation factor 1 / (1 - R_i^2) of a kept row: how much of row i the other
+// kept rows explain), out[1] = 1 if any entry of the diagonal of P is not finite.  One workgroup.
+__global__ __launch_bounds__(1024) void vif_max_kernel(const float* __restrict__ P, const float* __restrict__ H, int n, double* __restrict__ out) {
+  __shared__ double sh[16];
+  __shared__ int bad[16];
+  double v = 0.0; int b = 0;
+  for (int i = threadIdx.x; i < n; i += 1024) {
+    const double x = (double)P[(int64_t)i * n + i] * (double)H[(int64_t)i * n + i];
+    if (!(x == x) || !(fabs(x) < 1e300)) b = 1; else v = fmax(v, x);
+  }
+  for (int o = 32; o > 0; o >>= 1) { v = fmax(v, __shfl_down(v, o, 64)); b |= __shfl_down(b, o, 64); }
+  if ((threadIdx.x & 63) == 0) { sh[threadIdx.x >> 6] = v; bad[threadIdx.x >> 6] = b; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int i = 1; i < 16; i++) { v = fmax(v, sh[i]); b |= bad[i]; }
+    out[0] = v; out[1] = (double)b;
+  }
+}
+
+// The inverse by the float64-storage sweep (default), or by the float32 sweep refined by Newton-Schulz
+// (osscar_debug_refined_inverse(1): the two are held against each other in the tests).
+bool g_refined_inverse = false;
+
 // B_known (optional, kr x m): the weights are known exactly (dense layer: B = W), only G_K is gathered beside them.
 osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b, const float* B_known = nullptr) {
   hipStream_t s = c->stream;
   const int kr = c->kr, m = c->m;
   HIPCHK(c, launch_gather(c->H, c->d1, c->rowsK, kr, c->rowsK, kr, b.HKK, kr, s));
   if (b.i8 && b.i8->kexp) HIPCHK(c, launch_i8_kexp(b.HKK, kr, kr, b.i8->kexp, s));
-  HIPCHK(c, launch_gather(c->H, c->d1, c->rowsK, kr, c->rowsK, kr, b.P, kr, s));
   HIPCHK(c, hipMemsetAsync(c->notpd, 0, 64 * 4, s));
-  HIPCHK(c, spd_inverse_inplace(b.P, kr, b.panels, b.panels + (int64_t)kr * INV_NB, c->small, c->notpd, s));
-  // Newton-Schulz: P <- P + P (I - H_KK P), residual accumulated in float64
   const SplitBufs* sp = b.sp;
   osscar_status st = OSSCAR_OK;
+  bool correct = false;          // does B = P G_K get its residual correction?
   TileRef t_low{}, t_b{};
   if (sp) {
     if ((st = stage_tiles(c, 0, kr, kr, true, &t_low)) != OSSCAR_OK) return st;
     if ((st = stage_tiles(c, 1, kr, m, false, &t_b)) != OSSCAR_OK) return st;
   }
+  if (!g_refined_inverse) {
+    // The sweep on a float64 copy of H_KK (in the memory of T1 and T2), rounded to float32 once: exact to that rounding.
+    HIPCHK(c, hipEventRecord(c->ev_s[2][0], s));
+    HIPCHK(c, spd_inverse_f64(b.HKK, kr, kr, b.P, reinterpret_cast<double*>(b.T1), reinterpret_cast<double*>(b.panels), c->small, c->notpd, s));
+    HIPCHK(c, hipEventRecord(c->ev_s[2][1], s));
+    HIPCHK(c, launch_absmax(b.P, (int64_t)kr * kr, c->partial, s));
+    hipLaunchKernelGGL(vif_max_kernel, dim3(1), dim3(1024), 0, s, b.P, b.HKK, kr, c->scal + 20);
+    double part[256], vif[2] = {0, 0}; int32_t bad = 0;
+    HIPCHK(c, hipMemcpyAsync(part, c->partial, sizeof part, hipMemcpyDeviceToHost, s));
+    HIPCHK(c, hipMemcpyAsync(vif, c->scal + 20, 16, hipMemcpyDeviceToHost, s));
+    HIPCHK(c, hipMemcpyAsync(&bad, c->notpd, 4, hipMemcpyDeviceToHost, s));
+    HIPCHK(c, hipStreamSynchronize(s));
+    { float ms = 0; hipEventElapsedTime(&ms, c->ev_s[2][0], c->ev_s[2][1]); c->timers[9] = ms; }
+    c->timers[10] = 0; c->timers[11] = vif[0];
+    double pmax = 0;
+    for (double v : part) if (v > pmax || v != v) pmax = v;      // a NaN anywhere in P makes pmax NaN
+    if (bad || vif[1] != 0.0 || !(pmax < 1e300) || !(vif[0] >= 0.999))
+      return fail(c, OSSCAR_ENOTPD, "H restricted to the kept rows is not positive definite to working precision "
+                                     "(pivot flag %d, largest |P| %.3g, largest P_ii H_ii %.3g)", bad, pmax, vif[0]);
+    // P is exact to its float32 rounding, which still costs B = P G_K about 6e-8 times the cancellation in that product.
+    // The largest P_ii H_ii measures it: 1.5 - 25 on the benchmark recipes and the correlated test layers, 270 and 1800 on
+    // the two test layers where B without the correction left the objective off by more than 1e-5; from 100 on B is
+    // corrected against its float64 residual.
+    correct = vif[0] >= 100.0;
+  } else {
+  HIPCHK(c, launch_gather(c->H, c->d1, c->rowsK, kr, c->rowsK, kr, b.P, kr, s));
+  HIPCHK(c, spd_inverse_inplace(b.P, kr, b.panels, b.panels + (int64_t)kr * INV_NB, c->small, c->notpd, s));
+  // Newton-Schulz: P <- P + P (I - H_KK P), residual accumulated in float64
   double last_resid = 1.0;
   for (int step = 0; step < 3; step++) {
     HIPCHK(c, hipEventRecord(c->ev_s[2][0], s));
@@ -419,6 +468,9 @@ osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b, const float* 
       return fail(c, OSSCAR_ENOTPD, "the inverse of H on the kept rows did not converge (|I - H P|_max = %.3g after three "
                                      "Newton-Schulz steps): H_KK is too ill-conditioned for float32 storage", resid);
   }
+  // the residual before the last step is this path's measure of the conditioning (2e-5 on the benchmark layers)
+  correct = !(last_resid < 4e-5);
+  }
 
   // B = P G_K, then B += P (G_K - H_KK B)
   HIPCHK(c, launch_gather(c->G, m, c->rowsK, kr, nullptr, m, b.GK, m, s));
@@ -426,11 +478,6 @@ osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b, const float* 
     HIPCHK(c, hipMemcpyAsync(b.B, B_known, (size_t)kr * m * 4, hipMemcpyDeviceToDevice, s));
     return OSSCAR_OK;
   }
-  // After the last step |I - H P| is about last_resid^2, so the inverse is exact to its float32 storage.  That rounding alone
-  // still costs B = P G_K about 6e-8 times the cancellation in the product, which grows with the conditioning of H_KK; the
-  // residual before the step is a cheap measure of it (2e-5 on the OPT-shaped benchmark layers, 1e-4 and more on layers
-  // where B = P G_K alone left the objective off by 1e-3), and above 4e-5 B is corrected against the float64 residual.
-  const bool correct = !(last_resid < 4e-5);
   float* B0 = correct ? b.T3 : b.B;
   HIPCHK(c, big_gemm(s, b.i8, kr, m, kr, b.P, kr, b.GK, m, nullptr, 0, B0, m, 1.0, 0.0, 0.0, 0, 1, 0, 1));
   if (!correct) return OSSCAR_OK;
@@ -471,9 +518,10 @@ I8Bufs carve_i8(osscar_ctx* c, Carve& cv) {
 InvBufs carve_inv(osscar_ctx* c, Carve& cv) {
   const int64_t kr = c->kr, m = c->m;
   InvBufs b;
-  b.HKK = cv.take<float>(kr * kr); b.P = cv.take<float>(kr * kr); b.T1 = cv.take<float>(kr * kr); b.T2 = cv.take<float>(kr * kr);
+  b.HKK = cv.take<float>(kr * kr); b.P = cv.take<float>(kr * kr);
+  b.T1 = cv.take<float>(2 * kr * kr); b.T2 = b.T1 + kr * kr;      // together: the kr x kr float64 work matrix of the sweep inverse
   b.GK = cv.take<float>(kr * m); b.B = cv.take<float>(kr * m); b.T3 = cv.take<float>(kr * m); b.T4 = cv.take<float>(kr * m);
-  b.panels = cv.take<float>(3 * kr * INV_NB);
+  b.panels = cv.take<float>(6 * kr * INV_NB);                      // three panels of float64
   return b;
 }
 
@@ -1393,6 +1441,7 @@ int32_t osscar_debug_tile_schedule(int64_t d1, int32_t* out_host, int32_t capaci
 
 osscar_status osscar_debug_gemm_log(int32_t enable) { gemm_log_enable(enable); return OSSCAR_OK; }
 osscar_status osscar_debug_int_products(int32_t enable) { g_i8_products = enable != 0; return OSSCAR_OK; }
+osscar_status osscar_debug_refined_inverse(int32_t enable) { g_refined_inverse = enable != 0; return OSSCAR_OK; }
 int32_t osscar_debug_gemm_log_read(double* out_host, int32_t capacity) {
   if (!out_host || capacity < 0) return -1;
   return gemm_log_read(out_host, capacity);

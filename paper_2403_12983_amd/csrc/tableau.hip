@@ -381,6 +381,285 @@ hipError_t spd_inverse_inplace(float* A, int n, float* panel, float* panelD, dou
 }
 
 // ------------------------------------------------------------------------------------------------
+// The same blocked sweep with the working matrix held in float64.  In float32 storage every one of the n / 128 panel
+// updates rounds every entry again, and the inverse comes out with |I - H P| of 1e-5: it then needs a Newton-Schulz step
+// whose residual I - H P is a full n^3 product with float64 sums (93 ms for n = 14336, a third of the state build).  Held
+// in float64 the swept matrix is exact to 1e-12 and is rounded to float32 once: the same accuracy as after that step, for a
+// rank-128 update that moves 16 bytes per entry instead of 8 (0.5 ms instead of 0.33 ms per panel).
+// ------------------------------------------------------------------------------------------------
+constexpr int PANEL_ROWS64 = 32;
+__device__ __forceinline__ double nsym64(const double* __restrict__ N, int64_t ld, int i, int t) {
+  return (i >= t) ? N[(int64_t)i * ld + t] : N[(int64_t)t * ld + i];
+}
+// A[i][j] = H[i][j] for j <= i (only the lower triangle is ever read)
+__global__ void widen_lower_kernel(const float* __restrict__ H, int64_t ldh, int n, double* __restrict__ A) {
+  const int64_t tot = (int64_t)n * n;
+  for (int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; idx < tot; idx += (int64_t)gridDim.x * blockDim.x) {
+    const int i = (int)(idx / n), j = (int)(idx % n);
+    if (j <= i) A[idx] = (double)H[(int64_t)i * ldh + j];
+  }
+}
+// P[i][j] = P[j][i] = float(-A[i][j]), j <= i: the swept lower triangle -H^-1 as the full float32 inverse
+__global__ void narrow_negate_mirror_kernel(const double* __restrict__ A, int n, float* __restrict__ P) {
+  const int64_t tot = (int64_t)n * n;
+  for (int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; idx < tot; idx += (int64_t)gridDim.x * blockDim.x) {
+    const int i = (int)(idx / n), j = (int)(idx % n);
+    P[idx] = (float)(-(j <= i ? A[idx] : A[(int64_t)j * n + i]));
+  }
+}
+__global__ __launch_bounds__(256) void extract_panel64_kernel(const double* __restrict__ N, int64_t ld, int n, int t0, int w,
+                                                               double* __restrict__ C) {
+  __shared__ double T[PANEL_ROWS64][129];
+  const int i0 = blockIdx.x * PANEL_ROWS64, tid = threadIdx.x;
+  if (i0 >= t0 + w) {
+    for (int idx = tid; idx < PANEL_ROWS64 * w; idx += 256) {
+      const int r = idx / w, c = idx % w;
+      if (i0 + r < n) C[(int64_t)(i0 + r) * w + c] = N[(int64_t)(i0 + r) * ld + t0 + c];
+    }
+    return;
+  }
+  if (i0 + PANEL_ROWS64 <= t0) {
+    for (int idx = tid; idx < PANEL_ROWS64 * w; idx += 256) {
+      const int c = idx / PANEL_ROWS64, r = idx % PANEL_ROWS64;
+      T[r][c] = N[(int64_t)(t0 + c) * ld + i0 + r];
+    }
+  } else {
+    for (int idx = tid; idx < PANEL_ROWS64 * w; idx += 256) {
+      const int r = idx / w, c = idx % w;
+      T[r][c] = (i0 + r < n) ? nsym64(N, ld, i0 + r, t0 + c) : 0.0;
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < PANEL_ROWS64 * w; idx += 256) {
+    const int r = idx / w, c = idx % w;
+    if (i0 + r < n) C[(int64_t)(i0 + r) * w + c] = T[r][c];
+  }
+}
+__global__ __launch_bounds__(256) void inv_block64_kernel(const double* __restrict__ C, int w, int t0, double* __restrict__ D,
+                                                           int32_t* notpd) {
+  __shared__ double buf[64 * (INV_NB / 16)];
+  for (int idx = threadIdx.x; idx < w * w; idx += 256) {
+    const int r = idx / w, c = idx % w;
+    D[idx] = C[(int64_t)(t0 + r) * w + c];
+  }
+  small_inverse<INV_NB / 16>(D, w, +1, notpd, buf);
+}
+// outz = C D and Cz = C, both with the pivot rows zeroed: the operands of the bulk update; the pivot-row fix reads outz
+// outside the pivot rows only.  8 rows per workgroup, thread (h, c) sums 4 rows of column c, k ascending.
+__global__ __launch_bounds__(256) void panel_times_small64_kernel(const double* __restrict__ C, const double* __restrict__ D, int n, int w,
+                                                                   int t0, double* __restrict__ outz, double* __restrict__ Cz) {
+  __shared__ double Csh[8][128];
+  const int r0 = blockIdx.x * 8, tid = threadIdx.x;
+  for (int idx = tid; idx < 8 * w; idx += 256) {
+    const int r = idx / w, k = idx % w;
+    Csh[r][k] = (r0 + r < n) ? C[(int64_t)(r0 + r) * w + k] : 0.0;
+  }
+  __syncthreads();
+  const int c = tid & 127, h = tid >> 7;
+  if (c >= w) return;
+  double acc[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int k = 0; k < w; k++) {
+    const double dv = D[k * w + c];
+#pragma unroll
+    for (int r = 0; r < 4; r++) acc[r] += Csh[h * 4 + r][k] * dv;
+  }
+#pragma unroll
+  for (int r = 0; r < 4; r++) {
+    const int i = r0 + h * 4 + r;
+    if (i >= n) continue;
+    const bool piv = i >= t0 && i < t0 + w;
+    outz[(int64_t)i * w + c] = piv ? 0.0 : acc[r];
+    Cz[(int64_t)i * w + c] = piv ? 0.0 : Csh[h * 4 + r][c];
+  }
+}
+__global__ __launch_bounds__(256) void inv_fix64_kernel(double* __restrict__ N, int64_t ld, int n, int t0, int w,
+                                                         const double* __restrict__ CD, const double* __restrict__ D) {
+  __shared__ double T[PANEL_ROWS64][129];
+  const int i0 = blockIdx.x * PANEL_ROWS64, tid = threadIdx.x;
+  if (i0 >= t0 + w) {
+    for (int idx = tid; idx < PANEL_ROWS64 * w; idx += 256) {
+      const int r = idx / w, c = idx % w;
+      if (i0 + r < n) N[(int64_t)(i0 + r) * ld + t0 + c] = CD[(int64_t)(i0 + r) * w + c];
+    }
+    return;
+  }
+  for (int idx = tid; idx < PANEL_ROWS64 * w; idx += 256) {
+    const int r = idx / w, c = idx % w;
+    T[r][c] = (i0 + r < n) ? CD[(int64_t)(i0 + r) * w + c] : 0.0;
+  }
+  __syncthreads();
+  if (i0 + PANEL_ROWS64 <= t0) {
+    for (int idx = tid; idx < PANEL_ROWS64 * w; idx += 256) {
+      const int c = idx / PANEL_ROWS64, r = idx % PANEL_ROWS64;
+      N[(int64_t)(t0 + c) * ld + i0 + r] = T[r][c];
+    }
+    return;
+  }
+  for (int idx = tid; idx < PANEL_ROWS64 * w; idx += 256) {
+    const int r = idx / w, c = idx % w, l = i0 + r;
+    if (l >= n) continue;
+    if (l < t0) N[(int64_t)(t0 + c) * ld + l] = T[r][c];
+    else if (l >= t0 + w) N[(int64_t)l * ld + t0 + c] = T[r][c];
+    else if (c <= l - t0) N[(int64_t)l * ld + t0 + c] = -D[(l - t0) * w + c];
+  }
+}
+
+// N[i][j] -= sum_k A[i][k] B[j][k] on the tiles of the lower block triangle; A, B: n x w float64 (w <= 128), N: n x n float64.
+// One workgroup per 128 x 128 tile, 4 waves x (4 x 4) v_mfma_f64_16x16x4_f64, the contraction in steps of 16 through LDS
+// (rows of 144 doubles: the four k of a quarter-wave's operand read fall in different bank groups); the tile of N is read,
+// changed and written from registers, 16 values per thread at a time.  Tiles in 8 x 8 super-blocks per XCD.
+typedef double swd4 __attribute__((ext_vector_type(4)));
+constexpr int SW_LD = 144;
+__global__ __launch_bounds__(256, 2) void sweep_update64_kernel(const double* __restrict__ A, const double* __restrict__ B, int n, int w,
+                                                                 double* __restrict__ N) {
+  extern __shared__ double sw_lds[];           // 72 KB: above the static limit, so taken dynamically
+  double (*As)[16][SW_LD] = reinterpret_cast<double (*)[16][SW_LD]>(sw_lds);
+  double (*Bs)[16][SW_LD] = reinterpret_cast<double (*)[16][SW_LD]>(sw_lds + 2 * 16 * SW_LD);
+  int tm, tn;
+  {
+    const int tiles = (n + 127) / 128, nr = (tiles + 7) / 8;
+    const int b = blockIdx.x, xcd = b & 7, slot = b >> 3;
+    const int sb = (slot / 64) * 8 + xcd, within = slot % 64;
+    if (sb >= nr * (nr + 1) / 2) return;
+    int r = (int)((sqrtf(8.f * (float)sb + 1.f) - 1.f) * 0.5f);
+    while ((r + 1) * (r + 2) / 2 <= sb) r++;
+    while (r * (r + 1) / 2 > sb) r--;
+    tm = r * 8 + within / 8;
+    tn = (sb - r * (r + 1) / 2) * 8 + within % 8;
+    if (tm >= tiles || tn > tm) return;
+  }
+  const int m0 = tm * 128, n0 = tn * 128;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+  const int lrow = tid >> 1, lk = (tid & 1) * 8;        // staging: thread = (row of the tile, half of the 16 k)
+  const double* ap = (m0 + lrow < n) ? A + (int64_t)(m0 + lrow) * w : nullptr;
+  const double* bp = (n0 + lrow < n) ? B + (int64_t)(n0 + lrow) * w : nullptr;
+  swd4 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+#pragma unroll
+    for (int j = 0; j < 4; j++) acc[i][j] = swd4{0.0, 0.0, 0.0, 0.0};
+  double ra[8], rb[8];
+  const int ktiles = (w + 15) / 16;
+  const bool vec = (w & 7) == 0;       // then a thread's eight k are inside or outside as a whole, and 64-byte aligned
+  auto gload = [&](int kt) {
+    const int k0 = kt * 16 + lk;
+    if (vec) {
+      if (ap && k0 < w) {
+        const double2* p = reinterpret_cast<const double2*>(ap + k0);
+#pragma unroll
+        for (int e = 0; e < 4; e++) { const double2 q = p[e]; ra[2 * e] = q.x; ra[2 * e + 1] = q.y; }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; e++) ra[e] = 0.0;
+      }
+      if (bp && k0 < w) {
+        const double2* p = reinterpret_cast<const double2*>(bp + k0);
+#pragma unroll
+        for (int e = 0; e < 4; e++) { const double2 q = p[e]; rb[2 * e] = q.x; rb[2 * e + 1] = q.y; }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; e++) rb[e] = 0.0;
+      }
+      return;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      const int k = k0 + e;
+      ra[e] = (ap && k < w) ? ap[k] : 0.0;
+      rb[e] = (bp && k < w) ? bp[k] : 0.0;
+    }
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int e = 0; e < 8; e++) { As[buf][lk + e][lrow] = ra[e]; Bs[buf][lk + e][lrow] = rb[e]; }
+  };
+  // the first 16 rows of this wave's part of the tile of N are requested now and arrive while the products run
+  const int rbase = m0 + wm * 64 + (lane >> 4), cbase = n0 + wn * 64 + (lane & 15);
+  double cv[4][4];
+  auto cload = [&](int i, double (&dst)[4][4]) {
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        const int row = rbase + i * 16 + 4 * r, col = cbase + j * 16;
+        dst[j][r] = (row < n && col < n) ? N[(int64_t)row * n + col] : 0.0;
+      }
+  };
+  cload(0, cv);
+  if (ktiles > 0) { gload(0); sstore(0); }
+  __syncthreads();
+  for (int kt = 0; kt < ktiles; kt++) {
+    const int buf = kt & 1;
+    if (kt + 1 < ktiles) gload(kt + 1);
+#pragma unroll
+    for (int kk = 0; kk < 4; kk++) {
+      const int k = kk * 4 + (lane >> 4);
+      double a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; i++) a[i] = As[buf][k][wm * 64 + i * 16 + (lane & 15)];
+#pragma unroll
+      for (int j = 0; j < 4; j++) b[j] = Bs[buf][k][wn * 64 + j * 16 + (lane & 15)];
+#pragma unroll
+      for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < ktiles) sstore(buf ^ 1);
+    __syncthreads();
+  }
+  // lane holds D[4 r + lane/16][lane%16] of each 16 x 16 tile; the next 16 rows are requested before these are stored
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    double nx[4][4];
+    if (i < 3) cload(i + 1, nx);
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        const int row = rbase + i * 16 + 4 * r, col = cbase + j * 16;
+        if (row < n && col < n) N[(int64_t)row * n + col] = cv[j][r] - acc[i][j][r];
+      }
+    if (i < 3) {
+#pragma unroll
+      for (int j = 0; j < 4; j++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) cv[j][r] = nx[j][r];
+    }
+  }
+}
+
+// P (n x n float32, full) = H^-1 for the SPD H (n x n float32, leading dimension ldh; only its lower triangle is read).
+// A64: n x n float64 work matrix; panels: 3 n INV_NB float64; small: INV_NB^2 float64; notpd_flag as for spd_inverse_inplace.
+hipError_t spd_inverse_f64(const float* H, int64_t ldh, int n, float* P, double* A64, double* panels, double* small,
+                           int32_t* notpd_flag, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  const int64_t tot = (int64_t)n * n;
+  int blocks = (int)((tot + 1023) / 1024); if (blocks > 131072) blocks = 131072;
+  hipLaunchKernelGGL(widen_lower_kernel, dim3(blocks), dim3(256), 0, s, H, ldh, n, A64);
+  double* panel = panels;
+  double* panelDz = panels + (int64_t)n * INV_NB;
+  double* panelCz = panels + 2 * (int64_t)n * INV_NB;
+  const size_t shmem = (size_t)2 * 2 * 16 * SW_LD * sizeof(double);
+  {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sweep_update64_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+    if (e != hipSuccess) return e;
+  }
+  const int tiles = (n + 127) / 128, nr = (tiles + 7) / 8;
+  const unsigned upd_grid = (unsigned)((nr * (nr + 1) / 2 + 7) / 8 * 8 * 64);
+  const int rb = (n + PANEL_ROWS64 - 1) / PANEL_ROWS64;
+  for (int t0 = 0; t0 < n; t0 += INV_NB) {
+    const int w = (n - t0 < INV_NB) ? n - t0 : INV_NB;
+    hipLaunchKernelGGL(extract_panel64_kernel, dim3(rb), dim3(256), 0, s, A64, (int64_t)n, n, t0, w, panel);
+    hipLaunchKernelGGL(inv_block64_kernel, dim3(1), dim3(256), 0, s, panel, w, t0, small, notpd_flag);
+    hipLaunchKernelGGL(panel_times_small64_kernel, dim3((n + 7) / 8), dim3(256), 0, s, panel, small, n, w, t0, panelDz, panelCz);
+    hipLaunchKernelGGL(sweep_update64_kernel, dim3(upd_grid), dim3(256), shmem, s, panelDz, panelCz, n, w, A64);
+    hipLaunchKernelGGL(inv_fix64_kernel, dim3(rb), dim3(256), 0, s, A64, (int64_t)n, n, t0, w, panelDz, small);
+  }
+  hipLaunchKernelGGL(narrow_negate_mirror_kernel, dim3(blocks), dim3(256), 0, s, A64, n, P);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
 // scores: gram[h] = Z_h Z_h^T, dblk[h] = N_hh (float64), score[h] = Tr(gram_h |N_hh|^-1)
 // ------------------------------------------------------------------------------------------------
 // one workgroup per group; wave w takes the pairs (r, c), c <= r, in a fixed order, lanes over columns

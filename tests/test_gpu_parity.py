@@ -211,6 +211,36 @@ def test_int8_digit_products_match_float64_accumulation(name):
     assert rel(W1, W2) < 1e-6 and abs(f1 - f2) <= 1e-7 * abs(f2)
 
 
+@pytest.mark.parametrize("name", ["cfg2s", "cfg3s", "cfg5odd", "mix_bf16_f32", "i8ragged", "i8even"])
+def test_float64_sweep_inverse_matches_the_refined_float32_one(name):
+    """P = H_KK^-1 by the blocked sweep on a float64 copy, rounded to float32 once (the default), against the sweep in
+    float32 storage refined by Newton-Schulz steps with a float64-accumulated residual: both are the inverse to float32
+    rounding, so they agree entry by entry to a few units of it (relative to sqrt(P_ii P_jj)) and both meet the oracle."""
+    from paper_2403_12983_amd import binding as B
+    c = case(name)
+    cfg = c.cfg
+    st = orc.init_state(c.H, c.G, c.K0, cfg.q)
+    dp = np.sqrt(np.diag(st.P))
+    out = []
+    try:
+        for refined in (False, True):
+            B.refined_inverse(refined)
+            s = c.solver()
+            c.gram(s)
+            obj0 = s.osscar_init_support()
+            out.append((obj0, T(s, "T_P"), T(s, "T_B"), s.osscar_get_timers()[11]))
+            s.close()
+    finally:
+        B.refined_inverse(False)
+    (o1, P1, B1, vif), (o2, P2, B2, resid) = out
+    assert vif >= 1.0 and resid < 1e-3                     # slot 11: largest P_ii H_ii on one route, |I - H P| on the other
+    assert np.max(np.abs(P1 - P2) / np.outer(dp, dp)) < 3e-7
+    for P in (P1, P2):
+        assert np.max(np.abs(P - st.P) / np.outer(dp, dp)) < 2e-5
+    assert rel(B1, st.What_K) < 2e-5 and rel(B2, st.What_K) < 2e-5
+    assert abs(o1 - o2) <= 2e-6 * abs(o2)
+
+
 def check_trajectory(c, r, rel_tol=0.0, always=False, exact_in=False, tol_obj=1e-5, tol_score=0.0):
     """The library's trajectory replayed by the oracle: every choice within GAP of the oracle's best, every
     applied swap improving, the stop justified, the objective trace equal to tol_obj.  tol_score: relative error granted to
@@ -375,7 +405,7 @@ def test_search_variants(name):
     # the diagnostics: sixteen slots, times of the calls made are positive, slot 11 is the residual of the sweep inverse
     tm = s.osscar_get_timers()
     assert len(tm) == 16 and all(np.isfinite(tm)) and all(t >= 0 for t in tm)
-    assert tm[1] > 0 and tm[2] > 0 and tm[3] > 0 and 0 <= tm[11] < 1e-3
+    assert tm[1] > 0 and tm[2] > 0 and tm[3] > 0 and tm[11] >= 1.0      # slot 11: the largest P_ii H_ii of the kept rows
     s.close()
 
 
