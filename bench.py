@@ -24,8 +24,8 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 # HBM-side bytes per launch on cfg5 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a 1 GiB copy
 # (profiles/gemm_f64acc_cfg5_pmc.md: mean over the launches of one layer; profiles/gram_packed_cfg5_pmc.md: one chunk)
-GEMM64_TRAFFIC_CFG5 = 0.948e9
-GRAM_TRAFFIC_CFG5 = 97.25e9
+GEMM64_TRAFFIC_CFG5 = 0.498e9
+GRAM_TRAFFIC_CFG5 = 95.1e9
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -249,10 +249,21 @@ def main():
     gl_flops = float(rows_per_launch) * d1 * (d1 + 1)
     gl_bytes = 2.0 * rows_per_launch * d1 + 8.0 * d1 * (d1 + 1)       # the packed chunk read once; the float64 lower triangle read and written
     gram_traffic = GRAM_TRAFFIC_CFG5 if (a.config == "cfg5" and a.rows is None) else None
-    g_flops = 2.0 * n_inv ** 3                                         # largest float64-accumulating launch: I - H_KK P
-    g_bytes = 4.0 * 3 * n_inv * n_inv
+    # the inverse by the float64 sweep (timer slot 9): n / 128 rank-128 updates of the lower triangle, n^3 flops in all,
+    # each reading and writing the 8-byte triangle once
+    inv_flops = float(n_inv) ** 3
+    inv_bytes = 2.0 * 8.0 * (n_inv * (n_inv + 128) / 2.0) * ((n_inv + 127) // 128)
     # mean algorithmic bytes of a float64-accumulating launch: A and B read once, C written once (float32; 8 bytes for a float64 output)
     rows64 = [r for r in log if not int(r[3]) & 17]
+    big64 = None
+    if rows64:
+        rb_ = max(rows64, key=lambda r: r[0] * r[1] * r[2])
+        same = [r for r in rows64 if (r[0], r[1], r[2], r[3]) == (rb_[0], rb_[1], rb_[2], rb_[3]) and r[4] > 0]
+        fl_ = 2.0 * rb_[0] * rb_[1] * rb_[2] * (0.5 if int(rb_[3]) & 4 else 1.0)
+        ms_ = sum(r[4] for r in same) / max(len(same), 1)
+        big64 = {"what": f"{int(rb_[0])} x {int(rb_[1])} x {int(rb_[2])}: the residual G_K - H_KK B of the back-solve", "flops": fl_,
+                 "ms": ms_ if ms_ > 0 else None, "achieved": fl_ / (ms_ * 1e-3) / 1e12 if ms_ > 0 else None,
+                 "frac": fl_ / (ms_ * 1e-3) / 1e12 / 78.6 if ms_ > 0 else None}
     alg64 = (sum(4.0 * (r[0] * r[2] + r[2] * r[1]) + (8.0 if int(r[3]) & 2 else 4.0) * r[0] * r[1] * (0.5 if int(r[3]) & 4 else 1.0)
                  for r in rows64) / len(rows64)) if rows64 else None
     out = {
@@ -293,10 +304,17 @@ def main():
                                  "flops_per_launch": (w64 * 1e12 * ms64 * 1e-3 / n64) if (w64 and n64) else None,
                                  "ms_per_launch": (ms64 / n64) if n64 else None,
                                  "algorithmic_bytes_per_launch": alg64,
-                                 "largest_launch": {"what": "I - H_KK P of the Newton-Schulz step", "flops": g_flops,
-                                                    "algorithmic_bytes": g_bytes, "ms": gemm_ms if gemm_ms > 0 else None,
-                                                    "achieved": g_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None,
-                                                    "frac": g_flops / (gemm_ms * 1e-3) / 1e12 / 78.6 if gemm_ms > 0 else None}},
+                                 "largest_launch": big64},
+        # The inverse of H on the kept rows: blocked sweep on a float64 copy, n / 128 panels; the rank-128 update of the 8-byte
+        # lower triangle (sweep_update64_kernel) is bound by the float64 matrix cores and by the read + write of the triangle
+        # alike; the duration (timer slot 9) also contains the 128 x 128 pivot inverses, one workgroup each.
+        "roofline_inverse_sweep": {"kernel": "spd_inverse_f64: sweep_update64_kernel + panel kernels, order "
+                                             f"{n_inv}", "ms": gemm_ms if gemm_ms > 0 else None, "flops": inv_flops,
+                                   "algorithmic_bytes": inv_bytes,
+                                   "TFLOPs": inv_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None,
+                                   "frac_of_fp64_mfma_peak": inv_flops / (gemm_ms * 1e-3) / 1e12 / 78.6 if gemm_ms > 0 else None,
+                                   "GBps": inv_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else None,
+                                   "frac_of_hbm_peak": inv_bytes / (gemm_ms * 1e-3) / 1e9 / 8000.0 if gemm_ms > 0 else None},
         # The state-build products B, V, S, R on the int8 matrix cores: fifteen digit products per float product, so the pipe
         # runs 15 x the float rate; durations include the scaling and cutting of both operands.
         "roofline_gemm_int8": {"kernel": "i8_gemm_kernel (+ its packing kernels): float32 operands as five 7-bit digits, exact int32 sums; "
@@ -304,10 +322,9 @@ def main():
                                "bound": "mfma", "achieved": (15 * w8 / 1000.0) if w8 else None, "peak": 5.0, "unit": "POP/s",
                                "frac": (15 * w8 / 5000.0) if w8 else None, "float_equivalent_TFLOPs": w8,
                                "launches_per_layer": n8, "ms_per_layer": ms8},
-        # The float32-accumulating MFMA GEMM (v_mfma_f32_32x32x2_f32): the panel sweeps of the blocked inverse and E = C0 M^-1 of
-        # every flush; total flops / total time over all its launches of the timed steps.
-        "roofline_gemm_f32acc": {"kernel": "gemm_f32acc_kernel (float32 MFMA accumulation): sweeps of the inverse (bound by the "
-                                           "read and write of C), E = C0 M^-1 of the flushes", "bound": "mfma", "peak": 157.3, "unit": "TFLOP/s",
+        # The float32-accumulating MFMA GEMM (v_mfma_f32_32x32x2_f32): only the second route of the inverse and shapes that
+        # the packed kernels do not take launch it; total flops / total time over its launches of the timed steps (none on cfg5).
+        "roofline_gemm_f32acc": {"kernel": "gemm_f32acc_kernel (float32 MFMA accumulation)", "bound": "mfma", "peak": 157.3, "unit": "TFLOP/s",
                                  "achieved": w32, "frac": (w32 / 157.3) if w32 else None, "launches_per_layer": n32, "ms_per_layer": ms32},
         "state_build": {"candidate_side_products_ms": cand_ms, "inverse_correction_product_ms": gemm32_ms},
         "roofline_gram_phase": {"kernel": "gram_pack_kernel + gram_packed_kernel, the whole Gram phase (repacking included)",
