@@ -261,7 +261,7 @@ def main():
         same = [r for r in rows64 if (r[0], r[1], r[2], r[3]) == (rb_[0], rb_[1], rb_[2], rb_[3]) and r[4] > 0]
         fl_ = 2.0 * rb_[0] * rb_[1] * rb_[2] * (0.5 if int(rb_[3]) & 4 else 1.0)
         ms_ = sum(r[4] for r in same) / max(len(same), 1)
-        big64 = {"what": f"{int(rb_[0])} x {int(rb_[1])} x {int(rb_[2])}: the residual G_K - H_KK B of the back-solve", "flops": fl_,
+        big64 = {"what": f"{int(rb_[0])} x {int(rb_[1])} x {int(rb_[2])}", "flops": fl_,
                  "ms": ms_ if ms_ > 0 else None, "achieved": fl_ / (ms_ * 1e-3) / 1e12 if ms_ > 0 else None,
                  "frac": fl_ / (ms_ * 1e-3) / 1e12 / 78.6 if ms_ > 0 else None}
     alg64 = (sum(4.0 * (r[0] * r[2] + r[2] * r[1]) + (8.0 if int(r[3]) & 2 else 4.0) * r[0] * r[1] * (0.5 if int(r[3]) & 4 else 1.0)

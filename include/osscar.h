@@ -253,8 +253,8 @@ int32_t osscar_debug_gemm_log_read(double* out_host, int32_t capacity);
 
 /* The large products that define the state of a support (every dimension >= 1024: B = P G_K, V = P H_{K,Kc}, the Schur
  * complement S and R of Proposition 4.1's closed forms) run on the int8 matrix cores from five 7-bit digits per float32
- * operand, with exact integer sums (kind 16 in the log above); smaller ones, and the three residuals that refine the inverse,
- * the weights and the back-solve, on the float64-accumulating kernel.  osscar_debug_int_products(0) sends all of them to the
+ * operand, with exact integer sums (kind 16 in the log above), and so does the residual of the back-solve; smaller ones, and
+ * the residuals that involve the inverse, on the float64-accumulating kernel.  osscar_debug_int_products(0) sends all of them to the
  * float64-accumulating kernel, osscar_debug_int_products(1) restores the default.  Process-wide, for tests that hold the two
  * against each other. */
 osscar_status osscar_debug_int_products(int32_t enable);

@@ -282,8 +282,9 @@ hipError_t gemm(hipStream_t s, int M, int N, int K, const float* A, int64_t lda,
 }
 
 // The large products that define the state (B = P G_K, V, S, R): on the int8 matrix cores (i8gemm.hip) when every dimension
-// is at least I8_MIN_DIM and the scratch is there, else on the float64-accumulating kernel, which also keeps the three
-// residuals (of the inverse, of the weights, of the back-solve).  osscar_debug_int_products(0) sends everything there (tests).
+// is at least I8_MIN_DIM and the scratch is there, else on the float64-accumulating kernel, which also keeps the residuals
+// that involve P (of the Newton-Schulz route of the inverse, of the weight correction).  osscar_debug_int_products(0) sends
+// everything there (tests).
 struct I8Bufs {
   void* packA = nullptr; void* packB = nullptr; unsigned* mx = nullptr; size_t capA = 0, capB = 0, mx_entries = 0;
   int* kexp = nullptr;      // round(log2 sqrt(H_kk)) of the kept rows (the contraction index of every large product), once per state build
@@ -1311,6 +1312,7 @@ osscar_status osscar_backsolve(osscar_ctx* c, void* What, int64_t ldw_hat, int32
   {
     const int kr = c->kr, m = c->m;
     HIPCHK(c, launch_gather(c->H, c->d1, c->rowsK, kr, c->rowsK, kr, b.HKK, kr, s));
+    HIPCHK(c, launch_i8_kexp(b.HKK, kr, kr, ib.kexp, s));
     HIPCHK(c, launch_gather(c->G, m, c->rowsK, kr, nullptr, m, b.GK, m, s));
     hipLaunchKernelGGL(gather_sym_kernel, dim3(grid_for((int64_t)kr * kr)), dim3(256), 0, s, c->N, (int64_t)c->d1, c->rowsK, kr,
                        c->rowsK, kr, b.P, -1.f);
@@ -1322,7 +1324,9 @@ osscar_status osscar_backsolve(osscar_ctx* c, void* What, int64_t ldw_hat, int32
     }
     bool ok = false;
     for (int step = 0; step < 3 && !ok; step++) {
-      HIPCHK(c, gemm(s, kr, m, kr, b.HKK, kr, b.B, m, b.GK, m, b.T4, m, -1.0, 1.0));      // residual: float64 accumulation
+      // residual, sums exact: H_KK levelled along k and the weights B have no entries far below their row / column maxima,
+      // so the int8 digits carry both operands whole (unlike a residual that involves P)
+      HIPCHK(c, big_gemm(s, b.i8, kr, m, kr, b.HKK, kr, b.B, m, b.GK, m, b.T4, m, -1.0, 1.0, 0.0, 0, 0, 0, -1));
       // the correction is small, a few digits of it are enough: float32 accumulation, or the three leading products of
       // the bf16 pieces
       if (split) {
