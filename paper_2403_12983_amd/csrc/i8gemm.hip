@@ -23,11 +23,11 @@
 // Layout of a packed operand: packet (16 consecutive k of one row, one digit) at
 //     ((panel * nstages + stage) * I8_S + t) * 256 + kh * 128 + r,   panel = row / 128, stage = k / 32, kh = (k % 32) / 16, r = row % 128,
 // so a (stage, panel) block of I8_S * 4 KB is the A- or B-side input of one v_mfma_i32_32x32x32_i8 step of a 128-row tile.
-// The kernel: one workgroup (4 waves, one per SIMD, 512 registers each) per 128 x 128 tile, wave tile 64 x 64 = 2 x 2
-// matrix-core tiles x I8_S accumulator sets (320 registers); operand blocks go from global memory straight into LDS
-// (global_load_lds_dwordx4), three stage buffers, loads three stages ahead; one barrier per stage that waits for LDS
-// traffic only, placed before the last twelve products of the stage so that the next stage's first operands are on their
-// way while those run.
+// The kernel: one workgroup of 8 waves (two per SIMD) per 128 x 128 tile, wave tile 64 x 32 = 2 matrix-core tiles x I8_S
+// accumulator sets (160 registers); operand blocks go from global memory straight into LDS (global_load_lds_dwordx4), three
+// stage buffers, loads three stages ahead; one barrier per stage that waits for LDS traffic only, placed before the last
+// two products of the stage so that the next stage's row-side operands are on their way while those run.  (With 4 waves of
+// 64 x 64, one per SIMD, the 14336^3 product took 51 ms instead of 41 ms: nothing to run while a wave waits.)
 #include "internal.h"
 
 namespace osscar {
@@ -186,7 +186,7 @@ struct I8Args {
 
 __device__ __forceinline__ void lds_only_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-__global__ __launch_bounds__(256, 1) __attribute__((amdgpu_waves_per_eu(1, 1))) void i8_gemm_kernel(I8Args g) {
+__global__ __launch_bounds__(512, 1) void i8_gemm_kernel(I8Args g) {
   extern __shared__ uint4 lds[];                 // [3 stage buffers][A block | B block]
   // 8 x 8 super-blocks of tiles, dealt to the XCDs in turn (workgroup index modulo 8): the tiles an XCD works on together
   // share row and column panels in its L2.  lower_only: the super-blocks on or below the diagonal.
@@ -212,75 +212,67 @@ __global__ __launch_bounds__(256, 1) __attribute__((amdgpu_waves_per_eu(1, 1))) 
     }
   }
   const int nstages = g.nstages;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
-  v16i acc[S][2][2];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 2, wn = wave & 3;      // wave tile: 64 rows x 32 columns
+  v16i acc[S][2];
 #pragma unroll
   for (int q = 0; q < S; q++)
 #pragma unroll
     for (int a = 0; a < 2; a++)
 #pragma unroll
-      for (int b = 0; b < 2; b++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) acc[q][a][b][r] = 0;
-  const uint4* ga = g.Ap + (int64_t)tm * nstages * BLK + wave * 64 + lane;
-  const uint4* gb = g.Bp + (int64_t)tn * nstages * BLK + wave * 64 + lane;
-  // wave w, instruction i moves packets [(4 i + w) 64, +64) of a block: lane l's 16 bytes land at the LDS base + 16 l
-#define OSSCAR_I8_ISSUE(st_, buf_)                                                                                                 \
-  {                                                                                                                                \
-    _Pragma("unroll") for (int i = 0; i < S; i++) {                                                                                \
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ga + (int64_t)(st_) * BLK + i * 256),       \
-                                       (__attribute__((address_space(3))) void*)(lds + (buf_) * 2 * BLK + i * 256 + wave * 64), 16, 0, 0); \
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gb + (int64_t)(st_) * BLK + i * 256),       \
-                                       (__attribute__((address_space(3))) void*)(lds + (buf_) * 2 * BLK + BLK + i * 256 + wave * 64), 16, 0, 0); \
-    }                                                                                                                              \
+      for (int r = 0; r < 16; r++) acc[q][a][r] = 0;
+  const uint4* ga = g.Ap + (int64_t)tm * nstages * BLK;
+  const uint4* gb = g.Bp + (int64_t)tn * nstages * BLK;
+  // A stage is the A block followed by the B block, 2 BLK = 2560 packets; instruction i of a wave moves packets
+  // [512 i + 64 wave, + 64) (the boundary 1280 is a multiple of 64: a wave's 64 lie in one block); lane l's 16 bytes
+  // land at the LDS base + 16 l.
+  constexpr int NI = (2 * BLK) / 512;
+  static_assert((2 * BLK) % 512 == 0 && BLK % 64 == 0, "every wave issues the same number of loads per stage");
+#define OSSCAR_I8_ISSUE(st_, buf_)                                                                                               \
+  {                                                                                                                              \
+    _Pragma("unroll") for (int i = 0; i < NI; i++) {                                                                             \
+      const int p0 = i * 512 + wave * 64;                                                                                        \
+      const uint4* src = (p0 < BLK) ? ga + (int64_t)(st_) * BLK + p0 + lane : gb + (int64_t)(st_) * BLK + (p0 - BLK) + lane;     \
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,                                       \
+                                       (__attribute__((address_space(3))) void*)(lds + (buf_) * 2 * BLK + p0), 16, 0, 0);        \
+    }                                                                                                                            \
   }
   OSSCAR_I8_ISSUE(0, 0);
   if (nstages > 1) OSSCAR_I8_ISSUE(1, 1);
   if (nstages > 2) OSSCAR_I8_ISSUE(2, 2);
-  const int oa = (lane >> 5) * 128 + wm * 64 + (lane & 31), ob = (lane >> 5) * 128 + wn * 64 + (lane & 31);
+  const int oa = (lane >> 5) * 128 + wm * 64 + (lane & 31), ob = (lane >> 5) * 128 + wn * 32 + (lane & 31);
   // stage 0 has landed (each wave waits for its own loads of that stage, then the barrier)
-  if (nstages > 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * S) : "memory");
-  else if (nstages == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * S) : "memory");
+  if (nstages > 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NI) : "memory");
+  else if (nstages == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NI) : "memory");
   else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   lds_only_barrier();
-  v4i fa[2][S], fb0[2];
+  v4i fa[2][S];
 #pragma unroll
   for (int t = 0; t < S; t++)
 #pragma unroll
     for (int a = 0; a < 2; a++) { uint4 q = lds[t * 256 + oa + a * 32]; fa[a][t] = *reinterpret_cast<v4i*>(&q); }
-#pragma unroll
-  for (int b = 0; b < 2; b++) { uint4 q = lds[BLK + ob + b * 32]; fb0[b] = *reinterpret_cast<v4i*>(&q); }
   int buf = 0;
   for (int st = 0; st < nstages; st++) {
     const uint4* pb = lds + buf * 2 * BLK + BLK;
-    // column-side digits 0 .. S-3 against every row-side digit they meet: the bulk of the stage
+    // column-side digits 0 .. S-2 against every row-side digit they meet: 28 of the stage's 30 products
 #pragma unroll
-    for (int u = 0; u < S - 2; u++) {
-      v4i fb[2];
-      if (u == 0) { fb[0] = fb0[0]; fb[1] = fb0[1]; }
-      else {
-#pragma unroll
-        for (int b = 0; b < 2; b++) { uint4 q = pb[u * 256 + ob + b * 32]; fb[b] = *reinterpret_cast<v4i*>(&q); }
-      }
+    for (int u = 0; u < S - 1; u++) {
+      v4i fb;
+      { uint4 q = pb[u * 256 + ob]; fb = *reinterpret_cast<v4i*>(&q); }
 #pragma unroll
       for (int t = 0; t + u < S; t++)
 #pragma unroll
         for (int a = 0; a < 2; a++)
-#pragma unroll
-          for (int b = 0; b < 2; b++)
-            acc[t + u][a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[a][t], fb[b], acc[t + u][a][b], 0, 0, 0);
+          acc[t + u][a] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[a][t], fb, acc[t + u][a], 0, 0, 0);
     }
-    // The last two column-side digits of this stage go to registers; then every wave has taken all it needs from this
-    // stage's buffer, which the barrier establishes, and the buffer is refilled with the stage three ahead.
-    v4i fl[2][2];
-#pragma unroll
-    for (int u = S - 2; u < S; u++)
-#pragma unroll
-      for (int b = 0; b < 2; b++) { uint4 q = pb[u * 256 + ob + b * 32]; fl[u - (S - 2)][b] = *reinterpret_cast<v4i*>(&q); }
-    const bool next = st + 1 < nstages;
-    v4i na[2][S];
-    if (next) {
-      if (st + 2 < nstages) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * S) : "memory");      // stage st + 1 has landed, st + 2 may be in flight
+    // The last column-side digit goes to a register; then every wave has taken all it needs from this stage's buffer,
+    // which the barrier establishes, and the buffer is refilled with the stage three ahead.  The next stage's row-side
+    // operands are requested before the last two products of this one.
+    v4i fl;
+    { uint4 q = pb[(S - 1) * 256 + ob]; fl = *reinterpret_cast<v4i*>(&q); }
+    v4i a0[2];
+    a0[0] = fa[0][0]; a0[1] = fa[1][0];
+    if (st + 1 < nstages) {
+      if (st + 2 < nstages) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NI) : "memory");      // stage st + 1 has landed, st + 2 may be in flight
       else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       lds_only_barrier();
       if (st + 3 < nstages) { const int nb = buf; OSSCAR_I8_ISSUE(st + 3, nb); }
@@ -288,49 +280,33 @@ __global__ __launch_bounds__(256, 1) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 #pragma unroll
       for (int t = 0; t < S; t++)
 #pragma unroll
-        for (int a = 0; a < 2; a++) { uint4 q = qa[t * 256 + oa + a * 32]; na[a][t] = *reinterpret_cast<v4i*>(&q); }
-#pragma unroll
-      for (int b = 0; b < 2; b++) { uint4 q = qa[BLK + ob + b * 32]; fb0[b] = *reinterpret_cast<v4i*>(&q); }
+        for (int a = 0; a < 2; a++) { uint4 q = qa[t * 256 + oa + a * 32]; fa[a][t] = *reinterpret_cast<v4i*>(&q); }
     }
 #pragma unroll
-    for (int u = S - 2; u < S; u++)
-#pragma unroll
-      for (int t = 0; t + u < S; t++)
-#pragma unroll
-        for (int a = 0; a < 2; a++)
-#pragma unroll
-          for (int b = 0; b < 2; b++)
-            acc[t + u][a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[a][t], fl[u - (S - 2)][b], acc[t + u][a][b], 0, 0, 0);
-    if (next) {
-#pragma unroll
-      for (int t = 0; t < S; t++) { fa[0][t] = na[0][t]; fa[1][t] = na[1][t]; }
-    }
+    for (int a = 0; a < 2; a++) acc[S - 1][a] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[a], fl, acc[S - 1][a], 0, 0, 0);
     buf = (buf + 1) % 3;
   }
 #undef OSSCAR_I8_ISSUE
   // C layout of a 32 x 32 tile: register r = rr*4 + r3 holds row rr*8 + (lane/32)*4 + r3, column lane%32
+  const int col = tn * 128 + wn * 32 + (lane & 31);
+  const int eb = expo_of(g.mxb[col < g.N ? col : 0]);
 #pragma unroll
   for (int a = 0; a < 2; a++)
 #pragma unroll
-    for (int b = 0; b < 2; b++) {
-      const int col = tn * 128 + wn * 64 + b * 32 + (lane & 31);
-      const int eb = expo_of(g.mxb[col < g.N ? col : 0]);
+    for (int r = 0; r < 16; r++) {
+      const int row = tm * 128 + wm * 64 + a * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+      if (row < g.M && col < g.N) {
+        double v = 0.0;
 #pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const int row = tm * 128 + wm * 64 + a * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        if (row < g.M && col < g.N) {
-          double v = 0.0;
-#pragma unroll
-          for (int q = S - 1; q >= 0; q--) v = v * (1.0 / 128.0) + (double)acc[q][a][b][r];
-          v = ldexp(v, expo_of(g.mxa[row]) + eb - 12);
-          // the diagonal terms that were left out of the digits: k = row of A (A square), k = col of B (B square)
-          if (g.diag_a) v += (double)g.A[(int64_t)row * g.lda + row] * (double)g.B[(int64_t)row * g.ldb + col];
-          if (g.diag_b && !(g.diag_a && row == col)) v += (double)g.A[(int64_t)row * g.lda + col] * (double)g.B[(int64_t)col * g.ldb + col];
-          v *= g.alpha;
-          if (g.beta != 0.0) v += g.beta * (double)g.Cin[(int64_t)row * g.ldcin + col];
-          if (row == col) v += g.diag_add;
-          g.C[(int64_t)row * g.ldc + col] = (float)v;
-        }
+        for (int q = S - 1; q >= 0; q--) v = v * (1.0 / 128.0) + (double)acc[q][a][r];
+        v = ldexp(v, expo_of(g.mxa[row]) + eb - 12);
+        // the diagonal terms that were left out of the digits: k = row of A (A square), k = col of B (B square)
+        if (g.diag_a) v += (double)g.A[(int64_t)row * g.lda + row] * (double)g.B[(int64_t)row * g.ldb + col];
+        if (g.diag_b && !(g.diag_a && row == col)) v += (double)g.A[(int64_t)row * g.lda + col] * (double)g.B[(int64_t)col * g.ldb + col];
+        v *= g.alpha;
+        if (g.beta != 0.0) v += g.beta * (double)g.Cin[(int64_t)row * g.ldcin + col];
+        if (row == col) v += g.diag_add;
+        g.C[(int64_t)row * g.ldc + col] = (float)v;
       }
     }
 }
@@ -378,7 +354,7 @@ hipError_t launch_i8_gemm(const GemmArgs& g, void* packA, size_t capA, void* pac
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(i8_gemm_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(i8_gemm_kernel, dim3((unsigned)((nsb + 7) / 8 * 8 * 64)), dim3(256), shmem, s, a);
+  hipLaunchKernelGGL(i8_gemm_kernel, dim3((unsigned)((nsb + 7) / 8 * 8 * 64)), dim3(512), shmem, s, a);
   gemm_log_close(log_slot, s);
   return hipGetLastError();
 }

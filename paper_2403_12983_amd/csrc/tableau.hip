@@ -505,12 +505,12 @@ __global__ __launch_bounds__(256) void inv_fix64_kernel(double* __restrict__ N, 
 }
 
 // N[i][j] -= sum_k A[i][k] B[j][k] on the tiles of the lower block triangle; A, B: n x w float64 (w <= 128), N: n x n float64.
-// One workgroup per 128 x 128 tile, 4 waves x (4 x 4) v_mfma_f64_16x16x4_f64, the contraction in steps of 16 through LDS
+// One workgroup per 128 x 128 tile, 8 waves x (4 x 2) v_mfma_f64_16x16x4_f64, the contraction in steps of 16 through LDS
 // (rows of 144 doubles: the four k of a quarter-wave's operand read fall in different bank groups); the tile of N is read,
 // changed and written from registers, 16 values per thread at a time.  Tiles in 8 x 8 super-blocks per XCD.
 typedef double swd4 __attribute__((ext_vector_type(4)));
 constexpr int SW_LD = 144;
-__global__ __launch_bounds__(256, 2) void sweep_update64_kernel(const double* __restrict__ A, const double* __restrict__ B, int n, int w,
+__global__ __launch_bounds__(512, 2) void sweep_update64_kernel(const double* __restrict__ A, const double* __restrict__ B, int n, int w,
                                                                  double* __restrict__ N) {
   extern __shared__ double sw_lds[];           // 72 KB: above the static limit, so taken dynamically
   double (*As)[16][SW_LD] = reinterpret_cast<double (*)[16][SW_LD]>(sw_lds);
@@ -529,41 +529,35 @@ __global__ __launch_bounds__(256, 2) void sweep_update64_kernel(const double* __
     if (tm >= tiles || tn > tm) return;
   }
   const int m0 = tm * 128, n0 = tn * 128;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
-  const int lrow = tid >> 1, lk = (tid & 1) * 8;        // staging: thread = (row of the tile, half of the 16 k)
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 2, wn = wave & 3;   // wave tile: 64 rows x 32 columns
+  const int lrow = tid >> 2, lk = (tid & 3) * 4;        // staging: thread = (row of the tile, quarter of the 16 k)
   const double* ap = (m0 + lrow < n) ? A + (int64_t)(m0 + lrow) * w : nullptr;
   const double* bp = (n0 + lrow < n) ? B + (int64_t)(n0 + lrow) * w : nullptr;
-  swd4 acc[4][4];
+  swd4 acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; i++)
 #pragma unroll
-    for (int j = 0; j < 4; j++) acc[i][j] = swd4{0.0, 0.0, 0.0, 0.0};
-  double ra[8], rb[8];
+    for (int j = 0; j < 2; j++) acc[i][j] = swd4{0.0, 0.0, 0.0, 0.0};
+  double ra[4], rb[4];
   const int ktiles = (w + 15) / 16;
-  const bool vec = (w & 7) == 0;       // then a thread's eight k are inside or outside as a whole, and 64-byte aligned
+  const bool vec = (w & 3) == 0;       // then a thread's four k are inside or outside as a whole, and 32-byte aligned
   auto gload = [&](int kt) {
     const int k0 = kt * 16 + lk;
     if (vec) {
       if (ap && k0 < w) {
         const double2* p = reinterpret_cast<const double2*>(ap + k0);
-#pragma unroll
-        for (int e = 0; e < 4; e++) { const double2 q = p[e]; ra[2 * e] = q.x; ra[2 * e + 1] = q.y; }
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; e++) ra[e] = 0.0;
-      }
+        const double2 q0 = p[0], q1 = p[1];
+        ra[0] = q0.x; ra[1] = q0.y; ra[2] = q1.x; ra[3] = q1.y;
+      } else { ra[0] = ra[1] = ra[2] = ra[3] = 0.0; }
       if (bp && k0 < w) {
         const double2* p = reinterpret_cast<const double2*>(bp + k0);
-#pragma unroll
-        for (int e = 0; e < 4; e++) { const double2 q = p[e]; rb[2 * e] = q.x; rb[2 * e + 1] = q.y; }
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; e++) rb[e] = 0.0;
-      }
+        const double2 q0 = p[0], q1 = p[1];
+        rb[0] = q0.x; rb[1] = q0.y; rb[2] = q1.x; rb[3] = q1.y;
+      } else { rb[0] = rb[1] = rb[2] = rb[3] = 0.0; }
       return;
     }
 #pragma unroll
-    for (int e = 0; e < 8; e++) {
+    for (int e = 0; e < 4; e++) {
       const int k = k0 + e;
       ra[e] = (ap && k < w) ? ap[k] : 0.0;
       rb[e] = (bp && k < w) ? bp[k] : 0.0;
@@ -571,14 +565,14 @@ __global__ __launch_bounds__(256, 2) void sweep_update64_kernel(const double* __
   };
   auto sstore = [&](int buf) {
 #pragma unroll
-    for (int e = 0; e < 8; e++) { As[buf][lk + e][lrow] = ra[e]; Bs[buf][lk + e][lrow] = rb[e]; }
+    for (int e = 0; e < 4; e++) { As[buf][lk + e][lrow] = ra[e]; Bs[buf][lk + e][lrow] = rb[e]; }
   };
   // the first 16 rows of this wave's part of the tile of N are requested now and arrive while the products run
-  const int rbase = m0 + wm * 64 + (lane >> 4), cbase = n0 + wn * 64 + (lane & 15);
-  double cv[4][4];
-  auto cload = [&](int i, double (&dst)[4][4]) {
+  const int rbase = m0 + wm * 64 + (lane >> 4), cbase = n0 + wn * 32 + (lane & 15);
+  double cv[2][4];
+  auto cload = [&](int i, double (&dst)[2][4]) {
 #pragma unroll
-    for (int j = 0; j < 4; j++)
+    for (int j = 0; j < 2; j++)
 #pragma unroll
       for (int r = 0; r < 4; r++) {
         const int row = rbase + i * 16 + 4 * r, col = cbase + j * 16;
@@ -594,15 +588,15 @@ __global__ __launch_bounds__(256, 2) void sweep_update64_kernel(const double* __
 #pragma unroll
     for (int kk = 0; kk < 4; kk++) {
       const int k = kk * 4 + (lane >> 4);
-      double a[4], b[4];
+      double a[4], b[2];
 #pragma unroll
       for (int i = 0; i < 4; i++) a[i] = As[buf][k][wm * 64 + i * 16 + (lane & 15)];
 #pragma unroll
-      for (int j = 0; j < 4; j++) b[j] = Bs[buf][k][wn * 64 + j * 16 + (lane & 15)];
+      for (int j = 0; j < 2; j++) b[j] = Bs[buf][k][wn * 32 + j * 16 + (lane & 15)];
 #pragma unroll
       for (int i = 0; i < 4; i++)
 #pragma unroll
-        for (int j = 0; j < 4; j++) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < 2; j++) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
     }
     if (kt + 1 < ktiles) sstore(buf ^ 1);
     __syncthreads();
@@ -610,10 +604,10 @@ __global__ __launch_bounds__(256, 2) void sweep_update64_kernel(const double* __
   // lane holds D[4 r + lane/16][lane%16] of each 16 x 16 tile; the next 16 rows are requested before these are stored
 #pragma unroll
   for (int i = 0; i < 4; i++) {
-    double nx[4][4];
+    double nx[2][4];
     if (i < 3) cload(i + 1, nx);
 #pragma unroll
-    for (int j = 0; j < 4; j++)
+    for (int j = 0; j < 2; j++)
 #pragma unroll
       for (int r = 0; r < 4; r++) {
         const int row = rbase + i * 16 + 4 * r, col = cbase + j * 16;
@@ -621,7 +615,7 @@ __global__ __launch_bounds__(256, 2) void sweep_update64_kernel(const double* __
       }
     if (i < 3) {
 #pragma unroll
-      for (int j = 0; j < 4; j++)
+      for (int j = 0; j < 2; j++)
 #pragma unroll
         for (int r = 0; r < 4; r++) cv[j][r] = nx[j][r];
     }
@@ -652,7 +646,7 @@ hipError_t spd_inverse_f64(const float* H, int64_t ldh, int n, float* P, double*
     hipLaunchKernelGGL(extract_panel64_kernel, dim3(rb), dim3(256), 0, s, A64, (int64_t)n, n, t0, w, panel);
     hipLaunchKernelGGL(inv_block64_kernel, dim3(1), dim3(256), 0, s, panel, w, t0, small, notpd_flag);
     hipLaunchKernelGGL(panel_times_small64_kernel, dim3((n + 7) / 8), dim3(256), 0, s, panel, small, n, w, t0, panelDz, panelCz);
-    hipLaunchKernelGGL(sweep_update64_kernel, dim3(upd_grid), dim3(256), shmem, s, panelDz, panelCz, n, w, A64);
+    hipLaunchKernelGGL(sweep_update64_kernel, dim3(upd_grid), dim3(512), shmem, s, panelDz, panelCz, n, w, A64);
     hipLaunchKernelGGL(inv_fix64_kernel, dim3(rb), dim3(256), 0, s, A64, (int64_t)n, n, t0, w, panelDz, small);
   }
   hipLaunchKernelGGL(narrow_negate_mirror_kernel, dim3(blocks), dim3(256), 0, s, A64, n, P);
