@@ -213,7 +213,7 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
   if (ds.target_output) gram_phase += align_up((size_t)d1 * m * 8) + align_up(target_stage_bytes(m));
   auto init_bytes = [&](size_t a, size_t b) {   // kept rows a, candidate rows b
     return 4 * align_up(a * a * 4) + 3 * align_up(a * b * 4) + align_up(b * b * 4) + 4 * align_up(a * m * 4) + align_up(b * m * 4) +
-           align_up(6 * a * INV_NB * 4) + split_bytes(a, b, m) + i8_bytes(a, b, m) + 4096;
+           align_up(10 * a * INV_NB * 4) + split_bytes(a, b, m) + i8_bytes(a, b, m) + 4096;
   };
   size_t init_phase = init_bytes(kr, cr);
   if (ds.from_dense) {   // the nested schedule visits every kept-row count from d1 down to kr
@@ -403,7 +403,8 @@ osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b, const float* 
   if (!g_refined_inverse) {
     // The sweep on a float64 copy of H_KK (in the memory of T1 and T2), rounded to float32 once: exact to that rounding.
     HIPCHK(c, hipEventRecord(c->ev_s[2][0], s));
-    HIPCHK(c, spd_inverse_f64(b.HKK, kr, kr, b.P, reinterpret_cast<double*>(b.T1), reinterpret_cast<double*>(b.panels), c->small, c->notpd, s));
+    HIPCHK(c, spd_inverse_f64(b.HKK, kr, kr, b.P, reinterpret_cast<double*>(b.T1), reinterpret_cast<double*>(b.panels), c->small, c->notpd, s,
+                              c->ev_ok ? &c->side : nullptr));
     HIPCHK(c, hipEventRecord(c->ev_s[2][1], s));
     HIPCHK(c, launch_absmax(b.P, (int64_t)kr * kr, c->partial, s));
     hipLaunchKernelGGL(vif_max_kernel, dim3(1), dim3(1024), 0, s, b.P, b.HKK, kr, c->scal + 20);
@@ -522,7 +523,7 @@ InvBufs carve_inv(osscar_ctx* c, Carve& cv) {
   b.HKK = cv.take<float>(kr * kr); b.P = cv.take<float>(kr * kr);
   b.T1 = cv.take<float>(2 * kr * kr); b.T2 = b.T1 + kr * kr;      // together: the kr x kr float64 work matrix of the sweep inverse
   b.GK = cv.take<float>(kr * m); b.B = cv.take<float>(kr * m); b.T3 = cv.take<float>(kr * m); b.T4 = cv.take<float>(kr * m);
-  b.panels = cv.take<float>(6 * kr * INV_NB);                      // three panels of float64
+  b.panels = cv.take<float>(10 * kr * INV_NB);                     // five panels of float64
   return b;
 }
 

@@ -147,9 +147,12 @@ constexpr int INV_NB = 128;   // pivot block width of the sweep inverse
 // In-place inverse of the symmetric positive definite n x n matrix A (full storage on entry and exit)
 // by block sweeps of width INV_NB; panel/work buffers are caller-provided: panel (n*INV_NB), panelD (2*n*INV_NB),
 // small (INV_NB*INV_NB doubles).  notpd_flag (device int) is set if a pivot block is not definite.
-// The same with the working matrix in float64 (A64: n x n, panels: 3 n INV_NB float64): P = H^-1 rounded to float32 once.
+// The same with the working matrix in float64 (A64: n x n, panels: 5 n INV_NB float64): P = H^-1 rounded to float32 once.
+// side (optional): a second stream with two events, on which the bulk of each panel's update runs beside the next panel's
+// small kernels; every launch is joined back into s before the call returns.
+struct SideStream;
 hipError_t spd_inverse_f64(const float* H, int64_t ldh, int n, float* P, double* A64, double* panels, double* small,
-                           int32_t* notpd_flag, hipStream_t s);
+                           int32_t* notpd_flag, hipStream_t s, const SideStream* side = nullptr);
 hipError_t spd_inverse_inplace(float* A, int n, float* panel, float* panelD, double* small, int32_t* notpd_flag,
                                hipStream_t s);
 

@@ -510,13 +510,22 @@ __global__ __launch_bounds__(256) void inv_fix64_kernel(double* __restrict__ N, 
 // changed and written from registers, 16 values per thread at a time.  Tiles in 8 x 8 super-blocks per XCD.
 typedef double swd4 __attribute__((ext_vector_type(4)));
 constexpr int SW_LD = 144;
+// part = 0: every tile of the triangle.  The pivot rows of A and B are zero, so the tiles of tile row / column pk (the
+// pivot panel's) receive nothing and are always left alone (the pivot-row fix rewrites them, possibly meanwhile).
+// part = 1: only tile row and tile column pk + 1, what the next panel is made of (one workgroup per tile, blockIdx = the
+// other tile index); part = 2: everything but those.
 __global__ __launch_bounds__(512, 2) void sweep_update64_kernel(const double* __restrict__ A, const double* __restrict__ B, int n, int w,
-                                                                 double* __restrict__ N) {
+                                                                 double* __restrict__ N, int part, int pk) {
   extern __shared__ double sw_lds[];           // 72 KB: above the static limit, so taken dynamically
   double (*As)[16][SW_LD] = reinterpret_cast<double (*)[16][SW_LD]>(sw_lds);
   double (*Bs)[16][SW_LD] = reinterpret_cast<double (*)[16][SW_LD]>(sw_lds + 2 * 16 * SW_LD);
   int tm, tn;
-  {
+  if (part == 1) {
+    const int tiles = (n + 127) / 128, b = blockIdx.x, nx = pk + 1;
+    if (b >= tiles || nx >= tiles || b == pk) return;
+    tm = (b <= nx) ? nx : b;
+    tn = (b <= nx) ? b : nx;
+  } else {
     const int tiles = (n + 127) / 128, nr = (tiles + 7) / 8;
     const int b = blockIdx.x, xcd = b & 7, slot = b >> 3;
     const int sb = (slot / 64) * 8 + xcd, within = slot % 64;
@@ -527,6 +536,8 @@ __global__ __launch_bounds__(512, 2) void sweep_update64_kernel(const double* __
     tm = r * 8 + within / 8;
     tn = (sb - r * (r + 1) / 2) * 8 + within % 8;
     if (tm >= tiles || tn > tm) return;
+    if (tm == pk || tn == pk) return;
+    if (part == 2 && (tm == pk + 1 || tn == pk + 1)) return;
   }
   const int m0 = tm * 128, n0 = tn * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 2, wn = wave & 3;   // wave tile: 64 rows x 32 columns
@@ -623,16 +634,18 @@ __global__ __launch_bounds__(512, 2) void sweep_update64_kernel(const double* __
 }
 
 // P (n x n float32, full) = H^-1 for the SPD H (n x n float32, leading dimension ldh; only its lower triangle is read).
-// A64: n x n float64 work matrix; panels: 3 n INV_NB float64; small: INV_NB^2 float64; notpd_flag as for spd_inverse_inplace.
+// A64: n x n float64 work matrix; panels: 5 n INV_NB float64; small: INV_NB^2 float64; notpd_flag as for spd_inverse_inplace.
+// With a side stream the panel work of step k + 1 (extract, 128 x 128 inverse, panel x block: 0.2 ms during which one
+// workgroup, then a few, have the chip to themselves) runs beside the bulk update of step k: the tiles the next panel is made
+// of (tile row and column k + 1) are updated first by a launch of their own, the pivot rows of step k are fixed, and the
+// rest of the update goes to the side stream.  Each tile sees the same operations in the same order either way.
 hipError_t spd_inverse_f64(const float* H, int64_t ldh, int n, float* P, double* A64, double* panels, double* small,
-                           int32_t* notpd_flag, hipStream_t s) {
+                           int32_t* notpd_flag, hipStream_t s, const SideStream* side) {
   if (n <= 0) return hipSuccess;
   const int64_t tot = (int64_t)n * n;
   int blocks = (int)((tot + 1023) / 1024); if (blocks > 131072) blocks = 131072;
   hipLaunchKernelGGL(widen_lower_kernel, dim3(blocks), dim3(256), 0, s, H, ldh, n, A64);
   double* panel = panels;
-  double* panelDz = panels + (int64_t)n * INV_NB;
-  double* panelCz = panels + 2 * (int64_t)n * INV_NB;
   const size_t shmem = (size_t)2 * 2 * 16 * SW_LD * sizeof(double);
   {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sweep_update64_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
@@ -641,14 +654,36 @@ hipError_t spd_inverse_f64(const float* H, int64_t ldh, int n, float* P, double*
   const int tiles = (n + 127) / 128, nr = (tiles + 7) / 8;
   const unsigned upd_grid = (unsigned)((nr * (nr + 1) / 2 + 7) / 8 * 8 * 64);
   const int rb = (n + PANEL_ROWS64 - 1) / PANEL_ROWS64;
-  for (int t0 = 0; t0 < n; t0 += INV_NB) {
+  const bool two = side && side->stream && tiles > 2;
+  hipError_t err;
+  bool pending = false;              // a bulk update is running on the side stream
+  for (int t0 = 0, k = 0; t0 < n; t0 += INV_NB, k++) {
     const int w = (n - t0 < INV_NB) ? n - t0 : INV_NB;
+    // operand panels alternate: the bulk update of step k - 1 may still be reading the other pair
+    double* panelDz = panels + (int64_t)(1 + 2 * (k & 1)) * n * INV_NB;
+    double* panelCz = panelDz + (int64_t)n * INV_NB;
     hipLaunchKernelGGL(extract_panel64_kernel, dim3(rb), dim3(256), 0, s, A64, (int64_t)n, n, t0, w, panel);
     hipLaunchKernelGGL(inv_block64_kernel, dim3(1), dim3(256), 0, s, panel, w, t0, small, notpd_flag);
     hipLaunchKernelGGL(panel_times_small64_kernel, dim3((n + 7) / 8), dim3(256), 0, s, panel, small, n, w, t0, panelDz, panelCz);
-    hipLaunchKernelGGL(sweep_update64_kernel, dim3(upd_grid), dim3(512), shmem, s, panelDz, panelCz, n, w, A64);
+    if (pending) {                   // every tile outside this panel's own has to have step k - 1 behind it
+      if ((err = hipStreamWaitEvent(s, side->join, 0)) != hipSuccess) return err;
+      pending = false;
+    }
+    if (!two) {
+      hipLaunchKernelGGL(sweep_update64_kernel, dim3(upd_grid), dim3(512), shmem, s, panelDz, panelCz, n, w, A64, 0, k);
+      hipLaunchKernelGGL(inv_fix64_kernel, dim3(rb), dim3(256), 0, s, A64, (int64_t)n, n, t0, w, panelDz, small);
+      continue;
+    }
+    if (k + 1 < tiles) hipLaunchKernelGGL(sweep_update64_kernel, dim3(tiles), dim3(512), shmem, s, panelDz, panelCz, n, w, A64, 1, k);
+    if ((err = hipEventRecord(side->fork, s)) != hipSuccess) return err;
+    if ((err = hipStreamWaitEvent(side->stream, side->fork, 0)) != hipSuccess) return err;
+    hipLaunchKernelGGL(sweep_update64_kernel, dim3(upd_grid), dim3(512), shmem, side->stream, panelDz, panelCz, n, w, A64, 2, k);
+    if ((err = hipEventRecord(side->join, side->stream)) != hipSuccess) return err;
+    pending = true;
+    // tile row and column k only: no launch of this step's update touches them
     hipLaunchKernelGGL(inv_fix64_kernel, dim3(rb), dim3(256), 0, s, A64, (int64_t)n, n, t0, w, panelDz, small);
   }
+  if (pending && (err = hipStreamWaitEvent(s, side->join, 0)) != hipSuccess) return err;
   hipLaunchKernelGGL(narrow_negate_mirror_kernel, dim3(blocks), dim3(256), 0, s, A64, n, P);
   return hipGetLastError();
 }
