@@ -172,7 +172,9 @@ struct TabPtrs {
   int32_t* trace_out; int32_t* trace_in; float* trace_gap; double* trace_obj;
 };
 
-hipError_t launch_refresh_scores(const TabDims& d, const TabPtrs& t, hipStream_t s);   // gram, dblk, score from N, Z
+hipError_t launch_refresh_scores(const TabDims& d, const TabPtrs& t, hipStream_t s);
+hipError_t launch_refresh_blocks(const TabDims& d, const TabPtrs& t, hipStream_t s);        // first half: Gram and diagonal blocks
+hipError_t launch_refresh_from_blocks(const TabDims& d, const TabPtrs& t, hipStream_t s);   // second half: the scores from them   // gram, dblk, score from N, Z
 // ev (optional): three events recorded before the bulk update of N, after it, and after the update of Z.
 // single (optional, device): removal of the one group *single instead of a swap (Case 1 alone; no selection kernel).
 // exact_in: the entering group is the argmax of the exact gain of the pair with the selected leaving group.
@@ -242,7 +244,7 @@ hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyP
 hipError_t launch_lazy_block_remove(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, int take, const int32_t* pick,
                                     hipStream_t s);
 
-struct SideStream { hipStream_t stream = nullptr; hipEvent_t fork = nullptr, join = nullptr; };
+struct SideStream { hipStream_t stream = nullptr; hipEvent_t fork = nullptr, join = nullptr, mid = nullptr; };
 // side == nullptr (or no stream in it): everything in order on s
 hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode = 0,
                              const SideStream* side = nullptr);

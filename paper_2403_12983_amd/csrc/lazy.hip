@@ -695,22 +695,26 @@ __global__ __launch_bounds__(256) void lazy_convert_kernel(LazyPtrs L, int m, co
   }
 }
 
-// pivot rows / columns of N0 and pivot rows of Z0
+// pivot rows / columns of N0 and pivot rows of Z0.  Every entry is written by exactly one thread (the pending pivots are
+// distinct), so the pivots are spread over blockIdx.y: FIX_SPB of them per thread.
+constexpr int FIX_SPB = 8;
 __global__ __launch_bounds__(256) void lazy_fix_kernel(LazyPtrs L, float* __restrict__ N0, int d1,
                                                         const SearchCtrl* __restrict__ ctrl) {
   const int l = blockIdx.x * 256 + threadIdx.x;
   if (l >= d1) return;
   const int tau = tau_all(ctrl);
+  const int s0 = blockIdx.y * FIX_SPB, s1 = min(tau, s0 + FIX_SPB);
+  if (s0 >= s1) return;
   const int pr = L.pos[l];
   if (pr < 0) {
     const float* El = L.E + (int64_t)l * LAZY_TM;
-    for (int s = 0; s < tau; s++) {
+    for (int s = s0; s < s1; s++) {
       const int t = L.Tidx[s];
       const float v = L.Jsg[s] * El[s];
       if (l < t) N0[(int64_t)t * d1 + l] = v; else N0[(int64_t)l * d1 + t] = v;
     }
   } else {
-    for (int s = 0; s < tau; s++) {
+    for (int s = s0; s < s1; s++) {
       const int t = L.Tidx[s];
       if (l >= t) N0[(int64_t)l * d1 + t] = (float)(-(double)L.Jsg[pr] * (double)L.Jsg[s] * L.Minv[pr * LAZY_TM + s]);
     }
@@ -721,7 +725,8 @@ __global__ __launch_bounds__(256) void lazy_fix_z_kernel(LazyPtrs L, float* __re
   const int col = blockIdx.x * 256 + threadIdx.x;
   if (col >= m) return;
   const int tau = tau_all(ctrl);
-  for (int s = 0; s < tau; s++) Z0[(int64_t)L.Tidx[s] * m + col] = (float)((double)L.Jsg[s] * L.ZT[(int64_t)s * m + col]);
+  const int s0 = blockIdx.y * FIX_SPB, s1 = min(tau, s0 + FIX_SPB);
+  for (int s = s0; s < s1; s++) Z0[(int64_t)L.Tidx[s] * m + col] = (float)((double)L.Jsg[s] * L.ZT[(int64_t)s * m + col]);
 }
 __global__ __launch_bounds__(256) void lazy_reset_kernel(LazyPtrs L, SearchCtrl* ctrl) {
   const int tau = tau_all(ctrl);
@@ -946,19 +951,30 @@ __global__ __launch_bounds__(256, 2) void la_product_kernel(const uint4* __restr
 }
 
 // mode 0: half of the slots for kept rows, half for the others; 1: all for kept rows (removal-only loops); 2: none
-static hipError_t launch_candidates(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode) {
+struct CandCounts { int n_k, n_c; };
+static CandCounts cand_counts(int mode) {
+  // Swap search: 64 + 64 rows.  They cover about 97 % of the next 64 swaps' pivots; the rest take a spare slot and a pass
+  // over Z0 each (0.155 ms on the 28672 x 7168 layer), which costs less than the second 128-row tile of the product
+  // (0.85 ms): measured 0.33 ms per flush in favour of the smaller set.  The removal-only loops take all LAZY_NC rows:
+  // their block pivots cannot fetch a missing product.
+  return CandCounts{mode == 2 ? 0 : (mode == 1 ? LAZY_NC : LAZY_NC / 4), mode == 0 ? LAZY_NC / 4 : 0};
+}
+// the pick: reads the scores and the kept flags only (two sorts in one workgroup each: latency, no bandwidth)
+static hipError_t launch_candidate_pick(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode) {
   const int nblk = (d.p + 1023) / 1024;               // <= 64 (d1 <= 65536)
   const int per_block = std::min(32, 1024 / nblk);
   hipError_t e = hipMemsetAsync(L.cslot, 0xFF, (size_t)d.d1 * 4, s);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(cand_local_kernel, dim3(nblk), dim3(1024), 0, s, L, d.p, t.kept, t.score, per_block);
-  // Swap search: 64 + 64 rows.  They cover about 97 % of the next 64 swaps' pivots; the rest take a spare slot and a pass
-  // over Z0 each (0.155 ms on the 28672 x 7168 layer), which costs less than the second 128-row tile of the product
-  // (0.85 ms): measured 0.33 ms per flush in favour of the smaller set.  The removal-only loops take all LAZY_NC rows:
-  // their block pivots cannot fetch a missing product.
-  const int n_k = mode == 2 ? 0 : (mode == 1 ? LAZY_NC : LAZY_NC / 4), n_c = mode == 0 ? LAZY_NC / 4 : 0;
-  hipLaunchKernelGGL(cand_merge_kernel, dim3(1), dim3(1024), 0, s, L, nblk, per_block, n_k, n_c);
-  if (mode == 2) return hipGetLastError();
+  const CandCounts cc = cand_counts(mode);
+  hipLaunchKernelGGL(cand_merge_kernel, dim3(1), dim3(1024), 0, s, L, nblk, per_block, cc.n_k, cc.n_c);
+  return hipGetLastError();
+}
+// the products of the picked rows with the (flushed) Z0
+static hipError_t launch_candidate_products(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode) {
+  const CandCounts cc = cand_counts(mode);
+  const int n_k = cc.n_k, n_c = cc.n_c;
+  if (mode == 2) return hipSuccess;
   if (d.m % 8 == 0 && (n_k + n_c) % 128 == 0) {
     const int nstg = (d.m + LA_STG - 1) / LA_STG, nsb = (n_k + n_c) / 128;
     hipLaunchKernelGGL(la_pack_kernel, dim3(nstg, nsb), dim3(256), 0, s, L, t.Z, d.m, nstg, reinterpret_cast<uint4*>(L.ZcP));
@@ -972,6 +988,10 @@ static hipError_t launch_candidates(const TabDims& d, const TabPtrs& t, const La
   g.M = n_k + n_c; g.N = d.d1; g.K = d.m; g.A = L.Zc; g.lda = d.m; g.B = t.Z; g.ldb = d.m; g.trans_b = 1;
   g.C = L.GbT; g.ldc = d.d1; g.alpha = 1.0; g.beta = 0.0; g.c_is_f64 = 1;
   return launch_gemm_f64acc(g, s);
+}
+static hipError_t launch_candidates(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode) {
+  const hipError_t e = launch_candidate_pick(d, t, L, s, mode);
+  return e != hipSuccess ? e : launch_candidate_products(d, t, L, s, mode);
 }
 
 static hipError_t launch_partials(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s) {
@@ -1135,11 +1155,21 @@ hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs&
   const int rb = (d.d1 + 255) / 256, mb = (d.m + 255) / 256;
   const bool two = side && side->stream;
   hipStream_t sn = two ? side->stream : s;          // stream of the N0 update
+  hipError_t err;
+  if (two) {
+    // The candidates of the next cycle, from the scores as the swaps left them (the refresh below changes them in the last
+    // digits only, and the choice of candidates decides what is computed ahead, not any result): two sorts of one
+    // workgroup each, on the second stream while this one prepares the operands.
+    if ((err = hipEventRecord(side->fork, s)) != hipSuccess) return err;
+    if ((err = hipStreamWaitEvent(sn, side->fork, 0)) != hipSuccess) return err;
+    if ((err = launch_candidate_pick(d, t, L, sn, mode)) != hipSuccess) return err;
+    if ((err = hipEventRecord(side->mid, sn)) != hipSuccess) return err;
+  }
   hipLaunchKernelGGL(lazy_convert_kernel, dim3(512), dim3(256), 0, s, L, d.m, t.ctrl);
   GemmArgs e{};                         // E = C0 M^-1
   e.M = d.d1; e.N = LAZY_TM; e.K = LAZY_TM; e.A = L.C0R; e.lda = LAZY_TM; e.B = L.Minv32; e.ldb = LAZY_TM;
   e.C = L.E; e.ldc = LAZY_TM; e.alpha = 1.0; e.beta = 0.0;
-  hipError_t err = launch_gemm_f64acc(e, s);
+  err = launch_gemm_f64acc(e, s);
   if (err != hipSuccess) return err;
   // the three thin operands in matrix-core order (C0's pieces serve both updates)
   const int dpad = (d.d1 + 127) / 128 * 128, mpad = (d.m + 127) / 128 * 128;
@@ -1154,21 +1184,25 @@ hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs&
   // N0 -= E C0^T on the lower block triangle (pivot rows and columns are rewritten below)
   hipLaunchKernelGGL(rk_update_kernel, dim3((unsigned)L.n_tiles_sym), dim3(256), 0, sn, Epk, dpad, Cpk, dpad, t.N, (int64_t)d.d1, d.d1, d.d1,
                      L.tiles_sym);
-  hipLaunchKernelGGL(lazy_fix_kernel, dim3(rb), dim3(256), 0, sn, L, t.N, d.d1, t.ctrl);
-  if (two && (err = hipEventRecord(side->join, sn)) != hipSuccess) return err;
+  hipLaunchKernelGGL(lazy_fix_kernel, dim3(rb, LAZY_TM / FIX_SPB), dim3(256), 0, sn, L, t.N, d.d1, t.ctrl);
   // Z0 -= C0 ZT
   hipLaunchKernelGGL(rk_update_kernel, dim3((unsigned)L.n_tiles_rect), dim3(256), 0, s, Cpk, dpad, Zpk, mpad, t.Z, (int64_t)d.m, d.d1, d.m,
                      L.tiles_rect);
-  hipLaunchKernelGGL(lazy_fix_z_kernel, dim3(mb), dim3(256), 0, s, L, t.Z, d.m, t.ctrl);
+  hipLaunchKernelGGL(lazy_fix_z_kernel, dim3(mb, LAZY_TM / FIX_SPB), dim3(256), 0, s, L, t.Z, d.m, t.ctrl);
   if (two) {
-    // Candidates from the scores as the swaps left them (the refresh below changes them in the last digits only, and the
-    // choice of candidates decides what is computed ahead, not any result), products with the new Z0; meanwhile N0.
-    err = launch_candidates(d, t, L, s, mode);
+    // The second stream goes on, once both matrices are final, with the first half of the score refresh (row norms of Z0,
+    // diagonal of N0); this one with the products of the picked rows with the new Z0.
+    if ((err = hipEventRecord(side->fork, s)) != hipSuccess) return err;
+    if ((err = hipStreamWaitEvent(sn, side->fork, 0)) != hipSuccess) return err;
+    if ((err = launch_refresh_blocks(d, t, sn)) != hipSuccess) return err;
+    if ((err = hipEventRecord(side->join, sn)) != hipSuccess) return err;
+    if ((err = hipStreamWaitEvent(s, side->mid, 0)) != hipSuccess) return err;
+    err = launch_candidate_products(d, t, L, s, mode);
     if (err != hipSuccess) return err;
     if ((err = hipStreamWaitEvent(s, side->join, 0)) != hipSuccess) return err;
   }
   hipLaunchKernelGGL(lazy_reset_kernel, dim3(1), dim3(256), 0, s, L, t.ctrl);
-  err = launch_refresh_scores(d, t, s);
+  err = two ? launch_refresh_from_blocks(d, t, s) : launch_refresh_scores(d, t, s);
   if (err != hipSuccess) return err;
   err = launch_partials(d, t, L, s);
   if (err != hipSuccess) return err;

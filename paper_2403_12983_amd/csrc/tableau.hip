@@ -824,7 +824,9 @@ static void launch_score(const TabDims& d, const int32_t* kept, const double* gr
                        skip_if_done);
 }
 
-hipError_t launch_refresh_scores(const TabDims& d, const TabPtrs& t, hipStream_t s) {
+// the two halves of the refresh: the per-group Gram blocks and diagonal blocks (one pass over Z and the diagonal of N),
+// then the scores from them; a caller may run the first half on another stream
+hipError_t launch_refresh_blocks(const TabDims& d, const TabPtrs& t, hipStream_t s) {
   if (d.q == 1) {
     hipLaunchKernelGGL(gram_dblk_q1_kernel, dim3((d.d1 + 3) / 4), dim3(256), 0, s, d.d1, d.m, t.N, t.Z, t.gram, t.dblk);
   } else {
@@ -832,8 +834,15 @@ hipError_t launch_refresh_scores(const TabDims& d, const TabPtrs& t, hipStream_t
     hipLaunchKernelGGL(group_gram_kernel, dim3(d.p, nb * (nb + 1) / 2), dim3(256), 0, s, d, t.Z, t.gram, (const SearchCtrl*)nullptr);
     hipLaunchKernelGGL(dblk_copy_kernel, dim3(d.p), dim3(256), 0, s, d, t.N, t.dblk);
   }
+  return hipGetLastError();
+}
+hipError_t launch_refresh_from_blocks(const TabDims& d, const TabPtrs& t, hipStream_t s) {
   launch_score(d, t.kept, t.gram, t.dblk, t.score, t.ctrl, 0, s);
   return hipGetLastError();
+}
+hipError_t launch_refresh_scores(const TabDims& d, const TabPtrs& t, hipStream_t s) {
+  const hipError_t e = launch_refresh_blocks(d, t, s);
+  return e != hipSuccess ? e : launch_refresh_from_blocks(d, t, s);
 }
 
 // ------------------------------------------------------------------------------------------------
