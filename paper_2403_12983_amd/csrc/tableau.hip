@@ -665,22 +665,24 @@ hipError_t spd_inverse_f64(const float* H, int64_t ldh, int n, float* P, double*
     hipLaunchKernelGGL(extract_panel64_kernel, dim3(rb), dim3(256), 0, s, A64, (int64_t)n, n, t0, w, panel);
     hipLaunchKernelGGL(inv_block64_kernel, dim3(1), dim3(256), 0, s, panel, w, t0, small, notpd_flag);
     hipLaunchKernelGGL(panel_times_small64_kernel, dim3((n + 7) / 8), dim3(256), 0, s, panel, small, n, w, t0, panelDz, panelCz);
-    if (pending) {                   // every tile outside this panel's own has to have step k - 1 behind it
-      if ((err = hipStreamWaitEvent(s, side->join, 0)) != hipSuccess) return err;
-      pending = false;
-    }
     if (!two) {
       hipLaunchKernelGGL(sweep_update64_kernel, dim3(upd_grid), dim3(512), shmem, s, panelDz, panelCz, n, w, A64, 0, k);
       hipLaunchKernelGGL(inv_fix64_kernel, dim3(rb), dim3(256), 0, s, A64, (int64_t)n, n, t0, w, panelDz, small);
       continue;
     }
-    if (k + 1 < tiles) hipLaunchKernelGGL(sweep_update64_kernel, dim3(tiles), dim3(512), shmem, s, panelDz, panelCz, n, w, A64, 1, k);
+    // The bulk updates follow one another on the side stream without a gap: step k's needs its operands (ready here) and
+    // step k - 1 on every tile it touches (the stream's order), nothing from this stream's later work.
     if ((err = hipEventRecord(side->fork, s)) != hipSuccess) return err;
     if ((err = hipStreamWaitEvent(side->stream, side->fork, 0)) != hipSuccess) return err;
+    // This stream's next launch changes the next panel's tiles, which the bulk update of step k - 1 also does: it waits for
+    // that one (the event's latest record), not for step k's, whose launch leaves those tiles out.
+    if (pending && (err = hipStreamWaitEvent(s, side->join, 0)) != hipSuccess) return err;
     hipLaunchKernelGGL(sweep_update64_kernel, dim3(upd_grid), dim3(512), shmem, side->stream, panelDz, panelCz, n, w, A64, 2, k);
     if ((err = hipEventRecord(side->join, side->stream)) != hipSuccess) return err;
     pending = true;
-    // tile row and column k only: no launch of this step's update touches them
+    if (k + 1 < tiles) hipLaunchKernelGGL(sweep_update64_kernel, dim3(tiles), dim3(512), shmem, s, panelDz, panelCz, n, w, A64, 1, k);
+    // tile row and column k only: no launch of this step's update touches them, the next step's bulk update does (it is
+    // enqueued behind an event that this stream records after the fix)
     hipLaunchKernelGGL(inv_fix64_kernel, dim3(rb), dim3(256), 0, s, A64, (int64_t)n, n, t0, w, panelDz, small);
   }
   if (pending && (err = hipStreamWaitEvent(s, side->join, 0)) != hipSuccess) return err;
