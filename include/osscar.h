@@ -266,6 +266,15 @@ osscar_status osscar_debug_int_products(int32_t enable);
  * on the other route), slot 11 the largest P_ii H_ii (the residual |I - H_KK P| before the last step on the other route). */
 osscar_status osscar_debug_refined_inverse(int32_t enable);
 
+/* The library overlaps independent parts of two phases on a second stream of its own: in the inverse of H_KK the bulk of
+ * each panel's update beside the next panel's small kernels, in the flush of the delayed-update search (Proposition 4.1
+ * applied to 64 pending swaps at once) the update of N beside that of Z and the products computed ahead.
+ * osscar_debug_side_stream(0) runs everything in order on the context's stream, (1) (the default) restores the overlap.
+ * Process-wide.  The inverse is bit-identical either way (every tile sees the same operations in the same order); the
+ * search may differ in the last digits of the row norms, because the candidates for the products computed ahead are then
+ * picked after the score refresh instead of before it. */
+osscar_status osscar_debug_side_stream(int32_t enable);
+
 /* Host-only inspection of the Gram kernel's tile schedule (no device is touched): writes up to `capacity` (row, column)
  * pairs of 128 x 128 tiles, in workgroup order, to out_host (2 ints each; (-1, -1) = padding) and returns the length of
  * the schedule, or -1 for a bad d1.  Workgroup i runs on XCD i % 8. */

@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = ["osscar_workspace_bytes", "osscar_create", "osscar_destroy",
                     "osscar_set_quadratic",
                     "osscar_init_support", "osscar_init_greedy", "osscar_local_search", "osscar_block_search", "osscar_apply_swap", "osscar_backsolve",
                     "osscar_get_tensor", "osscar_get_scalars", "osscar_get_timers", "osscar_get_counters", "osscar_debug_tile_schedule",
-                    "osscar_debug_gemm_log", "osscar_debug_gemm_log_read", "osscar_debug_int_products", "osscar_debug_refined_inverse",
+                    "osscar_debug_gemm_log", "osscar_debug_gemm_log_read", "osscar_debug_int_products", "osscar_debug_refined_inverse", "osscar_debug_side_stream",
                     "osscar_gram_static", "osscar_last_error"]
 
 
@@ -83,6 +83,7 @@ def load_library():
     lib.osscar_debug_gemm_log.argtypes = [i32]
     lib.osscar_debug_int_products.argtypes = [i32]
     lib.osscar_debug_refined_inverse.argtypes = [i32]
+    lib.osscar_debug_side_stream.argtypes = [i32]
     lib.osscar_debug_gemm_log_read.restype = C.c_int32
     lib.osscar_debug_gemm_log_read.argtypes = [C.POINTER(dbl), i32]
     lib.osscar_gram_static.argtypes = [vp, i64, i64, i32, vp, i64, i32, i64, i64, dbl, dbl, vp, vp, vp, vp]
@@ -309,6 +310,11 @@ def i8_products(enable: bool):
 def refined_inverse(enable: bool):
     """The inverse by the float32 sweep + Newton-Schulz (True) instead of the float64-storage sweep (False, the default)."""
     load_library().osscar_debug_refined_inverse(1 if enable else 0)
+
+
+def side_stream(enable: bool):
+    """The library's second stream (overlap inside the inverse and the flush; the default) on or off."""
+    load_library().osscar_debug_side_stream(1 if enable else 0)
 
 
 def gemm_log_read(capacity: int = 16384) -> np.ndarray:

@@ -384,6 +384,9 @@ __global__ __launch_bounds__(1024) void vif_max_kernel(const float* __restrict__
 // The inverse by the float64-storage sweep (default), or by the float32 sweep refined by Newton-Schulz
 // (osscar_debug_refined_inverse(1): the two are held against each other in the tests).
 bool g_refined_inverse = false;
+// osscar_debug_side_stream(0): no second stream anywhere (tests hold the overlapped schedules against the in-order ones)
+bool g_side_stream = true;
+static const SideStream* side_of(const osscar_ctx* c) { return (g_side_stream && c->ev_ok) ? &c->side : nullptr; }
 
 // B_known (optional, kr x m): the weights are known exactly (dense layer: B = W), only G_K is gathered beside them.
 osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b, const float* B_known = nullptr) {
@@ -404,7 +407,7 @@ osscar_status inverse_and_weights(osscar_ctx* c, const InvBufs& b, const float* 
     // The sweep on a float64 copy of H_KK (in the memory of T1 and T2), rounded to float32 once: exact to that rounding.
     HIPCHK(c, hipEventRecord(c->ev_s[2][0], s));
     HIPCHK(c, spd_inverse_f64(b.HKK, kr, kr, b.P, reinterpret_cast<double*>(b.T1), reinterpret_cast<double*>(b.panels), c->small, c->notpd, s,
-                              c->ev_ok ? &c->side : nullptr));
+                              side_of(c)));
     HIPCHK(c, hipEventRecord(c->ev_s[2][1], s));
     HIPCHK(c, launch_absmax(b.P, (int64_t)kr * kr, c->partial, s));
     hipLaunchKernelGGL(vif_max_kernel, dim3(1), dim3(1024), 0, s, b.P, b.HKK, kr, c->scal + 20);
@@ -965,7 +968,7 @@ osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_e
       takes.push_back(take); batch += take; kept_b -= take;
     }
     if (takes.empty()) {   // the pending set is full: apply it and try again
-      HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, &c->side));
+      HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, side_of(c)));
       pending = 0;
       continue;
     }
@@ -979,7 +982,7 @@ osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_e
       int acc = 0, it_idx = 0;
       while (acc + takes[it_idx] <= done) { acc += takes[it_idx]; it_idx++; }
       const int off = done - acc;                       // removals of iteration it_idx already applied
-      HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, &c->side));       // also clears pause
+      HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, side_of(c)));       // also clears pause
       for (int i = off; i < takes[it_idx]; i++) HIPCHK(c, step(i));   // its pick list is still on the device
       pending = takes[it_idx] - off;
       batch = acc + takes[it_idx];
@@ -992,7 +995,7 @@ osscar_status osscar_init_greedy(osscar_ctx* c, int32_t t_hat, int32_t refresh_e
     kept_now -= batch;
     since_refresh += batch;
     const bool refresh = refresh_every > 0 && since_refresh >= refresh_every && kept_now > k;
-    if (use_lazy && (refresh || kept_now == k) && pending > 0) { HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, &c->side)); pending = 0; }
+    if (use_lazy && (refresh || kept_now == k) && pending > 0) { HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, side_of(c))); pending = 0; }
     if (refresh) {
       st = read_kept(c);
       if (st != OSSCAR_OK) return st;
@@ -1067,7 +1070,7 @@ osscar_status osscar_local_search(osscar_ctx* c, int32_t max_swaps, double rel_t
     };
     auto flush = [&]() -> osscar_status {
       HIPCHK(c, hipEventRecord(c->ev_s[0][0], s));
-      HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, &c->side));
+      HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, side_of(c)));
       HIPCHK(c, hipEventRecord(c->ev_s[0][1], s));
       flush_open = true; flushes++;
       since_flush = 0;
@@ -1217,7 +1220,7 @@ osscar_status osscar_block_search(osscar_ctx* c, int32_t max_iters, int32_t bloc
       done_pairs += did; idx += did; pending += 2 * did;
       if (idx < out.size()) {
         if (!use_lazy || !h.pause) return fail(c, OSSCAR_ESTATE, "internal: osscar_block_search stopped without a reason");
-        HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, &c->side));
+        HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, side_of(c)));
         pending = 0;
       }
     }
@@ -1226,7 +1229,7 @@ osscar_status osscar_block_search(osscar_ctx* c, int32_t max_iters, int32_t bloc
   std::vector<int32_t> out(take), inn(take);
   float gaps[2] = {0, 0};
   while (take > 0 && blocks < max_iters) {
-    if (use_lazy && pending + 2 * take > LAZY_TM) { HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, &c->side)); pending = 0; }
+    if (use_lazy && pending + 2 * take > LAZY_TM) { HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, side_of(c))); pending = 0; }
     HIPCHK(c, launch_greedy_pick(d, t, take, c->g_pick, c->g_gap, s, 0));
     HIPCHK(c, launch_greedy_pick(d, t, take, c->g_pick + 64, c->g_gap + 1, s, 1));
     HIPCHK(c, hipMemcpyAsync(out.data(), c->g_pick, (size_t)take * 4, hipMemcpyDeviceToHost, s));
@@ -1247,7 +1250,7 @@ osscar_status osscar_block_search(osscar_ctx* c, int32_t max_iters, int32_t bloc
     blocks++;
     if (!ok) {
       // take the move back: the same pairs in reverse (the pending pivots must reach the tableau first)
-      if (use_lazy && pending > 0) { HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, &c->side)); pending = 0; }
+      if (use_lazy && pending > 0) { HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, side_of(c))); pending = 0; }
       std::vector<int32_t> bo(inn.rbegin(), inn.rend()), bi(out.rbegin(), out.rend());
       st = run_pairs(bo, bi);
       if (st != OSSCAR_OK) return st;
@@ -1257,7 +1260,7 @@ osscar_status osscar_block_search(osscar_ctx* c, int32_t max_iters, int32_t bloc
     }
     accepted++;
   }
-  if (use_lazy && pending > 0) HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, &c->side));
+  if (use_lazy && pending > 0) HIPCHK(c, launch_lazy_flush(d, t, L, s, la_mode, side_of(c)));
   HIPCHK(c, hipEventRecord(c->ev_b, s));
   HIPCHK(c, hipStreamSynchronize(s));
   c->timers[3] = elapsed(c);
@@ -1449,6 +1452,7 @@ int32_t osscar_debug_tile_schedule(int64_t d1, int32_t* out_host, int32_t capaci
 osscar_status osscar_debug_gemm_log(int32_t enable) { gemm_log_enable(enable); return OSSCAR_OK; }
 osscar_status osscar_debug_int_products(int32_t enable) { g_i8_products = enable != 0; return OSSCAR_OK; }
 osscar_status osscar_debug_refined_inverse(int32_t enable) { g_refined_inverse = enable != 0; return OSSCAR_OK; }
+osscar_status osscar_debug_side_stream(int32_t enable) { g_side_stream = enable != 0; return OSSCAR_OK; }
 int32_t osscar_debug_gemm_log_read(double* out_host, int32_t capacity) {
   if (!out_host || capacity < 0) return -1;
   return gemm_log_read(out_host, capacity);

@@ -554,6 +554,25 @@ def test_cfg5_search_variants_agree():
         if min(a["trace_gap"].min(axis=0)) > 1e-9 or np.array_equal(sup, runs[0][1]):
             assert np.array_equal(sup, runs[0][1])
     print("cfg5 shape, %d swaps: look-ahead %.0f ms, pass per swap %.0f ms, in place %.0f ms" % (swaps, runs[0][3], runs[1][3], runs[2][3]))
+    # The second stream off: the inverse (112 panels here, each with its bulk update beside the next panel's kernels) must
+    # come out bit for bit the same, and the search must take the same swaps up to a tie.
+    from paper_2403_12983_amd import binding as B
+    s.osscar_init_support()
+    P_two = T(s, "T_P")
+    try:
+        B.side_stream(False)
+        s.osscar_init_support()
+        assert torch.equal(T(s, "T_P"), P_two)
+        del P_two
+        r = s.osscar_local_search(swaps, 0.0, 0)
+    finally:
+        B.side_stream(True)
+    assert r["accepted"] == swaps
+    for i in range(swaps):
+        if (a["trace_out"][i], a["trace_in"][i]) != (r["trace_out"][i], r["trace_in"][i]):
+            assert min(a["trace_gap"][i]) < GAP, (i, a["trace_gap"][i])
+            break
+    assert abs(r["obj_final"] - a["obj_final"]) <= 1e-6 * abs(a["obj_final"])
     s.close()
 
 

@@ -570,6 +570,45 @@ def test_two_runs_give_identical_bits(name):
         assert x == y, label
 
 
+@pytest.mark.parametrize("name", ["i8ragged", "i8even", "long"])
+def test_second_stream_schedules_equal_the_in_order_ones(name):
+    """The inverse overlaps each panel's bulk update with the next panel's small kernels on a second stream, the flush its
+    two updates and the products computed ahead.  Every tile sees the same operations in the same order either way, so the
+    state built by osscar_init_support (P, and B, V, R and the scores that follow from it) must be bit-identical with the
+    second stream switched off; a difference means a missing dependency between the streams.  The search takes the same
+    swaps (its candidates for the products computed ahead are picked at a different moment, which may change row norms in
+    the last digits, so objective and state are held to 1e-6 / 1e-5)."""
+    from paper_2403_12983_amd import binding as B
+    c = Case(inp.scaled(inp.CONFIGS["cfg3"], p=1024, m=264, n=6000, k=512, swaps=200)) if name == "long" else case(name)
+    swaps = 200 if name == "long" else 70
+    out = []
+    try:
+        for side in (True, False):
+            B.side_stream(side)
+            s = c.solver(swaps)
+            c.gram(s)
+            obj0 = s.osscar_init_support()
+            init = [T(s, k).tobytes() for k in ("T_P", "T_B", "T_V", "T_R", "T_REM", "T_ADD")]
+            r = s.osscar_local_search(swaps, 0.0, B.OSSCAR_SEARCH_ALWAYS_ACCEPT)
+            out.append((obj0, init, r, T(s, "T_P"), T(s, "T_B"), s.osscar_get_counters()))
+            s.close()
+    finally:
+        B.side_stream(True)
+    (o1, i1, r1, P1, B1, c1), (o2, i2, r2, P2, B2, c2) = out
+    assert o1 == o2
+    for label, x, y in zip(("P", "B", "V", "R", "REM", "ADD"), i1, i2):
+        assert x == y, label
+    assert r1["iters"] == r2["iters"] == swaps and c1["flushes"] >= 1 and c2["flushes"] >= 1          # at least one flush each
+    for i in range(swaps):
+        if (r1["trace_out"][i], r1["trace_in"][i]) != (r2["trace_out"][i], r2["trace_in"][i]):
+            assert min(r1["trace_gap"][i]) <= GAP, (i, r1["trace_gap"][i])
+            assert np.allclose(r1["trace_obj"][:i], r2["trace_obj"][:i], rtol=1e-6, atol=0)
+            break
+    else:
+        assert abs(r1["obj_final"] - r2["obj_final"]) <= 1e-6 * abs(r2["obj_final"])
+        assert rel(P1, P2) < 1e-5 and rel(B1, B2) < 1e-5
+
+
 # ------------------------------------------------------------------------------------------ set_quadratic
 # ------------------------------------------------------------------------------------------ nested schedule from the dense layer
 def dense_solver(c, max_swaps=None):
