@@ -202,21 +202,37 @@ hipError_t launch_mirror_lower(float* A, int n, int64_t lda, hipStream_t s) {
   return hipGetLastError();
 }
 
-// out[b] for 256 blocks, then the caller reduces on the host (256 doubles)
-__global__ __launch_bounds__(256) void absmax_partial_kernel(const float* __restrict__ A, int64_t n, double* out) {
-  __shared__ double sh[4];
+// out[b] for 256 blocks, then the caller reduces on the host (256 doubles).  A bandwidth-bound pass: 1024 threads per
+// block, four 16-byte loads in flight per thread (scalar loads for an unaligned start and for the tail).
+__device__ __forceinline__ float absmax_take(float v, float x) { x = fabsf(x); return (x > v || x != x) ? x : v; }
+__global__ __launch_bounds__(1024) void absmax_partial_kernel(const float* __restrict__ A, int64_t n, double* out) {
+  __shared__ float sh[16];
   // a NaN is taken (x != x) and then stays (nothing compares greater than it), so a NaN anywhere reaches the result
-  double v = 0;
-  for (int64_t i = blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    double x = fabs((double)A[i]); v = (x > v || x != x) ? x : v;
+  float v[4] = {0.f, 0.f, 0.f, 0.f};
+  const int64_t head = ((reinterpret_cast<uintptr_t>(A) & 15) == 0) ? 0 : n;      // unaligned: everything in the scalar loop
+  const int64_t n4 = (n - head) / 4;
+  const float4* A4 = reinterpret_cast<const float4*>(A);
+  const int64_t tid = blockIdx.x * 1024 + threadIdx.x, nth = (int64_t)gridDim.x * 1024;
+  for (int64_t i = tid; i < n4; i += 4 * nth) {
+    float4 q[4];
+#pragma unroll
+    for (int u = 0; u < 4; u++) { const int64_t k = i + u * nth; q[u] = A4[k < n4 ? k : i]; }
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+      v[u] = absmax_take(v[u], q[u].x); v[u] = absmax_take(v[u], q[u].y); v[u] = absmax_take(v[u], q[u].z); v[u] = absmax_take(v[u], q[u].w);
+    }
   }
-  for (int o = 32; o > 0; o >>= 1) { double w = __shfl_down(v, o, 64); v = (w > v || w != w) ? w : v; }
-  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  for (int64_t i = head == 0 ? 4 * n4 + tid : tid; i < n; i += nth) v[0] = absmax_take(v[0], A[i]);
+  float t = v[0];
+#pragma unroll
+  for (int u = 1; u < 4; u++) t = (v[u] > t || v[u] != v[u]) ? v[u] : t;
+  for (int o = 32; o > 0; o >>= 1) { const float w = __shfl_down(t, o, 64); t = (w > t || w != w) ? w : t; }
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = t;
   __syncthreads();
-  if (threadIdx.x == 0) { double t = 0; for (int i = 0; i < 4; i++) t = (sh[i] > t || sh[i] != sh[i]) ? sh[i] : t; out[blockIdx.x] = t; }
+  if (threadIdx.x == 0) { float r = 0.f; for (int i = 0; i < 16; i++) r = (sh[i] > r || sh[i] != sh[i]) ? sh[i] : r; out[blockIdx.x] = (double)r; }
 }
 hipError_t launch_absmax(const float* A, int64_t n, double* out, hipStream_t s) {  // out: 256 doubles
-  hipLaunchKernelGGL(absmax_partial_kernel, dim3(256), dim3(256), 0, s, A, n, out);
+  hipLaunchKernelGGL(absmax_partial_kernel, dim3(256), dim3(1024), 0, s, A, n, out);
   return hipGetLastError();
 }
 
@@ -399,12 +415,33 @@ __global__ void widen_lower_kernel(const float* __restrict__ H, int64_t ldh, int
     if (j <= i) A[idx] = (double)H[(int64_t)i * ldh + j];
   }
 }
-// P[i][j] = P[j][i] = float(-A[i][j]), j <= i: the swept lower triangle -H^-1 as the full float32 inverse
-__global__ void narrow_negate_mirror_kernel(const double* __restrict__ A, int n, float* __restrict__ P) {
-  const int64_t tot = (int64_t)n * n;
-  for (int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; idx < tot; idx += (int64_t)gridDim.x * blockDim.x) {
-    const int i = (int)(idx / n), j = (int)(idx % n);
-    P[idx] = (float)(-(j <= i ? A[idx] : A[(int64_t)j * n + i]));
+// P[i][j] = P[j][i] = float(-A[i][j]), j <= i: the swept lower triangle -H^-1 as the full float32 inverse.  One workgroup per
+// 32 x 32 tile on or below the diagonal; the mirrored tile is written from shared memory so that both writes run along rows.
+__global__ __launch_bounds__(256) void narrow_negate_mirror_kernel(const double* __restrict__ A, int n, float* __restrict__ P) {
+  __shared__ float T[32][33];
+  int bi = (int)((sqrtf(8.f * (float)blockIdx.x + 1.f) - 1.f) * 0.5f);
+  while ((int64_t)(bi + 1) * (bi + 2) / 2 <= (int64_t)blockIdx.x) bi++;
+  while ((int64_t)bi * (bi + 1) / 2 > (int64_t)blockIdx.x) bi--;
+  const int bj = (int)(blockIdx.x - (int64_t)bi * (bi + 1) / 2);
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+  for (int k = 0; k < 4; k++) {
+    const int r = ty + 8 * k, i = bi * 32 + r, j = bj * 32 + tx;
+    T[r][tx] = (i < n && j <= i) ? (float)(-A[(int64_t)i * n + j]) : 0.f;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 4; k++) {
+    const int r = ty + 8 * k;
+    const int i = bi * 32 + r, j = bj * 32 + tx;
+    if (i < n && j < n) {
+      if (j <= i) P[(int64_t)i * n + j] = T[r][tx];
+      else if (bi == bj) P[(int64_t)i * n + j] = T[tx][r];       // upper part of a diagonal tile
+    }
+    if (bi != bj) {
+      const int mi = bj * 32 + r, mj = bi * 32 + tx;             // the mirrored tile, row r of it = column r of this one
+      if (mi < n && mj < n) P[(int64_t)mi * n + mj] = T[tx][r];
+    }
   }
 }
 __global__ __launch_bounds__(256) void extract_panel64_kernel(const double* __restrict__ N, int64_t ld, int n, int t0, int w,
@@ -686,7 +723,8 @@ hipError_t spd_inverse_f64(const float* H, int64_t ldh, int n, float* P, double*
     hipLaunchKernelGGL(inv_fix64_kernel, dim3(rb), dim3(256), 0, s, A64, (int64_t)n, n, t0, w, panelDz, small);
   }
   if (pending && (err = hipStreamWaitEvent(s, side->join, 0)) != hipSuccess) return err;
-  hipLaunchKernelGGL(narrow_negate_mirror_kernel, dim3(blocks), dim3(256), 0, s, A64, n, P);
+  const int64_t t32 = (n + 31) / 32;
+  hipLaunchKernelGGL(narrow_negate_mirror_kernel, dim3((unsigned)(t32 * (t32 + 1) / 2)), dim3(256), 0, s, A64, n, P);
   return hipGetLastError();
 }
 
