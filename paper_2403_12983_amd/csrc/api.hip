@@ -192,7 +192,7 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
     L.pos = cv.take<int32_t>(d1); L.Tidx = cv.take<int32_t>(TM); L.Jsg = cv.take<float>(TM);
     L.C0R = cv.take<float>(d1 * TM); L.Minv = cv.take<double>(TM * TM); L.Minv32 = cv.take<float>(TM * TM);
     L.ZT = cv.take<double>(TM * m); L.ZT32 = cv.take<float>(TM * m); L.E = cv.take<float>(d1 * TM);
-    L.xg = cv.take<double>(TM); L.xj = cv.take<double>(TM); L.u1 = cv.take<double>(TM); L.u2 = cv.take<double>(TM);
+    L.xg = cv.take<double>(TM); L.xj = cv.take<double>(TM); L.u1 = cv.take<double>(4 * TM); L.u2 = cv.take<double>(4 * TM);      // GEMV_SPLIT partial sums per pending row
     L.cg = cv.take<double>(d1); L.cj = cv.take<double>(d1); L.w1 = cv.take<double>(d1); L.w2 = cv.take<double>(d1);
     L.y1 = cv.take<double>(m); L.y2 = cv.take<double>(m); L.y1f = cv.take<float>(m); L.y2f = cv.take<float>(m);
     L.part = cv.take<double>(((m + 63) / 64) * 5); L.ls = cv.take<double>(16);

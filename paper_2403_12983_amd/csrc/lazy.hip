@@ -343,6 +343,7 @@ constexpr int LAZY_CH = 4096;
 constexpr int GEMV_RPW = 4;        // rows per wave
 constexpr int GEMV_UNR = 4;        // float4 loads in flight per row and lane
 constexpr int GEMV_ROWS = 4 * GEMV_RPW;
+constexpr int GEMV_SPLIT = 4;      // leading workgroups per pending row of ZT (u1, u2 hold one partial sum per workgroup)
 
 __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float* __restrict__ Z0, int d1, int m, int col_blocks,
                                                          SearchCtrl* ctrl, int always_accept, int32_t* trace_out,
@@ -350,27 +351,40 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
   __shared__ float sy1[LAZY_CH], sy2[LAZY_CH];
   __shared__ int s_ok;
   if (idle(ctrl)) return;
-  constexpr int ZTB = LAZY_TM;                        // leading workgroups: one pending row of ZT each
+  constexpr int ZTB = LAZY_TM * GEMV_SPLIT;           // leading workgroups: a GEMV_SPLIT-th of one pending row of ZT each
   // the row workgroups have work only when a pivot's products were not computed ahead (workgroup 0 records the decision)
   if ((int)blockIdx.x >= ZTB && L.misc[MI_MISS] == 0) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // u = ZT [y1 y2], one pending row per leading workgroup: started before the acceptance sums (it does not depend on them;
-  // a rejected swap, which ends the search, just discards it)
+  // The partial records of the acceptance sums are requested first (wave 0; lane l takes the records l, l + 64, ...), then
+  // the workgroup's part of u: both are in flight together and neither waits for the other's round trip.
+  double pr[2][5];
+#pragma unroll
+  for (int h = 0; h < 2; h++)
+#pragma unroll
+    for (int k = 0; k < 5; k++) { const int b = lane + 64 * h; pr[h][k] = (wave == 0 && b < col_blocks) ? L.part[b * 5 + k] : 0.0; }
+  // u = ZT [y1 y2]: started before the acceptance sums (it does not depend on them; a rejected swap, which ends the search,
+  // just discards it).  Each leading workgroup takes one stretch of columns of one pending row, so that a thread has all its
+  // loads in flight at once; the stretches' sums are added in a fixed order by the kernel that uses u.
   double ua = 0, ub = 0;
-  if ((int)blockIdx.x < ZTB && (int)blockIdx.x < ctrl->tau) {
-    const double* zt = L.ZT + (int64_t)blockIdx.x * m;
-    for (int c0 = tid; c0 < m; c0 += 2048) {             // eight columns in flight per thread
+  const int urow = (int)blockIdx.x / GEMV_SPLIT, upart = (int)blockIdx.x % GEMV_SPLIT;
+  if ((int)blockIdx.x < ZTB && urow < ctrl->tau) {
+    const double* zt = L.ZT + (int64_t)urow * m;
+    const int chunk = (m + GEMV_SPLIT * 256 - 1) / (GEMV_SPLIT * 256) * 256;
+    const int c_begin = upart * chunk, c_end = min(m, c_begin + chunk);
+    for (int c0 = c_begin + tid; c0 < c_end; c0 += 2048) {             // eight columns in flight per thread
       double z[8], p1[8], p2[8];
 #pragma unroll
-      for (int u = 0; u < 8; u++) { const int c = c0 + 256 * u, cc = c < m ? c : c0; z[u] = zt[cc]; p1[u] = L.y1[cc]; p2[u] = L.y2[cc]; }
+      for (int u = 0; u < 8; u++) { const int c = c0 + 256 * u, cc = c < c_end ? c : c0; z[u] = zt[cc]; p1[u] = L.y1[cc]; p2[u] = L.y2[cc]; }
 #pragma unroll
-      for (int u = 0; u < 8; u++) if (c0 + 256 * u < m) { ua += z[u] * p1[u]; ub += z[u] * p2[u]; }
+      for (int u = 0; u < 8; u++) if (c0 + 256 * u < c_end) { ua += z[u] * p1[u]; ub += z[u] * p2[u]; }
     }
   }
   if (wave == 0) {
     // partial sums in a fixed order: lane l adds the records l, l + 64, ...; then a wave reduction
-    double sk[5] = {0, 0, 0, 0, 0};
-    for (int b = lane; b < col_blocks; b += 64)
+    double sk[5];
+#pragma unroll
+    for (int k = 0; k < 5; k++) sk[k] = pr[0][k] + pr[1][k];
+    for (int b = lane + 128; b < col_blocks; b += 64)
 #pragma unroll
       for (int k = 0; k < 5; k++) sk[k] += L.part[b * 5 + k];
 #pragma unroll
@@ -397,13 +411,12 @@ __global__ __launch_bounds__(256) void lazy_gemv_kernel(LazyPtrs L, const float*
   if (!s_ok) return;
   if ((int)blockIdx.x < ZTB) {
     __shared__ double ured[2][4];
-    const int row = blockIdx.x;
     const double a = wsum(ua), b = wsum(ub);
     if (lane == 0) { ured[0][wave] = a; ured[1][wave] = b; }
     __syncthreads();
     if (tid == 0) {                                      // zero beyond tau
-      L.u1[row] = ured[0][0] + ured[0][1] + ured[0][2] + ured[0][3];
-      L.u2[row] = ured[1][0] + ured[1][1] + ured[1][2] + ured[1][3];
+      L.u1[upart * LAZY_TM + urow] = ured[0][0] + ured[0][1] + ured[0][2] + ured[0][3];
+      L.u2[upart * LAZY_TM + urow] = ured[1][0] + ured[1][1] + ured[1][2] + ured[1][3];
     }
     return;
   }
@@ -532,7 +545,12 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
   const double Dg = L.ls[LS_DG], M1 = L.ls[LS_M1], Dj = L.ls[LS_DJ];
   const int b = blockIdx.x;
   if (b < row_blocks) {
-    for (int s = tid; s < LAZY_TM; s += 256) { sa[s] = L.u1[s]; sb[s] = L.u2[s]; }
+    for (int s = tid; s < LAZY_TM; s += 256) {            // u = the partial sums of the acceptance kernel's workgroups, in order
+      double a = 0, c = 0;
+#pragma unroll
+      for (int h = 0; h < GEMV_SPLIT; h++) { a += L.u1[h * LAZY_TM + s]; c += L.u2[h * LAZY_TM + s]; }
+      sa[s] = a; sb[s] = c;
+    }
     __syncthreads();
     const double y11 = L.ls[LS_Y11], y22 = L.ls[LS_Y22], y12 = L.ls[LS_Y12];
     const bool miss = L.misc[MI_MISS] != 0;
@@ -665,7 +683,7 @@ hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyP
   const int rb = (d.d1 + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, cb = (d.m + COLS_PER_BLOCK - 1) / COLS_PER_BLOCK;
   hipLaunchKernelGGL(lazy_prep_kernel, dim3(1), dim3(256), 0, s, L, t.N, d.d1, rb, t.kept, t.ctrl, single, forced_out, forced_in);
   hipLaunchKernelGGL(lazy_vectors_kernel, dim3(rb + cb + (d.d1 + 63) / 64), dim3(256), 0, s, L, t.N, t.Z, d.d1, d.m, rb, cb, t.ctrl);
-  const int gb = (d.d1 + GEMV_ROWS - 1) / GEMV_ROWS + LAZY_TM;
+  const int gb = (d.d1 + GEMV_ROWS - 1) / GEMV_ROWS + LAZY_TM * GEMV_SPLIT;
   if (ev) hipEventRecord(ev[0], s);
   hipLaunchKernelGGL(lazy_gemv_kernel, dim3(gb), dim3(256), 0, s, L, t.Z, d.d1, d.m, cb, t.ctrl, always_accept, t.trace_out,
                      t.trace_in, t.trace_gap, t.trace_obj, single ? 1 : 2);
