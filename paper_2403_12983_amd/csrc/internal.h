@@ -192,6 +192,8 @@ hipError_t launch_select(const TabDims& d, const TabPtrs& t, int forced_out, int
 constexpr int LAZY_TM = 128;     // capacity of the pending pivot set (two per swap)
 constexpr int LAZY_NC = 256;     // rows of Z0 whose products with all of Z0 are computed ahead, after every flush
 constexpr int LAZY_NS = 64;      // spare slots for pivots that were not among them
+constexpr int LAZY_NPICK_OUT = 88;  // swap search: kept rows picked by cost of removal ...
+constexpr int LAZY_NPICK_IN = 72;   // ... and rows outside the kept set picked by gain; together a multiple of 32
 constexpr int LAZY_BT = 16;      // rows that one block removal of the nested schedule takes at most
 struct SelRec { double mn1, mn2, mx1, mx2; int32_t imn, imx; };   // best / second-best scores of a block of rows
 struct LazyPtrs {

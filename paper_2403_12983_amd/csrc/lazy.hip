@@ -834,7 +834,8 @@ __global__ __launch_bounds__(256) void cand_gather_kernel(LazyPtrs L, const floa
 typedef float la_f16v __attribute__((ext_vector_type(16)));
 typedef __bf16 la_bf8 __attribute__((ext_vector_type(8)));
 constexpr int LA_STG = 32;                   // columns of Z per stage (two 16-deep matrix-core steps)
-constexpr int LA_PK = 3 * 4 * 128;           // 16-byte packets per stage: 3 pieces x 4 groups of 8 columns x 128 candidates
+// A workgroup multiplies its rows of Z0 with one block of NC = 32 NT candidates (NT = 4, 5 or 6 tiles of 32 per wave);
+// packets per stage and block: 3 pieces x 4 groups of 8 columns x NC candidates.
 
 __device__ __forceinline__ uint32_t la_rne(float x) {
   const uint32_t u = __float_as_uint(x);
@@ -856,15 +857,14 @@ __device__ __forceinline__ void la_split3(const float* v, uint4& p1, uint4& p2, 
   p3 = uint4{h3[0] | (h3[1] << 16), h3[2] | (h3[3] << 16), h3[4] | (h3[5] << 16), h3[6] | (h3[7] << 16)};
 }
 
-// ZcP[(sb * nstg + stage) * LA_PK + piece * 512 + kg * 128 + s] = columns stage*32 + kg*8 .. +8 of candidate sb*128 + s, piece
-// `piece` (zero for unused slots and beyond column m).  grid (nstg, ns / 128), 256 threads, two packets' worth of columns each.
-__global__ __launch_bounds__(256) void la_pack_kernel(LazyPtrs L, const float* __restrict__ Z0, int m, int nstg, uint4* __restrict__ ZcP) {
+// ZcP[(sb * nstg + stage) * 12 nc + piece * 4 nc + kg * nc + s] = columns stage*32 + kg*8 .. +8 of candidate sb*nc + s, piece
+// `piece` (zero for unused slots and beyond column m).  grid (nstg, number of blocks of nc candidates), 256 threads.
+__global__ __launch_bounds__(256) void la_pack_kernel(LazyPtrs L, const float* __restrict__ Z0, int m, int nstg, int nc, uint4* __restrict__ ZcP) {
   const int stage = blockIdx.x, sb = blockIdx.y, tid = threadIdx.x;
-  uint4* out = ZcP + ((int64_t)sb * nstg + stage) * LA_PK;
-#pragma unroll
-  for (int h = 0; h < 2; h++) {
-    const int pk = tid + 256 * h, kg = pk >> 7, sl = pk & 127;
-    const int r = L.cand[sb * 128 + sl], c0 = stage * LA_STG + kg * 8;
+  uint4* out = ZcP + ((int64_t)sb * nstg + stage) * 12 * nc;
+  for (int pk = tid; pk < 4 * nc; pk += 256) {
+    const int kg = pk / nc, sl = pk % nc;
+    const int r = L.cand[sb * nc + sl], c0 = stage * LA_STG + kg * 8;
     float v[8];
 #pragma unroll
     for (int j = 0; j < 8; j++) v[j] = 0.f;
@@ -875,72 +875,76 @@ __global__ __launch_bounds__(256) void la_pack_kernel(LazyPtrs L, const float* _
     }
     uint4 p1, p2, p3;
     la_split3(v, p1, p2, p3);
-    out[pk] = p1; out[512 + pk] = p2; out[1024 + pk] = p3;
+    out[pk] = p1; out[4 * nc + pk] = p2; out[8 * nc + pk] = p3;
   }
 }
 
-// GbT[(sb * 128 + s) * d1 + i] for i in [128 blockIdx.x, +128), s in [0, 128), sb = blockIdx.y.  m % 8 == 0.
+// GbT[(sb * NC + s) * d1 + i] for i in [128 blockIdx.x, +128), s in [0, NC), sb = blockIdx.y, NC = 32 NT.  m % 8 == 0.
 // Per stage of 32 columns the workgroup copies its 128 x 32 tile of Z0 (each row's 128 bytes by eight neighbouring lanes)
 // and the candidates' packed pieces into shared memory; the next stage's loads are in flight while this one is
 // multiplied.  Two workgroups share a compute unit.
 constexpr int LA_ZLD = LA_STG + 4;           // row stride of the Z0 tile in shared memory (floats)
+template <int NT>
 __global__ __launch_bounds__(256, 2) void la_product_kernel(const uint4* __restrict__ ZcP, const float* __restrict__ Z0, int d1, int m,
                                                              int nstg, double* __restrict__ GbT) {
-  __shared__ uint4 lzc[LA_PK];                                 // 24 KB
+  constexpr int NC = 32 * NT, PK = 12 * NC, NLD = (PK + 255) / 256;      // candidates, packets per stage, loads per thread
+  __shared__ uint4 lzc[PK];                                    // 6 KB per 32 candidates
   __shared__ __attribute__((aligned(16))) float lz0[128 * LA_ZLD];   // 18 KB
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, sb = blockIdx.y;
   const int i0 = blockIdx.x * 128;
-  const uint4* src = ZcP + (int64_t)sb * nstg * LA_PK + tid;
+  const uint4* src = ZcP + (int64_t)sb * nstg * PK + tid;
   // global -> shared assignment of the Z0 tile: thread t takes 4 columns (t % 8) * 4 of rows t / 8 + 32 j, j < 4
   const int lr = tid >> 3, lk = (tid & 7) * 4;
   auto rowp = [&](int j) { const int row = i0 + lr + 32 * j; return Z0 + (int64_t)(row < d1 ? row : d1 - 1) * m + lk; };
   const float *zsrc0 = rowp(0), *zsrc1 = rowp(1), *zsrc2 = rowp(2), *zsrc3 = rowp(3);      // rows past the end: clamped, never stored
-  la_f16v acc[4], acc2[4];
+  la_f16v acc[NT], acc2[NT];
 #pragma unroll
-  for (int t = 0; t < 4; t++)
+  for (int t = 0; t < NT; t++)
 #pragma unroll
     for (int r = 0; r < 16; r++) { acc[t][r] = 0.f; acc2[t][r] = 0.f; }
-  uint4 zc0, zc1, zc2, zc3, zc4, zc5;
+  uint4 zc[NLD];
   float4 zt0, zt1, zt2, zt3;
-#define OSSCAR_LA_GLOAD(stage_)                                                                              \
-  {                                                                                                          \
-    const uint4* p_ = src + (int64_t)(stage_) * LA_PK;                                                       \
-    zc0 = p_[0]; zc1 = p_[256]; zc2 = p_[512]; zc3 = p_[768]; zc4 = p_[1024]; zc5 = p_[1280];                \
-    const bool in_ = (stage_) * LA_STG + lk + 4 <= m;                                                        \
-    const float4 z_ = float4{0.f, 0.f, 0.f, 0.f};                                                            \
-    zt0 = in_ ? *reinterpret_cast<const float4*>(zsrc0 + (stage_) * LA_STG) : z_;                            \
-    zt1 = in_ ? *reinterpret_cast<const float4*>(zsrc1 + (stage_) * LA_STG) : z_;                            \
-    zt2 = in_ ? *reinterpret_cast<const float4*>(zsrc2 + (stage_) * LA_STG) : z_;                            \
-    zt3 = in_ ? *reinterpret_cast<const float4*>(zsrc3 + (stage_) * LA_STG) : z_;                            \
-  }
-  OSSCAR_LA_GLOAD(0);
+  auto gload = [&](int stage_) {
+    const uint4* p_ = src + (int64_t)stage_ * PK;
+#pragma unroll
+    for (int i = 0; i < NLD; i++) zc[i] = (tid + 256 * i < PK) ? p_[256 * i] : uint4{0u, 0u, 0u, 0u};
+    const bool in_ = stage_ * LA_STG + lk < m;              /* m % 4 == 0: a float4 is inside or outside as a whole */
+    const float4 z_ = float4{0.f, 0.f, 0.f, 0.f};
+    zt0 = in_ ? *reinterpret_cast<const float4*>(zsrc0 + stage_ * LA_STG) : z_;
+    zt1 = in_ ? *reinterpret_cast<const float4*>(zsrc1 + stage_ * LA_STG) : z_;
+    zt2 = in_ ? *reinterpret_cast<const float4*>(zsrc2 + stage_ * LA_STG) : z_;
+    zt3 = in_ ? *reinterpret_cast<const float4*>(zsrc3 + stage_ * LA_STG) : z_;
+  };
+  gload(0);
   int since = 0;
   const float* myrow = lz0 + (wave * 32 + (lane & 31)) * LA_ZLD + (lane >> 5) * 8;
   for (int stage = 0; stage < nstg; stage++) {
     __syncthreads();                                           // the previous stage has been read by every wave
-    lzc[tid] = zc0; lzc[tid + 256] = zc1; lzc[tid + 512] = zc2; lzc[tid + 768] = zc3; lzc[tid + 1024] = zc4; lzc[tid + 1280] = zc5;
+#pragma unroll
+    for (int i = 0; i < NLD; i++)
+      if (tid + 256 * i < PK) lzc[tid + 256 * i] = zc[i];
     *reinterpret_cast<float4*>(lz0 + lr * LA_ZLD + lk) = zt0;
     *reinterpret_cast<float4*>(lz0 + (lr + 32) * LA_ZLD + lk) = zt1;
     *reinterpret_cast<float4*>(lz0 + (lr + 64) * LA_ZLD + lk) = zt2;
     *reinterpret_cast<float4*>(lz0 + (lr + 96) * LA_ZLD + lk) = zt3;
     __syncthreads();
-    if (stage + 1 < nstg) OSSCAR_LA_GLOAD(stage + 1);
+    if (stage + 1 < nstg) gload(stage + 1);
 #pragma unroll
-    for (int ks = 0; ks < 2; ks++) {
-      const float4 va = *reinterpret_cast<const float4*>(myrow + ks * 16), vb = *reinterpret_cast<const float4*>(myrow + ks * 16 + 4);
-      const float v[8] = {va.x, va.y, va.z, va.w, vb.x, vb.y, vb.z, vb.w};
+    for (int ks = 0; ks < LA_STG / 16; ks++) {
+      const float4 v0 = *reinterpret_cast<const float4*>(myrow + ks * 16), v1 = *reinterpret_cast<const float4*>(myrow + ks * 16 + 4);
+      const float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
       uint4 b1, b2, b3;
       la_split3(v, b1, b2, b3);
       const la_bf8 f1 = *reinterpret_cast<const la_bf8*>(&b1), f2 = *reinterpret_cast<const la_bf8*>(&b2), f3 = *reinterpret_cast<const la_bf8*>(&b3);
-      const int off = (ks * 2 + (lane >> 5)) * 128 + (lane & 31);
+      const int off = (ks * 2 + (lane >> 5)) * NC + (lane & 31);
 #pragma unroll
-      for (int t = 0; t < 4; t++) {
-        uint4 q1 = lzc[off + t * 32], q2 = lzc[512 + off + t * 32], q3 = lzc[1024 + off + t * 32];
+      for (int t = 0; t < NT; t++) {
+        uint4 q1 = lzc[off + t * 32], q2 = lzc[4 * NC + off + t * 32], q3 = lzc[8 * NC + off + t * 32];
         const la_bf8 a1 = *reinterpret_cast<la_bf8*>(&q1), a2 = *reinterpret_cast<la_bf8*>(&q2), a3 = *reinterpret_cast<la_bf8*>(&q3);
         // smallest terms first
         acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a3, f1, acc[t], 0, 0, 0);
-        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, f3, acc[t], 0, 0, 0);
         acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, f2, acc[t], 0, 0, 0);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, f3, acc[t], 0, 0, 0);
         acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, f1, acc[t], 0, 0, 0);
         acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, f2, acc[t], 0, 0, 0);
         acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, f1, acc[t], 0, 0, 0);
@@ -949,7 +953,7 @@ __global__ __launch_bounds__(256, 2) void la_product_kernel(const uint4* __restr
     if (++since == 1024 / LA_STG && stage + 1 < nstg) {       // the sums inside the matrix cores never span more than 1024 columns
       since = 0;
 #pragma unroll
-      for (int t = 0; t < 4; t++)
+      for (int t = 0; t < NT; t++)
 #pragma unroll
         for (int r = 0; r < 16; r++) { acc2[t][r] += acc[t][r]; acc[t][r] = 0.f; }
     }
@@ -958,24 +962,26 @@ __global__ __launch_bounds__(256, 2) void la_product_kernel(const uint4* __restr
   const int i_lane = i0 + wave * 32 + (lane & 31);
   if (i_lane < d1) {
 #pragma unroll
-    for (int t = 0; t < 4; t++)
+    for (int t = 0; t < NT; t++)
 #pragma unroll
       for (int r = 0; r < 16; r++) {
         const int sl = t * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        GbT[(int64_t)(sb * 128 + sl) * d1 + i_lane] = (double)acc[t][r] + (double)acc2[t][r];
+        GbT[(int64_t)(sb * NC + sl) * d1 + i_lane] = (double)acc[t][r] + (double)acc2[t][r];
       }
   }
-#undef OSSCAR_LA_GLOAD
 }
 
 // mode 0: half of the slots for kept rows, half for the others; 1: all for kept rows (removal-only loops); 2: none
 struct CandCounts { int n_k, n_c; };
 static CandCounts cand_counts(int mode) {
-  // Swap search: 64 + 64 rows.  They cover about 97 % of the next 64 swaps' pivots; the rest take a spare slot and a pass
-  // over Z0 each (0.155 ms on the 28672 x 7168 layer), which costs less than the second 128-row tile of the product
-  // (0.85 ms): measured 0.33 ms per flush in favour of the smaller set.  The removal-only loops take all LAZY_NC rows:
-  // their block pivots cannot fetch a missing product.
-  return CandCounts{mode == 2 ? 0 : (mode == 1 ? LAZY_NC : LAZY_NC / 4), mode == 0 ? LAZY_NC / 4 : 0};
+  // Swap search: a cycle of 64 swaps takes 64 pivots from each side, and which rows they will be is known at flush time only
+  // up to the changes the swaps themselves make to the scores.  With exactly 64 + 64 rows picked, 8 % of the leaving and 2 %
+  // of the entering pivots of the 28672 x 7168 layer were not among them, and each such swap pays a pass over Z0 for the
+  // missing products (0.155 ms: 70 ms over 5000 swaps).  With 88 + 72 it is 0.4 % and 0.2 % (80 + 80: 1.3 % and none;
+  // 96 + 64: 0.2 % and 2 %), for a product that is a quarter longer.  256 picked rows (two blocks of the product) cost more
+  // than they save.  The removal-only loops take all LAZY_NC rows: their block pivots cannot fetch a missing product.
+  static_assert((LAZY_NPICK_OUT + LAZY_NPICK_IN) % 32 == 0 && LAZY_NPICK_OUT + LAZY_NPICK_IN <= LAZY_NC, "blocks of 32 candidates");
+  return CandCounts{mode == 2 ? 0 : (mode == 1 ? LAZY_NC : LAZY_NPICK_OUT), mode == 0 ? LAZY_NPICK_IN : 0};
 }
 // the pick: reads the scores and the kept flags only (two sorts in one workgroup each: latency, no bandwidth)
 static hipError_t launch_candidate_pick(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode) {
@@ -993,11 +999,17 @@ static hipError_t launch_candidate_products(const TabDims& d, const TabPtrs& t, 
   const CandCounts cc = cand_counts(mode);
   const int n_k = cc.n_k, n_c = cc.n_c;
   if (mode == 2) return hipSuccess;
-  if (d.m % 8 == 0 && (n_k + n_c) % 128 == 0) {
-    const int nstg = (d.m + LA_STG - 1) / LA_STG, nsb = (n_k + n_c) / 128;
-    hipLaunchKernelGGL(la_pack_kernel, dim3(nstg, nsb), dim3(256), 0, s, L, t.Z, d.m, nstg, reinterpret_cast<uint4*>(L.ZcP));
-    hipLaunchKernelGGL(la_product_kernel, dim3((d.d1 + 127) / 128, nsb), dim3(256), 0, s, reinterpret_cast<const uint4*>(L.ZcP), t.Z,
-                       d.d1, d.m, nstg, L.GbT);
+  // one block of 32 NT candidates per workgroup: 128 (and multiples of it, block by block), 160 or 192
+  const int ncand = n_k + n_c;
+  const int nt = (ncand % 128 == 0) ? 4 : ((ncand == 160) ? 5 : ((ncand == 192) ? 6 : 0));
+  if (d.m % 8 == 0 && nt > 0) {
+    const int nstg = (d.m + LA_STG - 1) / LA_STG, nc = 32 * nt, nsb = ncand / nc;
+    hipLaunchKernelGGL(la_pack_kernel, dim3(nstg, nsb), dim3(256), 0, s, L, t.Z, d.m, nstg, nc, reinterpret_cast<uint4*>(L.ZcP));
+    const dim3 grid((d.d1 + 127) / 128, nsb);
+    const uint4* zcp = reinterpret_cast<const uint4*>(L.ZcP);
+    if (nt == 4) hipLaunchKernelGGL(la_product_kernel<4>, grid, dim3(256), 0, s, zcp, t.Z, d.d1, d.m, nstg, L.GbT);
+    else if (nt == 5) hipLaunchKernelGGL(la_product_kernel<5>, grid, dim3(256), 0, s, zcp, t.Z, d.d1, d.m, nstg, L.GbT);
+    else hipLaunchKernelGGL(la_product_kernel<6>, grid, dim3(256), 0, s, zcp, t.Z, d.d1, d.m, nstg, L.GbT);
     return hipGetLastError();
   }
   // other shapes: the general matrix-product kernel on the gathered rows
