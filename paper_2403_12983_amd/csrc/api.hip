@@ -133,6 +133,7 @@ struct osscar_ctx {
   hipEvent_t ev_a = nullptr, ev_b = nullptr;
   hipEvent_t ev_s[EV_SAMPLES][3];
   hipEvent_t ev_g[2 * EV_SAMPLES];   // pairs around the launches of the Gram kernel of the last chunk call
+  SearchCtrl* snap = nullptr;         // pinned host memory for reading the control block
   int ev_g_used = 0; int64_t ev_g_rows = 0;
   SideStream side;   // the flush of the delayed-update search overlaps two of its products
   bool ev_ok = false;
@@ -655,6 +656,7 @@ osscar_status osscar_create(osscar_ctx** out, const osscar_desc* desc, void* wor
   for (int i = 0; i < EV_SAMPLES && c->ev_ok; i++)
     for (int j = 0; j < 3; j++) c->ev_ok = c->ev_ok && (hipEventCreate(&c->ev_s[i][j]) == hipSuccess);
   for (int i = 0; i < 2 * EV_SAMPLES && c->ev_ok; i++) c->ev_ok = c->ev_ok && (hipEventCreate(&c->ev_g[i]) == hipSuccess);
+  c->ev_ok = c->ev_ok && hipHostMalloc(reinterpret_cast<void**>(&c->snap), sizeof(SearchCtrl), hipHostMallocDefault) == hipSuccess;
   c->ev_ok = c->ev_ok && hipStreamCreateWithFlags(&c->side.stream, hipStreamNonBlocking) == hipSuccess &&
              hipEventCreateWithFlags(&c->side.fork, hipEventDisableTiming) == hipSuccess &&
              hipEventCreateWithFlags(&c->side.join, hipEventDisableTiming) == hipSuccess &&
@@ -676,6 +678,7 @@ osscar_status osscar_destroy(osscar_ctx* c) {
   for (int i = 0; i < EV_SAMPLES; i++)
     for (int j = 0; j < 3; j++) if (c->ev_s[i][j]) hipEventDestroy(c->ev_s[i][j]);
   for (int i = 0; i < 2 * EV_SAMPLES; i++) if (c->ev_g[i]) hipEventDestroy(c->ev_g[i]);
+  if (c->snap) hipHostFree(c->snap);
   delete c;
   return OSSCAR_OK;
 }
@@ -900,8 +903,11 @@ osscar_status osscar_init_support(osscar_ctx* c, int mode, const int32_t* groups
 }
 
 static osscar_status read_ctrl(osscar_ctx* c, SearchCtrl* h) {
-  HIPCHK(c, hipMemcpyAsync(h, c->ctrl, sizeof *h, hipMemcpyDeviceToHost, c->stream));
+  // through pinned memory: the search waits on this copy once per 64 swaps with the device idle meanwhile
+  SearchCtrl* dst = c->snap ? c->snap : h;
+  HIPCHK(c, hipMemcpyAsync(dst, c->ctrl, sizeof *h, hipMemcpyDeviceToHost, c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
+  if (dst != h) *h = *dst;
   return OSSCAR_OK;
 }
 

@@ -1186,21 +1186,22 @@ hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs&
   const bool two = side && side->stream;
   hipStream_t sn = two ? side->stream : s;          // stream of the N0 update
   hipError_t err;
-  if (two) {
-    // The candidates of the next cycle, from the scores as the swaps left them (the refresh below changes them in the last
-    // digits only, and the choice of candidates decides what is computed ahead, not any result): two sorts of one
-    // workgroup each, on the second stream while this one prepares the operands.
-    if ((err = hipEventRecord(side->fork, s)) != hipSuccess) return err;
-    if ((err = hipStreamWaitEvent(sn, side->fork, 0)) != hipSuccess) return err;
-    if ((err = launch_candidate_pick(d, t, L, sn, mode)) != hipSuccess) return err;
-    if ((err = hipEventRecord(side->mid, sn)) != hipSuccess) return err;
-  }
+  if (two && (err = hipEventRecord(side->fork, s)) != hipSuccess) return err;
+  // this stream's first kernels go in before the second stream's commands: the device is idle until they arrive
   hipLaunchKernelGGL(lazy_convert_kernel, dim3(512), dim3(256), 0, s, L, d.m, t.ctrl);
   GemmArgs e{};                         // E = C0 M^-1
   e.M = d.d1; e.N = LAZY_TM; e.K = LAZY_TM; e.A = L.C0R; e.lda = LAZY_TM; e.B = L.Minv32; e.ldb = LAZY_TM;
   e.C = L.E; e.ldc = LAZY_TM; e.alpha = 1.0; e.beta = 0.0;
   err = launch_gemm_f64acc(e, s);
   if (err != hipSuccess) return err;
+  if (two) {
+    // The candidates of the next cycle, from the scores as the swaps left them (the refresh below changes them in the last
+    // digits only, and the choice of candidates decides what is computed ahead, not any result): two sorts of one
+    // workgroup each, on the second stream while this one prepares the operands.
+    if ((err = hipStreamWaitEvent(sn, side->fork, 0)) != hipSuccess) return err;
+    if ((err = launch_candidate_pick(d, t, L, sn, mode)) != hipSuccess) return err;
+    if ((err = hipEventRecord(side->mid, sn)) != hipSuccess) return err;
+  }
   // the three thin operands in matrix-core order (C0's pieces serve both updates)
   const int dpad = (d.d1 + 127) / 128 * 128, mpad = (d.m + 127) / 128 * 128;
   uint4* Epk = reinterpret_cast<uint4*>(L.Epk); uint4* Cpk = reinterpret_cast<uint4*>(L.Cpk); uint4* Zpk = reinterpret_cast<uint4*>(L.Zpk);
