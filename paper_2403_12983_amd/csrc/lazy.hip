@@ -121,6 +121,21 @@ __device__ __forceinline__ void wave_merge(double& mn1, double& mn2, int& imn, d
   dpp_merge_step<0x143, 0xc>(mn1, mn2, imn, mx1, mx2, imx);
 }
 
+// The same moves on (value, index) alone: lane 63 ends with the smallest value (lowest index on ties) and the largest.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ void dpp_best_step(double& mn, int& imn, double& mx, int& imx) {
+  const double b = dpp_get_or<CTRL, ROW_MASK>(mn, INFINITY), c = dpp_get_or<CTRL, ROW_MASK>(mx, -INFINITY);
+  const int ib = dpp_get_or<CTRL, ROW_MASK>(imn, -1), ic = dpp_get_or<CTRL, ROW_MASK>(imx, -1);
+  const bool tb = (ib >= 0) && (imn < 0 || b < mn || (b == mn && ib < imn));
+  const bool tc = (ic >= 0) && (imx < 0 || c > mx || (c == mx && ic < imx));
+  mn = tb ? b : mn; imn = tb ? ib : imn; mx = tc ? c : mx; imx = tc ? ic : imx;
+}
+// ... and on plain values: lane 63 ends with the minimum of lo and the maximum of hi over the wave
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ void dpp_minmax_step(double& lo, double& hi) {
+  lo = fmin(lo, dpp_get_or<CTRL, ROW_MASK>(lo, INFINITY)); hi = fmax(hi, dpp_get_or<CTRL, ROW_MASK>(hi, -INFINITY));
+}
+
 // per-block record of the scores of rows [32 b, 32 b + 32): used after a flush; the update kernel writes the same records
 __global__ __launch_bounds__(64) void lazy_partials_kernel(LazyPtrs L, int p, const int32_t* __restrict__ kept,
                                                             const double* __restrict__ score) {
@@ -538,8 +553,8 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
                                                            double* __restrict__ rho, double* __restrict__ diag,
                                                            double* __restrict__ score, int single) {
   __shared__ double sa[LAZY_TM], sb[LAZY_TM];
-  __shared__ double w_mn1[4], w_mn2[4], w_mx1[4], w_mx2[4];
-  __shared__ int w_imn[4], w_imx[4];
+  __shared__ double s_mn[ROWS_PER_BLOCK], s_mx[ROWS_PER_BLOCK];
+  __shared__ int s_imn[ROWS_PER_BLOCK], s_imx[ROWS_PER_BLOCK];
   if (idle(ctrl)) return;
   const int tid = threadIdx.x, g = ctrl->g_out, j = ctrl->g_in, tau = ctrl->tau;
   const double Dg = L.ls[LS_DG], M1 = L.ls[LS_M1], Dj = L.ls[LS_DJ];
@@ -617,16 +632,36 @@ __global__ __launch_bounds__(256) void lazy_update_kernel(LazyPtrs L, const floa
         if (kp) { mn1 = sc; imn = row; } else { mx1 = sc; imx = row; }
       }
     }
-    // per-block record (the row leaders are lanes 0, 8, 16, ... of each wave)
-    double mn2 = INFINITY, mx2 = -INFINITY;
-    wave_merge(mn1, mn2, imn, mx1, mx2, imx);          // lanes that lead no row hold the neutral record
-    if ((tid & 63) == 63) { const int w = tid >> 6; w_mn1[w] = mn1; w_mn2[w] = mn2; w_imn[w] = imn; w_mx1[w] = mx1; w_mx2[w] = mx2; w_imx[w] = imx; }
+    // Per-block record.  The 32 row leaders (lanes 0, 8, 16, ... of each wave) hand their (cost, index) and (gain, index) to
+    // the first wave through shared memory; it picks the best of each side by data-parallel moves on (value, index) alone,
+    // then the second best as a plain minimum / maximum over the rows that did not win: half the instructions of merging
+    // full (best, second, index) records at every step, on what is the longest path through this kernel.
+    if ((tid & 7) == 0) { const int e = tid >> 3; s_mn[e] = mn1; s_imn[e] = imn; s_mx[e] = mx1; s_imx[e] = imx; }
     __syncthreads();
-    if (tid == 0) {
-      mn1 = w_mn1[0]; mn2 = w_mn2[0]; imn = w_imn[0]; mx1 = w_mx1[0]; mx2 = w_mx2[0]; imx = w_imx[0];
-      for (int w = 1; w < 4; w++) { merge_min(mn1, mn2, imn, w_mn1[w], w_mn2[w], w_imn[w]); merge_max(mx1, mx2, imx, w_mx1[w], w_mx2[w], w_imx[w]); }
-      SelRec rec; rec.mn1 = mn1; rec.mn2 = mn2; rec.mx1 = mx1; rec.mx2 = mx2; rec.imn = imn; rec.imx = imx;
-      L.sel[b] = rec;
+    if (tid < 64) {
+      const bool have = tid < ROWS_PER_BLOCK;
+      double vmn = have ? s_mn[tid & 31] : INFINITY, vmx = have ? s_mx[tid & 31] : -INFINITY;
+      int vin = have ? s_imn[tid & 31] : -1, vix = have ? s_imx[tid & 31] : -1;
+      const double own_mn = vmn, own_mx = vmx;
+      const int own_in = vin, own_ix = vix;
+      dpp_best_step<0xb1, 0xf>(vmn, vin, vmx, vix);
+      dpp_best_step<0x4e, 0xf>(vmn, vin, vmx, vix);
+      dpp_best_step<0x124, 0xf>(vmn, vin, vmx, vix);
+      dpp_best_step<0x128, 0xf>(vmn, vin, vmx, vix);
+      dpp_best_step<0x142, 0xa>(vmn, vin, vmx, vix);
+      dpp_best_step<0x143, 0xc>(vmn, vin, vmx, vix);
+      const int win_n = __builtin_amdgcn_readlane(vin, 63), win_x = __builtin_amdgcn_readlane(vix, 63);
+      double lo = (own_in >= 0 && own_in != win_n) ? own_mn : INFINITY, hi = (own_ix >= 0 && own_ix != win_x) ? own_mx : -INFINITY;
+      dpp_minmax_step<0xb1, 0xf>(lo, hi);
+      dpp_minmax_step<0x4e, 0xf>(lo, hi);
+      dpp_minmax_step<0x124, 0xf>(lo, hi);
+      dpp_minmax_step<0x128, 0xf>(lo, hi);
+      dpp_minmax_step<0x142, 0xa>(lo, hi);
+      dpp_minmax_step<0x143, 0xc>(lo, hi);
+      if (tid == 63) {
+        SelRec rec; rec.mn1 = vmn; rec.mn2 = lo; rec.mx1 = vmx; rec.mx2 = hi; rec.imn = vin; rec.imx = vix;
+        L.sel[b] = rec;
+      }
     }
   } else if (b < row_blocks + col_blocks) {
     const int cb = b - row_blocks, slice = tid >> 6, col = cb * COLS_PER_BLOCK + (tid & 63);
