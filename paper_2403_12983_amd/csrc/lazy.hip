@@ -13,10 +13,10 @@
 // w without a pass over Z0: y1, y2 are combinations of the current rows g, j of Z, and these of base rows:
 //     Z0 z_g^T = Z0 Z0[g, :]^T - sum_r x_g[r] Z0 Z0[T_r, :]^T,     x_g = M^-1 C0[g, :]^T,
 // so it is enough to know the products of Z0 with the base rows of g, j and of the pending pivots.  Which rows
-// will be pivots before the next flush is predictable (the LAZY_NC/2 cheapest removals and largest gains at
-// flush time cover them), so right after each flush one matrix product Zc Z0^T computes those products for
-// LAZY_NC candidate rows (GbT); a pivot outside the candidates costs one read-only pass over Z0 for its column
-// (kept in one of LAZY_NS spare slots).  Every
+// will be pivots before the next flush is predictable (the LAZY_NPICK_OUT cheapest removals and LAZY_NPICK_IN largest
+// gains at flush time cover all but a few per thousand of them), so right after each flush one matrix product Zc Z0^T
+// computes those products for these candidate rows (GbT); a pivot outside the candidates costs one read-only pass over
+// Z0 for its column (kept in one of LAZY_NS spare slots).  Every
 // LAZY_TM/2 iterations the pending rank-tau correction is applied to N0 and Z0 by matrix products on the
 // matrix cores.  The sequence of swaps is exactly that of the eager search (Proposition 4.1, Cases 1-3).
 //
