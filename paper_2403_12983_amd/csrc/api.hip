@@ -199,6 +199,7 @@ Layout carve_all(const osscar_desc& ds, void* base, osscar_ctx* c) {
     L.part = cv.take<double>(((m + 63) / 64) * 5); L.ls = cv.take<double>(16);
     L.sel = cv.take<SelRec>((d1 + 31) / 32);
     L.GbT = cv.take<double>((int64_t)(LAZY_NC + LAZY_NS) * d1); L.Zc = cv.take<float>((int64_t)LAZY_NC * m);
+    L.rowsq = cv.take<double>((int64_t)2 * ((m + 127) / 128) * d1);
     L.ZcP = cv.take<char>((int64_t)LAZY_NC * ((m + 31) / 32 * 32) * 6);
     L.Epk = cv.take<char>((int64_t)768 * ((d1 + 127) / 128 * 128)); L.Cpk = cv.take<char>((int64_t)768 * ((d1 + 127) / 128 * 128));
     L.Zpk = cv.take<char>((int64_t)768 * ((m + 127) / 128 * 128));

@@ -214,6 +214,7 @@ struct LazyPtrs {
   SelRec* sel;      // ceil(d1/32) per-block score records
   // products of Z0 with the rows of Z0 that are likely to become pivots before the next flush
   double* GbT;      // (LAZY_NC + LAZY_NS) x d1: row s = Z0 Z0[cand[s], :]^T
+  double* rowsq;    // 2 ceil(m / 128) x d1: sums of squares of every row's 64-column stretches, left by Z0's update in the flush
   float* Zc;        // LAZY_NC x m: the gathered rows (shapes that take the general matrix-product kernel)
   // flush: E, C0 and ZT cut into three bf16 pieces in matrix-core operand order (768 bytes per padded row / column), and the
   // tile schedules of the two updates (the Gram kernel's: lower triangle of d1 x d1, all of d1 x m), uploaded at create

@@ -1109,9 +1109,27 @@ __global__ __launch_bounds__(256) void rk_pack_cols_kernel(const float* __restri
   out[(int64_t)(32 + kg) * cpad + c] = p3;
 }
 
+// Sums of squares of the new values of a wave's 32 rows x 64 columns, one number per row, into out[row] (rows_left of them
+// exist).  v0, v1: the two 32 x 32 tiles side by side in the matrix cores' result layout (register r = rr*4 + r3 holds row
+// rr*8 + (lane/32)*4 + r3, column lane%32).  Squares and sums in float64; the 32 lanes of a half wave are added by
+// data-parallel moves in a fixed order, and lanes 31 and 63 write.
+__device__ __forceinline__ void rk_row_squares(const float* v0, const float* v1, double* __restrict__ out, int lane, int rows_left) {
+#pragma unroll
+  for (int r = 0; r < 16; r++) {
+    double q = (double)v0[r] * (double)v0[r] + (double)v1[r] * (double)v1[r];
+    q += dpp_get<0xb1, 0xf>(q);        // quad_perm [1, 0, 3, 2]
+    q += dpp_get<0x4e, 0xf>(q);        // quad_perm [2, 3, 0, 1]
+    q += dpp_get<0x124, 0xf>(q);       // row_ror:4
+    q += dpp_get<0x128, 0xf>(q);       // row_ror:8
+    q += dpp_get<0x142, 0xa>(q);       // row_bcast:15 into rows 1 and 3: lanes 16-31 and 48-63 hold their half wave's sum
+    const int row = (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+    if ((lane & 31) == 31 && row < rows_left) out[row] = q;
+  }
+}
+
 __global__ __launch_bounds__(256, 2) void rk_update_kernel(const uint4* __restrict__ Apk, int apad, const uint4* __restrict__ Bpk, int bpad,
                                                             float* __restrict__ C, int64_t ldc, int M, int N,
-                                                            const int2* __restrict__ tiles) {
+                                                            const int2* __restrict__ tiles, double* __restrict__ rowsq) {
   __shared__ uint4 la[3 * 4 * 128], lb[3 * 4 * 128];          // 24 KB each: [piece][kg of this quarter][row]
   const int2 tile = tiles[blockIdx.x];
   if (tile.x < 0) return;
@@ -1191,12 +1209,15 @@ __global__ __launch_bounds__(256, 2) void rk_update_kernel(const uint4* __restri
 #pragma unroll
       for (int r = 0; r < 16; r++) {
         float* pr = ca + (int64_t)((r >> 2) * 8 + (r & 3)) * ldc;
-        pr[0] = cv[0][r] - acc[a][0][r]; pr[32] = cv[1][r] - acc[a][1][r];
+        cv[0][r] -= acc[a][0][r]; cv[1][r] -= acc[a][1][r];
+        pr[0] = cv[0][r]; pr[32] = cv[1][r];
       }
+      if (rowsq) rk_row_squares(cv[0], cv[1], rowsq + (int64_t)(tile.y * 2 + wn) * M + i0 + wm * 64 + a * 32, lane, M - (i0 + wm * 64 + a * 32));
     }
   } else {
 #pragma unroll
-    for (int a = 0; a < 2; a++)
+    for (int a = 0; a < 2; a++) {
+      float nv[2][16];
 #pragma unroll
       for (int b = 0; b < 2; b++) {
         const int col = j0 + wn * 64 + b * 32 + (lane & 31);
@@ -1209,10 +1230,50 @@ __global__ __launch_bounds__(256, 2) void rk_update_kernel(const uint4* __restri
 #pragma unroll
         for (int r = 0; r < 16; r++) {
           const int row = i0 + wm * 64 + a * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-          if (row < M && col < N) C[(int64_t)row * ldc + col] = cv[r] - acc[a][b][r];
+          const bool in = row < M && col < N;
+          nv[b][r] = in ? cv[r] - acc[a][b][r] : 0.f;
+          if (in) C[(int64_t)row * ldc + col] = nv[b][r];
         }
       }
+      if (rowsq) rk_row_squares(nv[0], nv[1], rowsq + (int64_t)(tile.y * 2 + wn) * M + i0 + wm * 64 + a * 32, lane, M - (i0 + wm * 64 + a * 32));
+    }
   }
+}
+
+// First half of the score refresh after a flush: gram[h] = |Z0[h, :]|^2 from the stretch sums that Z0's update left (added in
+// a fixed order), dblk[h] = N0[h][h].  The pending pivots' rows were rewritten after the update (the fix): the trailing
+// LAZY_TM workgroups take one of them each and sum its squares from Z0 itself (wave sums, then the four waves in order).
+__global__ __launch_bounds__(256) void norms_from_stretches_kernel(LazyPtrs L, int d1, int m, int nstretch, int row_blocks,
+                                                                    const float* __restrict__ N0, const float* __restrict__ Z0,
+                                                                    double* __restrict__ gram, double* __restrict__ dblk,
+                                                                    const SearchCtrl* __restrict__ ctrl) {
+  if ((int)blockIdx.x < row_blocks) {
+    const int h = blockIdx.x * 256 + threadIdx.x;
+    if (h >= d1) return;
+    dblk[h] = (double)N0[(int64_t)h * d1 + h];
+    if (L.pos[h] >= 0) return;                     // a pending pivot: its row is summed below
+    double v = 0;
+    for (int p0 = 0; p0 < nstretch; p0 += 8) {     // eight loads in flight
+      double q[8];
+#pragma unroll
+      for (int u = 0; u < 8; u++) q[u] = (p0 + u < nstretch) ? L.rowsq[(int64_t)(p0 + u) * d1 + h] : 0.0;
+#pragma unroll
+      for (int u = 0; u < 8; u++) v += q[u];
+    }
+    gram[h] = v;
+    return;
+  }
+  __shared__ double red[4];
+  const int sidx = blockIdx.x - row_blocks;
+  if (sidx >= tau_all(ctrl)) return;
+  const int h = L.Tidx[sidx];
+  const float* z = Z0 + (int64_t)h * m;
+  double v = 0;
+  for (int c = threadIdx.x; c < m; c += 256) v += (double)z[c] * (double)z[c];
+  v = wsum(v);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  if (threadIdx.x == 0) gram[h] = red[0] + red[1] + red[2] + red[3];
 }
 
 hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode,
@@ -1249,18 +1310,21 @@ hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs&
   }
   // N0 -= E C0^T on the lower block triangle (pivot rows and columns are rewritten below)
   hipLaunchKernelGGL(rk_update_kernel, dim3((unsigned)L.n_tiles_sym), dim3(256), 0, sn, Epk, dpad, Cpk, dpad, t.N, (int64_t)d.d1, d.d1, d.d1,
-                     L.tiles_sym);
+                     L.tiles_sym, (double*)nullptr);
   hipLaunchKernelGGL(lazy_fix_kernel, dim3(rb, LAZY_TM / FIX_SPB), dim3(256), 0, sn, L, t.N, d.d1, t.ctrl);
   // Z0 -= C0 ZT
+  // (with two streams the kernel also leaves the sums of squares of every row's 64-column stretches: the row norms of the
+  // score refresh then come from these 25 MB instead of another pass over Z0)
   hipLaunchKernelGGL(rk_update_kernel, dim3((unsigned)L.n_tiles_rect), dim3(256), 0, s, Cpk, dpad, Zpk, mpad, t.Z, (int64_t)d.m, d.d1, d.m,
-                     L.tiles_rect);
+                     L.tiles_rect, two ? L.rowsq : (double*)nullptr);
   hipLaunchKernelGGL(lazy_fix_z_kernel, dim3(mb, LAZY_TM / FIX_SPB), dim3(256), 0, s, L, t.Z, d.m, t.ctrl);
   if (two) {
-    // The second stream goes on, once both matrices are final, with the first half of the score refresh (row norms of Z0,
-    // diagonal of N0); this one with the products of the picked rows with the new Z0.
+    // The second stream goes on, once both matrices are final, with the first half of the score refresh (row norms from the
+    // stretch sums, diagonal of N0); this one with the products of the picked rows with the new Z0.
     if ((err = hipEventRecord(side->fork, s)) != hipSuccess) return err;
     if ((err = hipStreamWaitEvent(sn, side->fork, 0)) != hipSuccess) return err;
-    if ((err = launch_refresh_blocks(d, t, sn)) != hipSuccess) return err;
+    hipLaunchKernelGGL(norms_from_stretches_kernel, dim3((d.d1 + 255) / 256 + LAZY_TM), dim3(256), 0, sn, L, d.d1, d.m, 2 * ((d.m + 127) / 128),
+                       (d.d1 + 255) / 256, t.N, t.Z, t.gram, t.dblk, t.ctrl);
     if ((err = hipEventRecord(side->join, sn)) != hipSuccess) return err;
     if ((err = hipStreamWaitEvent(s, side->mid, 0)) != hipSuccess) return err;
     err = launch_candidate_products(d, t, L, s, mode);
