@@ -927,6 +927,10 @@ __global__ __launch_bounds__(256, 2) void la_product_kernel(const uint4* __restr
   __shared__ __attribute__((aligned(16))) float lz0[128 * LA_ZLD];   // 18 KB
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, sb = blockIdx.y;
   const int i0 = blockIdx.x * 128;
+  // blockIdx.z: which part of the contraction (gridDim.z = 1, or 2 with the sums joined by atomic additions to a zeroed GbT:
+  // two terms added to zero give the same bits in either order)
+  const int st_begin = (int)blockIdx.z * ((nstg + (int)gridDim.z - 1) / (int)gridDim.z);
+  const int st_end = min(nstg, st_begin + (nstg + (int)gridDim.z - 1) / (int)gridDim.z);
   const uint4* src = ZcP + (int64_t)sb * nstg * PK + tid;
   // global -> shared assignment of the Z0 tile: thread t takes 4 columns (t % 8) * 4 of rows t / 8 + 32 j, j < 4
   const int lr = tid >> 3, lk = (tid & 7) * 4;
@@ -950,10 +954,11 @@ __global__ __launch_bounds__(256, 2) void la_product_kernel(const uint4* __restr
     zt2 = in_ ? *reinterpret_cast<const float4*>(zsrc2 + stage_ * LA_STG) : z_;
     zt3 = in_ ? *reinterpret_cast<const float4*>(zsrc3 + stage_ * LA_STG) : z_;
   };
-  gload(0);
+  if (st_begin >= st_end) return;
+  gload(st_begin);
   int since = 0;
   const float* myrow = lz0 + (wave * 32 + (lane & 31)) * LA_ZLD + (lane >> 5) * 8;
-  for (int stage = 0; stage < nstg; stage++) {
+  for (int stage = st_begin; stage < st_end; stage++) {
     __syncthreads();                                           // the previous stage has been read by every wave
 #pragma unroll
     for (int i = 0; i < NLD; i++)
@@ -963,7 +968,7 @@ __global__ __launch_bounds__(256, 2) void la_product_kernel(const uint4* __restr
     *reinterpret_cast<float4*>(lz0 + (lr + 64) * LA_ZLD + lk) = zt2;
     *reinterpret_cast<float4*>(lz0 + (lr + 96) * LA_ZLD + lk) = zt3;
     __syncthreads();
-    if (stage + 1 < nstg) gload(stage + 1);
+    if (stage + 1 < st_end) gload(stage + 1);
 #pragma unroll
     for (int ks = 0; ks < LA_STG / 16; ks++) {
       const float4 v0 = *reinterpret_cast<const float4*>(myrow + ks * 16), v1 = *reinterpret_cast<const float4*>(myrow + ks * 16 + 4);
@@ -985,7 +990,7 @@ __global__ __launch_bounds__(256, 2) void la_product_kernel(const uint4* __restr
         acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, f1, acc[t], 0, 0, 0);
       }
     }
-    if (++since == 1024 / LA_STG && stage + 1 < nstg) {       // the sums inside the matrix cores never span more than 1024 columns
+    if (++since == 1024 / LA_STG && stage + 1 < st_end) {     // the sums inside the matrix cores never span more than 1024 columns
       since = 0;
 #pragma unroll
       for (int t = 0; t < NT; t++)
@@ -1001,7 +1006,9 @@ __global__ __launch_bounds__(256, 2) void la_product_kernel(const uint4* __restr
 #pragma unroll
       for (int r = 0; r < 16; r++) {
         const int sl = t * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        GbT[(int64_t)(sb * NC + sl) * d1 + i_lane] = (double)acc[t][r] + (double)acc2[t][r];
+        double* dst = GbT + (int64_t)(sb * NC + sl) * d1 + i_lane;
+        const double v = (double)acc[t][r] + (double)acc2[t][r];
+        if (gridDim.z == 1) *dst = v; else unsafeAtomicAdd(dst, v);
       }
   }
 }
@@ -1040,7 +1047,14 @@ static hipError_t launch_candidate_products(const TabDims& d, const TabPtrs& t, 
   if (d.m % 8 == 0 && nt > 0) {
     const int nstg = (d.m + LA_STG - 1) / LA_STG, nc = 32 * nt, nsb = ncand / nc;
     hipLaunchKernelGGL(la_pack_kernel, dim3(nstg, nsb), dim3(256), 0, s, L, t.Z, d.m, nstg, nc, reinterpret_cast<uint4*>(L.ZcP));
-    const dim3 grid((d.d1 + 127) / 128, nsb);
+    // one block of candidates: 224 workgroups for 28672 rows would leave compute units empty and each of them with one
+    // latency chain over all of m; the contraction is then cut in two
+    const int ksplit = (((d.d1 + 127) / 128) * nsb < 400 && nstg >= 64) ? 2 : 1;
+    if (ksplit > 1) {
+      const hipError_t ez = hipMemsetAsync(L.GbT, 0, (size_t)ncand * d.d1 * sizeof(double), s);
+      if (ez != hipSuccess) return ez;
+    }
+    const dim3 grid((d.d1 + 127) / 128, nsb, ksplit);
     const uint4* zcp = reinterpret_cast<const uint4*>(L.ZcP);
     if (nt == 4) hipLaunchKernelGGL(la_product_kernel<4>, grid, dim3(256), 0, s, zcp, t.Z, d.d1, d.m, nstg, L.GbT);
     else if (nt == 5) hipLaunchKernelGGL(la_product_kernel<5>, grid, dim3(256), 0, s, zcp, t.Z, d.d1, d.m, nstg, L.GbT);
