@@ -1254,6 +1254,52 @@ __global__ __launch_bounds__(256, 2) void rk_update_kernel(const uint4* __restri
   }
 }
 
+// E = C0 M^-1 of the flush (d1 x 128 times 128 x 128, float32 operands, float64 sums on v_mfma_f64_16x16x4_f64, float32
+// result).  It stands at the head of the flush's longest chain, so what counts is its latency: the general matrix-product
+// kernel runs it as 224 workgroups of one 128 x 128 tile each (0.085 ms); here a workgroup takes 64 rows with all of M^-1
+// and its rows of C0 in shared memory (448 workgroups, no barrier inside the contraction).  M^-1 is symmetric bit for bit,
+// so its rows serve as the columns the product needs.  Wave w: rows 16 w .. 16 w + 15, eight 16 x 16 tiles.
+typedef double te_d4 __attribute__((ext_vector_type(4)));
+constexpr int TE_LD = LAZY_TM + 4;       // row stride in shared memory (floats): a quarter wave's 16 rows x 4 k fall on 32 banks twice
+__global__ __launch_bounds__(256) void thin_e_kernel(const float* __restrict__ C0R, const float* __restrict__ M32, float* __restrict__ E,
+                                                      int d1) {
+  static_assert(LAZY_TM == 128, "eight column tiles, thirty-two steps of four");
+  extern __shared__ float te_lds[];      // [128 rows of M^-1 | 64 rows of C0][TE_LD]
+  float* Ms = te_lds;
+  float* As = te_lds + LAZY_TM * TE_LD;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, i0 = blockIdx.x * 64;
+  for (int idx = tid; idx < LAZY_TM * (LAZY_TM / 4); idx += 256) {
+    const int r = idx >> 5, c4 = (idx & 31) * 4;
+    *reinterpret_cast<float4*>(Ms + r * TE_LD + c4) = *reinterpret_cast<const float4*>(M32 + r * LAZY_TM + c4);
+  }
+  for (int idx = tid; idx < 64 * (LAZY_TM / 4); idx += 256) {
+    const int r = idx >> 5, c4 = (idx & 31) * 4;
+    const float4 v = (i0 + r < d1) ? *reinterpret_cast<const float4*>(C0R + (int64_t)(i0 + r) * LAZY_TM + c4) : float4{0.f, 0.f, 0.f, 0.f};
+    *reinterpret_cast<float4*>(As + r * TE_LD + c4) = v;
+  }
+  __syncthreads();
+  te_d4 acc[8];
+#pragma unroll
+  for (int ct = 0; ct < 8; ct++) acc[ct] = te_d4{0.0, 0.0, 0.0, 0.0};
+  const float* arow = As + (wave * 16 + (lane & 15)) * TE_LD + (lane >> 4);
+  const float* mrow = Ms + (lane & 15) * TE_LD + (lane >> 4);
+#pragma unroll 4
+  for (int k0 = 0; k0 < LAZY_TM; k0 += 4) {
+    const double a = (double)arow[k0];
+#pragma unroll
+    for (int ct = 0; ct < 8; ct++) acc[ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, (double)mrow[ct * 16 * TE_LD + k0], acc[ct], 0, 0, 0);
+  }
+  // lane holds D[4 r + lane/16][lane%16] of each 16 x 16 tile
+#pragma unroll
+  for (int r = 0; r < 4; r++) {
+    const int row = i0 + wave * 16 + 4 * r + (lane >> 4);
+    if (row < d1) {
+#pragma unroll
+      for (int ct = 0; ct < 8; ct++) E[(int64_t)row * LAZY_TM + ct * 16 + (lane & 15)] = (float)acc[ct][r];
+    }
+  }
+}
+
 // First half of the score refresh after a flush: gram[h] = |Z0[h, :]|^2 from the stretch sums that Z0's update left (added in
 // a fixed order), dblk[h] = N0[h][h].  The pending pivots' rows were rewritten after the update (the fix): the trailing
 // LAZY_TM workgroups take one of them each and sum its squares from Z0 itself (wave sums, then the four waves in order).
@@ -1299,11 +1345,15 @@ hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs&
   if (two && (err = hipEventRecord(side->fork, s)) != hipSuccess) return err;
   // this stream's first kernels go in before the second stream's commands: the device is idle until they arrive
   hipLaunchKernelGGL(lazy_convert_kernel, dim3(512), dim3(256), 0, s, L, d.m, t.ctrl);
-  GemmArgs e{};                         // E = C0 M^-1
-  e.M = d.d1; e.N = LAZY_TM; e.K = LAZY_TM; e.A = L.C0R; e.lda = LAZY_TM; e.B = L.Minv32; e.ldb = LAZY_TM;
-  e.C = L.E; e.ldc = LAZY_TM; e.alpha = 1.0; e.beta = 0.0;
-  err = launch_gemm_f64acc(e, s);
-  if (err != hipSuccess) return err;
+  {                                     // E = C0 M^-1 (entered in the log of matrix products like the general kernel's launches)
+    const size_t shmem = (size_t)(LAZY_TM + 64) * TE_LD * sizeof(float);
+    if ((err = hipFuncSetAttribute(reinterpret_cast<const void*>(thin_e_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem)) != hipSuccess)
+      return err;
+    int log_slot = -1;
+    gemm_log_open(d.d1, LAZY_TM, LAZY_TM, 0, s, &log_slot);
+    hipLaunchKernelGGL(thin_e_kernel, dim3((d.d1 + 63) / 64), dim3(256), shmem, s, L.C0R, L.Minv32, L.E, d.d1);
+    gemm_log_close(log_slot, s);
+  }
   if (two) {
     // The candidates of the next cycle, from the scores as the swaps left them (the refresh below changes them in the last
     // digits only, and the choice of candidates decides what is computed ahead, not any result): two sorts of one
