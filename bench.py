@@ -24,8 +24,8 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 # HBM-side bytes per launch on cfg5 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a 1 GiB copy
 # (profiles/gemm_f64acc_cfg5_pmc.md: mean over the launches of one layer; profiles/gram_packed_cfg5_pmc.md: one chunk)
-GEMM64_TRAFFIC_CFG5 = 3.02e7
-GRAM_TRAFFIC_CFG5 = 91.7e9
+GEMM64_TRAFFIC_CFG5 = 2.99e7
+GRAM_TRAFFIC_CFG5 = 93.4e9
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -296,8 +296,8 @@ def main():
                      "ms_per_launch": gram_launch_ms if gram_launch_ms > 0 else None},
         # The float64-accumulating product (the residuals that refine the inverse, the weights and the back-solve; small
         # products): mean algorithmic flops per launch (2 M N K) / mean launch duration over every launch of the timed steps.
-        "roofline_gemm_f64acc": {"kernel": "gemm_f64acc_kernel (float32 operands, float64 MFMA accumulation): residuals; "
-                                           f"{n64:g} launches per layer",
+        "roofline_gemm_f64acc": {"kernel": "float32 operands, float64 MFMA accumulation: gemm_f64acc_kernel (residuals, small shapes) and "
+                                           f"thin_e_kernel (E = C0 M^-1 of every flush); {n64:g} launches per layer",
                                  "bound": "mfma", "achieved": w64, "peak": 78.6, "unit": "TFLOP/s", "frac": (w64 / 78.6) if w64 else None,
                                  "traffic": GEMM64_TRAFFIC_CFG5 if (a.config == "cfg5" and a.rows is None) else None,
                                  "launches_per_layer": n64, "ms_per_layer": ms64,
