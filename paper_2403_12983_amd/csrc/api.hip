@@ -660,8 +660,7 @@ osscar_status osscar_create(osscar_ctx** out, const osscar_desc* desc, void* wor
   c->ev_ok = c->ev_ok && hipHostMalloc(reinterpret_cast<void**>(&c->snap), sizeof(SearchCtrl), hipHostMallocDefault) == hipSuccess;
   c->ev_ok = c->ev_ok && hipStreamCreateWithFlags(&c->side.stream, hipStreamNonBlocking) == hipSuccess &&
              hipEventCreateWithFlags(&c->side.fork, hipEventDisableTiming) == hipSuccess &&
-             hipEventCreateWithFlags(&c->side.join, hipEventDisableTiming) == hipSuccess &&
-             hipEventCreateWithFlags(&c->side.mid, hipEventDisableTiming) == hipSuccess;
+             hipEventCreateWithFlags(&c->side.join, hipEventDisableTiming) == hipSuccess;
   if (!c->ev_ok) { osscar_destroy(c); return OSSCAR_EHIP; }
   *out = c;
   return OSSCAR_OK;
@@ -673,7 +672,6 @@ osscar_status osscar_destroy(osscar_ctx* c) {
   if (c->side.stream) { hipStreamSynchronize(c->side.stream); hipStreamDestroy(c->side.stream); }
   if (c->side.fork) hipEventDestroy(c->side.fork);
   if (c->side.join) hipEventDestroy(c->side.join);
-  if (c->side.mid) hipEventDestroy(c->side.mid);
   if (c->ev_a) hipEventDestroy(c->ev_a);
   if (c->ev_b) hipEventDestroy(c->ev_b);
   for (int i = 0; i < EV_SAMPLES; i++)

@@ -247,7 +247,7 @@ hipError_t launch_lazy_iteration(const TabDims& d, const TabPtrs& t, const LazyP
 hipError_t launch_lazy_block_remove(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, int take, const int32_t* pick,
                                     hipStream_t s);
 
-struct SideStream { hipStream_t stream = nullptr; hipEvent_t fork = nullptr, join = nullptr, mid = nullptr; };
+struct SideStream { hipStream_t stream = nullptr; hipEvent_t fork = nullptr, join = nullptr; };
 // side == nullptr (or no stream in it): everything in order on s
 hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs& L, hipStream_t s, int mode = 0,
                              const SideStream* side = nullptr);

@@ -1342,8 +1342,6 @@ hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs&
   const bool two = side && side->stream;
   hipStream_t sn = two ? side->stream : s;          // stream of the N0 update
   hipError_t err;
-  if (two && (err = hipEventRecord(side->fork, s)) != hipSuccess) return err;
-  // this stream's first kernels go in before the second stream's commands: the device is idle until they arrive
   hipLaunchKernelGGL(lazy_convert_kernel, dim3(512), dim3(256), 0, s, L, d.m, t.ctrl);
   {                                     // E = C0 M^-1 (entered in the log of matrix products like the general kernel's launches)
     const size_t shmem = (size_t)(LAZY_TM + 64) * TE_LD * sizeof(float);
@@ -1353,14 +1351,6 @@ hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs&
     gemm_log_open(d.d1, LAZY_TM, LAZY_TM, 0, s, &log_slot);
     hipLaunchKernelGGL(thin_e_kernel, dim3((d.d1 + 63) / 64), dim3(256), shmem, s, L.C0R, L.Minv32, L.E, d.d1);
     gemm_log_close(log_slot, s);
-  }
-  if (two) {
-    // The candidates of the next cycle, from the scores as the swaps left them (the refresh below changes them in the last
-    // digits only, and the choice of candidates decides what is computed ahead, not any result): two sorts of one
-    // workgroup each, on the second stream while this one prepares the operands.
-    if ((err = hipStreamWaitEvent(sn, side->fork, 0)) != hipSuccess) return err;
-    if ((err = launch_candidate_pick(d, t, L, sn, mode)) != hipSuccess) return err;
-    if ((err = hipEventRecord(side->mid, sn)) != hipSuccess) return err;
   }
   // the three thin operands in matrix-core order (C0's pieces serve both updates)
   const int dpad = (d.d1 + 127) / 128 * 128, mpad = (d.m + 127) / 128 * 128;
@@ -1390,8 +1380,10 @@ hipError_t launch_lazy_flush(const TabDims& d, const TabPtrs& t, const LazyPtrs&
     hipLaunchKernelGGL(norms_from_stretches_kernel, dim3((d.d1 + 255) / 256 + LAZY_TM), dim3(256), 0, sn, L, d.d1, d.m, 2 * ((d.m + 127) / 128),
                        (d.d1 + 255) / 256, t.N, t.Z, t.gram, t.dblk, t.ctrl);
     if ((err = hipEventRecord(side->join, sn)) != hipSuccess) return err;
-    if ((err = hipStreamWaitEvent(s, side->mid, 0)) != hipSuccess) return err;
-    err = launch_candidate_products(d, t, L, s, mode);
+    // The candidates of the next cycle, from the scores as the swaps left them (the refresh below changes them in the last
+    // digits only, and the choice of candidates decides what is computed ahead, not any result): two sorts of one
+    // workgroup each; this stream has the time, the second one's chain is the longer.
+    err = launch_candidates(d, t, L, s, mode);
     if (err != hipSuccess) return err;
     if ((err = hipStreamWaitEvent(s, side->join, 0)) != hipSuccess) return err;
   }
