@@ -252,6 +252,7 @@ __global__ __launch_bounds__(512, 1) void i8_gemm_kernel(I8Args g) {
     for (int a = 0; a < 2; a++) { uint4 q = lds[t * 256 + oa + a * 32]; fa[a][t] = *reinterpret_cast<v4i*>(&q); }
   int buf = 0;
   for (int st = 0; st < nstages; st++) {
+    __builtin_amdgcn_iglp_opt(0);
     const uint4* pb = lds + buf * 2 * BLK + BLK;
     // column-side digits 0 .. S-2 against every row-side digit they meet: 28 of the stage's 30 products
 #pragma unroll
