@@ -194,6 +194,7 @@ __global__ __launch_bounds__(256, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     if (more) OSSCAR_GLOAD(st + 1);
     const uint4* pa = lds + (buf * 2 + 0) * PK_SLOTS;
     const uint4* pb = diag ? pa : lds + (buf * 2 + 1) * PK_SLOTS;
+    __builtin_amdgcn_s_setprio(1);        // the wave that is multiplying goes first; the other wave of the SIMD issues its loads and stores in between
 #pragma unroll
     for (int ks = 0; ks < GBK / 16; ks++) {
       const int kgo = (ks * 2 + (lane >> 5)) * 128;
@@ -214,6 +215,7 @@ __global__ __launch_bounds__(256, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         for (int b = 0; b < WT; b++)
           acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
     }
+    __builtin_amdgcn_s_setprio(0);
     if (++in_window >= window && more) {
       in_window = 0;
 #pragma unroll
