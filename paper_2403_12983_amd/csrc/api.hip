@@ -57,16 +57,6 @@ struct Carve {
 __global__ void fill_f64_kernel(double* p, int64_t n, double v) {
   for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
 }
-__global__ void fill_f32_kernel(float* p, int64_t n, float v) {
-  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
-}
-__global__ void symmetrize_kernel(const float* __restrict__ A, float* __restrict__ out, int n) {
-  int64_t tot = (int64_t)n * n;
-  for (int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; idx < tot; idx += (int64_t)gridDim.x * blockDim.x) {
-    int i = (int)(idx / n), j = (int)(idx % n);
-    out[idx] = 0.5f * (A[idx] + A[(int64_t)j * n + i]);
-  }
-}
 // out = the symmetric matrix whose lower triangle is that of A
 __global__ void mirror_from_lower_kernel(const float* __restrict__ A, float* __restrict__ out, int n) {
   int64_t tot = (int64_t)n * n;

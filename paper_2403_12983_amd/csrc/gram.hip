@@ -356,7 +356,6 @@ hipError_t launch_gram_packed(const void* Xc, int64_t n_c, int64_t ldx, int d1, 
   const int npanels = (d1 + 127) / 128, npanels_y = Yc ? (m + 127) / 128 : 0;
   const int ntiles = npanels * (npanels + 1) / 2;
   const int window = 16;   // 1024 tokens per MFMA accumulation window
-  const size_t shmem = (size_t)2 * 2 * PK_SLOTS * 16;
   for (int64_t r0 = 0; r0 < n_c; r0 += pack_rows) {
     const int64_t nr = std::min<int64_t>(pack_rows, n_c - r0);
     const int nstages = (int)((nr + GBK - 1) / GBK);
@@ -439,7 +438,6 @@ hipError_t launch_hw_split(const float* H, int d1, const void* W, int64_t ldw, i
   if (pack_rows < GBK || pack_rows % GBK || !tiles || tile_entries == 0) return hipErrorInvalidValue;
   const int npanels = (d1 + 127) / 128, npanels_w = (m + 127) / 128;
   const int window = 16;
-  const size_t shmem = (size_t)2 * 2 * PK_SLOTS * 16;
   for (int64_t r0 = 0; r0 < d1; r0 += pack_rows) {
     const int64_t nr = std::min<int64_t>(pack_rows, d1 - r0);
     const int nstages = (int)((nr + GBK - 1) / GBK);
