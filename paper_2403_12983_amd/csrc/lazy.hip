@@ -1170,63 +1170,72 @@ __global__ __launch_bounds__(256, 2) void rk_update_kernel(const uint4* __restri
     rb2 = *OSSCAR_RK_ADDR(Bpk, bpad, j0, 2, kq_); rb3 = *OSSCAR_RK_ADDR(Bpk, bpad, j0, 3, kq_);                    \
     rb4 = *OSSCAR_RK_ADDR(Bpk, bpad, j0, 4, kq_); rb5 = *OSSCAR_RK_ADDR(Bpk, bpad, j0, 5, kq_);                    \
   }
+#define OSSCAR_RK_STAGE()                                                                                          \
+  {                                                                                                                \
+    __syncthreads();                                                                                               \
+    la[tid] = ra0; la[tid + 256] = ra1; la[tid + 512] = ra2; la[tid + 768] = ra3; la[tid + 1024] = ra4; la[tid + 1280] = ra5; \
+    lb[tid] = rb0; lb[tid + 256] = rb1; lb[tid + 512] = rb2; lb[tid + 768] = rb3; lb[tid + 1024] = rb4; lb[tid + 1280] = rb5; \
+    __syncthreads();                                                                                               \
+  }
+// the six piece products of a quarter, smallest terms first
+#define OSSCAR_RK_PRODUCTS()                                                                                       \
+  _Pragma("unroll") for (int ks = 0; ks < 2; ks++) {                                                               \
+    const int off = (ks * 2 + (lane >> 5)) * 128 + (lane & 31);                                                    \
+    la_bf8 fa[2][3], fb[2][3];                                                                                     \
+    _Pragma("unroll") for (int a = 0; a < 2; a++)                                                                  \
+      _Pragma("unroll") for (int p = 0; p < 3; p++) { uint4 q = la[p * 512 + off + wm * 64 + a * 32]; fa[a][p] = *reinterpret_cast<la_bf8*>(&q); } \
+    _Pragma("unroll") for (int b = 0; b < 2; b++)                                                                  \
+      _Pragma("unroll") for (int p = 0; p < 3; p++) { uint4 q = lb[p * 512 + off + wn * 64 + b * 32]; fb[b][p] = *reinterpret_cast<la_bf8*>(&q); } \
+    _Pragma("unroll") for (int a = 0; a < 2; a++)                                                                  \
+      _Pragma("unroll") for (int b = 0; b < 2; b++) {                                                              \
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][2], fb[b][0], acc[a][b], 0, 0, 0);               \
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][0], fb[b][2], acc[a][b], 0, 0, 0);               \
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][1], fb[b][1], acc[a][b], 0, 0, 0);               \
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][1], fb[b][0], acc[a][b], 0, 0, 0);               \
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][0], fb[b][1], acc[a][b], 0, 0, 0);               \
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][0], fb[b][0], acc[a][b], 0, 0, 0);               \
+      }                                                                                                            \
+  }
   OSSCAR_RK_GLOAD(0);
 #pragma unroll 1
-  for (int kq = 0; kq < 4; kq++) {
-    __syncthreads();
-    la[tid] = ra0; la[tid + 256] = ra1; la[tid + 512] = ra2; la[tid + 768] = ra3; la[tid + 1024] = ra4; la[tid + 1280] = ra5;
-    lb[tid] = rb0; lb[tid + 256] = rb1; lb[tid + 512] = rb2; lb[tid + 768] = rb3; lb[tid + 1024] = rb4; lb[tid + 1280] = rb5;
-    __syncthreads();
-    if (kq + 1 < 4) OSSCAR_RK_GLOAD(kq + 1);
-#pragma unroll
-    for (int ks = 0; ks < 2; ks++) {
-      const int off = (ks * 2 + (lane >> 5)) * 128 + (lane & 31);
-      la_bf8 fa[2][3], fb[2][3];
-#pragma unroll
-      for (int a = 0; a < 2; a++)
-#pragma unroll
-        for (int p = 0; p < 3; p++) { uint4 q = la[p * 512 + off + wm * 64 + a * 32]; fa[a][p] = *reinterpret_cast<la_bf8*>(&q); }
-#pragma unroll
-      for (int b = 0; b < 2; b++)
-#pragma unroll
-        for (int p = 0; p < 3; p++) { uint4 q = lb[p * 512 + off + wn * 64 + b * 32]; fb[b][p] = *reinterpret_cast<la_bf8*>(&q); }
-#pragma unroll
-      for (int a = 0; a < 2; a++)
-#pragma unroll
-        for (int b = 0; b < 2; b++) {
-          // smallest terms first
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][2], fb[b][0], acc[a][b], 0, 0, 0);
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][0], fb[b][2], acc[a][b], 0, 0, 0);
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][1], fb[b][1], acc[a][b], 0, 0, 0);
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][1], fb[b][0], acc[a][b], 0, 0, 0);
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][0], fb[b][1], acc[a][b], 0, 0, 0);
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][0], fb[b][0], acc[a][b], 0, 0, 0);
-        }
-    }
+  for (int kq = 0; kq < 3; kq++) {
+    OSSCAR_RK_STAGE();
+    OSSCAR_RK_GLOAD(kq + 1);
+    OSSCAR_RK_PRODUCTS();
   }
+  OSSCAR_RK_STAGE();
+  // C layout of a 32 x 32 tile: register r = rr*4 + r3 holds row rr*8 + (lane/32)*4 + r3, column lane%32.
+  // A whole tile's values of C are requested before the last quarter's products, in the registers the operand loads have
+  // left free, so that their way from memory runs beside the matrix-core work instead of after it (requesting half of them
+  // a quarter earlier changed nothing).
+  float* cbase = C + (int64_t)(i0 + wm * 64 + (lane >> 5) * 4) * ldc + j0 + wn * 64 + (lane & 31);
+  const bool whole = (i0 + 128 <= M && j0 + 128 <= N);
+  float cv[2][2][16];
+  if (whole) {
+#pragma unroll
+    for (int a = 0; a < 2; a++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const float* pr = cbase + (int64_t)(a * 32 + (r >> 2) * 8 + (r & 3)) * ldc;
+        cv[a][0][r] = pr[0]; cv[a][1][r] = pr[32];
+      }
+  }
+  OSSCAR_RK_PRODUCTS();
+#undef OSSCAR_RK_PRODUCTS
+#undef OSSCAR_RK_STAGE
 #undef OSSCAR_RK_GLOAD
 #undef OSSCAR_RK_ADDR
-  // C layout of a 32 x 32 tile: register r = rr*4 + r3 holds row rr*8 + (lane/32)*4 + r3, column lane%32.
-  // All of a thread's loads of C are issued before the first store (a load-subtract-store chain per element would pay the
-  // memory latency 64 times over).
-  float* cbase = C + (int64_t)(i0 + wm * 64 + (lane >> 5) * 4) * ldc + j0 + wn * 64 + (lane & 31);
-  if (i0 + 128 <= M && j0 + 128 <= N) {
+  if (whole) {
 #pragma unroll
     for (int a = 0; a < 2; a++) {
-      float cv[2][16];
       float* ca = cbase + (int64_t)(a * 32) * ldc;
 #pragma unroll
       for (int r = 0; r < 16; r++) {
-        const float* pr = ca + (int64_t)((r >> 2) * 8 + (r & 3)) * ldc;
-        cv[0][r] = pr[0]; cv[1][r] = pr[32];
-      }
-#pragma unroll
-      for (int r = 0; r < 16; r++) {
         float* pr = ca + (int64_t)((r >> 2) * 8 + (r & 3)) * ldc;
-        cv[0][r] -= acc[a][0][r]; cv[1][r] -= acc[a][1][r];
-        pr[0] = cv[0][r]; pr[32] = cv[1][r];
+        cv[a][0][r] -= acc[a][0][r]; cv[a][1][r] -= acc[a][1][r];
+        pr[0] = cv[a][0][r]; pr[32] = cv[a][1][r];
       }
-      if (rowsq) rk_row_squares(cv[0], cv[1], rowsq + (int64_t)(tile.y * 2 + wn) * M + i0 + wm * 64 + a * 32, lane, M - (i0 + wm * 64 + a * 32));
+      if (rowsq) rk_row_squares(cv[a][0], cv[a][1], rowsq + (int64_t)(tile.y * 2 + wn) * M + i0 + wm * 64 + a * 32, lane, M - (i0 + wm * 64 + a * 32));
     }
   } else {
 #pragma unroll
