@@ -542,29 +542,34 @@ __global__ __launch_bounds__(256) void inv_fix64_kernel(double* __restrict__ N, 
 }
 
 // N[i][j] -= sum_k A[i][k] B[j][k] on the tiles of the lower block triangle; A, B: n x w float64 (w <= 128), N: n x n float64.
-// One workgroup per 128 x 128 tile, 8 waves x (4 x 2) v_mfma_f64_16x16x4_f64, the contraction in steps of 16 through LDS
-// (rows of 144 doubles: the four k of a quarter-wave's operand read fall in different bank groups); the tile of N is read,
-// changed and written from registers, 16 values per thread at a time.  Tiles in 8 x 8 super-blocks per XCD.
+// One workgroup per half (128 rows x 64 columns) of a 128 x 128 tile, 8 waves x (2 x 2) v_mfma_f64_16x16x4_f64, the
+// contraction in steps of 16 through LDS (rows of 144 and 80 doubles: the four k of a quarter-wave's operand read fall in
+// different bank groups).  The workgroup's part of N (16 values per thread) is requested while the first products run and is
+// there when the last one ends: with a whole tile per workgroup the registers held a quarter of it at a time, and four
+// round trips to memory followed the products.  Tiles in 8 x 8 super-blocks per XCD, the two halves of a tile on one XCD.
 typedef double swd4 __attribute__((ext_vector_type(4)));
-constexpr int SW_LD = 144;
+constexpr int SW_LD = 144, SW_LDB = 80;
+constexpr size_t SW_LDS_BYTES = (size_t)2 * 16 * (SW_LD + SW_LDB) * sizeof(double);
 // part = 0: every tile of the triangle.  The pivot rows of A and B are zero, so the tiles of tile row / column pk (the
 // pivot panel's) receive nothing and are always left alone (the pivot-row fix rewrites them, possibly meanwhile).
-// part = 1: only tile row and tile column pk + 1, what the next panel is made of (one workgroup per tile, blockIdx = the
-// other tile index); part = 2: everything but those.
+// part = 1: only tile row and tile column pk + 1, what the next panel is made of (two workgroups per tile, blockIdx / 2 =
+// the other tile index); part = 2: everything but those.
 __global__ __launch_bounds__(512, 2) void sweep_update64_kernel(const double* __restrict__ A, const double* __restrict__ B, int n, int w,
                                                                  double* __restrict__ N, int part, int pk) {
-  extern __shared__ double sw_lds[];           // 72 KB: above the static limit, so taken dynamically
+  extern __shared__ double sw_lds[];           // 56 KB: above the static limit, so taken dynamically
   double (*As)[16][SW_LD] = reinterpret_cast<double (*)[16][SW_LD]>(sw_lds);
-  double (*Bs)[16][SW_LD] = reinterpret_cast<double (*)[16][SW_LD]>(sw_lds + 2 * 16 * SW_LD);
-  int tm, tn;
+  double (*Bs)[16][SW_LDB] = reinterpret_cast<double (*)[16][SW_LDB]>(sw_lds + 2 * 16 * SW_LD);
+  int tm, tn, half;
   if (part == 1) {
-    const int tiles = (n + 127) / 128, b = blockIdx.x, nx = pk + 1;
+    const int tiles = (n + 127) / 128, b = blockIdx.x >> 1, nx = pk + 1;
+    half = blockIdx.x & 1;
     if (b >= tiles || nx >= tiles || b == pk) return;
     tm = (b <= nx) ? nx : b;
     tn = (b <= nx) ? b : nx;
   } else {
     const int tiles = (n + 127) / 128, nr = (tiles + 7) / 8;
-    const int b = blockIdx.x, xcd = b & 7, slot = b >> 3;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 4;
+    half = (blockIdx.x >> 3) & 1;
     const int sb = (slot / 64) * 8 + xcd, within = slot % 64;
     if (sb >= nr * (nr + 1) / 2) return;
     int r = (int)((sqrtf(8.f * (float)sb + 1.f) - 1.f) * 0.5f);
@@ -576,14 +581,16 @@ __global__ __launch_bounds__(512, 2) void sweep_update64_kernel(const double* __
     if (tm == pk || tn == pk) return;
     if (part == 2 && (tm == pk + 1 || tn == pk + 1)) return;
   }
-  const int m0 = tm * 128, n0 = tn * 128;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 2, wn = wave & 3;   // wave tile: 64 rows x 32 columns
+  const int m0 = tm * 128, n0 = tn * 128 + half * 64;
+  if (n0 >= n) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;   // wave tile: 32 rows x 32 columns
   const int lrow = tid >> 2, lk = (tid & 3) * 4;        // staging: thread = (row of the tile, quarter of the 16 k)
+  const bool stage_b = lrow < 64;                       // B has 64 rows here
   const double* ap = (m0 + lrow < n) ? A + (int64_t)(m0 + lrow) * w : nullptr;
-  const double* bp = (n0 + lrow < n) ? B + (int64_t)(n0 + lrow) * w : nullptr;
-  swd4 acc[4][2];
+  const double* bp = (stage_b && n0 + lrow < n) ? B + (int64_t)(n0 + lrow) * w : nullptr;
+  swd4 acc[2][2];
 #pragma unroll
-  for (int i = 0; i < 4; i++)
+  for (int i = 0; i < 2; i++)
 #pragma unroll
     for (int j = 0; j < 2; j++) acc[i][j] = swd4{0.0, 0.0, 0.0, 0.0};
   double ra[4], rb[4];
@@ -613,61 +620,84 @@ __global__ __launch_bounds__(512, 2) void sweep_update64_kernel(const double* __
   };
   auto sstore = [&](int buf) {
 #pragma unroll
-    for (int e = 0; e < 4; e++) { As[buf][lk + e][lrow] = ra[e]; Bs[buf][lk + e][lrow] = rb[e]; }
+    for (int e = 0; e < 4; e++) As[buf][lk + e][lrow] = ra[e];
+    if (stage_b) {
+#pragma unroll
+      for (int e = 0; e < 4; e++) Bs[buf][lk + e][lrow] = rb[e];
+    }
   };
-  // the first 16 rows of this wave's part of the tile of N are requested now and arrive while the products run
-  const int rbase = m0 + wm * 64 + (lane >> 4), cbase = n0 + wn * 32 + (lane & 15);
-  double cv[2][4];
-  auto cload = [&](int i, double (&dst)[2][4]) {
+  // lane holds D[4 r + lane/16][lane%16] of each 16 x 16 tile
+  const int rbase = m0 + wm * 32 + (lane >> 4), cbase = n0 + wn * 32 + (lane & 15);
+  const bool whole = (m0 + 128 <= n && n0 + 64 <= n);
+  double* nbase = N + (int64_t)rbase * n + cbase;       // dereferenced only where the row and column exist
+  double cv[2][2][4];
+#pragma unroll
+  for (int i = 0; i < 2; i++)
 #pragma unroll
     for (int j = 0; j < 2; j++)
 #pragma unroll
-      for (int r = 0; r < 4; r++) {
-        const int row = rbase + i * 16 + 4 * r, col = cbase + j * 16;
-        dst[j][r] = (row < n && col < n) ? N[(int64_t)row * n + col] : 0.0;
-      }
-  };
-  cload(0, cv);
+      for (int r = 0; r < 4; r++) cv[i][j][r] = 0.0;
   if (ktiles > 0) { gload(0); sstore(0); }
   __syncthreads();
   for (int kt = 0; kt < ktiles; kt++) {
     const int buf = kt & 1;
     if (kt + 1 < ktiles) gload(kt + 1);
+    if (kt == 0) {
+      // requested behind the second stage's operands, so that no operand load queues up behind them before they are back
+      if (whole) {
+#pragma unroll
+        for (int i = 0; i < 2; i++)
+#pragma unroll
+          for (int j = 0; j < 2; j++)
+#pragma unroll
+            for (int r = 0; r < 4; r++) cv[i][j][r] = nbase[(int64_t)(i * 16 + 4 * r) * n + j * 16];
+      } else {
+#pragma unroll
+        for (int i = 0; i < 2; i++)
+#pragma unroll
+          for (int j = 0; j < 2; j++)
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+              const int row = rbase + i * 16 + 4 * r, col = cbase + j * 16;
+              cv[i][j][r] = (row < n && col < n) ? N[(int64_t)row * n + col] : 0.0;
+            }
+      }
+    }
 #pragma unroll
     for (int kk = 0; kk < 4; kk++) {
       const int k = kk * 4 + (lane >> 4);
-      double a[4], b[2];
+      double a[2], b[2];
 #pragma unroll
-      for (int i = 0; i < 4; i++) a[i] = As[buf][k][wm * 64 + i * 16 + (lane & 15)];
+      for (int i = 0; i < 2; i++) a[i] = As[buf][k][wm * 32 + i * 16 + (lane & 15)];
 #pragma unroll
       for (int j = 0; j < 2; j++) b[j] = Bs[buf][k][wn * 32 + j * 16 + (lane & 15)];
 #pragma unroll
-      for (int i = 0; i < 4; i++)
+      for (int i = 0; i < 2; i++)
 #pragma unroll
         for (int j = 0; j < 2; j++) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
     }
     if (kt + 1 < ktiles) sstore(buf ^ 1);
     __syncthreads();
   }
-  // lane holds D[4 r + lane/16][lane%16] of each 16 x 16 tile; the next 16 rows are requested before these are stored
+  if (ktiles == 0) return;
+  if (whole) {
 #pragma unroll
-  for (int i = 0; i < 4; i++) {
-    double nx[2][4];
-    if (i < 3) cload(i + 1, nx);
+    for (int i = 0; i < 2; i++)
+#pragma unroll
+      for (int j = 0; j < 2; j++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) nbase[(int64_t)(i * 16 + 4 * r) * n + j * 16] = cv[i][j][r] - acc[i][j][r];
+    return;
+  }
+#pragma unroll
+  for (int i = 0; i < 2; i++)
 #pragma unroll
     for (int j = 0; j < 2; j++)
 #pragma unroll
       for (int r = 0; r < 4; r++) {
         const int row = rbase + i * 16 + 4 * r, col = cbase + j * 16;
-        if (row < n && col < n) N[(int64_t)row * n + col] = cv[j][r] - acc[i][j][r];
+        if (row < n && col < n) N[(int64_t)row * n + col] = cv[i][j][r] - acc[i][j][r];
       }
-    if (i < 3) {
-#pragma unroll
-      for (int j = 0; j < 2; j++)
-#pragma unroll
-        for (int r = 0; r < 4; r++) cv[j][r] = nx[j][r];
-    }
-  }
 }
 
 // P (n x n float32, full) = H^-1 for the SPD H (n x n float32, leading dimension ldh; only its lower triangle is read).
@@ -683,13 +713,13 @@ hipError_t spd_inverse_f64(const float* H, int64_t ldh, int n, float* P, double*
   int blocks = (int)((tot + 1023) / 1024); if (blocks > 131072) blocks = 131072;
   hipLaunchKernelGGL(widen_lower_kernel, dim3(blocks), dim3(256), 0, s, H, ldh, n, A64);
   double* panel = panels;
-  const size_t shmem = (size_t)2 * 2 * 16 * SW_LD * sizeof(double);
+  const size_t shmem = SW_LDS_BYTES;
   {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sweep_update64_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     if (e != hipSuccess) return e;
   }
   const int tiles = (n + 127) / 128, nr = (tiles + 7) / 8;
-  const unsigned upd_grid = (unsigned)((nr * (nr + 1) / 2 + 7) / 8 * 8 * 64);
+  const unsigned upd_grid = (unsigned)((nr * (nr + 1) / 2 + 7) / 8 * 8 * 64) * 2;      // two workgroups per tile
   const int rb = (n + PANEL_ROWS64 - 1) / PANEL_ROWS64;
   const bool two = side && side->stream && tiles > 2;
   hipError_t err;
@@ -717,7 +747,7 @@ hipError_t spd_inverse_f64(const float* H, int64_t ldh, int n, float* P, double*
     hipLaunchKernelGGL(sweep_update64_kernel, dim3(upd_grid), dim3(512), shmem, side->stream, panelDz, panelCz, n, w, A64, 2, k);
     if ((err = hipEventRecord(side->join, side->stream)) != hipSuccess) return err;
     pending = true;
-    if (k + 1 < tiles) hipLaunchKernelGGL(sweep_update64_kernel, dim3(tiles), dim3(512), shmem, s, panelDz, panelCz, n, w, A64, 1, k);
+    if (k + 1 < tiles) hipLaunchKernelGGL(sweep_update64_kernel, dim3(2 * tiles), dim3(512), shmem, s, panelDz, panelCz, n, w, A64, 1, k);
     // tile row and column k only: no launch of this step's update touches them, the next step's bulk update does (it is
     // enqueued behind an event that this stream records after the fix)
     hipLaunchKernelGGL(inv_fix64_kernel, dim3(rb), dim3(256), 0, s, A64, (int64_t)n, n, t0, w, panelDz, small);
