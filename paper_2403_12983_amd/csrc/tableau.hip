@@ -639,6 +639,41 @@ __global__ __launch_bounds__(512, 2) void sweep_update64_kernel(const double* __
       for (int r = 0; r < 4; r++) cv[i][j][r] = 0.0;
   if (ktiles > 0) { gload(0); sstore(0); }
   __syncthreads();
+  if (whole && w == 128) {
+    // The usual case.  The 16 values of N are requested two per stage, each pair behind the next stage's operands: the wait
+    // for those operands at the end of a stage then covers the pair requested a stage earlier, and the requests to memory
+    // run through the whole contraction instead of piling up at its start.
+#pragma unroll
+    for (int kt = 0; kt < 8; kt++) {
+      const int buf = kt & 1;
+      if (kt + 1 < 8) gload(kt + 1);
+#pragma unroll
+      for (int e = kt * 2; e < kt * 2 + 2; e++)
+        cv[e >> 3][(e >> 2) & 1][e & 3] = nbase[(int64_t)((e >> 3) * 16 + 4 * (e & 3)) * n + ((e >> 2) & 1) * 16];
+#pragma unroll
+      for (int kk = 0; kk < 4; kk++) {
+        const int k = kk * 4 + (lane >> 4);
+        double a[2], b[2];
+#pragma unroll
+        for (int i = 0; i < 2; i++) a[i] = As[buf][k][wm * 32 + i * 16 + (lane & 15)];
+#pragma unroll
+        for (int j = 0; j < 2; j++) b[j] = Bs[buf][k][wn * 32 + j * 16 + (lane & 15)];
+#pragma unroll
+        for (int i = 0; i < 2; i++)
+#pragma unroll
+          for (int j = 0; j < 2; j++) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
+      }
+      if (kt + 1 < 8) sstore(buf ^ 1);
+      __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+#pragma unroll
+      for (int j = 0; j < 2; j++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) nbase[(int64_t)(i * 16 + 4 * r) * n + j * 16] = cv[i][j][r] - acc[i][j][r];
+    return;
+  }
   for (int kt = 0; kt < ktiles; kt++) {
     const int buf = kt & 1;
     if (kt + 1 < ktiles) gload(kt + 1);
