@@ -25,7 +25,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 # HBM-side bytes per launch on cfg5 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a 1 GiB copy
 # (profiles/gemm_f64acc_cfg5_pmc.md: mean over the launches of one layer; profiles/gram_packed_cfg5_pmc.md: one chunk)
 GEMM64_TRAFFIC_CFG5 = 2.99e7
-GRAM_TRAFFIC_CFG5 = 93.4e9
+GRAM_TRAFFIC_CFG5 = 93.9e9
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
