@@ -157,6 +157,7 @@ def main():
             r["iters"] = r["iters"] * a.block
         else:
             r = s.osscar_local_search(swaps, 0.0, fl, a.refresh_every)
+            info["counters"] = s.osscar_get_counters()
         ev[4].record()
         What, support, obj = s.osscar_backsolve()
         ev[5].record()
@@ -336,7 +337,8 @@ def main():
                                       "products plus one look-ahead product Zc Z^T.  An eager in-place up/downdate of P, B, V, R would "
                                       "move bytes_per_swap_eager per swap",
                               "ms_per_swap": ms_swap, "accept_and_u_kernel_ms": 1e3 * upd_n, "iteration_kernels_ms": 1e3 * upd_z,
-                              "flushes_total_ms": flush_ms, "bytes_per_swap_eager": bytes_swap_alg} if lazy else
+                              "flushes_total_ms": flush_ms, "bytes_per_swap_eager": bytes_swap_alg,
+                              "last_layer_counts": info.get("counters")} if lazy else
                              {"note": "in-place search: every swap is one rank-2q pass over the tableau (N: lower triangle, Z)",
                               "ms_per_swap": ms_swap, "update_N_ms": 1e3 * upd_n, "update_Z_ms": 1e3 * upd_z,
                               "bytes_per_swap": bytes_swap_alg,
