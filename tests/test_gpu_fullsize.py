@@ -66,8 +66,8 @@ def sampled_tiles_of_gram(cfg, X, H, lam, nblocks=6, seed=5):
 
 
 def progress(msg):
-    """A line per finished step of a long test, to stdout and to gpurun_out/pytest_progress.log (the oracle's steps at the
-    size of the benchmark layer take a minute each)."""
+    """A line per finished step of a long test, to stdout and to a progress file in the run's output folder (the oracle's
+    steps at the size of the benchmark layer take a minute each)."""
     import os
     import time
     line = f"[{time.strftime('%H:%M:%S')}] {msg}"
